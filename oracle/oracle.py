@@ -1,0 +1,239 @@
+"""ctypes wrapper around the plain-C oracle (mtp_oracle.c).
+
+TEST INFRASTRUCTURE ONLY.  Importable from tests/, the smoke check and the
+benchmark's cpu_baseline leg; never from the product package.  It does not
+import the HIP binding and shares nothing with it.
+
+Two builds of the same source: `f32` (the reference precision of this build) and
+`f64` (bounds the float build's own rounding error).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import Dict, Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "mtp_oracle.c")
+
+
+def lib_path(precision: str) -> str:
+    return os.path.join(_HERE, f"libmtp_oracle_{precision}.so")
+
+
+def build(force: bool = False) -> None:
+    """Compile both precisions with gcc (plain -O2: no fast-math, sums stay left to right)."""
+    for prec, flag in (("f32", []), ("f64", ["-DORC_F64"])):
+        out = lib_path(prec)
+        if not force and os.path.exists(out) and os.path.getmtime(out) >= os.path.getmtime(_SRC):
+            continue
+        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-Wextra", *flag, _SRC,
+               "-o", out, "-lm"]
+        subprocess.run(cmd, check=True)
+
+
+class _Config(C.Structure):
+    _fields_ = [("d_model", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("d_ffn", C.c_int32), ("vocab_size", C.c_int32),
+                ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("kv_capacity", C.c_int32),
+                ("recur_pre_norm", C.c_int32)]
+
+
+_W_FIELDS = ["embed", "lm_head", "g_hnorm", "g_enorm", "g_attn_norm", "g_mlp_norm", "g_final_norm", "w_proj",
+             "w_q", "w_k", "w_v", "b_q", "b_k", "b_v", "w_o", "w_gate", "w_up", "w_down"]
+_T_FIELDS = ["c", "x", "q", "k", "v", "attn", "x1", "m", "x2"]
+
+
+class _Weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _W_FIELDS]
+
+
+class _Trace(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _T_FIELDS]
+
+
+def _ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _u16(a) -> np.ndarray:
+    a = np.ascontiguousarray(a)
+    assert a.dtype == np.uint16, a.dtype
+    return a
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+class Oracle:
+    """shape: any object with d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab_size, rms_eps, rope_theta."""
+
+    def __init__(self, shape, weights: Dict[str, np.ndarray], kv_capacity: int, precision: str = "f32",
+                 recur_pre_norm: bool = False):
+        build()
+        self.lib = C.CDLL(lib_path(precision))
+        self.real = np.float32 if precision == "f32" else np.float64
+        assert self.lib.orc_real_bytes() == np.dtype(self.real).itemsize
+        self.shape = shape
+        self.cfg = _Config(shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.d_ffn,
+                           shape.vocab_size, shape.rms_eps, shape.rope_theta, kv_capacity, int(recur_pre_norm))
+        self._keep = {k: _u16(v) for k, v in weights.items()}
+        self.w = _Weights(**{n: (_ptr(self._keep[n]) if n in self._keep else None) for n in _W_FIELDS})
+        self.lib.orc_round_bf16.restype = C.c_uint16
+        self.lib.orc_round_bf16.argtypes = [C.c_float if precision == "f32" else C.c_double]
+        self.lib.orc_widen_bf16.restype = C.c_float
+        self.lib.orc_widen_bf16.argtypes = [C.c_uint16]
+
+    # -- helpers ---------------------------------------------------------
+    @property
+    def threads(self) -> int:
+        return int(self.lib.orc_num_threads())
+
+    def set_threads(self, n: int) -> None:
+        self.lib.orc_set_threads(C.c_int(n))
+
+    def _r(self, a) -> np.ndarray:
+        return np.ascontiguousarray(a, dtype=self.real)
+
+    def round_bf16(self, x: float) -> int:
+        return int(self.lib.orc_round_bf16(x))
+
+    # -- building blocks ---------------------------------------------------
+    def rmsnorm(self, u, g_bits, eps: Optional[float] = None) -> np.ndarray:
+        u = self._r(u)
+        g = _u16(g_bits)
+        out = np.empty_like(u)
+        eps = self.shape.rms_eps if eps is None else eps
+        self.lib.orc_rmsnorm(_ptr(u), _ptr(g), C.c_int32(u.size), C.c_float(eps), _ptr(out))
+        return out
+
+    def linear(self, W_bits, x, bias_bits=None) -> np.ndarray:
+        W = _u16(W_bits)
+        x = self._r(x)
+        n_out, n_in = W.shape
+        assert x.size == n_in
+        b = None if bias_bits is None else _u16(bias_bits)
+        y = np.empty(n_out, dtype=self.real)
+        self.lib.orc_linear(_ptr(W), _ptr(b), _ptr(x), C.c_int32(n_out), C.c_int32(n_in), _ptr(y))
+        return y
+
+    def rope(self, u, n_heads: int, head_dim: int, pos: int, theta: Optional[float] = None) -> np.ndarray:
+        u = self._r(u).copy()
+        theta = self.shape.rope_theta if theta is None else theta
+        self.lib.orc_rope(_ptr(u), C.c_int32(n_heads), C.c_int32(head_dim), C.c_int32(pos), C.c_float(theta))
+        return u
+
+    def attention(self, q, kc_bits, vc_bits, length: int) -> np.ndarray:
+        kc, vc = _u16(kc_bits), _u16(vc_bits)
+        Hkv, cap, hd = kc.shape
+        q = self._r(q)
+        Hq = q.size // hd
+        out = np.empty(Hq * hd, dtype=self.real)
+        rc = self.lib.orc_attention(_ptr(q), _ptr(kc), _ptr(vc), C.c_int32(length), C.c_int32(cap), C.c_int32(Hq),
+                                    C.c_int32(Hkv), C.c_int32(hd), _ptr(out))
+        if rc:
+            raise ValueError(f"orc_attention failed: {rc}")
+        return out.reshape(Hq, hd)
+
+    def swiglu(self, w_gate_bits, w_up_bits, y) -> np.ndarray:
+        wg, wu = _u16(w_gate_bits), _u16(w_up_bits)
+        F, d = wg.shape
+        y = self._r(y)
+        m = np.empty(F, dtype=self.real)
+        self.lib.orc_swiglu(_ptr(wg), _ptr(wu), _ptr(y), C.c_int32(F), C.c_int32(d), _ptr(m))
+        return m
+
+    def lm_head(self, W_bits, ids, h):
+        """Returns (logits [n], best_index, margin)."""
+        W = _u16(W_bits)
+        V, d = W.shape
+        ids_a = None if ids is None else _i32(ids)
+        n = V if ids_a is None else ids_a.size
+        h = self._r(h)
+        z = np.empty(n, dtype=self.real)
+        bi = C.c_int32(0)
+        mg = (C.c_float if self.real == np.float32 else C.c_double)(0)
+        rc = self.lib.orc_lm_head(_ptr(W), C.c_int32(V), _ptr(ids_a), C.c_int32(n), C.c_int32(d), _ptr(h), _ptr(z),
+                                  C.byref(bi), C.byref(mg))
+        if rc:
+            raise ValueError(f"orc_lm_head failed: {rc}")
+        return z, int(bi.value), float(mg.value)
+
+    # -- one step / K steps --------------------------------------------------
+    def step(self, h, token: int, kc_bits: np.ndarray, vc_bits: np.ndarray, pos: int, ids, want_logits=True,
+             trace: bool = False):
+        """One head application for one sequence.  kc_bits/vc_bits [Hkv][cap][hd] are updated in place.
+        Returns dict(hhat, logits, draft, margin, [trace arrays])."""
+        s = self.shape
+        assert kc_bits.dtype == np.uint16 and kc_bits.flags.c_contiguous and vc_bits.flags.c_contiguous
+        assert kc_bits.shape == (s.n_kv_heads, self.cfg.kv_capacity, s.head_dim)
+        h = self._r(h)
+        ids_a = None if ids is None else _i32(ids)
+        n = s.vocab_size if ids_a is None else ids_a.size
+        hhat = np.empty(s.d_model, dtype=self.real)
+        logits = np.empty(n, dtype=self.real) if want_logits else None
+        did = C.c_int32(-1)
+        mg = (C.c_float if self.real == np.float32 else C.c_double)(0)
+        tr_arrays = None
+        tr = None
+        if trace:
+            sizes = {"c": 2 * s.d_model, "x": s.d_model, "q": s.n_q_heads * s.head_dim,
+                     "k": s.n_kv_heads * s.head_dim, "v": s.n_kv_heads * s.head_dim,
+                     "attn": s.n_q_heads * s.head_dim, "x1": s.d_model, "m": s.d_ffn, "x2": s.d_model}
+            tr_arrays = {k: np.empty(v, dtype=self.real) for k, v in sizes.items()}
+            tr = _Trace(**{k: _ptr(v) for k, v in tr_arrays.items()})
+        rc = self.lib.orc_step(C.byref(self.cfg), C.byref(self.w), _ptr(h), C.c_int32(token), _ptr(kc_bits),
+                               _ptr(vc_bits), C.c_int32(pos), _ptr(ids_a), C.c_int32(n), _ptr(hhat), _ptr(logits),
+                               C.byref(did), C.byref(mg), C.byref(tr) if tr is not None else None)
+        if rc:
+            raise ValueError(f"orc_step failed: {rc}")
+        out = {"hhat": hhat, "logits": logits, "draft": int(did.value), "margin": float(mg.value)}
+        if tr_arrays:
+            out.update(tr_arrays)
+        return out
+
+    def chain(self, K: int, hidden_in_bits, token_in, k_cache_bits, v_cache_bits, kv_len, ids, forced=None,
+              want_logits: bool = True, want_hidden: bool = True):
+        """K recursive draft steps for a batch.  Caches [B][Hkv][cap][hd] are updated in place.
+        Returns dict(draft [B][K], logits [B][K][n], hidden [B][K][d], margin [B][K])."""
+        s = self.shape
+        hid = _u16(hidden_in_bits)
+        B = hid.shape[0]
+        tok = _i32(token_in)
+        kvl = _i32(kv_len)
+        assert k_cache_bits.dtype == np.uint16 and k_cache_bits.flags.c_contiguous and v_cache_bits.flags.c_contiguous
+        assert k_cache_bits.shape[1:] == (s.n_kv_heads, self.cfg.kv_capacity, s.head_dim)
+        assert k_cache_bits.shape[0] >= B
+        ids_a = None if ids is None else _i32(ids)
+        n = s.vocab_size if ids_a is None else ids_a.size
+        fr = None if forced is None else _i32(forced).reshape(B, K - 1)
+        draft = np.full((B, K), -1, dtype=np.int32)
+        logits = np.empty((B, K, n), dtype=self.real) if want_logits else None
+        hidden = np.empty((B, K, s.d_model), dtype=self.real) if want_hidden else None
+        margin = np.empty((B, K), dtype=self.real)
+        rc = self.lib.orc_chain(C.byref(self.cfg), C.byref(self.w), C.c_int32(B), C.c_int32(K), _ptr(hid), _ptr(tok),
+                                _ptr(k_cache_bits), _ptr(v_cache_bits), _ptr(kvl), _ptr(fr), _ptr(ids_a),
+                                C.c_int32(n), _ptr(draft), _ptr(logits), _ptr(hidden), _ptr(margin))
+        if rc:
+            raise ValueError(f"orc_chain failed: {rc}")
+        return {"draft": draft, "logits": logits, "hidden": hidden, "margin": margin}
+
+
+def accept(draft, target, kv_len, mode: int = 0, precision: str = "f32"):
+    """Returns dict(accept_len [B], out_tokens [B][K+1], kv_len [B] (new), pending [B])."""
+    build()
+    lib = C.CDLL(lib_path(precision))
+    dr = _i32(draft)
+    B, K = dr.shape
+    tg = _i32(target).reshape(B, K + 1)
+    kvl = _i32(kv_len).copy()
+    acc = np.empty(B, dtype=np.int32)
+    out = np.empty((B, K + 1), dtype=np.int32)
+    pend = np.empty(B, dtype=np.int32)
+    lib.orc_accept(C.c_int32(B), C.c_int32(K), _ptr(dr), _ptr(tg), C.c_int32(mode), _ptr(kvl), _ptr(acc), _ptr(out),
+                   _ptr(pend))
+    return {"accept_len": acc, "out_tokens": out, "kv_len": kvl, "pending": pend}
