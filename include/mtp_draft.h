@@ -1,0 +1,172 @@
+/*
+ * mtp_draft.h - C ABI of the MI355X (gfx950) FastMTP draft library.
+ *
+ * The library runs the drafting phase of FastMTP (arXiv 2509.18362, Sec. 2.3): K recursive
+ * applications of ONE multi-token-prediction head whose weights are shared by all draft depths
+ * (Sec. 2.1 "Architecture Design"), with the compressed output head of Sec. 2.2 / Eq. (3), followed
+ * by sequential greedy acceptance against the target model's tokens (Sec. 2.3 "Verification phase").
+ *
+ * Conventions
+ *   - "device" pointers are HIP device memory on the current device, owned by the caller; "host"
+ *     pointers are ordinary host memory.  The library allocates no device memory of its own: all
+ *     scratch lives in the caller's workspace.
+ *   - bf16 tensors are 16-bit brain-float bit patterns; matrices are row-major [out][in].
+ *   - Every device pointer must be 16-byte aligned.
+ *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = default stream) and the
+ *     calls return without waiting for it, except where stated.
+ *   - Every function returning int32_t returns MTP_OK (0) or a negative mtp_status; on a host-detected
+ *     error nothing is enqueued and no output is written.
+ *   - One handle must not be used from two streams at the same time: calls share its workspace.
+ */
+#ifndef MTP_DRAFT_H
+#define MTP_DRAFT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MTP_OK = 0,
+    MTP_ERR_NULL = -1,         /* a required pointer is NULL                                  */
+    MTP_ERR_ALIGN = -2,        /* a device pointer is not 16-byte aligned                     */
+    MTP_ERR_CONFIG = -3,       /* unsupported or inconsistent mtp_config                      */
+    MTP_ERR_BATCH = -4,        /* B outside [1, max_batch]                                    */
+    MTP_ERR_STEPS = -5,        /* K outside [1, max_draft_steps]                              */
+    MTP_ERR_SUBSET = -6,       /* subset_index out of range, or an invalid id list at init    */
+    MTP_ERR_WORKSPACE = -7,    /* workspace too small                                         */
+    MTP_ERR_HIP = -8,          /* a HIP runtime call failed                                   */
+    MTP_ERR_KV_OVERFLOW = -9,  /* device saw kv_len[b] + K > kv_capacity (from mtp_poll_error)*/
+    MTP_ERR_TOKEN_RANGE = -10, /* device saw an input token id outside [0, vocab_size)        */
+    MTP_ERR_MODE = -11         /* unknown rollback_mode                                       */
+} mtp_status;
+
+/* Shape of the head (Sec. 3.1 "Model Configuration" for the 7B case) and limits of this handle. Host POD. */
+typedef struct {
+    int32_t d_model;         /* d; multiple of 32                                              */
+    int32_t n_q_heads;       /* Hq                                                             */
+    int32_t n_kv_heads;      /* Hkv; Hq / Hkv must be 1, 2, 4 or 8                             */
+    int32_t head_dim;        /* hd; 64 or 128                                                  */
+    int32_t d_ffn;           /* F, SwiGLU width; multiple of 8                                 */
+    int32_t vocab_size;      /* |V|                                                            */
+    float rms_eps;           /* added to the mean square inside every RMSNorm                  */
+    float rope_theta;        /* rotary base; pairs are (j, j + hd/2), the full head is rotated */
+    int32_t max_batch;       /* largest B a call may pass; rows of the KV cache                */
+    int32_t kv_capacity;     /* cache slots per (sequence, KV head)                            */
+    int32_t max_draft_steps; /* largest K a call may pass                                      */
+} mtp_config;
+
+/* Device pointers to the head's tensors, all bf16.  The embedding table and the output head are the main
+ * model's (Sec. 2.1: only the head is fine-tuned; Sec. 2.2: W is the main model's output head). */
+typedef struct {
+    const void *embed;   /* [V][d]                                                            */
+    const void *lm_head; /* [V][d]  W of Eq. (3)                                              */
+    const void *g_hnorm, *g_enorm, *g_attn_norm, *g_mlp_norm, *g_final_norm; /* RMSNorm gains, [d] each */
+    const void *w_proj;  /* [d][2d]; columns 0..d-1 multiply the normalised hidden state,
+                            columns d..2d-1 the normalised token embedding                    */
+    const void *w_q;     /* [Hq*hd][d]                                                        */
+    const void *w_k;     /* [Hkv*hd][d]                                                       */
+    const void *w_v;     /* [Hkv*hd][d]                                                       */
+    const void *b_q, *b_k, *b_v; /* [Hq*hd], [Hkv*hd], [Hkv*hd]; each may be NULL (no bias)  */
+    const void *w_o;     /* [d][Hq*hd]                                                        */
+    const void *w_gate;  /* [F][d]                                                            */
+    const void *w_up;    /* [F][d]                                                            */
+    const void *w_down;  /* [d][F]                                                            */
+} mtp_weights;
+
+typedef struct mtp_handle mtp_handle; /* host object: configuration, pointers, launch plan */
+
+/* Text for a status code (static storage). */
+const char *mtp_status_string(int32_t status);
+
+/* Bytes of device workspace a handle with this configuration needs.  Host-only, touches no device.
+ * Returns 0 if the configuration is not supported. */
+size_t mtp_workspace_bytes(const mtp_config *cfg);
+
+/*
+ * Create a handle (Sec. 2.2: one id list V_high^(l) per language l; the caller picks one per call).
+ *   n_subsets    number of compressed vocabularies (may be 0)
+ *   subset_ids   host array of n_subsets device pointers; list s holds subset_sizes[s] int32 ids, strictly
+ *                ascending, each in [0, vocab_size).  Row i of the compressed head is W[subset_ids[s][i], :].
+ *   subset_sizes host array of n_subsets sizes, each in [1, vocab_size]
+ *   workspace    device memory of at least mtp_workspace_bytes(cfg) bytes; the library keeps using it until
+ *                mtp_draft_destroy and it must not be shared between handles that run concurrently
+ * The id lists are copied to the host once and validated here (this call synchronises the device); the
+ * device copies stay owned by the caller and must outlive the handle.  The workspace is zeroed.
+ */
+int32_t mtp_draft_init(mtp_handle **out, const mtp_config *cfg, const mtp_weights *weights, int32_t n_subsets,
+                       const int32_t *const *subset_ids, const int32_t *subset_sizes, void *workspace,
+                       size_t workspace_bytes);
+
+/*
+ * K recursive draft steps for B sequences (Sec. 2.3 "Drafting phase"), enqueued without any host wait.
+ * Step k = 1..K for sequence b, at cache position p = kv_len[b] + k - 1:
+ *   c   = [ RMSNorm(h; g_hnorm) ; RMSNorm(embed[x_k]; g_enorm) ]      h = hidden_in[b] at k = 1, else the
+ *                                                                     previous step's output hidden state;
+ *                                                                     x_1 = token_in[b], x_k = draft d_{k-1}
+ *   x   = w_proj c
+ *   y   = RMSNorm(x; g_attn_norm); q,k,v = w_q y + b_q, ...; rotary at position p on q and k;
+ *         k and v are rounded to bf16 into cache slot p; attention of the Hq query heads over slots 0..p
+ *   x1  = x + w_o attn;  x2 = x1 + w_down( silu(w_gate y2) * (w_up y2) ), y2 = RMSNorm(x1; g_mlp_norm)
+ *   hh  = RMSNorm(x2; g_final_norm)                                   the step's output hidden state
+ *   z_i = lm_head[ids[i], :] . hh  for i < n (Eq. (3));  d_k = ids[argmax_i z_i], lowest i on ties
+ * All arithmetic is float32 on bf16 weights; activations entering a matrix product are carried as the sum of
+ * two bf16 numbers (relative error below 2^-16).
+ *
+ *   subset_index  which id list to use; -1 = the full vocabulary (ids[i] = i, n = vocab_size)
+ *   hidden_in     device [B][d] bf16: the target model's last hidden state per sequence
+ *   token_in      device [B] int32: the verified token whose embedding pairs with hidden_in
+ *   k_cache, v_cache  device [max_batch][Hkv][kv_capacity][hd] bf16; keys are stored after the rotary
+ *                 embedding.  Slots kv_len[b] .. kv_len[b]+K-1 of sequence b are overwritten; others are only read
+ *   kv_len        device [B] int32: valid entries per sequence before the call; not modified
+ *   forced_tokens device [B][K-1] int32 or NULL: if given, x_k = forced_tokens[b][k-2] for k >= 2 instead of
+ *                 the previous draft (teacher forcing as in Sec. 2.1 "Training Mechanism"; a test hook)
+ *   draft_out     device [B][K] int32: drafted full-vocabulary ids
+ *   logits_out    device [B][K][n] float32 or NULL
+ *   hidden_out    device [B][K][d] float32 or NULL: hh of every step
+ * Host-detected errors: NULL/misaligned pointers, B, K, subset_index.  Device-detected conditions
+ * (kv_len[b] + K > kv_capacity, token id out of range) make the affected sequence write draft id -1 from the
+ * failing step on, leave its cache untouched, and set a sticky error word read by mtp_poll_error.
+ */
+int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, const void *hidden_in,
+                        const int32_t *token_in, void *k_cache, void *v_cache, const int32_t *kv_len,
+                        const int32_t *forced_tokens, int32_t *draft_out, float *logits_out, float *hidden_out,
+                        void *hip_stream);
+
+/*
+ * Sequential greedy acceptance (Sec. 2.3 "Verification phase": accept until the first position where the draft
+ * differs from the target model's token; Sec. 3.1: strict criteria, greedy decoding) and draft-cache bookkeeping.
+ *   draft      device [B][K] int32   d_1..d_K (from mtp_draft_steps)
+ *   target     device [B][K+1] int32 g_1..g_{K+1}: the target model's greedy tokens at the same positions,
+ *              full-vocabulary ids (verification is not compressed, Sec. 2.2 last sentence)
+ *   rollback_mode 0 = keep confirmed entries: cache slot kv_len+j-1 was built from input token x_j (x_1 verified,
+ *                     x_j = d_{j-1}), so min(a+1, K) slots stay;  pending = 1 iff a == K (no entry for d_K yet)
+ *                 1 = discard every slot written while drafting (kv_len unchanged), pending = 0
+ *   kv_len     device [B] int32, in: length before drafting; out: length after rollback.  No cache bytes move.
+ *   accept_len device [B] int32: a in [0, K]
+ *   out_tokens device [B][K+1] int32: d_1..d_a, g_{a+1}, then -1
+ *   pending    device [B] int32
+ */
+int32_t mtp_accept(mtp_handle *h, int32_t B, int32_t K, const int32_t *draft, const int32_t *target,
+                   int32_t rollback_mode, int32_t *kv_len, int32_t *accept_len, int32_t *out_tokens,
+                   int32_t *pending, void *hip_stream);
+
+/* Waits for `hip_stream`, then returns and clears the sticky device error word:
+ * MTP_OK, MTP_ERR_KV_OVERFLOW or MTP_ERR_TOKEN_RANGE (or MTP_ERR_HIP). */
+int32_t mtp_poll_error(mtp_handle *h, void *hip_stream);
+
+/* Duration in milliseconds of the kernels that the most recent mtp_draft_steps call enqueued, measured with
+ * HIP events recorded on that call's stream (the events are recorded only after mtp_set_timing(h, 1)).
+ * Waits for the stop event.  Returns a negative value if timing is off or nothing was recorded. */
+float mtp_last_draft_ms(mtp_handle *h);
+int32_t mtp_set_timing(mtp_handle *h, int32_t enable);
+
+/* Frees the host object.  Device memory stays with the caller. */
+void mtp_draft_destroy(mtp_handle *h);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MTP_DRAFT_H */

@@ -1,0 +1,220 @@
+"""Thin ctypes binding of libmtp_draft.so: same names as the C ABI (include/mtp_draft.h), argument marshalling only.
+
+Tensors are passed as torch CUDA tensors (or raw integer addresses); PyTorch supplies device memory and streams,
+every step of the draft path runs inside the library's HIP kernels.  There is no fallback: if the library is not
+built, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmtp_draft.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                      "(or python paper_2509_18362_amd/build.py) first; there is no CPU fallback")
+_lib = C.CDLL(LIB_PATH)
+
+MTP_OK = 0
+STATUS = {0: "MTP_OK", -1: "MTP_ERR_NULL", -2: "MTP_ERR_ALIGN", -3: "MTP_ERR_CONFIG", -4: "MTP_ERR_BATCH",
+          -5: "MTP_ERR_STEPS", -6: "MTP_ERR_SUBSET", -7: "MTP_ERR_WORKSPACE", -8: "MTP_ERR_HIP",
+          -9: "MTP_ERR_KV_OVERFLOW", -10: "MTP_ERR_TOKEN_RANGE", -11: "MTP_ERR_MODE"}
+EXPORTS = ["mtp_status_string", "mtp_workspace_bytes", "mtp_draft_init", "mtp_draft_steps", "mtp_accept",
+           "mtp_poll_error", "mtp_set_timing", "mtp_last_draft_ms", "mtp_draft_destroy"]
+# mtp_set_timing modes
+TIMING_OFF, TIMING_CALL = 0, 1
+PHASES = ["proj", "qkv", "attn", "oproj", "gateup", "down", "lmhead"]
+
+
+def timing_phase(name: str) -> int:
+    return 2 + PHASES.index(name)
+
+
+class mtp_config(C.Structure):
+    _fields_ = [("d_model", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("d_ffn", C.c_int32), ("vocab_size", C.c_int32),
+                ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("max_batch", C.c_int32),
+                ("kv_capacity", C.c_int32), ("max_draft_steps", C.c_int32)]
+
+
+WEIGHT_FIELDS = ["embed", "lm_head", "g_hnorm", "g_enorm", "g_attn_norm", "g_mlp_norm", "g_final_norm", "w_proj",
+                 "w_q", "w_k", "w_v", "b_q", "b_k", "b_v", "w_o", "w_gate", "w_up", "w_down"]
+
+
+class mtp_weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in WEIGHT_FIELDS]
+
+
+_lib.mtp_status_string.restype = C.c_char_p
+_lib.mtp_status_string.argtypes = [C.c_int32]
+_lib.mtp_workspace_bytes.restype = C.c_size_t
+_lib.mtp_workspace_bytes.argtypes = [C.POINTER(mtp_config)]
+_lib.mtp_draft_init.restype = C.c_int32
+_lib.mtp_draft_init.argtypes = [C.POINTER(C.c_void_p), C.POINTER(mtp_config), C.POINTER(mtp_weights), C.c_int32,
+                                C.POINTER(C.c_void_p), C.POINTER(C.c_int32), C.c_void_p, C.c_size_t]
+_lib.mtp_draft_steps.restype = C.c_int32
+_lib.mtp_draft_steps.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32] + [C.c_void_p] * 10
+_lib.mtp_accept.restype = C.c_int32
+_lib.mtp_accept.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32] + [C.c_void_p] * 5
+_lib.mtp_poll_error.restype = C.c_int32
+_lib.mtp_poll_error.argtypes = [C.c_void_p, C.c_void_p]
+_lib.mtp_set_timing.restype = C.c_int32
+_lib.mtp_set_timing.argtypes = [C.c_void_p, C.c_int32]
+_lib.mtp_last_draft_ms.restype = C.c_float
+_lib.mtp_last_draft_ms.argtypes = [C.c_void_p]
+_lib.mtp_draft_destroy.restype = None
+_lib.mtp_draft_destroy.argtypes = [C.c_void_p]
+
+
+def _addr(t) -> Optional[int]:
+    """Device address of a torch tensor, an int address, or None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return int(t.data_ptr())
+
+
+def make_config(shape, max_batch: int, kv_capacity: int, max_draft_steps: int) -> mtp_config:
+    return mtp_config(shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.d_ffn,
+                      shape.vocab_size, shape.rms_eps, shape.rope_theta, max_batch, kv_capacity, max_draft_steps)
+
+
+def mtp_status_string(status: int) -> str:
+    return _lib.mtp_status_string(status).decode()
+
+
+def mtp_workspace_bytes(cfg: mtp_config) -> int:
+    return int(_lib.mtp_workspace_bytes(C.byref(cfg)))
+
+
+def mtp_draft_init(cfg: mtp_config, weights: Dict[str, object], subsets: Sequence[object],
+                   subset_sizes: Sequence[int], workspace, workspace_bytes: int):
+    """Returns (status, handle).  weights: name -> device tensor/address (biases optional)."""
+    w = mtp_weights(**{n: _addr(weights.get(n)) for n in WEIGHT_FIELDS})
+    ns = len(subsets)
+    ids = (C.c_void_p * max(ns, 1))(*[_addr(s) for s in subsets])
+    sizes = (C.c_int32 * max(ns, 1))(*[int(s) for s in subset_sizes])
+    handle = C.c_void_p(None)
+    st = _lib.mtp_draft_init(C.byref(handle), C.byref(cfg), C.byref(w), ns, ids if ns else None,
+                             sizes if ns else None, _addr(workspace), workspace_bytes)
+    return int(st), (handle if st == MTP_OK else None)
+
+
+def mtp_draft_steps(handle, B: int, K: int, subset_index: int, hidden_in, token_in, k_cache, v_cache, kv_len,
+                    forced_tokens, draft_out, logits_out, hidden_out, stream: int = 0) -> int:
+    return int(_lib.mtp_draft_steps(handle, B, K, subset_index, _addr(hidden_in), _addr(token_in), _addr(k_cache),
+                                    _addr(v_cache), _addr(kv_len), _addr(forced_tokens), _addr(draft_out),
+                                    _addr(logits_out), _addr(hidden_out), stream or None))
+
+
+def mtp_accept(handle, B: int, K: int, draft, target, rollback_mode: int, kv_len, accept_len, out_tokens, pending,
+               stream: int = 0) -> int:
+    return int(_lib.mtp_accept(handle, B, K, _addr(draft), _addr(target), rollback_mode, _addr(kv_len),
+                               _addr(accept_len), _addr(out_tokens), _addr(pending), stream or None))
+
+
+def mtp_poll_error(handle, stream: int = 0) -> int:
+    return int(_lib.mtp_poll_error(handle, stream or None))
+
+
+def mtp_set_timing(handle, mode: int) -> int:
+    return int(_lib.mtp_set_timing(handle, mode))
+
+
+def mtp_last_draft_ms(handle) -> float:
+    return float(_lib.mtp_last_draft_ms(handle))
+
+
+def mtp_draft_destroy(handle) -> None:
+    _lib.mtp_draft_destroy(handle)
+
+
+class MTPError(RuntimeError):
+    def __init__(self, status: int):
+        super().__init__(f"{STATUS.get(status, status)}: {mtp_status_string(status)}")
+        self.status = status
+
+
+class DraftEngine:
+    """Convenience owner of the device buffers of one handle (memory plumbing only).
+
+    weights_bits: name -> numpy uint16 array (bf16 bit patterns); subsets: list of sorted int32 numpy id lists.
+    """
+
+    def __init__(self, shape, weights_bits: Dict[str, object], subsets: Sequence[object], max_batch: int,
+                 kv_capacity: int, max_draft_steps: int, device: str = "cuda:0"):
+        import numpy as np
+        import torch
+        self.torch = torch
+        self.device = torch.device(device)
+        self.shape = shape
+        self.cfg = make_config(shape, max_batch, kv_capacity, max_draft_steps)
+        # numpy bit patterns are uploaded; tensors already on the device are shared as they are
+        self.w = {k: (v if isinstance(v, torch.Tensor) else
+                      torch.from_numpy(np.ascontiguousarray(v).view(np.int16)).to(self.device))
+                  for k, v in weights_bits.items()}
+        self.subsets = [torch.from_numpy(np.ascontiguousarray(s, dtype=np.int32)).to(self.device) for s in subsets]
+        nbytes = mtp_workspace_bytes(self.cfg)
+        if nbytes == 0:
+            raise MTPError(-3)
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        st, self.handle = mtp_draft_init(self.cfg, self.w, self.subsets, [s.numel() for s in self.subsets],
+                                         self.workspace, nbytes)
+        if st != MTP_OK:
+            raise MTPError(st)
+
+    def subset_size(self, subset_index: int) -> int:
+        return self.shape.vocab_size if subset_index < 0 else self.subsets[subset_index].numel()
+
+    def to_device_bits(self, a):
+        import numpy as np
+        return self.torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).to(self.device)
+
+    def to_device_i32(self, a):
+        import numpy as np
+        return self.torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(self.device)
+
+    def draft(self, K: int, subset_index: int, hidden_in, token_in, k_cache, v_cache, kv_len, forced=None,
+              want_logits: bool = False, want_hidden: bool = False, stream: int = 0):
+        """All tensor arguments are device tensors.  Returns dict(draft, logits, hidden) of device tensors."""
+        torch = self.torch
+        B = token_in.numel()
+        n = self.subset_size(subset_index)
+        draft = torch.empty((B, K), dtype=torch.int32, device=self.device)
+        logits = torch.empty((B, K, n), dtype=torch.float32, device=self.device) if want_logits else None
+        hidden = torch.empty((B, K, self.shape.d_model), dtype=torch.float32, device=self.device) if want_hidden \
+            else None
+        st = mtp_draft_steps(self.handle, B, K, subset_index, hidden_in, token_in, k_cache, v_cache, kv_len, forced,
+                             draft, logits, hidden, stream)
+        if st != MTP_OK:
+            raise MTPError(st)
+        return {"draft": draft, "logits": logits, "hidden": hidden}
+
+    def accept(self, draft, target, kv_len, mode: int = 0, stream: int = 0):
+        torch = self.torch
+        B, K = draft.shape
+        acc = torch.empty(B, dtype=torch.int32, device=self.device)
+        out = torch.empty((B, K + 1), dtype=torch.int32, device=self.device)
+        pend = torch.empty(B, dtype=torch.int32, device=self.device)
+        st = mtp_accept(self.handle, B, K, draft, target, mode, kv_len, acc, out, pend, stream)
+        if st != MTP_OK:
+            raise MTPError(st)
+        return {"accept_len": acc, "out_tokens": out, "pending": pend, "kv_len": kv_len}
+
+    def poll_error(self, stream: int = 0) -> int:
+        return mtp_poll_error(self.handle, stream)
+
+    def close(self) -> None:
+        if getattr(self, "handle", None) is not None:
+            mtp_draft_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

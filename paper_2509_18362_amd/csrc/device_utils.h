@@ -1,0 +1,93 @@
+// Device-side helpers for the gfx950 draft kernels: bf16 packing, 64-lane reductions, MFMA wrappers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mtp {
+
+constexpr int kWave = 64;
+constexpr int kBlock = 512;            // threads per workgroup in every phase
+constexpr int kWaves = kBlock / kWave; // 8
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+// round to nearest even; NaN stays NaN
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// x ~= hi + lo with hi, lo bf16: keeps 16 mantissa bits of a float activation through a bf16 MFMA
+__device__ __forceinline__ void split_bf16(float x, uint16_t &hi, uint16_t &lo) {
+    hi = f32_to_bf16(x);
+    lo = f32_to_bf16(x - bf16_to_f32(hi));
+}
+
+__device__ __forceinline__ float lo_half(uint32_t packed) { return __uint_as_float(packed << 16); }
+__device__ __forceinline__ float hi_half(uint32_t packed) { return __uint_as_float(packed & 0xffff0000u); }
+
+// ---- cross-lane sums -------------------------------------------------------------------------------
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float x) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, true));
+}
+// sum over the 16 lanes of a DPP row; every lane of the row gets the total
+__device__ __forceinline__ float row16_sum(float x) {
+    x += dpp_f32<0xB1>(x);  // quad_perm [1,0,3,2]
+    x += dpp_f32<0x4E>(x);  // quad_perm [2,3,0,1]
+    x += dpp_f32<0x141>(x); // row_half_mirror
+    x += dpp_f32<0x140>(x); // row_mirror
+    return x;
+}
+// sum over 8 consecutive lanes (aligned groups of 8)
+__device__ __forceinline__ float oct_sum(float x) {
+    x += dpp_f32<0xB1>(x);
+    x += dpp_f32<0x4E>(x);
+    x += dpp_f32<0x141>(x);
+    return x;
+}
+__device__ __forceinline__ float wave_sum(float x) {
+    x = row16_sum(x);
+    x += __shfl_xor(x, 16, kWave);
+    x += __shfl_xor(x, 32, kWave);
+    return x;
+}
+// sum over the whole workgroup; red must hold kWaves floats; contains two barriers
+__device__ __forceinline__ float block_sum(float x, float *red) {
+    x = wave_sum(x);
+    __syncthreads();
+    if ((threadIdx.x & (kWave - 1)) == 0) red[threadIdx.x / kWave] = x;
+    __syncthreads();
+    float t = 0.f;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) t += red[w];
+    return t;
+}
+
+// ---- argmax key: larger logit wins, then smaller index ------------------------------------------------
+__device__ __forceinline__ uint32_t orderable(float f) {
+    uint32_t u = __float_as_uint(f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ unsigned long long argmax_key(float logit, uint32_t index) {
+    return ((unsigned long long)orderable(logit) << 32) | (unsigned long long)(0xffffffffu - index);
+}
+__device__ __forceinline__ uint32_t key_index(unsigned long long key) { return 0xffffffffu - (uint32_t)key; }
+
+// ---- 16x16x32 bf16 MFMA: D[i][j] += sum_k A[i][k] * B[k][j] -------------------------------------------
+// lane l supplies A[l%16][(l/16)*8 .. +8] and B[(l/16)*8 .. +8][l%16]; it receives D[(l/16)*4 + v][l%16], v = 0..3
+__device__ __forceinline__ f32x4 mfma16(u32x4 a, u32x4 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0,
+                                                   0, 0);
+}
+
+__device__ __forceinline__ u32x4 ldg16(const void *p) { return *reinterpret_cast<const u32x4 *>(p); }
+
+} // namespace mtp

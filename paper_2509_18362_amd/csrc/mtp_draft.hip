@@ -1,0 +1,489 @@
+// C ABI of the FastMTP draft library for MI355X (gfx950): host-side validation, launch plan and kernel wrappers.
+// See include/mtp_draft.h for the contract of every entry point.
+#include "../../include/mtp_draft.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "phases.h"
+
+using namespace mtp;
+
+namespace {
+
+enum Phase : int { PH_PROJ = 0, PH_QKV, PH_ATTN, PH_OPROJ, PH_GATEUP, PH_DOWN, PH_LMHEAD, PH_COUNT };
+
+// ---- kernels: one launch per phase ------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void k_proj(DraftParams p, int step) {
+    extern __shared__ __align__(16) char smem[];
+    phase_proj(p, step, blockIdx.x, gridDim.x, smem);
+}
+__global__ __launch_bounds__(kBlock) void k_qkv(DraftParams p, int step) {
+    extern __shared__ __align__(16) char smem[];
+    phase_qkv(p, step, blockIdx.x, gridDim.x, smem);
+}
+template <int G, int HD>
+__global__ __launch_bounds__(kBlock) void k_attn(DraftParams p, int step) {
+    extern __shared__ __align__(16) char smem[];
+    phase_attn<G, HD>(p, step, blockIdx.x, gridDim.x, smem);
+}
+__global__ __launch_bounds__(kBlock) void k_oproj(DraftParams p, int step) {
+    extern __shared__ __align__(16) char smem[];
+    phase_oproj(p, step, blockIdx.x, gridDim.x, smem);
+}
+__global__ __launch_bounds__(kBlock) void k_gateup(DraftParams p, int step) {
+    extern __shared__ __align__(16) char smem[];
+    phase_gateup(p, step, blockIdx.x, gridDim.x, smem);
+}
+__global__ __launch_bounds__(kBlock) void k_down(DraftParams p, int step) {
+    extern __shared__ __align__(16) char smem[];
+    phase_down(p, step, blockIdx.x, gridDim.x, smem);
+}
+__global__ __launch_bounds__(kBlock) void k_lmhead(DraftParams p, int step) {
+    extern __shared__ __align__(16) char smem[];
+    phase_lmhead(p, step, blockIdx.x, gridDim.x, smem);
+}
+__global__ void k_finalize(DraftParams p) { phase_finalize(p, blockIdx.x); }
+
+// Sequential acceptance up to the first mismatch and the draft-cache length after it (Sec. 2.3 "Verification phase").
+__global__ void k_accept(int B, int K, const int *draft, const int *target, int mode, int *kv_len, int *accept_len,
+                         int *out_tokens, int *pending) {
+    int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    const int *dr = draft + (size_t)b * K;
+    const int *tg = target + (size_t)b * (K + 1);
+    int a = 0;
+    while (a < K && dr[a] == tg[a]) ++a;
+    int *out = out_tokens + (size_t)b * (K + 1);
+    for (int j = 0; j <= K; ++j) out[j] = j < a ? dr[j] : (j == a ? tg[a] : -1);
+    accept_len[b] = a;
+    if (mode == 0) {
+        kv_len[b] += min(a + 1, K);
+        pending[b] = (a == K) ? 1 : 0;
+    } else {
+        pending[b] = 0;
+    }
+}
+
+typedef void (*phase_kernel_t)(DraftParams, int);
+
+phase_kernel_t attn_kernel(int G, int HD) {
+    if (HD == 128) {
+        switch (G) {
+        case 1: return k_attn<1, 128>;
+        case 2: return k_attn<2, 128>;
+        case 4: return k_attn<4, 128>;
+        case 8: return k_attn<8, 128>;
+        }
+    } else if (HD == 64) {
+        switch (G) {
+        case 1: return k_attn<1, 64>;
+        case 2: return k_attn<2, 64>;
+        case 4: return k_attn<4, 64>;
+        case 8: return k_attn<8, 64>;
+        }
+    }
+    return nullptr;
+}
+size_t attn_lds_bytes(int G, int HD) {
+    int tpi = kWave / (HD / 8), ns = kWaves * tpi;
+    size_t fl = (size_t)G * HD + HD + 2 * HD + (size_t)ns * G * HD + (size_t)ns * G * 2;
+    return fl * sizeof(float) + 64;
+}
+
+// ---- plan: how a call of B sequences is cut up ----------------------------------------------------------
+constexpr int kTargetAttnItems = 2048; // (sequence, KV head, split) items aimed for
+constexpr int kMinSplitTokens = 64;
+constexpr size_t kLdsSmallBatch = 72 * 1024;  // two workgroups per CU
+constexpr size_t kLdsLargeBatch = 150 * 1024; // one workgroup per CU, more sequences per weight pass
+
+int split_tokens_for(const mtp_config &c, int B) {
+    long long t = ((long long)c.kv_capacity * B * c.n_kv_heads + kTargetAttnItems - 1) / kTargetAttnItems;
+    t = std::max<long long>(t, kMinSplitTokens);
+    t = (t + 63) / 64 * 64;
+    return (int)t;
+}
+int max_splits_for(const mtp_config &c, int B) {
+    int t = split_tokens_for(c, B);
+    return (c.kv_capacity + t - 1) / t;
+}
+size_t attn_part_floats(const mtp_config &c) {
+    size_t best = 0;
+    for (int B = 1; B <= c.max_batch; ++B)
+        best = std::max(best, (size_t)B * max_splits_for(c, B));
+    return best * c.n_q_heads * (c.head_dim + 2);
+}
+
+bool config_ok(const mtp_config *c) {
+    if (!c) return false;
+    if (c->d_model < 32 || c->d_model > 8192 || c->d_model % 32) return false;
+    if (c->head_dim != 64 && c->head_dim != 128) return false;
+    if (c->n_q_heads < 1 || c->n_kv_heads < 1 || c->n_q_heads % c->n_kv_heads) return false;
+    int G = c->n_q_heads / c->n_kv_heads;
+    if (G != 1 && G != 2 && G != 4 && G != 8) return false;
+    if (c->d_ffn < 8 || c->d_ffn % 8) return false;
+    if (c->vocab_size < 1) return false;
+    if (c->max_batch < 1 || c->max_batch > kBlock) return false;
+    if (c->max_draft_steps < 1 || c->kv_capacity < c->max_draft_steps) return false;
+    if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f)) return false;
+    if ((long long)c->n_q_heads * c->head_dim > 65536) return false;
+    return true;
+}
+
+constexpr size_t kAlign = 256;
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+struct WsLayout {
+    size_t x, qkv, attn, x1, m, x2, hhat, keys, err, attn_cnt, attn_part, total;
+};
+WsLayout ws_layout(const mtp_config &c) {
+    WsLayout l{};
+    size_t mb = c.max_batch, d = c.d_model, qd = (size_t)c.n_q_heads * c.head_dim,
+           kvd = (size_t)c.n_kv_heads * c.head_dim;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        size_t o = off;
+        off = align_up(off + bytes);
+        return o;
+    };
+    l.x = take(mb * d * 4);
+    l.qkv = take(mb * (qd + 2 * kvd) * 4);
+    l.attn = take(mb * qd * 4);
+    l.x1 = take(mb * d * 4);
+    l.m = take(mb * (size_t)c.d_ffn * 4);
+    l.x2 = take(mb * d * 4);
+    l.hhat = take(mb * d * 4);
+    l.keys = take((size_t)c.max_draft_steps * mb * 8);
+    l.err = take(4);
+    l.attn_cnt = take(mb * c.n_kv_heads * 4);
+    l.attn_part = take(attn_part_floats(c) * 4);
+    l.total = off;
+    return l;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+} // namespace
+
+struct mtp_handle {
+    mtp_config cfg;
+    mtp_weights w;
+    std::vector<const int *> subset_dev;
+    std::vector<int> subset_n;
+    char *ws;
+    WsLayout lay;
+    int num_cus;
+    size_t lds_limit;
+    phase_kernel_t attn_fn;
+    int timing;         // 0 off, 1 whole call, 2 + phase: every launch of one phase
+    hipEvent_t ev[2];   // whole call
+    std::vector<hipEvent_t> pev; // per-step pairs for one phase
+    int pev_used;
+    bool ev_recorded;
+};
+
+extern "C" {
+
+const char *mtp_status_string(int32_t s) {
+    switch (s) {
+    case MTP_OK: return "ok";
+    case MTP_ERR_NULL: return "required pointer is NULL";
+    case MTP_ERR_ALIGN: return "device pointer is not 16-byte aligned";
+    case MTP_ERR_CONFIG: return "unsupported or inconsistent configuration";
+    case MTP_ERR_BATCH: return "batch size outside [1, max_batch]";
+    case MTP_ERR_STEPS: return "draft steps outside [1, max_draft_steps]";
+    case MTP_ERR_SUBSET: return "invalid subset index or id list";
+    case MTP_ERR_WORKSPACE: return "workspace too small";
+    case MTP_ERR_HIP: return "HIP runtime call failed";
+    case MTP_ERR_KV_OVERFLOW: return "kv_len + K exceeds kv_capacity for some sequence";
+    case MTP_ERR_TOKEN_RANGE: return "token id outside the vocabulary";
+    case MTP_ERR_MODE: return "unknown rollback mode";
+    default: return "unknown status";
+    }
+}
+
+size_t mtp_workspace_bytes(const mtp_config *cfg) {
+    if (!config_ok(cfg)) return 0;
+    return ws_layout(*cfg).total;
+}
+
+int32_t mtp_draft_init(mtp_handle **out, const mtp_config *cfg, const mtp_weights *w, int32_t n_subsets,
+                       const int32_t *const *subset_ids, const int32_t *subset_sizes, void *workspace,
+                       size_t workspace_bytes) {
+    if (!out || !cfg || !w || !workspace) return MTP_ERR_NULL;
+    *out = nullptr;
+    if (!config_ok(cfg)) return MTP_ERR_CONFIG;
+    const void *req[] = {w->embed, w->lm_head, w->g_hnorm, w->g_enorm, w->g_attn_norm, w->g_mlp_norm,
+                         w->g_final_norm, w->w_proj, w->w_q, w->w_k, w->w_v, w->w_o, w->w_gate, w->w_up, w->w_down};
+    for (const void *p : req)
+        if (!p) return MTP_ERR_NULL;
+    const void *all[] = {w->embed, w->lm_head, w->g_hnorm, w->g_enorm, w->g_attn_norm, w->g_mlp_norm,
+                         w->g_final_norm, w->w_proj, w->w_q, w->w_k, w->w_v, w->b_q, w->b_k, w->b_v, w->w_o,
+                         w->w_gate, w->w_up, w->w_down, workspace};
+    for (const void *p : all)
+        if (!aligned16(p)) return MTP_ERR_ALIGN;
+    if (n_subsets < 0) return MTP_ERR_SUBSET;
+    if (n_subsets > 0 && (!subset_ids || !subset_sizes)) return MTP_ERR_NULL;
+    WsLayout lay = ws_layout(*cfg);
+    if (workspace_bytes < lay.total) return MTP_ERR_WORKSPACE;
+
+    // id lists: strictly ascending, inside the vocabulary
+    std::vector<int32_t> host;
+    for (int s = 0; s < n_subsets; ++s) {
+        if (!subset_ids[s]) return MTP_ERR_NULL;
+        if (!aligned16(subset_ids[s])) return MTP_ERR_ALIGN;
+        int n = subset_sizes[s];
+        if (n < 1 || n > cfg->vocab_size) return MTP_ERR_SUBSET;
+        host.resize(n);
+        if (hipMemcpy(host.data(), subset_ids[s], (size_t)n * 4, hipMemcpyDeviceToHost) != hipSuccess)
+            return MTP_ERR_HIP;
+        if (host[0] < 0 || host[n - 1] >= cfg->vocab_size) return MTP_ERR_SUBSET;
+        for (int i = 1; i < n; ++i)
+            if (host[i] <= host[i - 1]) return MTP_ERR_SUBSET;
+    }
+
+    mtp_handle *h = new (std::nothrow) mtp_handle();
+    if (!h) return MTP_ERR_HIP;
+    h->cfg = *cfg;
+    h->w = *w;
+    for (int s = 0; s < n_subsets; ++s) {
+        h->subset_dev.push_back(subset_ids[s]);
+        h->subset_n.push_back(subset_sizes[s]);
+    }
+    h->ws = static_cast<char *>(workspace);
+    h->lay = lay;
+    h->timing = 0;
+    h->ev_recorded = false;
+    h->pev_used = 0;
+    int dev = 0, cus = 0, lds = 0;
+    bool ok = hipGetDevice(&dev) == hipSuccess &&
+              hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
+              hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) == hipSuccess;
+    ok = ok && hipEventCreate(&h->ev[0]) == hipSuccess && hipEventCreate(&h->ev[1]) == hipSuccess;
+    if (ok) {
+        h->pev.resize(2 * (size_t)cfg->max_draft_steps);
+        for (auto &e : h->pev) ok = ok && hipEventCreate(&e) == hipSuccess;
+    }
+    h->num_cus = cus;
+    h->lds_limit = (size_t)lds;
+    h->attn_fn = attn_kernel(cfg->n_q_heads / cfg->n_kv_heads, cfg->head_dim);
+    ok = ok && h->attn_fn != nullptr;
+    // allow the large-LDS launches
+    const void *fns[] = {(const void *)k_proj, (const void *)k_qkv, (const void *)k_oproj, (const void *)k_gateup,
+                         (const void *)k_down, (const void *)k_lmhead, (const void *)h->attn_fn};
+    for (const void *f : fns)
+        ok = ok && hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)h->lds_limit) == hipSuccess;
+    ok = ok && hipMemset(workspace, 0, lay.total) == hipSuccess && hipDeviceSynchronize() == hipSuccess;
+    if (!ok) {
+        (void)hipGetLastError();
+        delete h;
+        return MTP_ERR_HIP;
+    }
+    *out = h;
+    return MTP_OK;
+}
+
+int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, const void *hidden_in,
+                        const int32_t *token_in, void *k_cache, void *v_cache, const int32_t *kv_len,
+                        const int32_t *forced_tokens, int32_t *draft_out, float *logits_out, float *hidden_out,
+                        void *hip_stream) {
+    if (!h || !hidden_in || !token_in || !k_cache || !v_cache || !kv_len || !draft_out) return MTP_ERR_NULL;
+    const void *ptrs[] = {hidden_in, token_in, k_cache, v_cache, kv_len, forced_tokens, draft_out, logits_out,
+                          hidden_out};
+    for (const void *p : ptrs)
+        if (!aligned16(p)) return MTP_ERR_ALIGN;
+    const mtp_config &c = h->cfg;
+    if (B < 1 || B > c.max_batch) return MTP_ERR_BATCH;
+    if (K < 1 || K > c.max_draft_steps) return MTP_ERR_STEPS;
+    if (subset_index < -1 || subset_index >= (int)h->subset_dev.size()) return MTP_ERR_SUBSET;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+
+    DraftParams p{};
+    p.d = c.d_model;
+    p.Hq = c.n_q_heads;
+    p.Hkv = c.n_kv_heads;
+    p.hd = c.head_dim;
+    p.F = c.d_ffn;
+    p.V = c.vocab_size;
+    p.qd = c.n_q_heads * c.head_dim;
+    p.kvd = c.n_kv_heads * c.head_dim;
+    p.qkv_dim = p.qd + 2 * p.kvd;
+    p.cap = c.kv_capacity;
+    p.eps = c.rms_eps;
+    p.theta = c.rope_theta;
+    p.B = B;
+    p.K = K;
+    p.ids = subset_index < 0 ? nullptr : h->subset_dev[subset_index];
+    p.n = subset_index < 0 ? c.vocab_size : h->subset_n[subset_index];
+    const mtp_weights &w = h->w;
+    auto u16 = [](const void *q) { return static_cast<const uint16_t *>(q); };
+    p.embed = u16(w.embed);
+    p.lm_head = u16(w.lm_head);
+    p.g_h = u16(w.g_hnorm);
+    p.g_e = u16(w.g_enorm);
+    p.g_attn = u16(w.g_attn_norm);
+    p.g_mlp = u16(w.g_mlp_norm);
+    p.g_final = u16(w.g_final_norm);
+    p.w_proj = u16(w.w_proj);
+    p.w_q = u16(w.w_q);
+    p.w_k = u16(w.w_k);
+    p.w_v = u16(w.w_v);
+    p.b_q = u16(w.b_q);
+    p.b_k = u16(w.b_k);
+    p.b_v = u16(w.b_v);
+    p.w_o = u16(w.w_o);
+    p.w_gate = u16(w.w_gate);
+    p.w_up = u16(w.w_up);
+    p.w_down = u16(w.w_down);
+    p.hidden_in = u16(hidden_in);
+    p.token_in = token_in;
+    p.kv_len = kv_len;
+    p.forced = forced_tokens;
+    p.k_cache = static_cast<uint16_t *>(k_cache);
+    p.v_cache = static_cast<uint16_t *>(v_cache);
+    p.draft_out = draft_out;
+    p.logits_out = logits_out;
+    p.hidden_out = hidden_out;
+    char *ws = h->ws;
+    const WsLayout &l = h->lay;
+    p.x = reinterpret_cast<float *>(ws + l.x);
+    p.qkv = reinterpret_cast<float *>(ws + l.qkv);
+    p.attn = reinterpret_cast<float *>(ws + l.attn);
+    p.x1 = reinterpret_cast<float *>(ws + l.x1);
+    p.m = reinterpret_cast<float *>(ws + l.m);
+    p.x2 = reinterpret_cast<float *>(ws + l.x2);
+    p.hhat = reinterpret_cast<float *>(ws + l.hhat);
+    p.keys = reinterpret_cast<unsigned long long *>(ws + l.keys);
+    p.err = reinterpret_cast<int *>(ws + l.err);
+    p.attn_cnt = reinterpret_cast<int *>(ws + l.attn_cnt);
+    p.attn_part = reinterpret_cast<float *>(ws + l.attn_part);
+    p.max_batch = c.max_batch;
+    p.split_tokens = split_tokens_for(c, B);
+    p.max_splits = max_splits_for(c, B);
+
+    // sequences per weight pass, bounded by LDS
+    size_t budget = std::min(h->lds_limit, B <= 2 ? kLdsSmallBatch : kLdsLargeBatch);
+    auto fit = [&](int Kdim, int nmat) {
+        int nb = 1;
+        while (nb < std::min(B, 16) && gemv_lds_bytes(Kdim, nb + 1, nmat) <= budget) ++nb;
+        return nb;
+    };
+    p.nb_proj = fit(2 * p.d, 1);
+    p.nb_d = fit(p.d, 2);
+    p.nb_q = fit(p.qd, 1);
+    p.nb_down = fit(p.F, 1);
+    const size_t lds_proj = gemv_lds_bytes(2 * p.d, p.nb_proj, 1), lds_d1 = gemv_lds_bytes(p.d, p.nb_d, 1),
+                 lds_d2 = gemv_lds_bytes(p.d, p.nb_d, 2), lds_q = gemv_lds_bytes(p.qd, p.nb_q, 1),
+                 lds_down = gemv_lds_bytes(p.F, p.nb_down, 1), lds_attn = attn_lds_bytes(p.Hq / p.Hkv, p.hd);
+    const size_t lds_max = std::max({lds_proj, lds_d2, lds_q, lds_down, lds_attn});
+    if (lds_max > h->lds_limit) return MTP_ERR_CONFIG;
+
+    const int grid = h->num_cus * (B <= 2 ? 2 : 1);
+    const int attn_items = B * p.Hkv * p.max_splits;
+    const int attn_grid = std::max(1, std::min(attn_items, h->num_cus * 2));
+
+    const int tphase = h->timing >= 2 ? h->timing - 2 : -1;
+    h->pev_used = 0;
+    auto launch = [&](int phase, phase_kernel_t fn, int g, size_t lds, int step) {
+        if (phase == tphase) (void)hipEventRecord(h->pev[2 * (size_t)step], st);
+        hipLaunchKernelGGL(fn, dim3(g), dim3(kBlock), lds, st, p, step);
+        if (phase == tphase) {
+            (void)hipEventRecord(h->pev[2 * (size_t)step + 1], st);
+            h->pev_used = step + 1;
+        }
+    };
+    if (h->timing == 1) (void)hipEventRecord(h->ev[0], st);
+    for (int step = 0; step < K; ++step) {
+        launch(PH_PROJ, k_proj, grid, lds_proj, step);
+        launch(PH_QKV, k_qkv, grid, lds_d1, step);
+        launch(PH_ATTN, h->attn_fn, attn_grid, lds_attn, step);
+        launch(PH_OPROJ, k_oproj, grid, lds_q, step);
+        launch(PH_GATEUP, k_gateup, grid, lds_d2, step);
+        launch(PH_DOWN, k_down, grid, lds_down, step);
+        launch(PH_LMHEAD, k_lmhead, grid, lds_d1, step);
+    }
+    hipLaunchKernelGGL(k_finalize, dim3(1), dim3(kBlock), 0, st, p);
+    if (h->timing == 1) {
+        (void)hipEventRecord(h->ev[1], st);
+        h->ev_recorded = true;
+    }
+    if (hipGetLastError() != hipSuccess) return MTP_ERR_HIP;
+    return MTP_OK;
+}
+
+int32_t mtp_accept(mtp_handle *h, int32_t B, int32_t K, const int32_t *draft, const int32_t *target,
+                   int32_t rollback_mode, int32_t *kv_len, int32_t *accept_len, int32_t *out_tokens,
+                   int32_t *pending, void *hip_stream) {
+    if (!h || !draft || !target || !kv_len || !accept_len || !out_tokens || !pending) return MTP_ERR_NULL;
+    const void *ptrs[] = {draft, target, kv_len, accept_len, out_tokens, pending};
+    for (const void *p : ptrs)
+        if (!aligned16(p)) return MTP_ERR_ALIGN;
+    if (B < 1 || B > h->cfg.max_batch) return MTP_ERR_BATCH;
+    if (K < 1 || K > h->cfg.max_draft_steps) return MTP_ERR_STEPS;
+    if (rollback_mode != 0 && rollback_mode != 1) return MTP_ERR_MODE;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    hipLaunchKernelGGL(k_accept, dim3((B + 63) / 64), dim3(64), 0, st, B, K, draft, target, rollback_mode, kv_len,
+                       accept_len, out_tokens, pending);
+    if (hipGetLastError() != hipSuccess) return MTP_ERR_HIP;
+    return MTP_OK;
+}
+
+int32_t mtp_poll_error(mtp_handle *h, void *hip_stream) {
+    if (!h) return MTP_ERR_NULL;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    int word = 0;
+    int *dev = reinterpret_cast<int *>(h->ws + h->lay.err);
+    if (hipMemcpyAsync(&word, dev, 4, hipMemcpyDeviceToHost, st) != hipSuccess) return MTP_ERR_HIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return MTP_ERR_HIP;
+    if (word != 0) {
+        if (hipMemsetAsync(dev, 0, 4, st) != hipSuccess) return MTP_ERR_HIP;
+        if (hipStreamSynchronize(st) != hipSuccess) return MTP_ERR_HIP;
+    }
+    if (word & kErrKvOverflow) return MTP_ERR_KV_OVERFLOW;
+    if (word & kErrTokenRange) return MTP_ERR_TOKEN_RANGE;
+    return MTP_OK;
+}
+
+int32_t mtp_set_timing(mtp_handle *h, int32_t mode) {
+    if (!h) return MTP_ERR_NULL;
+    if (mode < 0 || mode >= 2 + PH_COUNT) return MTP_ERR_MODE;
+    h->timing = mode;
+    h->ev_recorded = false;
+    h->pev_used = 0;
+    return MTP_OK;
+}
+
+float mtp_last_draft_ms(mtp_handle *h) {
+    if (!h) return -1.f;
+    float ms = 0.f;
+    if (h->timing == 1 && h->ev_recorded) {
+        if (hipEventSynchronize(h->ev[1]) != hipSuccess) return -1.f;
+        if (hipEventElapsedTime(&ms, h->ev[0], h->ev[1]) != hipSuccess) return -1.f;
+        return ms;
+    }
+    if (h->timing >= 2 && h->pev_used > 0) { // mean duration of the selected phase's launches
+        float tot = 0.f;
+        for (int s = 0; s < h->pev_used; ++s) {
+            if (hipEventSynchronize(h->pev[2 * (size_t)s + 1]) != hipSuccess) return -1.f;
+            if (hipEventElapsedTime(&ms, h->pev[2 * (size_t)s], h->pev[2 * (size_t)s + 1]) != hipSuccess) return -1.f;
+            tot += ms;
+        }
+        return tot / (float)h->pev_used;
+    }
+    return -1.f;
+}
+
+void mtp_draft_destroy(mtp_handle *h) {
+    if (!h) return;
+    (void)hipEventDestroy(h->ev[0]);
+    (void)hipEventDestroy(h->ev[1]);
+    for (auto &e : h->pev) (void)hipEventDestroy(e);
+    delete h;
+}
+
+} // extern "C"

@@ -26,6 +26,8 @@ import numpy as np
 
 BASE_SEED = 250918362
 _CHUNK = 1 << 22  # elements drawn per independent stream
+_DIRECT_CACHE_ELEMS = 1 << 28  # KV caches up to this size are drawn element by element
+_POOL_ELEMS = 1 << 26
 
 
 @dataclasses.dataclass(frozen=True)
@@ -181,11 +183,27 @@ def make_activations(wl: Workload, ctx: Optional[np.ndarray] = None, threads: in
     cap = capacity if capacity is not None else kv_capacity_for(wl, ctx)
     hidden = normal_bf16(wl.index, _S_HIDDEN, (B, s.d_model), 0.0, 1.0, threads)
     token = _rng(wl.index, _S_TOKEN).integers(0, s.vocab_size, size=B).astype(np.int32)
-    kc = normal_bf16(wl.index, _S_KCACHE, (B, s.n_kv_heads, cap, s.head_dim), 0.0, 1.0, threads)
-    vc = normal_bf16(wl.index, _S_VCACHE, (B, s.n_kv_heads, cap, s.head_dim), 0.0, 1.0, threads)
-    for b in range(B):
-        kc[b, :, ctx[b]:, :] = 0
-        vc[b, :, ctx[b]:, :] = 0
+    shape = (B, s.n_kv_heads, cap, s.head_dim)
+    if int(np.prod(shape)) <= _DIRECT_CACHE_ELEMS:
+        kc = normal_bf16(wl.index, _S_KCACHE, shape, 0.0, 1.0, threads)
+        vc = normal_bf16(wl.index, _S_VCACHE, shape, 0.0, 1.0, threads)
+        for b in range(B):
+            kc[b, :, ctx[b]:, :] = 0
+            vc[b, :, ctx[b]:, :] = 0
+    else:
+        # very large caches: every (sequence, KV head) stream is a window, at a seeded offset, into one pool of
+        # N(0,1) draws; within a stream the entries are still independent
+        pool_k = normal_bf16(wl.index, _S_KCACHE, (_POOL_ELEMS,), 0.0, 1.0, threads)
+        pool_v = normal_bf16(wl.index, _S_VCACHE, (_POOL_ELEMS,), 0.0, 1.0, threads)
+        offs = _rng(wl.index, _S_KCACHE + 50).integers(0, (_POOL_ELEMS - cap * s.head_dim) // s.head_dim,
+                                                       size=(2, B, s.n_kv_heads)) * s.head_dim
+        kc = np.zeros(shape, dtype=np.uint16)
+        vc = np.zeros(shape, dtype=np.uint16)
+        for b in range(B):
+            nel = int(ctx[b]) * s.head_dim
+            for g in range(s.n_kv_heads):
+                kc[b, g].reshape(-1)[:nel] = pool_k[offs[0, b, g]:offs[0, b, g] + nel]
+                vc[b, g].reshape(-1)[:nel] = pool_v[offs[1, b, g]:offs[1, b, g] + nel]
     return {"hidden_in": hidden, "token_in": token, "kv_len": ctx.copy(), "k_cache": kc, "v_cache": vc,
             "kv_capacity": cap}
 

@@ -1,0 +1,341 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on the same seeded inputs.
+
+Bars (stated with the build's target): accept lengths, emitted tokens, kv_len and pending bit-exact; logits within
+2e-2 max-abs of the float32 oracle; drafted ids equal wherever the oracle's top-1/top-2 margin exceeds 1e-2.
+A tighter bound (LOGIT_TIGHT) guards the design itself: activations enter every product as hi+lo bf16 pairs
+(relative error < 2^-16) and sums are float32, so the measured gap sits near 1e-4; a dropped lo term or a wrong
+lane mapping would land between the two bounds.
+"""
+import itertools
+
+import numpy as np
+import pytest
+
+from paper_2509_18362_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+LOGIT_TOL = 2e-2
+LOGIT_TIGHT = 2e-3
+MARGIN = 1e-2
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available()
+    from oracle.oracle import Oracle
+    from oracle import oracle as orc_mod
+    from paper_2509_18362_amd import binding
+    return {"torch": torch, "Oracle": Oracle, "orc": orc_mod, "binding": binding}
+
+
+def appended_entries_close(got_bits, ref_bits):
+    """Appended cache entries: both sides round a float32 value to bf16, but they sum in different orders, so the
+    float32 values differ by ~1e-6 of the vector's scale and the rounded ones by at most one bf16 step (2^-7
+    relative) plus that absolute slack (which matters only for entries that cancel to almost zero)."""
+    g = synth.bf16_bits_to_f32(got_bits).astype(np.float64)
+    r = synth.bf16_bits_to_f32(ref_bits).astype(np.float64)
+    scale = max(float(np.abs(r).max()), 1e-30)
+    return bool((np.abs(g - r) <= 2.0 ** -7 * np.abs(r) + 1e-5 * scale).all())
+
+
+def run_both(gpu, shape, w_host, w_dev, act, subsets, subset_index, K, engine=None, forced="oracle", seqs=None,
+             max_batch=None):
+    """Runs the oracle (float32) and the library on the same inputs.  `forced="oracle"`: the library is fed the
+    oracle's drafts at steps 2..K so both chains see identical inputs; `None`: free-running.
+    `seqs`: oracle only on these sequences (library always runs the whole batch)."""
+    torch, Oracle, binding = gpu["torch"], gpu["Oracle"], gpu["binding"]
+    B = len(act["kv_len"])
+    cap = act["kv_capacity"]
+    ids = None if subset_index < 0 else subsets[subset_index]
+    sel = list(range(B)) if seqs is None else list(seqs)
+    orc = Oracle(shape, w_host, cap, "f32")
+    okc, ovc = act["k_cache"][sel].copy(), act["v_cache"][sel].copy()
+    ref = orc.chain(K, act["hidden_in"][sel], act["token_in"][sel], okc, ovc, act["kv_len"][sel], ids)
+    own = engine is None
+    if own:
+        engine = binding.DraftEngine(shape, w_dev, subsets, max_batch or B, cap, K)
+    dkc, dvc = engine.to_device_bits(act["k_cache"]), engine.to_device_bits(act["v_cache"])
+    forced_dev = None
+    if forced == "oracle" and K > 1:
+        full = np.zeros((B, K - 1), dtype=np.int32)
+        full[sel] = ref["draft"][:, :K - 1]
+        forced_dev = engine.to_device_i32(full)
+    out = engine.draft(K, subset_index, engine.to_device_bits(act["hidden_in"]), engine.to_device_i32(act["token_in"]),
+                       dkc, dvc, engine.to_device_i32(act["kv_len"]), forced=forced_dev, want_logits=True,
+                       want_hidden=True)
+    torch.cuda.synchronize()
+    assert engine.poll_error() == 0
+    res = {"draft": out["draft"].cpu().numpy()[sel], "logits": out["logits"].cpu().numpy()[sel],
+           "hidden": out["hidden"].cpu().numpy()[sel],
+           "k_cache": dkc.cpu().numpy().view(np.uint16)[sel], "v_cache": dvc.cpu().numpy().view(np.uint16)[sel]}
+    if own:
+        engine.close()
+    return ref, res, (okc, ovc)
+
+
+def check_chain(ref, res, caches, kv_len, K, aligned=True):
+    okc, ovc = caches
+    gap = float(np.abs(ref["logits"] - res["logits"]).max()) if aligned else None
+    if aligned:
+        assert gap <= LOGIT_TOL, gap
+        assert gap <= LOGIT_TIGHT, gap
+        assert np.abs(ref["hidden"] - res["hidden"]).max() <= 2e-3
+        clear = ref["margin"] > MARGIN
+        assert clear.any()
+        np.testing.assert_array_equal(ref["draft"][clear], res["draft"][clear])
+    else:  # free-running: compare every chain up to its first unclear step
+        for b in range(ref["draft"].shape[0]):
+            for k in range(K):
+                if ref["margin"][b, k] <= MARGIN:
+                    break
+                assert ref["draft"][b, k] == res["draft"][b, k]
+                assert np.abs(ref["logits"][b, k] - res["logits"][b, k]).max() <= LOGIT_TOL
+    # cache: prior entries untouched, appended entries equal up to one bf16 step (the two sides sum in different orders)
+    for i, L in enumerate(kv_len):
+        L = int(L)
+        assert np.array_equal(res["k_cache"][i][:, :L], okc[i][:, :L])
+        assert np.array_equal(res["v_cache"][i][:, :L], ovc[i][:, :L])
+        if aligned:
+            assert appended_entries_close(res["k_cache"][i][:, L:L + K], okc[i][:, L:L + K])
+            assert appended_entries_close(res["v_cache"][i][:, L:L + K], ovc[i][:, L:L + K])
+        assert np.array_equal(res["k_cache"][i][:, L + K:], okc[i][:, L + K:])
+    return gap
+
+
+# ------------------------------------------------------------------------------------------ tiny head (config 1)
+def test_tiny_chain_forced_and_free(gpu, tiny):
+    act, ids = tiny["act"], tiny["ids"]
+    for forced in ("oracle", None):
+        ref, res, caches = run_both(gpu, tiny["shape"], tiny["w"], tiny["w"], act, [ids], 0, 3, forced=forced)
+        check_chain(ref, res, caches, act["kv_len"], 3, aligned=(forced == "oracle"))
+
+
+def test_tiny_ragged_batch_and_empty_context(gpu, tiny):
+    """B = 5 with contexts 0 (no prior entries), 1, 63, 64 and 150: spans split boundaries and the degenerate case."""
+    wl = tiny["wl"]
+    act = synth.make_activations(wl, ctx=np.array([0, 1, 63, 64, 150], dtype=np.int32), capacity=192)
+    ref, res, caches = run_both(gpu, tiny["shape"], tiny["w"], tiny["w"], act, [tiny["ids"]], 0, 3)
+    check_chain(ref, res, caches, act["kv_len"], 3)
+
+
+def test_tiny_full_vocab_equals_identity_subset(gpu, tiny):
+    """Eq. (3) with the identity list is the full head: same logits bit for bit on the device as well."""
+    act = tiny["act"]
+    V = tiny["shape"].vocab_size
+    ident = np.arange(V, dtype=np.int32)
+    ref, res_full, caches = run_both(gpu, tiny["shape"], tiny["w"], tiny["w"], act, [ident], -1, 2)
+    check_chain(ref, res_full, caches, act["kv_len"], 2)
+    _, res_id, _ = run_both(gpu, tiny["shape"], tiny["w"], tiny["w"], act, [ident], 0, 2)
+    np.testing.assert_array_equal(res_full["logits"], res_id["logits"])
+    np.testing.assert_array_equal(res_full["draft"], res_id["draft"])
+
+
+def test_tiny_without_bias_and_single_step(gpu, tiny):
+    w = {k: v for k, v in tiny["w"].items() if not k.startswith("b_")}
+    act = tiny["act"]
+    ref, res, caches = run_both(gpu, tiny["shape"], w, w, act, [tiny["ids"]], 0, 1)
+    check_chain(ref, res, caches, act["kv_len"], 1)
+
+
+def test_tiny_ragged_subset_sizes(gpu, tiny):
+    """Subset sizes that are not multiples of the 16-row tile, down to a single id."""
+    act = tiny["act"]
+    rng = np.random.default_rng(5)
+    V = tiny["shape"].vocab_size
+    subsets = [np.sort(rng.choice(V, size=n, replace=False)).astype(np.int32) for n in (1, 17, 1000, 4095)]
+    torch, binding = gpu["torch"], gpu["binding"]
+    eng = binding.DraftEngine(tiny["shape"], tiny["w"], subsets, 1, act["kv_capacity"], 2)
+    for si in range(len(subsets)):
+        ref, res, caches = run_both(gpu, tiny["shape"], tiny["w"], tiny["w"], act, subsets, si, 2, engine=eng)
+        if subsets[si].size > 1:
+            check_chain(ref, res, caches, act["kv_len"], 2)
+        else:
+            assert (res["draft"] == subsets[si][0]).all()
+    eng.close()
+
+
+def test_tiny_determinism(gpu, tiny):
+    """Same inputs, repeated calls: identical ids and logits (the cross-workgroup argmax and the split merge are
+    order-independent)."""
+    torch, binding = gpu["torch"], gpu["binding"]
+    act = synth.make_activations(tiny["wl"], ctx=np.array([150, 20, 77], dtype=np.int32), capacity=192)
+    eng = binding.DraftEngine(tiny["shape"], tiny["w"], [tiny["ids"]], 3, 192, 3)
+    outs = []
+    for _ in range(5):
+        o = eng.draft(3, 0, eng.to_device_bits(act["hidden_in"]), eng.to_device_i32(act["token_in"]),
+                      eng.to_device_bits(act["k_cache"]), eng.to_device_bits(act["v_cache"]),
+                      eng.to_device_i32(act["kv_len"]), want_logits=True)
+        torch.cuda.synchronize()
+        outs.append((o["draft"].cpu().numpy(), o["logits"].cpu().numpy()))
+    for d, l in outs[1:]:
+        np.testing.assert_array_equal(d, outs[0][0])
+        np.testing.assert_array_equal(l, outs[0][1])
+    eng.close()
+
+
+def test_device_detected_errors(gpu, tiny):
+    torch, binding = gpu["torch"], gpu["binding"]
+    cap = 192
+    act = synth.make_activations(tiny["wl"], ctx=np.array([100, 190], dtype=np.int32), capacity=cap)
+    eng = binding.DraftEngine(tiny["shape"], tiny["w"], [tiny["ids"]], 2, cap, 3)
+    kc, vc = eng.to_device_bits(act["k_cache"]), eng.to_device_bits(act["v_cache"])
+    o = eng.draft(3, 0, eng.to_device_bits(act["hidden_in"]), eng.to_device_i32(act["token_in"]), kc, vc,
+                  eng.to_device_i32(act["kv_len"]))
+    torch.cuda.synchronize()
+    assert eng.poll_error() == -9  # sequence 1: 190 + 3 > 192
+    assert eng.poll_error() == 0   # the error word is cleared by the poll
+    d = o["draft"].cpu().numpy()
+    assert (d[1] == -1).all() and (d[0] >= 0).all()
+    np.testing.assert_array_equal(kc.cpu().numpy().view(np.uint16)[1], act["k_cache"][1])  # cache untouched
+    tok = act["token_in"].copy()
+    tok[0] = tiny["shape"].vocab_size
+    eng.draft(1, 0, eng.to_device_bits(act["hidden_in"]), eng.to_device_i32(tok), kc, vc,
+              eng.to_device_i32(np.array([100, 100])))
+    torch.cuda.synchronize()
+    assert eng.poll_error() == -10
+    # host-detected
+    assert binding.mtp_draft_steps(eng.handle, 3, 1, 0, kc, kc, kc, vc, kc, None, kc, None, None) == -4
+    assert binding.mtp_draft_steps(eng.handle, 1, 4, 0, kc, kc, kc, vc, kc, None, kc, None, None) == -5
+    assert binding.mtp_draft_steps(eng.handle, 1, 1, 1, kc, kc, kc, vc, kc, None, kc, None, None) == -6
+    assert binding.mtp_draft_steps(eng.handle, 1, 1, 0, None, kc, kc, vc, kc, None, kc, None, None) == -1
+    assert binding.mtp_draft_steps(eng.handle, 1, 1, 0, kc.data_ptr() + 2, kc, kc, vc, kc, None, kc, None, None) == -2
+    assert binding.mtp_accept(eng.handle, 1, 1, kc, kc, 2, kc, kc, kc, kc) == -11
+    eng.close()
+    # an invalid id list is refused at init
+    bad = np.array([5, 5, 9], dtype=np.int32)
+    with pytest.raises(binding.MTPError) as e:
+        binding.DraftEngine(tiny["shape"], tiny["w"], [bad], 1, cap, 1)
+    assert e.value.status == -6
+
+
+# ------------------------------------------------------------------------------------------ accept / rollback
+@pytest.mark.parametrize("K", [1, 3, 5])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_accept_bit_exact(gpu, tiny, K, mode):
+    torch, binding, orc = gpu["torch"], gpu["binding"], gpu["orc"]
+    pats = list(itertools.product([0, 1], repeat=K))
+    B = len(pats)
+    rng = np.random.default_rng(K * 7 + mode)
+    draft = rng.integers(0, 4096, size=(B, K)).astype(np.int32)
+    target = rng.integers(0, 4096, size=(B, K + 1)).astype(np.int32)
+    for bi, pt in enumerate(pats):
+        for j in range(K):
+            target[bi, j] = draft[bi, j] if pt[j] else (draft[bi, j] + 1 + j) % 4096
+    L = rng.integers(0, 100, size=B).astype(np.int32)
+    want = orc.accept(draft, target, L, mode)
+    eng = binding.DraftEngine(tiny["shape"], tiny["w"], [], B, 192, K)
+    kv = eng.to_device_i32(L)
+    got = eng.accept(eng.to_device_i32(draft), eng.to_device_i32(target), kv, mode)
+    torch.cuda.synchronize()
+    for k in ("accept_len", "out_tokens", "pending", "kv_len"):
+        np.testing.assert_array_equal(got[k].cpu().numpy(), want[k])
+    eng.close()
+
+
+def test_draft_then_accept_rollback(gpu, tiny):
+    """Whole cycle on a ragged batch: draft, accept against a synthetic target chain, and check that the cache
+    below the new kv_len still equals what drafting left there."""
+    torch, binding, orc = gpu["torch"], gpu["binding"], gpu["orc"]
+    wl = tiny["wl"]
+    ctx = np.array([10, 64, 100, 129, 31, 5, 77, 150], dtype=np.int32)
+    act = synth.make_activations(wl, ctx=ctx, capacity=192)
+    K = 3
+    eng = binding.DraftEngine(tiny["shape"], tiny["w"], [tiny["ids"]], len(ctx), 192, K)
+    kc, vc = eng.to_device_bits(act["k_cache"]), eng.to_device_bits(act["v_cache"])
+    kv = eng.to_device_i32(act["kv_len"])
+    o = eng.draft(K, 0, eng.to_device_bits(act["hidden_in"]), eng.to_device_i32(act["token_in"]), kc, vc, kv)
+    torch.cuda.synchronize()
+    drafts = o["draft"].cpu().numpy()
+    before = kc.cpu().numpy().copy()
+    tgt = synth.make_targets(wl, drafts, accept_prob=0.7)
+    want = orc.accept(drafts, tgt, act["kv_len"], 0)
+    got = eng.accept(o["draft"], eng.to_device_i32(tgt), kv, 0)
+    torch.cuda.synchronize()
+    for k in ("accept_len", "out_tokens", "pending", "kv_len"):
+        np.testing.assert_array_equal(got[k].cpu().numpy(), want[k])
+    assert len(set(want["accept_len"].tolist())) > 1
+    np.testing.assert_array_equal(kc.cpu().numpy(), before)  # rollback moves no bytes
+    assert (want["kv_len"] - act["kv_len"] == np.minimum(want["accept_len"] + 1, K)).all()
+    eng.close()
+
+
+# ------------------------------------------------------------------------------------------ 7B-shaped head
+@pytest.fixture(scope="module")
+def big(gpu):
+    """7B-shaped weights (shared by configs 2-5), on the host for the oracle and on the device for the library."""
+    torch = gpu["torch"]
+    wl = synth.WORKLOADS["c2_7b_b1"]
+    w = synth.make_weights(wl, threads=16)
+    dev = {k: torch.from_numpy(v.view(np.int16)).to("cuda:0") for k, v in w.items()}
+    return {"w": w, "dev": dev, "shape": wl.shape}
+
+
+def test_7b_batch1_ctx2048(gpu, big):
+    wl = synth.WORKLOADS["c2_7b_b1"]
+    act = synth.make_activations(wl)
+    subsets = synth.make_subsets(wl)
+    ref, res, caches = run_both(gpu, big["shape"], big["w"], big["dev"], act, subsets, 0, wl.draft_steps)
+    gap = check_chain(ref, res, caches, act["kv_len"], wl.draft_steps)
+    print("c2 max |dlogit| =", gap)
+    ref, res, caches = run_both(gpu, big["shape"], big["w"], big["dev"], act, subsets, 0, wl.draft_steps, forced=None)
+    check_chain(ref, res, caches, act["kv_len"], wl.draft_steps, aligned=False)
+
+
+def test_7b_vocab_sweep_ctx8192(gpu, big):
+    """Full 151680-row head against nested compressed heads; the compressed logits are rows of the full ones."""
+    wl = synth.WORKLOADS["c4_7b_vocab"]
+    act = synth.make_activations(wl)
+    subsets = synth.make_subsets(wl)
+    binding = gpu["binding"]
+    eng = binding.DraftEngine(big["shape"], big["dev"], subsets, 1, act["kv_capacity"], wl.draft_steps)
+    K = 2
+    ref_full, res_full, caches = run_both(gpu, big["shape"], big["w"], big["dev"], act, subsets, -1, K, engine=eng)
+    check_chain(ref_full, res_full, caches, act["kv_len"], K)
+    for si in (0, 2):
+        ref, res, caches = run_both(gpu, big["shape"], big["w"], big["dev"], act, subsets, si, K, engine=eng)
+        check_chain(ref, res, caches, act["kv_len"], K)
+        # step 1 sees the same inputs whatever the head: compressed logits are a row gather of the full logits
+        np.testing.assert_array_equal(res["logits"][0, 0], res_full["logits"][0, 0][subsets[si]])
+    assert set(subsets[0]).issubset(set(subsets[1])) and set(subsets[1]).issubset(set(subsets[2]))
+    eng.close()
+
+
+def test_7b_batch16_ragged_with_accept(gpu, big):
+    torch, binding, orc = gpu["torch"], gpu["binding"], gpu["orc"]
+    wl = synth.WORKLOADS["c3_7b_b16"]
+    act = synth.make_activations(wl, threads=16)
+    subsets = synth.make_subsets(wl)
+    K = wl.draft_steps
+    seqs = [0, 3, 8, 9, 15]  # shortest (719), longest (3958) and three others
+    eng = binding.DraftEngine(big["shape"], big["dev"], subsets, wl.batch, act["kv_capacity"], K)
+    ref, res, caches = run_both(gpu, big["shape"], big["w"], big["dev"], act, subsets, 0, K, engine=eng, seqs=seqs)
+    check_chain(ref, res, caches, act["kv_len"][seqs], K)
+    # accept + rollback on the whole batch, per-position acceptance 0.8
+    kv = eng.to_device_i32(act["kv_len"])
+    o = eng.draft(K, 0, eng.to_device_bits(act["hidden_in"]), eng.to_device_i32(act["token_in"]),
+                  eng.to_device_bits(act["k_cache"]), eng.to_device_bits(act["v_cache"]), kv)
+    torch.cuda.synchronize()
+    drafts = o["draft"].cpu().numpy()
+    tgt = synth.make_targets(wl, drafts)
+    want = orc.accept(drafts, tgt, act["kv_len"], 0)
+    got = eng.accept(o["draft"], eng.to_device_i32(tgt), kv, 0)
+    torch.cuda.synchronize()
+    for k in ("accept_len", "out_tokens", "pending", "kv_len"):
+        np.testing.assert_array_equal(got[k].cpu().numpy(), want[k])
+    eng.close()
+
+
+def test_7b_batch64_long_context_sampled(gpu, big):
+    """Throughput regime (B = 64, contexts in [8192, 32768], K = 5): the library runs the whole batch, the oracle
+    the shortest, the longest and one more sequence."""
+    wl = synth.WORKLOADS["c5_7b_b64"]
+    act = synth.make_activations(wl, threads=16)
+    subsets = synth.make_subsets(wl)
+    K = wl.draft_steps
+    L = act["kv_len"]
+    seqs = sorted({int(np.argmin(L)), int(np.argmax(L)), 7})
+    ref, res, caches = run_both(gpu, big["shape"], big["w"], big["dev"], act, subsets, 0, K, seqs=seqs,
+                                max_batch=wl.batch)
+    check_chain(ref, res, caches, L[seqs], K)
