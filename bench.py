@@ -1,0 +1,174 @@
+#!/usr/bin/env python3
+"""Benchmark of the FastMTP draft path on one MI355X.
+
+One "step" = one pass of the whole hot path over one batch: K recursive draft steps of the shared MTP head with the
+compressed output head (mtp_draft_steps), then acceptance + rollback against a synthetic target chain (mtp_accept).
+Inputs are seeded and synthetic (7B-shaped head, bf16 ~N(0,0.02) weights), resident in HBM before timing starts.
+
+Prints ONE JSON line: draft tokens/s (value), ms per step, and the objects `roofline` (dominant kernel against the
+8 TB/s HBM peak), `full_vocab` (same path with the uncompressed head) and `cpu_baseline` (the CPU oracle, timed on
+this machine's host cores on the same workload).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_bytes_per_mtp_step(shape, n_rows: int, ctx, k_index: int, with_ids: bool) -> float:
+    """HBM bytes one draft step must move: every weight of the head once, n_rows rows of the output head (+ the id
+    list), and the K/V entries of every sequence up to and including the new one (k_index = 1-based step)."""
+    d, F = shape.d_model, shape.d_ffn
+    body = 2.0 * (2 * d * d + (shape.q_dim + 2 * shape.kv_dim) * d + d * shape.q_dim + 3 * F * d)
+    head = 2.0 * n_rows * d + (4.0 * n_rows if with_ids else 0.0)
+    kv = sum((int(L) + k_index) * 2 * shape.kv_dim * 2.0 for L in ctx)
+    return body + head + kv
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--workload", default="c2_7b_b1")
+    ap.add_argument("--subset", type=int, default=0, help="index into the workload's subset list; -1 = full vocabulary")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-full-vocab", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding are part of it); "
+              "run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2509_18362_amd import binding, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    wl = synth.WORKLOADS[args.workload]
+    shape, K, B = wl.shape, wl.draft_steps, wl.batch
+    t0 = time.time()
+    w = synth.make_weights(wl if wl.shape is synth.TINY else synth.WORKLOADS["c2_7b_b1"], threads=16)
+    act = synth.make_activations(wl, threads=16)
+    subsets = synth.make_subsets(wl)
+    gen_s = time.time() - t0
+    cap = act["kv_capacity"]
+    eng = binding.DraftEngine(shape, w, subsets, B, cap, K, device="cuda:0")
+    hidden = eng.to_device_bits(act["hidden_in"])
+    token = eng.to_device_i32(act["token_in"])
+    kc, vc = eng.to_device_bits(act["k_cache"]), eng.to_device_bits(act["v_cache"])
+    kv0 = eng.to_device_i32(act["kv_len"])
+    kv = kv0.clone()
+    draft = torch.empty((B, K), dtype=torch.int32, device="cuda:0")
+    acc = torch.empty(B, dtype=torch.int32, device="cuda:0")
+    out_tok = torch.empty((B, K + 1), dtype=torch.int32, device="cuda:0")
+    pend = torch.empty(B, dtype=torch.int32, device="cuda:0")
+    stream = 0  # the null stream, which is also torch's current stream here
+
+    def one_step(subset_index, target):
+        st = binding.mtp_draft_steps(eng.handle, B, K, subset_index, hidden, token, kc, vc, kv, None, draft, None,
+                                     None, stream)
+        assert st == 0, binding.mtp_status_string(st)
+        st = binding.mtp_accept(eng.handle, B, K, draft, target, 0, kv, acc, out_tok, pend, stream)
+        assert st == 0, binding.mtp_status_string(st)
+        kv.copy_(kv0)  # replay the same cycle next time (4*B bytes, device to device)
+
+    def timed(subset_index, steps, warmup):
+        # target chain built from this configuration's own drafts (stand-in for the target model's verification)
+        dummy = torch.zeros((B, K + 1), dtype=torch.int32, device="cuda:0")
+        one_step(subset_index, dummy)
+        torch.cuda.synchronize()
+        assert eng.poll_error() == 0
+        target = eng.to_device_i32(synth.make_targets(wl, draft.cpu().numpy()))
+        for _ in range(warmup):
+            one_step(subset_index, target)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(steps):
+            one_step(subset_index, target)
+        torch.cuda.synchronize()
+        el = time.perf_counter() - t
+        return el, float(acc.float().mean().item())
+
+    elapsed, mean_accept = timed(args.subset, args.steps, args.warmup)
+    n_rows = eng.subset_size(args.subset)
+    chain_bytes = sum(algorithmic_bytes_per_mtp_step(shape, n_rows, act["kv_len"], k, args.subset >= 0)
+                      for k in range(1, K + 1))
+    tok_s = B * K * args.steps / elapsed
+    us_per_mtp_step = elapsed / (args.steps * K) * 1e6
+    path_gbs = chain_bytes * args.steps / elapsed / 1e9
+
+    # dominant kernel: the compressed-head launch (final norm + gathered rows + argmax), timed with HIP events on the
+    # launch stream over a region of the same length
+    binding.mtp_set_timing(eng.handle, binding.timing_phase("lmhead"))
+    dummy = eng.to_device_i32(synth.make_targets(wl, draft.cpu().numpy()))
+    durs = []
+    for i in range(args.steps):
+        one_step(args.subset, dummy)
+        if i % 10 == 9 or i == args.steps - 1:  # reading the events waits for the stream: do it sparsely
+            durs.append(binding.mtp_last_draft_ms(eng.handle))
+    torch.cuda.synchronize()
+    binding.mtp_set_timing(eng.handle, binding.TIMING_OFF)
+    k_ms = float(np.median(durs))
+    head_bytes = 2.0 * n_rows * shape.d_model + (4.0 * n_rows if args.subset >= 0 else 0.0)
+    roofline = {"bound": "hbm", "kernel": "k_lmhead", "achieved": head_bytes / (k_ms * 1e-3) / 1e9,
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": head_bytes / (k_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                "traffic": None, "bytes_per_launch": head_bytes, "avg_launch_us": k_ms * 1e3,
+                "whole_path_achieved": path_gbs, "whole_path_frac": path_gbs / HBM_PEAK_GBS}
+
+    full = None
+    if not args.no_full_vocab and args.subset >= 0:
+        fs = max(10, args.steps // 4)
+        el_f, acc_f = timed(-1, fs, max(3, args.warmup // 4))
+        full = {"value": B * K * fs / el_f, "unit": "draft tokens/s", "us_per_mtp_step": el_f / (fs * K) * 1e6,
+                "rows": shape.vocab_size, "compressed_speedup": (el_f / fs) / (elapsed / args.steps),
+                "roofline_speedup": sum(algorithmic_bytes_per_mtp_step(shape, shape.vocab_size, act["kv_len"], k, False)
+                                        for k in range(1, K + 1)) / chain_bytes}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle.oracle import Oracle
+        orc = Oracle(shape, w, cap, "f32")
+        ids = None if args.subset < 0 else subsets[args.subset]
+        nseq = min(B, 4)  # a bounded sample: at most four sequences of the batch
+        reps, t = 0, time.perf_counter()
+        while True:
+            orc.chain(K, act["hidden_in"][:nseq], act["token_in"][:nseq], act["k_cache"][:nseq].copy(),
+                      act["v_cache"][:nseq].copy(), act["kv_len"][:nseq], ids, want_logits=False, want_hidden=False)
+            reps += 1
+            el_c = time.perf_counter() - t
+            if el_c >= args.cpu_seconds and reps >= 2 or el_c >= 3 * args.cpu_seconds:
+                break
+        cpu = {"value": nseq * K * reps / el_c, "unit": "draft tokens/s", "cores": orc.threads, "kind": "oracle",
+               "sample": f"{reps} repetitions of the oracle's K={K} chain on {nseq} of {B} sequences of {wl.name}",
+               "us_per_mtp_step": el_c / (reps * K) * 1e6 / nseq * B}
+
+    line = {
+        "metric": "draft tokens/sec (and us per MTP step, HBM GB/s vs peak), compressed vs full vocab",
+        "value": tok_s, "unit": "draft tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16 weights and KV, f32 accumulate", "data": "synthetic",
+        "config": {"workload": wl.name, "batch": B, "draft_steps": K, "context": [int(act["kv_len"].min()),
+                                                                                   int(act["kv_len"].max())],
+                   "head_rows": n_rows, "vocab": shape.vocab_size, "d_model": shape.d_model},
+        "us_per_mtp_step": us_per_mtp_step, "mean_accept_len": mean_accept,
+        "algorithmic_bytes_per_step": chain_bytes, "roofline": roofline, "full_vocab": full, "cpu_baseline": cpu,
+        "input_generation_s": gen_s,
+    }
+    eng.close()
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -40,7 +40,8 @@ typedef enum {
     MTP_ERR_HIP = -8,          /* a HIP runtime call failed                                   */
     MTP_ERR_KV_OVERFLOW = -9,  /* device saw kv_len[b] + K > kv_capacity (from mtp_poll_error)*/
     MTP_ERR_TOKEN_RANGE = -10, /* device saw an input token id outside [0, vocab_size)        */
-    MTP_ERR_MODE = -11         /* unknown rollback_mode                                       */
+    MTP_ERR_MODE = -11,        /* unknown rollback_mode / launch mode / timing mode           */
+    MTP_ERR_TIMEOUT = -12      /* device: a grid barrier of the single-launch path timed out   */
 } mtp_status;
 
 /* Shape of the head (Sec. 3.1 "Model Configuration" for the 7B case) and limits of this handle. Host POD. */
@@ -157,11 +158,33 @@ int32_t mtp_accept(mtp_handle *h, int32_t B, int32_t K, const int32_t *draft, co
  * MTP_OK, MTP_ERR_KV_OVERFLOW or MTP_ERR_TOKEN_RANGE (or MTP_ERR_HIP). */
 int32_t mtp_poll_error(mtp_handle *h, void *hip_stream);
 
-/* Duration in milliseconds of the kernels that the most recent mtp_draft_steps call enqueued, measured with
- * HIP events recorded on that call's stream (the events are recorded only after mtp_set_timing(h, 1)).
- * Waits for the stop event.  Returns a negative value if timing is off or nothing was recorded. */
+/*
+ * Timing of the most recent mtp_draft_steps call with HIP events recorded on that call's stream.
+ *   mtp_set_timing(h, 0)      no events (default)
+ *   mtp_set_timing(h, 1)      one event pair around everything the call enqueues
+ *   mtp_set_timing(h, 2 + f)  one pair around each launch of phase f (0 proj, 1 qkv, 2 attn, 3 oproj, 4 gateup,
+ *                             5 down, 6 lmhead); such calls use one launch per phase whatever the launch mode
+ * mtp_last_draft_ms waits for the last event and returns milliseconds (mode 1: the call; mode 2 + f: the mean over
+ * the call's K launches of phase f), or a negative value if nothing was recorded.
+ */
+int32_t mtp_set_timing(mtp_handle *h, int32_t mode);
 float mtp_last_draft_ms(mtp_handle *h);
-int32_t mtp_set_timing(mtp_handle *h, int32_t enable);
+
+/*
+ * How mtp_draft_steps enqueues its work.
+ *   0 (default) one launch per phase (7 or 8 per step) plus one to publish the last draft id.
+ *   1           one cooperative launch runs all phases of all K steps; phases are separated by grid-wide
+ *               barriers inside the kernel.  A barrier that is not passed within ~2 s sets MTP_ERR_TIMEOUT.
+ * Results are identical in both modes.
+ */
+int32_t mtp_set_launch_mode(mtp_handle *h, int32_t mode);
+
+/*
+ * Diagnostics for the single-launch mode: device_buffer (device, int64 [max_draft_steps][16], or NULL to stop)
+ * receives workgroup 0's 100 MHz wall-clock stamps: entry 2f = start of phase f, 2f+1 = its end (= start of the
+ * barrier after it), entry 14 = end of the step's last barrier.
+ */
+int32_t mtp_set_phase_trace(mtp_handle *h, void *device_buffer);
 
 /* Frees the host object.  Device memory stays with the caller. */
 void mtp_draft_destroy(mtp_handle *h);

@@ -21,9 +21,11 @@ _lib = C.CDLL(LIB_PATH)
 MTP_OK = 0
 STATUS = {0: "MTP_OK", -1: "MTP_ERR_NULL", -2: "MTP_ERR_ALIGN", -3: "MTP_ERR_CONFIG", -4: "MTP_ERR_BATCH",
           -5: "MTP_ERR_STEPS", -6: "MTP_ERR_SUBSET", -7: "MTP_ERR_WORKSPACE", -8: "MTP_ERR_HIP",
-          -9: "MTP_ERR_KV_OVERFLOW", -10: "MTP_ERR_TOKEN_RANGE", -11: "MTP_ERR_MODE"}
+          -9: "MTP_ERR_KV_OVERFLOW", -10: "MTP_ERR_TOKEN_RANGE", -11: "MTP_ERR_MODE", -12: "MTP_ERR_TIMEOUT"}
 EXPORTS = ["mtp_status_string", "mtp_workspace_bytes", "mtp_draft_init", "mtp_draft_steps", "mtp_accept",
-           "mtp_poll_error", "mtp_set_timing", "mtp_last_draft_ms", "mtp_draft_destroy"]
+           "mtp_poll_error", "mtp_set_timing", "mtp_last_draft_ms", "mtp_set_launch_mode", "mtp_set_phase_trace",
+           "mtp_draft_destroy"]
+LAUNCH_PER_PHASE, LAUNCH_SINGLE = 0, 1
 # mtp_set_timing modes
 TIMING_OFF, TIMING_CALL = 0, 1
 PHASES = ["proj", "qkv", "attn", "oproj", "gateup", "down", "lmhead"]
@@ -65,6 +67,10 @@ _lib.mtp_set_timing.restype = C.c_int32
 _lib.mtp_set_timing.argtypes = [C.c_void_p, C.c_int32]
 _lib.mtp_last_draft_ms.restype = C.c_float
 _lib.mtp_last_draft_ms.argtypes = [C.c_void_p]
+_lib.mtp_set_launch_mode.restype = C.c_int32
+_lib.mtp_set_launch_mode.argtypes = [C.c_void_p, C.c_int32]
+_lib.mtp_set_phase_trace.restype = C.c_int32
+_lib.mtp_set_phase_trace.argtypes = [C.c_void_p, C.c_void_p]
 _lib.mtp_draft_destroy.restype = None
 _lib.mtp_draft_destroy.argtypes = [C.c_void_p]
 
@@ -127,6 +133,14 @@ def mtp_set_timing(handle, mode: int) -> int:
 
 def mtp_last_draft_ms(handle) -> float:
     return float(_lib.mtp_last_draft_ms(handle))
+
+
+def mtp_set_launch_mode(handle, mode: int) -> int:
+    return int(_lib.mtp_set_launch_mode(handle, mode))
+
+
+def mtp_set_phase_trace(handle, device_buffer) -> int:
+    return int(_lib.mtp_set_phase_trace(handle, _addr(device_buffer)))
 
 
 def mtp_draft_destroy(handle) -> None:

@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cmath>
 #include <cstdio>
 #include <cstring>
 #include <new>
@@ -16,7 +17,7 @@ using namespace mtp;
 
 namespace {
 
-enum Phase : int { PH_PROJ = 0, PH_QKV, PH_ATTN, PH_OPROJ, PH_GATEUP, PH_DOWN, PH_LMHEAD, PH_COUNT };
+enum Phase : int { PH_PROJ = 0, PH_QKV, PH_ATTN, PH_OPROJ, PH_GATEUP, PH_DOWN, PH_LMHEAD, PH_COUNT, PH_MERGE };
 
 // ---- kernels: one launch per phase ------------------------------------------------------------------
 __global__ __launch_bounds__(kBlock) void k_proj(DraftParams p, int step) {
@@ -31,6 +32,11 @@ template <int G, int HD>
 __global__ __launch_bounds__(kBlock) void k_attn(DraftParams p, int step) {
     extern __shared__ __align__(16) char smem[];
     phase_attn<G, HD>(p, step, blockIdx.x, gridDim.x, smem);
+}
+template <int HD>
+__global__ __launch_bounds__(kBlock) void k_attn_merge(DraftParams p, int step) {
+    extern __shared__ __align__(16) char smem[];
+    phase_attn_merge<HD>(p, step, blockIdx.x, gridDim.x, smem);
 }
 __global__ __launch_bounds__(kBlock) void k_oproj(DraftParams p, int step) {
     extern __shared__ __align__(16) char smem[];
@@ -49,6 +55,14 @@ __global__ __launch_bounds__(kBlock) void k_lmhead(DraftParams p, int step) {
     phase_lmhead(p, step, blockIdx.x, gridDim.x, smem);
 }
 __global__ void k_finalize(DraftParams p) { phase_finalize(p, blockIdx.x); }
+template <int G, int HD>
+__global__ __launch_bounds__(kBlock) void k_fused(DraftParams) {
+    extern __shared__ __align__(16) char smem[];
+    // the phases are called out of line and take the parameters by reference: point them at the kernel-argument
+    // segment (the struct is the only argument, at offset 0) instead of a per-lane stack copy
+    const DraftParams *p = (const DraftParams *)__builtin_amdgcn_kernarg_segment_ptr();
+    fused_steps<G, HD>(*p, smem);
+}
 
 // Sequential acceptance up to the first mismatch and the draft-cache length after it (Sec. 2.3 "Verification phase").
 __global__ void k_accept(int B, int K, const int *draft, const int *target, int mode, int *kv_len, int *accept_len,
@@ -90,6 +104,25 @@ phase_kernel_t attn_kernel(int G, int HD) {
     }
     return nullptr;
 }
+typedef void (*fused_kernel_t)(DraftParams);
+fused_kernel_t fused_kernel(int G, int HD) {
+    if (HD == 128) {
+        switch (G) {
+        case 1: return k_fused<1, 128>;
+        case 2: return k_fused<2, 128>;
+        case 4: return k_fused<4, 128>;
+        case 8: return k_fused<8, 128>;
+        }
+    } else if (HD == 64) {
+        switch (G) {
+        case 1: return k_fused<1, 64>;
+        case 2: return k_fused<2, 64>;
+        case 4: return k_fused<4, 64>;
+        case 8: return k_fused<8, 64>;
+        }
+    }
+    return nullptr;
+}
 size_t attn_lds_bytes(int G, int HD) {
     int tpi = kWave / (HD / 8), ns = kWaves * tpi;
     size_t fl = (size_t)G * HD + HD + 2 * HD + (size_t)ns * G * HD + (size_t)ns * G * 2;
@@ -97,8 +130,8 @@ size_t attn_lds_bytes(int G, int HD) {
 }
 
 // ---- plan: how a call of B sequences is cut up ----------------------------------------------------------
-constexpr int kTargetAttnItems = 2048; // (sequence, KV head, split) items aimed for
-constexpr int kMinSplitTokens = 64;
+constexpr int kTargetAttnItems = 1024; // (sequence, KV head, split) items aimed for
+constexpr int kMinSplitTokens = 128;
 constexpr size_t kLdsSmallBatch = 72 * 1024;  // two workgroups per CU
 constexpr size_t kLdsLargeBatch = 150 * 1024; // one workgroup per CU, more sequences per weight pass
 
@@ -130,6 +163,7 @@ bool config_ok(const mtp_config *c) {
     if (c->vocab_size < 1) return false;
     if (c->max_batch < 1 || c->max_batch > kBlock) return false;
     if (c->max_draft_steps < 1 || c->kv_capacity < c->max_draft_steps) return false;
+    if (c->kv_capacity > 2048 * kMinSplitTokens) return false; // the merge keeps one weight per split per wave in LDS
     if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f)) return false;
     if ((long long)c->n_q_heads * c->head_dim > 65536) return false;
     return true;
@@ -139,7 +173,7 @@ constexpr size_t kAlign = 256;
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct WsLayout {
-    size_t x, qkv, attn, x1, m, x2, hhat, keys, err, attn_cnt, attn_part, total;
+    size_t x, qkv, attn, o, m, dn, hhat, keys, err, bar, rope_inv, attn_part, total;
 };
 WsLayout ws_layout(const mtp_config &c) {
     WsLayout l{};
@@ -154,13 +188,14 @@ WsLayout ws_layout(const mtp_config &c) {
     l.x = take(mb * d * 4);
     l.qkv = take(mb * (qd + 2 * kvd) * 4);
     l.attn = take(mb * qd * 4);
-    l.x1 = take(mb * d * 4);
+    l.o = take(mb * d * 4);
     l.m = take(mb * (size_t)c.d_ffn * 4);
-    l.x2 = take(mb * d * 4);
+    l.dn = take(mb * d * 4);
     l.hhat = take(mb * d * 4);
     l.keys = take((size_t)c.max_draft_steps * mb * 8);
     l.err = take(4);
-    l.attn_cnt = take(mb * c.n_kv_heads * 4);
+    l.bar = take(8);
+    l.rope_inv = take((size_t)c.head_dim / 2 * 8);
     l.attn_part = take(attn_part_floats(c) * 4);
     l.total = off;
     return l;
@@ -179,7 +214,11 @@ struct mtp_handle {
     WsLayout lay;
     int num_cus;
     size_t lds_limit;
-    phase_kernel_t attn_fn;
+    phase_kernel_t attn_fn, merge_fn;
+    fused_kernel_t fused_fn;
+    int mode;                    // 0: one launch per phase, 1: single cooperative launch for the whole call
+    unsigned long long bar_count; // host mirror of the device barrier counter
+    long long *trace;             // optional device buffer for phase time stamps
     int timing;         // 0 off, 1 whole call, 2 + phase: every launch of one phase
     hipEvent_t ev[2];   // whole call
     std::vector<hipEvent_t> pev; // per-step pairs for one phase
@@ -202,7 +241,8 @@ const char *mtp_status_string(int32_t s) {
     case MTP_ERR_HIP: return "HIP runtime call failed";
     case MTP_ERR_KV_OVERFLOW: return "kv_len + K exceeds kv_capacity for some sequence";
     case MTP_ERR_TOKEN_RANGE: return "token id outside the vocabulary";
-    case MTP_ERR_MODE: return "unknown rollback mode";
+    case MTP_ERR_MODE: return "unknown mode";
+    case MTP_ERR_TIMEOUT: return "a workgroup waited too long at a grid barrier; results of that call are invalid";
     default: return "unknown status";
     }
 }
@@ -272,13 +312,27 @@ int32_t mtp_draft_init(mtp_handle **out, const mtp_config *cfg, const mtp_weight
     h->num_cus = cus;
     h->lds_limit = (size_t)lds;
     h->attn_fn = attn_kernel(cfg->n_q_heads / cfg->n_kv_heads, cfg->head_dim);
-    ok = ok && h->attn_fn != nullptr;
+    h->merge_fn = cfg->head_dim == 128 ? k_attn_merge<128> : k_attn_merge<64>;
+    h->fused_fn = fused_kernel(cfg->n_q_heads / cfg->n_kv_heads, cfg->head_dim);
+    h->mode = 0;
+    h->bar_count = 0;
+    h->trace = nullptr;
+    ok = ok && h->attn_fn != nullptr && h->fused_fn != nullptr;
     // allow the large-LDS launches
     const void *fns[] = {(const void *)k_proj, (const void *)k_qkv, (const void *)k_oproj, (const void *)k_gateup,
-                         (const void *)k_down, (const void *)k_lmhead, (const void *)h->attn_fn};
+                         (const void *)k_down, (const void *)k_lmhead, (const void *)h->attn_fn, (const void *)h->merge_fn,
+                         (const void *)h->fused_fn};
     for (const void *f : fns)
         ok = ok && hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)h->lds_limit) == hipSuccess;
-    ok = ok && hipMemset(workspace, 0, lay.total) == hipSuccess && hipDeviceSynchronize() == hipSuccess;
+    ok = ok && hipMemset(workspace, 0, lay.total) == hipSuccess;
+    {
+        std::vector<double> inv((size_t)cfg->head_dim / 2);
+        for (size_t j = 0; j < inv.size(); ++j)
+            inv[j] = std::pow((double)cfg->rope_theta, -2.0 * (double)j / (double)cfg->head_dim);
+        ok = ok && hipMemcpy(static_cast<char *>(workspace) + lay.rope_inv, inv.data(), inv.size() * 8,
+                             hipMemcpyHostToDevice) == hipSuccess;
+    }
+    ok = ok && hipDeviceSynchronize() == hipSuccess;
     if (!ok) {
         (void)hipGetLastError();
         delete h;
@@ -354,14 +408,18 @@ int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_inde
     p.x = reinterpret_cast<float *>(ws + l.x);
     p.qkv = reinterpret_cast<float *>(ws + l.qkv);
     p.attn = reinterpret_cast<float *>(ws + l.attn);
-    p.x1 = reinterpret_cast<float *>(ws + l.x1);
+    p.o = reinterpret_cast<float *>(ws + l.o);
     p.m = reinterpret_cast<float *>(ws + l.m);
-    p.x2 = reinterpret_cast<float *>(ws + l.x2);
+    p.dn = reinterpret_cast<float *>(ws + l.dn);
     p.hhat = reinterpret_cast<float *>(ws + l.hhat);
     p.keys = reinterpret_cast<unsigned long long *>(ws + l.keys);
     p.err = reinterpret_cast<int *>(ws + l.err);
-    p.attn_cnt = reinterpret_cast<int *>(ws + l.attn_cnt);
+    p.rope_inv = reinterpret_cast<const double *>(ws + l.rope_inv);
     p.attn_part = reinterpret_cast<float *>(ws + l.attn_part);
+    p.bar = reinterpret_cast<unsigned long long *>(ws + l.bar);
+    p.bar_base = h->bar_count;
+    p.bar_timeout = 200000000ll; // 2 s of the 100 MHz wall clock
+    p.trace = h->trace;
     p.max_batch = c.max_batch;
     p.split_tokens = split_tokens_for(c, B);
     p.max_splits = max_splits_for(c, B);
@@ -379,16 +437,40 @@ int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_inde
     p.nb_down = fit(p.F, 1);
     const size_t lds_proj = gemv_lds_bytes(2 * p.d, p.nb_proj, 1), lds_d1 = gemv_lds_bytes(p.d, p.nb_d, 1),
                  lds_d2 = gemv_lds_bytes(p.d, p.nb_d, 2), lds_q = gemv_lds_bytes(p.qd, p.nb_q, 1),
-                 lds_down = gemv_lds_bytes(p.F, p.nb_down, 1), lds_attn = attn_lds_bytes(p.Hq / p.Hkv, p.hd);
+                 lds_down = gemv_lds_bytes(p.F, p.nb_down, 1),
+                 lds_attn = std::max(attn_lds_bytes(p.Hq / p.Hkv, p.hd), (size_t)kWaves * p.max_splits * 4 + 64),
+                 lds_merge = (size_t)kWaves * p.max_splits * 4 + 64;
     const size_t lds_max = std::max({lds_proj, lds_d2, lds_q, lds_down, lds_attn});
     if (lds_max > h->lds_limit) return MTP_ERR_CONFIG;
 
     const int grid = h->num_cus * (B <= 2 ? 2 : 1);
     const int attn_items = B * p.Hkv * p.max_splits;
     const int attn_grid = std::max(1, std::min(attn_items, h->num_cus * 2));
+    const int merge_grid = std::max(1, std::min((B * p.Hq + kWaves - 1) / kWaves, h->num_cus));
 
     const int tphase = h->timing >= 2 ? h->timing - 2 : -1;
     h->pev_used = 0;
+    if (h->mode == 1 && tphase < 0) {
+        // single launch: every workgroup must be resident at once, which the cooperative launch checks
+        int per_cu = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)h->fused_fn, kBlock, lds_max) !=
+                hipSuccess || per_cu < 1)
+            return MTP_ERR_HIP;
+        const int fgrid = h->num_cus * std::min(per_cu, B <= 2 ? 2 : 1);
+        void *args[] = {(void *)&p};
+        if (h->timing == 1) (void)hipEventRecord(h->ev[0], st);
+        if (hipLaunchCooperativeKernel((const void *)h->fused_fn, dim3(fgrid), dim3(kBlock), args,
+                                       (unsigned)lds_max, st) != hipSuccess) {
+            (void)hipGetLastError();
+            return MTP_ERR_HIP;
+        }
+        h->bar_count += (unsigned long long)fgrid * (kBarriersPerStep + (p.max_splits > 1 ? 1 : 0)) * K;
+        if (h->timing == 1) {
+            (void)hipEventRecord(h->ev[1], st);
+            h->ev_recorded = true;
+        }
+        return MTP_OK;
+    }
     auto launch = [&](int phase, phase_kernel_t fn, int g, size_t lds, int step) {
         if (phase == tphase) (void)hipEventRecord(h->pev[2 * (size_t)step], st);
         hipLaunchKernelGGL(fn, dim3(g), dim3(kBlock), lds, st, p, step);
@@ -402,6 +484,7 @@ int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_inde
         launch(PH_PROJ, k_proj, grid, lds_proj, step);
         launch(PH_QKV, k_qkv, grid, lds_d1, step);
         launch(PH_ATTN, h->attn_fn, attn_grid, lds_attn, step);
+        if (p.max_splits > 1) launch(PH_MERGE, h->merge_fn, merge_grid, lds_merge, step);
         launch(PH_OPROJ, k_oproj, grid, lds_q, step);
         launch(PH_GATEUP, k_gateup, grid, lds_d2, step);
         launch(PH_DOWN, k_down, grid, lds_down, step);
@@ -442,8 +525,13 @@ int32_t mtp_poll_error(mtp_handle *h, void *hip_stream) {
     if (hipStreamSynchronize(st) != hipSuccess) return MTP_ERR_HIP;
     if (word != 0) {
         if (hipMemsetAsync(dev, 0, 4, st) != hipSuccess) return MTP_ERR_HIP;
+        if (word & kErrBarrierTimeout) { // the barrier counter is out of step with the host's mirror: restart both
+            if (hipMemsetAsync(h->ws + h->lay.bar, 0, 8, st) != hipSuccess) return MTP_ERR_HIP;
+            h->bar_count = 0;
+        }
         if (hipStreamSynchronize(st) != hipSuccess) return MTP_ERR_HIP;
     }
+    if (word & kErrBarrierTimeout) return MTP_ERR_TIMEOUT;
     if (word & kErrKvOverflow) return MTP_ERR_KV_OVERFLOW;
     if (word & kErrTokenRange) return MTP_ERR_TOKEN_RANGE;
     return MTP_OK;
@@ -455,6 +543,20 @@ int32_t mtp_set_timing(mtp_handle *h, int32_t mode) {
     h->timing = mode;
     h->ev_recorded = false;
     h->pev_used = 0;
+    return MTP_OK;
+}
+
+int32_t mtp_set_launch_mode(mtp_handle *h, int32_t mode) {
+    if (!h) return MTP_ERR_NULL;
+    if (mode != 0 && mode != 1) return MTP_ERR_MODE;
+    h->mode = mode;
+    return MTP_OK;
+}
+
+int32_t mtp_set_phase_trace(mtp_handle *h, void *device_buffer) {
+    if (!h) return MTP_ERR_NULL;
+    if (!aligned16(device_buffer)) return MTP_ERR_ALIGN;
+    h->trace = static_cast<long long *>(device_buffer);
     return MTP_OK;
 }
 

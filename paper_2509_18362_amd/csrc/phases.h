@@ -26,17 +26,21 @@ struct DraftParams {
     int *draft_out;
     float *logits_out, *hidden_out;
     // workspace
-    float *x, *qkv, *attn, *x1, *m, *x2, *hhat, *attn_part;
+    float *x, *qkv, *attn, *o, *m, *dn, *hhat, *attn_part; // o = w_o attn, dn = w_down m (residuals added by consumers)
     unsigned long long *keys; // [max_draft_steps][max_batch] packed (logit, index) maxima
     int *err;                 // sticky error word
-    int *attn_cnt;            // [max_batch][Hkv] arrival counters of the split-KV merge
+    const double *rope_inv;   // [hd/2] rotary pair frequencies theta^(-2j/hd), computed on the host in double
+    unsigned long long *bar;  // grid-barrier arrival counter of the single-launch path (only ever grows)
+    unsigned long long bar_base; // its value when this launch starts
+    long long bar_timeout;    // wall-clock ticks a workgroup may wait at one barrier before giving up
+    long long *trace;         // optional [K][16] wall-clock stamps (100 MHz) of workgroup 0 in the single-launch path
     int max_batch;
     // launch plan
     int split_tokens, max_splits; // attention: tokens per split, splits per (sequence, KV head)
     int nb_proj, nb_d, nb_q, nb_down; // sequences staged in LDS per pass, by reduction length (2d, d, Hq*hd, F)
 };
 
-enum : int { kErrKvOverflow = 1, kErrTokenRange = 2 };
+enum : int { kErrKvOverflow = 1, kErrTokenRange = 2, kErrBarrierTimeout = 4 };
 
 // ---------------------------------------------------------------------------------------------------
 // per-sequence state helpers
@@ -72,9 +76,12 @@ constexpr int kMaxNormIter = 4; // d <= 4 * 4 * kBlock = 8192
 
 // RMSNorm(u; g) of one vector of length d (Sec. 2.1: DeepSeek-V3 MTP module uses RMSNorm on both inputs), written to
 // hi/lo (bf16) and optionally to out_f32.  SRC_BF16: u is bf16 bits, else float.  Contains barriers.
+// add1/add2 (float, optional) are added to the source element-wise first, in that order: the residual stream is
+// kept as its summands and put together where it is consumed.
 template <bool SRC_BF16>
 __device__ void stage_rmsnorm(const void *src, const uint16_t *gain, int d, float eps, uint16_t *hi, uint16_t *lo,
-                              float *red, float *out_f32, float *out2_f32 = nullptr) {
+                              float *red, float *out_f32, float *out2_f32 = nullptr, const float *add1 = nullptr,
+                              const float *add2 = nullptr) {
     float v[kMaxNormIter][4];
     float ss = 0.f;
 #pragma unroll
@@ -93,6 +100,20 @@ __device__ void stage_rmsnorm(const void *src, const uint16_t *gain, int d, floa
                 v[it][1] = raw.y;
                 v[it][2] = raw.z;
                 v[it][3] = raw.w;
+            }
+            if (add1) {
+                f32x4 a = *reinterpret_cast<const f32x4 *>(add1 + e);
+                v[it][0] += a.x;
+                v[it][1] += a.y;
+                v[it][2] += a.z;
+                v[it][3] += a.w;
+            }
+            if (add2) {
+                f32x4 a = *reinterpret_cast<const f32x4 *>(add2 + e);
+                v[it][0] += a.x;
+                v[it][1] += a.y;
+                v[it][2] += a.z;
+                v[it][3] += a.w;
             }
 #pragma unroll
             for (int q = 0; q < 4; ++q) ss += v[it][q] * v[it][q];
@@ -148,25 +169,41 @@ __device__ void stage_plain(const float *src, int K, int kpad, uint16_t *hi, uin
 // ---------------------------------------------------------------------------------------------------
 // weight-streaming core
 // ---------------------------------------------------------------------------------------------------
+// Barrier that orders LDS traffic only.  __syncthreads() also waits for every outstanding global load, which
+// would drain the weight prefetch at each tile boundary.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // For rows [r0, r1) of NMAT matrices that share the input: out[mat][i][row] = sum_k W_mat[row][k] * act[i][k],
 // i < nb sequences.  The rows are cut into 16-row tiles; the 8 waves split the reduction range of each tile and
 // their partial sums meet in LDS.  Weight loads run one chunk (U MFMA k-steps) ahead of the MFMAs, across tile
-// boundaries, so the HBM stream never drains inside a phase.
-//   rowptr(mat, row) -> const uint16_t* : start of a weight row (K bf16, 16-byte aligned)
+// boundaries, and the first chunk is requested before the activations are staged, so the HBM stream starts with
+// the phase and never drains inside it.  The inner loop is branch-free: out-of-range rows and k-steps re-read a
+// valid address and meet a zero activation operand instead of being predicated off.
+//   rowptr(mat, row) -> const uint16_t* : start of a weight row (K bf16, 16-byte aligned, finite values)
+//   stage()                             : fills act_hi/act_lo (may use barriers); called once, after the first loads
 //   epi(i, row, sums[NMAT])             : called by one thread per (sequence, row)
 // LDS: act_hi/act_lo [nb][kpad] bf16 (kpad = K rounded up to 32, zero padded); partial [2][kWaves][NMAT][nbmax][16].
-template <int NMAT, int U, class RowPtr, class Epi>
+template <int NMAT, int U, class RowPtr, class Stage, class Epi>
 __device__ void gemv_rows(RowPtr rowptr, int K, int r0, int r1, int nb, int nbmax, const uint16_t *act_hi,
-                          const uint16_t *act_lo, int kpad, float *partial, Epi &epi) {
+                          const uint16_t *act_lo, int kpad, float *partial, Stage stage, Epi &epi) {
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     const int j = lane & 15, g = lane >> 4;
     const int nks = (K + 31) / 32;
     const int per = (nks + kWaves - 1) / kWaves;
-    const int ks0 = min(wave * per, nks), ks1 = min(ks0 + per, nks);
+    const int ks0 = min(wave * per, nks), ks1 = min(ks0 + per, nks); // ks1 >= 1
     const int nch = (per + U - 1) / U;
     const int ntiles = (r1 - r0 + 15) / 16;
-    if (ntiles <= 0) return;
+    if (ntiles <= 0) { // nothing to compute; still take part in the staging barriers
+        stage();
+        return;
+    }
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
+    const int jact = min(j, nb - 1);
+    const bool jok = j < nb;
 
     const uint16_t *base[NMAT];     // row start for the tile whose loads are being issued
     const uint16_t *base_nxt[NMAT]; // ... and for the tile after it (fetched early: a gather reads an index first)
@@ -180,11 +217,10 @@ __device__ void gemv_rows(RowPtr rowptr, int K, int r0, int r1, int nb, int nbma
     auto load = [&](u32x4(&buf)[NMAT][U], int ch) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            int ks = ks0 + ch * U + u;
-            int k = ks * 32 + g * 8;
-            bool ok = ks < ks1 && k < K;
+            int ks = min(ks0 + ch * U + u, ks1 - 1);
+            int k = min(ks * 32 + g * 8, K - 8);
 #pragma unroll
-            for (int mt = 0; mt < NMAT; ++mt) buf[mt][u] = ok ? ldg16(base[mt] + k) : zero4;
+            for (int mt = 0; mt < NMAT; ++mt) buf[mt][u] = ldg16(base[mt] + k);
         }
     };
 
@@ -202,17 +238,16 @@ __device__ void gemv_rows(RowPtr rowptr, int K, int r0, int r1, int nb, int nbma
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             int ks = ks0 + ch * U + u;
-            if (ks < ks1) { // wave-uniform
-                u32x4 ah = zero4, al = zero4;
-                if (j < nb) {
-                    ah = *reinterpret_cast<const u32x4 *>(act_hi + (size_t)j * kpad + ks * 32 + g * 8);
-                    al = *reinterpret_cast<const u32x4 *>(act_lo + (size_t)j * kpad + ks * 32 + g * 8);
-                }
+            bool ok = jok && ks < ks1;
+            int kse = min(ks, nks - 1);
+            u32x4 ah = *reinterpret_cast<const u32x4 *>(act_hi + (size_t)jact * kpad + kse * 32 + g * 8);
+            u32x4 al = *reinterpret_cast<const u32x4 *>(act_lo + (size_t)jact * kpad + kse * 32 + g * 8);
+            ah = ok ? ah : zero4;
+            al = ok ? al : zero4;
 #pragma unroll
-                for (int mt = 0; mt < NMAT; ++mt) {
-                    acc_h[mt] = mfma16(ah, buf[mt][u], acc_h[mt]);
-                    acc_l[mt] = mfma16(al, buf[mt][u], acc_l[mt]);
-                }
+            for (int mt = 0; mt < NMAT; ++mt) {
+                acc_h[mt] = mfma16(ah, buf[mt][u], acc_h[mt]);
+                acc_l[mt] = mfma16(al, buf[mt][u], acc_l[mt]);
             }
         }
     };
@@ -230,7 +265,7 @@ __device__ void gemv_rows(RowPtr rowptr, int K, int r0, int r1, int nb, int nbma
             }
         }
         clear();
-        __syncthreads();
+        lds_barrier();
         if ((int)threadIdx.x < 16 * nb) {
             int i = threadIdx.x >> 4, jj = threadIdx.x & 15;
             float sums[NMAT];
@@ -247,23 +282,26 @@ __device__ void gemv_rows(RowPtr rowptr, int K, int r0, int r1, int nb, int nbma
     };
 
     u32x4 wb0[NMAT][U], wb1[NMAT][U];
-    int tile = 0, ch = 0;       // position of the compute stream
-    int ltile = 0, lch = 0;     // position of the load stream
-    auto advance_load = [&]() { // move the load stream one chunk on; returns false past the end
+    int tile = 0, ch = 0;   // position of the compute stream
+    int ltile = 0, lch = 0; // position of the load stream
+    auto advance_load = [&]() { // move the load stream one chunk on; past the end it stays on the last chunk
         if (++lch == nch) {
-            lch = 0;
-            ++ltile;
-            if (ltile >= ntiles) return false;
+            if (ltile + 1 < ntiles) {
+                lch = 0;
+                ++ltile;
 #pragma unroll
-            for (int mt = 0; mt < NMAT; ++mt) {
-                base[mt] = base_nxt[mt];
-                base_nxt[mt] = rowptr(mt, row_of(min(ltile + 1, ntiles - 1)));
+                for (int mt = 0; mt < NMAT; ++mt) {
+                    base[mt] = base_nxt[mt];
+                    base_nxt[mt] = rowptr(mt, row_of(min(ltile + 1, ntiles - 1)));
+                }
+            } else {
+                lch = nch - 1;
             }
         }
-        return true;
     };
     auto step = [&](u32x4(&cur)[NMAT][U], u32x4(&nxt)[NMAT][U]) {
-        if (advance_load()) load(nxt, lch);
+        advance_load();
+        load(nxt, lch);
         compute(cur, ch);
         if (++ch == nch) {
             finish_tile(tile);
@@ -272,6 +310,7 @@ __device__ void gemv_rows(RowPtr rowptr, int K, int r0, int r1, int nb, int nbma
         }
     };
     load(wb0, 0);
+    stage();
     const int total = ntiles * nch;
     for (int it = 0; it < total; it += 2) {
         step(wb0, wb1);
@@ -327,27 +366,29 @@ __device__ void phase_proj(const DraftParams &p, int step, int vb, int nvb, char
     GemvLds l = gemv_lds(smem, 2 * d, nbmax, 1);
     for (int b0 = 0; b0 < p.B; b0 += nbmax) {
         int nb = min(nbmax, p.B - b0);
-        __syncthreads();
-        for (int i = 0; i < nb; ++i) {
-            int b = b0 + i;
-            int tok = step_token(p, b, step);
-            uint16_t *hi = l.hi + (size_t)i * l.kpad, *lo = l.lo + (size_t)i * l.kpad;
-            if (step == 0)
-                stage_rmsnorm<true>(p.hidden_in + (size_t)b * d, p.g_h, d, p.eps, hi, lo, l.red, nullptr);
-            else
-                stage_rmsnorm<false>(p.hhat + (size_t)b * d, p.g_h, d, p.eps, hi, lo, l.red, nullptr);
-            stage_rmsnorm<true>(p.embed + (size_t)tok * d, p.g_e, d, p.eps, hi + d, lo + d, l.red, nullptr);
-        }
-        __syncthreads();
+        auto stage = [&]() {
+            __syncthreads();
+            for (int i = 0; i < nb; ++i) {
+                int b = b0 + i;
+                int tok = step_token(p, b, step);
+                uint16_t *hi = l.hi + (size_t)i * l.kpad, *lo = l.lo + (size_t)i * l.kpad;
+                if (step == 0)
+                    stage_rmsnorm<true>(p.hidden_in + (size_t)b * d, p.g_h, d, p.eps, hi, lo, l.red, nullptr);
+                else
+                    stage_rmsnorm<false>(p.hhat + (size_t)b * d, p.g_h, d, p.eps, hi, lo, l.red, nullptr);
+                stage_rmsnorm<true>(p.embed + (size_t)tok * d, p.g_e, d, p.eps, hi + d, lo + d, l.red, nullptr);
+            }
+            __syncthreads();
+        };
         auto rowptr = [&](int, int row) { return p.w_proj + (size_t)row * 2 * d; };
         auto epi = [&](int i, int row, float(&s)[1]) { p.x[(size_t)(b0 + i) * d + row] = s[0]; };
-        gemv_rows<1, 8>(rowptr, 2 * d, r0, r1, nb, nbmax, l.hi, l.lo, l.kpad, l.partial, epi);
+        gemv_rows<1, 8>(rowptr, 2 * d, r0, r1, nb, nbmax, l.hi, l.lo, l.kpad, l.partial, stage, epi);
     }
 }
 
 // ---------------------------------------------------------------------------------------------------
-// phase 2: attention-input RMSNorm + fused QKV projection (+bias)          (step 4)
-// Rotary embedding and the cache append happen where q, k, v are consumed (phase_attn).
+// phase 2: attention-input RMSNorm + fused QKV projection                  (step 4)
+// Bias, rotary embedding and the cache append happen where q, k, v are consumed (phase_attn).
 // ---------------------------------------------------------------------------------------------------
 __device__ void phase_qkv(const DraftParams &p, int step, int vb, int nvb, char *smem) {
     const int d = p.d, rows = p.qkv_dim;
@@ -357,51 +398,56 @@ __device__ void phase_qkv(const DraftParams &p, int step, int vb, int nvb, char 
     GemvLds l = gemv_lds(smem, d, nbmax, 1);
     for (int b0 = 0; b0 < p.B; b0 += nbmax) {
         int nb = min(nbmax, p.B - b0);
-        __syncthreads();
-        for (int i = 0; i < nb; ++i)
-            stage_rmsnorm<false>(p.x + (size_t)(b0 + i) * d, p.g_attn, d, p.eps, l.hi + (size_t)i * l.kpad,
-                                 l.lo + (size_t)i * l.kpad, l.red, nullptr);
-        __syncthreads();
+        auto stage = [&]() {
+            __syncthreads();
+            for (int i = 0; i < nb; ++i)
+                stage_rmsnorm<false>(p.x + (size_t)(b0 + i) * d, p.g_attn, d, p.eps, l.hi + (size_t)i * l.kpad,
+                                     l.lo + (size_t)i * l.kpad, l.red, nullptr);
+            __syncthreads();
+        };
         auto rowptr = [&](int, int row) {
             if (row < p.qd) return p.w_q + (size_t)row * d;
             if (row < p.qd + p.kvd) return p.w_k + (size_t)(row - p.qd) * d;
             return p.w_v + (size_t)(row - p.qd - p.kvd) * d;
         };
-        auto epi = [&](int i, int row, float(&s)[1]) {
-            float bias = 0.f;
-            if (row < p.qd) {
-                if (p.b_q) bias = bf16_to_f32(p.b_q[row]);
-            } else if (row < p.qd + p.kvd) {
-                if (p.b_k) bias = bf16_to_f32(p.b_k[row - p.qd]);
-            } else {
-                if (p.b_v) bias = bf16_to_f32(p.b_v[row - p.qd - p.kvd]);
-            }
-            p.qkv[(size_t)(b0 + i) * rows + row] = s[0] + bias;
-        };
-        gemv_rows<1, 8>(rowptr, d, r0, r1, nb, nbmax, l.hi, l.lo, l.kpad, l.partial, epi);
+        // biases are added where q, k, v are consumed: the epilogue stays free of loads
+        auto epi = [&](int i, int row, float(&s)[1]) { p.qkv[(size_t)(b0 + i) * rows + row] = s[0]; };
+        gemv_rows<1, 8>(rowptr, d, r0, r1, nb, nbmax, l.hi, l.lo, l.kpad, l.partial, stage, epi);
     }
 }
 
 // ---------------------------------------------------------------------------------------------------
-// phase 3: rotary embedding, cache append, split-KV grouped-query decode attention, split merge   (steps 5-6)
+// phase 3: bias, rotary embedding, cache append, split-KV grouped-query decode attention      (steps 5-6)
 // ---------------------------------------------------------------------------------------------------
 // One work item = (sequence, KV head, split of `split_tokens` cache slots).  The G query heads of the group share
 // every key/value they read.  A token's head vector is spread over HD/8 lanes (16 bytes each), so a wave-wide
 // load covers 64/(HD/8) consecutive tokens = 1 KiB of contiguous cache.  Each lane group keeps its own online
-// softmax state; the groups of all 8 waves are merged through LDS, the splits through a workspace in global
-// memory by whichever workgroup arrives last at the (sequence, KV head) counter.
+// softmax state; the groups of all 8 waves are merged through LDS.  A sequence that fits one split is finished
+// here; otherwise the item leaves (sum of p*V, max, sum of p) per head in the workspace for phase_attn_merge.
+// At batch 1 the phase moves little data and is bound by its chain of dependent memory round trips, so the first
+// cache loads are issued before anything else and the rotary table costs no double-precision transcendental.
 template <int G, int HD>
 struct AttnLds {
-    static constexpr int LPT = HD / 8;          // lanes per token
-    static constexpr int TPI = kWave / LPT;     // tokens per wave-wide load
+    static constexpr int LPT = HD / 8;           // lanes per token
+    static constexpr int TPI = kWave / LPT;      // tokens per wave-wide load
     static constexpr int NSTREAM = kWaves * TPI; // independent softmax streams per workgroup
     float q[G][HD];
     float cs[HD / 2], sn[HD / 2];
     float knew[HD], vnew[HD];
     float acc[NSTREAM][G][HD];
     float ml[NSTREAM][G][2];
-    int is_last;
 };
+
+// cos/sin of pos * inv_freq with the product and the reduction to [-pi, pi] in double, the rest in float
+__device__ __forceinline__ void rope_cos_sin(int pos, double inv_freq, float &cs, float &sn) {
+    const double two_pi_hi = 6.283185307179586232, two_pi_lo = 2.4492935982947064e-16, inv_two_pi = 0.15915494309189535;
+    double ang = (double)pos * inv_freq;
+    double n = rint(ang * inv_two_pi);
+    double r = fma(-n, two_pi_lo, fma(-n, two_pi_hi, ang));
+    float rf = (float)r;
+    cs = cosf(rf);
+    sn = sinf(rf);
+}
 
 template <int G, int HD>
 __device__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char *smem) {
@@ -428,40 +474,59 @@ __device__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char
         const uint16_t *kc = p.k_cache + ((size_t)b * p.Hkv + kvh) * p.cap * HD;
         const uint16_t *vc = p.v_cache + ((size_t)b * p.Hkv + kvh) * p.cap * HD;
         const float *qkv = p.qkv + (size_t)b * p.qkv_dim;
+        const int nblk = (ntok + TPI - 1) / TPI;
+
+        u32x4 kr[U], vr[U];
+        bool ok[U];
+        auto load_blocks = [&](int base) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                int t = (base + u * kWaves) * TPI + tq;
+                ok[u] = t < ntok;
+                size_t off = (size_t)(t0 + (ok[u] ? t : 0)) * HD + c * 8; // slot t0 is always inside the cache
+                kr[u] = ldg16(kc + off);
+                vr[u] = ldg16(vc + off);
+            }
+        };
+        load_blocks(wave); // in flight while q, the rotary table and the new key/value are prepared
 
         __syncthreads(); // LDS of the previous item is free
-        if (tid < HD / 2) {
-            // angle in double: positions reach 2^15 and the pair frequency spans six decades
-            double inv = pow((double)p.theta, -2.0 * (double)tid / (double)HD);
-            double sn, cs;
-            sincos((double)pnew * inv, &sn, &cs);
-            s.cs[tid] = (float)cs;
-            s.sn[tid] = (float)sn;
-        }
+        if (tid < HD / 2) rope_cos_sin(pnew, p.rope_inv[tid], s.cs[tid], s.sn[tid]);
         __syncthreads();
         for (int idx = tid; idx < G * HD / 2; idx += kBlock) {
             int gq = idx / (HD / 2), jj = idx % (HD / 2);
             const float *src = qkv + (size_t)(kvh * G + gq) * HD;
             float a = src[jj], bb = src[jj + HD / 2], cs = s.cs[jj], sn = s.sn[jj];
+            if (p.b_q) {
+                a += bf16_to_f32(p.b_q[(kvh * G + gq) * HD + jj]);
+                bb += bf16_to_f32(p.b_q[(kvh * G + gq) * HD + jj + HD / 2]);
+            }
             s.q[gq][jj] = (a * cs - bb * sn) * scale;
             s.q[gq][jj + HD / 2] = (bb * cs + a * sn) * scale;
         }
         if (last) {
             uint16_t *kdst = p.k_cache + (((size_t)b * p.Hkv + kvh) * p.cap + pnew) * HD;
             uint16_t *vdst = p.v_cache + (((size_t)b * p.Hkv + kvh) * p.cap + pnew) * HD;
-            if (tid < HD / 2) {
+            if (tid >= kWave * 4 && tid < kWave * 4 + HD / 2) {
+                int e = tid - kWave * 4;
                 const float *src = qkv + p.qd + (size_t)kvh * HD;
-                float a = src[tid], bb = src[tid + HD / 2], cs = s.cs[tid], sn = s.sn[tid];
-                uint16_t r0 = f32_to_bf16(a * cs - bb * sn), r1 = f32_to_bf16(bb * cs + a * sn);
-                s.knew[tid] = bf16_to_f32(r0);
-                s.knew[tid + HD / 2] = bf16_to_f32(r1);
-                if (!dead) {
-                    kdst[tid] = r0;
-                    kdst[tid + HD / 2] = r1;
+                float a = src[e], bb = src[e + HD / 2], cs = s.cs[e], sn = s.sn[e];
+                if (p.b_k) {
+                    a += bf16_to_f32(p.b_k[kvh * HD + e]);
+                    bb += bf16_to_f32(p.b_k[kvh * HD + e + HD / 2]);
                 }
-            } else if (tid >= kWave * 2 && tid < kWave * 2 + HD) {
-                int e = tid - kWave * 2;
-                uint16_t r = f32_to_bf16(qkv[p.qd + p.kvd + (size_t)kvh * HD + e]);
+                uint16_t r0 = f32_to_bf16(a * cs - bb * sn), r1 = f32_to_bf16(bb * cs + a * sn);
+                s.knew[e] = bf16_to_f32(r0);
+                s.knew[e + HD / 2] = bf16_to_f32(r1);
+                if (!dead) {
+                    kdst[e] = r0;
+                    kdst[e + HD / 2] = r1;
+                }
+            } else if (tid >= kWave * 6 && tid < kWave * 6 + HD) {
+                int e = tid - kWave * 6;
+                float vraw = qkv[p.qd + p.kvd + (size_t)kvh * HD + e];
+                if (p.b_v) vraw += bf16_to_f32(p.b_v[kvh * HD + e]);
+                uint16_t r = f32_to_bf16(vraw);
                 s.vnew[e] = bf16_to_f32(r);
                 if (!dead) vdst[e] = r;
             }
@@ -482,13 +547,13 @@ __device__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char
             for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
         }
 
-        auto absorb = [&](const float(&sc)[U][G], const float(&vv)[U][8], const bool(&ok)[U]) {
+        auto absorb = [&](const float(&sc)[U][G], const float(&vv)[U][8], const bool(&okk)[U]) {
 #pragma unroll
             for (int g = 0; g < G; ++g) {
                 float mb = mx[g];
 #pragma unroll
                 for (int u = 0; u < U; ++u)
-                    if (ok[u]) mb = fmaxf(mb, sc[u][g]);
+                    if (okk[u]) mb = fmaxf(mb, sc[u][g]);
                 if (mb == -INFINITY) continue;
                 float alpha = expf(mx[g] - mb); // 0 when nothing was absorbed before
                 float sm = sum[g] * alpha;
@@ -496,7 +561,7 @@ __device__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char
                 for (int e = 0; e < 8; ++e) acc[g][e] *= alpha;
 #pragma unroll
                 for (int u = 0; u < U; ++u)
-                    if (ok[u]) {
+                    if (okk[u]) {
                         float pr = expf(sc[u][g] - mb);
                         sm += pr;
 #pragma unroll
@@ -507,18 +572,8 @@ __device__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char
             }
         };
 
-        const int nblk = (ntok + TPI - 1) / TPI;
         for (int base = wave; base < nblk; base += kWaves * U) {
-            u32x4 kr[U], vr[U];
-            bool ok[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                int t = (base + u * kWaves) * TPI + tq;
-                ok[u] = t < ntok;
-                size_t off = (size_t)(t0 + t) * HD + c * 8;
-                kr[u] = ok[u] ? ldg16(kc + off) : u32x4{0u, 0u, 0u, 0u};
-                vr[u] = ok[u] ? ldg16(vc + off) : u32x4{0u, 0u, 0u, 0u};
-            }
+            if (base != wave) load_blocks(base);
             float sc[U][G], vv[U][8];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -544,10 +599,10 @@ __device__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char
         }
         if (last && wave == 0) { // the token being appended, from LDS; every lane group computes it, group 0 keeps it
             float sc[U][G], vv[U][8];
-            bool ok[U];
+            bool okn[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                ok[u] = (u == 0) && (tq == 0);
+                okn[u] = (u == 0) && (tq == 0);
 #pragma unroll
                 for (int g = 0; g < G; ++g) sc[u][g] = 0.f;
 #pragma unroll
@@ -562,7 +617,7 @@ __device__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char
                 for (int e = 0; e < 8; ++e) a += q[g][e] * s.knew[c * 8 + e];
                 sc[0][g] = (LPT == 16) ? row16_sum(a) : oct_sum(a);
             }
-            absorb(sc, vv, ok);
+            absorb(sc, vv, okn);
         }
 
         // merge the lane groups of the workgroup
@@ -602,38 +657,60 @@ __device__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char
                 }
             }
         }
-        if (nsplit > 1) {
-            __threadfence();
-            __syncthreads();
-            if (tid == 0) {
-                int old = __hip_atomic_fetch_add(&p.attn_cnt[b * p.Hkv + kvh], 1, __ATOMIC_ACQ_REL,
-                                                 __HIP_MEMORY_SCOPE_AGENT);
-                s.is_last = (old == nsplit - 1);
+    }
+}
+
+// phase 3b: merge of the split partials.  One wave per (sequence, query head) whose context spans several splits:
+// weights exp(max_s - max) / sum over splits are formed once (in a wave-private LDS strip), then every lane sums its
+// share of the head dimension with sixteen loads in flight.
+template <int HD>
+__device__ void phase_attn_merge(const DraftParams &p, int step, int vb, int nvb, char *smem) {
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const int T = p.split_tokens, S = p.max_splits;
+    const int PW = HD + 2;
+    float *w = reinterpret_cast<float *>(smem) + (size_t)wave * S;
+    const int n_items = p.B * p.Hq;
+    for (int item = vb * kWaves + wave; item < n_items; item += nvb * kWaves) {
+        const int b = item / p.Hq, hq = item % p.Hq;
+        const int Lb = seq_dead(p, b) ? 0 : p.kv_len[b];
+        const int nsplit = (Lb + step + 1 + T - 1) / T;
+        if (nsplit <= 1) continue; // finished by phase_attn
+        const float *src = p.attn_part + ((size_t)b * p.Hq + hq) * S * PW;
+        float M = -INFINITY;
+        for (int s2 = lane; s2 < nsplit; s2 += kWave) {
+            float m = src[(size_t)s2 * PW + HD];
+            w[s2] = m;
+            M = fmaxf(M, m);
+        }
+#pragma unroll
+        for (int off = 1; off < kWave; off <<= 1) M = fmaxf(M, __shfl_xor(M, off, kWave));
+        float Ls = 0.f;
+        for (int s2 = lane; s2 < nsplit; s2 += kWave) {
+            float e = expf(w[s2] - M);
+            w[s2] = e;
+            Ls += src[(size_t)s2 * PW + HD + 1] * e;
+        }
+        Ls = wave_sum(Ls);
+        const float inv = 1.0f / Ls;
+        // w[] was written by this wave's own lanes: LDS ops of one wave complete in order, no barrier needed
+        for (int dd = lane; dd < HD; dd += kWave) {
+            float A = 0.f;
+            int s2 = 0;
+            for (; s2 + 16 <= nsplit; s2 += 16) {
+                float t[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) t[u] = src[(size_t)(s2 + u) * PW + dd];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) A += t[u] * w[s2 + u];
             }
-            __syncthreads();
-            if (s.is_last) {
-                __threadfence();
-                for (int o = tid; o < G * HD; o += kBlock) {
-                    int g = o / HD, dd = o % HD, hq = kvh * G + g;
-                    const float *src = p.attn_part + ((size_t)b * p.Hq + hq) * S * PW;
-                    float M = -INFINITY;
-                    for (int s2 = 0; s2 < nsplit; ++s2) M = fmaxf(M, src[(size_t)s2 * PW + HD]);
-                    float Ls = 0.f, A = 0.f;
-                    for (int s2 = 0; s2 < nsplit; ++s2) {
-                        float w = expf(src[(size_t)s2 * PW + HD] - M);
-                        Ls += src[(size_t)s2 * PW + HD + 1] * w;
-                        A += src[(size_t)s2 * PW + dd] * w;
-                    }
-                    p.attn[(size_t)b * p.qd + (size_t)hq * HD + dd] = A / Ls;
-                }
-                if (tid == 0) p.attn_cnt[b * p.Hkv + kvh] = 0; // ready for the next step
-            }
+            for (; s2 < nsplit; ++s2) A += src[(size_t)s2 * PW + dd] * w[s2];
+            p.attn[(size_t)b * p.qd + (size_t)hq * HD + dd] = A * inv;
         }
     }
 }
 
 // ---------------------------------------------------------------------------------------------------
-// phase 4: output projection + residual                                      (step 7)
+// phase 4: output projection (its residual add happens in the consumers)      (step 7)
 // ---------------------------------------------------------------------------------------------------
 __device__ void phase_oproj(const DraftParams &p, int, int vb, int nvb, char *smem) {
     const int d = p.d, K = p.qd;
@@ -643,16 +720,16 @@ __device__ void phase_oproj(const DraftParams &p, int, int vb, int nvb, char *sm
     GemvLds l = gemv_lds(smem, K, nbmax, 1);
     for (int b0 = 0; b0 < p.B; b0 += nbmax) {
         int nb = min(nbmax, p.B - b0);
-        __syncthreads();
-        for (int i = 0; i < nb; ++i)
-            stage_plain(p.attn + (size_t)(b0 + i) * K, K, l.kpad, l.hi + (size_t)i * l.kpad, l.lo + (size_t)i * l.kpad);
-        __syncthreads();
-        auto rowptr = [&](int, int row) { return p.w_o + (size_t)row * K; };
-        auto epi = [&](int i, int row, float(&s)[1]) {
-            size_t o = (size_t)(b0 + i) * d + row;
-            p.x1[o] = p.x[o] + s[0];
+        auto stage = [&]() {
+            __syncthreads();
+            for (int i = 0; i < nb; ++i)
+                stage_plain(p.attn + (size_t)(b0 + i) * K, K, l.kpad, l.hi + (size_t)i * l.kpad,
+                            l.lo + (size_t)i * l.kpad);
+            __syncthreads();
         };
-        gemv_rows<1, 8>(rowptr, K, r0, r1, nb, nbmax, l.hi, l.lo, l.kpad, l.partial, epi);
+        auto rowptr = [&](int, int row) { return p.w_o + (size_t)row * K; };
+        auto epi = [&](int i, int row, float(&s)[1]) { p.o[(size_t)(b0 + i) * d + row] = s[0]; };
+        gemv_rows<1, 8>(rowptr, K, r0, r1, nb, nbmax, l.hi, l.lo, l.kpad, l.partial, stage, epi);
     }
 }
 
@@ -667,22 +744,25 @@ __device__ void phase_gateup(const DraftParams &p, int, int vb, int nvb, char *s
     GemvLds l = gemv_lds(smem, d, nbmax, 2);
     for (int b0 = 0; b0 < p.B; b0 += nbmax) {
         int nb = min(nbmax, p.B - b0);
-        __syncthreads();
-        for (int i = 0; i < nb; ++i)
-            stage_rmsnorm<false>(p.x1 + (size_t)(b0 + i) * d, p.g_mlp, d, p.eps, l.hi + (size_t)i * l.kpad,
-                                 l.lo + (size_t)i * l.kpad, l.red, nullptr);
-        __syncthreads();
+        auto stage = [&]() {
+            __syncthreads();
+            for (int i = 0; i < nb; ++i)
+                stage_rmsnorm<false>(p.x + (size_t)(b0 + i) * d, p.g_mlp, d, p.eps, l.hi + (size_t)i * l.kpad,
+                                     l.lo + (size_t)i * l.kpad, l.red, nullptr, nullptr,
+                                     p.o + (size_t)(b0 + i) * d); // x1 = x + w_o attn
+            __syncthreads();
+        };
         auto rowptr = [&](int mt, int row) { return (mt == 0 ? p.w_gate : p.w_up) + (size_t)row * d; };
         auto epi = [&](int i, int row, float(&s)[2]) {
             float gt = s[0];
             p.m[(size_t)(b0 + i) * F + row] = (gt / (1.0f + expf(-gt))) * s[1];
         };
-        gemv_rows<2, 4>(rowptr, d, r0, r1, nb, nbmax, l.hi, l.lo, l.kpad, l.partial, epi);
+        gemv_rows<2, 4>(rowptr, d, r0, r1, nb, nbmax, l.hi, l.lo, l.kpad, l.partial, stage, epi);
     }
 }
 
 // ---------------------------------------------------------------------------------------------------
-// phase 6: down projection + residual                                         (step 9, first half)
+// phase 6: down projection (its residual add happens in the consumer)         (step 9, first half)
 // ---------------------------------------------------------------------------------------------------
 __device__ void phase_down(const DraftParams &p, int, int vb, int nvb, char *smem) {
     const int d = p.d, K = p.F;
@@ -692,16 +772,16 @@ __device__ void phase_down(const DraftParams &p, int, int vb, int nvb, char *sme
     GemvLds l = gemv_lds(smem, K, nbmax, 1);
     for (int b0 = 0; b0 < p.B; b0 += nbmax) {
         int nb = min(nbmax, p.B - b0);
-        __syncthreads();
-        for (int i = 0; i < nb; ++i)
-            stage_plain(p.m + (size_t)(b0 + i) * K, K, l.kpad, l.hi + (size_t)i * l.kpad, l.lo + (size_t)i * l.kpad);
-        __syncthreads();
-        auto rowptr = [&](int, int row) { return p.w_down + (size_t)row * K; };
-        auto epi = [&](int i, int row, float(&s)[1]) {
-            size_t o = (size_t)(b0 + i) * d + row;
-            p.x2[o] = p.x1[o] + s[0];
+        auto stage = [&]() {
+            __syncthreads();
+            for (int i = 0; i < nb; ++i)
+                stage_plain(p.m + (size_t)(b0 + i) * K, K, l.kpad, l.hi + (size_t)i * l.kpad,
+                            l.lo + (size_t)i * l.kpad);
+            __syncthreads();
         };
-        gemv_rows<1, 8>(rowptr, K, r0, r1, nb, nbmax, l.hi, l.lo, l.kpad, l.partial, epi);
+        auto rowptr = [&](int, int row) { return p.w_down + (size_t)row * K; };
+        auto epi = [&](int i, int row, float(&s)[1]) { p.dn[(size_t)(b0 + i) * d + row] = s[0]; };
+        gemv_rows<1, 8>(rowptr, K, r0, r1, nb, nbmax, l.hi, l.lo, l.kpad, l.partial, stage, epi);
     }
 }
 
@@ -719,16 +799,19 @@ __device__ void phase_lmhead(const DraftParams &p, int step, int vb, int nvb, ch
     GemvLds l = gemv_lds(smem, d, nbmax, 1);
     for (int b0 = 0; b0 < p.B; b0 += nbmax) {
         int nb = min(nbmax, p.B - b0);
-        __syncthreads();
-        for (int i = 0; i < nb; ++i) {
-            int b = b0 + i;
-            // workgroup 0 also publishes the step's output hidden state: for the next step and for the caller
-            float *hh = (vb == 0) ? p.hhat + (size_t)b * d : nullptr;
-            float *ho = (vb == 0 && p.hidden_out) ? p.hidden_out + ((size_t)b * p.K + step) * d : nullptr;
-            stage_rmsnorm<false>(p.x2 + (size_t)b * d, p.g_final, d, p.eps, l.hi + (size_t)i * l.kpad,
-                                 l.lo + (size_t)i * l.kpad, l.red, hh, ho);
-        }
-        __syncthreads();
+        auto stage = [&]() {
+            __syncthreads();
+            for (int i = 0; i < nb; ++i) {
+                int b = b0 + i;
+                // workgroup 0 also publishes the step's output hidden state: for the next step and for the caller
+                float *hh = (vb == 0) ? p.hhat + (size_t)b * d : nullptr;
+                float *ho = (vb == 0 && p.hidden_out) ? p.hidden_out + ((size_t)b * p.K + step) * d : nullptr;
+                stage_rmsnorm<false>(p.x + (size_t)b * d, p.g_final, d, p.eps, l.hi + (size_t)i * l.kpad,
+                                     l.lo + (size_t)i * l.kpad, l.red, hh, ho, p.o + (size_t)b * d,
+                                     p.dn + (size_t)b * d); // x2 = (x + w_o attn) + w_down m
+            }
+            __syncthreads();
+        };
         unsigned long long best = 0ull;
         auto rowptr = [&](int, int row) {
             int r = p.ids ? p.ids[row] : row;
@@ -739,7 +822,7 @@ __device__ void phase_lmhead(const DraftParams &p, int step, int vb, int nvb, ch
             unsigned long long key = argmax_key(s[0], (uint32_t)row);
             best = key > best ? key : best;
         };
-        gemv_rows<1, 8>(rowptr, d, r0, r1, nb, nbmax, l.hi, l.lo, l.kpad, l.partial, epi);
+        gemv_rows<1, 8>(rowptr, d, r0, r1, nb, nbmax, l.hi, l.lo, l.kpad, l.partial, stage, epi);
         // threads 16*i .. 16*i+15 hold candidates of sequence i
         if ((int)threadIdx.x < 16 * nb) {
 #pragma unroll
@@ -762,5 +845,108 @@ __device__ void phase_finalize(const DraftParams &p, int vb) {
         p.draft_out[(size_t)b * p.K + p.K - 1] = seq_dead(p, b) ? -1 : (p.ids ? p.ids[i] : (int)i);
     }
 }
+
+// ---------------------------------------------------------------------------------------------------
+// single-launch path: all phases of all K steps in one cooperative kernel
+// ---------------------------------------------------------------------------------------------------
+// Grid-wide barrier on a counter that only grows: barrier number `epoch` (1-based within the launch) is passed
+// when the counter reaches bar_base + epoch * gridDim.x.  The release/acquire fences at agent scope make every
+// workgroup's global writes visible to every other workgroup (the XCDs' L2 caches are not coherent by themselves).
+// A workgroup that waits longer than bar_timeout ticks sets the sticky error word; from then on every barrier of
+// every workgroup falls through, so the grid always drains.
+__device__ __forceinline__ void grid_barrier(const DraftParams &p, unsigned &epoch) {
+    ++epoch;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const unsigned long long target = p.bar_base + (unsigned long long)epoch * gridDim.x;
+        __hip_atomic_fetch_add(p.bar, 1ull, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        const long long t0 = wall_clock64();
+        unsigned spins = 0;
+        while (__hip_atomic_load(p.bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+            if ((++spins & 63u) == 0) { // now and then: has anyone given up, or is it time to
+                if (__hip_atomic_load(p.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & kErrBarrierTimeout) break;
+                if (wall_clock64() - t0 > p.bar_timeout) {
+                    atomicOr(p.err, kErrBarrierTimeout);
+                    break;
+                }
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    }
+    __syncthreads();
+}
+
+// Out-of-line copies of the phases: inlined together they would share one register budget and spill.
+__device__ __noinline__ void call_proj(const DraftParams &p, int step, int vb, int nvb, char *smem) {
+    phase_proj(p, step, vb, nvb, smem);
+}
+__device__ __noinline__ void call_qkv(const DraftParams &p, int step, int vb, int nvb, char *smem) {
+    phase_qkv(p, step, vb, nvb, smem);
+}
+template <int G, int HD>
+__device__ __noinline__ void call_attn(const DraftParams &p, int step, int vb, int nvb, char *smem) {
+    phase_attn<G, HD>(p, step, vb, nvb, smem);
+}
+__device__ __noinline__ void call_oproj(const DraftParams &p, int step, int vb, int nvb, char *smem) {
+    phase_oproj(p, step, vb, nvb, smem);
+}
+__device__ __noinline__ void call_gateup(const DraftParams &p, int step, int vb, int nvb, char *smem) {
+    phase_gateup(p, step, vb, nvb, smem);
+}
+__device__ __noinline__ void call_down(const DraftParams &p, int step, int vb, int nvb, char *smem) {
+    phase_down(p, step, vb, nvb, smem);
+}
+__device__ __noinline__ void call_lmhead(const DraftParams &p, int step, int vb, int nvb, char *smem) {
+    phase_lmhead(p, step, vb, nvb, smem);
+}
+
+template <int G, int HD>
+__device__ void fused_steps(const DraftParams &p, char *smem) {
+    const int vb = blockIdx.x, nvb = gridDim.x;
+    unsigned epoch = 0;
+    int stamp_i = 0;
+    auto stamp = [&](int step) {
+        if (p.trace && vb == 0 && threadIdx.x == 0) p.trace[step * 16 + stamp_i] = wall_clock64();
+        ++stamp_i;
+    };
+    for (int step = 0; step < p.K; ++step) {
+        stamp_i = 0;
+        stamp(step);
+        call_proj(p, step, vb, nvb, smem);
+        stamp(step);
+        grid_barrier(p, epoch);
+        stamp(step);
+        call_qkv(p, step, vb, nvb, smem);
+        stamp(step);
+        grid_barrier(p, epoch);
+        stamp(step);
+        call_attn<G, HD>(p, step, vb, nvb, smem);
+        if (p.max_splits > 1) {
+            grid_barrier(p, epoch);
+            phase_attn_merge<HD>(p, step, vb, nvb, smem);
+        }
+        stamp(step);
+        grid_barrier(p, epoch);
+        stamp(step);
+        call_oproj(p, step, vb, nvb, smem);
+        stamp(step);
+        grid_barrier(p, epoch);
+        stamp(step);
+        call_gateup(p, step, vb, nvb, smem);
+        stamp(step);
+        grid_barrier(p, epoch);
+        stamp(step);
+        call_down(p, step, vb, nvb, smem);
+        stamp(step);
+        grid_barrier(p, epoch);
+        stamp(step);
+        call_lmhead(p, step, vb, nvb, smem);
+        stamp(step);
+        grid_barrier(p, epoch);
+        stamp(step);
+    }
+    phase_finalize(p, vb);
+}
+constexpr int kBarriersPerStep = 7; // one more per step when the attention is split (max_splits > 1)
 
 } // namespace mtp
