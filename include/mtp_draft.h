@@ -46,11 +46,11 @@ typedef enum {
 
 /* Shape of the head (Sec. 3.1 "Model Configuration" for the 7B case) and limits of this handle. Host POD. */
 typedef struct {
-    int32_t d_model;         /* d; multiple of 32                                              */
+    int32_t d_model;         /* d; multiple of 32, 256..8192                                   */
     int32_t n_q_heads;       /* Hq                                                             */
     int32_t n_kv_heads;      /* Hkv; Hq / Hkv must be 1, 2, 4 or 8                             */
     int32_t head_dim;        /* hd; 64 or 128                                                  */
-    int32_t d_ffn;           /* F, SwiGLU width; multiple of 8                                 */
+    int32_t d_ffn;           /* F, SwiGLU width; multiple of 8, at least 256; Hq*hd >= 256 too */
     int32_t vocab_size;      /* |V|                                                            */
     float rms_eps;           /* added to the mean square inside every RMSNorm                  */
     float rope_theta;        /* rotary base; pairs are (j, j + hd/2), the full head is rotated */

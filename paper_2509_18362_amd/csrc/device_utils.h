@@ -89,5 +89,9 @@ __device__ __forceinline__ f32x4 mfma16(u32x4 a, u32x4 b, f32x4 c) {
 }
 
 __device__ __forceinline__ u32x4 ldg16(const void *p) { return *reinterpret_cast<const u32x4 *>(p); }
+// streaming load: the data is used once, keep it from displacing reusable lines in the caches
+__device__ __forceinline__ u32x4 ldg16_stream(const void *p) {
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+}
 
 } // namespace mtp

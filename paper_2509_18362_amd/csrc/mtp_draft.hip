@@ -12,6 +12,7 @@
 #include <vector>
 
 #include "phases.h"
+#include "fused.h"
 
 using namespace mtp;
 
@@ -58,10 +59,10 @@ __global__ void k_finalize(DraftParams p) { phase_finalize(p, blockIdx.x); }
 template <int G, int HD>
 __global__ __launch_bounds__(kBlock) void k_fused(DraftParams) {
     extern __shared__ __align__(16) char smem[];
-    // the phases are called out of line and take the parameters by reference: point them at the kernel-argument
-    // segment (the struct is the only argument, at offset 0) instead of a per-lane stack copy
+    // the attention phase is called out of line and takes the parameters by reference: point it at the
+    // kernel-argument segment (the struct is the only argument, at offset 0) instead of a per-lane stack copy
     const DraftParams *p = (const DraftParams *)__builtin_amdgcn_kernarg_segment_ptr();
-    fused_steps<G, HD>(*p, smem);
+    fused_steps2<G, HD>(*p, smem);
 }
 
 // Sequential acceptance up to the first mismatch and the draft-cache length after it (Sec. 2.3 "Verification phase").
@@ -154,12 +155,13 @@ size_t attn_part_floats(const mtp_config &c) {
 
 bool config_ok(const mtp_config *c) {
     if (!c) return false;
-    if (c->d_model < 32 || c->d_model > 8192 || c->d_model % 32) return false;
+    if (c->d_model < 256 || c->d_model > 8192 || c->d_model % 32) return false;
     if (c->head_dim != 64 && c->head_dim != 128) return false;
     if (c->n_q_heads < 1 || c->n_kv_heads < 1 || c->n_q_heads % c->n_kv_heads) return false;
     int G = c->n_q_heads / c->n_kv_heads;
     if (G != 1 && G != 2 && G != 4 && G != 8) return false;
-    if (c->d_ffn < 8 || c->d_ffn % 8) return false;
+    if (c->d_ffn < 256 || c->d_ffn % 8) return false;
+    if (c->n_q_heads * c->head_dim < 256) return false; // every reduction length holds at least one 256-element chunk
     if (c->vocab_size < 1) return false;
     if (c->max_batch < 1 || c->max_batch > kBlock) return false;
     if (c->max_draft_steps < 1 || c->kv_capacity < c->max_draft_steps) return false;
@@ -170,10 +172,11 @@ bool config_ok(const mtp_config *c) {
 }
 
 constexpr size_t kAlign = 256;
+constexpr int kMaxFusedGrid = 1024; // workgroups of the single-launch kernel (one per CU)
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct WsLayout {
-    size_t x, qkv, attn, o, m, dn, hhat, keys, err, bar, rope_inv, attn_part, total;
+    size_t x, qkv, attn, o, m, dn, hhat, keys, err, bar, cand, rope_inv, attn_part, total;
 };
 WsLayout ws_layout(const mtp_config &c) {
     WsLayout l{};
@@ -194,7 +197,8 @@ WsLayout ws_layout(const mtp_config &c) {
     l.hhat = take(mb * d * 4);
     l.keys = take((size_t)c.max_draft_steps * mb * 8);
     l.err = take(4);
-    l.bar = take(8);
+    l.bar = take(kBarWords * 8);
+    l.cand = take((size_t)c.max_draft_steps * mb * kMaxFusedGrid * 8);
     l.rope_inv = take((size_t)c.head_dim / 2 * 8);
     l.attn_part = take(attn_part_floats(c) * 4);
     l.total = off;
@@ -217,7 +221,8 @@ struct mtp_handle {
     phase_kernel_t attn_fn, merge_fn;
     fused_kernel_t fused_fn;
     int mode;                    // 0: one launch per phase, 1: single cooperative launch for the whole call
-    unsigned long long bar_count; // host mirror of the device barrier counter
+    unsigned long long bar_epochs; // barriers completed by earlier single-launch calls (mirror of the device state)
+    int fused_grid;                // workgroups of those calls; the counters assume it never changes
     long long *trace;             // optional device buffer for phase time stamps
     int timing;         // 0 off, 1 whole call, 2 + phase: every launch of one phase
     hipEvent_t ev[2];   // whole call
@@ -315,7 +320,8 @@ int32_t mtp_draft_init(mtp_handle **out, const mtp_config *cfg, const mtp_weight
     h->merge_fn = cfg->head_dim == 128 ? k_attn_merge<128> : k_attn_merge<64>;
     h->fused_fn = fused_kernel(cfg->n_q_heads / cfg->n_kv_heads, cfg->head_dim);
     h->mode = 0;
-    h->bar_count = 0;
+    h->bar_epochs = 0;
+    h->fused_grid = 0;
     h->trace = nullptr;
     ok = ok && h->attn_fn != nullptr && h->fused_fn != nullptr;
     // allow the large-LDS launches
@@ -417,7 +423,8 @@ int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_inde
     p.rope_inv = reinterpret_cast<const double *>(ws + l.rope_inv);
     p.attn_part = reinterpret_cast<float *>(ws + l.attn_part);
     p.bar = reinterpret_cast<unsigned long long *>(ws + l.bar);
-    p.bar_base = h->bar_count;
+    p.bar_base = h->bar_epochs;
+    p.cand = reinterpret_cast<unsigned long long *>(ws + l.cand);
     p.bar_timeout = 200000000ll; // 2 s of the 100 MHz wall clock
     p.trace = h->trace;
     p.max_batch = c.max_batch;
@@ -443,7 +450,7 @@ int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_inde
     const size_t lds_max = std::max({lds_proj, lds_d2, lds_q, lds_down, lds_attn});
     if (lds_max > h->lds_limit) return MTP_ERR_CONFIG;
 
-    const int grid = h->num_cus * (B <= 2 ? 2 : 1);
+    const int grid = h->num_cus; // one 512-thread workgroup per CU: the register ring leaves no room for a second
     const int attn_items = B * p.Hkv * p.max_splits;
     const int attn_grid = std::max(1, std::min(attn_items, h->num_cus * 2));
     const int merge_grid = std::max(1, std::min((B * p.Hq + kWaves - 1) / kWaves, h->num_cus));
@@ -451,25 +458,36 @@ int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_inde
     const int tphase = h->timing >= 2 ? h->timing - 2 : -1;
     h->pev_used = 0;
     if (h->mode == 1 && tphase < 0) {
-        // single launch: every workgroup must be resident at once, which the cooperative launch checks
-        int per_cu = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)h->fused_fn, kBlock, lds_max) !=
-                hipSuccess || per_cu < 1)
-            return MTP_ERR_HIP;
-        const int fgrid = h->num_cus * std::min(per_cu, B <= 2 ? 2 : 1);
-        void *args[] = {(void *)&p};
-        if (h->timing == 1) (void)hipEventRecord(h->ev[0], st);
-        if (hipLaunchCooperativeKernel((const void *)h->fused_fn, dim3(fgrid), dim3(kBlock), args,
-                                       (unsigned)lds_max, st) != hipSuccess) {
-            (void)hipGetLastError();
-            return MTP_ERR_HIP;
+        // single launch: all B sequences are staged together and every workgroup must be resident at once (one
+        // per CU; the cooperative launch checks it).  Falls back to one launch per phase when LDS cannot hold B.
+        const int fgrid = std::min(h->num_cus, kMaxFusedGrid);
+        size_t region = std::max({fused_gemv_region(p.d, p.qd, p.F, B), lds_attn, lds_merge});
+        region = (region + 255) / 256 * 256;
+        const size_t ids_bytes = ((size_t)(p.n + fgrid - 1) / fgrid * 4 + 255) / 256 * 256;
+        const size_t lds_fused = region + ids_bytes + 256;
+        if (B <= 16 && lds_fused <= h->lds_limit) {
+            p.fused_gemv_bytes = (int)region;
+            p.fused_ids_bytes = (int)ids_bytes;
+            if (h->fused_grid != fgrid) { // first use, or the grid changed: restart the barrier counters
+                if (hipMemsetAsync(ws + l.bar, 0, kBarWords * 8, st) != hipSuccess) return MTP_ERR_HIP;
+                h->bar_epochs = 0;
+                h->fused_grid = fgrid;
+                p.bar_base = 0;
+            }
+            void *args[] = {(void *)&p};
+            if (h->timing == 1) (void)hipEventRecord(h->ev[0], st);
+            if (hipLaunchCooperativeKernel((const void *)h->fused_fn, dim3(fgrid), dim3(kBlock), args,
+                                           (unsigned)lds_fused, st) != hipSuccess) {
+                (void)hipGetLastError();
+                return MTP_ERR_HIP;
+            }
+            h->bar_epochs += (unsigned long long)K * (kBarriersPerStep + (p.max_splits > 1 ? 1 : 0));
+            if (h->timing == 1) {
+                (void)hipEventRecord(h->ev[1], st);
+                h->ev_recorded = true;
+            }
+            return MTP_OK;
         }
-        h->bar_count += (unsigned long long)fgrid * (kBarriersPerStep + (p.max_splits > 1 ? 1 : 0)) * K;
-        if (h->timing == 1) {
-            (void)hipEventRecord(h->ev[1], st);
-            h->ev_recorded = true;
-        }
-        return MTP_OK;
     }
     auto launch = [&](int phase, phase_kernel_t fn, int g, size_t lds, int step) {
         if (phase == tphase) (void)hipEventRecord(h->pev[2 * (size_t)step], st);
@@ -527,7 +545,8 @@ int32_t mtp_poll_error(mtp_handle *h, void *hip_stream) {
         if (hipMemsetAsync(dev, 0, 4, st) != hipSuccess) return MTP_ERR_HIP;
         if (word & kErrBarrierTimeout) { // the barrier counter is out of step with the host's mirror: restart both
             if (hipMemsetAsync(h->ws + h->lay.bar, 0, 8, st) != hipSuccess) return MTP_ERR_HIP;
-            h->bar_count = 0;
+            h->bar_epochs = 0;
+    h->fused_grid = 0;
         }
         if (hipStreamSynchronize(st) != hipSuccess) return MTP_ERR_HIP;
     }

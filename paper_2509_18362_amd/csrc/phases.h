@@ -30,8 +30,10 @@ struct DraftParams {
     unsigned long long *keys; // [max_draft_steps][max_batch] packed (logit, index) maxima
     int *err;                 // sticky error word
     const double *rope_inv;   // [hd/2] rotary pair frequencies theta^(-2j/hd), computed on the host in double
-    unsigned long long *bar;  // grid-barrier arrival counter of the single-launch path (only ever grows)
-    unsigned long long bar_base; // its value when this launch starts
+    unsigned long long *bar;  // grid-barrier counters and flags of the single-launch path (they only ever grow)
+    unsigned long long bar_base; // barriers completed by earlier launches
+    unsigned long long *cand; // [max_draft_steps][max_batch][grid] per-workgroup argmax candidates (single launch)
+    int fused_gemv_bytes, fused_ids_bytes; // LDS carve-up of the single-launch kernel
     long long bar_timeout;    // wall-clock ticks a workgroup may wait at one barrier before giving up
     long long *trace;         // optional [K][16] wall-clock stamps (100 MHz) of workgroup 0 in the single-launch path
     int max_batch;
@@ -79,7 +81,7 @@ constexpr int kMaxNormIter = 4; // d <= 4 * 4 * kBlock = 8192
 // add1/add2 (float, optional) are added to the source element-wise first, in that order: the residual stream is
 // kept as its summands and put together where it is consumed.
 template <bool SRC_BF16>
-__device__ void stage_rmsnorm(const void *src, const uint16_t *gain, int d, float eps, uint16_t *hi, uint16_t *lo,
+__device__ __forceinline__ void stage_rmsnorm(const void *src, const uint16_t *gain, int d, float eps, uint16_t *hi, uint16_t *lo,
                               float *red, float *out_f32, float *out2_f32 = nullptr, const float *add1 = nullptr,
                               const float *add2 = nullptr) {
     float v[kMaxNormIter][4];
@@ -146,7 +148,7 @@ __device__ void stage_rmsnorm(const void *src, const uint16_t *gain, int d, floa
 }
 
 // plain copy of a float vector of length K (multiple of 4) into hi/lo, zero-padded to kpad
-__device__ void stage_plain(const float *src, int K, int kpad, uint16_t *hi, uint16_t *lo) {
+__device__ __forceinline__ void stage_plain(const float *src, int K, int kpad, uint16_t *hi, uint16_t *lo) {
     for (int e = threadIdx.x * 4; e < kpad; e += kBlock * 4) {
         u32x2 ph = {0u, 0u}, pl = {0u, 0u};
         if (e < K) {
@@ -179,143 +181,168 @@ __device__ __forceinline__ void lds_barrier() {
 
 // For rows [r0, r1) of NMAT matrices that share the input: out[mat][i][row] = sum_k W_mat[row][k] * act[i][k],
 // i < nb sequences.  The rows are cut into 16-row tiles; the 8 waves split the reduction range of each tile and
-// their partial sums meet in LDS.  Weight loads run one chunk (U MFMA k-steps) ahead of the MFMAs, across tile
-// boundaries, and the first chunk is requested before the activations are staged, so the HBM stream starts with
-// the phase and never drains inside it.  The inner loop is branch-free: out-of-range rows and k-steps re-read a
-// valid address and meet a zero activation operand instead of being predicated off.
+// their partial sums meet in LDS.  A wave's work is a sequence of chunks (tile, part of its k-range); one chunk is
+// eight 16-byte loads per lane = 8 KiB of weights.  A ring of kRingDepth chunks lives in registers: it is primed
+// before the activations exist (so HBM is busy while they are staged, or while a grid barrier completes) and a
+// slot is refilled as soon as its MFMAs have been issued, across tile boundaries.  The inner loop is branch-free:
+// a chunk is always read from inside its row (shifted left at the end of the row) and lanes whose elements belong
+// to another chunk, another wave or another sequence slot get a zero activation operand.
 //   rowptr(mat, row) -> const uint16_t* : start of a weight row (K bf16, 16-byte aligned, finite values)
-//   stage()                             : fills act_hi/act_lo (may use barriers); called once, after the first loads
 //   epi(i, row, sums[NMAT])             : called by one thread per (sequence, row)
-// LDS: act_hi/act_lo [nb][kpad] bf16 (kpad = K rounded up to 32, zero padded); partial [2][kWaves][NMAT][nbmax][16].
-template <int NMAT, int U, class RowPtr, class Stage, class Epi>
-__device__ void gemv_rows(RowPtr rowptr, int K, int r0, int r1, int nb, int nbmax, const uint16_t *act_hi,
-                          const uint16_t *act_lo, int kpad, float *partial, Stage stage, Epi &epi) {
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-    const int j = lane & 15, g = lane >> 4;
-    const int nks = (K + 31) / 32;
-    const int per = (nks + kWaves - 1) / kWaves;
-    const int ks0 = min(wave * per, nks), ks1 = min(ks0 + per, nks); // ks1 >= 1
-    const int nch = (per + U - 1) / U;
-    const int ntiles = (r1 - r0 + 15) / 16;
-    if (ntiles <= 0) { // nothing to compute; still take part in the staging barriers
-        stage();
-        return;
-    }
-    const u32x4 zero4 = {0u, 0u, 0u, 0u};
-    const int jact = min(j, nb - 1);
-    const bool jok = j < nb;
+// LDS: act_hi/act_lo [nb][kpad] bf16; partial [2][kWaves][NMAT][nbmax][16] float.
+constexpr int kRingDepth = 3;  // weight chunks in flight per wave (3 x 8 KiB)
+constexpr int kChunkLoads = 8; // 16-byte loads per lane per chunk
+struct Ring {
+    u32x4 b[kRingDepth][kChunkLoads];
+};
 
-    const uint16_t *base[NMAT];     // row start for the tile whose loads are being issued
-    const uint16_t *base_nxt[NMAT]; // ... and for the tile after it (fetched early: a gather reads an index first)
-    auto row_of = [&](int tile) { return min(r0 + tile * 16 + j, r1 - 1); };
+struct GemvGeom {
+    int K, r0, r1, ntiles, nks, ks0, ks1, nch, total; // total = ntiles * nch chunks for every wave of the workgroup
+    int j, g, wave;
+};
+
+template <int NMAT>
+__device__ __forceinline__ GemvGeom gemv_geom_rows(int K, int r0, int r1) {
+    constexpr int U = kChunkLoads / NMAT;
+    GemvGeom q;
+    const int lane = threadIdx.x & (kWave - 1);
+    q.wave = threadIdx.x / kWave;
+    q.j = lane & 15;
+    q.g = lane >> 4;
+    q.K = K;
+    q.r0 = r0;
+    q.r1 = r1;
+    q.nks = (K + 31) / 32;
+    const int per = (q.nks + kWaves - 1) / kWaves;
+    q.ks0 = min(q.wave * per, q.nks);
+    q.ks1 = min(q.ks0 + per, q.nks);
+    q.nch = (per + U - 1) / U;
+    q.ntiles = max((r1 - r0 + 15) / 16, 0);
+    q.total = q.ntiles * q.nch;
+    return q;
+}
+
+// request chunk (tile, ch) of this wave into buf: per matrix one base address and immediate offsets
+template <int NMAT, class RowPtr>
+__device__ __forceinline__ void gemv_issue(const GemvGeom &q, RowPtr rowptr, u32x4 (&buf)[kChunkLoads], int tile,
+                                           int ch) {
+    constexpr int U = kChunkLoads / NMAT;
+    const int row = min(q.r0 + tile * 16 + q.j, q.r1 - 1);
+    const int kstart = min((q.ks0 + ch * U) * 32, q.K - U * 32); // the chunk never leaves its row
 #pragma unroll
     for (int mt = 0; mt < NMAT; ++mt) {
-        base[mt] = rowptr(mt, row_of(0));
-        base_nxt[mt] = rowptr(mt, row_of(min(1, ntiles - 1)));
+        const uint16_t *base = rowptr(mt, row) + kstart + q.g * 8;
+#pragma unroll
+        for (int u = 0; u < U; ++u) buf[mt * U + u] = ldg16(base + u * 32);
     }
+}
 
-    auto load = [&](u32x4(&buf)[NMAT][U], int ch) {
+// fill the ring with the first kRingDepth chunks (fewer if the phase is shorter)
+template <int NMAT, class RowPtr>
+__device__ __forceinline__ void gemv_prime(const GemvGeom &q, RowPtr rowptr, Ring &ring) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            int ks = min(ks0 + ch * U + u, ks1 - 1);
-            int k = min(ks * 32 + g * 8, K - 8);
-#pragma unroll
-            for (int mt = 0; mt < NMAT; ++mt) buf[mt][u] = ldg16(base[mt] + k);
-        }
-    };
+    for (int s = 0; s < kRingDepth; ++s)
+        if (s < q.total) gemv_issue<NMAT>(q, rowptr, ring.b[s], s / q.nch, s % q.nch);
+}
 
+// consume the whole phase; the ring must have been primed and the activations staged
+template <int NMAT, class RowPtr, class Epi>
+__device__ __forceinline__ void gemv_run(const GemvGeom &q, RowPtr rowptr, Ring &ring, int nb, int nbmax,
+                                         const uint16_t *act_hi, const uint16_t *act_lo, int kpad, float *partial,
+                                         Epi &epi) {
+    constexpr int U = kChunkLoads / NMAT;
+    if (q.total <= 0) return;
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+    const int jact = min(q.j, nb - 1);
+    const bool jok = q.j < nb;
     f32x4 acc_h[NMAT], acc_l[NMAT];
-    auto clear = [&]() {
 #pragma unroll
-        for (int mt = 0; mt < NMAT; ++mt) {
-            acc_h[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-            acc_l[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-        }
-    };
-    clear();
-
-    auto compute = [&](u32x4(&buf)[NMAT][U], int ch) {
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            int ks = ks0 + ch * U + u;
-            bool ok = jok && ks < ks1;
-            int kse = min(ks, nks - 1);
-            u32x4 ah = *reinterpret_cast<const u32x4 *>(act_hi + (size_t)jact * kpad + kse * 32 + g * 8);
-            u32x4 al = *reinterpret_cast<const u32x4 *>(act_lo + (size_t)jact * kpad + kse * 32 + g * 8);
-            ah = ok ? ah : zero4;
-            al = ok ? al : zero4;
-#pragma unroll
-            for (int mt = 0; mt < NMAT; ++mt) {
-                acc_h[mt] = mfma16(ah, buf[mt][u], acc_h[mt]);
-                acc_l[mt] = mfma16(al, buf[mt][u], acc_l[mt]);
-            }
-        }
-    };
-
-    auto finish_tile = [&](int tile) {
-        float *pb = partial + (size_t)(tile & 1) * kWaves * NMAT * nbmax * 16;
-#pragma unroll
-        for (int mt = 0; mt < NMAT; ++mt) {
-            f32x4 s = acc_h[mt] + acc_l[mt];
-            float sv[4] = {s.x, s.y, s.z, s.w};
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                int i = g * 4 + v;
-                if (i < nb) pb[((wave * NMAT + mt) * nbmax + i) * 16 + j] = sv[v];
-            }
-        }
-        clear();
-        lds_barrier();
-        if ((int)threadIdx.x < 16 * nb) {
-            int i = threadIdx.x >> 4, jj = threadIdx.x & 15;
-            float sums[NMAT];
-#pragma unroll
-            for (int mt = 0; mt < NMAT; ++mt) {
-                float s = 0.f;
-#pragma unroll
-                for (int w = 0; w < kWaves; ++w) s += pb[((w * NMAT + mt) * nbmax + i) * 16 + jj];
-                sums[mt] = s;
-            }
-            int row = r0 + tile * 16 + jj;
-            if (row < r1) epi(i, row, sums);
-        }
-    };
-
-    u32x4 wb0[NMAT][U], wb1[NMAT][U];
-    int tile = 0, ch = 0;   // position of the compute stream
-    int ltile = 0, lch = 0; // position of the load stream
-    auto advance_load = [&]() { // move the load stream one chunk on; past the end it stays on the last chunk
-        if (++lch == nch) {
-            if (ltile + 1 < ntiles) {
-                lch = 0;
-                ++ltile;
-#pragma unroll
-                for (int mt = 0; mt < NMAT; ++mt) {
-                    base[mt] = base_nxt[mt];
-                    base_nxt[mt] = rowptr(mt, row_of(min(ltile + 1, ntiles - 1)));
-                }
-            } else {
-                lch = nch - 1;
-            }
-        }
-    };
-    auto step = [&](u32x4(&cur)[NMAT][U], u32x4(&nxt)[NMAT][U]) {
-        advance_load();
-        load(nxt, lch);
-        compute(cur, ch);
-        if (++ch == nch) {
-            finish_tile(tile);
-            ch = 0;
-            ++tile;
-        }
-    };
-    load(wb0, 0);
-    stage();
-    const int total = ntiles * nch;
-    for (int it = 0; it < total; it += 2) {
-        step(wb0, wb1);
-        if (it + 1 < total) step(wb1, wb0);
+    for (int mt = 0; mt < NMAT; ++mt) {
+        acc_h[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        acc_l[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
+    int ct = 0, cc = 0;                                   // chunk being consumed
+    int it = kRingDepth / q.nch, ic = kRingDepth % q.nch; // chunk to request next
+    for (int n0 = 0; n0 < q.total; n0 += kRingDepth) {
+#pragma unroll
+        for (int s = 0; s < kRingDepth; ++s) {
+            if (n0 + s < q.total) { // uniform
+                const int own_lo = (q.ks0 + cc * U) * 32;
+                const int own_hi = min(q.ks0 + (cc + 1) * U, q.ks1) * 32;
+                const int kstart = min(own_lo, q.K - U * 32);
+                const int e0 = kstart + q.g * 8;
+                const uint16_t *ah_p = act_hi + (size_t)jact * kpad + e0;
+                const uint16_t *al_p = act_lo + (size_t)jact * kpad + e0;
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const bool ok = jok && (e0 + u * 32 >= own_lo) && (e0 + u * 32 < own_hi);
+                    u32x4 ah = *reinterpret_cast<const u32x4 *>(ah_p + u * 32);
+                    u32x4 al = *reinterpret_cast<const u32x4 *>(al_p + u * 32);
+                    ah = ok ? ah : zero4;
+                    al = ok ? al : zero4;
+#pragma unroll
+                    for (int mt = 0; mt < NMAT; ++mt) {
+                        acc_h[mt] = mfma16(ah, ring.b[s][mt * U + u], acc_h[mt]);
+                        acc_l[mt] = mfma16(al, ring.b[s][mt * U + u], acc_l[mt]);
+                    }
+                    // keep the scheduler from hoisting all of the chunk's LDS reads (64 registers) above the MFMAs
+                    if (u % 2 == 1) __builtin_amdgcn_sched_barrier(0);
+                }
+                if (n0 + s + kRingDepth < q.total) { // the slot is free again: request the chunk kRingDepth ahead
+                    gemv_issue<NMAT>(q, rowptr, ring.b[s], it, ic);
+                    if (++ic == q.nch) {
+                        ic = 0;
+                        ++it;
+                    }
+                }
+                if (cc == q.nch - 1) { // tile complete: meet the other waves' partial sums in LDS
+                    float *pb = partial + (size_t)(ct & 1) * kWaves * NMAT * nbmax * 16;
+#pragma unroll
+                    for (int mt = 0; mt < NMAT; ++mt) {
+                        f32x4 sv = acc_h[mt] + acc_l[mt];
+                        float e[4] = {sv.x, sv.y, sv.z, sv.w};
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) {
+                            int i = q.g * 4 + v;
+                            if (i < nb) pb[((q.wave * NMAT + mt) * nbmax + i) * 16 + q.j] = e[v];
+                        }
+                        acc_h[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+                        acc_l[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    }
+                    lds_barrier();
+                    if ((int)threadIdx.x < 16 * nb) {
+                        int i = threadIdx.x >> 4, jj = threadIdx.x & 15;
+                        float sums[NMAT];
+#pragma unroll
+                        for (int mt = 0; mt < NMAT; ++mt) {
+                            float sacc = 0.f;
+#pragma unroll
+                            for (int w = 0; w < kWaves; ++w) sacc += pb[((w * NMAT + mt) * nbmax + i) * 16 + jj];
+                            sums[mt] = sacc;
+                        }
+                        int row = q.r0 + ct * 16 + jj;
+                        if (row < q.r1) epi(i, row, sums);
+                    }
+                    cc = 0;
+                    ++ct;
+                } else {
+                    ++cc;
+                }
+            }
+        }
+    }
+}
+
+// one pass of a phase launched on its own: request the first chunks, stage the activations, stream the rest
+template <int NMAT, int UNUSED, class RowPtr, class Stage, class Epi>
+__device__ __forceinline__ void gemv_rows(RowPtr rowptr, int K, int r0, int r1, int nb, int nbmax,
+                                          const uint16_t *act_hi, const uint16_t *act_lo, int kpad, float *partial,
+                                          Stage stage, Epi &epi) {
+    const GemvGeom q = gemv_geom_rows<NMAT>(K, r0, r1);
+    Ring ring;
+    gemv_prime<NMAT>(q, rowptr, ring);
+    stage(); // ends with a barrier: the activations are visible to every wave
+    gemv_run<NMAT>(q, rowptr, ring, nb, nbmax, act_hi, act_lo, kpad, partial, epi);
 }
 
 // carve-up of the dynamic LDS of a matrix-vector phase
@@ -846,107 +873,11 @@ __device__ void phase_finalize(const DraftParams &p, int vb) {
     }
 }
 
-// ---------------------------------------------------------------------------------------------------
-// single-launch path: all phases of all K steps in one cooperative kernel
-// ---------------------------------------------------------------------------------------------------
-// Grid-wide barrier on a counter that only grows: barrier number `epoch` (1-based within the launch) is passed
-// when the counter reaches bar_base + epoch * gridDim.x.  The release/acquire fences at agent scope make every
-// workgroup's global writes visible to every other workgroup (the XCDs' L2 caches are not coherent by themselves).
-// A workgroup that waits longer than bar_timeout ticks sets the sticky error word; from then on every barrier of
-// every workgroup falls through, so the grid always drains.
-__device__ __forceinline__ void grid_barrier(const DraftParams &p, unsigned &epoch) {
-    ++epoch;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const unsigned long long target = p.bar_base + (unsigned long long)epoch * gridDim.x;
-        __hip_atomic_fetch_add(p.bar, 1ull, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-        const long long t0 = wall_clock64();
-        unsigned spins = 0;
-        while (__hip_atomic_load(p.bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
-            if ((++spins & 63u) == 0) { // now and then: has anyone given up, or is it time to
-                if (__hip_atomic_load(p.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & kErrBarrierTimeout) break;
-                if (wall_clock64() - t0 > p.bar_timeout) {
-                    atomicOr(p.err, kErrBarrierTimeout);
-                    break;
-                }
-            }
-        }
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-    }
-    __syncthreads();
-}
-
-// Out-of-line copies of the phases: inlined together they would share one register budget and spill.
-__device__ __noinline__ void call_proj(const DraftParams &p, int step, int vb, int nvb, char *smem) {
-    phase_proj(p, step, vb, nvb, smem);
-}
-__device__ __noinline__ void call_qkv(const DraftParams &p, int step, int vb, int nvb, char *smem) {
-    phase_qkv(p, step, vb, nvb, smem);
-}
+// Out-of-line copy of the attention phase for the single-launch kernel: inlined next to the weight-streaming code
+// it would share one register budget with the prefetch ring and spill.
 template <int G, int HD>
 __device__ __noinline__ void call_attn(const DraftParams &p, int step, int vb, int nvb, char *smem) {
     phase_attn<G, HD>(p, step, vb, nvb, smem);
 }
-__device__ __noinline__ void call_oproj(const DraftParams &p, int step, int vb, int nvb, char *smem) {
-    phase_oproj(p, step, vb, nvb, smem);
-}
-__device__ __noinline__ void call_gateup(const DraftParams &p, int step, int vb, int nvb, char *smem) {
-    phase_gateup(p, step, vb, nvb, smem);
-}
-__device__ __noinline__ void call_down(const DraftParams &p, int step, int vb, int nvb, char *smem) {
-    phase_down(p, step, vb, nvb, smem);
-}
-__device__ __noinline__ void call_lmhead(const DraftParams &p, int step, int vb, int nvb, char *smem) {
-    phase_lmhead(p, step, vb, nvb, smem);
-}
-
-template <int G, int HD>
-__device__ void fused_steps(const DraftParams &p, char *smem) {
-    const int vb = blockIdx.x, nvb = gridDim.x;
-    unsigned epoch = 0;
-    int stamp_i = 0;
-    auto stamp = [&](int step) {
-        if (p.trace && vb == 0 && threadIdx.x == 0) p.trace[step * 16 + stamp_i] = wall_clock64();
-        ++stamp_i;
-    };
-    for (int step = 0; step < p.K; ++step) {
-        stamp_i = 0;
-        stamp(step);
-        call_proj(p, step, vb, nvb, smem);
-        stamp(step);
-        grid_barrier(p, epoch);
-        stamp(step);
-        call_qkv(p, step, vb, nvb, smem);
-        stamp(step);
-        grid_barrier(p, epoch);
-        stamp(step);
-        call_attn<G, HD>(p, step, vb, nvb, smem);
-        if (p.max_splits > 1) {
-            grid_barrier(p, epoch);
-            phase_attn_merge<HD>(p, step, vb, nvb, smem);
-        }
-        stamp(step);
-        grid_barrier(p, epoch);
-        stamp(step);
-        call_oproj(p, step, vb, nvb, smem);
-        stamp(step);
-        grid_barrier(p, epoch);
-        stamp(step);
-        call_gateup(p, step, vb, nvb, smem);
-        stamp(step);
-        grid_barrier(p, epoch);
-        stamp(step);
-        call_down(p, step, vb, nvb, smem);
-        stamp(step);
-        grid_barrier(p, epoch);
-        stamp(step);
-        call_lmhead(p, step, vb, nvb, smem);
-        stamp(step);
-        grid_barrier(p, epoch);
-        stamp(step);
-    }
-    phase_finalize(p, vb);
-}
-constexpr int kBarriersPerStep = 7; // one more per step when the attention is split (max_splits > 1)
 
 } // namespace mtp
