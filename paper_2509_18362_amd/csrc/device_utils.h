@@ -89,9 +89,16 @@ __device__ __forceinline__ f32x4 mfma16(u32x4 a, u32x4 b, f32x4 c) {
 }
 
 __device__ __forceinline__ u32x4 ldg16(const void *p) { return *reinterpret_cast<const u32x4 *>(p); }
-// streaming load: the data is used once, keep it from displacing reusable lines in the caches
-__device__ __forceinline__ u32x4 ldg16_stream(const void *p) {
-    return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+// Row-streaming loads through a buffer descriptor: the wave-uniform row start and length sit in four scalar
+// registers, the position inside the row in one more, and a single vector register (16 bytes per lane) serves every
+// load.  No vector registers are spent - or recycled, which stalls on loads still in flight - on 64-bit address
+// arithmetic, and an offset past the row's end would read zeros instead of faulting.
+typedef __amdgpu_buffer_rsrc_t row_rsrc;
+__device__ __forceinline__ row_rsrc make_row_rsrc(const uint16_t *uniform_row, int row_bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(uniform_row), 0, row_bytes, 0x00020000);
+}
+__device__ __forceinline__ u32x4 row_load16(row_rsrc r, int lane_byte_off, int uniform_byte_off) {
+    return __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(r, lane_byte_off, uniform_byte_off, 0));
 }
 
 } // namespace mtp

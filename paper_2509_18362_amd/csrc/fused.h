@@ -80,22 +80,6 @@ __device__ __forceinline__ GemvGeom gemv_geom(int K, int rows, int vb, int nvb) 
     return gemv_geom_rows<NMAT>(K, r0, r1);
 }
 
-// maximum of a 64-bit key over the workgroup; red64 holds kWaves words; contains two barriers
-__device__ __forceinline__ unsigned long long block_max_u64(unsigned long long v, unsigned long long *red64) {
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-        unsigned long long o = __shfl_xor(v, off, kWave);
-        v = o > v ? o : v;
-    }
-    __syncthreads();
-    if ((threadIdx.x & (kWave - 1)) == 0) red64[threadIdx.x / kWave] = v;
-    __syncthreads();
-    unsigned long long r = 0ull;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) r = red64[w] > r ? red64[w] : r;
-    return r;
-}
-
 // LDS of the single-launch path: the matrix-vector region (reused by the attention phases), then the id strip of
 // the compressed head, then small reduction scratch.
 __host__ __device__ inline size_t fused_gemv_region(int d, int qd, int F, int nb) {

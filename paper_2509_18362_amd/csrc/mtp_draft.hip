@@ -176,7 +176,7 @@ constexpr int kMaxFusedGrid = 1024; // workgroups of the single-launch kernel (o
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct WsLayout {
-    size_t x, qkv, attn, o, m, dn, hhat, keys, err, bar, cand, rope_inv, attn_part, total;
+    size_t x, qkv, attn, o, m, dn, hhat, err, bar, cand, rope_inv, attn_part, total;
 };
 WsLayout ws_layout(const mtp_config &c) {
     WsLayout l{};
@@ -195,7 +195,6 @@ WsLayout ws_layout(const mtp_config &c) {
     l.m = take(mb * (size_t)c.d_ffn * 4);
     l.dn = take(mb * d * 4);
     l.hhat = take(mb * d * 4);
-    l.keys = take((size_t)c.max_draft_steps * mb * 8);
     l.err = take(4);
     l.bar = take(kBarWords * 8);
     l.cand = take((size_t)c.max_draft_steps * mb * kMaxFusedGrid * 8);
@@ -418,7 +417,6 @@ int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_inde
     p.m = reinterpret_cast<float *>(ws + l.m);
     p.dn = reinterpret_cast<float *>(ws + l.dn);
     p.hhat = reinterpret_cast<float *>(ws + l.hhat);
-    p.keys = reinterpret_cast<unsigned long long *>(ws + l.keys);
     p.err = reinterpret_cast<int *>(ws + l.err);
     p.rope_inv = reinterpret_cast<const double *>(ws + l.rope_inv);
     p.attn_part = reinterpret_cast<float *>(ws + l.attn_part);
@@ -450,7 +448,9 @@ int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_inde
     const size_t lds_max = std::max({lds_proj, lds_d2, lds_q, lds_down, lds_attn});
     if (lds_max > h->lds_limit) return MTP_ERR_CONFIG;
 
-    const int grid = h->num_cus; // one 512-thread workgroup per CU: the register ring leaves no room for a second
+    const int grid = std::min(h->num_cus, kMaxFusedGrid); // one 512-thread workgroup per CU: the register ring
+                                                          // leaves no room for a second
+    p.head_grid = grid;
     const int attn_items = B * p.Hkv * p.max_splits;
     const int attn_grid = std::max(1, std::min(attn_items, h->num_cus * 2));
     const int merge_grid = std::max(1, std::min((B * p.Hq + kWaves - 1) / kWaves, h->num_cus));
@@ -466,6 +466,7 @@ int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_inde
         const size_t ids_bytes = ((size_t)(p.n + fgrid - 1) / fgrid * 4 + 255) / 256 * 256;
         const size_t lds_fused = region + ids_bytes + 256;
         if (B <= 16 && lds_fused <= h->lds_limit) {
+            p.head_grid = fgrid;
             p.fused_gemv_bytes = (int)region;
             p.fused_ids_bytes = (int)ids_bytes;
             if (h->fused_grid != fgrid) { // first use, or the grid changed: restart the barrier counters

@@ -27,12 +27,13 @@ struct DraftParams {
     float *logits_out, *hidden_out;
     // workspace
     float *x, *qkv, *attn, *o, *m, *dn, *hhat, *attn_part; // o = w_o attn, dn = w_down m (residuals added by consumers)
-    unsigned long long *keys; // [max_draft_steps][max_batch] packed (logit, index) maxima
     int *err;                 // sticky error word
     const double *rope_inv;   // [hd/2] rotary pair frequencies theta^(-2j/hd), computed on the host in double
     unsigned long long *bar;  // grid-barrier counters and flags of the single-launch path (they only ever grow)
     unsigned long long bar_base; // barriers completed by earlier launches
-    unsigned long long *cand; // [max_draft_steps][max_batch][grid] per-workgroup argmax candidates (single launch)
+    unsigned long long *cand; // [max_draft_steps][max_batch][head_grid] packed (logit, index) maximum of every
+                              // workgroup of the output-head phase; the consumer takes the maximum over them
+    int head_grid;            // workgroups of the output-head phase
     int fused_gemv_bytes, fused_ids_bytes; // LDS carve-up of the single-launch kernel
     long long bar_timeout;    // wall-clock ticks a workgroup may wait at one barrier before giving up
     long long *trace;         // optional [K][16] wall-clock stamps (100 MHz) of workgroup 0 in the single-launch path
@@ -52,23 +53,35 @@ __device__ __forceinline__ bool seq_dead(const DraftParams &p, int b) {
     return L < 0 || L + p.K > p.cap;
 }
 
-// token whose embedding enters step `step` (0-based) for sequence b; out-of-range ids are reported and replaced by 0
-__device__ __forceinline__ int step_token(const DraftParams &p, int b, int step) {
-    int tok;
-    if (step == 0)
-        tok = p.token_in[b];
-    else if (p.forced)
-        tok = p.forced[(size_t)b * (p.K - 1) + step - 1];
-    else {
-        uint32_t i = key_index(p.keys[(size_t)(step - 1) * p.max_batch + b]);
-        if (i >= (uint32_t)p.n) i = 0;
-        tok = p.ids ? p.ids[i] : (int)i;
+// maximum of a 64-bit key over the workgroup; red64 holds kWaves words; contains two barriers
+__device__ __forceinline__ unsigned long long block_max_u64(unsigned long long v, unsigned long long *red64) {
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        unsigned long long o = __shfl_xor(v, off, kWave);
+        v = o > v ? o : v;
     }
-    if (tok < 0 || tok >= p.V) {
-        atomicOr(p.err, kErrTokenRange);
-        tok = 0;
-    }
-    return tok;
+    __syncthreads();
+    if ((threadIdx.x & (kWave - 1)) == 0) red64[threadIdx.x / kWave] = v;
+    __syncthreads();
+    unsigned long long r = 0ull;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) r = red64[w] > r ? red64[w] : r;
+    return r;
+}
+
+// Winner of the output head of `step` for sequence b: maximum over the candidates the head's workgroups left behind
+// (larger logit first, then lower subset index).  Called by all threads of a workgroup; contains barriers.
+__device__ __forceinline__ unsigned long long winner_key(const DraftParams &p, int step, int b,
+                                                         unsigned long long *red64) {
+    const unsigned long long *cand = p.cand + ((size_t)step * p.max_batch + b) * p.head_grid;
+    unsigned long long best = 0ull;
+    for (int w = threadIdx.x; w < p.head_grid; w += kBlock) best = cand[w] > best ? cand[w] : best;
+    return block_max_u64(best, red64);
+}
+__device__ __forceinline__ int key_token(const DraftParams &p, unsigned long long key) {
+    uint32_t i = key_index(key);
+    if (i >= (uint32_t)p.n) i = 0;
+    return p.ids ? p.ids[i] : (int)i;
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -166,6 +179,13 @@ __device__ __forceinline__ void stage_plain(const float *src, int K, int kpad, u
         *reinterpret_cast<u32x2 *>(hi + e) = ph;
         *reinterpret_cast<u32x2 *>(lo + e) = pl;
     }
+}
+
+// rows [r0, r1) of workgroup vb when `rows` rows are dealt out as evenly as possible
+__device__ __forceinline__ void row_share(int rows, int vb, int nvb, int &r0, int &r1) {
+    int q = rows / nvb, rem = rows % nvb;
+    r0 = vb * q + min(vb, rem);
+    r1 = r0 + q + (vb < rem ? 1 : 0);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -345,6 +365,145 @@ __device__ __forceinline__ void gemv_rows(RowPtr rowptr, int K, int r0, int r1, 
     gemv_run<NMAT>(q, rowptr, ring, nb, nbmax, act_hi, act_lo, kpad, partial, epi);
 }
 
+// ---------------------------------------------------------------------------------------------------
+// row mode: the weight-streaming core for up to four sequences
+// ---------------------------------------------------------------------------------------------------
+// A wave owns whole weight rows and reads them front to back: every load instruction fetches 1 KiB of one row
+// (lane l gets elements [512 b + 8 l, 512 b + 8 l + 8) of 512-element block b), and the activations are read from
+// LDS in exactly the same lane order.  Fed to the 16x16x32 MFMA as they are, lane (i, g) of the A operand and lane
+// (j, g) of the B operand hold elements (16 g + i) 8 .. +8 and (16 g + j) 8 .. +8 of the block, so the DIAGONAL of
+// the 16x16 result holds sixteen partial dot products that together cover the block; accumulating over the blocks of
+// a row and summing the diagonal at the end of the row gives the row's dot product.  15/16 of the MFMA work is
+// thrown away, which is free here: the matrix cores idle at batch 1, while the vector ALUs (address arithmetic
+// only), the row-contiguous access pattern and the absence of any cross-wave reduction are what a bandwidth-bound
+// kernel wants.  Rows are dealt evenly to all waves of the grid, so phases whose row count is not a multiple of the
+// 16-row MFMA tile (q/k/v, gate/up) stay balanced.  One MFMA pair (hi, lo) per sequence per block.
+constexpr int kRowModeMaxSeq = 4;
+
+// NB: compile-time number of sequence slots (1, 2 or 4); slots at or beyond nb compute on a zero operand.  The
+// consume loop must stay straight-line code, or the compiler falls back to waiting for every outstanding load.
+template <int NMAT, int NB, class RowPtr, class Stage, class Epi>
+__device__ __forceinline__ void gemv_rowmode(RowPtr rowptr, int K, int rows, int vb, int nvb, int nb,
+                                             const uint16_t *act_hi, const uint16_t *act_lo, int kpad, Stage stage,
+                                             Epi &epi) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    // Rows are interleaved over all waves of the grid (row r belongs to wave r mod #waves): at any moment the grid
+    // reads a compact, advancing window of the matrix, like one linear sweep, instead of thousands of far-apart streams.
+    const int stride = nvb * kWaves;
+    const int wr0 = vb * kWaves + wave;
+    const int nrows = wr0 < rows ? (rows - wr0 + stride - 1) / stride : 0;
+    const int wr_last = wr0 + max(nrows - 1, 0) * stride;
+    const int nblk = (K + 511) / 512;                          // 512-element blocks per row (the last may overlap)
+    const int cpr = (nblk + kChunkLoads - 1) / kChunkLoads;    // chunks per (row, matrix): a chunk never straddles rows
+    const int nchunks = nrows * NMAT * cpr;                    // uniform per wave
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+
+    // load stream position: (row, matrix, chunk within the row); stays on the last chunk past the end
+    int l_row = wr0, l_mt = 0, l_c = 0;
+    auto issue_chunk = [&](u32x4(&buf)[kChunkLoads]) {
+        const row_rsrc rs = make_row_rsrc(rowptr(l_mt, min(l_row, wr_last)), K * 2); // uniform for the wave
+#pragma unroll
+        for (int u = 0; u < kChunkLoads; ++u) {
+            const int blk = min(l_c * kChunkLoads + u, nblk - 1); // empty slots of a row's last chunk re-read its last block
+            buf[u] = row_load16(rs, lane * 16, min(blk * 512, K - 512) * 2);
+        }
+        if (++l_c == cpr) {
+            l_c = 0;
+            if (++l_mt == NMAT) {
+                l_mt = 0;
+                l_row += stride;
+            }
+        }
+    };
+
+    Ring ring;
+#pragma unroll
+    for (int s = 0; s < kRingDepth; ++s)
+        if (s < nchunks) issue_chunk(ring.b[s]);
+    stage(); // ends with a barrier: the activations are visible to every wave
+    if (nchunks <= 0) return;
+
+    f32x4 acc_h[NB], acc_l[NB];
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+        acc_h[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+        acc_l[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    float sums[NB][NMAT];
+    const int dv = (lane & 15) - 4 * (lane >> 4); // which of this lane's four results lies on the diagonal, if any
+    int c_row = wr0, c_mt = 0, c_c = 0;
+    for (int n0 = 0; n0 < nchunks; n0 += kRingDepth) {
+#pragma unroll
+        for (int s = 0; s < kRingDepth; ++s) {
+            if (n0 + s < nchunks) { // uniform
+#pragma unroll
+                for (int u = 0; u < kChunkLoads; ++u) {
+                    const int blk = c_c * kChunkLoads + u;
+                    const int e0 = min(min(blk, nblk - 1) * 512, K - 512) + lane * 8;
+                    // slots past the row's last block contribute nothing; a last block that was shifted left to stay
+                    // inside the row only contributes the elements the block before it did not cover
+                    const bool own = blk < nblk && e0 >= blk * 512;
+#pragma unroll
+                    for (int i = 0; i < NB; ++i) {
+                        const int ia = min(i, nb - 1); // slots beyond nb re-read a valid row and are zeroed
+                        u32x4 ah = *reinterpret_cast<const u32x4 *>(act_hi + (size_t)ia * kpad + e0);
+                        u32x4 al = *reinterpret_cast<const u32x4 *>(act_lo + (size_t)ia * kpad + e0);
+                        const bool use = own && i < nb;
+                        ah = use ? ah : zero4;
+                        al = use ? al : zero4;
+                        acc_h[i] = mfma16(ah, ring.b[s][u], acc_h[i]);
+                        acc_l[i] = mfma16(al, ring.b[s][u], acc_l[i]);
+                    }
+                }
+                if (n0 + s + kRingDepth < nchunks) issue_chunk(ring.b[s]); // the slot is free again
+                if (++c_c == cpr) { // end of a row of matrix c_mt: sum the diagonal
+                    c_c = 0;
+#pragma unroll
+                    for (int i = 0; i < NB; ++i) {
+                        f32x4 t = acc_h[i] + acc_l[i];
+                        float v = dv == 0 ? t.x : dv == 1 ? t.y : dv == 2 ? t.z : dv == 3 ? t.w : 0.f;
+                        v = wave_sum(v);
+#pragma unroll
+                        for (int mt = 0; mt < NMAT; ++mt) sums[i][mt] = (mt == c_mt) ? v : sums[i][mt];
+                        acc_h[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+                        acc_l[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    }
+                    if (++c_mt == NMAT) {
+                        c_mt = 0;
+                        if (lane == 0) {
+#pragma unroll
+                            for (int i = 0; i < NB; ++i)
+                                if (i < nb) epi(i, c_row, sums[i]);
+                        }
+                        c_row += stride;
+                    }
+                }
+            }
+        }
+    }
+}
+
+__device__ __forceinline__ bool use_row_mode(int nb, int K) { return nb <= kRowModeMaxSeq && K >= 512; }
+
+// picks the core by batch chunk and reduction length (both uniform for the launch)
+template <int NMAT, class RowPtr, class Stage, class Epi>
+__device__ __forceinline__ void gemv_auto(RowPtr rowptr, int K, int rows, int vb, int nvb, int nb, int nbmax,
+                                          const uint16_t *act_hi, const uint16_t *act_lo, int kpad, float *partial,
+                                          Stage stage, Epi &epi) {
+    int r0, r1;
+    row_share(rows, vb, nvb, r0, r1); // tile mode: a contiguous share of the rows per workgroup
+    if (use_row_mode(nb, K)) {
+        if (nb == 1)
+            gemv_rowmode<NMAT, 1>(rowptr, K, rows, vb, nvb, nb, act_hi, act_lo, kpad, stage, epi);
+        else if (nb == 2)
+            gemv_rowmode<NMAT, 2>(rowptr, K, rows, vb, nvb, nb, act_hi, act_lo, kpad, stage, epi);
+        else
+            gemv_rowmode<NMAT, 4>(rowptr, K, rows, vb, nvb, nb, act_hi, act_lo, kpad, stage, epi);
+    } else
+        gemv_rows<NMAT, 0>(rowptr, K, r0, r1, nb, nbmax, act_hi, act_lo, kpad, partial, stage, epi);
+}
+
 // carve-up of the dynamic LDS of a matrix-vector phase
 struct GemvLds {
     uint16_t *hi, *lo;
@@ -365,30 +524,13 @@ __device__ inline GemvLds gemv_lds(char *smem, int K, int nb, int nmat) {
     return l;
 }
 
-// rows [r0, r1) of workgroup vb when `rows` rows are dealt out as evenly as possible
-__device__ __forceinline__ void row_share(int rows, int vb, int nvb, int &r0, int &r1) {
-    int q = rows / nvb, rem = rows % nvb;
-    r0 = vb * q + min(vb, rem);
-    r1 = r0 + q + (vb < rem ? 1 : 0);
-}
 
 // ---------------------------------------------------------------------------------------------------
 // phase 1: embedding gather + dual RMSNorm + concat + 2d->d projection   (steps 1-3 of the draft step)
 // ---------------------------------------------------------------------------------------------------
-__device__ void phase_proj(const DraftParams &p, int step, int vb, int nvb, char *smem) {
+__device__ __forceinline__ void phase_proj(const DraftParams &p, int step, int vb, int nvb, char *smem) {
     const int d = p.d;
-    int r0, r1;
-    row_share(d, vb, nvb, r0, r1);
-    if (vb == 0 && (int)threadIdx.x < p.B) {
-        int b = threadIdx.x;
-        p.keys[(size_t)step * p.max_batch + b] = 0ull; // this step's argmax accumulator
-        if (seq_dead(p, b)) atomicOr(p.err, kErrKvOverflow);
-        if (step > 0) { // the previous step's winner is final now
-            uint32_t i = key_index(p.keys[(size_t)(step - 1) * p.max_batch + b]);
-            if (i >= (uint32_t)p.n) i = 0;
-            p.draft_out[(size_t)b * p.K + step - 1] = seq_dead(p, b) ? -1 : (p.ids ? p.ids[i] : (int)i);
-        }
-    }
+    if (step == 0 && vb == 0 && (int)threadIdx.x < p.B && seq_dead(p, threadIdx.x)) atomicOr(p.err, kErrKvOverflow);
     const int nbmax = p.nb_proj;
     GemvLds l = gemv_lds(smem, 2 * d, nbmax, 1);
     for (int b0 = 0; b0 < p.B; b0 += nbmax) {
@@ -397,7 +539,19 @@ __device__ void phase_proj(const DraftParams &p, int step, int vb, int nvb, char
             __syncthreads();
             for (int i = 0; i < nb; ++i) {
                 int b = b0 + i;
-                int tok = step_token(p, b, step);
+                // x_1 is the verified token; afterwards the previous step's draft (or the forced token)
+                int tok;
+                if (step == 0) {
+                    tok = p.token_in[b];
+                } else {
+                    int did = key_token(p, winner_key(p, step - 1, b, reinterpret_cast<unsigned long long *>(l.red)));
+                    if (vb == 0 && threadIdx.x == 0) p.draft_out[(size_t)b * p.K + step - 1] = seq_dead(p, b) ? -1 : did;
+                    tok = p.forced ? p.forced[(size_t)b * (p.K - 1) + step - 1] : did;
+                }
+                if (tok < 0 || tok >= p.V) { // reported, and replaced by id 0 so that every access stays in bounds
+                    if (threadIdx.x == 0) atomicOr(p.err, kErrTokenRange);
+                    tok = 0;
+                }
                 uint16_t *hi = l.hi + (size_t)i * l.kpad, *lo = l.lo + (size_t)i * l.kpad;
                 if (step == 0)
                     stage_rmsnorm<true>(p.hidden_in + (size_t)b * d, p.g_h, d, p.eps, hi, lo, l.red, nullptr);
@@ -409,7 +563,7 @@ __device__ void phase_proj(const DraftParams &p, int step, int vb, int nvb, char
         };
         auto rowptr = [&](int, int row) { return p.w_proj + (size_t)row * 2 * d; };
         auto epi = [&](int i, int row, float(&s)[1]) { p.x[(size_t)(b0 + i) * d + row] = s[0]; };
-        gemv_rows<1, 8>(rowptr, 2 * d, r0, r1, nb, nbmax, l.hi, l.lo, l.kpad, l.partial, stage, epi);
+        gemv_auto<1>(rowptr, 2 * d, d, vb, nvb, nb, nbmax, l.hi, l.lo, l.kpad, l.partial, stage, epi);
     }
 }
 
@@ -417,10 +571,8 @@ __device__ void phase_proj(const DraftParams &p, int step, int vb, int nvb, char
 // phase 2: attention-input RMSNorm + fused QKV projection                  (step 4)
 // Bias, rotary embedding and the cache append happen where q, k, v are consumed (phase_attn).
 // ---------------------------------------------------------------------------------------------------
-__device__ void phase_qkv(const DraftParams &p, int step, int vb, int nvb, char *smem) {
+__device__ __forceinline__ void phase_qkv(const DraftParams &p, int step, int vb, int nvb, char *smem) {
     const int d = p.d, rows = p.qkv_dim;
-    int r0, r1;
-    row_share(rows, vb, nvb, r0, r1);
     const int nbmax = p.nb_d;
     GemvLds l = gemv_lds(smem, d, nbmax, 1);
     for (int b0 = 0; b0 < p.B; b0 += nbmax) {
@@ -439,7 +591,7 @@ __device__ void phase_qkv(const DraftParams &p, int step, int vb, int nvb, char 
         };
         // biases are added where q, k, v are consumed: the epilogue stays free of loads
         auto epi = [&](int i, int row, float(&s)[1]) { p.qkv[(size_t)(b0 + i) * rows + row] = s[0]; };
-        gemv_rows<1, 8>(rowptr, d, r0, r1, nb, nbmax, l.hi, l.lo, l.kpad, l.partial, stage, epi);
+        gemv_auto<1>(rowptr, d, rows, vb, nvb, nb, nbmax, l.hi, l.lo, l.kpad, l.partial, stage, epi);
     }
 }
 
@@ -739,10 +891,8 @@ __device__ void phase_attn_merge(const DraftParams &p, int step, int vb, int nvb
 // ---------------------------------------------------------------------------------------------------
 // phase 4: output projection (its residual add happens in the consumers)      (step 7)
 // ---------------------------------------------------------------------------------------------------
-__device__ void phase_oproj(const DraftParams &p, int, int vb, int nvb, char *smem) {
+__device__ __forceinline__ void phase_oproj(const DraftParams &p, int, int vb, int nvb, char *smem) {
     const int d = p.d, K = p.qd;
-    int r0, r1;
-    row_share(d, vb, nvb, r0, r1);
     const int nbmax = p.nb_q;
     GemvLds l = gemv_lds(smem, K, nbmax, 1);
     for (int b0 = 0; b0 < p.B; b0 += nbmax) {
@@ -756,17 +906,15 @@ __device__ void phase_oproj(const DraftParams &p, int, int vb, int nvb, char *sm
         };
         auto rowptr = [&](int, int row) { return p.w_o + (size_t)row * K; };
         auto epi = [&](int i, int row, float(&s)[1]) { p.o[(size_t)(b0 + i) * d + row] = s[0]; };
-        gemv_rows<1, 8>(rowptr, K, r0, r1, nb, nbmax, l.hi, l.lo, l.kpad, l.partial, stage, epi);
+        gemv_auto<1>(rowptr, K, d, vb, nvb, nb, nbmax, l.hi, l.lo, l.kpad, l.partial, stage, epi);
     }
 }
 
 // ---------------------------------------------------------------------------------------------------
 // phase 5: MLP-input RMSNorm + gate and up projections + SiLU(gate) * up       (step 8)
 // ---------------------------------------------------------------------------------------------------
-__device__ void phase_gateup(const DraftParams &p, int, int vb, int nvb, char *smem) {
+__device__ __forceinline__ void phase_gateup(const DraftParams &p, int, int vb, int nvb, char *smem) {
     const int d = p.d, F = p.F;
-    int r0, r1;
-    row_share(F, vb, nvb, r0, r1);
     const int nbmax = p.nb_d;
     GemvLds l = gemv_lds(smem, d, nbmax, 2);
     for (int b0 = 0; b0 < p.B; b0 += nbmax) {
@@ -784,17 +932,15 @@ __device__ void phase_gateup(const DraftParams &p, int, int vb, int nvb, char *s
             float gt = s[0];
             p.m[(size_t)(b0 + i) * F + row] = (gt / (1.0f + expf(-gt))) * s[1];
         };
-        gemv_rows<2, 4>(rowptr, d, r0, r1, nb, nbmax, l.hi, l.lo, l.kpad, l.partial, stage, epi);
+        gemv_auto<2>(rowptr, d, F, vb, nvb, nb, nbmax, l.hi, l.lo, l.kpad, l.partial, stage, epi);
     }
 }
 
 // ---------------------------------------------------------------------------------------------------
 // phase 6: down projection (its residual add happens in the consumer)         (step 9, first half)
 // ---------------------------------------------------------------------------------------------------
-__device__ void phase_down(const DraftParams &p, int, int vb, int nvb, char *smem) {
+__device__ __forceinline__ void phase_down(const DraftParams &p, int, int vb, int nvb, char *smem) {
     const int d = p.d, K = p.F;
-    int r0, r1;
-    row_share(d, vb, nvb, r0, r1);
     const int nbmax = p.nb_down;
     GemvLds l = gemv_lds(smem, K, nbmax, 1);
     for (int b0 = 0; b0 < p.B; b0 += nbmax) {
@@ -808,7 +954,7 @@ __device__ void phase_down(const DraftParams &p, int, int vb, int nvb, char *sme
         };
         auto rowptr = [&](int, int row) { return p.w_down + (size_t)row * K; };
         auto epi = [&](int i, int row, float(&s)[1]) { p.dn[(size_t)(b0 + i) * d + row] = s[0]; };
-        gemv_rows<1, 8>(rowptr, K, r0, r1, nb, nbmax, l.hi, l.lo, l.kpad, l.partial, stage, epi);
+        gemv_auto<1>(rowptr, K, d, vb, nvb, nb, nbmax, l.hi, l.lo, l.kpad, l.partial, stage, epi);
     }
 }
 
@@ -818,10 +964,8 @@ __device__ void phase_down(const DraftParams &p, int, int vb, int nvb, char *sme
 // Row i of the compressed head is lm_head[ids[i]]; rows are dealt out in subset order, so every workgroup scans a
 // contiguous, ascending range of subset indices.  Each reducing thread keeps the best (logit, index) it has seen;
 // the workgroup's winner per sequence goes into a 64-bit atomic max whose key orders by logit, then by lower index.
-__device__ void phase_lmhead(const DraftParams &p, int step, int vb, int nvb, char *smem) {
+__device__ __forceinline__ void phase_lmhead(const DraftParams &p, int step, int vb, int nvb, char *smem) {
     const int d = p.d, n = p.n;
-    int r0, r1;
-    row_share(n, vb, nvb, r0, r1);
     const int nbmax = p.nb_d;
     GemvLds l = gemv_lds(smem, d, nbmax, 1);
     for (int b0 = 0; b0 < p.B; b0 += nbmax) {
@@ -839,7 +983,12 @@ __device__ void phase_lmhead(const DraftParams &p, int step, int vb, int nvb, ch
             }
             __syncthreads();
         };
-        unsigned long long best = 0ull;
+        // best (logit, index) seen by this thread: in row mode lane 0 of a wave reports every sequence, in tile
+        // mode a thread reports one sequence only
+        const bool rowmode = use_row_mode(nb, d);
+        unsigned long long best[kRowModeMaxSeq];
+#pragma unroll
+        for (int i = 0; i < kRowModeMaxSeq; ++i) best[i] = 0ull;
         auto rowptr = [&](int, int row) {
             int r = p.ids ? p.ids[row] : row;
             return p.lm_head + (size_t)r * d;
@@ -847,29 +996,48 @@ __device__ void phase_lmhead(const DraftParams &p, int step, int vb, int nvb, ch
         auto epi = [&](int i, int row, float(&s)[1]) {
             if (p.logits_out) p.logits_out[((size_t)(b0 + i) * p.K + step) * n + row] = s[0];
             unsigned long long key = argmax_key(s[0], (uint32_t)row);
-            best = key > best ? key : best;
+#pragma unroll
+            for (int q = 0; q < kRowModeMaxSeq; ++q)
+                if (q == (rowmode ? i : 0)) best[q] = key > best[q] ? key : best[q];
         };
-        gemv_rows<1, 8>(rowptr, d, r0, r1, nb, nbmax, l.hi, l.lo, l.kpad, l.partial, stage, epi);
-        // threads 16*i .. 16*i+15 hold candidates of sequence i
-        if ((int)threadIdx.x < 16 * nb) {
+        gemv_auto<1>(rowptr, d, n, vb, nvb, nb, nbmax, l.hi, l.lo, l.kpad, l.partial, stage, epi);
+        unsigned long long *red64 = reinterpret_cast<unsigned long long *>(l.partial); // free again after the barrier
+        __syncthreads();
+        if (rowmode) {
+            if ((threadIdx.x & (kWave - 1)) == 0) {
+#pragma unroll
+                for (int i = 0; i < kRowModeMaxSeq; ++i) red64[(threadIdx.x / kWave) * kRowModeMaxSeq + i] = best[i];
+            }
+            __syncthreads();
+            if ((int)threadIdx.x < nb) {
+                unsigned long long m = 0ull;
+#pragma unroll
+                for (int w = 0; w < kWaves; ++w) {
+                    unsigned long long c = red64[w * kRowModeMaxSeq + threadIdx.x];
+                    m = c > m ? c : m;
+                }
+                p.cand[((size_t)step * p.max_batch + b0 + threadIdx.x) * p.head_grid + vb] = m;
+            }
+        } else if ((int)threadIdx.x < 16 * nb) { // threads 16*i .. 16*i+15 hold candidates of sequence i
+            unsigned long long m = best[0];
 #pragma unroll
             for (int off = 1; off < 16; off <<= 1) {
-                unsigned long long o = __shfl_xor(best, off, kWave);
-                best = o > best ? o : best;
+                unsigned long long o = __shfl_xor(m, off, kWave);
+                m = o > m ? o : m;
             }
-            if ((threadIdx.x & 15) == 0 && best != 0ull)
-                atomicMax(&p.keys[(size_t)step * p.max_batch + b0 + (threadIdx.x >> 4)], best);
+            if ((threadIdx.x & 15) == 0)
+                p.cand[((size_t)step * p.max_batch + b0 + (threadIdx.x >> 4)) * p.head_grid + vb] = m;
         }
     }
 }
 
-// after the last step: publish the last draft id
+// after the last step: publish the last draft id (one workgroup)
 __device__ void phase_finalize(const DraftParams &p, int vb) {
-    if (vb == 0 && (int)threadIdx.x < p.B) {
-        int b = threadIdx.x;
-        uint32_t i = key_index(p.keys[(size_t)(p.K - 1) * p.max_batch + b]);
-        if (i >= (uint32_t)p.n) i = 0;
-        p.draft_out[(size_t)b * p.K + p.K - 1] = seq_dead(p, b) ? -1 : (p.ids ? p.ids[i] : (int)i);
+    __shared__ unsigned long long red64[kWaves];
+    if (vb != 0) return;
+    for (int b = 0; b < p.B; ++b) {
+        int did = key_token(p, winner_key(p, p.K - 1, b, red64));
+        if (threadIdx.x == 0) p.draft_out[(size_t)b * p.K + p.K - 1] = seq_dead(p, b) ? -1 : did;
     }
 }
 
