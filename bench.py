@@ -22,6 +22,20 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+PMC_SUMMARY = os.path.join(ROOT, "profiles", "pmc_hbm_traffic_c2_7b_b1.md")
+
+
+def measured_traffic(kernel: str):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary (FETCH_SIZE and WRITE_SIZE, each
+    scaled by what the same counter reads for a copy of known size); None if the summary does not cover it."""
+    try:
+        for line in open(PMC_SUMMARY):
+            cells = [c.strip() for c in line.split("|")]
+            if len(cells) > 5 and cells[1] == kernel:
+                return float(cells[-2])
+    except OSError:
+        pass
+    return None
 
 
 def algorithmic_bytes_per_mtp_step(shape, n_rows: int, ctx, k_index: int, with_ids: bool) -> float:
@@ -44,6 +58,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full-vocab", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    ap.add_argument("--copy-calib", action="store_true",
+                    help="also run one plain 256 MiB device copy (a known-size reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding are part of it); "
@@ -100,6 +116,11 @@ def main() -> int:
         el = time.perf_counter() - t
         return el, float(acc.float().mean().item())
 
+    if args.copy_calib:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
     elapsed, mean_accept = timed(args.subset, args.steps, args.warmup)
     n_rows = eng.subset_size(args.subset)
     chain_bytes = sum(algorithmic_bytes_per_mtp_step(shape, n_rows, act["kv_len"], k, args.subset >= 0)
@@ -123,7 +144,8 @@ def main() -> int:
     head_bytes = 2.0 * n_rows * shape.d_model + (4.0 * n_rows if args.subset >= 0 else 0.0)
     roofline = {"bound": "hbm", "kernel": "k_lmhead", "achieved": head_bytes / (k_ms * 1e-3) / 1e9,
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": head_bytes / (k_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                "traffic": None, "bytes_per_launch": head_bytes, "avg_launch_us": k_ms * 1e3,
+                "traffic": measured_traffic("k_lmhead") if (args.workload == "c2_7b_b1" and args.subset == 0) else None,
+                "bytes_per_launch": head_bytes, "avg_launch_us": k_ms * 1e3,
                 "whole_path_achieved": path_gbs, "whole_path_frac": path_gbs / HBM_PEAK_GBS}
 
     full = None

@@ -210,6 +210,19 @@ def test_device_detected_errors(gpu, tiny):
     assert e.value.status == -6
 
 
+def test_single_launch_mode_matches_oracle(gpu, tiny):
+    """The cooperative single-launch path (grid barriers inside one kernel) against the oracle, ragged batch."""
+    torch, binding = gpu["torch"], gpu["binding"]
+    act = synth.make_activations(tiny["wl"], ctx=np.array([0, 130, 64], dtype=np.int32), capacity=192)
+    eng = binding.DraftEngine(tiny["shape"], tiny["w"], [tiny["ids"]], 3, 192, 3)
+    assert binding.mtp_set_launch_mode(eng.handle, binding.LAUNCH_SINGLE) == 0
+    for _ in range(2):  # twice: the barrier counters carry over from call to call
+        ref, res, caches = run_both(gpu, tiny["shape"], tiny["w"], tiny["w"], act, [tiny["ids"]], 0, 3, engine=eng)
+        check_chain(ref, res, caches, act["kv_len"], 3)
+    assert binding.mtp_set_launch_mode(eng.handle, 7) == -11
+    eng.close()
+
+
 # ------------------------------------------------------------------------------------------ accept / rollback
 @pytest.mark.parametrize("K", [1, 3, 5])
 @pytest.mark.parametrize("mode", [0, 1])
@@ -281,6 +294,13 @@ def test_7b_batch1_ctx2048(gpu, big):
     print("c2 max |dlogit| =", gap)
     ref, res, caches = run_both(gpu, big["shape"], big["w"], big["dev"], act, subsets, 0, wl.draft_steps, forced=None)
     check_chain(ref, res, caches, act["kv_len"], wl.draft_steps, aligned=False)
+    # the same through the single-launch path
+    binding = gpu["binding"]
+    eng = binding.DraftEngine(big["shape"], big["dev"], subsets, 1, act["kv_capacity"], wl.draft_steps)
+    assert binding.mtp_set_launch_mode(eng.handle, binding.LAUNCH_SINGLE) == 0
+    ref, res, caches = run_both(gpu, big["shape"], big["w"], big["dev"], act, subsets, 0, wl.draft_steps, engine=eng)
+    check_chain(ref, res, caches, act["kv_len"], wl.draft_steps)
+    eng.close()
 
 
 def test_7b_vocab_sweep_ctx8192(gpu, big):
