@@ -97,8 +97,13 @@ typedef __amdgpu_buffer_rsrc_t row_rsrc;
 __device__ __forceinline__ row_rsrc make_row_rsrc(const uint16_t *uniform_row, int row_bytes) {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(uniform_row), 0, row_bytes, 0x00020000);
 }
+// STREAM: non-temporal load.  Data read this way does not displace what sits in the 256 MB memory-side cache, so
+// a tensor read with plain loads (the output head) can stay there from one draft step to the next while the rest
+// of the weights stream by.
+template <bool STREAM>
 __device__ __forceinline__ u32x4 row_load16(row_rsrc r, int lane_byte_off, int uniform_byte_off) {
-    return __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(r, lane_byte_off, uniform_byte_off, 0));
+    return __builtin_bit_cast(
+        u32x4, __builtin_amdgcn_raw_buffer_load_b128(r, lane_byte_off, uniform_byte_off, STREAM ? 2 : 0));
 }
 
 } // namespace mtp

@@ -109,10 +109,10 @@ struct RpO {
     const DraftParams &p;
     __device__ __forceinline__ const uint16_t *operator()(int, int row) const { return p.w_o + (size_t)row * p.qd; }
 };
-struct RpGateUp {
+struct RpGateUp { // rows 0..F-1 are w_gate's, F..2F-1 w_up's
     const DraftParams &p;
-    __device__ __forceinline__ const uint16_t *operator()(int mt, int row) const {
-        return (mt == 0 ? p.w_gate : p.w_up) + (size_t)row * p.d;
+    __device__ __forceinline__ const uint16_t *operator()(int, int row) const {
+        return row < p.F ? p.w_gate + (size_t)row * p.d : p.w_up + (size_t)(row - p.F) * p.d;
     }
 };
 struct RpDown {
@@ -141,7 +141,7 @@ __device__ __forceinline__ void fused_prime(const DraftParams &p, Ring &ring, co
     } else if (PH == FP_O) {
         gemv_prime<1>(gemv_geom<1>(p.qd, p.d, vb, nvb), RpO{p}, ring);
     } else if (PH == FP_GATEUP) {
-        gemv_prime<2>(gemv_geom<2>(p.d, p.F, vb, nvb), RpGateUp{p}, ring);
+        gemv_prime<1>(gemv_geom<1>(p.d, 2 * p.F, vb, nvb), RpGateUp{p}, ring);
     } else if (PH == FP_DOWN) {
         gemv_prime<1>(gemv_geom<1>(p.F, p.d, vb, nvb), RpDown{p}, ring);
     } else {
@@ -265,17 +265,14 @@ __device__ __forceinline__ void fused_steps2(const DraftParams &p, char *smem) {
         stamp(step);
         // ---- gate / up ---------------------------------------------------------------------------------------
         {
-            GemvLds l = gemv_lds(gemv_smem, d, nbmax, 2);
+            GemvLds l = gemv_lds(gemv_smem, d, nbmax, 1);
             for (int i = 0; i < nb; ++i)
                 stage_rmsnorm<false>(p.x + (size_t)i * d, p.g_mlp, d, p.eps, l.hi + (size_t)i * l.kpad,
                                      l.lo + (size_t)i * l.kpad, l.red, nullptr, nullptr, p.o + (size_t)i * d);
             __syncthreads();
-            auto epi = [&](int i, int row, float(&s)[2]) {
-                float gt = s[0];
-                p.m[(size_t)i * p.F + row] = (gt / (1.0f + expf(-gt))) * s[1];
-            };
-            gemv_run<2>(gemv_geom<2>(d, p.F, vb, nvb), RpGateUp{p}, ring, nb, nbmax, l.hi, l.lo, l.kpad, l.partial,
-                        epi);
+            auto epi = [&](int i, int row, float(&s)[1]) { p.gu[(size_t)i * 2 * p.F + row] = s[0]; };
+            gemv_run<1>(gemv_geom<1>(d, 2 * p.F, vb, nvb), RpGateUp{p}, ring, nb, nbmax, l.hi, l.lo, l.kpad,
+                        l.partial, epi);
         }
         stamp(step);
         bar_arrive(p, ++epoch);
@@ -287,7 +284,8 @@ __device__ __forceinline__ void fused_steps2(const DraftParams &p, char *smem) {
             GemvLds l = gemv_lds(gemv_smem, p.F, nbmax, 1);
             __syncthreads();
             for (int i = 0; i < nb; ++i)
-                stage_plain(p.m + (size_t)i * p.F, p.F, l.kpad, l.hi + (size_t)i * l.kpad, l.lo + (size_t)i * l.kpad);
+                stage_swiglu(p.gu + (size_t)i * 2 * p.F, p.F, l.kpad, l.hi + (size_t)i * l.kpad,
+                             l.lo + (size_t)i * l.kpad);
             __syncthreads();
             auto epi = [&](int i, int row, float(&s)[1]) { p.dn[(size_t)i * d + row] = s[0]; };
             gemv_run<1>(gemv_geom<1>(p.F, d, vb, nvb), RpDown{p}, ring, nb, nbmax, l.hi, l.lo, l.kpad, l.partial,

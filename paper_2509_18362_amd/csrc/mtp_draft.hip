@@ -176,7 +176,7 @@ constexpr int kMaxFusedGrid = 1024; // workgroups of the single-launch kernel (o
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct WsLayout {
-    size_t x, qkv, attn, o, m, dn, hhat, err, bar, cand, rope_inv, attn_part, total;
+    size_t x, qkv, attn, o, gu, dn, hhat, err, bar, cand, rope_inv, attn_part, total;
 };
 WsLayout ws_layout(const mtp_config &c) {
     WsLayout l{};
@@ -192,7 +192,7 @@ WsLayout ws_layout(const mtp_config &c) {
     l.qkv = take(mb * (qd + 2 * kvd) * 4);
     l.attn = take(mb * qd * 4);
     l.o = take(mb * d * 4);
-    l.m = take(mb * (size_t)c.d_ffn * 4);
+    l.gu = take(mb * (size_t)c.d_ffn * 2 * 4);
     l.dn = take(mb * d * 4);
     l.hhat = take(mb * d * 4);
     l.err = take(4);
@@ -414,7 +414,7 @@ int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_inde
     p.qkv = reinterpret_cast<float *>(ws + l.qkv);
     p.attn = reinterpret_cast<float *>(ws + l.attn);
     p.o = reinterpret_cast<float *>(ws + l.o);
-    p.m = reinterpret_cast<float *>(ws + l.m);
+    p.gu = reinterpret_cast<float *>(ws + l.gu);
     p.dn = reinterpret_cast<float *>(ws + l.dn);
     p.hhat = reinterpret_cast<float *>(ws + l.hhat);
     p.err = reinterpret_cast<int *>(ws + l.err);

@@ -26,7 +26,8 @@ struct DraftParams {
     int *draft_out;
     float *logits_out, *hidden_out;
     // workspace
-    float *x, *qkv, *attn, *o, *m, *dn, *hhat, *attn_part; // o = w_o attn, dn = w_down m (residuals added by consumers)
+    float *x, *qkv, *attn, *o, *gu, *dn, *hhat, *attn_part; // o = w_o attn, gu = [w_gate y2; w_up y2], dn = w_down m
+                                                            // (residuals and SiLU*mul are applied by the consumers)
     int *err;                 // sticky error word
     const double *rope_inv;   // [hd/2] rotary pair frequencies theta^(-2j/hd), computed on the host in double
     unsigned long long *bar;  // grid-barrier counters and flags of the single-launch path (they only ever grow)
@@ -171,6 +172,29 @@ __device__ __forceinline__ void stage_plain(const float *src, int K, int kpad, u
             split_bf16(raw.y, h[1], l[1]);
             split_bf16(raw.z, h[2], l[2]);
             split_bf16(raw.w, h[3], l[3]);
+            ph.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
+            ph.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
+            pl.x = (uint32_t)l[0] | ((uint32_t)l[1] << 16);
+            pl.y = (uint32_t)l[2] | ((uint32_t)l[3] << 16);
+        }
+        *reinterpret_cast<u32x2 *>(hi + e) = ph;
+        *reinterpret_cast<u32x2 *>(lo + e) = pl;
+    }
+}
+
+// m = silu(g) * u from the gate/up projection output gu = [g (F floats); u (F floats)], silu(z) = z / (1 + exp(-z)),
+// into hi/lo, zero-padded to kpad
+__device__ __forceinline__ void stage_swiglu(const float *gu, int F, int kpad, uint16_t *hi, uint16_t *lo) {
+    for (int e = threadIdx.x * 4; e < kpad; e += kBlock * 4) {
+        u32x2 ph = {0u, 0u}, pl = {0u, 0u};
+        if (e < F) {
+            f32x4 g = *reinterpret_cast<const f32x4 *>(gu + e);
+            f32x4 u = *reinterpret_cast<const f32x4 *>(gu + F + e);
+            float m[4] = {(g.x / (1.0f + expf(-g.x))) * u.x, (g.y / (1.0f + expf(-g.y))) * u.y,
+                          (g.z / (1.0f + expf(-g.z))) * u.z, (g.w / (1.0f + expf(-g.w))) * u.w};
+            uint16_t h[4], l[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) split_bf16(m[q], h[q], l[q]);
             ph.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
             ph.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
             pl.x = (uint32_t)l[0] | ((uint32_t)l[1] << 16);
@@ -382,7 +406,7 @@ constexpr int kRowModeMaxSeq = 4;
 
 // NB: compile-time number of sequence slots (1, 2 or 4); slots at or beyond nb compute on a zero operand.  The
 // consume loop must stay straight-line code, or the compiler falls back to waiting for every outstanding load.
-template <int NMAT, int NB, class RowPtr, class Stage, class Epi>
+template <int NMAT, int NB, bool STREAM, class RowPtr, class Stage, class Epi>
 __device__ __forceinline__ void gemv_rowmode(RowPtr rowptr, int K, int rows, int vb, int nvb, int nb,
                                              const uint16_t *act_hi, const uint16_t *act_lo, int kpad, Stage stage,
                                              Epi &epi) {
@@ -406,7 +430,7 @@ __device__ __forceinline__ void gemv_rowmode(RowPtr rowptr, int K, int rows, int
 #pragma unroll
         for (int u = 0; u < kChunkLoads; ++u) {
             const int blk = min(l_c * kChunkLoads + u, nblk - 1); // empty slots of a row's last chunk re-read its last block
-            buf[u] = row_load16(rs, lane * 16, min(blk * 512, K - 512) * 2);
+            buf[u] = row_load16<STREAM>(rs, lane * 16, min(blk * 512, K - 512) * 2);
         }
         if (++l_c == cpr) {
             l_c = 0;
@@ -487,7 +511,7 @@ __device__ __forceinline__ void gemv_rowmode(RowPtr rowptr, int K, int rows, int
 __device__ __forceinline__ bool use_row_mode(int nb, int K) { return nb <= kRowModeMaxSeq && K >= 512; }
 
 // picks the core by batch chunk and reduction length (both uniform for the launch)
-template <int NMAT, class RowPtr, class Stage, class Epi>
+template <int NMAT, bool STREAM, class RowPtr, class Stage, class Epi>
 __device__ __forceinline__ void gemv_auto(RowPtr rowptr, int K, int rows, int vb, int nvb, int nb, int nbmax,
                                           const uint16_t *act_hi, const uint16_t *act_lo, int kpad, float *partial,
                                           Stage stage, Epi &epi) {
@@ -495,11 +519,11 @@ __device__ __forceinline__ void gemv_auto(RowPtr rowptr, int K, int rows, int vb
     row_share(rows, vb, nvb, r0, r1); // tile mode: a contiguous share of the rows per workgroup
     if (use_row_mode(nb, K)) {
         if (nb == 1)
-            gemv_rowmode<NMAT, 1>(rowptr, K, rows, vb, nvb, nb, act_hi, act_lo, kpad, stage, epi);
+            gemv_rowmode<NMAT, 1, STREAM>(rowptr, K, rows, vb, nvb, nb, act_hi, act_lo, kpad, stage, epi);
         else if (nb == 2)
-            gemv_rowmode<NMAT, 2>(rowptr, K, rows, vb, nvb, nb, act_hi, act_lo, kpad, stage, epi);
+            gemv_rowmode<NMAT, 2, STREAM>(rowptr, K, rows, vb, nvb, nb, act_hi, act_lo, kpad, stage, epi);
         else
-            gemv_rowmode<NMAT, 4>(rowptr, K, rows, vb, nvb, nb, act_hi, act_lo, kpad, stage, epi);
+            gemv_rowmode<NMAT, 4, STREAM>(rowptr, K, rows, vb, nvb, nb, act_hi, act_lo, kpad, stage, epi);
     } else
         gemv_rows<NMAT, 0>(rowptr, K, r0, r1, nb, nbmax, act_hi, act_lo, kpad, partial, stage, epi);
 }
@@ -563,7 +587,7 @@ __device__ __forceinline__ void phase_proj(const DraftParams &p, int step, int v
         };
         auto rowptr = [&](int, int row) { return p.w_proj + (size_t)row * 2 * d; };
         auto epi = [&](int i, int row, float(&s)[1]) { p.x[(size_t)(b0 + i) * d + row] = s[0]; };
-        gemv_auto<1>(rowptr, 2 * d, d, vb, nvb, nb, nbmax, l.hi, l.lo, l.kpad, l.partial, stage, epi);
+        gemv_auto<1, true>(rowptr, 2 * d, d, vb, nvb, nb, nbmax, l.hi, l.lo, l.kpad, l.partial, stage, epi);
     }
 }
 
@@ -591,7 +615,7 @@ __device__ __forceinline__ void phase_qkv(const DraftParams &p, int step, int vb
         };
         // biases are added where q, k, v are consumed: the epilogue stays free of loads
         auto epi = [&](int i, int row, float(&s)[1]) { p.qkv[(size_t)(b0 + i) * rows + row] = s[0]; };
-        gemv_auto<1>(rowptr, d, rows, vb, nvb, nb, nbmax, l.hi, l.lo, l.kpad, l.partial, stage, epi);
+        gemv_auto<1, true>(rowptr, d, rows, vb, nvb, nb, nbmax, l.hi, l.lo, l.kpad, l.partial, stage, epi);
     }
 }
 
@@ -906,17 +930,17 @@ __device__ __forceinline__ void phase_oproj(const DraftParams &p, int, int vb, i
         };
         auto rowptr = [&](int, int row) { return p.w_o + (size_t)row * K; };
         auto epi = [&](int i, int row, float(&s)[1]) { p.o[(size_t)(b0 + i) * d + row] = s[0]; };
-        gemv_auto<1>(rowptr, K, d, vb, nvb, nb, nbmax, l.hi, l.lo, l.kpad, l.partial, stage, epi);
+        gemv_auto<1, true>(rowptr, K, d, vb, nvb, nb, nbmax, l.hi, l.lo, l.kpad, l.partial, stage, epi);
     }
 }
 
 // ---------------------------------------------------------------------------------------------------
-// phase 5: MLP-input RMSNorm + gate and up projections + SiLU(gate) * up       (step 8)
+// phase 5: MLP-input RMSNorm + gate and up projections (SiLU(gate) * up is formed by the consumer)   (step 8)
 // ---------------------------------------------------------------------------------------------------
 __device__ __forceinline__ void phase_gateup(const DraftParams &p, int, int vb, int nvb, char *smem) {
     const int d = p.d, F = p.F;
     const int nbmax = p.nb_d;
-    GemvLds l = gemv_lds(smem, d, nbmax, 2);
+    GemvLds l = gemv_lds(smem, d, nbmax, 1);
     for (int b0 = 0; b0 < p.B; b0 += nbmax) {
         int nb = min(nbmax, p.B - b0);
         auto stage = [&]() {
@@ -927,17 +951,16 @@ __device__ __forceinline__ void phase_gateup(const DraftParams &p, int, int vb, 
                                      p.o + (size_t)(b0 + i) * d); // x1 = x + w_o attn
             __syncthreads();
         };
-        auto rowptr = [&](int mt, int row) { return (mt == 0 ? p.w_gate : p.w_up) + (size_t)row * d; };
-        auto epi = [&](int i, int row, float(&s)[2]) {
-            float gt = s[0];
-            p.m[(size_t)(b0 + i) * F + row] = (gt / (1.0f + expf(-gt))) * s[1];
-        };
-        gemv_auto<2>(rowptr, d, F, vb, nvb, nb, nbmax, l.hi, l.lo, l.kpad, l.partial, stage, epi);
+        // the 2F rows of [w_gate; w_up] are dealt out as one list: the two halves of a SwiGLU pair need not meet
+        // here (the consumer multiplies them), which keeps every wave within one row of the average load
+        auto rowptr = [&](int, int row) { return row < F ? p.w_gate + (size_t)row * d : p.w_up + (size_t)(row - F) * d; };
+        auto epi = [&](int i, int row, float(&s)[1]) { p.gu[(size_t)(b0 + i) * 2 * F + row] = s[0]; };
+        gemv_auto<1, true>(rowptr, d, 2 * F, vb, nvb, nb, nbmax, l.hi, l.lo, l.kpad, l.partial, stage, epi);
     }
 }
 
 // ---------------------------------------------------------------------------------------------------
-// phase 6: down projection (its residual add happens in the consumer)         (step 9, first half)
+// phase 6: SiLU(gate) * up, down projection (its residual add happens in the consumer)   (steps 8-9)
 // ---------------------------------------------------------------------------------------------------
 __device__ __forceinline__ void phase_down(const DraftParams &p, int, int vb, int nvb, char *smem) {
     const int d = p.d, K = p.F;
@@ -948,13 +971,13 @@ __device__ __forceinline__ void phase_down(const DraftParams &p, int, int vb, in
         auto stage = [&]() {
             __syncthreads();
             for (int i = 0; i < nb; ++i)
-                stage_plain(p.m + (size_t)(b0 + i) * K, K, l.kpad, l.hi + (size_t)i * l.kpad,
-                            l.lo + (size_t)i * l.kpad);
+                stage_swiglu(p.gu + (size_t)(b0 + i) * 2 * K, K, l.kpad, l.hi + (size_t)i * l.kpad,
+                             l.lo + (size_t)i * l.kpad); // m = silu(w_gate y2) * (w_up y2)
             __syncthreads();
         };
         auto rowptr = [&](int, int row) { return p.w_down + (size_t)row * K; };
         auto epi = [&](int i, int row, float(&s)[1]) { p.dn[(size_t)(b0 + i) * d + row] = s[0]; };
-        gemv_auto<1>(rowptr, K, d, vb, nvb, nb, nbmax, l.hi, l.lo, l.kpad, l.partial, stage, epi);
+        gemv_auto<1, true>(rowptr, K, d, vb, nvb, nb, nbmax, l.hi, l.lo, l.kpad, l.partial, stage, epi);
     }
 }
 
@@ -1000,7 +1023,7 @@ __device__ __forceinline__ void phase_lmhead(const DraftParams &p, int step, int
             for (int q = 0; q < kRowModeMaxSeq; ++q)
                 if (q == (rowmode ? i : 0)) best[q] = key > best[q] ? key : best[q];
         };
-        gemv_auto<1>(rowptr, d, n, vb, nvb, nb, nbmax, l.hi, l.lo, l.kpad, l.partial, stage, epi);
+        gemv_auto<1, false>(rowptr, d, n, vb, nvb, nb, nbmax, l.hi, l.lo, l.kpad, l.partial, stage, epi);
         unsigned long long *red64 = reinterpret_cast<unsigned long long *>(l.partial); // free again after the barrier
         __syncthreads();
         if (rowmode) {
