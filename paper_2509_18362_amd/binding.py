@@ -10,6 +10,11 @@ import ctypes as C
 import os
 from typing import Dict, Optional, Sequence
 
+# PyTorch first: it ships its own copy of the HIP runtime and loads it by path.  Loaded afterwards, this library's
+# dependency on the runtime resolves to that copy; loaded before it, the system's copy would come in as a second
+# runtime in the same process, which then finds no device.
+import torch  # noqa: F401  (isort: keep above the CDLL call)
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmtp_draft.so")
 

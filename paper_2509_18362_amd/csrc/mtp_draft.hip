@@ -55,7 +55,7 @@ __global__ __launch_bounds__(kBlock) void k_lmhead(DraftParams p, int step) {
     extern __shared__ __align__(16) char smem[];
     phase_lmhead(p, step, blockIdx.x, gridDim.x, smem);
 }
-__global__ void k_finalize(DraftParams p) { phase_finalize(p, blockIdx.x); }
+__global__ void k_finalize(DraftParams p) { phase_finalize(p, blockIdx.x, gridDim.x); }
 template <int G, int HD>
 __global__ __launch_bounds__(kBlock) void k_fused(DraftParams) {
     extern __shared__ __align__(16) char smem[];
@@ -284,8 +284,12 @@ int32_t mtp_draft_init(mtp_handle **out, const mtp_config *cfg, const mtp_weight
         int n = subset_sizes[s];
         if (n < 1 || n > cfg->vocab_size) return MTP_ERR_SUBSET;
         host.resize(n);
-        if (hipMemcpy(host.data(), subset_ids[s], (size_t)n * 4, hipMemcpyDeviceToHost) != hipSuccess)
+        hipError_t e = hipMemcpy(host.data(), subset_ids[s], (size_t)n * 4, hipMemcpyDeviceToHost);
+        if (e != hipSuccess) {
+            fprintf(stderr, "mtp_draft_init: reading subset %d failed: %s\n", s, hipGetErrorString(e));
+            (void)hipGetLastError();
             return MTP_ERR_HIP;
+        }
         if (host[0] < 0 || host[n - 1] >= cfg->vocab_size) return MTP_ERR_SUBSET;
         for (int i = 1; i < n; ++i)
             if (host[i] <= host[i - 1]) return MTP_ERR_SUBSET;
@@ -305,13 +309,23 @@ int32_t mtp_draft_init(mtp_handle **out, const mtp_config *cfg, const mtp_weight
     h->ev_recorded = false;
     h->pev_used = 0;
     int dev = 0, cus = 0, lds = 0;
-    bool ok = hipGetDevice(&dev) == hipSuccess &&
-              hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
-              hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) == hipSuccess;
-    ok = ok && hipEventCreate(&h->ev[0]) == hipSuccess && hipEventCreate(&h->ev[1]) == hipSuccess;
+    bool ok = true;
+    // the first HIP call that fails is named on stderr; the calls after it are skipped
+    auto run = [&](hipError_t e, const char *what) {
+        if (ok && e != hipSuccess) {
+            fprintf(stderr, "mtp_draft_init: %s failed: %s\n", what, hipGetErrorString(e));
+            ok = false;
+        }
+    };
+    run(hipGetDevice(&dev), "hipGetDevice");
+    if (ok) run(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev), "CU count query");
+    if (ok) run(hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev), "LDS size query");
+    if (ok) run(hipEventCreate(&h->ev[0]), "hipEventCreate");
+    if (ok) run(hipEventCreate(&h->ev[1]), "hipEventCreate");
     if (ok) {
         h->pev.resize(2 * (size_t)cfg->max_draft_steps);
-        for (auto &e : h->pev) ok = ok && hipEventCreate(&e) == hipSuccess;
+        for (auto &e : h->pev)
+            if (ok) run(hipEventCreate(&e), "hipEventCreate");
     }
     h->num_cus = cus;
     h->lds_limit = (size_t)lds;
@@ -322,22 +336,30 @@ int32_t mtp_draft_init(mtp_handle **out, const mtp_config *cfg, const mtp_weight
     h->bar_epochs = 0;
     h->fused_grid = 0;
     h->trace = nullptr;
-    ok = ok && h->attn_fn != nullptr && h->fused_fn != nullptr;
+    if (ok && (h->attn_fn == nullptr || h->fused_fn == nullptr)) {
+        fprintf(stderr, "mtp_draft_init: no kernel for this head geometry\n");
+        ok = false;
+    }
     // allow the large-LDS launches
-    const void *fns[] = {(const void *)k_proj, (const void *)k_qkv, (const void *)k_oproj, (const void *)k_gateup,
-                         (const void *)k_down, (const void *)k_lmhead, (const void *)h->attn_fn, (const void *)h->merge_fn,
-                         (const void *)h->fused_fn};
-    for (const void *f : fns)
-        ok = ok && hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)h->lds_limit) == hipSuccess;
-    ok = ok && hipMemset(workspace, 0, lay.total) == hipSuccess;
-    {
+    const struct {
+        const void *fn;
+        const char *name;
+    } fns[] = {{(const void *)k_proj, "k_proj"},         {(const void *)k_qkv, "k_qkv"},
+               {(const void *)k_oproj, "k_oproj"},       {(const void *)k_gateup, "k_gateup"},
+               {(const void *)k_down, "k_down"},         {(const void *)k_lmhead, "k_lmhead"},
+               {(const void *)h->attn_fn, "k_attn"},     {(const void *)h->merge_fn, "k_attn_merge"},
+               {(const void *)h->fused_fn, "k_fused"}};
+    for (const auto &f : fns)
+        if (ok) run(hipFuncSetAttribute(f.fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)h->lds_limit), f.name);
+    if (ok) run(hipMemset(workspace, 0, lay.total), "workspace clear");
+    if (ok) {
         std::vector<double> inv((size_t)cfg->head_dim / 2);
         for (size_t j = 0; j < inv.size(); ++j)
             inv[j] = std::pow((double)cfg->rope_theta, -2.0 * (double)j / (double)cfg->head_dim);
-        ok = ok && hipMemcpy(static_cast<char *>(workspace) + lay.rope_inv, inv.data(), inv.size() * 8,
-                             hipMemcpyHostToDevice) == hipSuccess;
+        run(hipMemcpy(static_cast<char *>(workspace) + lay.rope_inv, inv.data(), inv.size() * 8, hipMemcpyHostToDevice),
+            "rope table upload");
     }
-    ok = ok && hipDeviceSynchronize() == hipSuccess;
+    if (ok) run(hipDeviceSynchronize(), "hipDeviceSynchronize");
     if (!ok) {
         (void)hipGetLastError();
         delete h;
@@ -509,7 +531,7 @@ int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_inde
         launch(PH_DOWN, k_down, grid, lds_down, step);
         launch(PH_LMHEAD, k_lmhead, grid, lds_d1, step);
     }
-    hipLaunchKernelGGL(k_finalize, dim3(1), dim3(kBlock), 0, st, p);
+    hipLaunchKernelGGL(k_finalize, dim3((B + kWaves - 1) / kWaves), dim3(kBlock), 0, st, p);
     if (h->timing == 1) {
         (void)hipEventRecord(h->ev[1], st);
         h->ev_recorded = true;

@@ -161,6 +161,95 @@ __device__ __forceinline__ void stage_rmsnorm(const void *src, const uint16_t *g
     }
 }
 
+// The same by ONE wave, in two passes over the source (the second pass hits L1/L2): used when a workgroup stages
+// several sequences, one per wave, instead of one after the other.
+template <bool SRC_BF16>
+__device__ __forceinline__ void stage_rmsnorm_wave(const void *src, const uint16_t *gain, int d, float eps,
+                                                   uint16_t *hi, uint16_t *lo, float *out_f32, float *out2_f32 = nullptr,
+                                                   const float *add1 = nullptr, const float *add2 = nullptr) {
+    const int lane = threadIdx.x & (kWave - 1);
+    auto load4 = [&](int e, float(&v)[4]) {
+        if (SRC_BF16) {
+            u32x2 raw = *reinterpret_cast<const u32x2 *>(static_cast<const uint16_t *>(src) + e);
+            v[0] = lo_half(raw.x);
+            v[1] = hi_half(raw.x);
+            v[2] = lo_half(raw.y);
+            v[3] = hi_half(raw.y);
+        } else {
+            f32x4 raw = *reinterpret_cast<const f32x4 *>(static_cast<const float *>(src) + e);
+            v[0] = raw.x;
+            v[1] = raw.y;
+            v[2] = raw.z;
+            v[3] = raw.w;
+        }
+        if (add1) {
+            f32x4 a = *reinterpret_cast<const f32x4 *>(add1 + e);
+            v[0] += a.x;
+            v[1] += a.y;
+            v[2] += a.z;
+            v[3] += a.w;
+        }
+        if (add2) {
+            f32x4 a = *reinterpret_cast<const f32x4 *>(add2 + e);
+            v[0] += a.x;
+            v[1] += a.y;
+            v[2] += a.z;
+            v[3] += a.w;
+        }
+    };
+    float ss = 0.f;
+    for (int e = lane * 4; e < d; e += kWave * 4) {
+        float v[4];
+        load4(e, v);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) ss += v[q] * v[q];
+    }
+    const float inv = 1.0f / sqrtf(wave_sum(ss) / (float)d + eps);
+    for (int e = lane * 4; e < d; e += kWave * 4) {
+        float v[4];
+        load4(e, v);
+        u32x2 g = *reinterpret_cast<const u32x2 *>(gain + e);
+        float o[4] = {lo_half(g.x) * (v[0] * inv), hi_half(g.x) * (v[1] * inv), lo_half(g.y) * (v[2] * inv),
+                      hi_half(g.y) * (v[3] * inv)};
+        uint16_t h[4], l[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) split_bf16(o[q], h[q], l[q]);
+        u32x2 ph = {(uint32_t)h[0] | ((uint32_t)h[1] << 16), (uint32_t)h[2] | ((uint32_t)h[3] << 16)};
+        u32x2 pl = {(uint32_t)l[0] | ((uint32_t)l[1] << 16), (uint32_t)l[2] | ((uint32_t)l[3] << 16)};
+        *reinterpret_cast<u32x2 *>(hi + e) = ph;
+        *reinterpret_cast<u32x2 *>(lo + e) = pl;
+        f32x4 w = {o[0], o[1], o[2], o[3]};
+        if (out_f32) *reinterpret_cast<f32x4 *>(out_f32 + e) = w;
+        if (out2_f32) *reinterpret_cast<f32x4 *>(out2_f32 + e) = w;
+    }
+}
+
+// Staging of nb sequences: alone, a sequence gets the whole workgroup (shortest latency); several are dealt to the
+// waves.  f(i, whole_workgroup) stages sequence i.  Ends with a barrier.
+template <class F>
+__device__ __forceinline__ void stage_sequences(int nb, F f) {
+    __syncthreads();
+    if (nb == 1) {
+        f(0, true);
+    } else {
+        for (int i = threadIdx.x / kWave; i < nb; i += kWaves) f(i, false);
+    }
+    __syncthreads();
+}
+
+// winner_key by one wave
+__device__ __forceinline__ unsigned long long winner_key_wave(const DraftParams &p, int step, int b) {
+    const unsigned long long *cand = p.cand + ((size_t)step * p.max_batch + b) * p.head_grid;
+    unsigned long long best = 0ull;
+    for (int w = threadIdx.x & (kWave - 1); w < p.head_grid; w += kWave) best = cand[w] > best ? cand[w] : best;
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        unsigned long long o = __shfl_xor(best, off, kWave);
+        best = o > best ? o : best;
+    }
+    return best;
+}
+
 // plain copy of a float vector of length K (multiple of 4) into hi/lo, zero-padded to kpad
 __device__ __forceinline__ void stage_plain(const float *src, int K, int kpad, uint16_t *hi, uint16_t *lo) {
     for (int e = threadIdx.x * 4; e < kpad; e += kBlock * 4) {
@@ -560,30 +649,39 @@ __device__ __forceinline__ void phase_proj(const DraftParams &p, int step, int v
     for (int b0 = 0; b0 < p.B; b0 += nbmax) {
         int nb = min(nbmax, p.B - b0);
         auto stage = [&]() {
-            __syncthreads();
-            for (int i = 0; i < nb; ++i) {
-                int b = b0 + i;
+            stage_sequences(nb, [&](int i, bool whole) {
+                const int b = b0 + i;
+                const bool lead = whole ? threadIdx.x == 0 : (threadIdx.x & (kWave - 1)) == 0;
                 // x_1 is the verified token; afterwards the previous step's draft (or the forced token)
                 int tok;
                 if (step == 0) {
                     tok = p.token_in[b];
                 } else {
-                    int did = key_token(p, winner_key(p, step - 1, b, reinterpret_cast<unsigned long long *>(l.red)));
-                    if (vb == 0 && threadIdx.x == 0) p.draft_out[(size_t)b * p.K + step - 1] = seq_dead(p, b) ? -1 : did;
+                    unsigned long long key = whole ? winner_key(p, step - 1, b, reinterpret_cast<unsigned long long *>(l.red))
+                                                   : winner_key_wave(p, step - 1, b);
+                    int did = key_token(p, key);
+                    if (vb == 0 && lead) p.draft_out[(size_t)b * p.K + step - 1] = seq_dead(p, b) ? -1 : did;
                     tok = p.forced ? p.forced[(size_t)b * (p.K - 1) + step - 1] : did;
                 }
                 if (tok < 0 || tok >= p.V) { // reported, and replaced by id 0 so that every access stays in bounds
-                    if (threadIdx.x == 0) atomicOr(p.err, kErrTokenRange);
+                    if (lead) atomicOr(p.err, kErrTokenRange);
                     tok = 0;
                 }
                 uint16_t *hi = l.hi + (size_t)i * l.kpad, *lo = l.lo + (size_t)i * l.kpad;
-                if (step == 0)
-                    stage_rmsnorm<true>(p.hidden_in + (size_t)b * d, p.g_h, d, p.eps, hi, lo, l.red, nullptr);
-                else
-                    stage_rmsnorm<false>(p.hhat + (size_t)b * d, p.g_h, d, p.eps, hi, lo, l.red, nullptr);
-                stage_rmsnorm<true>(p.embed + (size_t)tok * d, p.g_e, d, p.eps, hi + d, lo + d, l.red, nullptr);
-            }
-            __syncthreads();
+                if (whole) {
+                    if (step == 0)
+                        stage_rmsnorm<true>(p.hidden_in + (size_t)b * d, p.g_h, d, p.eps, hi, lo, l.red, nullptr);
+                    else
+                        stage_rmsnorm<false>(p.hhat + (size_t)b * d, p.g_h, d, p.eps, hi, lo, l.red, nullptr);
+                    stage_rmsnorm<true>(p.embed + (size_t)tok * d, p.g_e, d, p.eps, hi + d, lo + d, l.red, nullptr);
+                } else {
+                    if (step == 0)
+                        stage_rmsnorm_wave<true>(p.hidden_in + (size_t)b * d, p.g_h, d, p.eps, hi, lo, nullptr);
+                    else
+                        stage_rmsnorm_wave<false>(p.hhat + (size_t)b * d, p.g_h, d, p.eps, hi, lo, nullptr);
+                    stage_rmsnorm_wave<true>(p.embed + (size_t)tok * d, p.g_e, d, p.eps, hi + d, lo + d, nullptr);
+                }
+            });
         };
         auto rowptr = [&](int, int row) { return p.w_proj + (size_t)row * 2 * d; };
         auto epi = [&](int i, int row, float(&s)[1]) { p.x[(size_t)(b0 + i) * d + row] = s[0]; };
@@ -602,11 +700,14 @@ __device__ __forceinline__ void phase_qkv(const DraftParams &p, int step, int vb
     for (int b0 = 0; b0 < p.B; b0 += nbmax) {
         int nb = min(nbmax, p.B - b0);
         auto stage = [&]() {
-            __syncthreads();
-            for (int i = 0; i < nb; ++i)
-                stage_rmsnorm<false>(p.x + (size_t)(b0 + i) * d, p.g_attn, d, p.eps, l.hi + (size_t)i * l.kpad,
-                                     l.lo + (size_t)i * l.kpad, l.red, nullptr);
-            __syncthreads();
+            stage_sequences(nb, [&](int i, bool whole) {
+                const float *src = p.x + (size_t)(b0 + i) * d;
+                uint16_t *hi = l.hi + (size_t)i * l.kpad, *lo = l.lo + (size_t)i * l.kpad;
+                if (whole)
+                    stage_rmsnorm<false>(src, p.g_attn, d, p.eps, hi, lo, l.red, nullptr);
+                else
+                    stage_rmsnorm_wave<false>(src, p.g_attn, d, p.eps, hi, lo, nullptr);
+            });
         };
         auto rowptr = [&](int, int row) {
             if (row < p.qd) return p.w_q + (size_t)row * d;
@@ -944,12 +1045,14 @@ __device__ __forceinline__ void phase_gateup(const DraftParams &p, int, int vb, 
     for (int b0 = 0; b0 < p.B; b0 += nbmax) {
         int nb = min(nbmax, p.B - b0);
         auto stage = [&]() {
-            __syncthreads();
-            for (int i = 0; i < nb; ++i)
-                stage_rmsnorm<false>(p.x + (size_t)(b0 + i) * d, p.g_mlp, d, p.eps, l.hi + (size_t)i * l.kpad,
-                                     l.lo + (size_t)i * l.kpad, l.red, nullptr, nullptr,
-                                     p.o + (size_t)(b0 + i) * d); // x1 = x + w_o attn
-            __syncthreads();
+            stage_sequences(nb, [&](int i, bool whole) {
+                const float *src = p.x + (size_t)(b0 + i) * d, *res = p.o + (size_t)(b0 + i) * d; // x1 = x + w_o attn
+                uint16_t *hi = l.hi + (size_t)i * l.kpad, *lo = l.lo + (size_t)i * l.kpad;
+                if (whole)
+                    stage_rmsnorm<false>(src, p.g_mlp, d, p.eps, hi, lo, l.red, nullptr, nullptr, res);
+                else
+                    stage_rmsnorm_wave<false>(src, p.g_mlp, d, p.eps, hi, lo, nullptr, nullptr, res);
+            });
         };
         // the 2F rows of [w_gate; w_up] are dealt out as one list: the two halves of a SwiGLU pair need not meet
         // here (the consumer multiplies them), which keeps every wave within one row of the average load
@@ -994,17 +1097,20 @@ __device__ __forceinline__ void phase_lmhead(const DraftParams &p, int step, int
     for (int b0 = 0; b0 < p.B; b0 += nbmax) {
         int nb = min(nbmax, p.B - b0);
         auto stage = [&]() {
-            __syncthreads();
-            for (int i = 0; i < nb; ++i) {
-                int b = b0 + i;
+            stage_sequences(nb, [&](int i, bool whole) {
+                const int b = b0 + i;
                 // workgroup 0 also publishes the step's output hidden state: for the next step and for the caller
                 float *hh = (vb == 0) ? p.hhat + (size_t)b * d : nullptr;
                 float *ho = (vb == 0 && p.hidden_out) ? p.hidden_out + ((size_t)b * p.K + step) * d : nullptr;
-                stage_rmsnorm<false>(p.x + (size_t)b * d, p.g_final, d, p.eps, l.hi + (size_t)i * l.kpad,
-                                     l.lo + (size_t)i * l.kpad, l.red, hh, ho, p.o + (size_t)b * d,
-                                     p.dn + (size_t)b * d); // x2 = (x + w_o attn) + w_down m
-            }
-            __syncthreads();
+                uint16_t *hi = l.hi + (size_t)i * l.kpad, *lo = l.lo + (size_t)i * l.kpad;
+                // x2 = (x + w_o attn) + w_down m
+                if (whole)
+                    stage_rmsnorm<false>(p.x + (size_t)b * d, p.g_final, d, p.eps, hi, lo, l.red, hh, ho,
+                                         p.o + (size_t)b * d, p.dn + (size_t)b * d);
+                else
+                    stage_rmsnorm_wave<false>(p.x + (size_t)b * d, p.g_final, d, p.eps, hi, lo, hh, ho,
+                                              p.o + (size_t)b * d, p.dn + (size_t)b * d);
+            });
         };
         // best (logit, index) seen by this thread: in row mode lane 0 of a wave reports every sequence, in tile
         // mode a thread reports one sequence only
@@ -1054,13 +1160,19 @@ __device__ __forceinline__ void phase_lmhead(const DraftParams &p, int step, int
     }
 }
 
-// after the last step: publish the last draft id (one workgroup)
-__device__ void phase_finalize(const DraftParams &p, int vb) {
-    __shared__ unsigned long long red64[kWaves];
-    if (vb != 0) return;
-    for (int b = 0; b < p.B; ++b) {
-        int did = key_token(p, winner_key(p, p.K - 1, b, red64));
-        if (threadIdx.x == 0) p.draft_out[(size_t)b * p.K + p.K - 1] = seq_dead(p, b) ? -1 : did;
+// after the last step: publish the last draft id; one wave per sequence takes the maximum over the candidates
+__device__ void phase_finalize(const DraftParams &p, int vb, int nvb) {
+    const int lane = threadIdx.x & (kWave - 1);
+    for (int b = vb * kWaves + threadIdx.x / kWave; b < p.B; b += nvb * kWaves) {
+        const unsigned long long *cand = p.cand + ((size_t)(p.K - 1) * p.max_batch + b) * p.head_grid;
+        unsigned long long best = 0ull;
+        for (int w = lane; w < p.head_grid; w += kWave) best = cand[w] > best ? cand[w] : best;
+#pragma unroll
+        for (int off = 1; off < kWave; off <<= 1) {
+            unsigned long long o = __shfl_xor(best, off, kWave);
+            best = o > best ? o : best;
+        }
+        if (lane == 0) p.draft_out[(size_t)b * p.K + p.K - 1] = seq_dead(p, b) ? -1 : key_token(p, best);
     }
 }
 

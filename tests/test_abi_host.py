@@ -77,3 +77,13 @@ def test_calls_reject_null_handle():
     assert b.mtp_set_timing(None, 1) == -1
     assert b.mtp_last_draft_ms(None) < 0
     b.mtp_draft_destroy(None)
+
+
+def test_one_hip_runtime_in_the_process():
+    """The library must bind to the HIP runtime PyTorch has loaded, whatever the import order of the caller: a
+    second copy of the runtime in the process finds no device."""
+    paths = set()
+    for line in open("/proc/self/maps"):
+        if "libamdhip64" in line:
+            paths.add(os.path.realpath(line.split()[-1]))
+    assert len(paths) == 1, paths
