@@ -1,0 +1,508 @@
+// Batched weight streaming for 5..64 sequences per pass (gfx950): every weight is read from HBM once per pass.
+//
+// The activations of a phase arrive already split into bf16 hi + lo, written to global memory by the phase before
+// (they stay in L2), so the A operand of the 16x16x32 MFMA (16 sequences x 32 elements) is loaded straight into
+// registers and reused for every weight tile the wave holds at that depth: no LDS staging, no barrier until a group
+// of tiles is complete.  A wave keeps eight accumulators: 8/NA weight tiles (16 rows each) times NA sequence tiles.
+//
+// Work split of a phase over the grid: RG row groups times KP reduction parts.  Phases with many rows per workgroup
+// (gate/up, the output head) use KP = 1; phases with one 16-row tile per workgroup would reload all activations for
+// 16 rows, so they put eight tiles into a row group and split the reduction over KP workgroups instead.  Inside a
+// workgroup the eight waves split the workgroup's reduction range; their sums meet in LDS, the workgroup's sums go
+// to a partial buffer in global memory, and the LAST workgroup of a row group to arrive (a ticket counter) adds the
+// KP partials in a fixed order and runs the phase's epilogue.  With KP = 1 the same code runs without the ticket.
+//
+// RMSNorm (Sec. 2.1) costs no pass over the activations here: the producer writes gain * u (split) and the sum of
+// squares of its rows, and because W (s g*u) = s W (g*u), the consumer multiplies its results by
+// s = 1/sqrt(mean(u^2) + eps) in the epilogue.
+#pragma once
+#include "phases.h"
+
+namespace mtp {
+
+constexpr int kBatchAcc = 8;      // accumulators per wave
+constexpr int kBatchMaxSeq = 64;  // sequences per pass
+// A lane offset at or beyond the end of every buffer (the host checks that each matrix is smaller than 2 GiB): such a
+// load returns zeros and moves no data.  Adding the wave-uniform offset (a few MiB at most) cannot wrap it around.
+constexpr uint32_t kOobOffset = 0x80000000u;
+
+
+template <int NA>
+struct BatchShape {
+    static constexpr int TG = kBatchAcc / NA;   // weight tiles per group
+    static constexpr int D = NA == 1 ? 3 : 4;   // items (one depth step of a group) in flight per wave
+    static constexpr int NL = TG + 2 * NA;      // 16-byte loads per lane per item
+};
+
+__host__ __device__ inline size_t batch_lds_bytes(int max_rows_per_wg) {
+    return (size_t)2 * kWaves * kBatchAcc * kWave * 16 + kBatchMaxSeq * 4 + (size_t)max_rows_per_wg * 4 + 256;
+}
+
+// The bf16 hi/lo pair of one float, as the A operand wants it
+__device__ __forceinline__ void store_split(uint16_t *hi, size_t lo_off, size_t idx, float v) {
+    uint16_t h, l;
+    split_bf16(v, h, l);
+    hi[idx] = h;
+    hi[lo_off + idx] = l;
+}
+
+// s_b = 1/sqrt(mean(u_b^2) + eps) for the nb sequences of the pass, from the producers' per-tile sums of squares
+__device__ __forceinline__ void batch_scales(const DraftParams &p, int kind, float *scale_lds) {
+    const int bl = threadIdx.x >> 3, sub = threadIdx.x & 7;
+    const int npart = p.d / 16;
+    float s = 0.f;
+    if (bl < p.nb) {
+        const float *src = p.ssq + ((size_t)kind * p.max_batch + p.b0 + bl) * npart;
+        for (int i = sub; i < npart; i += 8) s += src[i];
+    }
+    s = oct_sum(s);
+    if (sub == 0 && bl < kBatchMaxSeq) scale_lds[bl] = bl < p.nb ? 1.0f / sqrtf(s / (float)p.d + p.eps) : 0.f;
+}
+
+// ---------------------------------------------------------------------------------------------------
+// the core.  Ph supplies:
+//   NMAT (1, or 2 = adjacent tiles form (gate, up) pairs), STREAM (non-temporal weight loads), GATHER (rows through
+//   the id list), SCALE (SSQ_* kind whose scale the epilogue needs, or -1),
+//   K, rows (per matrix), in (hi array of the input activations),
+//   tile(vt, base, mat_rows, row0, row_end): matrix (start, rows) and first row of virtual tile vt; rows at or past
+//   row_end do not exist,
+//   epi(bf, vt, j, sums[NMAT], scale_lds): results of sequences b0+bf .. +3 (components of the f32x4) for row j of
+//   virtual tile vt (NMAT = 2: vt is the gate tile), run by all 64 lanes of a wave together,
+//   finish(rg, smem): after the last epilogue of the row group (all threads).
+// ---------------------------------------------------------------------------------------------------
+template <int NA, class Ph>
+__device__ __forceinline__ void bgemv(const DraftParams &p, Ph &ph, int RG, int KP, char *smem) {
+    using S = BatchShape<NA>;
+    constexpr int NMAT = Ph::NMAT, TG = S::TG, D = S::D, NL = S::NL;
+    const int wg = blockIdx.x;
+    if (wg >= RG * KP) return;
+    const int kp = wg % KP, rg = wg / KP;
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave, j = lane & 15, g = lane >> 4;
+    const int K = ph.K;
+    const int units = (ph.rows + 15) / 16;
+    const int u0 = (int)((long long)rg * units / RG), u1 = (int)((long long)(rg + 1) * units / RG);
+    const int vt0 = u0 * NMAT, nvt = (u1 - u0) * NMAT, ntv = units * NMAT;
+    const int ngroups = (nvt + TG - 1) / TG;
+    const int nks = (K + 31) / 32;
+    const int ksA = (int)((long long)kp * nks / KP), ksB = (int)((long long)(kp + 1) * nks / KP);
+    const int per = max((ksB - ksA + kWaves - 1) / kWaves, 1); // items per group, the same for every wave
+    // depth steps are dealt to the waves round robin: at any time the eight waves of the workgroup read eight
+    // neighbouring 64-byte pieces of every row, 512 contiguous bytes
+    const int total = ngroups * per;
+
+    f32x4 *partial = reinterpret_cast<f32x4 *>(smem);                           // [2][kWaves][kBatchAcc][kWave]
+    float *scale_lds = reinterpret_cast<float *>(partial + 2 * kWaves * kBatchAcc * kWave); // [kBatchMaxSeq]
+    int *ids_lds = reinterpret_cast<int *>(scale_lds + kBatchMaxSeq);           // [rows of this row group]
+    if (Ph::GATHER) {
+        const int r0 = u0 * 16, nr = (u1 - u0) * 16;
+        for (int i = threadIdx.x; i < nr; i += kBlock) {
+            int pos = min(r0 + i, ph.rows - 1);
+            ids_lds[i] = ph.ids ? ph.ids[pos] : pos;
+        }
+        __syncthreads();
+    }
+
+    // activations: one descriptor over the hi and lo arrays; lane (j, g) reads sequence at*16 + j, elements 8g..8g+8
+    const size_t lo_bytes = p.a_lo * 2;
+    const row_rsrc ar = make_row_rsrc(ph.in, (int)(2 * lo_bytes));
+    int voff_a[NA];
+#pragma unroll
+    for (int at = 0; at < NA; ++at)
+        voff_a[at] = (int)((size_t)min(p.b0 + at * 16 + j, p.B - 1) * p.a_stride * 2 + g * 16);
+
+    row_rsrc wr[TG];
+    int voff_w[TG];
+    auto setup_group = [&](int grp) {
+#pragma unroll
+        for (int ts = 0; ts < TG; ++ts) {
+            const int t = grp * TG + ts;
+            const uint16_t *base;
+            int mat_rows, row0, row_end;
+            ph.tile(vt0 + min(t, nvt - 1), base, mat_rows, row0, row_end);
+            wr[ts] = make_row_rsrc(base, (int)((size_t)mat_rows * K * 2));
+            const int r = row0 + j;
+            const bool ok = t < nvt && r < row_end;
+            const int phys = Ph::GATHER ? ids_lds[(min(t, nvt - 1) / NMAT) * 16 + j] : r;
+            voff_w[ts] = ok ? (int)((size_t)phys * K * 2 + g * 16) : (int)kOobOffset;
+        }
+    };
+    u32x4 ring[D][NL];
+    int ig = 0, ik = 0; // next item to request: group, and which of this wave's depth steps
+    auto issue = [&](u32x4(&slot)[NL]) {
+        const int ks = min(ksA + ik * kWaves + wave, nks - 1);
+        const int soff = min(ks * 32, K - 32) * 2; // the last, ragged step is shifted left to stay inside the row
+#pragma unroll
+        for (int ts = 0; ts < TG; ++ts) slot[ts] = row_load16<Ph::STREAM>(wr[ts], voff_w[ts], soff);
+#pragma unroll
+        for (int at = 0; at < NA; ++at) {
+            slot[TG + 2 * at] = row_load16<false>(ar, voff_a[at], soff);
+            slot[TG + 2 * at + 1] = row_load16<false>(ar, voff_a[at], soff + (int)lo_bytes);
+        }
+        if (++ik == per) {
+            ik = 0;
+            ++ig;
+            if (ig < ngroups) setup_group(ig);
+        }
+    };
+    setup_group(0);
+#pragma unroll
+    for (int s = 0; s < D; ++s)
+        if (s < total) issue(ring[s]);
+    // with the first loads under way: the norm scales for the epilogue (visible after the first group's barrier)
+    if (Ph::SCALE >= 0) batch_scales(p, Ph::SCALE, scale_lds);
+
+    f32x4 acc[kBatchAcc];
+#pragma unroll
+    for (int a = 0; a < kBatchAcc; ++a) acc[a] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+    float *part = p.part;
+    int cg = 0, ck = 0;
+    for (int n0 = 0; n0 < total; n0 += D) {
+#pragma unroll
+        for (int s = 0; s < D; ++s) {
+            if (n0 + s < total) { // uniform
+                const int ksn = ksA + ck * kWaves + wave;
+                const int ks = min(ksn, nks - 1);
+                const int koff = min(ks * 32, K - 32);
+                // lanes whose eight elements were already counted by the step before (ragged end), or all lanes of a
+                // step beyond this wave's range, contribute zeros
+                const int cut = ksn < ksB ? (ks * 32 - koff) / 8 : 4;
+                const bool dead = g < cut;
+#pragma unroll
+                for (int at = 0; at < NA; ++at) {
+                    const u32x4 ah = dead ? zero4 : ring[s][TG + 2 * at];
+                    const u32x4 al = dead ? zero4 : ring[s][TG + 2 * at + 1];
+#pragma unroll
+                    for (int ts = 0; ts < TG; ++ts) {
+                        acc[ts * NA + at] = mfma16(ah, ring[s][ts], acc[ts * NA + at]);
+                        acc[ts * NA + at] = mfma16(al, ring[s][ts], acc[ts * NA + at]);
+                    }
+                }
+                if (n0 + s + D < total) issue(ring[s]);
+                if (++ck == per) { // group complete: meet the other waves in LDS, hand the sums to the partial buffer
+                    ck = 0;
+                    f32x4 *pb = partial + (size_t)(cg & 1) * kWaves * kBatchAcc * kWave;
+#pragma unroll
+                    for (int a = 0; a < kBatchAcc; ++a) {
+                        pb[(wave * kBatchAcc + a) * kWave + lane] = acc[a];
+                        acc[a] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    }
+                    lds_barrier();
+                    {
+                        const int a = wave; // this thread adds accumulator `wave`, element `lane`, of all waves
+                        f32x4 sum = pb[a * kWave + lane];
+#pragma unroll
+                        for (int w = 1; w < kWaves; ++w) sum += pb[(w * kBatchAcc + a) * kWave + lane];
+                        const int ts = a / NA, at = a % NA, t = cg * TG + ts;
+                        if (t < nvt)
+                            *reinterpret_cast<f32x4 *>(part + ((((size_t)kp * ntv + vt0 + t) * NA + at) * kWave + lane) * 4) =
+                                sum;
+                    }
+                    ++cg;
+                }
+            }
+        }
+    }
+
+    // ---- the last workgroup of the row group adds the parts and runs the epilogue ----
+    __syncthreads(); // every store of this workgroup's sums has completed
+    if (KP > 1) {
+        int *flag = reinterpret_cast<int *>(partial); // the partial sums in LDS are dead now
+        if (threadIdx.x == 0) {
+            // release: the sums above become visible to the other compute dies before the ticket does;
+            // acquire: the last to arrive drops stale lines of its L1 and L2 before it reads the others' sums
+            int old = __hip_atomic_fetch_add(p.ticket + rg, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+            *flag = (old == KP - 1);
+            if (old == KP - 1) p.ticket[rg] = 0; // ready for the next launch
+        }
+        __syncthreads();
+        const bool last = *flag != 0;
+        __syncthreads();
+        if (!last) return;
+    }
+    constexpr int NQ = kBatchAcc / NMAT; // (tile or pair, sequence tile) slots with an epilogue
+    if (wave < NQ) {
+        for (int grp = 0; grp < ngroups; ++grp) {
+            const int q = wave, at = q % NA, tq = q / NA; // tq: tile (NMAT = 1) or pair (NMAT = 2) inside the group
+            const int t = grp * TG + tq * NMAT;           // first virtual tile of the slot, relative to vt0
+            if (t < nvt) {                                 // uniform for the wave
+                f32x4 sums[NMAT];
+#pragma unroll
+                for (int m = 0; m < NMAT; ++m) {
+                    const float *src = part + (((size_t)(vt0 + t + m) * NA + at) * kWave + lane) * 4;
+                    const size_t kstride = (size_t)ntv * NA * kWave * 4;
+                    f32x4 sacc = {0.f, 0.f, 0.f, 0.f};
+                    for (int k2 = 0; k2 < KP; k2 += 8) { // eight loads in flight, added in the order of the parts
+                        f32x4 v[8];
+#pragma unroll
+                        for (int u = 0; u < 8; ++u)
+                            v[u] = *reinterpret_cast<const f32x4 *>(src + (size_t)min(k2 + u, KP - 1) * kstride);
+#pragma unroll
+                        for (int u = 0; u < 8; ++u)
+                            if (k2 + u < KP) sacc += v[u];
+                    }
+                    sums[m] = sacc;
+                }
+                ph.epi(at * 16 + g * 4, vt0 + t, j, sums, scale_lds);
+            }
+        }
+    }
+    ph.finish(rg, reinterpret_cast<char *>(partial));
+}
+
+// ---------------------------------------------------------------------------------------------------
+// the phases of a draft step (Sec. 2.1, Fig. 1) on the batched core
+// ---------------------------------------------------------------------------------------------------
+struct BgBase {
+    static constexpr int NMAT = 1;
+    static constexpr bool STREAM = true, GATHER = false;
+    static constexpr int SCALE = -1;
+    const DraftParams &p;
+    int K, rows;
+    const uint16_t *in;
+    const int *ids = nullptr;
+    __device__ BgBase(const DraftParams &p_, int K_, int rows_, const uint16_t *in_) : p(p_), K(K_), rows(rows_), in(in_) {}
+    __device__ __forceinline__ void finish(int, char *) {}
+    // sum over the sixteen rows of a tile of v*v, for the four sequences of this lane; lanes with j == 0 store it
+    __device__ __forceinline__ void store_ssq(int kind, int bf, int vt, int j, const float (&v)[4]) const {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            float s = row16_sum(v[c] * v[c]);
+            const int bl = bf + c;
+            if (j == 0 && bl < p.nb) p.ssq[((size_t)kind * p.max_batch + p.b0 + bl) * (p.d / 16) + vt] = s;
+        }
+    }
+};
+
+// 2d -> d projection of [RMSNorm(h); RMSNorm(E[token])] (already normalised by the preparation kernel).  Leaves x,
+// and g_attn * x with its sums of squares for the q/k/v projection.
+struct BgProj : BgBase {
+    __device__ BgProj(const DraftParams &p_) : BgBase(p_, 2 * p_.d, p_.d, p_.act[0]) {}
+    __device__ __forceinline__ void tile(int vt, const uint16_t *&base, int &mat_rows, int &row0, int &row_end) const {
+        base = p.w_proj;
+        mat_rows = row_end = p.d;
+        row0 = vt * 16;
+    }
+    __device__ __forceinline__ void epi(int bf, int vt, int j, const f32x4 (&s)[1], const float *) const {
+        const int row = vt * 16 + j;
+        const float v[4] = {s[0].x, s[0].y, s[0].z, s[0].w};
+        const float gn = bf16_to_f32(p.g_attn[row]);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int bl = bf + c;
+            if (bl < p.nb) {
+                const size_t b = p.b0 + bl;
+                p.x[b * p.d + row] = v[c];
+                store_split(p.act[1], p.a_lo, b * p.a_stride + row, gn * v[c]);
+            }
+        }
+        store_ssq(SSQ_X, bf, vt, j, v);
+    }
+};
+
+// q/k/v projection of RMSNorm(x; g_attn); bias, rotary embedding and the cache append happen in the attention phase
+struct BgQkv : BgBase {
+    static constexpr int SCALE = SSQ_X;
+    __device__ BgQkv(const DraftParams &p_) : BgBase(p_, p_.d, p_.qkv_dim, p_.act[1]) {}
+    __device__ __forceinline__ void tile(int vt, const uint16_t *&base, int &mat_rows, int &row0, int &row_end) const {
+        const int r = vt * 16;
+        if (r < p.qd) {
+            base = p.w_q;
+            mat_rows = p.qd;
+            row0 = r;
+        } else if (r < p.qd + p.kvd) {
+            base = p.w_k;
+            mat_rows = p.kvd;
+            row0 = r - p.qd;
+        } else {
+            base = p.w_v;
+            mat_rows = p.kvd;
+            row0 = r - p.qd - p.kvd;
+        }
+        row_end = mat_rows;
+    }
+    __device__ __forceinline__ void epi(int bf, int vt, int j, const f32x4 (&s)[1], const float *scale) const {
+        const int row = vt * 16 + j;
+        const float v[4] = {s[0].x, s[0].y, s[0].z, s[0].w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int bl = bf + c;
+            if (bl < p.nb) p.qkv[(size_t)(p.b0 + bl) * p.qkv_dim + row] = v[c] * scale[bl];
+        }
+    }
+};
+
+// output projection of the attention result; leaves x1 = x + W_o a, and g_mlp * x1 with its sums of squares
+struct BgOproj : BgBase {
+    __device__ BgOproj(const DraftParams &p_) : BgBase(p_, p_.qd, p_.d, p_.act[0]) {}
+    __device__ __forceinline__ void tile(int vt, const uint16_t *&base, int &mat_rows, int &row0, int &row_end) const {
+        base = p.w_o;
+        mat_rows = row_end = p.d;
+        row0 = vt * 16;
+    }
+    __device__ __forceinline__ void epi(int bf, int vt, int j, const f32x4 (&s)[1], const float *) const {
+        const int row = vt * 16 + j;
+        float v[4] = {s[0].x, s[0].y, s[0].z, s[0].w};
+        const float gn = bf16_to_f32(p.g_mlp[row]);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int bl = bf + c;
+            if (bl < p.nb) {
+                const size_t b = p.b0 + bl;
+                v[c] += p.x[b * p.d + row];
+                p.o[b * p.d + row] = v[c];
+                store_split(p.act[1], p.a_lo, b * p.a_stride + row, gn * v[c]);
+            } else {
+                v[c] = 0.f;
+            }
+        }
+        store_ssq(SSQ_X1, bf, vt, j, v);
+    }
+};
+
+// gate and up projections of RMSNorm(x1; g_mlp) as pairs of tiles; leaves m = silu(gate) * up, split
+struct BgGateUp : BgBase {
+    static constexpr int NMAT = 2;
+    static constexpr int SCALE = SSQ_X1;
+    __device__ BgGateUp(const DraftParams &p_) : BgBase(p_, p_.d, p_.F, p_.act[1]) {}
+    __device__ __forceinline__ void tile(int vt, const uint16_t *&base, int &mat_rows, int &row0, int &row_end) const {
+        base = (vt & 1) ? p.w_up : p.w_gate;
+        mat_rows = row_end = p.F;
+        row0 = (vt >> 1) * 16;
+    }
+    __device__ __forceinline__ void epi(int bf, int vt, int j, const f32x4 (&s)[2], const float *scale) const {
+        const int row = (vt >> 1) * 16 + j;
+        const float gv[4] = {s[0].x, s[0].y, s[0].z, s[0].w}, uv[4] = {s[1].x, s[1].y, s[1].z, s[1].w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int bl = bf + c;
+            if (bl < p.nb && row < p.F) {
+                const float gs = gv[c] * scale[bl], us = uv[c] * scale[bl];
+                store_split(p.act[0], p.a_lo, (size_t)(p.b0 + bl) * p.a_stride + row, (gs / (1.0f + expf(-gs))) * us);
+            }
+        }
+    }
+};
+
+// down projection; leaves x2 = x1 + W_down m, and g_final * x2 with its sums of squares for the output head
+struct BgDown : BgBase {
+    __device__ BgDown(const DraftParams &p_) : BgBase(p_, p_.F, p_.d, p_.act[0]) {}
+    __device__ __forceinline__ void tile(int vt, const uint16_t *&base, int &mat_rows, int &row0, int &row_end) const {
+        base = p.w_down;
+        mat_rows = row_end = p.d;
+        row0 = vt * 16;
+    }
+    __device__ __forceinline__ void epi(int bf, int vt, int j, const f32x4 (&s)[1], const float *) const {
+        const int row = vt * 16 + j;
+        float v[4] = {s[0].x, s[0].y, s[0].z, s[0].w};
+        const float gn = bf16_to_f32(p.g_final[row]);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int bl = bf + c;
+            if (bl < p.nb) {
+                const size_t b = p.b0 + bl;
+                v[c] += p.o[b * p.d + row];
+                p.dn[b * p.d + row] = v[c];
+                store_split(p.act[1], p.a_lo, b * p.a_stride + row, gn * v[c]);
+            } else {
+                v[c] = 0.f;
+            }
+        }
+        store_ssq(SSQ_X2, bf, vt, j, v);
+    }
+};
+
+// output head over the compressed vocabulary (Sec. 2.2, Eq. (3)): logits of RMSNorm(x2; g_final) against the listed
+// rows, and per row group the best (logit, position) of every sequence
+struct BgHead : BgBase {
+    static constexpr bool STREAM = false, GATHER = true;
+    static constexpr int SCALE = SSQ_X2;
+    int step;
+    unsigned long long best[4] = {0ull, 0ull, 0ull, 0ull};
+    int bf_mine = 0;
+    __device__ BgHead(const DraftParams &p_, int step_) : BgBase(p_, p_.d, p_.n, p_.act[1]), step(step_) { ids = p_.ids; }
+    __device__ __forceinline__ void tile(int vt, const uint16_t *&base, int &mat_rows, int &row0, int &row_end) const {
+        base = p.lm_head;
+        mat_rows = p.V;
+        row_end = p.n;
+        row0 = vt * 16;
+    }
+    __device__ __forceinline__ void epi(int bf, int vt, int j, const f32x4 (&s)[1], const float *scale) {
+        const int pos = vt * 16 + j;
+        const float v[4] = {s[0].x, s[0].y, s[0].z, s[0].w};
+        bf_mine = bf; // a wave always serves the same sequence tile
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int bl = bf + c;
+            if (bl < p.nb && pos < p.n) {
+                const float logit = v[c] * scale[bl];
+                if (p.logits_out) p.logits_out[((size_t)(p.b0 + bl) * p.K + step) * p.n + pos] = logit;
+                const unsigned long long key = argmax_key(logit, (uint32_t)pos);
+                best[c] = key > best[c] ? key : best[c];
+            }
+        }
+    }
+    // candidates: maximum over the sixteen rows of a lane group, then over the waves that served the same sequences
+    __device__ __forceinline__ void finish(int rg, char *smem) {
+        unsigned long long *red = reinterpret_cast<unsigned long long *>(smem); // [kWaves][kBatchMaxSeq]
+        __syncthreads();
+        for (int i = threadIdx.x; i < kWaves * kBatchMaxSeq; i += kBlock) red[i] = 0ull;
+        __syncthreads();
+        const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            unsigned long long m = best[c];
+#pragma unroll
+            for (int off = 1; off < 16; off <<= 1) {
+                unsigned long long o = __shfl_xor(m, off, kWave);
+                m = o > m ? o : m;
+            }
+            if ((lane & 15) == 0 && m != 0ull) red[wave * kBatchMaxSeq + bf_mine + c] = m;
+        }
+        __syncthreads();
+        if ((int)threadIdx.x < p.nb) {
+            unsigned long long m = 0ull;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) {
+                unsigned long long c = red[w * kBatchMaxSeq + threadIdx.x];
+                m = c > m ? c : m;
+            }
+            p.cand[((size_t)step * p.max_batch + p.b0 + threadIdx.x) * p.head_grid + rg] = m;
+        }
+    }
+};
+
+// ---------------------------------------------------------------------------------------------------
+// preparation kernel, one workgroup per sequence, before every step and once after the last:
+//   s > 0: the id drafted by step s-1 and its output hidden state  h_hat = RMSNorm(x2; g_final)
+//   s < K: the input of step s, [RMSNorm(h; g_h); RMSNorm(E[token]; g_e)], split into bf16 hi + lo
+// ---------------------------------------------------------------------------------------------------
+__device__ __forceinline__ void phase_bprep(const DraftParams &p, int step, char *smem) {
+    const int b = blockIdx.x, d = p.d;
+    float *red = reinterpret_cast<float *>(smem);
+    uint16_t *hi = p.act[0] + (size_t)b * p.a_stride;
+    uint16_t *lo = hi + p.a_lo;
+    if (step == 0 && threadIdx.x == 0 && seq_dead(p, b)) atomicOr(p.err, kErrKvOverflow);
+    int did = 0;
+    if (step > 0) {
+        did = key_token(p, winner_key(p, step - 1, b, reinterpret_cast<unsigned long long *>(red)));
+        if (threadIdx.x == 0) p.draft_out[(size_t)b * p.K + step - 1] = seq_dead(p, b) ? -1 : did;
+        float *ho = p.hidden_out ? p.hidden_out + ((size_t)b * p.K + step - 1) * d : nullptr;
+        // the hi/lo halves written here are overwritten below or never read
+        stage_rmsnorm<false>(p.dn + (size_t)b * d, p.g_final, d, p.eps, hi, lo, red, p.hhat + (size_t)b * d, ho);
+        __syncthreads();
+    }
+    if (step >= p.K) return;
+    int tok = step == 0 ? p.token_in[b] : (p.forced ? p.forced[(size_t)b * (p.K - 1) + step - 1] : did);
+    if (tok < 0 || tok >= p.V) { // reported, and replaced by id 0 so that every access stays in bounds
+        if (threadIdx.x == 0) atomicOr(p.err, kErrTokenRange);
+        tok = 0;
+    }
+    if (step == 0)
+        stage_rmsnorm<true>(p.hidden_in + (size_t)b * d, p.g_h, d, p.eps, hi, lo, red, nullptr);
+    else
+        stage_rmsnorm<false>(p.hhat + (size_t)b * d, p.g_h, d, p.eps, hi, lo, red, nullptr);
+    stage_rmsnorm<true>(p.embed + (size_t)tok * d, p.g_e, d, p.eps, hi + d, lo + d, red, nullptr);
+}
+
+} // namespace mtp

@@ -1,0 +1,18 @@
+// Host-side entry points of the batched path (kernels live in mtp_batch.hip, the caller in mtp_draft.hip).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "phases.h"
+
+namespace mtp {
+
+// dynamic LDS of a batched matrix phase whose row groups hold at most `rows_per_group` rows
+size_t bgemv_lds_bytes(int rows_per_group);
+// raises the dynamic-LDS limit of every batched kernel; false if a call failed
+bool batch_allow_lds(size_t lds_limit);
+// one batched matrix phase (BG_* index) for the sequences [p.b0, p.b0 + p.nb)
+void launch_bgemv(int phase, const DraftParams &p, int step, int grid, size_t lds, hipStream_t st);
+// the preparation kernel before step `step` (step == K: after the last step), all sequences
+void launch_bprep(const DraftParams &p, int step, hipStream_t st);
+
+} // namespace mtp

@@ -1,0 +1,77 @@
+// Kernels of the batched draft path (five or more sequences per call) for gfx950.
+#include <hip/hip_runtime.h>
+
+#include "batch.h"
+#include "batch_launch.h"
+
+namespace mtp {
+namespace {
+
+template <int PH, int NA>
+__global__ __launch_bounds__(kBlock) void k_bgemv(DraftParams p, int step) {
+    extern __shared__ __align__(16) char smem[];
+    if constexpr (PH == BG_PROJ) {
+        BgProj ph(p);
+        bgemv<NA>(p, ph, p.bg_rg[PH], p.bg_kp[PH], smem);
+    } else if constexpr (PH == BG_QKV) {
+        BgQkv ph(p);
+        bgemv<NA>(p, ph, p.bg_rg[PH], p.bg_kp[PH], smem);
+    } else if constexpr (PH == BG_OPROJ) {
+        BgOproj ph(p);
+        bgemv<NA>(p, ph, p.bg_rg[PH], p.bg_kp[PH], smem);
+    } else if constexpr (PH == BG_GATEUP) {
+        BgGateUp ph(p);
+        bgemv<NA>(p, ph, p.bg_rg[PH], p.bg_kp[PH], smem);
+    } else if constexpr (PH == BG_DOWN) {
+        BgDown ph(p);
+        bgemv<NA>(p, ph, p.bg_rg[PH], p.bg_kp[PH], smem);
+    } else {
+        BgHead ph(p, step);
+        bgemv<NA>(p, ph, p.bg_rg[PH], p.bg_kp[PH], smem);
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void k_bprep(DraftParams p, int step) {
+    __shared__ __align__(16) char smem[256];
+    phase_bprep(p, step, smem);
+}
+
+typedef void (*bg_kernel_t)(DraftParams, int);
+template <int PH>
+bg_kernel_t pick_na(int na) {
+    return na == 1 ? k_bgemv<PH, 1> : na == 2 ? k_bgemv<PH, 2> : k_bgemv<PH, 4>;
+}
+bg_kernel_t pick(int phase, int na) {
+    switch (phase) {
+    case BG_PROJ: return pick_na<BG_PROJ>(na);
+    case BG_QKV: return pick_na<BG_QKV>(na);
+    case BG_OPROJ: return pick_na<BG_OPROJ>(na);
+    case BG_GATEUP: return pick_na<BG_GATEUP>(na);
+    case BG_DOWN: return pick_na<BG_DOWN>(na);
+    default: return pick_na<BG_LMHEAD>(na);
+    }
+}
+int tiles_for(int nb) { return nb <= 16 ? 1 : nb <= 32 ? 2 : 4; }
+
+} // namespace
+
+size_t bgemv_lds_bytes(int rows_per_group) { return batch_lds_bytes(rows_per_group); }
+
+bool batch_allow_lds(size_t lds_limit) {
+    bool ok = true;
+    for (int ph = 0; ph < BG_COUNT; ++ph)
+        for (int na = 1; na <= 4; na *= 2)
+            ok = ok && hipFuncSetAttribute((const void *)pick(ph, na), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)lds_limit) == hipSuccess;
+    return ok;
+}
+
+void launch_bgemv(int phase, const DraftParams &p, int step, int grid, size_t lds, hipStream_t st) {
+    hipLaunchKernelGGL(pick(phase, tiles_for(p.nb)), dim3(grid), dim3(kBlock), lds, st, p, step);
+}
+
+void launch_bprep(const DraftParams &p, int step, hipStream_t st) {
+    hipLaunchKernelGGL(k_bprep, dim3(p.B), dim3(kBlock), 0, st, p, step);
+}
+
+} // namespace mtp

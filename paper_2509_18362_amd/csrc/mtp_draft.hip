@@ -13,6 +13,7 @@
 
 #include "phases.h"
 #include "fused.h"
+#include "batch_launch.h"
 
 using namespace mtp;
 
@@ -177,7 +178,23 @@ size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct WsLayout {
     size_t x, qkv, attn, o, gu, dn, hhat, err, bar, cand, rope_inv, attn_part, total;
+    // batched path (max_batch above kBatchMinSeq - 1 only)
+    size_t act0, act1, ssq, part, ticket, a_lo;
+    int a_stride;
 };
+
+// the batched path serves calls with this many sequences or more; fewer take the row-streaming kernels
+constexpr int kBatchMinSeq = 5;
+constexpr int kBatchPassSeq = 64;     // sequences per weight pass of the batched path
+constexpr int kBatchGroupTiles = 8;   // weight tiles per wave and group
+constexpr size_t kBatchTileBytes = 1024; // one 16 x 16 float tile of partial sums
+
+// virtual 16-row tiles of the widest batched phase (gate/up pairs count twice)
+size_t batch_max_tiles(const mtp_config &c) {
+    size_t qkv = ((size_t)(c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim + 15) / 16;
+    return std::max({(size_t)(c.vocab_size + 15) / 16, 2 * (((size_t)c.d_ffn + 15) / 16), qkv,
+                     ((size_t)c.d_model + 15) / 16});
+}
 WsLayout ws_layout(const mtp_config &c) {
     WsLayout l{};
     size_t mb = c.max_batch, d = c.d_model, qd = (size_t)c.n_q_heads * c.head_dim,
@@ -200,6 +217,19 @@ WsLayout ws_layout(const mtp_config &c) {
     l.cand = take((size_t)c.max_draft_steps * mb * kMaxFusedGrid * 8);
     l.rope_inv = take((size_t)c.head_dim / 2 * 8);
     l.attn_part = take(attn_part_floats(c) * 4);
+    if (c.max_batch >= kBatchMinSeq) {
+        size_t kmax = std::max({2 * d, qd, (size_t)c.d_ffn});
+        l.a_stride = (int)((kmax + 31) / 32 * 32);
+        l.a_lo = mb * (size_t)l.a_stride;
+        l.act0 = take(2 * l.a_lo * 2);
+        l.act1 = take(2 * l.a_lo * 2);
+        l.ssq = take((size_t)3 * mb * (d / 16) * 4);
+        // [reduction parts][tiles][sequence tiles]: split phases hold at most eight tiles per row group and at most
+        // kMaxFusedGrid workgroups, unsplit ones every tile once
+        size_t tiles = std::max(batch_max_tiles(c), (size_t)kBatchGroupTiles * kMaxFusedGrid);
+        l.part = take(tiles * (kBatchPassSeq / 16) * kBatchTileBytes);
+        l.ticket = take((size_t)kMaxFusedGrid * 4);
+    }
     l.total = off;
     return l;
 }
@@ -351,6 +381,10 @@ int32_t mtp_draft_init(mtp_handle **out, const mtp_config *cfg, const mtp_weight
                {(const void *)h->fused_fn, "k_fused"}};
     for (const auto &f : fns)
         if (ok) run(hipFuncSetAttribute(f.fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)h->lds_limit), f.name);
+    if (ok && cfg->max_batch >= kBatchMinSeq && !batch_allow_lds(h->lds_limit)) {
+        fprintf(stderr, "mtp_draft_init: raising the LDS limit of the batched kernels failed\n");
+        ok = false;
+    }
     if (ok) run(hipMemset(workspace, 0, lay.total), "workspace clear");
     if (ok) {
         std::vector<double> inv((size_t)cfg->head_dim / 2);
@@ -512,15 +546,95 @@ int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_inde
             return MTP_OK;
         }
     }
-    auto launch = [&](int phase, phase_kernel_t fn, int g, size_t lds, int step) {
+    auto mark_begin = [&](int phase, int step) {
         if (phase == tphase) (void)hipEventRecord(h->pev[2 * (size_t)step], st);
-        hipLaunchKernelGGL(fn, dim3(g), dim3(kBlock), lds, st, p, step);
+    };
+    auto mark_end = [&](int phase, int step) {
         if (phase == tphase) {
             (void)hipEventRecord(h->pev[2 * (size_t)step + 1], st);
             h->pev_used = step + 1;
         }
     };
+    auto launch = [&](int phase, phase_kernel_t fn, int g, size_t lds, int step) {
+        mark_begin(phase, step);
+        hipLaunchKernelGGL(fn, dim3(g), dim3(kBlock), lds, st, p, step);
+        mark_end(phase, step);
+    };
     if (h->timing == 1) (void)hipEventRecord(h->ev[0], st);
+
+    // Five or more sequences: the batched kernels, every weight read once per pass of up to 64 sequences.  Their
+    // buffer loads address a matrix with 32-bit offsets and mark missing rows with an offset of 2 GiB.
+    const size_t widest = std::max({(size_t)p.V * p.d, (size_t)p.d * 2 * p.d, (size_t)p.F * p.d, (size_t)p.qd * p.d}) * 2;
+    if (B >= kBatchMinSeq && h->mode == 0 && widest < ((size_t)1 << 31)) {
+        p.act[0] = reinterpret_cast<uint16_t *>(ws + l.act0);
+        p.act[1] = reinterpret_cast<uint16_t *>(ws + l.act1);
+        p.a_lo = l.a_lo;
+        p.a_stride = l.a_stride;
+        p.attn_split = p.act[0];
+        p.ssq = reinterpret_cast<float *>(ws + l.ssq);
+        p.part = reinterpret_cast<float *>(ws + l.part);
+        p.ticket = reinterpret_cast<int *>(ws + l.ticket);
+        size_t lds_bg[BG_COUNT];
+        // units: 16-row tiles (gate/up: pairs of tiles); kdim: reduction length
+        auto plan = [&](int ph, int units, int nmat, int kdim) {
+            const int nks = (kdim + 31) / 32;
+            int rg, kp = 1;
+            if ((long long)units * nmat >= 4ll * grid) {
+                rg = std::min(grid, units);
+            } else {
+                const int per_group = kBatchGroupTiles / nmat;
+                rg = std::min(grid, (units + per_group - 1) / per_group);
+                kp = std::max(1, std::min(grid / rg, nks / kWaves));
+            }
+            p.bg_rg[ph] = rg;
+            p.bg_kp[ph] = kp;
+            lds_bg[ph] = bgemv_lds_bytes(((units + rg - 1) / rg) * 16);
+        };
+        plan(BG_PROJ, p.d / 16, 1, 2 * p.d);
+        plan(BG_QKV, p.qkv_dim / 16, 1, p.d);
+        plan(BG_OPROJ, p.d / 16, 1, p.qd);
+        plan(BG_GATEUP, (p.F + 15) / 16, 2, p.d);
+        plan(BG_DOWN, p.d / 16, 1, p.F);
+        plan(BG_LMHEAD, (p.n + 15) / 16, 1, p.d);
+        for (int ph = 0; ph < BG_COUNT; ++ph)
+            if (lds_bg[ph] > h->lds_limit) return MTP_ERR_CONFIG;
+        p.head_grid = p.bg_rg[BG_LMHEAD];
+        auto matrix_phase = [&](int timed_as, int ph, int step) {
+            for (int b0 = 0; b0 < B; b0 += kBatchPassSeq) {
+                p.b0 = b0;
+                p.nb = std::min(kBatchPassSeq, B - b0);
+                launch_bgemv(ph, p, step, p.bg_rg[ph] * p.bg_kp[ph], lds_bg[ph], st);
+            }
+            mark_end(timed_as, step);
+        };
+        for (int step = 0; step < K; ++step) {
+            mark_begin(PH_PROJ, step);
+            launch_bprep(p, step, st);
+            matrix_phase(PH_PROJ, BG_PROJ, step);
+            mark_begin(PH_QKV, step);
+            matrix_phase(PH_QKV, BG_QKV, step);
+            mark_begin(PH_ATTN, step);
+            hipLaunchKernelGGL(h->attn_fn, dim3(attn_grid), dim3(kBlock), lds_attn, st, p, step);
+            if (p.max_splits > 1)
+                hipLaunchKernelGGL(h->merge_fn, dim3(merge_grid), dim3(kBlock), lds_merge, st, p, step);
+            mark_end(PH_ATTN, step);
+            mark_begin(PH_OPROJ, step);
+            matrix_phase(PH_OPROJ, BG_OPROJ, step);
+            mark_begin(PH_GATEUP, step);
+            matrix_phase(PH_GATEUP, BG_GATEUP, step);
+            mark_begin(PH_DOWN, step);
+            matrix_phase(PH_DOWN, BG_DOWN, step);
+            mark_begin(PH_LMHEAD, step);
+            matrix_phase(PH_LMHEAD, BG_LMHEAD, step);
+        }
+        launch_bprep(p, K, st);
+        if (h->timing == 1) {
+            (void)hipEventRecord(h->ev[1], st);
+            h->ev_recorded = true;
+        }
+        if (hipGetLastError() != hipSuccess) return MTP_ERR_HIP;
+        return MTP_OK;
+    }
     for (int step = 0; step < K; ++step) {
         launch(PH_PROJ, k_proj, grid, lds_proj, step);
         launch(PH_QKV, k_qkv, grid, lds_d1, step);

@@ -42,9 +42,22 @@ struct DraftParams {
     // launch plan
     int split_tokens, max_splits; // attention: tokens per split, splits per (sequence, KV head)
     int nb_proj, nb_d, nb_q, nb_down; // sequences staged in LDS per pass, by reduction length (2d, d, Hq*hd, F)
+    // batched path (five or more sequences): activations travel between the phases as bf16 hi + lo in global memory
+    uint16_t *act[2];    // two [max_batch][a_stride] hi arrays, each followed (a_lo elements later) by its lo array
+    size_t a_lo;
+    int a_stride;
+    uint16_t *attn_split; // where the attention phases also leave their result split (nullptr: they do not)
+    float *ssq;          // [3][max_batch][d/16] sums of squares over 16-row tiles of x, x1, x2
+    float *part;         // partial sums of the row groups, [KP][tiles][sequence tiles][64] x 4 floats
+    int *ticket;         // arrival counters of the row groups (zero between launches)
+    int b0, nb;          // sequences of this pass
+    int bg_rg[6], bg_kp[6]; // row groups and reduction parts of the six matrix phases
 };
 
 enum : int { kErrKvOverflow = 1, kErrTokenRange = 2, kErrBarrierTimeout = 4 };
+// matrix phases of the batched path, and the vectors whose sums of squares travel with them
+enum : int { BG_PROJ = 0, BG_QKV, BG_OPROJ, BG_GATEUP, BG_DOWN, BG_LMHEAD, BG_COUNT };
+enum : int { SSQ_X = 0, SSQ_X1, SSQ_X2, SSQ_COUNT };
 
 // ---------------------------------------------------------------------------------------------------
 // per-sequence state helpers
@@ -623,13 +636,17 @@ struct GemvLds {
     float *partial, *red;
     int kpad;
 };
+// Row stride of the staged activations: K rounded up to the MFMA depth, plus 16 bytes.  The sixteen lanes that read
+// the same 16-byte column of sixteen different sequences then hit sixteen different groups of four LDS banks; with a
+// stride that is a multiple of 256 bytes they would all hit the same group.
+__host__ __device__ inline int gemv_kpad(int K) { return (K + 31) / 32 * 32 + 8; }
 __host__ __device__ inline size_t gemv_lds_bytes(int K, int nb, int nmat) {
-    size_t kpad = (size_t)((K + 31) / 32) * 32;
+    size_t kpad = (size_t)gemv_kpad(K);
     return 2 * kpad * nb * sizeof(uint16_t) + (size_t)2 * kWaves * nmat * nb * 16 * sizeof(float) + 64;
 }
 __device__ inline GemvLds gemv_lds(char *smem, int K, int nb, int nmat) {
     GemvLds l;
-    l.kpad = ((K + 31) / 32) * 32;
+    l.kpad = gemv_kpad(K);
     l.hi = reinterpret_cast<uint16_t *>(smem);
     l.lo = l.hi + (size_t)l.kpad * nb;
     l.partial = reinterpret_cast<float *>(l.lo + (size_t)l.kpad * nb);
@@ -951,7 +968,15 @@ __device__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char
             }
             int hq = kvh * G + g;
             if (nsplit == 1) {
-                p.attn[(size_t)b * p.qd + (size_t)hq * HD + dd] = A / Ls;
+                const float r = A / Ls;
+                p.attn[(size_t)b * p.qd + (size_t)hq * HD + dd] = r;
+                if (p.attn_split) {
+                    uint16_t h, l;
+                    split_bf16(r, h, l);
+                    const size_t at = (size_t)b * p.a_stride + (size_t)hq * HD + dd;
+                    p.attn_split[at] = h;
+                    p.attn_split[p.a_lo + at] = l;
+                }
             } else {
                 float *dst = p.attn_part + (((size_t)b * p.Hq + hq) * S + sp) * PW;
                 dst[dd] = A;
@@ -1008,7 +1033,15 @@ __device__ void phase_attn_merge(const DraftParams &p, int step, int vb, int nvb
                 for (int u = 0; u < 16; ++u) A += t[u] * w[s2 + u];
             }
             for (; s2 < nsplit; ++s2) A += src[(size_t)s2 * PW + dd] * w[s2];
-            p.attn[(size_t)b * p.qd + (size_t)hq * HD + dd] = A * inv;
+            const float r = A * inv;
+            p.attn[(size_t)b * p.qd + (size_t)hq * HD + dd] = r;
+            if (p.attn_split) {
+                uint16_t h, l;
+                split_bf16(r, h, l);
+                const size_t at = (size_t)b * p.a_stride + (size_t)hq * HD + dd;
+                p.attn_split[at] = h;
+                p.attn_split[p.a_lo + at] = l;
+            }
         }
     }
 }
