@@ -1,0 +1,300 @@
+// Split-KV GQA attention of one new token over the draft cache on the matrix cores (gfx950), for long contexts
+// and batches: the vector-ALU version in phases.h spends about 130 instructions per four tokens and is
+// instruction-bound well below the HBM rate; here a wave spends that on thirty-two.
+//
+// Same work items, same outputs and same split partials as phase_attn (steps 5 and 6 of the draft step; Sec. 2.1: the
+// MTP head is one decoder layer, here with grouped-query attention over its own KV cache).  A wave takes 32 tokens
+// per iteration:
+//   S^T = K Q^T   16x16x32 MFMAs with the 16 tokens of a tile as rows and the query heads of the KV head as columns
+//                 (G of 16 used); K rows come straight from the cache (a lane holds HD/4 consecutive elements of its
+//                 token), the query sits in registers as bf16 hi + lo, pre-multiplied by log2(e)/sqrt(HD).
+//   online softmax in the MFMA result layout: a lane holds 2 x 4 tokens of ONE head column, so the running maximum,
+//                 the rescale factor and the running sum are per-lane scalars; the maximum of a step is combined
+//                 over the four lane groups of a column with two shuffles.
+//   O^T += V^T P  with the 16 dimensions of a block as rows and the heads as columns, contraction over the 32 tokens.
+//                 The eight probabilities a lane just computed are exactly the eight contraction elements the P
+//                 operand wants from it (tokens 4g..4g+3 of both tiles: the assignment of tokens to MFMA depth slots
+//                 is free as long as both operands agree), split into bf16 hi + lo.  V has to be transposed: the
+//                 wave parks its 32 V rows in a private LDS strip (row stride HD*2 + 16 bytes, which spreads the
+//                 four lane groups over different banks) and gathers eight 16-bit values per lane and block.
+// Loads of the next iteration (16 KiB per wave) are in flight while the current one is computed.
+#pragma once
+#include "phases.h"
+
+namespace mtp {
+
+template <int G, int HD>
+struct AttnMfmaLds {
+    static constexpr int VS = HD * 2 + 16;  // bytes per parked V row
+    static constexpr int NSTREAM = kWaves + 1; // one softmax stream per wave, one for the token being appended
+    float q[G][HD];
+    float cs[HD / 2], sn[HD / 2];
+    float knew[HD], vnew[HD];
+    float acc[NSTREAM][G][HD];
+    float ml[NSTREAM][G][2];
+    alignas(16) unsigned char v[kWaves][32][VS];
+};
+
+template <int G, int HD>
+__device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb, char *smem) {
+    using L = AttnMfmaLds<G, HD>;
+    constexpr int NS = HD / 32;        // MFMA depth steps over the head dimension
+    constexpr int NDB = HD / 16;       // 16-dimension blocks of the output
+    constexpr int LPT = HD / 8;        // lanes per V row in a wave-wide load
+    constexpr int TPI = kWave / LPT;   // V rows per wave-wide load
+    constexpr int NV = 32 / TPI;       // loads per lane for the 32 V rows of an iteration
+    constexpr int NSTREAM = L::NSTREAM;
+    constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
+    L &s = *reinterpret_cast<L *>(smem);
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const int i16 = lane & 15, g4 = lane >> 4;
+    const int T = p.split_tokens, S = p.max_splits;
+    const int n_items = p.B * p.Hkv * S;
+    const float scale = 1.0f / sqrtf((float)HD);
+    const int PW = HD + 2; // floats per (head, split) partial: acc[HD], max, sum
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+
+    for (int item = vb; item < n_items; item += nvb) {
+        const int b = item / (p.Hkv * S), rem = item % (p.Hkv * S), kvh = rem / S, sp = rem % S;
+        const bool dead = seq_dead(p, b);
+        const int Lb = dead ? 0 : p.kv_len[b];
+        const int len = Lb + step + 1, pnew = len - 1;
+        const int nsplit = (len + T - 1) / T;
+        if (sp >= nsplit) continue; // uniform for the workgroup
+        const int t0 = sp * T, t1 = min(t0 + T, len);
+        const bool last = (sp == nsplit - 1);
+        const int ntok = last ? (t1 - 1 - t0) : (t1 - t0); // slots read from the cache; the new token comes from qkv
+        const uint16_t *kc = p.k_cache + (((size_t)b * p.Hkv + kvh) * p.cap + t0) * HD;
+        const uint16_t *vc = p.v_cache + (((size_t)b * p.Hkv + kvh) * p.cap + t0) * HD;
+        const float *qkv = p.qkv + (size_t)b * p.qkv_dim;
+        const int niter = (ntok + 31) / 32;
+
+        u32x4 kn[2][NS], vr[NV];
+        auto load_iter = [&](int it) {
+#pragma unroll
+            for (int tl = 0; tl < 2; ++tl) {
+                const int tok = min(it * 32 + tl * 16 + i16, ntok - 1); // rows past the end repeat the last one
+                const uint16_t *src = kc + (size_t)tok * HD + g4 * (HD / 4);
+#pragma unroll
+                for (int u = 0; u < NS; ++u) kn[tl][u] = ldg16(src + u * 8);
+            }
+#pragma unroll
+            for (int u = 0; u < NV; ++u) {
+                const int tok = min(it * 32 + u * TPI + lane / LPT, ntok - 1);
+                vr[u] = ldg16(vc + (size_t)tok * HD + (lane % LPT) * 8);
+            }
+        };
+        if (wave < niter) load_iter(wave); // in flight while q, the rotary table and the new key/value are prepared
+
+        __syncthreads(); // LDS of the previous item is free
+        if (tid < HD / 2) rope_cos_sin(pnew, p.rope_inv[tid], s.cs[tid], s.sn[tid]);
+        __syncthreads();
+        for (int idx = tid; idx < G * HD / 2; idx += kBlock) {
+            int gq = idx / (HD / 2), jj = idx % (HD / 2);
+            const float *src = qkv + (size_t)(kvh * G + gq) * HD;
+            float a = src[jj], bb = src[jj + HD / 2], cs = s.cs[jj], sn = s.sn[jj];
+            if (p.b_q) {
+                a += bf16_to_f32(p.b_q[(kvh * G + gq) * HD + jj]);
+                bb += bf16_to_f32(p.b_q[(kvh * G + gq) * HD + jj + HD / 2]);
+            }
+            s.q[gq][jj] = (a * cs - bb * sn) * scale;
+            s.q[gq][jj + HD / 2] = (bb * cs + a * sn) * scale;
+        }
+        if (last) {
+            uint16_t *kdst = p.k_cache + (((size_t)b * p.Hkv + kvh) * p.cap + pnew) * HD;
+            uint16_t *vdst = p.v_cache + (((size_t)b * p.Hkv + kvh) * p.cap + pnew) * HD;
+            if (tid >= kWave * 4 && tid < kWave * 4 + HD / 2) {
+                int e = tid - kWave * 4;
+                const float *src = qkv + p.qd + (size_t)kvh * HD;
+                float a = src[e], bb = src[e + HD / 2], cs = s.cs[e], sn = s.sn[e];
+                if (p.b_k) {
+                    a += bf16_to_f32(p.b_k[kvh * HD + e]);
+                    bb += bf16_to_f32(p.b_k[kvh * HD + e + HD / 2]);
+                }
+                uint16_t r0 = f32_to_bf16(a * cs - bb * sn), r1 = f32_to_bf16(bb * cs + a * sn);
+                s.knew[e] = bf16_to_f32(r0);
+                s.knew[e + HD / 2] = bf16_to_f32(r1);
+                if (!dead) {
+                    kdst[e] = r0;
+                    kdst[e + HD / 2] = r1;
+                }
+            } else if (tid >= kWave * 6 && tid < kWave * 6 + HD) {
+                int e = tid - kWave * 6;
+                float vraw = qkv[p.qd + p.kvd + (size_t)kvh * HD + e];
+                if (p.b_v) vraw += bf16_to_f32(p.b_v[kvh * HD + e]);
+                uint16_t r = f32_to_bf16(vraw);
+                s.vnew[e] = bf16_to_f32(r);
+                if (!dead) vdst[e] = r;
+            }
+        }
+        __syncthreads();
+
+        // the query operand: column i16 = query head, depth slot g4 holds elements g4*HD/4 + 8u .. +8 for step u
+        u32x4 qh[NS], ql[NS];
+#pragma unroll
+        for (int u = 0; u < NS; ++u) {
+            uint32_t h[4] = {0u, 0u, 0u, 0u}, l[4] = {0u, 0u, 0u, 0u};
+            if (i16 < G) {
+                const float *src = &s.q[i16 < G ? i16 : 0][g4 * (HD / 4) + u * 8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    uint16_t hh, ll;
+                    split_bf16(src[e] * kLog2e, hh, ll);
+                    h[e >> 1] |= (uint32_t)hh << ((e & 1) * 16);
+                    l[e >> 1] |= (uint32_t)ll << ((e & 1) * 16);
+                }
+            }
+            qh[u] = u32x4{h[0], h[1], h[2], h[3]};
+            ql[u] = u32x4{l[0], l[1], l[2], l[3]};
+        }
+
+        float mx = -INFINITY, lsum = 0.f; // of head column i16, in units of log2
+        f32x4 oacc[NDB];
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) oacc[db] = f32x4{0.f, 0.f, 0.f, 0.f};
+        unsigned char *vrow = &s.v[wave][0][0];
+
+        for (int it = wave; it < niter; it += kWaves) {
+            // park the V rows, then request the next iteration's rows into the same registers
+#pragma unroll
+            for (int u = 0; u < NV; ++u)
+                *reinterpret_cast<u32x4 *>(vrow + (size_t)(u * TPI + lane / LPT) * L::VS + (lane % LPT) * 16) = vr[u];
+            u32x4 kcur[2][NS];
+#pragma unroll
+            for (int tl = 0; tl < 2; ++tl)
+#pragma unroll
+                for (int u = 0; u < NS; ++u) kcur[tl][u] = kn[tl][u];
+            if (it + kWaves < niter) load_iter(it + kWaves);
+
+            // scores of 2 x 16 tokens against the G heads
+            f32x4 sc[2];
+#pragma unroll
+            for (int tl = 0; tl < 2; ++tl) {
+                f32x4 a = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int u = 0; u < NS; ++u) {
+                    a = mfma16(kcur[tl][u], qh[u], a);
+                    a = mfma16(kcur[tl][u], ql[u], a);
+                }
+                sc[tl] = a;
+            }
+            float sv[8] = {sc[0].x, sc[0].y, sc[0].z, sc[0].w, sc[1].x, sc[1].y, sc[1].z, sc[1].w};
+            float tmax = -INFINITY;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int tok = it * 32 + (e >> 2) * 16 + g4 * 4 + (e & 3);
+                sv[e] = tok < ntok ? sv[e] : -INFINITY;
+                tmax = fmaxf(tmax, sv[e]);
+            }
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 16, kWave));
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, kWave));
+            const float mnew = fmaxf(mx, tmax); // finite: an iteration holds at least one token
+            const float alpha = (mx == mnew) ? 1.0f : __builtin_amdgcn_exp2f(mx - mnew);
+            mx = mnew;
+            float pv[8], psum = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                pv[e] = sv[e] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(sv[e] - mnew);
+                psum += pv[e];
+            }
+            lsum = lsum * alpha + psum;
+            uint32_t ph[4], pl[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                uint16_t h0, l0, h1, l1;
+                split_bf16(pv[2 * e], h0, l0);
+                split_bf16(pv[2 * e + 1], h1, l1);
+                ph[e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+                pl[e] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+            }
+            const u32x4 pH = {ph[0], ph[1], ph[2], ph[3]}, pL = {pl[0], pl[1], pl[2], pl[3]};
+
+            // the parked rows were written by this wave's own lanes; LDS operations of a wave complete in order
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int db = 0; db < NDB; ++db) {
+                // rows = dimensions db*16 + i16; depth slot g4, element e = token 4 g4 + e (e < 4) or 16 + 4 g4 + e - 4
+                const unsigned char *col = vrow + (db * 16 + i16) * 2;
+                uint32_t w[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int ta = (e < 2 ? 0 : 16) + g4 * 4 + (2 * e & 3), tb = ta + 1;
+                    const uint32_t a = *reinterpret_cast<const uint16_t *>(col + (size_t)ta * L::VS);
+                    const uint32_t c = *reinterpret_cast<const uint16_t *>(col + (size_t)tb * L::VS);
+                    w[e] = a | (c << 16);
+                }
+                const u32x4 va = {w[0], w[1], w[2], w[3]};
+                f32x4 o = oacc[db] * alpha;
+                o = mfma16(va, pH, o);
+                o = mfma16(va, pL, o);
+                oacc[db] = o;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
+
+        // ---- merge the waves (and the token being appended) through LDS ----
+        lsum += __shfl_xor(lsum, 16, kWave);
+        lsum += __shfl_xor(lsum, 32, kWave);
+        if (i16 < G) {
+#pragma unroll
+            for (int db = 0; db < NDB; ++db) {
+                const float o[4] = {oacc[db].x, oacc[db].y, oacc[db].z, oacc[db].w};
+#pragma unroll
+                for (int v = 0; v < 4; ++v) s.acc[wave][i16][db * 16 + g4 * 4 + v] = o[v];
+            }
+            if (g4 == 0) {
+                s.ml[wave][i16][0] = mx * kLn2;
+                s.ml[wave][i16][1] = lsum;
+            }
+        }
+        if (wave < G) { // stream kWaves: the new token, score q . k_new from LDS
+            float a = 0.f;
+            for (int e = lane; e < HD; e += kWave) a += s.q[wave][e] * s.knew[e];
+            a = wave_sum(a);
+            if (lane == 0) {
+                s.ml[kWaves][wave][0] = last ? a : -INFINITY;
+                s.ml[kWaves][wave][1] = 1.0f;
+            }
+            for (int e = lane; e < HD; e += kWave) s.acc[kWaves][wave][e] = last ? s.vnew[e] : 0.f;
+        }
+        __syncthreads();
+        for (int o = tid; o < G * HD; o += kBlock) {
+            int g = o / HD, dd = o % HD;
+            float M = -INFINITY;
+            for (int st = 0; st < NSTREAM; ++st) M = fmaxf(M, s.ml[st][g][0]);
+            float Ls = 0.f, A = 0.f;
+            for (int st = 0; st < NSTREAM; ++st) {
+                float mm = s.ml[st][g][0];
+                if (mm != -INFINITY) {
+                    float w = expf(mm - M);
+                    Ls += s.ml[st][g][1] * w;
+                    A += s.acc[st][g][dd] * w;
+                }
+            }
+            int hq = kvh * G + g;
+            if (nsplit == 1) {
+                const float r = A / Ls;
+                p.attn[(size_t)b * p.qd + (size_t)hq * HD + dd] = r;
+                if (p.attn_split) {
+                    uint16_t h, l;
+                    split_bf16(r, h, l);
+                    const size_t at = (size_t)b * p.a_stride + (size_t)hq * HD + dd;
+                    p.attn_split[at] = h;
+                    p.attn_split[p.a_lo + at] = l;
+                }
+            } else {
+                float *dst = p.attn_part + (((size_t)b * p.Hq + hq) * S + sp) * PW;
+                dst[dd] = A;
+                if (dd == 0) {
+                    dst[HD] = M;
+                    dst[HD + 1] = Ls;
+                }
+            }
+        }
+    }
+}
+
+} // namespace mtp

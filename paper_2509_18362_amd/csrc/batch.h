@@ -30,8 +30,8 @@ constexpr uint32_t kOobOffset = 0x80000000u;
 template <int NA>
 struct BatchShape {
     static constexpr int TG = kBatchAcc / NA;   // weight tiles per group
-    static constexpr int D = NA == 1 ? 3 : 4;   // items (one depth step of a group) in flight per wave
-    static constexpr int NL = TG + 2 * NA;      // 16-byte loads per lane per item
+    static constexpr int D = 2;                 // items (one double depth step of a group) in flight per wave
+    static constexpr int NL = 2 * TG + 4 * NA;  // 16-byte loads per lane per item
 };
 
 __host__ __device__ inline size_t batch_lds_bytes(int max_rows_per_wg) {
@@ -83,11 +83,14 @@ __device__ __forceinline__ void bgemv(const DraftParams &p, Ph &ph, int RG, int 
     const int u0 = (int)((long long)rg * units / RG), u1 = (int)((long long)(rg + 1) * units / RG);
     const int vt0 = u0 * NMAT, nvt = (u1 - u0) * NMAT, ntv = units * NMAT;
     const int ngroups = (nvt + TG - 1) / TG;
-    const int nks = (K + 31) / 32;
+    // The reduction runs in double steps of 64 elements (128 bytes of a row): lane (j, g) holds bytes 32g .. 32g+32 of
+    // the piece, of row j (weights) or sequence j (activations); its first 16 bytes feed one MFMA, the other 16 the
+    // next - any assignment of elements to MFMA depth slots is fine as long as both operands use the same one.  Two
+    // loads of a lane are neighbours, so a wave always consumes whole 128-byte lines.  Double steps are dealt to the
+    // waves round robin: at any time the eight waves read eight neighbouring pieces of every row, 1 KiB in a row.
+    const int nks = (K + 63) / 64;
     const int ksA = (int)((long long)kp * nks / KP), ksB = (int)((long long)(kp + 1) * nks / KP);
     const int per = max((ksB - ksA + kWaves - 1) / kWaves, 1); // items per group, the same for every wave
-    // depth steps are dealt to the waves round robin: at any time the eight waves of the workgroup read eight
-    // neighbouring 64-byte pieces of every row, 512 contiguous bytes
     const int total = ngroups * per;
 
     f32x4 *partial = reinterpret_cast<f32x4 *>(smem);                           // [2][kWaves][kBatchAcc][kWave]
@@ -102,13 +105,13 @@ __device__ __forceinline__ void bgemv(const DraftParams &p, Ph &ph, int RG, int 
         __syncthreads();
     }
 
-    // activations: one descriptor over the hi and lo arrays; lane (j, g) reads sequence at*16 + j, elements 8g..8g+8
+    // activations: one descriptor over the hi and lo arrays; lane (j, g) reads sequence at*16 + j
     const size_t lo_bytes = p.a_lo * 2;
     const row_rsrc ar = make_row_rsrc(ph.in, (int)(2 * lo_bytes));
     int voff_a[NA];
 #pragma unroll
     for (int at = 0; at < NA; ++at)
-        voff_a[at] = (int)((size_t)min(p.b0 + at * 16 + j, p.B - 1) * p.a_stride * 2 + g * 16);
+        voff_a[at] = (int)((size_t)min(p.b0 + at * 16 + j, p.B - 1) * p.a_stride * 2 + g * 32);
 
     row_rsrc wr[TG];
     int voff_w[TG];
@@ -123,20 +126,25 @@ __device__ __forceinline__ void bgemv(const DraftParams &p, Ph &ph, int RG, int 
             const int r = row0 + j;
             const bool ok = t < nvt && r < row_end;
             const int phys = Ph::GATHER ? ids_lds[(min(t, nvt - 1) / NMAT) * 16 + j] : r;
-            voff_w[ts] = ok ? (int)((size_t)phys * K * 2 + g * 16) : (int)kOobOffset;
+            voff_w[ts] = ok ? (int)((size_t)phys * K * 2 + g * 32) : (int)kOobOffset;
         }
     };
     u32x4 ring[D][NL];
     int ig = 0, ik = 0; // next item to request: group, and which of this wave's depth steps
     auto issue = [&](u32x4(&slot)[NL]) {
         const int ks = min(ksA + ik * kWaves + wave, nks - 1);
-        const int soff = min(ks * 32, K - 32) * 2; // the last, ragged step is shifted left to stay inside the row
+        const int soff = min(ks * 64, K - 64) * 2; // the last, ragged step is shifted left to stay inside the row
 #pragma unroll
-        for (int ts = 0; ts < TG; ++ts) slot[ts] = row_load16<Ph::STREAM>(wr[ts], voff_w[ts], soff);
+        for (int ts = 0; ts < TG; ++ts) {
+            slot[2 * ts] = row_load16<Ph::STREAM>(wr[ts], voff_w[ts], soff);
+            slot[2 * ts + 1] = row_load16<Ph::STREAM>(wr[ts], voff_w[ts] + 16, soff);
+        }
 #pragma unroll
         for (int at = 0; at < NA; ++at) {
-            slot[TG + 2 * at] = row_load16<false>(ar, voff_a[at], soff);
-            slot[TG + 2 * at + 1] = row_load16<false>(ar, voff_a[at], soff + (int)lo_bytes);
+            slot[2 * TG + 4 * at] = row_load16<false>(ar, voff_a[at], soff);
+            slot[2 * TG + 4 * at + 1] = row_load16<false>(ar, voff_a[at] + 16, soff);
+            slot[2 * TG + 4 * at + 2] = row_load16<false>(ar, voff_a[at], soff + (int)lo_bytes);
+            slot[2 * TG + 4 * at + 3] = row_load16<false>(ar, voff_a[at] + 16, soff + (int)lo_bytes);
         }
         if (++ik == per) {
             ik = 0;
@@ -163,19 +171,22 @@ __device__ __forceinline__ void bgemv(const DraftParams &p, Ph &ph, int RG, int 
             if (n0 + s < total) { // uniform
                 const int ksn = ksA + ck * kWaves + wave;
                 const int ks = min(ksn, nks - 1);
-                const int koff = min(ks * 32, K - 32);
-                // lanes whose eight elements were already counted by the step before (ragged end), or all lanes of a
-                // step beyond this wave's range, contribute zeros
-                const int cut = ksn < ksB ? (ks * 32 - koff) / 8 : 4;
-                const bool dead = g < cut;
+                const int koff = min(ks * 64, K - 64);
+                // 8-element pieces that were already counted by the step before (ragged end), or all pieces of a
+                // step beyond the workgroup's range, contribute zeros
+                const int cut = ksn < ksB ? (ks * 64 - koff) / 8 : 8;
 #pragma unroll
-                for (int at = 0; at < NA; ++at) {
-                    const u32x4 ah = dead ? zero4 : ring[s][TG + 2 * at];
-                    const u32x4 al = dead ? zero4 : ring[s][TG + 2 * at + 1];
+                for (int hf = 0; hf < 2; ++hf) {
+                    const bool dead = g * 2 + hf < cut;
 #pragma unroll
-                    for (int ts = 0; ts < TG; ++ts) {
-                        acc[ts * NA + at] = mfma16(ah, ring[s][ts], acc[ts * NA + at]);
-                        acc[ts * NA + at] = mfma16(al, ring[s][ts], acc[ts * NA + at]);
+                    for (int at = 0; at < NA; ++at) {
+                        const u32x4 ah = dead ? zero4 : ring[s][2 * TG + 4 * at + hf];
+                        const u32x4 al = dead ? zero4 : ring[s][2 * TG + 4 * at + 2 + hf];
+#pragma unroll
+                        for (int ts = 0; ts < TG; ++ts) {
+                            acc[ts * NA + at] = mfma16(ah, ring[s][2 * ts + hf], acc[ts * NA + at]);
+                            acc[ts * NA + at] = mfma16(al, ring[s][2 * ts + hf], acc[ts * NA + at]);
+                        }
                     }
                 }
                 if (n0 + s + D < total) issue(ring[s]);

@@ -1,6 +1,7 @@
 // Kernels of the batched draft path (five or more sequences per call) for gfx950.
 #include <hip/hip_runtime.h>
 
+#include "attn_mfma.h"
 #include "batch.h"
 #include "batch_launch.h"
 
@@ -36,7 +37,31 @@ __global__ __launch_bounds__(kBlock) void k_bprep(DraftParams p, int step) {
     phase_bprep(p, step, smem);
 }
 
+template <int G, int HD>
+__global__ __launch_bounds__(kBlock) void k_attn_mfma(DraftParams p, int step) {
+    extern __shared__ __align__(16) char smem[];
+    phase_attn_mfma<G, HD>(p, step, blockIdx.x, gridDim.x, smem);
+}
+
 typedef void (*bg_kernel_t)(DraftParams, int);
+bg_kernel_t attn_mfma_kernel(int G, int HD) {
+    if (HD == 128) {
+        switch (G) {
+        case 1: return k_attn_mfma<1, 128>;
+        case 2: return k_attn_mfma<2, 128>;
+        case 4: return k_attn_mfma<4, 128>;
+        case 8: return k_attn_mfma<8, 128>;
+        }
+    } else if (HD == 64) {
+        switch (G) {
+        case 1: return k_attn_mfma<1, 64>;
+        case 2: return k_attn_mfma<2, 64>;
+        case 4: return k_attn_mfma<4, 64>;
+        case 8: return k_attn_mfma<8, 64>;
+        }
+    }
+    return nullptr;
+}
 template <int PH>
 bg_kernel_t pick_na(int na) {
     return na == 1 ? k_bgemv<PH, 1> : na == 2 ? k_bgemv<PH, 2> : k_bgemv<PH, 4>;
@@ -57,8 +82,30 @@ int tiles_for(int nb) { return nb <= 16 ? 1 : nb <= 32 ? 2 : 4; }
 
 size_t bgemv_lds_bytes(int rows_per_group) { return batch_lds_bytes(rows_per_group); }
 
+size_t attn_mfma_lds_bytes(int G, int HD) {
+    switch (HD * 16 + G) {
+    case 128 * 16 + 1: return sizeof(AttnMfmaLds<1, 128>);
+    case 128 * 16 + 2: return sizeof(AttnMfmaLds<2, 128>);
+    case 128 * 16 + 4: return sizeof(AttnMfmaLds<4, 128>);
+    case 128 * 16 + 8: return sizeof(AttnMfmaLds<8, 128>);
+    case 64 * 16 + 1: return sizeof(AttnMfmaLds<1, 64>);
+    case 64 * 16 + 2: return sizeof(AttnMfmaLds<2, 64>);
+    case 64 * 16 + 4: return sizeof(AttnMfmaLds<4, 64>);
+    case 64 * 16 + 8: return sizeof(AttnMfmaLds<8, 64>);
+    }
+    return 0;
+}
+
+void launch_attn_mfma(int G, int HD, const DraftParams &p, int step, int grid, size_t lds, hipStream_t st) {
+    hipLaunchKernelGGL(attn_mfma_kernel(G, HD), dim3(grid), dim3(kBlock), lds, st, p, step);
+}
+
 bool batch_allow_lds(size_t lds_limit) {
     bool ok = true;
+    for (int hd = 64; hd <= 128; hd *= 2)
+        for (int g = 1; g <= 8; g *= 2)
+            ok = ok && hipFuncSetAttribute((const void *)attn_mfma_kernel(g, hd),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_limit) == hipSuccess;
     for (int ph = 0; ph < BG_COUNT; ++ph)
         for (int na = 1; na <= 4; na *= 2)
             ok = ok && hipFuncSetAttribute((const void *)pick(ph, na), hipFuncAttributeMaxDynamicSharedMemorySize,

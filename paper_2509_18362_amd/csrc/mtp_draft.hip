@@ -134,6 +134,7 @@ size_t attn_lds_bytes(int G, int HD) {
 // ---- plan: how a call of B sequences is cut up ----------------------------------------------------------
 constexpr int kTargetAttnItems = 1024; // (sequence, KV head, split) items aimed for
 constexpr int kMinSplitTokens = 128;
+constexpr int kMfmaAttnMinSplit = 256; // splits of at least this many tokens use the matrix-core attention
 constexpr size_t kLdsSmallBatch = 72 * 1024;  // two workgroups per CU
 constexpr size_t kLdsLargeBatch = 150 * 1024; // one workgroup per CU, more sequences per weight pass
 
@@ -381,8 +382,8 @@ int32_t mtp_draft_init(mtp_handle **out, const mtp_config *cfg, const mtp_weight
                {(const void *)h->fused_fn, "k_fused"}};
     for (const auto &f : fns)
         if (ok) run(hipFuncSetAttribute(f.fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)h->lds_limit), f.name);
-    if (ok && cfg->max_batch >= kBatchMinSeq && !batch_allow_lds(h->lds_limit)) {
-        fprintf(stderr, "mtp_draft_init: raising the LDS limit of the batched kernels failed\n");
+    if (ok && !batch_allow_lds(h->lds_limit)) {
+        fprintf(stderr, "mtp_draft_init: raising the LDS limit of the batched and matrix-core attention kernels failed\n");
         ok = false;
     }
     if (ok) run(hipMemset(workspace, 0, lay.total), "workspace clear");
@@ -499,7 +500,8 @@ int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_inde
     const size_t lds_proj = gemv_lds_bytes(2 * p.d, p.nb_proj, 1), lds_d1 = gemv_lds_bytes(p.d, p.nb_d, 1),
                  lds_d2 = gemv_lds_bytes(p.d, p.nb_d, 2), lds_q = gemv_lds_bytes(p.qd, p.nb_q, 1),
                  lds_down = gemv_lds_bytes(p.F, p.nb_down, 1),
-                 lds_attn = std::max(attn_lds_bytes(p.Hq / p.Hkv, p.hd), (size_t)kWaves * p.max_splits * 4 + 64),
+                 lds_attn = std::max({attn_lds_bytes(p.Hq / p.Hkv, p.hd), attn_mfma_lds_bytes(p.Hq / p.Hkv, p.hd) + 64,
+                                      (size_t)kWaves * p.max_splits * 4 + 64}),
                  lds_merge = (size_t)kWaves * p.max_splits * 4 + 64;
     const size_t lds_max = std::max({lds_proj, lds_d2, lds_q, lds_down, lds_attn});
     if (lds_max > h->lds_limit) return MTP_ERR_CONFIG;
@@ -555,6 +557,15 @@ int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_inde
             h->pev_used = step + 1;
         }
     };
+    // long splits go to the matrix-core attention; short ones (small batch, short context) to the latency-lean
+    // vector version
+    const bool mfma_attn = p.split_tokens >= kMfmaAttnMinSplit;
+    auto launch_attention = [&](int step) {
+        if (mfma_attn)
+            launch_attn_mfma(p.Hq / p.Hkv, p.hd, p, step, attn_grid, lds_attn, st);
+        else
+            hipLaunchKernelGGL(h->attn_fn, dim3(attn_grid), dim3(kBlock), lds_attn, st, p, step);
+    };
     auto launch = [&](int phase, phase_kernel_t fn, int g, size_t lds, int step) {
         mark_begin(phase, step);
         hipLaunchKernelGGL(fn, dim3(g), dim3(kBlock), lds, st, p, step);
@@ -577,7 +588,7 @@ int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_inde
         size_t lds_bg[BG_COUNT];
         // units: 16-row tiles (gate/up: pairs of tiles); kdim: reduction length
         auto plan = [&](int ph, int units, int nmat, int kdim) {
-            const int nks = (kdim + 31) / 32;
+            const int nks = (kdim + 63) / 64; // double depth steps; every wave of a workgroup should get one
             int rg, kp = 1;
             if ((long long)units * nmat >= 4ll * grid) {
                 rg = std::min(grid, units);
@@ -614,7 +625,7 @@ int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_inde
             mark_begin(PH_QKV, step);
             matrix_phase(PH_QKV, BG_QKV, step);
             mark_begin(PH_ATTN, step);
-            hipLaunchKernelGGL(h->attn_fn, dim3(attn_grid), dim3(kBlock), lds_attn, st, p, step);
+            launch_attention(step);
             if (p.max_splits > 1)
                 hipLaunchKernelGGL(h->merge_fn, dim3(merge_grid), dim3(kBlock), lds_merge, st, p, step);
             mark_end(PH_ATTN, step);
@@ -638,7 +649,9 @@ int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_inde
     for (int step = 0; step < K; ++step) {
         launch(PH_PROJ, k_proj, grid, lds_proj, step);
         launch(PH_QKV, k_qkv, grid, lds_d1, step);
-        launch(PH_ATTN, h->attn_fn, attn_grid, lds_attn, step);
+        mark_begin(PH_ATTN, step);
+        launch_attention(step);
+        mark_end(PH_ATTN, step);
         if (p.max_splits > 1) launch(PH_MERGE, h->merge_fn, merge_grid, lds_merge, step);
         launch(PH_OPROJ, k_oproj, grid, lds_q, step);
         launch(PH_GATEUP, k_gateup, grid, lds_d2, step);

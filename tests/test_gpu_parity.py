@@ -120,6 +120,18 @@ def test_tiny_ragged_batch_and_empty_context(gpu, tiny):
     check_chain(ref, res, caches, act["kv_len"], 3)
 
 
+def test_tiny_long_capacity_matrix_core_attention(gpu, tiny):
+    """A large cache capacity makes the split plan long enough for the matrix-core attention kernel (448 tokens per
+    split here) and, with seven sequences, for the batched matrix phases.  Contexts cover: nothing cached, fewer
+    tokens than one 16-row tile, exactly one 32-token iteration, one more, several iterations per wave, and several
+    splits (merged by the second kernel)."""
+    wl = tiny["wl"]
+    ctx = np.array([0, 1, 31, 32, 33, 300, 1000], dtype=np.int32)
+    act = synth.make_activations(wl, ctx=ctx, capacity=32768)
+    ref, res, caches = run_both(gpu, tiny["shape"], tiny["w"], tiny["w"], act, [tiny["ids"]], 0, 3)
+    check_chain(ref, res, caches, act["kv_len"], 3)
+
+
 def test_tiny_full_vocab_equals_identity_subset(gpu, tiny):
     """Eq. (3) with the identity list is the full head: same logits bit for bit on the device as well."""
     act = tiny["act"]
