@@ -132,7 +132,7 @@ size_t attn_lds_bytes(int G, int HD) {
 }
 
 // ---- plan: how a call of B sequences is cut up ----------------------------------------------------------
-constexpr int kTargetAttnItems = 512; // (sequence, KV head, split) items aimed for
+constexpr int kTargetAttnItems = 256; // (sequence, KV head, split) items aimed for
 constexpr int kMinSplitTokens = 128;
 constexpr int kMfmaAttnMinSplit = 256; // splits of at least this many tokens use the matrix-core attention
 constexpr size_t kLdsSmallBatch = 72 * 1024;  // two workgroups per CU
