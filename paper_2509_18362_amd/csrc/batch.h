@@ -59,6 +59,58 @@ __device__ __forceinline__ void batch_scales(const DraftParams &p, int kind, flo
     if (sub == 0 && bl < kBatchMaxSeq) scale_lds[bl] = bl < p.nb ? 1.0f / sqrtf(s / (float)p.d + p.eps) : 0.f;
 }
 
+// Adds the KP parts of one epilogue slot (virtual tile vt, or the pair starting there, and sequence tile at) in the
+// order of the parts and hands the sums to the phase's epilogue.  Called by whole waves.
+template <int NA, class Ph>
+__device__ __forceinline__ void bg_slot_epilogue(const DraftParams &p, Ph &ph, int KP, int ntv, int vt, int at,
+                                                 const float *scale_lds) {
+    constexpr int NMAT = Ph::NMAT;
+    const int lane = threadIdx.x & (kWave - 1), j = lane & 15, g = lane >> 4;
+    f32x4 sums[NMAT];
+#pragma unroll
+    for (int m = 0; m < NMAT; ++m) {
+        const float *src = p.part + (((size_t)(vt + m) * NA + at) * kWave + lane) * 4;
+        const size_t kstride = (size_t)ntv * NA * kWave * 4;
+        f32x4 sacc = {0.f, 0.f, 0.f, 0.f};
+        for (int k2 = 0; k2 < KP; k2 += 8) { // eight loads in flight
+            f32x4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                v[u] = *reinterpret_cast<const f32x4 *>(src + (size_t)min(k2 + u, KP - 1) * kstride);
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (k2 + u < KP) sacc += v[u];
+        }
+        sums[m] = sacc;
+    }
+    ph.epi(at * 16 + g * 4, vt, j, sums, scale_lds);
+}
+
+// The end of a matrix phase: the workgroup's sums are in the partial buffer.  The last workgroup of the row group to
+// arrive adds the KP parts in the order of the parts and runs the epilogue (KP = 1: no ticket).  slots(f) calls
+// f(t, at) for every (first virtual tile relative to vt0, sequence tile) the calling WAVE is responsible for.
+template <int NA, class Ph, class Slots>
+__device__ __forceinline__ void bg_tail(const DraftParams &p, Ph &ph, int KP, int rg, int ntv, int vt0, char *smem,
+                                        const float *scale_lds, Slots slots) {
+    __syncthreads(); // every store of this workgroup's sums has completed
+    if (KP > 1) {
+        int *flag = reinterpret_cast<int *>(smem); // the LDS of the main loop is dead now
+        if (threadIdx.x == 0) {
+            // release: the sums above become visible to the other compute dies before the ticket does;
+            // acquire: the last to arrive drops stale lines of its L1 and L2 before it reads the others' sums
+            int old = __hip_atomic_fetch_add(p.ticket + rg, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+            *flag = (old == KP - 1);
+            if (old == KP - 1) p.ticket[rg] = 0; // ready for the next launch
+        }
+        __syncthreads();
+        const bool last = *flag != 0;
+        __syncthreads();
+        if (!last) return;
+    }
+    slots([&](int t, int at) { bg_slot_epilogue<NA>(p, ph, KP, ntv, vt0 + t, at, scale_lds); }); // uniform per wave
+    ph.finish(rg, smem);
+}
+
 // ---------------------------------------------------------------------------------------------------
 // the core.  Ph supplies:
 //   NMAT (1, or 2 = adjacent tiles form (gate, up) pairs), STREAM (non-temporal weight loads), GATHER (rows through
@@ -215,50 +267,186 @@ __device__ __forceinline__ void bgemv(const DraftParams &p, Ph &ph, int RG, int 
         }
     }
 
-    // ---- the last workgroup of the row group adds the parts and runs the epilogue ----
-    __syncthreads(); // every store of this workgroup's sums has completed
-    if (KP > 1) {
-        int *flag = reinterpret_cast<int *>(partial); // the partial sums in LDS are dead now
-        if (threadIdx.x == 0) {
-            // release: the sums above become visible to the other compute dies before the ticket does;
-            // acquire: the last to arrive drops stale lines of its L1 and L2 before it reads the others' sums
-            int old = __hip_atomic_fetch_add(p.ticket + rg, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-            *flag = (old == KP - 1);
-            if (old == KP - 1) p.ticket[rg] = 0; // ready for the next launch
+    bg_tail<NA>(p, ph, KP, rg, ntv, vt0, reinterpret_cast<char *>(partial), scale_lds, [&](auto f) {
+        constexpr int NQ = kBatchAcc / NMAT; // (tile or pair, sequence tile) slots with an epilogue: one per wave
+        if (wave < NQ)
+            for (int grp = 0; grp < ngroups; ++grp) {
+                const int t = grp * TG + (wave / NA) * NMAT;
+                if (t < nvt) f(t, wave % NA);
+            }
+    });
+}
+
+// ---------------------------------------------------------------------------------------------------
+// the core for 17..64 sequences (NA = 2 or 4 sequence tiles).  With the waves splitting the reduction, every wave
+// would fetch 2*NA KiB of activations per KiB of weights from L2; here the waves split the TILES of a block instead
+// (8/NA tiles per wave, 64/NA per block) and walk the reduction range together: the activations of a double step
+// (NA*16 sequences x 64 elements, hi and lo) are fetched once per workgroup - each thread brings NA/2 pieces along
+// with its weights - parked in one of two LDS buffers and read from there by all waves.  One barrier per step (it does
+// not wait for loads in flight); no reduction across waves.  Everything else (row groups x reduction parts, partial
+// buffer, ticket, epilogues) is as above.
+// ---------------------------------------------------------------------------------------------------
+template <int NA, class Ph>
+__device__ __forceinline__ void bgemv_lds(const DraftParams &p, Ph &ph, int RG, int KP, char *smem) {
+    static_assert(NA == 2 || NA == 4, "sequence tiles per pass");
+    constexpr int NMAT = Ph::NMAT;
+    constexpr int TW = kBatchAcc / NA; // weight tiles per wave
+    constexpr int TB = kWaves * TW;    // weight tiles per block
+    constexpr int NP = NA / 2;         // 16-byte pieces of the activation chunk per thread
+    constexpr int D = NA == 4 ? 4 : 3; // steps in flight per wave
+    constexpr int NL = 2 * TW + NP;
+    constexpr int AROW = 272;          // bytes per sequence in an LDS buffer: 128 hi, 128 lo, 16 to stagger the banks
+    constexpr int ABYTES = NA * 16 * AROW;
+    const int wg = blockIdx.x;
+    if (wg >= RG * KP) return;
+    const int kp = wg % KP, rg = wg / KP;
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave, j = lane & 15, g = lane >> 4;
+    const int K = ph.K;
+    const int units = (ph.rows + 15) / 16;
+    const int u0 = (int)((long long)rg * units / RG), u1 = (int)((long long)(rg + 1) * units / RG);
+    const int vt0 = u0 * NMAT, nvt = (u1 - u0) * NMAT, ntv = units * NMAT;
+    const int nblocks = (nvt + TB - 1) / TB;
+    const int nks = (K + 63) / 64;
+    const int ksA = (int)((long long)kp * nks / KP), ksB = (int)((long long)(kp + 1) * nks / KP);
+    const int steps = max(ksB - ksA, 1);
+    const int total = nblocks * steps;
+
+    char *abuf = smem;                                                    // [2][NA*16][AROW]
+    float *scale_lds = reinterpret_cast<float *>(smem + 2 * ABYTES);      // [kBatchMaxSeq]
+    int *ids_lds = reinterpret_cast<int *>(scale_lds + kBatchMaxSeq);     // [rows of this row group]
+    if (Ph::GATHER) {
+        const int r0 = u0 * 16, nr = (u1 - u0) * 16;
+        for (int i = threadIdx.x; i < nr; i += kBlock) {
+            int pos = min(r0 + i, ph.rows - 1);
+            ids_lds[i] = ph.ids ? ph.ids[pos] : pos;
         }
         __syncthreads();
-        const bool last = *flag != 0;
-        __syncthreads();
-        if (!last) return;
     }
-    constexpr int NQ = kBatchAcc / NMAT; // (tile or pair, sequence tile) slots with an epilogue
-    if (wave < NQ) {
-        for (int grp = 0; grp < ngroups; ++grp) {
-            const int q = wave, at = q % NA, tq = q / NA; // tq: tile (NMAT = 1) or pair (NMAT = 2) inside the group
-            const int t = grp * TG + tq * NMAT;           // first virtual tile of the slot, relative to vt0
-            if (t < nvt) {                                 // uniform for the wave
-                f32x4 sums[NMAT];
+
+    // this thread's pieces of the activation chunk: piece = (sequence, hi or lo, 16 bytes of the 128)
+    const size_t lo_bytes = p.a_lo * 2;
+    const row_rsrc ar = make_row_rsrc(ph.in, (int)(2 * lo_bytes));
+    int voff_g[NP], off_l[NP];
 #pragma unroll
-                for (int m = 0; m < NMAT; ++m) {
-                    const float *src = part + (((size_t)(vt0 + t + m) * NA + at) * kWave + lane) * 4;
-                    const size_t kstride = (size_t)ntv * NA * kWave * 4;
-                    f32x4 sacc = {0.f, 0.f, 0.f, 0.f};
-                    for (int k2 = 0; k2 < KP; k2 += 8) { // eight loads in flight, added in the order of the parts
-                        f32x4 v[8];
+    for (int r = 0; r < NP; ++r) {
+        const int pid = threadIdx.x + r * kBlock, seq = pid >> 4, hl = (pid >> 3) & 1, c = pid & 7;
+        voff_g[r] = (int)((size_t)min(p.b0 + seq, p.B - 1) * p.a_stride * 2 + c * 16 + (hl ? lo_bytes : 0));
+        off_l[r] = seq * AROW + hl * 128 + c * 16;
+    }
+
+    // tiles (pairs of tiles) of a block are dealt to the waves round robin: a row group with few tiles still keeps
+    // as many waves busy as it has tiles
+    auto tile_of = [&](int tw) { return (tw / NMAT) * (kWaves * NMAT) + wave * NMAT + (tw % NMAT); };
+    row_rsrc wr[TW];
+    int voff_w[TW];
+    auto setup_block = [&](int blk) {
 #pragma unroll
-                        for (int u = 0; u < 8; ++u)
-                            v[u] = *reinterpret_cast<const f32x4 *>(src + (size_t)min(k2 + u, KP - 1) * kstride);
+        for (int tw = 0; tw < TW; ++tw) {
+            const int t = blk * TB + tile_of(tw);
+            const uint16_t *base;
+            int mat_rows, row0, row_end;
+            ph.tile(vt0 + min(t, nvt - 1), base, mat_rows, row0, row_end);
+            wr[tw] = make_row_rsrc(base, (int)((size_t)mat_rows * K * 2));
+            const int r = row0 + j;
+            const bool ok = t < nvt && r < row_end;
+            const int phys = Ph::GATHER ? ids_lds[(min(t, nvt - 1) / NMAT) * 16 + j] : r;
+            voff_w[tw] = ok ? (int)((size_t)phys * K * 2 + g * 32) : (int)kOobOffset;
+        }
+    };
+    u32x4 ring[D][NL];
+    int ib = 0, ik = 0; // next step to request: block, double step of the workgroup's range
+    auto issue = [&](u32x4(&slot)[NL]) {
+        const int ks = min(ksA + ik, nks - 1);
+        const int soff = min(ks * 64, K - 64) * 2; // the last, ragged step is shifted left to stay inside the row
 #pragma unroll
-                        for (int u = 0; u < 8; ++u)
-                            if (k2 + u < KP) sacc += v[u];
+        for (int tw = 0; tw < TW; ++tw) {
+            slot[2 * tw] = row_load16<Ph::STREAM>(wr[tw], voff_w[tw], soff);
+            slot[2 * tw + 1] = row_load16<Ph::STREAM>(wr[tw], voff_w[tw] + 16, soff);
+        }
+#pragma unroll
+        for (int r = 0; r < NP; ++r) slot[2 * TW + r] = row_load16<false>(ar, voff_g[r], soff);
+        if (++ik == steps) {
+            ik = 0;
+            ++ib;
+            if (ib < nblocks) setup_block(ib);
+        }
+    };
+    setup_block(0);
+#pragma unroll
+    for (int s = 0; s < D; ++s)
+        if (s < total) issue(ring[s]);
+    if (Ph::SCALE >= 0 && !p.bg_sep[Ph::WHICH]) batch_scales(p, Ph::SCALE, scale_lds); // visible after the first barrier
+
+    f32x4 acc[kBatchAcc];
+#pragma unroll
+    for (int a = 0; a < kBatchAcc; ++a) acc[a] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+    float *part = p.part;
+    int cb = 0, ck = 0;
+    for (int n0 = 0; n0 < total; n0 += D) {
+#pragma unroll
+        for (int s = 0; s < D; ++s) {
+            if (n0 + s < total) { // uniform
+                const int ksn = ksA + ck;
+                const int ks = min(ksn, nks - 1);
+                const int koff = min(ks * 64, K - 64);
+                const int cut = ksn < ksB ? (ks * 64 - koff) / 8 : 8; // pieces counted before, or an empty range
+                // Park the chunk.  The buffer was last read two steps ago, and every wave has passed the barrier of
+                // the step in between since.
+                char *ab = abuf + ((n0 + s) & 1) * ABYTES;
+#pragma unroll
+                for (int r = 0; r < NP; ++r) *reinterpret_cast<u32x4 *>(ab + off_l[r]) = ring[s][2 * TW + r];
+                lds_barrier();
+#pragma unroll
+                for (int at = 0; at < NA; ++at) {
+                    const char *row = ab + (at * 16 + j) * AROW + g * 32;
+                    u32x4 ah[2], al[2];
+#pragma unroll
+                    for (int hf = 0; hf < 2; ++hf) {
+                        const bool dead = g * 2 + hf < cut;
+                        ah[hf] = dead ? zero4 : *reinterpret_cast<const u32x4 *>(row + hf * 16);
+                        al[hf] = dead ? zero4 : *reinterpret_cast<const u32x4 *>(row + 128 + hf * 16);
                     }
-                    sums[m] = sacc;
+#pragma unroll
+                    for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+                        for (int tw = 0; tw < TW; ++tw) {
+                            acc[tw * NA + at] = mfma16(ah[hf], ring[s][2 * tw + hf], acc[tw * NA + at]);
+                            acc[tw * NA + at] = mfma16(al[hf], ring[s][2 * tw + hf], acc[tw * NA + at]);
+                        }
                 }
-                ph.epi(at * 16 + g * 4, vt0 + t, j, sums, scale_lds);
+                if (n0 + s + D < total) issue(ring[s]);
+                if (++ck == steps) { // block complete: this wave's sums go to the partial buffer
+                    ck = 0;
+#pragma unroll
+                    for (int tw = 0; tw < TW; ++tw) {
+                        const int t = cb * TB + tile_of(tw);
+#pragma unroll
+                        for (int at = 0; at < NA; ++at) {
+                            if (t < nvt)
+                                *reinterpret_cast<f32x4 *>(
+                                    part + ((((size_t)kp * ntv + vt0 + t) * NA + at) * kWave + lane) * 4) = acc[tw * NA + at];
+                            acc[tw * NA + at] = f32x4{0.f, 0.f, 0.f, 0.f};
+                        }
+                    }
+                    ++cb;
+                }
             }
         }
     }
-    ph.finish(rg, reinterpret_cast<char *>(partial));
+    // With many reduction parts the last workgroup of a row group would add parts x tiles x sequence tiles partial
+    // tiles alone: the host then launches the epilogue as a kernel of its own, spread over the whole chip.
+    if (p.bg_sep[Ph::WHICH]) return;
+    bg_tail<NA>(p, ph, KP, rg, ntv, vt0, smem, scale_lds, [&](auto f) {
+        for (int blk = 0; blk < nblocks; ++blk)
+#pragma unroll
+            for (int tw = 0; tw < TW; tw += NMAT) {
+                const int t = blk * TB + tile_of(tw);
+                if (t < nvt)
+#pragma unroll
+                    for (int at = 0; at < NA; ++at) f(t, at);
+            }
+    });
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -288,6 +476,7 @@ struct BgBase {
 // 2d -> d projection of [RMSNorm(h); RMSNorm(E[token])] (already normalised by the preparation kernel).  Leaves x,
 // and g_attn * x with its sums of squares for the q/k/v projection.
 struct BgProj : BgBase {
+    static constexpr int WHICH = BG_PROJ;
     __device__ BgProj(const DraftParams &p_) : BgBase(p_, 2 * p_.d, p_.d, p_.act[0]) {}
     __device__ __forceinline__ void tile(int vt, const uint16_t *&base, int &mat_rows, int &row0, int &row_end) const {
         base = p.w_proj;
@@ -313,6 +502,7 @@ struct BgProj : BgBase {
 
 // q/k/v projection of RMSNorm(x; g_attn); bias, rotary embedding and the cache append happen in the attention phase
 struct BgQkv : BgBase {
+    static constexpr int WHICH = BG_QKV;
     static constexpr int SCALE = SSQ_X;
     __device__ BgQkv(const DraftParams &p_) : BgBase(p_, p_.d, p_.qkv_dim, p_.act[1]) {}
     __device__ __forceinline__ void tile(int vt, const uint16_t *&base, int &mat_rows, int &row0, int &row_end) const {
@@ -345,6 +535,7 @@ struct BgQkv : BgBase {
 
 // output projection of the attention result; leaves x1 = x + W_o a, and g_mlp * x1 with its sums of squares
 struct BgOproj : BgBase {
+    static constexpr int WHICH = BG_OPROJ;
     __device__ BgOproj(const DraftParams &p_) : BgBase(p_, p_.qd, p_.d, p_.act[0]) {}
     __device__ __forceinline__ void tile(int vt, const uint16_t *&base, int &mat_rows, int &row0, int &row_end) const {
         base = p.w_o;
@@ -373,6 +564,7 @@ struct BgOproj : BgBase {
 
 // gate and up projections of RMSNorm(x1; g_mlp) as pairs of tiles; leaves m = silu(gate) * up, split
 struct BgGateUp : BgBase {
+    static constexpr int WHICH = BG_GATEUP;
     static constexpr int NMAT = 2;
     static constexpr int SCALE = SSQ_X1;
     __device__ BgGateUp(const DraftParams &p_) : BgBase(p_, p_.d, p_.F, p_.act[1]) {}
@@ -397,6 +589,7 @@ struct BgGateUp : BgBase {
 
 // down projection; leaves x2 = x1 + W_down m, and g_final * x2 with its sums of squares for the output head
 struct BgDown : BgBase {
+    static constexpr int WHICH = BG_DOWN;
     __device__ BgDown(const DraftParams &p_) : BgBase(p_, p_.F, p_.d, p_.act[0]) {}
     __device__ __forceinline__ void tile(int vt, const uint16_t *&base, int &mat_rows, int &row0, int &row_end) const {
         base = p.w_down;
@@ -426,11 +619,11 @@ struct BgDown : BgBase {
 // output head over the compressed vocabulary (Sec. 2.2, Eq. (3)): logits of RMSNorm(x2; g_final) against the listed
 // rows, and per row group the best (logit, position) of every sequence
 struct BgHead : BgBase {
+    static constexpr int WHICH = BG_LMHEAD;
     static constexpr bool STREAM = false, GATHER = true;
     static constexpr int SCALE = SSQ_X2;
     int step;
-    unsigned long long best[4] = {0ull, 0ull, 0ull, 0ull};
-    int bf_mine = 0;
+    unsigned long long best[kBatchMaxSeq / 16][4] = {}; // by sequence tile; a lane sees four sequences of each
     __device__ BgHead(const DraftParams &p_, int step_) : BgBase(p_, p_.d, p_.n, p_.act[1]), step(step_) { ids = p_.ids; }
     __device__ __forceinline__ void tile(int vt, const uint16_t *&base, int &mat_rows, int &row0, int &row_end) const {
         base = p.lm_head;
@@ -441,7 +634,7 @@ struct BgHead : BgBase {
     __device__ __forceinline__ void epi(int bf, int vt, int j, const f32x4 (&s)[1], const float *scale) {
         const int pos = vt * 16 + j;
         const float v[4] = {s[0].x, s[0].y, s[0].z, s[0].w};
-        bf_mine = bf; // a wave always serves the same sequence tile
+        const int at = bf >> 4;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const int bl = bf + c;
@@ -449,7 +642,9 @@ struct BgHead : BgBase {
                 const float logit = v[c] * scale[bl];
                 if (p.logits_out) p.logits_out[((size_t)(p.b0 + bl) * p.K + step) * p.n + pos] = logit;
                 const unsigned long long key = argmax_key(logit, (uint32_t)pos);
-                best[c] = key > best[c] ? key : best[c];
+#pragma unroll
+                for (int a = 0; a < kBatchMaxSeq / 16; ++a) // static indices keep the array in registers
+                    if (a == at) best[a][c] = key > best[a][c] ? key : best[a][c];
             }
         }
     }
@@ -461,15 +656,17 @@ struct BgHead : BgBase {
         __syncthreads();
         const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            unsigned long long m = best[c];
+        for (int a = 0; a < kBatchMaxSeq / 16; ++a)
 #pragma unroll
-            for (int off = 1; off < 16; off <<= 1) {
-                unsigned long long o = __shfl_xor(m, off, kWave);
-                m = o > m ? o : m;
+            for (int c = 0; c < 4; ++c) {
+                unsigned long long m = best[a][c];
+#pragma unroll
+                for (int off = 1; off < 16; off <<= 1) {
+                    unsigned long long o = __shfl_xor(m, off, kWave);
+                    m = o > m ? o : m;
+                }
+                if ((lane & 15) == 0 && m != 0ull) red[wave * kBatchMaxSeq + a * 16 + (lane >> 4) * 4 + c] = m;
             }
-            if ((lane & 15) == 0 && m != 0ull) red[wave * kBatchMaxSeq + bf_mine + c] = m;
-        }
         __syncthreads();
         if ((int)threadIdx.x < p.nb) {
             unsigned long long m = 0ull;
@@ -482,6 +679,18 @@ struct BgHead : BgBase {
         }
     }
 };
+
+// The epilogue of a matrix phase as a kernel of its own: one wave per slot (tile, sequence tile), any grid.
+template <int NA, class Ph>
+__device__ __forceinline__ void phase_bepilogue(const DraftParams &p, Ph &ph, int KP, char *smem) {
+    static_assert(Ph::NMAT == 1, "pairs keep the ticket path");
+    float *scale_lds = reinterpret_cast<float *>(smem);
+    if (Ph::SCALE >= 0) batch_scales(p, Ph::SCALE, scale_lds);
+    __syncthreads();
+    const int ntv = (ph.rows + 15) / 16, nslots = ntv * NA;
+    for (int id = blockIdx.x * kWaves + threadIdx.x / kWave; id < nslots; id += gridDim.x * kWaves)
+        bg_slot_epilogue<NA>(p, ph, KP, ntv, id / NA, id % NA, scale_lds);
+}
 
 // ---------------------------------------------------------------------------------------------------
 // preparation kernel, one workgroup per sequence, before every step and once after the last:

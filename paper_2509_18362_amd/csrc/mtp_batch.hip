@@ -8,27 +8,54 @@
 namespace mtp {
 namespace {
 
+// up to 16 sequences: the waves split the reduction; more: they split the tiles and share the activations in LDS
+template <int NA, class Ph>
+__device__ __forceinline__ void run_phase(const DraftParams &p, Ph &ph, int which, char *smem) {
+    if constexpr (NA == 1)
+        bgemv<1>(p, ph, p.bg_rg[which], p.bg_kp[which], smem);
+    else
+        bgemv_lds<NA>(p, ph, p.bg_rg[which], p.bg_kp[which], smem);
+}
+
 template <int PH, int NA>
 __global__ __launch_bounds__(kBlock) void k_bgemv(DraftParams p, int step) {
     extern __shared__ __align__(16) char smem[];
     if constexpr (PH == BG_PROJ) {
         BgProj ph(p);
-        bgemv<NA>(p, ph, p.bg_rg[PH], p.bg_kp[PH], smem);
+        run_phase<NA>(p, ph, PH, smem);
     } else if constexpr (PH == BG_QKV) {
         BgQkv ph(p);
-        bgemv<NA>(p, ph, p.bg_rg[PH], p.bg_kp[PH], smem);
+        run_phase<NA>(p, ph, PH, smem);
     } else if constexpr (PH == BG_OPROJ) {
         BgOproj ph(p);
-        bgemv<NA>(p, ph, p.bg_rg[PH], p.bg_kp[PH], smem);
+        run_phase<NA>(p, ph, PH, smem);
     } else if constexpr (PH == BG_GATEUP) {
         BgGateUp ph(p);
-        bgemv<NA>(p, ph, p.bg_rg[PH], p.bg_kp[PH], smem);
+        run_phase<NA>(p, ph, PH, smem);
     } else if constexpr (PH == BG_DOWN) {
         BgDown ph(p);
-        bgemv<NA>(p, ph, p.bg_rg[PH], p.bg_kp[PH], smem);
+        run_phase<NA>(p, ph, PH, smem);
     } else {
         BgHead ph(p, step);
-        bgemv<NA>(p, ph, p.bg_rg[PH], p.bg_kp[PH], smem);
+        run_phase<NA>(p, ph, PH, smem);
+    }
+}
+
+template <int PH, int NA>
+__global__ __launch_bounds__(kBlock) void k_bepilogue(DraftParams p, int) {
+    __shared__ __align__(16) char smem[kBatchMaxSeq * 4];
+    if constexpr (PH == BG_PROJ) {
+        BgProj ph(p);
+        phase_bepilogue<NA>(p, ph, p.bg_kp[PH], smem);
+    } else if constexpr (PH == BG_QKV) {
+        BgQkv ph(p);
+        phase_bepilogue<NA>(p, ph, p.bg_kp[PH], smem);
+    } else if constexpr (PH == BG_OPROJ) {
+        BgOproj ph(p);
+        phase_bepilogue<NA>(p, ph, p.bg_kp[PH], smem);
+    } else {
+        BgDown ph(p);
+        phase_bepilogue<NA>(p, ph, p.bg_kp[PH], smem);
     }
 }
 
@@ -77,6 +104,18 @@ bg_kernel_t pick(int phase, int na) {
     }
 }
 int tiles_for(int nb) { return nb <= 16 ? 1 : nb <= 32 ? 2 : 4; }
+template <int PH>
+bg_kernel_t pick_epilogue_na(int na) {
+    return na == 2 ? k_bepilogue<PH, 2> : k_bepilogue<PH, 4>;
+}
+bg_kernel_t pick_epilogue(int phase, int na) {
+    switch (phase) {
+    case BG_PROJ: return pick_epilogue_na<BG_PROJ>(na);
+    case BG_QKV: return pick_epilogue_na<BG_QKV>(na);
+    case BG_OPROJ: return pick_epilogue_na<BG_OPROJ>(na);
+    default: return pick_epilogue_na<BG_DOWN>(na);
+    }
+}
 
 } // namespace
 
@@ -114,7 +153,13 @@ bool batch_allow_lds(size_t lds_limit) {
 }
 
 void launch_bgemv(int phase, const DraftParams &p, int step, int grid, size_t lds, hipStream_t st) {
-    hipLaunchKernelGGL(pick(phase, tiles_for(p.nb)), dim3(grid), dim3(kBlock), lds, st, p, step);
+    const int na = tiles_for(p.nb);
+    hipLaunchKernelGGL(pick(phase, na), dim3(grid), dim3(kBlock), lds, st, p, step);
+    if (na > 1 && p.bg_sep[phase]) { // one wave per (tile, sequence tile)
+        const int rows = phase == BG_QKV ? p.qkv_dim : p.d;
+        const int slots = (rows + 15) / 16 * na;
+        hipLaunchKernelGGL(pick_epilogue(phase, na), dim3((slots + kWaves - 1) / kWaves), dim3(kBlock), 0, st, p, step);
+    }
 }
 
 void launch_bprep(const DraftParams &p, int step, hipStream_t st) {

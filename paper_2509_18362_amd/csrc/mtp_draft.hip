@@ -225,9 +225,9 @@ WsLayout ws_layout(const mtp_config &c) {
         l.act0 = take(2 * l.a_lo * 2);
         l.act1 = take(2 * l.a_lo * 2);
         l.ssq = take((size_t)3 * mb * (d / 16) * 4);
-        // [reduction parts][tiles][sequence tiles]: split phases hold at most eight tiles per row group and at most
-        // kMaxFusedGrid workgroups, unsplit ones every tile once
-        size_t tiles = std::max(batch_max_tiles(c), (size_t)kBatchGroupTiles * kMaxFusedGrid);
+        // [reduction parts][tiles][sequence tiles]: split phases hold parts x tiles x sequence tiles <= 64 per
+        // workgroup (of at most kMaxFusedGrid), unsplit ones every tile once
+        size_t tiles = std::max(batch_max_tiles(c), (size_t)2 * kBatchGroupTiles * kMaxFusedGrid);
         l.part = take(tiles * (kBatchPassSeq / 16) * kBatchTileBytes);
         l.ticket = take((size_t)kMaxFusedGrid * 4);
     }
@@ -587,18 +587,29 @@ int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_inde
         p.ticket = reinterpret_cast<int *>(ws + l.ticket);
         size_t lds_bg[BG_COUNT];
         // units: 16-row tiles (gate/up: pairs of tiles); kdim: reduction length
+        // One plan per call: passes of one call share it (a last, smaller pass runs a little off its optimum).
+        // Up to 16 sequences a workgroup's waves split the reduction and a row group holds eight tiles; above, its
+        // waves split the 64/NA tiles of a block.  A phase with fewer tiles than that per workgroup splits the
+        // reduction over KP workgroups, each keeping at least four double steps.
+        const int na = B <= 16 ? 1 : B <= 32 ? 2 : 4;
+        const int block_tiles = na == 1 ? kBatchGroupTiles : kWaves * (kBatchGroupTiles / na);
         auto plan = [&](int ph, int units, int nmat, int kdim) {
-            const int nks = (kdim + 63) / 64; // double depth steps; every wave of a workgroup should get one
+            const int nks = (kdim + 63) / 64; // double depth steps
+            const long long ntv = (long long)units * nmat;
             int rg, kp = 1;
-            if ((long long)units * nmat >= 4ll * grid) {
+            if (na == 1 && ntv >= 4ll * grid) {
                 rg = std::min(grid, units);
             } else {
-                const int per_group = kBatchGroupTiles / nmat;
-                rg = std::min(grid, (units + per_group - 1) / per_group);
-                kp = std::max(1, std::min(grid / rg, nks / kWaves));
+                kp = (int)std::max(1ll, std::min<long long>((long long)grid * block_tiles / ntv,
+                                                             na == 1 ? nks / kWaves : nks / 4));
+                kp = std::max(1, std::min(kp, grid));
+                rg = std::max(1, std::min(grid / kp, units));
             }
             p.bg_rg[ph] = rg;
             p.bg_kp[ph] = kp;
+            // many parts above 16 sequences: the sums are added by an epilogue kernel spread over the chip instead
+            // of the last workgroup of each row group (passes of up to 16 sequences keep their own tail)
+            p.bg_sep[ph] = (na > 1 && kp >= 4 && nmat == 1 && ph != BG_LMHEAD) ? 1 : 0;
             lds_bg[ph] = bgemv_lds_bytes(((units + rg - 1) / rg) * 16);
         };
         plan(BG_PROJ, p.d / 16, 1, 2 * p.d);

@@ -52,6 +52,7 @@ struct DraftParams {
     int *ticket;         // arrival counters of the row groups (zero between launches)
     int b0, nb;          // sequences of this pass
     int bg_rg[6], bg_kp[6]; // row groups and reduction parts of the six matrix phases
+    int bg_sep[6];          // 1: the phase's epilogue runs as a kernel of its own
 };
 
 enum : int { kErrKvOverflow = 1, kErrTokenRange = 2, kErrBarrierTimeout = 4 };

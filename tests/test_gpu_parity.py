@@ -132,6 +132,19 @@ def test_tiny_long_capacity_matrix_core_attention(gpu, tiny):
     check_chain(ref, res, caches, act["kv_len"], 3)
 
 
+@pytest.mark.parametrize("B", [17, 20, 40, 70])
+def test_tiny_wide_batches(gpu, tiny, B):
+    """Batches above 16 take the core whose waves split the tiles (two or four sequence tiles, the last one ragged);
+    70 sequences are two weight passes (64 + 6).  The tiny head has a reduction length (d_ffn = 688) that is not a
+    multiple of the 64-element double step, and row counts that leave most tile slots of a block empty."""
+    wl = tiny["wl"]
+    rng = np.random.default_rng(100 + B)
+    ctx = rng.integers(0, 120, size=B).astype(np.int32)
+    act = synth.make_activations(wl, ctx=ctx, capacity=192)
+    ref, res, caches = run_both(gpu, tiny["shape"], tiny["w"], tiny["w"], act, [tiny["ids"]], 0, 3)
+    check_chain(ref, res, caches, act["kv_len"], 3)
+
+
 def test_tiny_full_vocab_equals_identity_subset(gpu, tiny):
     """Eq. (3) with the identity list is the full head: same logits bit for bit on the device as well."""
     act = tiny["act"]
