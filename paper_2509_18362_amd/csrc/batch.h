@@ -34,8 +34,11 @@ struct BatchShape {
     static constexpr int NL = 2 * TG + 4 * NA;  // 16-byte loads per lane per item
 };
 
+// partial sums of the waves (or, for wide batches, the two activation buffers, which are smaller), the
+// transposition strips, the norm scales, the ids of the row group
 __host__ __device__ inline size_t batch_lds_bytes(int max_rows_per_wg) {
-    return (size_t)2 * kWaves * kBatchAcc * kWave * 16 + kBatchMaxSeq * 4 + (size_t)max_rows_per_wg * 4 + 256;
+    return (size_t)kWaves * kBatchAcc * kWave * 16 + (size_t)kWaves * 2 * 2304 + kBatchMaxSeq * 4 +
+           (size_t)max_rows_per_wg * 4 + 256;
 }
 
 // The bf16 hi/lo pair of one float, as the A operand wants it
@@ -44,6 +47,31 @@ __device__ __forceinline__ void store_split(uint16_t *hi, size_t lo_off, size_t 
     split_bf16(v, h, l);
     hi[idx] = h;
     hi[lo_off + idx] = l;
+}
+
+// A 16-row x 128-byte tile travels from memory to the MFMA operand layout in two hops.  Loaded straight into the
+// layout (lane (j, g): row j, bytes 32g..), every lane of a load instruction touches another row: sixteen 16-byte
+// pieces per 64 B/clk address-unit pass, which caps a CU near 16 B/clk.  Instead a lane loads row (lane / 8) [+ 8],
+// bytes 16 (lane % 8): eight lanes cover one 128-byte line, four times fewer address-unit cycles.  The wave then
+// parks the two halves in a private LDS strip (row stride 144 bytes: the sixteen rows of a transposed read fall
+// into different banks) and reads its operand pieces back.  LDS operations of one wave complete in order, so a strip
+// can be rewritten right after it was read.
+constexpr int kStripRow = 144, kStripBytes = 16 * kStripRow;
+__device__ __forceinline__ void strip_park(char *strip, const u32x4 &rows_lo, const u32x4 &rows_hi) {
+    const int lane = threadIdx.x & (kWave - 1);
+    char *dst = strip + (lane >> 3) * kStripRow + (lane & 7) * 16;
+    *reinterpret_cast<u32x4 *>(dst) = rows_lo;
+    *reinterpret_cast<u32x4 *>(dst + 8 * kStripRow) = rows_hi;
+}
+// piece hf (0, 1) of lane (j, g): bytes 32 g + 16 hf of row j
+__device__ __forceinline__ void strip_fetch(const char *strip, u32x4 &hf0, u32x4 &hf1) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const char *src = strip + (lane & 15) * kStripRow + (lane >> 4) * 32;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    hf0 = *reinterpret_cast<const u32x4 *>(src);
+    hf1 = *reinterpret_cast<const u32x4 *>(src + 16);
 }
 
 // s_b = 1/sqrt(mean(u_b^2) + eps) for the nb sequences of the pass, from the producers' per-tile sums of squares
@@ -129,7 +157,9 @@ __device__ __forceinline__ void bgemv(const DraftParams &p, Ph &ph, int RG, int 
     const int wg = blockIdx.x;
     if (wg >= RG * KP) return;
     const int kp = wg % KP, rg = wg / KP;
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave, j = lane & 15, g = lane >> 4;
+    const int lane = threadIdx.x & (kWave - 1), j = lane & 15, g = lane >> 4;
+    // said explicitly to be wave-uniform: offsets and descriptors derived from it then stay in scalar registers
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
     const int K = ph.K;
     const int units = (ph.rows + 15) / 16;
     const int u0 = (int)((long long)rg * units / RG), u1 = (int)((long long)(rg + 1) * units / RG);
@@ -143,10 +173,10 @@ __device__ __forceinline__ void bgemv(const DraftParams &p, Ph &ph, int RG, int 
     const int nks = (K + 63) / 64;
     const int ksA = (int)((long long)kp * nks / KP), ksB = (int)((long long)(kp + 1) * nks / KP);
     const int per = max((ksB - ksA + kWaves - 1) / kWaves, 1); // items per group, the same for every wave
-    const int total = ngroups * per;
 
-    f32x4 *partial = reinterpret_cast<f32x4 *>(smem);                           // [2][kWaves][kBatchAcc][kWave]
-    float *scale_lds = reinterpret_cast<float *>(partial + 2 * kWaves * kBatchAcc * kWave); // [kBatchMaxSeq]
+    f32x4 *partial = reinterpret_cast<f32x4 *>(smem);                           // [kWaves][kBatchAcc][kWave]
+    char *strips = reinterpret_cast<char *>(partial + kWaves * kBatchAcc * kWave); // [kWaves][2] transposition strips
+    float *scale_lds = reinterpret_cast<float *>(strips + kWaves * 2 * kStripBytes); // [kBatchMaxSeq]
     int *ids_lds = reinterpret_cast<int *>(scale_lds + kBatchMaxSeq);           // [rows of this row group]
     if (Ph::GATHER) {
         const int r0 = u0 * 16, nr = (u1 - u0) * 16;
@@ -160,13 +190,16 @@ __device__ __forceinline__ void bgemv(const DraftParams &p, Ph &ph, int RG, int 
     // activations: one descriptor over the hi and lo arrays; lane (j, g) reads sequence at*16 + j
     const size_t lo_bytes = p.a_lo * 2;
     const row_rsrc ar = make_row_rsrc(ph.in, (int)(2 * lo_bytes));
-    int voff_a[NA];
+    // a lane fetches sequence at*16 + lane/8 [+ 8], bytes 16 (lane % 8) of the 128-byte piece
+    int voff_a[NA][2];
 #pragma unroll
     for (int at = 0; at < NA; ++at)
-        voff_a[at] = (int)((size_t)min(p.b0 + at * 16 + j, p.B - 1) * p.a_stride * 2 + g * 32);
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+            voff_a[at][h] = (int)((size_t)min(p.b0 + at * 16 + (lane >> 3) + 8 * h, p.B - 1) * p.a_stride * 2 + (lane & 7) * 16);
 
     row_rsrc wr[TG];
-    int voff_w[TG];
+    int voff_w[TG][2];
     auto setup_group = [&](int grp) {
 #pragma unroll
         for (int ts = 0; ts < TG; ++ts) {
@@ -175,95 +208,110 @@ __device__ __forceinline__ void bgemv(const DraftParams &p, Ph &ph, int RG, int 
             int mat_rows, row0, row_end;
             ph.tile(vt0 + min(t, nvt - 1), base, mat_rows, row0, row_end);
             wr[ts] = make_row_rsrc(base, (int)((size_t)mat_rows * K * 2));
-            const int r = row0 + j;
-            const bool ok = t < nvt && r < row_end;
-            const int phys = Ph::GATHER ? ids_lds[(min(t, nvt - 1) / NMAT) * 16 + j] : r;
-            voff_w[ts] = ok ? (int)((size_t)phys * K * 2 + g * 32) : (int)kOobOffset;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int jr = (lane >> 3) + 8 * h, r = row0 + jr;
+                const bool ok = t < nvt && r < row_end;
+                const int phys = Ph::GATHER ? ids_lds[(min(t, nvt - 1) / NMAT) * 16 + jr] : r;
+                voff_w[ts][h] = ok ? (int)((size_t)phys * K * 2 + (lane & 7) * 16) : (int)kOobOffset;
+            }
         }
     };
+    // The ring is refilled without any branch: a conditional load would leave the compiler unable to count the loads
+    // in flight, and it would then wait for all of them before every use.  Items past the end of a group are
+    // requested beyond the buffers' ends instead (zeros, no traffic) and contribute nothing.
     u32x4 ring[D][NL];
-    int ig = 0, ik = 0; // next item to request: group, and which of this wave's depth steps
-    auto issue = [&](u32x4(&slot)[NL]) {
-        const int ks = min(ksA + ik * kWaves + wave, nks - 1);
+    auto issue = [&](u32x4(&slot)[NL], int idx) { // item idx of the current group
+        const int ks = min(ksA + idx * kWaves + wave, nks - 1);
         const int soff = min(ks * 64, K - 64) * 2; // the last, ragged step is shifted left to stay inside the row
+        const bool live = idx < per;
 #pragma unroll
-        for (int ts = 0; ts < TG; ++ts) {
-            slot[2 * ts] = row_load16<Ph::STREAM>(wr[ts], voff_w[ts], soff);
-            slot[2 * ts + 1] = row_load16<Ph::STREAM>(wr[ts], voff_w[ts] + 16, soff);
-        }
+        for (int ts = 0; ts < TG; ++ts)
 #pragma unroll
-        for (int at = 0; at < NA; ++at) {
-            slot[2 * TG + 4 * at] = row_load16<false>(ar, voff_a[at], soff);
-            slot[2 * TG + 4 * at + 1] = row_load16<false>(ar, voff_a[at] + 16, soff);
-            slot[2 * TG + 4 * at + 2] = row_load16<false>(ar, voff_a[at], soff + (int)lo_bytes);
-            slot[2 * TG + 4 * at + 3] = row_load16<false>(ar, voff_a[at] + 16, soff + (int)lo_bytes);
-        }
-        if (++ik == per) {
-            ik = 0;
-            ++ig;
-            if (ig < ngroups) setup_group(ig);
-        }
+            for (int h = 0; h < 2; ++h)
+                slot[2 * ts + h] = row_load16<Ph::STREAM>(wr[ts], live ? voff_w[ts][h] : (int)kOobOffset, soff);
+#pragma unroll
+        for (int at = 0; at < NA; ++at)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int vo = live ? voff_a[at][h] : (int)kOobOffset;
+                slot[2 * TG + 4 * at + h] = row_load16<false>(ar, vo, soff);
+                slot[2 * TG + 4 * at + 2 + h] = row_load16<false>(ar, vo, soff + (int)lo_bytes);
+            }
     };
-    setup_group(0);
-#pragma unroll
-    for (int s = 0; s < D; ++s)
-        if (s < total) issue(ring[s]);
-    // with the first loads under way: the norm scales for the epilogue (visible after the first group's barrier)
-    if (Ph::SCALE >= 0) batch_scales(p, Ph::SCALE, scale_lds);
-
     f32x4 acc[kBatchAcc];
 #pragma unroll
     for (int a = 0; a < kBatchAcc; ++a) acc[a] = f32x4{0.f, 0.f, 0.f, 0.f};
-    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+    char *strip0 = strips + (size_t)wave * 2 * kStripBytes, *strip1 = strip0 + kStripBytes;
     float *part = p.part;
-    int cg = 0, ck = 0;
-    for (int n0 = 0; n0 < total; n0 += D) {
+    for (int grp = 0; grp < ngroups; ++grp) {
+        setup_group(grp);
 #pragma unroll
-        for (int s = 0; s < D; ++s) {
-            if (n0 + s < total) { // uniform
-                const int ksn = ksA + ck * kWaves + wave;
+        for (int s = 0; s < D; ++s) issue(ring[s], s);
+        // with the first loads under way: the norm scales for the epilogue (visible after the group's barrier)
+        if (Ph::SCALE >= 0 && grp == 0) batch_scales(p, Ph::SCALE, scale_lds);
+        for (int n0 = 0; n0 < per; n0 += D) {
+#pragma unroll
+            for (int s = 0; s < D; ++s) {
+                const int idx = n0 + s;
+                const int ksn = ksA + idx * kWaves + wave;
                 const int ks = min(ksn, nks - 1);
                 const int koff = min(ks * 64, K - 64);
                 // 8-element pieces that were already counted by the step before (ragged end), or all pieces of a
-                // step beyond the workgroup's range, contribute zeros
-                const int cut = ksn < ksB ? (ks * 64 - koff) / 8 : 8;
+                // step beyond the workgroup's range or the group's end, contribute zeros
+                const int cut = (idx < per && ksn < ksB) ? (ks * 64 - koff) / 8 : 8;
+                const uint32_t keep0 = g * 2 < cut ? 0u : 0xFFFFFFFFu, keep1 = g * 2 + 1 < cut ? 0u : 0xFFFFFFFFu;
+                // the activations of the step, through the strips into operand layout
+                u32x4 ah[NA][2], al[NA][2];
 #pragma unroll
-                for (int hf = 0; hf < 2; ++hf) {
-                    const bool dead = g * 2 + hf < cut;
+                for (int at = 0; at < NA; ++at) {
+                    strip_park(strip0, ring[s][2 * TG + 4 * at], ring[s][2 * TG + 4 * at + 1]);
+                    strip_park(strip1, ring[s][2 * TG + 4 * at + 2], ring[s][2 * TG + 4 * at + 3]);
+                    strip_fetch(strip0, ah[at][0], ah[at][1]);
+                    strip_fetch(strip1, al[at][0], al[at][1]);
+                    ah[at][0] &= keep0;
+                    al[at][0] &= keep0;
+                    ah[at][1] &= keep1;
+                    al[at][1] &= keep1;
+                }
+                // the weight tiles, one strip ahead of the MFMAs
+                strip_park(strip0, ring[s][0], ring[s][1]);
+#pragma unroll
+                for (int ts = 0; ts < TG; ++ts) {
+                    char *cur = (ts & 1) ? strip1 : strip0, *nxt = (ts & 1) ? strip0 : strip1;
+                    u32x4 w0, w1;
+                    strip_fetch(cur, w0, w1);
+                    if (ts + 1 < TG) strip_park(nxt, ring[s][2 * ts + 2], ring[s][2 * ts + 3]);
 #pragma unroll
                     for (int at = 0; at < NA; ++at) {
-                        const u32x4 ah = dead ? zero4 : ring[s][2 * TG + 4 * at + hf];
-                        const u32x4 al = dead ? zero4 : ring[s][2 * TG + 4 * at + 2 + hf];
-#pragma unroll
-                        for (int ts = 0; ts < TG; ++ts) {
-                            acc[ts * NA + at] = mfma16(ah, ring[s][2 * ts + hf], acc[ts * NA + at]);
-                            acc[ts * NA + at] = mfma16(al, ring[s][2 * ts + hf], acc[ts * NA + at]);
-                        }
+                        f32x4 a = acc[ts * NA + at];
+                        a = mfma16(ah[at][0], w0, a);
+                        a = mfma16(al[at][0], w0, a);
+                        a = mfma16(ah[at][1], w1, a);
+                        a = mfma16(al[at][1], w1, a);
+                        acc[ts * NA + at] = a;
                     }
                 }
-                if (n0 + s + D < total) issue(ring[s]);
-                if (++ck == per) { // group complete: meet the other waves in LDS, hand the sums to the partial buffer
-                    ck = 0;
-                    f32x4 *pb = partial + (size_t)(cg & 1) * kWaves * kBatchAcc * kWave;
-#pragma unroll
-                    for (int a = 0; a < kBatchAcc; ++a) {
-                        pb[(wave * kBatchAcc + a) * kWave + lane] = acc[a];
-                        acc[a] = f32x4{0.f, 0.f, 0.f, 0.f};
-                    }
-                    lds_barrier();
-                    {
-                        const int a = wave; // this thread adds accumulator `wave`, element `lane`, of all waves
-                        f32x4 sum = pb[a * kWave + lane];
-#pragma unroll
-                        for (int w = 1; w < kWaves; ++w) sum += pb[(w * kBatchAcc + a) * kWave + lane];
-                        const int ts = a / NA, at = a % NA, t = cg * TG + ts;
-                        if (t < nvt)
-                            *reinterpret_cast<f32x4 *>(part + ((((size_t)kp * ntv + vt0 + t) * NA + at) * kWave + lane) * 4) =
-                                sum;
-                    }
-                    ++cg;
-                }
+                issue(ring[s], idx + D);
             }
+        }
+        // group complete: meet the other waves in LDS, hand the sums to the partial buffer
+        f32x4 *pb = partial;
+        __syncthreads(); // the previous group's sums have been read; also drains the ring's trailing requests
+#pragma unroll
+        for (int a = 0; a < kBatchAcc; ++a) {
+            pb[(wave * kBatchAcc + a) * kWave + lane] = acc[a];
+            acc[a] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+        __syncthreads();
+        {
+            const int a = wave; // this thread adds accumulator `wave`, element `lane`, of all waves
+            f32x4 sum = pb[a * kWave + lane];
+#pragma unroll
+            for (int w = 1; w < kWaves; ++w) sum += pb[(w * kBatchAcc + a) * kWave + lane];
+            const int ts = a / NA, at = a % NA, t = grp * TG + ts;
+            if (t < nvt)
+                *reinterpret_cast<f32x4 *>(part + ((((size_t)kp * ntv + vt0 + t) * NA + at) * kWave + lane) * 4) = sum;
         }
     }
 
@@ -300,7 +348,9 @@ __device__ __forceinline__ void bgemv_lds(const DraftParams &p, Ph &ph, int RG, 
     const int wg = blockIdx.x;
     if (wg >= RG * KP) return;
     const int kp = wg % KP, rg = wg / KP;
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave, j = lane & 15, g = lane >> 4;
+    const int lane = threadIdx.x & (kWave - 1), j = lane & 15, g = lane >> 4;
+    // said explicitly to be wave-uniform: offsets and descriptors derived from it then stay in scalar registers
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
     const int K = ph.K;
     const int units = (ph.rows + 15) / 16;
     const int u0 = (int)((long long)rg * units / RG), u1 = (int)((long long)(rg + 1) * units / RG);
@@ -309,7 +359,6 @@ __device__ __forceinline__ void bgemv_lds(const DraftParams &p, Ph &ph, int RG, 
     const int nks = (K + 63) / 64;
     const int ksA = (int)((long long)kp * nks / KP), ksB = (int)((long long)(kp + 1) * nks / KP);
     const int steps = max(ksB - ksA, 1);
-    const int total = nblocks * steps;
 
     char *abuf = smem;                                                    // [2][NA*16][AROW]
     float *scale_lds = reinterpret_cast<float *>(smem + 2 * ABYTES);      // [kBatchMaxSeq]
@@ -353,86 +402,89 @@ __device__ __forceinline__ void bgemv_lds(const DraftParams &p, Ph &ph, int RG, 
             voff_w[tw] = ok ? (int)((size_t)phys * K * 2 + g * 32) : (int)kOobOffset;
         }
     };
+    // branch-free refill, as in the core above: steps past the end of the range are requested beyond the buffers' ends
     u32x4 ring[D][NL];
-    int ib = 0, ik = 0; // next step to request: block, double step of the workgroup's range
-    auto issue = [&](u32x4(&slot)[NL]) {
-        const int ks = min(ksA + ik, nks - 1);
+    auto issue = [&](u32x4(&slot)[NL], int idx) { // step idx of the current block
+        const int ks = min(ksA + idx, nks - 1);
         const int soff = min(ks * 64, K - 64) * 2; // the last, ragged step is shifted left to stay inside the row
+        const bool live = idx < steps;
 #pragma unroll
         for (int tw = 0; tw < TW; ++tw) {
-            slot[2 * tw] = row_load16<Ph::STREAM>(wr[tw], voff_w[tw], soff);
-            slot[2 * tw + 1] = row_load16<Ph::STREAM>(wr[tw], voff_w[tw] + 16, soff);
+            const int vo = live ? voff_w[tw] : (int)kOobOffset;
+            slot[2 * tw] = row_load16<Ph::STREAM>(wr[tw], vo, soff);
+            slot[2 * tw + 1] = row_load16<Ph::STREAM>(wr[tw], vo + 16, soff);
         }
 #pragma unroll
-        for (int r = 0; r < NP; ++r) slot[2 * TW + r] = row_load16<false>(ar, voff_g[r], soff);
-        if (++ik == steps) {
-            ik = 0;
-            ++ib;
-            if (ib < nblocks) setup_block(ib);
-        }
+        for (int r = 0; r < NP; ++r) slot[2 * TW + r] = row_load16<false>(ar, live ? voff_g[r] : (int)kOobOffset, soff);
     };
-    setup_block(0);
-#pragma unroll
-    for (int s = 0; s < D; ++s)
-        if (s < total) issue(ring[s]);
-    if (Ph::SCALE >= 0 && !p.bg_sep[Ph::WHICH]) batch_scales(p, Ph::SCALE, scale_lds); // visible after the first barrier
-
     f32x4 acc[kBatchAcc];
 #pragma unroll
     for (int a = 0; a < kBatchAcc; ++a) acc[a] = f32x4{0.f, 0.f, 0.f, 0.f};
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
     float *part = p.part;
-    int cb = 0, ck = 0;
-    for (int n0 = 0; n0 < total; n0 += D) {
+    for (int blk = 0; blk < nblocks; ++blk) {
+        setup_block(blk);
 #pragma unroll
-        for (int s = 0; s < D; ++s) {
-            if (n0 + s < total) { // uniform
-                const int ksn = ksA + ck;
+        for (int s = 0; s < D; ++s) issue(ring[s], s);
+        if (Ph::SCALE >= 0 && blk == 0 && !p.bg_sep[Ph::WHICH])
+            batch_scales(p, Ph::SCALE, scale_lds); // visible after the first step's barrier
+        for (int n0 = 0; n0 < steps; n0 += D) {
+#pragma unroll
+            for (int s = 0; s < D; ++s) {
+                const int idx = n0 + s;
+                const int ksn = ksA + idx;
                 const int ks = min(ksn, nks - 1);
                 const int koff = min(ks * 64, K - 64);
-                const int cut = ksn < ksB ? (ks * 64 - koff) / 8 : 8; // pieces counted before, or an empty range
+                // pieces counted before (ragged end), or a step past the range: zeros
+                const int cut = (idx < steps && ksn < ksB) ? (ks * 64 - koff) / 8 : 8;
                 // Park the chunk.  The buffer was last read two steps ago, and every wave has passed the barrier of
                 // the step in between since.
-                char *ab = abuf + ((n0 + s) & 1) * ABYTES;
+                char *ab = abuf + (idx & 1) * ABYTES;
 #pragma unroll
                 for (int r = 0; r < NP; ++r) *reinterpret_cast<u32x4 *>(ab + off_l[r]) = ring[s][2 * TW + r];
                 lds_barrier();
+                // all operands first, then the MFMAs ordered so that consecutive ones feed different accumulators
+                u32x4 ah[NA][2], al[NA][2];
 #pragma unroll
                 for (int at = 0; at < NA; ++at) {
                     const char *row = ab + (at * 16 + j) * AROW + g * 32;
-                    u32x4 ah[2], al[2];
 #pragma unroll
                     for (int hf = 0; hf < 2; ++hf) {
                         const bool dead = g * 2 + hf < cut;
-                        ah[hf] = dead ? zero4 : *reinterpret_cast<const u32x4 *>(row + hf * 16);
-                        al[hf] = dead ? zero4 : *reinterpret_cast<const u32x4 *>(row + 128 + hf * 16);
+                        const uint32_t keep = dead ? 0u : 0xFFFFFFFFu; // a mask, not a branch around the LDS read
+                        ah[at][hf] = *reinterpret_cast<const u32x4 *>(row + hf * 16) & keep;
+                        al[at][hf] = *reinterpret_cast<const u32x4 *>(row + 128 + hf * 16) & keep;
                     }
-#pragma unroll
-                    for (int hf = 0; hf < 2; ++hf)
-#pragma unroll
-                        for (int tw = 0; tw < TW; ++tw) {
-                            acc[tw * NA + at] = mfma16(ah[hf], ring[s][2 * tw + hf], acc[tw * NA + at]);
-                            acc[tw * NA + at] = mfma16(al[hf], ring[s][2 * tw + hf], acc[tw * NA + at]);
-                        }
                 }
-                if (n0 + s + D < total) issue(ring[s]);
-                if (++ck == steps) { // block complete: this wave's sums go to the partial buffer
-                    ck = 0;
 #pragma unroll
-                    for (int tw = 0; tw < TW; ++tw) {
-                        const int t = cb * TB + tile_of(tw);
+                for (int hf = 0; hf < 2; ++hf) {
 #pragma unroll
-                        for (int at = 0; at < NA; ++at) {
-                            if (t < nvt)
-                                *reinterpret_cast<f32x4 *>(
-                                    part + ((((size_t)kp * ntv + vt0 + t) * NA + at) * kWave + lane) * 4) = acc[tw * NA + at];
-                            acc[tw * NA + at] = f32x4{0.f, 0.f, 0.f, 0.f};
-                        }
-                    }
-                    ++cb;
+                    for (int tw = 0; tw < TW; ++tw)
+#pragma unroll
+                        for (int at = 0; at < NA; ++at)
+                            acc[tw * NA + at] = mfma16(ah[at][hf], ring[s][2 * tw + hf], acc[tw * NA + at]);
+#pragma unroll
+                    for (int tw = 0; tw < TW; ++tw)
+#pragma unroll
+                        for (int at = 0; at < NA; ++at)
+                            acc[tw * NA + at] = mfma16(al[at][hf], ring[s][2 * tw + hf], acc[tw * NA + at]);
                 }
+                issue(ring[s], idx + D);
             }
         }
+        // block complete: this wave's sums go to the partial buffer
+#pragma unroll
+        for (int tw = 0; tw < TW; ++tw) {
+            const int t = blk * TB + tile_of(tw);
+#pragma unroll
+            for (int at = 0; at < NA; ++at) {
+                if (t < nvt)
+                    *reinterpret_cast<f32x4 *>(part + ((((size_t)kp * ntv + vt0 + t) * NA + at) * kWave + lane) * 4) =
+                        acc[tw * NA + at];
+                acc[tw * NA + at] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+        }
+        __syncthreads(); // the LDS buffers are free for the next block; drains the ring's trailing requests
     }
     // With many reduction parts the last workgroup of a row group would add parts x tiles x sequence tiles partial
     // tiles alone: the host then launches the epilogue as a kernel of its own, spread over the whole chip.
