@@ -361,7 +361,8 @@ __device__ __forceinline__ void bgemv_lds(const DraftParams &p, Ph &ph, int RG, 
     const int steps = max(ksB - ksA, 1);
 
     char *abuf = smem;                                                    // [2][NA*16][AROW]
-    float *scale_lds = reinterpret_cast<float *>(smem + 2 * ABYTES);      // [kBatchMaxSeq]
+    char *strips = smem + 2 * ABYTES;                                     // [kWaves][2] transposition strips
+    float *scale_lds = reinterpret_cast<float *>(strips + kWaves * 2 * kStripBytes); // [kBatchMaxSeq]
     int *ids_lds = reinterpret_cast<int *>(scale_lds + kBatchMaxSeq);     // [rows of this row group]
     if (Ph::GATHER) {
         const int r0 = u0 * 16, nr = (u1 - u0) * 16;
@@ -387,7 +388,7 @@ __device__ __forceinline__ void bgemv_lds(const DraftParams &p, Ph &ph, int RG, 
     // as many waves busy as it has tiles
     auto tile_of = [&](int tw) { return (tw / NMAT) * (kWaves * NMAT) + wave * NMAT + (tw % NMAT); };
     row_rsrc wr[TW];
-    int voff_w[TW];
+    int voff_w[TW][2];
     auto setup_block = [&](int blk) {
 #pragma unroll
         for (int tw = 0; tw < TW; ++tw) {
@@ -396,10 +397,13 @@ __device__ __forceinline__ void bgemv_lds(const DraftParams &p, Ph &ph, int RG, 
             int mat_rows, row0, row_end;
             ph.tile(vt0 + min(t, nvt - 1), base, mat_rows, row0, row_end);
             wr[tw] = make_row_rsrc(base, (int)((size_t)mat_rows * K * 2));
-            const int r = row0 + j;
-            const bool ok = t < nvt && r < row_end;
-            const int phys = Ph::GATHER ? ids_lds[(min(t, nvt - 1) / NMAT) * 16 + j] : r;
-            voff_w[tw] = ok ? (int)((size_t)phys * K * 2 + g * 32) : (int)kOobOffset;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) { // a lane fetches row lane/8 [+ 8], bytes 16 (lane % 8): see strip_park
+                const int jr = (lane >> 3) + 8 * h, r = row0 + jr;
+                const bool ok = t < nvt && r < row_end;
+                const int phys = Ph::GATHER ? ids_lds[(min(t, nvt - 1) / NMAT) * 16 + jr] : r;
+                voff_w[tw][h] = ok ? (int)((size_t)phys * K * 2 + (lane & 7) * 16) : (int)kOobOffset;
+            }
         }
     };
     // branch-free refill, as in the core above: steps past the end of the range are requested beyond the buffers' ends
@@ -409,11 +413,10 @@ __device__ __forceinline__ void bgemv_lds(const DraftParams &p, Ph &ph, int RG, 
         const int soff = min(ks * 64, K - 64) * 2; // the last, ragged step is shifted left to stay inside the row
         const bool live = idx < steps;
 #pragma unroll
-        for (int tw = 0; tw < TW; ++tw) {
-            const int vo = live ? voff_w[tw] : (int)kOobOffset;
-            slot[2 * tw] = row_load16<Ph::STREAM>(wr[tw], vo, soff);
-            slot[2 * tw + 1] = row_load16<Ph::STREAM>(wr[tw], vo + 16, soff);
-        }
+        for (int tw = 0; tw < TW; ++tw)
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+                slot[2 * tw + h] = row_load16<Ph::STREAM>(wr[tw], live ? voff_w[tw][h] : (int)kOobOffset, soff);
 #pragma unroll
         for (int r = 0; r < NP; ++r) slot[2 * TW + r] = row_load16<false>(ar, live ? voff_g[r] : (int)kOobOffset, soff);
     };
@@ -421,6 +424,7 @@ __device__ __forceinline__ void bgemv_lds(const DraftParams &p, Ph &ph, int RG, 
 #pragma unroll
     for (int a = 0; a < kBatchAcc; ++a) acc[a] = f32x4{0.f, 0.f, 0.f, 0.f};
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
+    char *strip0 = strips + (size_t)wave * 2 * kStripBytes, *strip1 = strip0 + kStripBytes;
     float *part = p.part;
     for (int blk = 0; blk < nblocks; ++blk) {
         setup_block(blk);
@@ -456,18 +460,21 @@ __device__ __forceinline__ void bgemv_lds(const DraftParams &p, Ph &ph, int RG, 
                         al[at][hf] = *reinterpret_cast<const u32x4 *>(row + 128 + hf * 16) & keep;
                     }
                 }
+                // the weight tiles through the strips, one strip ahead of the MFMAs
+                strip_park(strip0, ring[s][0], ring[s][1]);
 #pragma unroll
-                for (int hf = 0; hf < 2; ++hf) {
+                for (int tw = 0; tw < TW; ++tw) {
+                    char *cur = (tw & 1) ? strip1 : strip0, *nxt = (tw & 1) ? strip0 : strip1;
+                    u32x4 w[2];
+                    strip_fetch(cur, w[0], w[1]);
+                    if (tw + 1 < TW) strip_park(nxt, ring[s][2 * tw + 2], ring[s][2 * tw + 3]);
 #pragma unroll
-                    for (int tw = 0; tw < TW; ++tw)
+                    for (int hf = 0; hf < 2; ++hf) {
 #pragma unroll
-                        for (int at = 0; at < NA; ++at)
-                            acc[tw * NA + at] = mfma16(ah[at][hf], ring[s][2 * tw + hf], acc[tw * NA + at]);
+                        for (int at = 0; at < NA; ++at) acc[tw * NA + at] = mfma16(ah[at][hf], w[hf], acc[tw * NA + at]);
 #pragma unroll
-                    for (int tw = 0; tw < TW; ++tw)
-#pragma unroll
-                        for (int at = 0; at < NA; ++at)
-                            acc[tw * NA + at] = mfma16(al[at][hf], ring[s][2 * tw + hf], acc[tw * NA + at]);
+                        for (int at = 0; at < NA; ++at) acc[tw * NA + at] = mfma16(al[at][hf], w[hf], acc[tw * NA + at]);
+                    }
                 }
                 issue(ring[s], idx + D);
             }

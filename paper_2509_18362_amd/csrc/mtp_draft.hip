@@ -592,9 +592,8 @@ int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_inde
         // waves split the 64/NA tiles of a block.  A phase with fewer tiles than that per workgroup splits the
         // reduction over KP workgroups, each keeping at least four double steps.
         const int na = B <= 16 ? 1 : B <= 32 ? 2 : 4;
-        // tiles a row group should hold at least: eight (up to 16 sequences: one group of a wave; above: one tile or
-        // pair of tiles per wave - fewer reduction parts are worth more than full blocks)
-        const int block_tiles = kBatchGroupTiles;
+        // tiles a row group should hold: eight up to 16 sequences (one group of a wave), a full block of 64/NA above
+        const int block_tiles = na == 1 ? kBatchGroupTiles : kWaves * (kBatchGroupTiles / na);
         auto plan = [&](int ph, int units, int nmat, int kdim) {
             const int nks = (kdim + 63) / 64; // double depth steps
             const long long ntv = (long long)units * nmat;
@@ -602,7 +601,7 @@ int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_inde
             if (na == 1 && ntv >= 4ll * grid) {
                 rg = std::min(grid, units);
             } else {
-                kp = (int)std::max(1ll, std::min<long long>((long long)grid * block_tiles * (na == 1 ? 1 : nmat) / ntv,
+                kp = (int)std::max(1ll, std::min<long long>((long long)grid * block_tiles / ntv,
                                                              na == 1 ? nks / kWaves : nks / 4));
                 kp = std::max(1, std::min(kp, grid));
                 rg = std::max(1, std::min(grid / kp, units));
