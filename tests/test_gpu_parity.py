@@ -145,6 +145,29 @@ def test_tiny_wide_batches(gpu, tiny, B):
     check_chain(ref, res, caches, act["kv_len"], 3)
 
 
+# head geometries that together instantiate every (query-group size, head dimension) variant of the attention kernels
+GEOMETRIES = [(4, 4, 64), (8, 2, 64), (8, 1, 64), (2, 2, 128), (2, 1, 128), (4, 1, 128), (8, 1, 128)]
+
+
+@pytest.mark.parametrize("hq,hkv,hd", GEOMETRIES)
+@pytest.mark.parametrize("long_splits", [False, True])
+def test_small_heads_every_attention_variant(gpu, hq, hkv, hd, long_splits):
+    """Group sizes 1, 2, 4, 8 at head dimensions 64 and 128, each through the short-split vector attention (small
+    cache capacity) and through the matrix-core attention with merged splits (large capacity), three sequences
+    (row-streaming matrix phases) with ragged contexts, K = 2."""
+    shape = synth.HeadShape(256, hq, hkv, hd, 512, 2048)
+    wl = synth.Workload(f"sweep_{hq}_{hkv}_{hd}", 40 + hq + 3 * hkv + hd, shape, 3, 0, 0, (512,), 2, 0.5,
+                        zipf_subset=False)
+    w = synth.make_weights(wl)
+    ids = synth.make_subsets(wl)[0]
+    ctx = np.array([0, 45, 700 if long_splits else 130], dtype=np.int32)
+    # three sequences and hkv KV heads: a split holds capacity * 3 * hkv / 256 tokens (at least 128)
+    cap = 768 if not long_splits else 256 * 256 // (3 * hkv) + 64
+    act = synth.make_activations(wl, ctx=ctx, capacity=cap)
+    ref, res, caches = run_both(gpu, shape, w, w, act, [ids], 0, 2)
+    check_chain(ref, res, caches, act["kv_len"], 2)
+
+
 def test_tiny_full_vocab_equals_identity_subset(gpu, tiny):
     """Eq. (3) with the identity list is the full head: same logits bit for bit on the device as well."""
     act = tiny["act"]
