@@ -148,6 +148,24 @@ def main() -> int:
                 "bytes_per_launch": head_bytes, "avg_launch_us": k_ms * 1e3,
                 "whole_path_achieved": path_gbs, "whole_path_frac": path_gbs / HBM_PEAK_GBS}
 
+    # spread of the K-step chain alone (HIP events inside the library around one mtp_draft_steps call), and the
+    # acceptance kernel alone (back-to-back launches between two events on the same stream)
+    binding.mtp_set_timing(eng.handle, binding.TIMING_CALL)
+    chain_us = []
+    for _ in range(min(args.steps, 100)):
+        one_step(args.subset, dummy)
+        chain_us.append(binding.mtp_last_draft_ms(eng.handle) * 1e3)
+    binding.mtp_set_timing(eng.handle, binding.TIMING_OFF)
+    p10, p50, p90 = (float(np.percentile(chain_us, q)) for q in (10, 50, 90))
+    n_acc = 200
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(n_acc):
+        binding.mtp_accept(eng.handle, B, K, draft, dummy, 1, kv, acc, out_tok, pend, stream)  # mode 1: kv_len unchanged
+    e1.record()
+    torch.cuda.synchronize()
+    accept_us = e0.elapsed_time(e1) * 1e3 / n_acc
+
     full = None
     if not args.no_full_vocab and args.subset >= 0:
         fs = max(10, args.steps // 4)
@@ -184,6 +202,8 @@ def main() -> int:
                                                                                    int(act["kv_len"].max())],
                    "head_rows": n_rows, "vocab": shape.vocab_size, "d_model": shape.d_model},
         "us_per_mtp_step": us_per_mtp_step, "mean_accept_len": mean_accept,
+        "chain_us": {"p10": p10, "p50": p50, "p90": p90, "what": f"{K} draft steps, one library call"},
+        "accept_us": accept_us,
         "algorithmic_bytes_per_step": chain_bytes, "roofline": roofline, "full_vocab": full, "cpu_baseline": cpu,
         "input_generation_s": gen_s,
     }
