@@ -249,7 +249,7 @@ __device__ __forceinline__ void bgemv(const DraftParams &p, Ph &ph, int RG, int 
 #pragma unroll
         for (int s = 0; s < D; ++s) issue(ring[s], s);
         // with the first loads under way: the norm scales for the epilogue (visible after the group's barrier)
-        if (Ph::SCALE >= 0 && grp == 0) batch_scales(p, Ph::SCALE, scale_lds);
+        if (Ph::SCALE >= 0 && grp == 0 && !p.bg_sep[Ph::WHICH]) batch_scales(p, Ph::SCALE, scale_lds);
         for (int n0 = 0; n0 < per; n0 += D) {
 #pragma unroll
             for (int s = 0; s < D; ++s) {
@@ -315,6 +315,7 @@ __device__ __forceinline__ void bgemv(const DraftParams &p, Ph &ph, int RG, int 
         }
     }
 
+    if (p.bg_sep[Ph::WHICH]) return; // the epilogue runs as a kernel of its own (see bgemv_lds)
     bg_tail<NA>(p, ph, KP, rg, ntv, vt0, reinterpret_cast<char *>(partial), scale_lds, [&](auto f) {
         constexpr int NQ = kBatchAcc / NMAT; // (tile or pair, sequence tile) slots with an epilogue: one per wave
         if (wave < NQ)
@@ -739,16 +740,18 @@ struct BgHead : BgBase {
     }
 };
 
-// The epilogue of a matrix phase as a kernel of its own: one wave per slot (tile, sequence tile), any grid.
+// The epilogue of a matrix phase as a kernel of its own: one wave per slot (tile or pair of tiles, sequence tile), any
+// grid; phases that keep state per workgroup (the output head's candidates) finish per workgroup of THIS kernel.
 template <int NA, class Ph>
 __device__ __forceinline__ void phase_bepilogue(const DraftParams &p, Ph &ph, int KP, char *smem) {
-    static_assert(Ph::NMAT == 1, "pairs keep the ticket path");
-    float *scale_lds = reinterpret_cast<float *>(smem);
+    constexpr int NMAT = Ph::NMAT;
+    float *scale_lds = reinterpret_cast<float *>(smem + kWaves * kBatchMaxSeq * 8); // behind finish()'s scratch
     if (Ph::SCALE >= 0) batch_scales(p, Ph::SCALE, scale_lds);
     __syncthreads();
-    const int ntv = (ph.rows + 15) / 16, nslots = ntv * NA;
+    const int ntv = (ph.rows + 15) / 16 * NMAT, nslots = ntv / NMAT * NA;
     for (int id = blockIdx.x * kWaves + threadIdx.x / kWave; id < nslots; id += gridDim.x * kWaves)
-        bg_slot_epilogue<NA>(p, ph, KP, ntv, id / NA, id % NA, scale_lds);
+        bg_slot_epilogue<NA>(p, ph, KP, ntv, (id / NA) * NMAT, id % NA, scale_lds);
+    ph.finish(blockIdx.x, smem);
 }
 
 // ---------------------------------------------------------------------------------------------------

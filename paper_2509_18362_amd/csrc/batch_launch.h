@@ -12,6 +12,8 @@ size_t bgemv_lds_bytes(int rows_per_group);
 bool batch_allow_lds(size_t lds_limit);
 // one batched matrix phase (BG_* index) for the sequences [p.b0, p.b0 + p.nb)
 void launch_bgemv(int phase, const DraftParams &p, int step, int grid, size_t lds, hipStream_t st);
+// workgroups of the separate epilogue kernel of a phase for `na` sequence tiles (at most 1024)
+int batch_epilogue_grid(int phase, const DraftParams &p, int na);
 // the preparation kernel before step `step` (step == K: after the last step), all sequences
 void launch_bprep(const DraftParams &p, int step, hipStream_t st);
 

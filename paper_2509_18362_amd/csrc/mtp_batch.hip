@@ -1,6 +1,8 @@
 // Kernels of the batched draft path (five or more sequences per call) for gfx950.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include "attn_mfma.h"
 #include "batch.h"
 #include "batch_launch.h"
@@ -42,8 +44,8 @@ __global__ __launch_bounds__(kBlock) void k_bgemv(DraftParams p, int step) {
 }
 
 template <int PH, int NA>
-__global__ __launch_bounds__(kBlock) void k_bepilogue(DraftParams p, int) {
-    __shared__ __align__(16) char smem[kBatchMaxSeq * 4];
+__global__ __launch_bounds__(kBlock) void k_bepilogue(DraftParams p, int step) {
+    __shared__ __align__(16) char smem[kWaves * kBatchMaxSeq * 8 + kBatchMaxSeq * 4];
     if constexpr (PH == BG_PROJ) {
         BgProj ph(p);
         phase_bepilogue<NA>(p, ph, p.bg_kp[PH], smem);
@@ -53,8 +55,14 @@ __global__ __launch_bounds__(kBlock) void k_bepilogue(DraftParams p, int) {
     } else if constexpr (PH == BG_OPROJ) {
         BgOproj ph(p);
         phase_bepilogue<NA>(p, ph, p.bg_kp[PH], smem);
-    } else {
+    } else if constexpr (PH == BG_GATEUP) {
+        BgGateUp ph(p);
+        phase_bepilogue<NA>(p, ph, p.bg_kp[PH], smem);
+    } else if constexpr (PH == BG_DOWN) {
         BgDown ph(p);
+        phase_bepilogue<NA>(p, ph, p.bg_kp[PH], smem);
+    } else {
+        BgHead ph(p, step);
         phase_bepilogue<NA>(p, ph, p.bg_kp[PH], smem);
     }
 }
@@ -106,20 +114,28 @@ bg_kernel_t pick(int phase, int na) {
 int tiles_for(int nb) { return nb <= 16 ? 1 : nb <= 32 ? 2 : 4; }
 template <int PH>
 bg_kernel_t pick_epilogue_na(int na) {
-    return na == 2 ? k_bepilogue<PH, 2> : k_bepilogue<PH, 4>;
+    return na == 1 ? k_bepilogue<PH, 1> : na == 2 ? k_bepilogue<PH, 2> : k_bepilogue<PH, 4>;
 }
 bg_kernel_t pick_epilogue(int phase, int na) {
     switch (phase) {
     case BG_PROJ: return pick_epilogue_na<BG_PROJ>(na);
     case BG_QKV: return pick_epilogue_na<BG_QKV>(na);
     case BG_OPROJ: return pick_epilogue_na<BG_OPROJ>(na);
-    default: return pick_epilogue_na<BG_DOWN>(na);
+    case BG_GATEUP: return pick_epilogue_na<BG_GATEUP>(na);
+    case BG_DOWN: return pick_epilogue_na<BG_DOWN>(na);
+    default: return pick_epilogue_na<BG_LMHEAD>(na);
     }
 }
 
 } // namespace
 
 size_t bgemv_lds_bytes(int rows_per_group) { return batch_lds_bytes(rows_per_group); }
+
+int batch_epilogue_grid(int phase, const DraftParams &p, int na) {
+    const int rows = phase == BG_QKV ? p.qkv_dim : phase == BG_GATEUP ? p.F : phase == BG_LMHEAD ? p.n : p.d;
+    const int slots = (rows + 15) / 16 * na;
+    return std::min((slots + kWaves - 1) / kWaves, 1024);
+}
 
 size_t attn_mfma_lds_bytes(int G, int HD) {
     switch (HD * 16 + G) {
@@ -155,11 +171,10 @@ bool batch_allow_lds(size_t lds_limit) {
 void launch_bgemv(int phase, const DraftParams &p, int step, int grid, size_t lds, hipStream_t st) {
     const int na = tiles_for(p.nb);
     hipLaunchKernelGGL(pick(phase, na), dim3(grid), dim3(kBlock), lds, st, p, step);
-    if (na > 1 && p.bg_sep[phase]) { // one wave per (tile, sequence tile)
-        const int rows = phase == BG_QKV ? p.qkv_dim : p.d;
-        const int slots = (rows + 15) / 16 * na;
-        hipLaunchKernelGGL(pick_epilogue(phase, na), dim3((slots + kWaves - 1) / kWaves), dim3(kBlock), 0, st, p, step);
-    }
+    if (p.bg_sep[phase]) // one wave per (tile or pair of tiles, sequence tile)
+        hipLaunchKernelGGL(pick_epilogue(phase, na),
+                           dim3(phase == BG_LMHEAD ? p.head_grid : batch_epilogue_grid(phase, p, na)), dim3(kBlock), 0, st,
+                           p, step);
 }
 
 void launch_bprep(const DraftParams &p, int step, hipStream_t st) {
