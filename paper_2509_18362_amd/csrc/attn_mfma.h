@@ -35,8 +35,8 @@ struct AttnMfmaLds {
     alignas(16) unsigned char v[kWaves][32][VS];
 };
 
-template <int G, int HD>
-__device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb, char *smem) {
+template <int G, int HD, bool COH = false, class Hook = NoHook>
+__device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb, char *smem, Hook before_q = Hook()) {
     using L = AttnMfmaLds<G, HD>;
     constexpr int NS = HD / 32;        // MFMA depth steps over the head dimension
     constexpr int NDB = HD / 16;       // 16-dimension blocks of the output
@@ -54,6 +54,7 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
     const int PW = HD + 2; // floats per (head, split) partial: acc[HD], max, sum
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
 
+    bool first_item = true;
     for (int item = vb; item < n_items; item += nvb) {
         const int b = item / (p.Hkv * S), rem = item % (p.Hkv * S), kvh = rem / S, sp = rem % S;
         const bool dead = seq_dead(p, b);
@@ -85,6 +86,10 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
             }
         };
         if (wave < niter) load_iter(wave); // in flight while q, the rotary table and the new key/value are prepared
+        if (first_item) {
+            before_q();
+            first_item = false;
+        }
 
         __syncthreads(); // LDS of the previous item is free
         if (tid < HD / 2) rope_cos_sin(pnew, p.rope_inv[tid], s.cs[tid], s.sn[tid]);
@@ -92,7 +97,7 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
         for (int idx = tid; idx < G * HD / 2; idx += kBlock) {
             int gq = idx / (HD / 2), jj = idx % (HD / 2);
             const float *src = qkv + (size_t)(kvh * G + gq) * HD;
-            float a = src[jj], bb = src[jj + HD / 2], cs = s.cs[jj], sn = s.sn[jj];
+            float a = ld_f32<COH>(src + jj), bb = ld_f32<COH>(src + jj + HD / 2), cs = s.cs[jj], sn = s.sn[jj];
             if (p.b_q) {
                 a += bf16_to_f32(p.b_q[(kvh * G + gq) * HD + jj]);
                 bb += bf16_to_f32(p.b_q[(kvh * G + gq) * HD + jj + HD / 2]);
@@ -106,7 +111,7 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
             if (tid >= kWave * 4 && tid < kWave * 4 + HD / 2) {
                 int e = tid - kWave * 4;
                 const float *src = qkv + p.qd + (size_t)kvh * HD;
-                float a = src[e], bb = src[e + HD / 2], cs = s.cs[e], sn = s.sn[e];
+                float a = ld_f32<COH>(src + e), bb = ld_f32<COH>(src + e + HD / 2), cs = s.cs[e], sn = s.sn[e];
                 if (p.b_k) {
                     a += bf16_to_f32(p.b_k[kvh * HD + e]);
                     bb += bf16_to_f32(p.b_k[kvh * HD + e + HD / 2]);
@@ -115,16 +120,16 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
                 s.knew[e] = bf16_to_f32(r0);
                 s.knew[e + HD / 2] = bf16_to_f32(r1);
                 if (!dead) {
-                    kdst[e] = r0;
-                    kdst[e + HD / 2] = r1;
+                    st_u16<COH>(kdst + e, r0);
+                    st_u16<COH>(kdst + e + HD / 2, r1);
                 }
             } else if (tid >= kWave * 6 && tid < kWave * 6 + HD) {
                 int e = tid - kWave * 6;
-                float vraw = qkv[p.qd + p.kvd + (size_t)kvh * HD + e];
+                float vraw = ld_f32<COH>(qkv + p.qd + p.kvd + (size_t)kvh * HD + e);
                 if (p.b_v) vraw += bf16_to_f32(p.b_v[kvh * HD + e]);
                 uint16_t r = f32_to_bf16(vraw);
                 s.vnew[e] = bf16_to_f32(r);
-                if (!dead) vdst[e] = r;
+                if (!dead) st_u16<COH>(vdst + e, r);
             }
         }
         __syncthreads();
@@ -277,7 +282,7 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
             int hq = kvh * G + g;
             if (nsplit == 1) {
                 const float r = A / Ls;
-                p.attn[(size_t)b * p.qd + (size_t)hq * HD + dd] = r;
+                st_f32<COH>(p.attn + (size_t)b * p.qd + (size_t)hq * HD + dd, r);
                 if (p.attn_split) {
                     uint16_t h, l;
                     split_bf16(r, h, l);
@@ -287,14 +292,15 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
                 }
             } else {
                 float *dst = p.attn_part + (((size_t)b * p.Hq + hq) * S + sp) * PW;
-                dst[dd] = A;
+                st_f32<COH>(dst + dd, A);
                 if (dd == 0) {
-                    dst[HD] = M;
-                    dst[HD + 1] = Ls;
+                    st_f32<COH>(dst + HD, M);
+                    st_f32<COH>(dst + HD + 1, Ls);
                 }
             }
         }
     }
+    if (first_item) before_q();
 }
 
 } // namespace mtp

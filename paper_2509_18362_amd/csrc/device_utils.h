@@ -89,6 +89,66 @@ __device__ __forceinline__ f32x4 mfma16(u32x4 a, u32x4 b, f32x4 c) {
 }
 
 __device__ __forceinline__ u32x4 ldg16(const void *p) { return *reinterpret_cast<const u32x4 *>(p); }
+
+// ---- device-coherent accesses ---------------------------------------------------------------------------
+// Inside ONE kernel, data handed from a workgroup to workgroups on other compute dies (each die has its own L2)
+// must bypass the non-coherent caches: relaxed atomics at device scope do exactly that, access by access, without
+// the write-back and invalidation of whole caches that a release/acquire pair costs (about 4 us per barrier here).
+// COH = false: plain accesses (data produced by an earlier kernel).
+template <bool COH>
+__device__ __forceinline__ float ld_f32(const float *p) {
+    if (COH) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return *p;
+}
+template <bool COH>
+__device__ __forceinline__ unsigned long long ld_u64(const unsigned long long *p) {
+    if (COH) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return *p;
+}
+template <bool COH>
+__device__ __forceinline__ f32x4 ld_f32x4(const float *p) { // 16-byte aligned
+    if (COH) {
+        const unsigned long long *q = reinterpret_cast<const unsigned long long *>(p);
+        unsigned long long a = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        unsigned long long b = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return f32x4{__uint_as_float((uint32_t)a), __uint_as_float((uint32_t)(a >> 32)), __uint_as_float((uint32_t)b),
+                     __uint_as_float((uint32_t)(b >> 32))};
+    }
+    return *reinterpret_cast<const f32x4 *>(p);
+}
+template <bool COH>
+__device__ __forceinline__ void st_f32(float *p, float v) {
+    if (COH)
+        __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else
+        *p = v;
+}
+template <bool COH>
+__device__ __forceinline__ void st_f32x4(float *p, f32x4 v) { // 16-byte aligned
+    if (COH) {
+        unsigned long long *q = reinterpret_cast<unsigned long long *>(p);
+        __hip_atomic_store(q, (unsigned long long)__float_as_uint(v.x) | ((unsigned long long)__float_as_uint(v.y) << 32),
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(q + 1, (unsigned long long)__float_as_uint(v.z) | ((unsigned long long)__float_as_uint(v.w) << 32),
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else {
+        *reinterpret_cast<f32x4 *>(p) = v;
+    }
+}
+template <bool COH>
+__device__ __forceinline__ void st_u64(unsigned long long *p, unsigned long long v) {
+    if (COH)
+        __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else
+        *p = v;
+}
+template <bool COH>
+__device__ __forceinline__ void st_u16(uint16_t *p, uint16_t v) {
+    if (COH)
+        __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else
+        *p = v;
+}
 // Row-streaming loads through a buffer descriptor: the wave-uniform row start and length sit in four scalar
 // registers, the position inside the row in one more, and a single vector register (16 bytes per lane) serves every
 // load.  No vector registers are spent - or recycled, which stalls on loads still in flight - on 64-bit address

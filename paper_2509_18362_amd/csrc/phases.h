@@ -41,6 +41,7 @@ struct DraftParams {
     int max_batch;
     // launch plan
     int split_tokens, max_splits; // attention: tokens per split, splits per (sequence, KV head)
+    int mfma_attn;                // the splits are long enough for the matrix-core attention
     int nb_proj, nb_d, nb_q, nb_down; // sequences staged in LDS per pass, by reduction length (2d, d, Hq*hd, F)
     // batched path (five or more sequences): activations travel between the phases as bf16 hi + lo in global memory
     uint16_t *act[2];    // two [max_batch][a_stride] hi arrays, each followed (a_lo elements later) by its lo array
@@ -86,11 +87,15 @@ __device__ __forceinline__ unsigned long long block_max_u64(unsigned long long v
 
 // Winner of the output head of `step` for sequence b: maximum over the candidates the head's workgroups left behind
 // (larger logit first, then lower subset index).  Called by all threads of a workgroup; contains barriers.
+template <bool COH = false>
 __device__ __forceinline__ unsigned long long winner_key(const DraftParams &p, int step, int b,
                                                          unsigned long long *red64) {
     const unsigned long long *cand = p.cand + ((size_t)step * p.max_batch + b) * p.head_grid;
     unsigned long long best = 0ull;
-    for (int w = threadIdx.x; w < p.head_grid; w += kBlock) best = cand[w] > best ? cand[w] : best;
+    for (int w = threadIdx.x; w < p.head_grid; w += kBlock) {
+        const unsigned long long c = ld_u64<COH>(cand + w);
+        best = c > best ? c : best;
+    }
     return block_max_u64(best, red64);
 }
 __device__ __forceinline__ int key_token(const DraftParams &p, unsigned long long key) {
@@ -108,7 +113,9 @@ constexpr int kMaxNormIter = 4; // d <= 4 * 4 * kBlock = 8192
 // hi/lo (bf16) and optionally to out_f32.  SRC_BF16: u is bf16 bits, else float.  Contains barriers.
 // add1/add2 (float, optional) are added to the source element-wise first, in that order: the residual stream is
 // kept as its summands and put together where it is consumed.
-template <bool SRC_BF16>
+// COH: the float source, add1, add2 are read and out_f32 is written with device-coherent accesses (out2_f32, an output
+// of the call, is not).
+template <bool SRC_BF16, bool COH = false>
 __device__ __forceinline__ void stage_rmsnorm(const void *src, const uint16_t *gain, int d, float eps, uint16_t *hi, uint16_t *lo,
                               float *red, float *out_f32, float *out2_f32 = nullptr, const float *add1 = nullptr,
                               const float *add2 = nullptr) {
@@ -125,21 +132,21 @@ __device__ __forceinline__ void stage_rmsnorm(const void *src, const uint16_t *g
                 v[it][2] = lo_half(raw.y);
                 v[it][3] = hi_half(raw.y);
             } else {
-                f32x4 raw = *reinterpret_cast<const f32x4 *>(static_cast<const float *>(src) + e);
+                f32x4 raw = ld_f32x4<COH>(static_cast<const float *>(src) + e);
                 v[it][0] = raw.x;
                 v[it][1] = raw.y;
                 v[it][2] = raw.z;
                 v[it][3] = raw.w;
             }
             if (add1) {
-                f32x4 a = *reinterpret_cast<const f32x4 *>(add1 + e);
+                f32x4 a = ld_f32x4<COH>(add1 + e);
                 v[it][0] += a.x;
                 v[it][1] += a.y;
                 v[it][2] += a.z;
                 v[it][3] += a.w;
             }
             if (add2) {
-                f32x4 a = *reinterpret_cast<const f32x4 *>(add2 + e);
+                f32x4 a = ld_f32x4<COH>(add2 + e);
                 v[it][0] += a.x;
                 v[it][1] += a.y;
                 v[it][2] += a.z;
@@ -169,7 +176,7 @@ __device__ __forceinline__ void stage_rmsnorm(const void *src, const uint16_t *g
             *reinterpret_cast<u32x2 *>(hi + e) = ph;
             *reinterpret_cast<u32x2 *>(lo + e) = pl;
             f32x4 w = {o[0], o[1], o[2], o[3]};
-            if (out_f32) *reinterpret_cast<f32x4 *>(out_f32 + e) = w;
+            if (out_f32) st_f32x4<COH>(out_f32 + e, w);
             if (out2_f32) *reinterpret_cast<f32x4 *>(out2_f32 + e) = w;
         }
     }
@@ -265,11 +272,12 @@ __device__ __forceinline__ unsigned long long winner_key_wave(const DraftParams 
 }
 
 // plain copy of a float vector of length K (multiple of 4) into hi/lo, zero-padded to kpad
+template <bool COH = false>
 __device__ __forceinline__ void stage_plain(const float *src, int K, int kpad, uint16_t *hi, uint16_t *lo) {
     for (int e = threadIdx.x * 4; e < kpad; e += kBlock * 4) {
         u32x2 ph = {0u, 0u}, pl = {0u, 0u};
         if (e < K) {
-            f32x4 raw = *reinterpret_cast<const f32x4 *>(src + e);
+            f32x4 raw = ld_f32x4<COH>(src + e);
             uint16_t h[4], l[4];
             split_bf16(raw.x, h[0], l[0]);
             split_bf16(raw.y, h[1], l[1]);
@@ -287,12 +295,13 @@ __device__ __forceinline__ void stage_plain(const float *src, int K, int kpad, u
 
 // m = silu(g) * u from the gate/up projection output gu = [g (F floats); u (F floats)], silu(z) = z / (1 + exp(-z)),
 // into hi/lo, zero-padded to kpad
+template <bool COH = false>
 __device__ __forceinline__ void stage_swiglu(const float *gu, int F, int kpad, uint16_t *hi, uint16_t *lo) {
     for (int e = threadIdx.x * 4; e < kpad; e += kBlock * 4) {
         u32x2 ph = {0u, 0u}, pl = {0u, 0u};
         if (e < F) {
-            f32x4 g = *reinterpret_cast<const f32x4 *>(gu + e);
-            f32x4 u = *reinterpret_cast<const f32x4 *>(gu + F + e);
+            f32x4 g = ld_f32x4<COH>(gu + e);
+            f32x4 u = ld_f32x4<COH>(gu + F + e);
             float m[4] = {(g.x / (1.0f + expf(-g.x))) * u.x, (g.y / (1.0f + expf(-g.y))) * u.y,
                           (g.z / (1.0f + expf(-g.z))) * u.z, (g.w / (1.0f + expf(-g.w))) * u.w};
             uint16_t h[4], l[4];
@@ -771,8 +780,14 @@ __device__ __forceinline__ void rope_cos_sin(int pos, double inv_freq, float &cs
     sn = sinf(rf);
 }
 
-template <int G, int HD>
-__device__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char *smem) {
+// COH: q/k/v are read, and the appended cache entries, the result and the split partials written, with
+// device-coherent accesses (the phases of a step run inside one kernel)
+struct NoHook {
+    __device__ __forceinline__ void operator()() const {}
+};
+// before_q: called once, by all threads, after the first cache loads have been requested and before q/k/v are read
+template <int G, int HD, bool COH = false, class Hook = NoHook>
+__device__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char *smem, Hook before_q = Hook()) {
     using L = AttnLds<G, HD>;
     constexpr int LPT = L::LPT, TPI = L::TPI, NSTREAM = L::NSTREAM, U = 4;
     L &s = *reinterpret_cast<L *>(smem);
@@ -783,6 +798,7 @@ __device__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char
     const float scale = 1.0f / sqrtf((float)HD);
     const int PW = HD + 2; // floats per (head, split) partial: acc[HD], max, sum
 
+    bool first_item = true;
     for (int item = vb; item < n_items; item += nvb) {
         const int b = item / (p.Hkv * S), rem = item % (p.Hkv * S), kvh = rem / S, sp = rem % S;
         const bool dead = seq_dead(p, b);
@@ -811,6 +827,10 @@ __device__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char
             }
         };
         load_blocks(wave); // in flight while q, the rotary table and the new key/value are prepared
+        if (first_item) {
+            before_q();
+            first_item = false;
+        }
 
         __syncthreads(); // LDS of the previous item is free
         if (tid < HD / 2) rope_cos_sin(pnew, p.rope_inv[tid], s.cs[tid], s.sn[tid]);
@@ -818,7 +838,7 @@ __device__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char
         for (int idx = tid; idx < G * HD / 2; idx += kBlock) {
             int gq = idx / (HD / 2), jj = idx % (HD / 2);
             const float *src = qkv + (size_t)(kvh * G + gq) * HD;
-            float a = src[jj], bb = src[jj + HD / 2], cs = s.cs[jj], sn = s.sn[jj];
+            float a = ld_f32<COH>(src + jj), bb = ld_f32<COH>(src + jj + HD / 2), cs = s.cs[jj], sn = s.sn[jj];
             if (p.b_q) {
                 a += bf16_to_f32(p.b_q[(kvh * G + gq) * HD + jj]);
                 bb += bf16_to_f32(p.b_q[(kvh * G + gq) * HD + jj + HD / 2]);
@@ -832,7 +852,7 @@ __device__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char
             if (tid >= kWave * 4 && tid < kWave * 4 + HD / 2) {
                 int e = tid - kWave * 4;
                 const float *src = qkv + p.qd + (size_t)kvh * HD;
-                float a = src[e], bb = src[e + HD / 2], cs = s.cs[e], sn = s.sn[e];
+                float a = ld_f32<COH>(src + e), bb = ld_f32<COH>(src + e + HD / 2), cs = s.cs[e], sn = s.sn[e];
                 if (p.b_k) {
                     a += bf16_to_f32(p.b_k[kvh * HD + e]);
                     bb += bf16_to_f32(p.b_k[kvh * HD + e + HD / 2]);
@@ -841,16 +861,16 @@ __device__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char
                 s.knew[e] = bf16_to_f32(r0);
                 s.knew[e + HD / 2] = bf16_to_f32(r1);
                 if (!dead) {
-                    kdst[e] = r0;
-                    kdst[e + HD / 2] = r1;
+                    st_u16<COH>(kdst + e, r0);
+                    st_u16<COH>(kdst + e + HD / 2, r1);
                 }
             } else if (tid >= kWave * 6 && tid < kWave * 6 + HD) {
                 int e = tid - kWave * 6;
-                float vraw = qkv[p.qd + p.kvd + (size_t)kvh * HD + e];
+                float vraw = ld_f32<COH>(qkv + p.qd + p.kvd + (size_t)kvh * HD + e);
                 if (p.b_v) vraw += bf16_to_f32(p.b_v[kvh * HD + e]);
                 uint16_t r = f32_to_bf16(vraw);
                 s.vnew[e] = bf16_to_f32(r);
-                if (!dead) vdst[e] = r;
+                if (!dead) st_u16<COH>(vdst + e, r);
             }
         }
         __syncthreads();
@@ -970,7 +990,7 @@ __device__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char
             int hq = kvh * G + g;
             if (nsplit == 1) {
                 const float r = A / Ls;
-                p.attn[(size_t)b * p.qd + (size_t)hq * HD + dd] = r;
+                st_f32<COH>(p.attn + (size_t)b * p.qd + (size_t)hq * HD + dd, r);
                 if (p.attn_split) {
                     uint16_t h, l;
                     split_bf16(r, h, l);
@@ -980,20 +1000,21 @@ __device__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char
                 }
             } else {
                 float *dst = p.attn_part + (((size_t)b * p.Hq + hq) * S + sp) * PW;
-                dst[dd] = A;
+                st_f32<COH>(dst + dd, A);
                 if (dd == 0) {
-                    dst[HD] = M;
-                    dst[HD + 1] = Ls;
+                    st_f32<COH>(dst + HD, M);
+                    st_f32<COH>(dst + HD + 1, Ls);
                 }
             }
         }
     }
+    if (first_item) before_q();
 }
 
 // phase 3b: merge of the split partials.  One wave per (sequence, query head) whose context spans several splits:
 // weights exp(max_s - max) / sum over splits are formed once (in a wave-private LDS strip), then every lane sums its
 // share of the head dimension with sixteen loads in flight.
-template <int HD>
+template <int HD, bool COH = false>
 __device__ void phase_attn_merge(const DraftParams &p, int step, int vb, int nvb, char *smem) {
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     const int T = p.split_tokens, S = p.max_splits;
@@ -1008,7 +1029,7 @@ __device__ void phase_attn_merge(const DraftParams &p, int step, int vb, int nvb
         const float *src = p.attn_part + ((size_t)b * p.Hq + hq) * S * PW;
         float M = -INFINITY;
         for (int s2 = lane; s2 < nsplit; s2 += kWave) {
-            float m = src[(size_t)s2 * PW + HD];
+            float m = ld_f32<COH>(src + (size_t)s2 * PW + HD);
             w[s2] = m;
             M = fmaxf(M, m);
         }
@@ -1018,7 +1039,7 @@ __device__ void phase_attn_merge(const DraftParams &p, int step, int vb, int nvb
         for (int s2 = lane; s2 < nsplit; s2 += kWave) {
             float e = expf(w[s2] - M);
             w[s2] = e;
-            Ls += src[(size_t)s2 * PW + HD + 1] * e;
+            Ls += ld_f32<COH>(src + (size_t)s2 * PW + HD + 1) * e;
         }
         Ls = wave_sum(Ls);
         const float inv = 1.0f / Ls;
@@ -1029,13 +1050,13 @@ __device__ void phase_attn_merge(const DraftParams &p, int step, int vb, int nvb
             for (; s2 + 16 <= nsplit; s2 += 16) {
                 float t[16];
 #pragma unroll
-                for (int u = 0; u < 16; ++u) t[u] = src[(size_t)(s2 + u) * PW + dd];
+                for (int u = 0; u < 16; ++u) t[u] = ld_f32<COH>(src + (size_t)(s2 + u) * PW + dd);
 #pragma unroll
                 for (int u = 0; u < 16; ++u) A += t[u] * w[s2 + u];
             }
-            for (; s2 < nsplit; ++s2) A += src[(size_t)s2 * PW + dd] * w[s2];
+            for (; s2 < nsplit; ++s2) A += ld_f32<COH>(src + (size_t)s2 * PW + dd) * w[s2];
             const float r = A * inv;
-            p.attn[(size_t)b * p.qd + (size_t)hq * HD + dd] = r;
+            st_f32<COH>(p.attn + (size_t)b * p.qd + (size_t)hq * HD + dd, r);
             if (p.attn_split) {
                 uint16_t h, l;
                 split_bf16(r, h, l);
