@@ -52,7 +52,6 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
     const int n_items = p.B * p.Hkv * S;
     const float scale = 1.0f / sqrtf((float)HD);
     const int PW = HD + 2; // floats per (head, split) partial: acc[HD], max, sum
-    const u32x4 zero4 = {0u, 0u, 0u, 0u};
 
     bool first_item = true;
     for (int item = vb; item < n_items; item += nvb) {

@@ -157,7 +157,7 @@ __device__ __forceinline__ void bgemv(const DraftParams &p, Ph &ph, int RG, int 
     const int wg = blockIdx.x;
     if (wg >= RG * KP) return;
     const int kp = wg % KP, rg = wg / KP;
-    const int lane = threadIdx.x & (kWave - 1), j = lane & 15, g = lane >> 4;
+    const int lane = threadIdx.x & (kWave - 1), g = lane >> 4;
     // said explicitly to be wave-uniform: offsets and descriptors derived from it then stay in scalar registers
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
     const int K = ph.K;
@@ -424,7 +424,6 @@ __device__ __forceinline__ void bgemv_lds(const DraftParams &p, Ph &ph, int RG, 
     f32x4 acc[kBatchAcc];
 #pragma unroll
     for (int a = 0; a < kBatchAcc; ++a) acc[a] = f32x4{0.f, 0.f, 0.f, 0.f};
-    const u32x4 zero4 = {0u, 0u, 0u, 0u};
     char *strip0 = strips + (size_t)wave * 2 * kStripBytes, *strip1 = strip0 + kStripBytes;
     float *part = p.part;
     for (int blk = 0; blk < nblocks; ++blk) {

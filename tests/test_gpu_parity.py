@@ -132,10 +132,10 @@ def test_tiny_long_capacity_matrix_core_attention(gpu, tiny):
     check_chain(ref, res, caches, act["kv_len"], 3)
 
 
-@pytest.mark.parametrize("B", [17, 20, 40, 70])
+@pytest.mark.parametrize("B", [17, 20, 40, 70, 130])
 def test_tiny_wide_batches(gpu, tiny, B):
     """Batches above 16 take the core whose waves split the tiles (two or four sequence tiles, the last one ragged);
-    70 sequences are two weight passes (64 + 6).  The tiny head has a reduction length (d_ffn = 688) that is not a
+    70 sequences are two weight passes (64 + 6), 130 are three (64 + 64 + 2).  The tiny head has a reduction length (d_ffn = 688) that is not a
     multiple of the 64-element double step, and row counts that leave most tile slots of a block empty."""
     wl = tiny["wl"]
     rng = np.random.default_rng(100 + B)
