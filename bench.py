@@ -58,6 +58,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full-vocab", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    ap.add_argument("--k-sweep-target-ms", type=float, default=0.0,
+                    help="if > 0: add a MODEL of the draft-length sweep (Sec. 3.5) for this assumed target-forward time")
     ap.add_argument("--copy-calib", action="store_true",
                     help="also run one plain 256 MiB device copy (a known-size reference for HBM byte counters)")
     args = ap.parse_args()
@@ -207,6 +209,12 @@ def main() -> int:
         "algorithmic_bytes_per_step": chain_bytes, "roofline": roofline, "full_vocab": full, "cpu_baseline": cpu,
         "input_generation_s": gen_s,
     }
+    if args.k_sweep_target_ms > 0:
+        from paper_2509_18362_amd import ksweep
+        line["k_sweep_model"] = {
+            "assumed_target_forward_ms": args.k_sweep_target_ms,
+            "acceptance": "paper's 0.81/0.56/0.36 cumulative (Sec. 3.4), later positions extrapolated",
+            "rows": ksweep.sweep(us_per_mtp_step * 1e-6, accept_us * 1e-6, args.k_sweep_target_ms * 1e-3)}
     eng.close()
     print(json.dumps(line))
     return 0

@@ -87,3 +87,17 @@ def test_one_hip_runtime_in_the_process():
         if "libamdhip64" in line:
             paths.add(os.path.realpath(line.split()[-1]))
     assert len(paths) == 1, paths
+
+
+def test_draft_length_sweep_model_matches_the_printed_tau():
+    """tau at K = 3 from the paper's per-position acceptance is the printed 2.73 (tests/golden/paper_values.txt);
+    with free drafting the speed-up equals tau, and it falls once a draft step costs more than it brings."""
+    from paper_2509_18362_amd import ksweep
+    cond = ksweep.conditional_rates(7)
+    assert abs(ksweep.expected_tokens(3, cond) - 2.73) < 1e-9
+    assert abs(cond[0] - 0.81) < 1e-12 and abs(cond[1] - 0.56 / 0.81) < 1e-12 and cond[3] == cond[2]
+    free = ksweep.sweep(0.0, 0.0, 1.0)
+    assert all(abs(r["speedup_vs_plain_decoding"] - r["tau"]) < 1e-12 for r in free)
+    costly = ksweep.sweep(0.5, 0.0, 1.0)
+    best = max(costly, key=lambda r: r["speedup_vs_plain_decoding"])["K"]
+    assert best < 7 and costly[-1]["speedup_vs_plain_decoding"] < costly[best - 1]["speedup_vs_plain_decoding"]
