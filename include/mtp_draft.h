@@ -172,10 +172,15 @@ float mtp_last_draft_ms(mtp_handle *h);
 
 /*
  * How mtp_draft_steps enqueues its work.
- *   0 (default) one launch per phase (7 or 8 per step) plus one to publish the last draft id.
- *   1           one cooperative launch runs all phases of all K steps; phases are separated by grid-wide
- *               barriers inside the kernel.  A barrier that is not passed within ~2 s sets MTP_ERR_TIMEOUT.
- * Results are identical in both modes.
+ *   0 (default) one launch per phase.  Up to four sequences: 7 or 8 launches per step plus one to publish the
+ *               last draft id.  Five or more: the batched kernels (every weight read once per pass of up to 64
+ *               sequences), one preparation launch per step, and one epilogue launch after each matrix phase whose
+ *               reduction is split over workgroups.
+ *   1           one cooperative launch runs all phases of all K steps (up to 16 sequences; otherwise as mode 0);
+ *               phases are separated by grid-wide barriers inside the kernel.  A barrier that is not passed within
+ *               ~2 s sets MTP_ERR_TIMEOUT.
+ * Other values return MTP_ERR_MODE.  Results agree between the modes to rounding (bit for bit up to four
+ * sequences).
  */
 int32_t mtp_set_launch_mode(mtp_handle *h, int32_t mode);
 
