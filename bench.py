@@ -55,6 +55,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--workload", default="c2_7b_b1")
     ap.add_argument("--subset", type=int, default=0, help="index into the workload's subset list; -1 = full vocabulary")
+    ap.add_argument("--identity-list", action="store_true",
+                    help="time the indirect head with the identity id list (all V rows through the gather path)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full-vocab", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
@@ -79,6 +81,9 @@ def main() -> int:
     w = synth.make_weights(wl if wl.shape is synth.TINY else synth.WORKLOADS["c2_7b_b1"], threads=16)
     act = synth.make_activations(wl, threads=16)
     subsets = synth.make_subsets(wl)
+    if args.identity_list:
+        subsets = list(subsets) + [np.arange(shape.vocab_size, dtype=np.int32)]
+        args.subset = len(subsets) - 1
     gen_s = time.time() - t0
     cap = act["kv_capacity"]
     eng = binding.DraftEngine(shape, w, subsets, B, cap, K, device="cuda:0")
@@ -194,6 +199,25 @@ def main() -> int:
         cpu = {"value": nseq * K * reps / el_c, "unit": "draft tokens/s", "cores": orc.threads, "kind": "oracle",
                "sample": f"{reps} repetitions of the oracle's K={K} chain on {nseq} of {B} sequences of {wl.name}",
                "us_per_mtp_step": el_c / (reps * K) * 1e6 / nseq * B}
+        # the same on one thread (one sequence, at least one chain, about a third of the budget)
+        all_threads = orc.threads
+        orc.set_threads(1)
+        reps1, t = 0, time.perf_counter()
+        while True:
+            orc.chain(K, act["hidden_in"][:1], act["token_in"][:1], act["k_cache"][:1].copy(),
+                      act["v_cache"][:1].copy(), act["kv_len"][:1], ids, want_logits=False, want_hidden=False)
+            reps1 += 1
+            el_1 = time.perf_counter() - t
+            if el_1 >= args.cpu_seconds / 3:
+                break
+        orc.set_threads(all_threads)
+        cpu["single_thread"] = {"value": K * reps1 / el_1, "unit": "draft tokens/s",
+                                "sample": f"{reps1} repetitions of the K={K} chain on 1 sequence"}
+        try:
+            with open("/proc/cpuinfo") as f:
+                cpu["cpu_model"] = next((l.split(":", 1)[1].strip() for l in f if l.startswith("model name")), None)
+        except OSError:
+            pass
 
     line = {
         "metric": "draft tokens/sec (and us per MTP step, HBM GB/s vs peak), compressed vs full vocab",
