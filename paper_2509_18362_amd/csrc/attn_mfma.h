@@ -6,8 +6,9 @@
 // MTP head is one decoder layer, here with grouped-query attention over its own KV cache).  A wave takes 32 tokens
 // per iteration:
 //   S^T = K Q^T   16x16x32 MFMAs with the 16 tokens of a tile as rows and the query heads of the KV head as columns
-//                 (G of 16 used); K rows come straight from the cache (a lane holds HD/4 consecutive elements of its
-//                 token), the query sits in registers as bf16 hi + lo, pre-multiplied by log2(e)/sqrt(HD).
+//                 (G of 16 used); K rows are loaded whole (coalesced) and turned into the operand layout (a lane
+//                 holds HD/4 consecutive elements of its token) through a wave-private LDS strip; the query sits in
+//                 registers as bf16 hi + lo, pre-multiplied by log2(e)/sqrt(HD).
 //   online softmax in the MFMA result layout: a lane holds 2 x 4 tokens of ONE head column, so the running maximum,
 //                 the rescale factor and the running sum are per-lane scalars; the maximum of a step is combined
 //                 over the four lane groups of a column with two shuffles.
@@ -33,6 +34,7 @@ struct AttnMfmaLds {
     float acc[NSTREAM][G][HD];
     float ml[NSTREAM][G][2];
     alignas(16) unsigned char v[kWaves][32][VS];
+    alignas(16) unsigned char k[kWaves][16][VS]; // one K tile per wave on its way into the MFMA operand layout
 };
 
 template <int G, int HD, bool COH = false, class Hook = NoHook>
@@ -72,12 +74,14 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
         u32x4 kn[2][NS], vr[NV];
         auto load_iter = [&](int it) {
 #pragma unroll
-            for (int tl = 0; tl < 2; ++tl) {
-                const int tok = min(it * 32 + tl * 16 + i16, ntok - 1); // rows past the end repeat the last one
-                const uint16_t *src = kc + (size_t)tok * HD + g4 * (HD / 4);
+            // K like V: a lane group of HD/8 lanes covers one row, so a load instruction reads whole rows (loaded
+            // straight into the operand layout every lane would touch another row, four times the address-unit work)
+            for (int tl = 0; tl < 2; ++tl)
 #pragma unroll
-                for (int u = 0; u < NS; ++u) kn[tl][u] = ldg16(src + u * 8);
-            }
+                for (int u = 0; u < NS; ++u) {
+                    const int tok = min(it * 32 + tl * 16 + u * TPI + lane / LPT, ntok - 1); // past the end: the last row again
+                    kn[tl][u] = ldg16(kc + (size_t)tok * HD + (lane % LPT) * 8);
+                }
 #pragma unroll
             for (int u = 0; u < NV; ++u) {
                 const int tok = min(it * 32 + u * TPI + lane / LPT, ntok - 1);
@@ -156,18 +160,29 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
         f32x4 oacc[NDB];
 #pragma unroll
         for (int db = 0; db < NDB; ++db) oacc[db] = f32x4{0.f, 0.f, 0.f, 0.f};
-        unsigned char *vrow = &s.v[wave][0][0];
+        unsigned char *vrow = &s.v[wave][0][0], *krow = &s.k[wave][0][0];
 
         for (int it = wave; it < niter; it += kWaves) {
             // park the V rows, then request the next iteration's rows into the same registers
 #pragma unroll
             for (int u = 0; u < NV; ++u)
                 *reinterpret_cast<u32x4 *>(vrow + (size_t)(u * TPI + lane / LPT) * L::VS + (lane % LPT) * 16) = vr[u];
+            // K through the wave's strip into the operand layout: row i16, elements g4*HD/4 + 8u .. +8 for step u
             u32x4 kcur[2][NS];
 #pragma unroll
-            for (int tl = 0; tl < 2; ++tl)
+            for (int tl = 0; tl < 2; ++tl) {
 #pragma unroll
-                for (int u = 0; u < NS; ++u) kcur[tl][u] = kn[tl][u];
+                for (int u = 0; u < NS; ++u)
+                    *reinterpret_cast<u32x4 *>(krow + (size_t)(u * TPI + lane / LPT) * L::VS + (lane % LPT) * 16) = kn[tl][u];
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+                for (int u = 0; u < NS; ++u)
+                    kcur[tl][u] = *reinterpret_cast<const u32x4 *>(krow + (size_t)i16 * L::VS + g4 * (HD / 2) + u * 16);
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+            }
             if (it + kWaves < niter) load_iter(it + kWaves);
 
             // scores of 2 x 16 tokens against the G heads
