@@ -21,8 +21,4 @@ void launch_bprep(const DraftParams &p, int step, hipStream_t st);
 size_t attn_mfma_lds_bytes(int G, int HD);
 void launch_attn_mfma(int G, int HD, const DraftParams &p, int step, int grid, size_t lds, hipStream_t st);
 
-// the whole call of one sequence as one cooperative kernel (persist.h): dynamic LDS, launch
-size_t persist_lds_bytes(int d, int qd, int F, int G, int HD, int max_splits, int *gemv_region);
-hipError_t launch_persist(int G, int HD, const DraftParams &p, int grid, size_t lds, hipStream_t st);
-
 } // namespace mtp

@@ -5,11 +5,20 @@
 // a phase that itself lasts 5-40 us.  Here every wave keeps a ring of weight chunks in registers; the first
 // chunks of the NEXT phase are requested right after the wave has signalled the end of the current phase, so
 // the memory system stays busy while the grid barrier completes and the new activations are staged.
+//
+// The barrier itself uses relaxed device-scope atomics only.  A release/acquire pair at device scope writes back
+// and invalidates whole caches (each compute die has its own L2): measured 6 us per barrier idle and 15 us on top
+// of a streaming phase, against 1.7 us and 5 us for the relaxed one.  What crosses a barrier - a few activation
+// vectors, the argmax candidates, the appended cache entries, the attention partials - is instead written and read
+// with device-coherent accesses (the <true> variants of the staging helpers and of ld_/st_ in device_utils.h),
+// access by access; weights and the older part of the KV cache are read-only inside the kernel and go through the
+// caches as usual.  An appended cache entry is written coherently by the one workgroup that owns it and read by
+// ordinary loads afterwards: no cache can hold an older copy of a slot that this call has not read before.
 #pragma once
 #include "phases.h"
 
 #ifndef FUSED_ATTN_CALL
-#define FUSED_ATTN_CALL(p, step, vb, nvb, smem) call_attn<G, HD>(p, step, vb, nvb, smem)
+#define FUSED_ATTN_CALL(p, step, vb, nvb, smem) call_attn<G, HD, true>(p, step, vb, nvb, smem)
 #endif
 
 namespace mtp {
@@ -29,21 +38,19 @@ constexpr int kBarStride = 32; // 64-bit words between counters: one 256-byte li
 constexpr size_t kBarWords = (size_t)kBarStride * (1 + 2 * kBarGroups);
 
 __device__ __forceinline__ void bar_arrive(const DraftParams &p, unsigned epoch) {
-    __syncthreads(); // every store of the phase has been issued and has completed (vmcnt(0))
+    __syncthreads(); // every store of the phase has completed (each wave waits for its own before the barrier)
     if (threadIdx.x == 0) {
         const int g = blockIdx.x % kBarGroups;
         const int gsize = ((int)gridDim.x - g + kBarGroups - 1) / kBarGroups;
         const unsigned long long e = p.bar_base + epoch; // barriers completed since the workspace was zeroed
         unsigned long long old =
-            __hip_atomic_fetch_add(p.bar + kBarStride * (1 + g), 1ull, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_fetch_add(p.bar + kBarStride * (1 + g), 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (old + 1 == e * (unsigned long long)gsize) {
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-            old = __hip_atomic_fetch_add(p.bar, 1ull, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+            old = __hip_atomic_fetch_add(p.bar, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (old + 1 == e * (unsigned long long)kBarGroups) {
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
 #pragma unroll
                 for (int i = 0; i < kBarGroups; ++i)
-                    __hip_atomic_store(p.bar + kBarStride * (1 + kBarGroups + i), e, __ATOMIC_RELEASE,
+                    __hip_atomic_store(p.bar + kBarStride * (1 + kBarGroups + i), e, __ATOMIC_RELAXED,
                                        __HIP_MEMORY_SCOPE_AGENT);
             }
         }
@@ -68,9 +75,8 @@ __device__ __forceinline__ void bar_wait(const DraftParams &p, unsigned epoch) {
                 }
             }
         }
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent"); // drop stale lines of L1 and of this XCD's L2
     }
-    lds_barrier(); // the other waves need not wait for their own prefetch here
+    lds_barrier(); // the other waves need not wait for their own prefetch here; also a compiler fence
 }
 
 template <int NMAT>
@@ -190,7 +196,10 @@ __device__ __forceinline__ void fused_steps2(const DraftParams &p, char *smem) {
                     // winner of the previous step: maximum over the workgroups' candidates
                     unsigned long long best = 0ull;
                     const unsigned long long *cand = p.cand + ((size_t)(step - 1) * p.max_batch + i) * nvb;
-                    for (int w = threadIdx.x; w < nvb; w += kBlock) best = cand[w] > best ? cand[w] : best;
+                    for (int w = threadIdx.x; w < nvb; w += kBlock) {
+                        const unsigned long long c = ld_u64<true>(cand + w);
+                        best = c > best ? c : best;
+                    }
                     best = block_max_u64(best, red64);
                     uint32_t bi = key_index(best);
                     if (bi >= (uint32_t)p.n) bi = 0;
@@ -207,11 +216,11 @@ __device__ __forceinline__ void fused_steps2(const DraftParams &p, char *smem) {
                 if (step == 0)
                     stage_rmsnorm<true>(p.hidden_in + (size_t)i * d, p.g_h, d, p.eps, hi, lo, l.red, nullptr);
                 else
-                    stage_rmsnorm<false>(p.hhat + (size_t)i * d, p.g_h, d, p.eps, hi, lo, l.red, nullptr);
+                    stage_rmsnorm<false, true>(p.hhat + (size_t)i * d, p.g_h, d, p.eps, hi, lo, l.red, nullptr);
                 stage_rmsnorm<true>(p.embed + (size_t)tok * d, p.g_e, d, p.eps, hi + d, lo + d, l.red, nullptr);
             }
             __syncthreads();
-            auto epi = [&](int i, int row, float(&s)[1]) { p.x[(size_t)i * d + row] = s[0]; };
+            auto epi = [&](int i, int row, float(&s)[1]) { st_f32<true>(p.x + (size_t)i * d + row, s[0]); };
             gemv_run<1>(gemv_geom<1>(2 * d, d, vb, nvb), RpProj{p}, ring, nb, nbmax, l.hi, l.lo, l.kpad, l.partial,
                         epi);
         }
@@ -224,10 +233,10 @@ __device__ __forceinline__ void fused_steps2(const DraftParams &p, char *smem) {
         {
             GemvLds l = gemv_lds(gemv_smem, d, nbmax, 1);
             for (int i = 0; i < nb; ++i)
-                stage_rmsnorm<false>(p.x + (size_t)i * d, p.g_attn, d, p.eps, l.hi + (size_t)i * l.kpad,
+                stage_rmsnorm<false, true>(p.x + (size_t)i * d, p.g_attn, d, p.eps, l.hi + (size_t)i * l.kpad,
                                      l.lo + (size_t)i * l.kpad, l.red, nullptr);
             __syncthreads();
-            auto epi = [&](int i, int row, float(&s)[1]) { p.qkv[(size_t)i * p.qkv_dim + row] = s[0]; };
+            auto epi = [&](int i, int row, float(&s)[1]) { st_f32<true>(p.qkv + (size_t)i * p.qkv_dim + row, s[0]); };
             gemv_run<1>(gemv_geom<1>(d, p.qkv_dim, vb, nvb), RpQkv{p}, ring, nb, nbmax, l.hi, l.lo, l.kpad,
                         l.partial, epi);
         }
@@ -241,7 +250,7 @@ __device__ __forceinline__ void fused_steps2(const DraftParams &p, char *smem) {
         bar_arrive(p, ++epoch);
         if (p.max_splits > 1) {
             bar_wait(p, epoch);
-            phase_attn_merge<HD>(p, step, vb, nvb, gemv_smem);
+            phase_attn_merge<HD, true>(p, step, vb, nvb, gemv_smem);
             bar_arrive(p, ++epoch);
         }
         fused_prime<FP_O>(p, ring, ids_lds);
@@ -252,10 +261,10 @@ __device__ __forceinline__ void fused_steps2(const DraftParams &p, char *smem) {
             GemvLds l = gemv_lds(gemv_smem, p.qd, nbmax, 1);
             __syncthreads();
             for (int i = 0; i < nb; ++i)
-                stage_plain(p.attn + (size_t)i * p.qd, p.qd, l.kpad, l.hi + (size_t)i * l.kpad,
+                stage_plain<true>(p.attn + (size_t)i * p.qd, p.qd, l.kpad, l.hi + (size_t)i * l.kpad,
                             l.lo + (size_t)i * l.kpad);
             __syncthreads();
-            auto epi = [&](int i, int row, float(&s)[1]) { p.o[(size_t)i * d + row] = s[0]; };
+            auto epi = [&](int i, int row, float(&s)[1]) { st_f32<true>(p.o + (size_t)i * d + row, s[0]); };
             gemv_run<1>(gemv_geom<1>(p.qd, d, vb, nvb), RpO{p}, ring, nb, nbmax, l.hi, l.lo, l.kpad, l.partial, epi);
         }
         stamp(step);
@@ -267,10 +276,10 @@ __device__ __forceinline__ void fused_steps2(const DraftParams &p, char *smem) {
         {
             GemvLds l = gemv_lds(gemv_smem, d, nbmax, 1);
             for (int i = 0; i < nb; ++i)
-                stage_rmsnorm<false>(p.x + (size_t)i * d, p.g_mlp, d, p.eps, l.hi + (size_t)i * l.kpad,
+                stage_rmsnorm<false, true>(p.x + (size_t)i * d, p.g_mlp, d, p.eps, l.hi + (size_t)i * l.kpad,
                                      l.lo + (size_t)i * l.kpad, l.red, nullptr, nullptr, p.o + (size_t)i * d);
             __syncthreads();
-            auto epi = [&](int i, int row, float(&s)[1]) { p.gu[(size_t)i * 2 * p.F + row] = s[0]; };
+            auto epi = [&](int i, int row, float(&s)[1]) { st_f32<true>(p.gu + (size_t)i * 2 * p.F + row, s[0]); };
             gemv_run<1>(gemv_geom<1>(d, 2 * p.F, vb, nvb), RpGateUp{p}, ring, nb, nbmax, l.hi, l.lo, l.kpad,
                         l.partial, epi);
         }
@@ -284,10 +293,10 @@ __device__ __forceinline__ void fused_steps2(const DraftParams &p, char *smem) {
             GemvLds l = gemv_lds(gemv_smem, p.F, nbmax, 1);
             __syncthreads();
             for (int i = 0; i < nb; ++i)
-                stage_swiglu(p.gu + (size_t)i * 2 * p.F, p.F, l.kpad, l.hi + (size_t)i * l.kpad,
+                stage_swiglu<true>(p.gu + (size_t)i * 2 * p.F, p.F, l.kpad, l.hi + (size_t)i * l.kpad,
                              l.lo + (size_t)i * l.kpad);
             __syncthreads();
-            auto epi = [&](int i, int row, float(&s)[1]) { p.dn[(size_t)i * d + row] = s[0]; };
+            auto epi = [&](int i, int row, float(&s)[1]) { st_f32<true>(p.dn + (size_t)i * d + row, s[0]); };
             gemv_run<1>(gemv_geom<1>(p.F, d, vb, nvb), RpDown{p}, ring, nb, nbmax, l.hi, l.lo, l.kpad, l.partial,
                         epi);
         }
@@ -302,7 +311,7 @@ __device__ __forceinline__ void fused_steps2(const DraftParams &p, char *smem) {
             for (int i = 0; i < nb; ++i) {
                 float *hh = (vb == 0) ? p.hhat + (size_t)i * d : nullptr;
                 float *ho = (vb == 0 && p.hidden_out) ? p.hidden_out + ((size_t)i * p.K + step) * d : nullptr;
-                stage_rmsnorm<false>(p.x + (size_t)i * d, p.g_final, d, p.eps, l.hi + (size_t)i * l.kpad,
+                stage_rmsnorm<false, true>(p.x + (size_t)i * d, p.g_final, d, p.eps, l.hi + (size_t)i * l.kpad,
                                      l.lo + (size_t)i * l.kpad, l.red, hh, ho, p.o + (size_t)i * d,
                                      p.dn + (size_t)i * d);
             }
@@ -322,7 +331,7 @@ __device__ __forceinline__ void fused_steps2(const DraftParams &p, char *smem) {
                     best = o2 > best ? o2 : best;
                 }
                 if ((threadIdx.x & 15) == 0)
-                    p.cand[((size_t)step * p.max_batch + (threadIdx.x >> 4)) * nvb + vb] = best;
+                    st_u64<true>(p.cand + ((size_t)step * p.max_batch + (threadIdx.x >> 4)) * nvb + vb, best);
             }
         }
         stamp(step);
@@ -336,7 +345,10 @@ __device__ __forceinline__ void fused_steps2(const DraftParams &p, char *smem) {
         for (int i = 0; i < nb; ++i) {
             unsigned long long best = 0ull;
             const unsigned long long *cand = p.cand + ((size_t)(p.K - 1) * p.max_batch + i) * nvb;
-            for (int w = threadIdx.x; w < nvb; w += kBlock) best = cand[w] > best ? cand[w] : best;
+            for (int w = threadIdx.x; w < nvb; w += kBlock) {
+                const unsigned long long c = ld_u64<true>(cand + w);
+                best = c > best ? c : best;
+            }
             best = block_max_u64(best, red64);
             uint32_t bi = key_index(best);
             if (bi >= (uint32_t)p.n) bi = 0;

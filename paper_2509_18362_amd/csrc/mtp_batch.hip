@@ -6,7 +6,6 @@
 #include "attn_mfma.h"
 #include "batch.h"
 #include "batch_launch.h"
-#include "persist.h"
 
 namespace mtp {
 namespace {
@@ -77,34 +76,6 @@ template <int G, int HD>
 __global__ __launch_bounds__(kBlock) void k_attn_mfma(DraftParams p, int step) {
     extern __shared__ __align__(16) char smem[];
     phase_attn_mfma<G, HD>(p, step, blockIdx.x, gridDim.x, smem);
-}
-
-template <int G, int HD>
-__global__ __launch_bounds__(kBlock) void k_persist(DraftParams) {
-    extern __shared__ __align__(16) char smem[];
-    // phases that are not inlined take the parameters by reference: point them at the kernel-argument segment (the
-    // struct is the only argument, at offset 0) instead of a per-lane stack copy
-    const DraftParams *p = (const DraftParams *)__builtin_amdgcn_kernarg_segment_ptr();
-    persist_steps<G, HD>(*p, smem);
-}
-typedef void (*persist_kernel_t)(DraftParams);
-persist_kernel_t persist_kernel(int G, int HD) {
-    if (HD == 128) {
-        switch (G) {
-        case 1: return k_persist<1, 128>;
-        case 2: return k_persist<2, 128>;
-        case 4: return k_persist<4, 128>;
-        case 8: return k_persist<8, 128>;
-        }
-    } else if (HD == 64) {
-        switch (G) {
-        case 1: return k_persist<1, 64>;
-        case 2: return k_persist<2, 64>;
-        case 4: return k_persist<4, 64>;
-        case 8: return k_persist<8, 64>;
-        }
-    }
-    return nullptr;
 }
 
 typedef void (*bg_kernel_t)(DraftParams, int);
@@ -184,31 +155,8 @@ void launch_attn_mfma(int G, int HD, const DraftParams &p, int step, int grid, s
     hipLaunchKernelGGL(attn_mfma_kernel(G, HD), dim3(grid), dim3(kBlock), lds, st, p, step);
 }
 
-size_t persist_lds_bytes(int d, int qd, int F, int G, int HD, int max_splits, int *gemv_region) {
-    size_t attn = (size_t)(HD / 2 * 0) + attn_mfma_lds_bytes(G, HD);
-    // the vector attention: q, rotary table, new k/v, per-lane-group accumulators and (max, sum)
-    const size_t ns = (size_t)kWaves * (kWave / (HD / 8));
-    const size_t vec = ((size_t)G * HD + HD + 2 * HD + ns * G * HD + ns * G * 2) * sizeof(float) + 64;
-    size_t region = std::max({gemv_lds_bytes(2 * d, 1, 1), gemv_lds_bytes(d, 1, 1), gemv_lds_bytes(qd, 1, 1),
-                              gemv_lds_bytes(F, 1, 1), attn + 64, vec, (size_t)kWaves * max_splits * 4 + 64});
-    region = (region + 255) / 256 * 256;
-    *gemv_region = (int)region;
-    return region + 256; // + the reduction scratch behind it
-}
-
-hipError_t launch_persist(int G, int HD, const DraftParams &p, int grid, size_t lds, hipStream_t st) {
-    persist_kernel_t fn = persist_kernel(G, HD);
-    if (!fn) return hipErrorInvalidValue;
-    void *args[] = {(void *)&p};
-    return hipLaunchCooperativeKernel((const void *)fn, dim3(grid), dim3(kBlock), args, (unsigned)lds, st);
-}
-
 bool batch_allow_lds(size_t lds_limit) {
     bool ok = true;
-    for (int hd = 64; hd <= 128; hd *= 2)
-        for (int g = 1; g <= 8; g *= 2)
-            ok = ok && hipFuncSetAttribute((const void *)persist_kernel(g, hd),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_limit) == hipSuccess;
     for (int hd = 64; hd <= 128; hd *= 2)
         for (int g = 1; g <= 8; g *= 2)
             ok = ok && hipFuncSetAttribute((const void *)attn_mfma_kernel(g, hd),

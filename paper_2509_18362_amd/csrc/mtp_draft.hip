@@ -515,35 +515,6 @@ int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_inde
 
     const int tphase = h->timing >= 2 ? h->timing - 2 : -1;
     h->pev_used = 0;
-    if (h->mode == 2 && tphase < 0 && B == 1 && p.d >= 512 && p.qd >= 512 && p.F >= 512) {
-        // One sequence: all phases of all K steps in one cooperative kernel on the row-streaming core, separated
-        // by relaxed grid barriers (persist.h).  Every workgroup must be resident at once: one per CU.
-        const int fgrid = std::min(h->num_cus, kMaxFusedGrid);
-        int region = 0;
-        const size_t lds_persist = persist_lds_bytes(p.d, p.qd, p.F, p.Hq / p.Hkv, p.hd, p.max_splits, &region);
-        if (lds_persist <= h->lds_limit) {
-            p.head_grid = fgrid;
-            p.fused_gemv_bytes = region;
-            p.mfma_attn = p.split_tokens >= kMfmaAttnMinSplit ? 1 : 0;
-            if (h->fused_grid != fgrid) { // first use, or the grid changed: restart the barrier counters
-                if (hipMemsetAsync(ws + l.bar, 0, kBarWords * 8, st) != hipSuccess) return MTP_ERR_HIP;
-                h->bar_epochs = 0;
-                h->fused_grid = fgrid;
-                p.bar_base = 0;
-            }
-            if (h->timing == 1) (void)hipEventRecord(h->ev[0], st);
-            if (launch_persist(p.Hq / p.Hkv, p.hd, p, fgrid, lds_persist, st) != hipSuccess) {
-                (void)hipGetLastError();
-                return MTP_ERR_HIP;
-            }
-            h->bar_epochs += (unsigned long long)K * (7 + (p.max_splits > 1 ? 1 : 0));
-            if (h->timing == 1) {
-                (void)hipEventRecord(h->ev[1], st);
-                h->ev_recorded = true;
-            }
-            return MTP_OK;
-        }
-    }
     if (h->mode == 1 && tphase < 0) {
         // single launch: all B sequences are staged together and every workgroup must be resident at once (one
         // per CU; the cooperative launch checks it).  Falls back to one launch per phase when LDS cannot hold B.
@@ -763,10 +734,7 @@ int32_t mtp_set_timing(mtp_handle *h, int32_t mode) {
 
 int32_t mtp_set_launch_mode(mtp_handle *h, int32_t mode) {
     if (!h) return MTP_ERR_NULL;
-    // Mode 2 (all steps of one sequence in one cooperative kernel with relaxed grid barriers, persist.h) is switched
-    // off: it matches the oracle on small heads, but its one run at the 7B shape ended in a GPU memory fault whose
-    // cause has not been found.
-    if (mode < 0 || mode > 1) return MTP_ERR_MODE;
+    if (mode != 0 && mode != 1) return MTP_ERR_MODE;
     h->mode = mode;
     return MTP_OK;
 }

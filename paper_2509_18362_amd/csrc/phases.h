@@ -1233,9 +1233,9 @@ __device__ void phase_finalize(const DraftParams &p, int vb, int nvb) {
 
 // Out-of-line copy of the attention phase for the single-launch kernel: inlined next to the weight-streaming code
 // it would share one register budget with the prefetch ring and spill.
-template <int G, int HD>
+template <int G, int HD, bool COH = false>
 __device__ __noinline__ void call_attn(const DraftParams &p, int step, int vb, int nvb, char *smem) {
-    phase_attn<G, HD>(p, step, vb, nvb, smem);
+    phase_attn<G, HD, COH>(p, step, vb, nvb, smem);
 }
 
 } // namespace mtp

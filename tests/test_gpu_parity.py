@@ -271,34 +271,6 @@ def test_single_launch_mode_matches_oracle(gpu, tiny):
     eng.close()
 
 
-@pytest.mark.skip(reason="the persistent kernel is switched off in the library: its run at the 7B shape ended in a GPU "
-                         "memory fault of unknown cause (these small-head cases passed)")
-@pytest.mark.parametrize("hq,hkv,hd,long_splits", [(4, 2, 128, False), (8, 2, 64, False), (4, 1, 128, True)])
-def test_persistent_kernel_matches_oracle(gpu, hq, hkv, hd, long_splits):
-    """One sequence, all K steps in one cooperative kernel with relaxed grid barriers and device-coherent hand-over
-    of the activations (every reduction length is at least 512 here, as the row-streaming core wants).  Several
-    calls on one engine: the barrier counters carry over, and the same workspace addresses are reused step after
-    step, call after call - stale cache lines would show as wrong logits."""
-    binding, torch = gpu["binding"], gpu["torch"]
-    shape = synth.HeadShape(512, hq, hkv, hd, 1024, 4096)
-    wl = synth.Workload(f"persist_{hq}_{hkv}_{hd}", 70 + hq + hkv + hd, shape, 1, 0, 0, (1024,), 4, 0.5, zipf_subset=False)
-    w = synth.make_weights(wl)
-    ids = synth.make_subsets(wl)[0]
-    cap = 512 if not long_splits else 256 * 256 // hkv + 64
-    eng = binding.DraftEngine(shape, w, [ids], 1, cap, 4)
-    assert binding.mtp_set_launch_mode(eng.handle, binding.LAUNCH_PERSISTENT) == 0
-    # (context, steps); the empty context with two steps only: from an empty context the chain amplifies rounding
-    # differences so much by its fourth step that appended keys can differ by two bf16 steps, on any launch mode
-    for ctx, K in ((300, 4), (0, 2), (77, 4), (450 if not long_splits else 1500, 4)):
-        act = synth.make_activations(wl, ctx=np.array([ctx], dtype=np.int32), capacity=cap)
-        ref, res, caches = run_both(gpu, shape, w, w, act, [ids], 0, K, engine=eng)
-        check_chain(ref, res, caches, act["kv_len"], K)
-        ref, res, caches = run_both(gpu, shape, w, w, act, [ids], 0, K, engine=eng, forced=None)
-        check_chain(ref, res, caches, act["kv_len"], K, aligned=False)
-    assert eng.poll_error() == 0
-    eng.close()
-
-
 # ------------------------------------------------------------------------------------------ accept / rollback
 @pytest.mark.parametrize("K", [1, 3, 5])
 @pytest.mark.parametrize("mode", [0, 1])
