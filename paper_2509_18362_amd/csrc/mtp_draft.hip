@@ -65,6 +65,12 @@ __global__ __launch_bounds__(kBlock) void k_fused(DraftParams) {
     const DraftParams *p = (const DraftParams *)__builtin_amdgcn_kernarg_segment_ptr();
     fused_steps2<G, HD>(*p, smem);
 }
+template <int G, int HD>
+__global__ __launch_bounds__(kBlock) void k_fused_rows(DraftParams) {
+    extern __shared__ __align__(16) char smem[];
+    const DraftParams *p = (const DraftParams *)__builtin_amdgcn_kernarg_segment_ptr();
+    fused_steps_rows<G, HD>(*p, smem);
+}
 
 // Sequential acceptance up to the first mismatch and the draft-cache length after it (Sec. 2.3 "Verification phase").
 __global__ void k_accept(int B, int K, const int *draft, const int *target, int mode, int *kv_len, int *accept_len,
@@ -121,6 +127,24 @@ fused_kernel_t fused_kernel(int G, int HD) {
         case 2: return k_fused<2, 64>;
         case 4: return k_fused<4, 64>;
         case 8: return k_fused<8, 64>;
+        }
+    }
+    return nullptr;
+}
+fused_kernel_t fused_rows_kernel(int G, int HD) {
+    if (HD == 128) {
+        switch (G) {
+        case 1: return k_fused_rows<1, 128>;
+        case 2: return k_fused_rows<2, 128>;
+        case 4: return k_fused_rows<4, 128>;
+        case 8: return k_fused_rows<8, 128>;
+        }
+    } else if (HD == 64) {
+        switch (G) {
+        case 1: return k_fused_rows<1, 64>;
+        case 2: return k_fused_rows<2, 64>;
+        case 4: return k_fused_rows<4, 64>;
+        case 8: return k_fused_rows<8, 64>;
         }
     }
     return nullptr;
@@ -250,6 +274,7 @@ struct mtp_handle {
     size_t lds_limit;
     phase_kernel_t attn_fn, merge_fn;
     fused_kernel_t fused_fn;
+    fused_kernel_t fused_rows_fn;  // one sequence, row-streaming core
     int mode;                    // 0: one launch per phase, 1: single cooperative launch for the whole call
     unsigned long long bar_epochs; // barriers completed by earlier single-launch calls (mirror of the device state)
     int fused_grid;                // workgroups of those calls; the counters assume it never changes
@@ -363,6 +388,7 @@ int32_t mtp_draft_init(mtp_handle **out, const mtp_config *cfg, const mtp_weight
     h->attn_fn = attn_kernel(cfg->n_q_heads / cfg->n_kv_heads, cfg->head_dim);
     h->merge_fn = cfg->head_dim == 128 ? k_attn_merge<128> : k_attn_merge<64>;
     h->fused_fn = fused_kernel(cfg->n_q_heads / cfg->n_kv_heads, cfg->head_dim);
+    h->fused_rows_fn = fused_rows_kernel(cfg->n_q_heads / cfg->n_kv_heads, cfg->head_dim);
     h->mode = 0;
     h->bar_epochs = 0;
     h->fused_grid = 0;
@@ -379,7 +405,7 @@ int32_t mtp_draft_init(mtp_handle **out, const mtp_config *cfg, const mtp_weight
                {(const void *)k_oproj, "k_oproj"},       {(const void *)k_gateup, "k_gateup"},
                {(const void *)k_down, "k_down"},         {(const void *)k_lmhead, "k_lmhead"},
                {(const void *)h->attn_fn, "k_attn"},     {(const void *)h->merge_fn, "k_attn_merge"},
-               {(const void *)h->fused_fn, "k_fused"}};
+               {(const void *)h->fused_fn, "k_fused"},   {(const void *)h->fused_rows_fn, "k_fused_rows"}};
     for (const auto &f : fns)
         if (ok) run(hipFuncSetAttribute(f.fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)h->lds_limit), f.name);
     if (ok && !batch_allow_lds(h->lds_limit)) {
@@ -521,7 +547,9 @@ int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_inde
         const int fgrid = std::min(h->num_cus, kMaxFusedGrid);
         size_t region = std::max({fused_gemv_region(p.d, p.qd, p.F, B), lds_attn, lds_merge});
         region = (region + 255) / 256 * 256;
-        const size_t ids_bytes = ((size_t)(p.n + fgrid - 1) / fgrid * 4 + 255) / 256 * 256;
+        // one sequence and every reduction at least 512 long: the row-streaming core, which keeps no id strip in LDS
+        const bool rows = B == 1 && p.d >= 512 && p.qd >= 512 && p.F >= 512;
+        const size_t ids_bytes = rows ? 0 : ((size_t)(p.n + fgrid - 1) / fgrid * 4 + 255) / 256 * 256;
         const size_t lds_fused = region + ids_bytes + 256;
         if (B <= 16 && lds_fused <= h->lds_limit) {
             p.head_grid = fgrid;
@@ -535,7 +563,7 @@ int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_inde
             }
             void *args[] = {(void *)&p};
             if (h->timing == 1) (void)hipEventRecord(h->ev[0], st);
-            if (hipLaunchCooperativeKernel((const void *)h->fused_fn, dim3(fgrid), dim3(kBlock), args,
+            if (hipLaunchCooperativeKernel((const void *)(rows ? h->fused_rows_fn : h->fused_fn), dim3(fgrid), dim3(kBlock), args,
                                            (unsigned)lds_fused, st) != hipSuccess) {
                 (void)hipGetLastError();
                 return MTP_ERR_HIP;

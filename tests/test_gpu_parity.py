@@ -75,7 +75,7 @@ def run_both(gpu, shape, w_host, w_dev, act, subsets, subset_index, K, engine=No
     return ref, res, (okc, ovc)
 
 
-def check_chain(ref, res, caches, kv_len, K, aligned=True):
+def check_chain(ref, res, caches, kv_len, K, aligned=True, need_clear=True):
     okc, ovc = caches
     gap = float(np.abs(ref["logits"] - res["logits"]).max()) if aligned else None
     if aligned:
@@ -83,7 +83,7 @@ def check_chain(ref, res, caches, kv_len, K, aligned=True):
         assert gap <= LOGIT_TIGHT, gap
         assert np.abs(ref["hidden"] - res["hidden"]).max() <= 2e-3
         clear = ref["margin"] > MARGIN
-        assert clear.any()
+        assert clear.any() or not need_clear
         np.testing.assert_array_equal(ref["draft"][clear], res["draft"][clear])
     else:  # free-running: compare every chain up to its first unclear step
         for b in range(ref["draft"].shape[0]):
@@ -269,6 +269,32 @@ def test_single_launch_mode_matches_oracle(gpu, tiny):
         check_chain(ref, res, caches, act["kv_len"], 3)
     assert binding.mtp_set_launch_mode(eng.handle, 7) == -11
     eng.close()
+
+
+ROW_GEOMETRIES = [(8, 8, 64), (8, 4, 64), (8, 2, 64), (8, 1, 64), (4, 4, 128), (4, 2, 128), (4, 1, 128), (8, 1, 128)]
+
+
+@pytest.mark.parametrize("hq,hkv,hd", ROW_GEOMETRIES)
+def test_single_launch_one_sequence_row_streaming(gpu, hq, hkv, hd):
+    """One sequence with every reduction at least 512 long takes the single-launch kernel on the row-streaming core.
+    Group sizes 1, 2, 4, 8 at both head dimensions; d_ffn = 688 is not a multiple of the 512-element row block; an
+    empty cache, a context inside one split (capacity 192) and several merged splits (capacity 768); every engine is
+    called twice, so the barrier counters carry over.  With one sequence and three steps a case may have no step
+    whose winner is clear of the runner-up; the ids are then only compared where it is."""
+    binding = gpu["binding"]
+    shape = synth.HeadShape(512, hq, hkv, hd, 688, 2048)
+    wl = synth.Workload(f"rows_{hq}_{hkv}_{hd}", 70 + hq + 3 * hkv + hd, shape, 1, 0, 0, (512,), 3, 0.5,
+                        zipf_subset=False)
+    w = synth.make_weights(wl)
+    ids = synth.make_subsets(wl)[0]
+    for ctx, cap, K in ((0, 192, 2), (150, 192, 3), (700, 768, 3)):
+        act = synth.make_activations(wl, ctx=np.array([ctx], dtype=np.int32), capacity=cap)
+        eng = binding.DraftEngine(shape, w, [ids], 1, cap, K)
+        assert binding.mtp_set_launch_mode(eng.handle, binding.LAUNCH_SINGLE) == 0
+        for _ in range(2):
+            ref, res, caches = run_both(gpu, shape, w, w, act, [ids], 0, K, engine=eng)
+            check_chain(ref, res, caches, act["kv_len"], K, need_clear=False)
+        eng.close()
 
 
 # ------------------------------------------------------------------------------------------ accept / rollback
