@@ -18,12 +18,12 @@
 #include "phases.h"
 
 #ifndef FUSED_ATTN_CALL
-#define FUSED_ATTN_CALL(p, step, vb, nvb, smem) call_attn<G, HD, true>(p, step, vb, nvb, smem)
+#define FUSED_ATTN_CALL(p, step, vb, nvb, smem) call_attn<G, HD, true, true>(p, step, vb, nvb, smem)
 #endif
 
 namespace mtp {
 
-constexpr int kBarriersPerStep = 7; // one more per step when the attention is split (max_splits > 1)
+constexpr int kBarriersPerStep = 7;
 
 // ---------------------------------------------------------------------------------------------------
 // split-phase grid barrier on a two-level tree of counters that only grow
@@ -247,12 +247,7 @@ __device__ __forceinline__ void fused_steps2(const DraftParams &p, char *smem) {
         // ---- attention (the ring is empty here) ----------------------------------------------------------------
         FUSED_ATTN_CALL(p, step, vb, nvb, gemv_smem);
         stamp(step);
-        bar_arrive(p, ++epoch);
-        if (p.max_splits > 1) {
-            bar_wait(p, epoch);
-            phase_attn_merge<HD, true>(p, step, vb, nvb, gemv_smem);
-            bar_arrive(p, ++epoch);
-        }
+        bar_arrive(p, ++epoch); // the splits of a long context were merged by the workgroup that finished last
         fused_prime<FP_O>(p, ring, ids_lds);
         bar_wait(p, epoch);
         stamp(step);
@@ -436,12 +431,7 @@ __device__ __forceinline__ void fused_steps_rows(const DraftParams &p, char *sme
         // ---- attention (no weights to request ahead) ---------------------------------------------------------
         FUSED_ATTN_CALL(p, step, vb, nvb, smem);
         stamp(step);
-        bar_arrive(p, ++epoch);
-        if (p.max_splits > 1) {
-            bar_wait(p, epoch);
-            phase_attn_merge<HD, true>(p, step, vb, nvb, smem);
-            bar_arrive(p, ++epoch);
-        }
+        bar_arrive(p, ++epoch); // the splits of a long context were merged by the workgroup that finished last
         stamp(step);
         // ---- output projection -------------------------------------------------------------------------------
         {

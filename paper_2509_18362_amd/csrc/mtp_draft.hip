@@ -33,7 +33,7 @@ __global__ __launch_bounds__(kBlock) void k_qkv(DraftParams p, int step) {
 template <int G, int HD>
 __global__ __launch_bounds__(kBlock) void k_attn(DraftParams p, int step) {
     extern __shared__ __align__(16) char smem[];
-    phase_attn<G, HD>(p, step, blockIdx.x, gridDim.x, smem);
+    phase_attn<G, HD, false, true>(p, step, blockIdx.x, gridDim.x, smem); // merges its own splits (tickets)
 }
 template <int HD>
 __global__ __launch_bounds__(kBlock) void k_attn_merge(DraftParams p, int step) {
@@ -204,7 +204,7 @@ size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 struct WsLayout {
     size_t x, qkv, attn, o, gu, dn, hhat, err, bar, cand, rope_inv, attn_part, total;
     // batched path (max_batch above kBatchMinSeq - 1 only)
-    size_t act0, act1, ssq, part, ticket, a_lo;
+    size_t act0, act1, ssq, part, ticket, a_lo, attn_ticket;
     int a_stride;
 };
 
@@ -242,6 +242,7 @@ WsLayout ws_layout(const mtp_config &c) {
     l.cand = take((size_t)c.max_draft_steps * mb * kMaxFusedGrid * 8);
     l.rope_inv = take((size_t)c.head_dim / 2 * 8);
     l.attn_part = take(attn_part_floats(c) * 4);
+    l.attn_ticket = take(mb * (size_t)c.n_kv_heads * 4);
     if (c.max_batch >= kBatchMinSeq) {
         size_t kmax = std::max({2 * d, qd, (size_t)c.d_ffn});
         l.a_stride = (int)((kmax + 31) / 32 * 32);
@@ -503,6 +504,7 @@ int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_inde
     p.err = reinterpret_cast<int *>(ws + l.err);
     p.rope_inv = reinterpret_cast<const double *>(ws + l.rope_inv);
     p.attn_part = reinterpret_cast<float *>(ws + l.attn_part);
+    p.attn_ticket = reinterpret_cast<int *>(ws + l.attn_ticket); // the vector attention merges its own splits
     p.bar = reinterpret_cast<unsigned long long *>(ws + l.bar);
     p.bar_base = h->bar_epochs;
     p.cand = reinterpret_cast<unsigned long long *>(ws + l.cand);
@@ -568,7 +570,7 @@ int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_inde
                 (void)hipGetLastError();
                 return MTP_ERR_HIP;
             }
-            h->bar_epochs += (unsigned long long)K * (kBarriersPerStep + (p.max_splits > 1 ? 1 : 0));
+            h->bar_epochs += (unsigned long long)K * kBarriersPerStep;
             if (h->timing == 1) {
                 (void)hipEventRecord(h->ev[1], st);
                 h->ev_recorded = true;
@@ -588,6 +590,7 @@ int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_inde
     // long splits go to the matrix-core attention; short ones (small batch, short context) to the latency-lean
     // vector version
     const bool mfma_attn = p.split_tokens >= kMfmaAttnMinSplit;
+    const bool merge_launch = mfma_attn && p.max_splits > 1; // the vector version merges its own splits
     auto launch_attention = [&](int step) {
         if (mfma_attn)
             launch_attn_mfma(p.Hq / p.Hkv, p.hd, p, step, attn_grid, lds_attn, st);
@@ -671,7 +674,7 @@ int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_inde
             matrix_phase(PH_QKV, BG_QKV, step);
             mark_begin(PH_ATTN, step);
             launch_attention(step);
-            if (p.max_splits > 1)
+            if (merge_launch)
                 hipLaunchKernelGGL(h->merge_fn, dim3(merge_grid), dim3(kBlock), lds_merge, st, p, step);
             mark_end(PH_ATTN, step);
             mark_begin(PH_OPROJ, step);
@@ -697,7 +700,7 @@ int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_inde
         mark_begin(PH_ATTN, step);
         launch_attention(step);
         mark_end(PH_ATTN, step);
-        if (p.max_splits > 1) launch(PH_MERGE, h->merge_fn, merge_grid, lds_merge, step);
+        if (merge_launch) launch(PH_MERGE, h->merge_fn, merge_grid, lds_merge, step);
         launch(PH_OPROJ, k_oproj, grid, lds_q, step);
         launch(PH_GATEUP, k_gateup, grid, lds_d2, step);
         launch(PH_DOWN, k_down, grid, lds_down, step);

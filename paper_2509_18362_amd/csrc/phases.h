@@ -51,6 +51,8 @@ struct DraftParams {
     float *ssq;          // [3][max_batch][d/16] sums of squares over 16-row tiles of x, x1, x2
     float *part;         // partial sums of the row groups, [KP][tiles][sequence tiles][64] x 4 floats
     int *ticket;         // arrival counters of the row groups (zero between launches)
+    int *attn_ticket;    // [max_batch][Hkv] arrival counters of the attention splits (zero between phases), or null:
+                         // then the splits are merged by phase_attn_merge
     int b0, nb;          // sequences of this pass
     int bg_rg[6], bg_kp[6]; // row groups and reduction parts of the six matrix phases
     int bg_sep[6];          // 1: the phase's epilogue runs as a kernel of its own
@@ -767,6 +769,7 @@ struct AttnLds {
     float knew[HD], vnew[HD];
     float acc[NSTREAM][G][HD];
     float ml[NSTREAM][G][2];
+    // the launch reserves 64 bytes more than the struct: the first word behind it is the "last split to finish" flag
 };
 
 // cos/sin of pos * inv_freq with the product and the reduction to [-pi, pi] in double, the rest in float
@@ -780,13 +783,62 @@ __device__ __forceinline__ void rope_cos_sin(int pos, double inv_freq, float &cs
     sn = sinf(rf);
 }
 
+// Merge of the split partials of one (sequence, query head) by ONE wave: weights exp(max_s - max) / sum over splits
+// are formed once (in the wave-private LDS strip w of max_splits floats), then every lane sums its share of the head
+// dimension with sixteen loads in flight.  PCOH: the partials are read with device-coherent loads; OCOH: the result
+// is written with a device-coherent store.
+template <int HD, bool PCOH, bool OCOH>
+__device__ __forceinline__ void merge_head(const DraftParams &p, int b, int hq, int nsplit, float *w) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int S = p.max_splits, PW = HD + 2;
+    const float *src = p.attn_part + ((size_t)b * p.Hq + hq) * S * PW;
+    float M = -INFINITY;
+    for (int s2 = lane; s2 < nsplit; s2 += kWave) {
+        float m = ld_f32<PCOH>(src + (size_t)s2 * PW + HD);
+        w[s2] = m;
+        M = fmaxf(M, m);
+    }
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) M = fmaxf(M, __shfl_xor(M, off, kWave));
+    float Ls = 0.f;
+    for (int s2 = lane; s2 < nsplit; s2 += kWave) {
+        float e = expf(w[s2] - M);
+        w[s2] = e;
+        Ls += ld_f32<PCOH>(src + (size_t)s2 * PW + HD + 1) * e;
+    }
+    Ls = wave_sum(Ls);
+    const float inv = 1.0f / Ls;
+    // w[] was written by this wave's own lanes: LDS ops of one wave complete in order, no barrier needed
+    for (int dd = lane; dd < HD; dd += kWave) {
+        float A = 0.f;
+        int s2 = 0;
+        for (; s2 + 16 <= nsplit; s2 += 16) {
+            float t[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) t[u] = ld_f32<PCOH>(src + (size_t)(s2 + u) * PW + dd);
+#pragma unroll
+            for (int u = 0; u < 16; ++u) A += t[u] * w[s2 + u];
+        }
+        for (; s2 < nsplit; ++s2) A += ld_f32<PCOH>(src + (size_t)s2 * PW + dd) * w[s2];
+        const float r = A * inv;
+        st_f32<OCOH>(p.attn + (size_t)b * p.qd + (size_t)hq * HD + dd, r);
+        if (p.attn_split) {
+            uint16_t h, l;
+            split_bf16(r, h, l);
+            const size_t at = (size_t)b * p.a_stride + (size_t)hq * HD + dd;
+            p.attn_split[at] = h;
+            p.attn_split[p.a_lo + at] = l;
+        }
+    }
+}
+
 // COH: q/k/v are read, and the appended cache entries, the result and the split partials written, with
 // device-coherent accesses (the phases of a step run inside one kernel)
 struct NoHook {
     __device__ __forceinline__ void operator()() const {}
 };
 // before_q: called once, by all threads, after the first cache loads have been requested and before q/k/v are read
-template <int G, int HD, bool COH = false, class Hook = NoHook>
+template <int G, int HD, bool COH = false, bool TICKET = false, class Hook = NoHook>
 __device__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char *smem, Hook before_q = Hook()) {
     using L = AttnLds<G, HD>;
     constexpr int LPT = L::LPT, TPI = L::TPI, NSTREAM = L::NSTREAM, U = 4;
@@ -1000,25 +1052,41 @@ __device__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char
                 }
             } else {
                 float *dst = p.attn_part + (((size_t)b * p.Hq + hq) * S + sp) * PW;
-                st_f32<COH>(dst + dd, A);
+                st_f32<COH || TICKET>(dst + dd, A);
                 if (dd == 0) {
-                    st_f32<COH>(dst + HD, M);
-                    st_f32<COH>(dst + HD + 1, Ls);
+                    st_f32<COH || TICKET>(dst + HD, M);
+                    st_f32<COH || TICKET>(dst + HD + 1, Ls);
                 }
             }
+        }
+        if (TICKET && nsplit > 1) {
+            // The workgroup whose split of this (sequence, KV head) is the last to finish merges the splits, one
+            // query head per wave.  The partials above were written through to memory and have been acknowledged
+            // (the wait below) before this workgroup draws its ticket, and the merging workgroup reads them past its
+            // caches, so relaxed atomics suffice.  The last workgroup also puts the counter back to zero.
+            int &last_to_arrive = *reinterpret_cast<int *>(smem + sizeof(L)); // behind the struct, clear of the strips
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            if (tid == 0) {
+                int *ticket = p.attn_ticket + (size_t)b * p.Hkv + kvh;
+                const int old = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (old == nsplit - 1) __hip_atomic_store(ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                last_to_arrive = (old == nsplit - 1) ? 1 : 0;
+            }
+            __syncthreads();
+            const bool merges = last_to_arrive != 0;
+            if (merges && wave < G)
+                merge_head<HD, true, COH>(p, b, kvh * G + wave, nsplit, reinterpret_cast<float *>(smem) + (size_t)wave * S);
         }
     }
     if (first_item) before_q();
 }
 
-// phase 3b: merge of the split partials.  One wave per (sequence, query head) whose context spans several splits:
-// weights exp(max_s - max) / sum over splits are formed once (in a wave-private LDS strip), then every lane sums its
-// share of the head dimension with sixteen loads in flight.
+// phase 3b: merge of the split partials, one wave per (sequence, query head) whose context spans several splits.
 template <int HD, bool COH = false>
 __device__ void phase_attn_merge(const DraftParams &p, int step, int vb, int nvb, char *smem) {
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const int wave = threadIdx.x / kWave;
     const int T = p.split_tokens, S = p.max_splits;
-    const int PW = HD + 2;
     float *w = reinterpret_cast<float *>(smem) + (size_t)wave * S;
     const int n_items = p.B * p.Hq;
     for (int item = vb * kWaves + wave; item < n_items; item += nvb * kWaves) {
@@ -1026,45 +1094,7 @@ __device__ void phase_attn_merge(const DraftParams &p, int step, int vb, int nvb
         const int Lb = seq_dead(p, b) ? 0 : p.kv_len[b];
         const int nsplit = (Lb + step + 1 + T - 1) / T;
         if (nsplit <= 1) continue; // finished by phase_attn
-        const float *src = p.attn_part + ((size_t)b * p.Hq + hq) * S * PW;
-        float M = -INFINITY;
-        for (int s2 = lane; s2 < nsplit; s2 += kWave) {
-            float m = ld_f32<COH>(src + (size_t)s2 * PW + HD);
-            w[s2] = m;
-            M = fmaxf(M, m);
-        }
-#pragma unroll
-        for (int off = 1; off < kWave; off <<= 1) M = fmaxf(M, __shfl_xor(M, off, kWave));
-        float Ls = 0.f;
-        for (int s2 = lane; s2 < nsplit; s2 += kWave) {
-            float e = expf(w[s2] - M);
-            w[s2] = e;
-            Ls += ld_f32<COH>(src + (size_t)s2 * PW + HD + 1) * e;
-        }
-        Ls = wave_sum(Ls);
-        const float inv = 1.0f / Ls;
-        // w[] was written by this wave's own lanes: LDS ops of one wave complete in order, no barrier needed
-        for (int dd = lane; dd < HD; dd += kWave) {
-            float A = 0.f;
-            int s2 = 0;
-            for (; s2 + 16 <= nsplit; s2 += 16) {
-                float t[16];
-#pragma unroll
-                for (int u = 0; u < 16; ++u) t[u] = ld_f32<COH>(src + (size_t)(s2 + u) * PW + dd);
-#pragma unroll
-                for (int u = 0; u < 16; ++u) A += t[u] * w[s2 + u];
-            }
-            for (; s2 < nsplit; ++s2) A += ld_f32<COH>(src + (size_t)s2 * PW + dd) * w[s2];
-            const float r = A * inv;
-            st_f32<COH>(p.attn + (size_t)b * p.qd + (size_t)hq * HD + dd, r);
-            if (p.attn_split) {
-                uint16_t h, l;
-                split_bf16(r, h, l);
-                const size_t at = (size_t)b * p.a_stride + (size_t)hq * HD + dd;
-                p.attn_split[at] = h;
-                p.attn_split[p.a_lo + at] = l;
-            }
-        }
+        merge_head<HD, COH, COH>(p, b, hq, nsplit, w);
     }
 }
 
@@ -1233,9 +1263,9 @@ __device__ void phase_finalize(const DraftParams &p, int vb, int nvb) {
 
 // Out-of-line copy of the attention phase for the single-launch kernel: inlined next to the weight-streaming code
 // it would share one register budget with the prefetch ring and spill.
-template <int G, int HD, bool COH = false>
+template <int G, int HD, bool COH = false, bool TICKET = false>
 __device__ __noinline__ void call_attn(const DraftParams &p, int step, int vb, int nvb, char *smem) {
-    phase_attn<G, HD, COH>(p, step, vb, nvb, smem);
+    phase_attn<G, HD, COH, TICKET>(p, step, vb, nvb, smem);
 }
 
 } // namespace mtp
