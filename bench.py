@@ -57,6 +57,9 @@ def main() -> int:
     ap.add_argument("--subset", type=int, default=0, help="index into the workload's subset list; -1 = full vocabulary")
     ap.add_argument("--identity-list", action="store_true",
                     help="time the indirect head with the identity id list (all V rows through the gather path)")
+    ap.add_argument("--launch-mode", default="auto", choices=("auto", "per-phase", "single"),
+                    help="how the library enqueues a call: one launch per phase, or one cooperative launch for all "
+                         "phases of all K steps; auto times both briefly for one sequence and keeps the faster")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full-vocab", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
@@ -128,6 +131,18 @@ def main() -> int:
         dst = torch.empty_like(src)
         dst.copy_(src)
         torch.cuda.synchronize()
+    mode_ids = {"per-phase": binding.LAUNCH_PER_PHASE, "single": binding.LAUNCH_SINGLE}
+    mode_us = {}
+    launch_mode = args.launch_mode
+    if launch_mode == "auto":
+        launch_mode = "per-phase"
+        if B == 1:  # the single launch pays off where a phase is short against a kernel boundary
+            for name, mid in mode_ids.items():
+                assert binding.mtp_set_launch_mode(eng.handle, mid) == 0
+                el, _ = timed(args.subset, max(20, args.steps // 5), max(5, args.warmup // 3))
+                mode_us[name] = el / (max(20, args.steps // 5) * K) * 1e6
+            launch_mode = min(mode_us, key=mode_us.get)
+    assert binding.mtp_set_launch_mode(eng.handle, mode_ids[launch_mode]) == 0
     elapsed, mean_accept = timed(args.subset, args.steps, args.warmup)
     n_rows = eng.subset_size(args.subset)
     chain_bytes = sum(algorithmic_bytes_per_mtp_step(shape, n_rows, act["kv_len"], k, args.subset >= 0)
@@ -226,7 +241,9 @@ def main() -> int:
         "vs_baseline": None, "dtype": "bf16 weights and KV, f32 accumulate", "data": "synthetic",
         "config": {"workload": wl.name, "batch": B, "draft_steps": K, "context": [int(act["kv_len"].min()),
                                                                                    int(act["kv_len"].max())],
-                   "head_rows": n_rows, "vocab": shape.vocab_size, "d_model": shape.d_model},
+                   "head_rows": n_rows, "vocab": shape.vocab_size, "d_model": shape.d_model,
+                   "launch_mode": launch_mode},
+        "launch_mode_trial_us_per_mtp_step": mode_us or None,
         "us_per_mtp_step": us_per_mtp_step, "mean_accept_len": mean_accept,
         "chain_us": {"p10": p10, "p50": p50, "p90": p90, "what": f"{K} draft steps, one library call"},
         "accept_us": accept_us,

@@ -520,7 +520,10 @@ constexpr int kRowModeMaxSeq = 4;
 
 // NB: compile-time number of sequence slots (1, 2 or 4); slots at or beyond nb compute on a zero operand.  The
 // consume loop must stay straight-line code, or the compiler falls back to waiting for every outstanding load.
-template <int NMAT, int NB, bool STREAM, class RowPtr, class Stage, class Epi>
+// DEPTH: chunks in flight per wave.  Two measure best (16 KiB per wave, 32 MiB over the chip); with three the phases
+// run 3-5 % slower.
+constexpr int kRowDepth = 2;
+template <int NMAT, int NB, bool STREAM, int DEPTH = kRowDepth, class RowPtr, class Stage, class Epi>
 __device__ __forceinline__ void gemv_rowmode(RowPtr rowptr, int K, int rows, int vb, int nvb, int nb,
                                              const uint16_t *act_hi, const uint16_t *act_lo, int kpad, Stage stage,
                                              Epi &epi) {
@@ -537,10 +540,15 @@ __device__ __forceinline__ void gemv_rowmode(RowPtr rowptr, int K, int rows, int
     const int nchunks = nrows * NMAT * cpr;                    // uniform per wave
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
 
-    // load stream position: (row, matrix, chunk within the row); stays on the last chunk past the end
-    int l_row = wr0, l_mt = 0, l_c = 0;
+    // load stream position: (row, matrix, chunk within the row), and the number of chunks requested so far.  A
+    // request past the wave's last chunk goes to an empty buffer (row 0, zero bytes): it returns zeros and moves no
+    // data, so the ring is filled and refilled without a branch.  After a conditional load the compiler no longer
+    // knows how many loads are outstanding and waits for all of them at the next use of any.
+    int l_row = wr0, l_mt = 0, l_c = 0, l_n = 0;
     auto issue_chunk = [&](u32x4(&buf)[kChunkLoads]) {
-        const row_rsrc rs = make_row_rsrc(rowptr(l_mt, min(l_row, wr_last)), K * 2); // uniform for the wave
+        const bool live = l_n < nchunks;
+        ++l_n;
+        const row_rsrc rs = make_row_rsrc(rowptr(l_mt, live ? min(l_row, wr_last) : 0), live ? K * 2 : 0); // uniform
 #pragma unroll
         for (int u = 0; u < kChunkLoads; ++u) {
             const int blk = min(l_c * kChunkLoads + u, nblk - 1); // empty slots of a row's last chunk re-read its last block
@@ -555,10 +563,9 @@ __device__ __forceinline__ void gemv_rowmode(RowPtr rowptr, int K, int rows, int
         }
     };
 
-    Ring ring;
+    u32x4 ring[DEPTH][kChunkLoads];
 #pragma unroll
-    for (int s = 0; s < kRingDepth; ++s)
-        if (s < nchunks) issue_chunk(ring.b[s]);
+    for (int s = 0; s < DEPTH; ++s) issue_chunk(ring[s]);
     stage(); // ends with a barrier: the activations are visible to every wave
     if (nchunks <= 0) return;
 
@@ -571,10 +578,13 @@ __device__ __forceinline__ void gemv_rowmode(RowPtr rowptr, int K, int rows, int
     float sums[NB][NMAT];
     const int dv = (lane & 15) - 4 * (lane >> 4); // which of this lane's four results lies on the diagonal, if any
     int c_row = wr0, c_mt = 0, c_c = 0;
-    for (int n0 = 0; n0 < nchunks; n0 += kRingDepth) {
+    for (int n0 = 0; n0 < nchunks; n0 += DEPTH) {
 #pragma unroll
-        for (int s = 0; s < kRingDepth; ++s) {
-            if (n0 + s < nchunks) { // uniform
+        for (int s = 0; s < DEPTH; ++s) {
+            // No branch around the loads of this body: slots past the wave's last chunk hold zeros and are "consumed"
+            // like the others, and every slot is refilled, so the number of loads in flight at each wait is known at
+            // compile time and a wait covers exactly the chunk that is consumed.
+            {
 #pragma unroll
                 for (int u = 0; u < kChunkLoads; ++u) {
                     const int blk = c_c * kChunkLoads + u;
@@ -590,12 +600,12 @@ __device__ __forceinline__ void gemv_rowmode(RowPtr rowptr, int K, int rows, int
                         const bool use = own && i < nb;
                         ah = use ? ah : zero4;
                         al = use ? al : zero4;
-                        acc_h[i] = mfma16(ah, ring.b[s][u], acc_h[i]);
-                        acc_l[i] = mfma16(al, ring.b[s][u], acc_l[i]);
+                        acc_h[i] = mfma16(ah, ring[s][u], acc_h[i]);
+                        acc_l[i] = mfma16(al, ring[s][u], acc_l[i]);
                     }
                 }
-                if (n0 + s + kRingDepth < nchunks) issue_chunk(ring.b[s]); // the slot is free again
-                if (++c_c == cpr) { // end of a row of matrix c_mt: sum the diagonal
+                issue_chunk(ring[s]); // the slot is free again
+                if (n0 + s < nchunks && ++c_c == cpr) { // end of a row of matrix c_mt: sum the diagonal
                     c_c = 0;
 #pragma unroll
                     for (int i = 0; i < NB; ++i) {
