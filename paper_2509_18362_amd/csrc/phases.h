@@ -802,6 +802,47 @@ __device__ __forceinline__ void merge_head(const DraftParams &p, int b, int hq, 
     const int lane = threadIdx.x & (kWave - 1);
     const int S = p.max_splits, PW = HD + 2;
     const float *src = p.attn_part + ((size_t)b * p.Hq + hq) * S * PW;
+    auto store = [&](int dd, float r) {
+        st_f32<OCOH>(p.attn + (size_t)b * p.qd + (size_t)hq * HD + dd, r);
+        if (p.attn_split) {
+            uint16_t h, l;
+            split_bf16(r, h, l);
+            const size_t at = (size_t)b * p.a_stride + (size_t)hq * HD + dd;
+            p.attn_split[at] = h;
+            p.attn_split[p.a_lo + at] = l;
+        }
+    };
+    // Up to 32 splits (the common case at one sequence): one round of loads.  Lane s reads the (max, sum) of split s,
+    // and every lane reads its HD/64 elements of all splits before any of it is used.
+    constexpr int ND = HD / kWave, NF = 32;
+    if (nsplit <= NF) {
+        float m = -INFINITY, l = 0.f, t[ND][NF];
+        if (lane < nsplit) {
+            m = ld_f32<PCOH>(src + (size_t)lane * PW + HD);
+            l = ld_f32<PCOH>(src + (size_t)lane * PW + HD + 1);
+        }
+#pragma unroll
+        for (int u = 0; u < NF; ++u)
+#pragma unroll
+            for (int k = 0; k < ND; ++k) t[k][u] = u < nsplit ? ld_f32<PCOH>(src + (size_t)u * PW + lane + k * kWave) : 0.f;
+        float M = m;
+#pragma unroll
+        for (int off = 1; off < kWave; off <<= 1) M = fmaxf(M, __shfl_xor(M, off, kWave));
+        const float e = lane < nsplit ? expf(m - M) : 0.f;
+        const float inv = 1.0f / wave_sum(l * e);
+        float A[ND];
+#pragma unroll
+        for (int k = 0; k < ND; ++k) A[k] = 0.f;
+#pragma unroll
+        for (int u = 0; u < NF; ++u) {
+            const float wu = __shfl(e, u, kWave);
+#pragma unroll
+            for (int k = 0; k < ND; ++k) A[k] += t[k][u] * wu;
+        }
+#pragma unroll
+        for (int k = 0; k < ND; ++k) store(lane + k * kWave, A[k] * inv);
+        return;
+    }
     float M = -INFINITY;
     for (int s2 = lane; s2 < nsplit; s2 += kWave) {
         float m = ld_f32<PCOH>(src + (size_t)s2 * PW + HD);
@@ -830,15 +871,7 @@ __device__ __forceinline__ void merge_head(const DraftParams &p, int b, int hq, 
             for (int u = 0; u < 16; ++u) A += t[u] * w[s2 + u];
         }
         for (; s2 < nsplit; ++s2) A += ld_f32<PCOH>(src + (size_t)s2 * PW + dd) * w[s2];
-        const float r = A * inv;
-        st_f32<OCOH>(p.attn + (size_t)b * p.qd + (size_t)hq * HD + dd, r);
-        if (p.attn_split) {
-            uint16_t h, l;
-            split_bf16(r, h, l);
-            const size_t at = (size_t)b * p.a_stride + (size_t)hq * HD + dd;
-            p.attn_split[at] = h;
-            p.attn_split[p.a_lo + at] = l;
-        }
+        store(dd, A * inv);
     }
 }
 
@@ -894,48 +927,62 @@ __device__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char
             first_item = false;
         }
 
-        __syncthreads(); // LDS of the previous item is free
-        if (tid < HD / 2) rope_cos_sin(pnew, p.rope_inv[tid], s.cs[tid], s.sn[tid]);
-        __syncthreads();
-        for (int idx = tid; idx < G * HD / 2; idx += kBlock) {
-            int gq = idx / (HD / 2), jj = idx % (HD / 2);
+        // Every global input of the prologue is requested before the first barrier, and the barriers order LDS
+        // traffic only, so the cache blocks above stay in flight: thread t < G*HD/2 rotates the element pair
+        // (t mod HD/2, + HD/2) of query head t / (HD/2); threads 256.. do the same for the new key, threads 384.. copy
+        // the new value.  256 is a multiple of HD/2, so a thread that has both duties uses one pair of rotary factors.
+        static_assert(G * HD / 2 <= kBlock && (kWave * 4) % (HD / 2) == 0 && kWave * 6 + HD <= kBlock, "thread roles");
+        const bool has_q = tid < G * HD / 2;
+        const bool has_k = last && tid >= kWave * 4 && tid < kWave * 4 + HD / 2;
+        const bool has_v = last && tid >= kWave * 6 && tid < kWave * 6 + HD;
+        const int jj = tid % (HD / 2), gq = tid / (HD / 2);
+        float qa = 0.f, qb = 0.f, ka = 0.f, kb = 0.f, vraw = 0.f, cs = 1.f, sn = 0.f;
+        if (has_q) {
             const float *src = qkv + (size_t)(kvh * G + gq) * HD;
-            float a = ld_f32<COH>(src + jj), bb = ld_f32<COH>(src + jj + HD / 2), cs = s.cs[jj], sn = s.sn[jj];
+            qa = ld_f32<COH>(src + jj);
+            qb = ld_f32<COH>(src + jj + HD / 2);
             if (p.b_q) {
-                a += bf16_to_f32(p.b_q[(kvh * G + gq) * HD + jj]);
-                bb += bf16_to_f32(p.b_q[(kvh * G + gq) * HD + jj + HD / 2]);
-            }
-            s.q[gq][jj] = (a * cs - bb * sn) * scale;
-            s.q[gq][jj + HD / 2] = (bb * cs + a * sn) * scale;
-        }
-        if (last) {
-            uint16_t *kdst = p.k_cache + (((size_t)b * p.Hkv + kvh) * p.cap + pnew) * HD;
-            uint16_t *vdst = p.v_cache + (((size_t)b * p.Hkv + kvh) * p.cap + pnew) * HD;
-            if (tid >= kWave * 4 && tid < kWave * 4 + HD / 2) {
-                int e = tid - kWave * 4;
-                const float *src = qkv + p.qd + (size_t)kvh * HD;
-                float a = ld_f32<COH>(src + e), bb = ld_f32<COH>(src + e + HD / 2), cs = s.cs[e], sn = s.sn[e];
-                if (p.b_k) {
-                    a += bf16_to_f32(p.b_k[kvh * HD + e]);
-                    bb += bf16_to_f32(p.b_k[kvh * HD + e + HD / 2]);
-                }
-                uint16_t r0 = f32_to_bf16(a * cs - bb * sn), r1 = f32_to_bf16(bb * cs + a * sn);
-                s.knew[e] = bf16_to_f32(r0);
-                s.knew[e + HD / 2] = bf16_to_f32(r1);
-                if (!dead) {
-                    st_u16<COH>(kdst + e, r0);
-                    st_u16<COH>(kdst + e + HD / 2, r1);
-                }
-            } else if (tid >= kWave * 6 && tid < kWave * 6 + HD) {
-                int e = tid - kWave * 6;
-                float vraw = ld_f32<COH>(qkv + p.qd + p.kvd + (size_t)kvh * HD + e);
-                if (p.b_v) vraw += bf16_to_f32(p.b_v[kvh * HD + e]);
-                uint16_t r = f32_to_bf16(vraw);
-                s.vnew[e] = bf16_to_f32(r);
-                if (!dead) st_u16<COH>(vdst + e, r);
+                qa += bf16_to_f32(p.b_q[(kvh * G + gq) * HD + jj]);
+                qb += bf16_to_f32(p.b_q[(kvh * G + gq) * HD + jj + HD / 2]);
             }
         }
-        __syncthreads();
+        if (has_k) {
+            const float *src = qkv + p.qd + (size_t)kvh * HD;
+            ka = ld_f32<COH>(src + jj);
+            kb = ld_f32<COH>(src + jj + HD / 2);
+            if (p.b_k) {
+                ka += bf16_to_f32(p.b_k[kvh * HD + jj]);
+                kb += bf16_to_f32(p.b_k[kvh * HD + jj + HD / 2]);
+            }
+        }
+        if (has_v) {
+            const int e = tid - kWave * 6;
+            vraw = ld_f32<COH>(qkv + p.qd + p.kvd + (size_t)kvh * HD + e);
+            if (p.b_v) vraw += bf16_to_f32(p.b_v[kvh * HD + e]);
+        }
+        if (has_q || has_k) rope_cos_sin(pnew, p.rope_inv[jj], cs, sn);
+        lds_barrier(); // LDS of the previous item is free
+        if (has_q) {
+            s.q[gq][jj] = (qa * cs - qb * sn) * scale;
+            s.q[gq][jj + HD / 2] = (qb * cs + qa * sn) * scale;
+        }
+        if (has_k) {
+            const uint16_t r0 = f32_to_bf16(ka * cs - kb * sn), r1 = f32_to_bf16(kb * cs + ka * sn);
+            s.knew[jj] = bf16_to_f32(r0);
+            s.knew[jj + HD / 2] = bf16_to_f32(r1);
+            if (!dead) {
+                uint16_t *kdst = p.k_cache + (((size_t)b * p.Hkv + kvh) * p.cap + pnew) * HD;
+                st_u16<COH>(kdst + jj, r0);
+                st_u16<COH>(kdst + jj + HD / 2, r1);
+            }
+        }
+        if (has_v) {
+            const int e = tid - kWave * 6;
+            const uint16_t r = f32_to_bf16(vraw);
+            s.vnew[e] = bf16_to_f32(r);
+            if (!dead) st_u16<COH>(p.v_cache + (((size_t)b * p.Hkv + kvh) * p.cap + pnew) * HD + e, r);
+        }
+        lds_barrier();
 
         float q[G][8];
 #pragma unroll
@@ -1023,7 +1070,6 @@ __device__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char
             }
             absorb(sc, vv, okn);
         }
-
         // merge the lane groups of the workgroup
         const int stream = wave * TPI + tq;
 #pragma unroll
@@ -1035,20 +1081,32 @@ __device__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char
                 s.ml[stream][g][1] = sum[g];
             }
         }
-        __syncthreads();
+        lds_barrier();
+        // wave g forms the weights of head g's streams once (lane = stream): exp(max_stream - max), zero for a stream
+        // that saw no token; they replace the stream maxima in LDS, and the head's maximum and weighted sum go where
+        // the rotary table used to be
+        static_assert(NSTREAM <= kWave && G <= kWaves && G <= HD / 2, "one wave per head, one lane per stream");
+        if (wave < G) {
+            const float mm = lane < NSTREAM ? s.ml[lane][wave][0] : -INFINITY;
+            const float ll = lane < NSTREAM ? s.ml[lane][wave][1] : 0.f;
+            float M = mm;
+#pragma unroll
+            for (int off = 1; off < kWave; off <<= 1) M = fmaxf(M, __shfl_xor(M, off, kWave));
+            const float w = mm != -INFINITY ? expf(mm - M) : 0.f;
+            const float Ls = wave_sum(ll * w);
+            if (lane < NSTREAM) s.ml[lane][wave][0] = w;
+            if (lane == 0) {
+                s.cs[wave] = M;
+                s.sn[wave] = Ls;
+            }
+        }
+        lds_barrier();
         for (int o = tid; o < G * HD; o += kBlock) {
             int g = o / HD, dd = o % HD;
-            float M = -INFINITY;
-            for (int st = 0; st < NSTREAM; ++st) M = fmaxf(M, s.ml[st][g][0]);
-            float Ls = 0.f, A = 0.f;
-            for (int st = 0; st < NSTREAM; ++st) {
-                float mm = s.ml[st][g][0];
-                if (mm != -INFINITY) {
-                    float w = expf(mm - M);
-                    Ls += s.ml[st][g][1] * w;
-                    A += s.acc[st][g][dd] * w;
-                }
-            }
+            const float M = s.cs[g], Ls = s.sn[g];
+            float A = 0.f;
+#pragma unroll 8
+            for (int st = 0; st < NSTREAM; ++st) A += s.acc[st][g][dd] * s.ml[st][g][0];
             int hq = kvh * G + g;
             if (nsplit == 1) {
                 const float r = A / Ls;
