@@ -386,6 +386,59 @@ int orc_chain(const orc_config *cfg, const orc_weights *w, int32_t B, int32_t K,
     return rc;
 }
 
+/* ---- first draft step over several new positions --------------------------- */
+
+/* Sec. 2.3 "Drafting phase": the first draft step runs over the shifted prefix, i.e. the head is applied to every new
+ * position with the TARGET model's hidden state of that position and the embedding of the token that follows it; the
+ * last position yields the first draft token, the others only extend the head's KV cache.  Position j of sequence b
+ * sits at cache slot kv_len[b] + j and attends slots 0 .. kv_len[b] + j (causal inside the new block).
+ * Here that is the one-position routine applied to the positions in order, each finding its predecessors' entries
+ * in the cache.
+ *   Arrays with a position axis are position-major: hidden_in [m_max][B][d] bf16, tokens [m_max][B],
+ *   draft_out [m_max][B], logits_out [m_max][B][n] or NULL, hidden_out [m_max][B][d] or NULL, margin_out
+ *   [m_max][B] or NULL.  ext_len [B]: number of new positions of each sequence, 0 .. m_max.
+ *   kv_len [B] is advanced by ext_len.  Positions at or beyond ext_len[b] report draft -1 and leave the other
+ *   outputs untouched.  A sequence whose new positions do not fit the cache (or with a negative length) is left
+ *   alone entirely (draft -1 everywhere, kv_len unchanged) and the function returns 1 after finishing the others.
+ */
+int orc_extend(const orc_config *cfg, const orc_weights *w, int32_t B, int32_t m_max, const uint16_t *hidden_in,
+               const int32_t *tokens, const int32_t *ext_len, uint16_t *k_cache, uint16_t *v_cache, int32_t *kv_len,
+               const int32_t *ids, int32_t n, int32_t *draft_out, real *logits_out, real *hidden_out,
+               real *margin_out) {
+    const int32_t d = cfg->d_model;
+    const size_t seq_stride = (size_t)cfg->n_kv_heads * cfg->kv_capacity * cfg->head_dim;
+    real *h = (real *)malloc((size_t)d * 2 * sizeof(real));
+    if (!h) return -13;
+    real *hhat = h + d;
+    int overflow = 0;
+    for (int32_t b = 0; b < B; ++b) {
+        const int32_t L = kv_len[b], m = ext_len[b];
+        for (int32_t j = 0; j < m_max; ++j) draft_out[(size_t)j * B + b] = -1;
+        if (L < 0 || m < 0 || m > m_max || L + m > cfg->kv_capacity) {
+            overflow = 1;
+            continue;
+        }
+        for (int32_t j = 0; j < m; ++j) {
+            const size_t r = (size_t)j * B + b;
+            for (int32_t i = 0; i < d; ++i) h[i] = (real)bf16_widen(hidden_in[r * d + i]);
+            int32_t did = -1;
+            real mg = 0;
+            int rc = orc_step(cfg, w, h, tokens[r], k_cache + b * seq_stride, v_cache + b * seq_stride, L + j, ids, n,
+                              hhat, logits_out ? logits_out + r * n : NULL, &did, &mg, NULL);
+            if (rc) {
+                free(h);
+                return rc;
+            }
+            draft_out[r] = did;
+            if (margin_out) margin_out[r] = mg;
+            if (hidden_out) memcpy(hidden_out + r * d, hhat, (size_t)d * sizeof(real));
+        }
+        kv_len[b] = L + m;
+    }
+    free(h);
+    return overflow;
+}
+
 /* ---- acceptance and cache bookkeeping ------------------------------------ */
 
 /* draft [B][K] = d_1..d_K, target [B][K+1] = g_1..g_{K+1} (the target model's greedy tokens at the same

@@ -223,6 +223,35 @@ class Oracle:
         return {"draft": draft, "logits": logits, "hidden": hidden, "margin": margin}
 
 
+    def extend(self, hidden_in_bits, tokens, ext_len, k_cache_bits, v_cache_bits, kv_len, ids,
+               want_logits: bool = True, want_hidden: bool = True):
+        """First draft step over several new positions (Sec. 2.3, "Drafting phase").
+        hidden_in_bits [m_max][B][d] bf16, tokens [m_max][B], ext_len [B].  Caches are updated in place.
+        Returns dict(draft [m_max][B], logits [m_max][B][n], hidden [m_max][B][d], margin [m_max][B],
+        kv_len [B] (new), overflow bool)."""
+        s = self.shape
+        hid = _u16(hidden_in_bits)
+        m_max, B = hid.shape[0], hid.shape[1]
+        tok = _i32(tokens).reshape(m_max, B)
+        el = _i32(ext_len)
+        kvl = _i32(kv_len).copy()
+        assert k_cache_bits.dtype == np.uint16 and k_cache_bits.flags.c_contiguous and v_cache_bits.flags.c_contiguous
+        assert k_cache_bits.shape[1:] == (s.n_kv_heads, self.cfg.kv_capacity, s.head_dim)
+        ids_a = None if ids is None else _i32(ids)
+        n = s.vocab_size if ids_a is None else ids_a.size
+        draft = np.full((m_max, B), -1, dtype=np.int32)
+        logits = np.zeros((m_max, B, n), dtype=self.real) if want_logits else None
+        hidden = np.zeros((m_max, B, s.d_model), dtype=self.real) if want_hidden else None
+        margin = np.zeros((m_max, B), dtype=self.real)
+        rc = self.lib.orc_extend(C.byref(self.cfg), C.byref(self.w), C.c_int32(B), C.c_int32(m_max), _ptr(hid),
+                                 _ptr(tok), _ptr(el), _ptr(k_cache_bits), _ptr(v_cache_bits), _ptr(kvl), _ptr(ids_a),
+                                 C.c_int32(n), _ptr(draft), _ptr(logits), _ptr(hidden), _ptr(margin))
+        if rc not in (0, 1):
+            raise ValueError(f"orc_extend failed: {rc}")
+        return {"draft": draft, "logits": logits, "hidden": hidden, "margin": margin, "kv_len": kvl,
+                "overflow": rc == 1}
+
+
 def accept(draft, target, kv_len, mode: int = 0, precision: str = "f32"):
     """Returns dict(accept_len [B], out_tokens [B][K+1], kv_len [B] (new), pending [B])."""
     build()

@@ -422,6 +422,145 @@ def test_batch_sequences_are_independent(orc, tiny):
         np.testing.assert_array_equal(one["logits"][0], full["logits"][b])
 
 
+# ---------------------------------------------------------------- first step over several positions
+def _extend_inputs(tiny, B, m_max, seed):
+    """Position-major synthetic inputs for the multi-position first step: bf16 hiddens like the workload's, tokens."""
+    s = tiny["shape"]
+    rng = np.random.default_rng(seed)
+    hid = rand_bits(rng, (m_max, B, s.d_model), std=float(synth.bf16_bits_to_f32(tiny["act"]["hidden_in"]).std()))
+    tok = rng.integers(0, s.vocab_size, size=(m_max, B)).astype(np.int32)
+    return hid, tok
+
+
+def test_extend_one_position_is_the_first_chain_step(orc, tiny):
+    act = tiny["act"]
+    B = len(act["kv_len"])
+    kc1, vc1 = act["k_cache"].copy(), act["v_cache"].copy()
+    kc2, vc2 = act["k_cache"].copy(), act["v_cache"].copy()
+    ch = orc.chain(1, act["hidden_in"], act["token_in"], kc1, vc1, act["kv_len"], tiny["ids"])
+    ex = orc.extend(act["hidden_in"][None], act["token_in"][None], np.ones(B, np.int32), kc2, vc2, act["kv_len"],
+                    tiny["ids"])
+    np.testing.assert_array_equal(ex["draft"][0], ch["draft"][:, 0])
+    np.testing.assert_array_equal(ex["logits"][0], ch["logits"][:, 0])
+    np.testing.assert_array_equal(ex["hidden"][0], ch["hidden"][:, 0])
+    np.testing.assert_array_equal(kc1, kc2)
+    np.testing.assert_array_equal(vc1, vc2)
+    np.testing.assert_array_equal(ex["kv_len"], act["kv_len"] + 1)
+
+
+def test_extend_vs_hf_qwen2_block_forward(orc, tiny):
+    """Four new positions through the Hugging Face Qwen2 layer in float64 against the oracle's position-by-position
+    result.  (1) One forward over the whole block with a causal mask on top of the prior cache: the library keeps
+    the new keys and values unrounded, hence the loose tolerance of the single-position pin.  (2) Position by
+    position with the library's own pieces on the cache as the oracle left it (new entries rounded to bf16): tight,
+    and a visible range that is one slot short is three orders of magnitude outside it.  Together they pin the
+    bookkeeping: position j sits at slot L + j, is rotated for that position, and sees slots 0 .. L + j."""
+    from transformers.cache_utils import DynamicCache
+    s, w, act = tiny["shape"], tiny["w"], tiny["act"]
+    m_lib, cfg, layer, rot = _hf_layer(s, w)
+    mm = 4
+    L = int(act["kv_len"][0])
+    hid, tok = _extend_inputs(tiny, 1, mm, 11)
+    kc, vc = act["k_cache"][:1].copy(), act["v_cache"][:1].copy()
+    ex = orc.extend(hid, tok, np.array([mm], np.int32), kc, vc, act["kv_len"][:1], tiny["ids"])
+    # the decoder layer's input at each position: dual norm + concat + projection (pinned on its own above)
+    d = s.d_model
+    xs = []
+    for j in range(mm):
+        c = torch.cat([F.rms_norm(widen(hid[j, 0]), (d,), widen(w["g_hnorm"]), eps=s.rms_eps),
+                       F.rms_norm(widen(w["embed"][tok[j, 0]]), (d,), widen(w["g_enorm"]), eps=s.rms_eps)])
+        xs.append(F.linear(c, widen(w["w_proj"])))
+    x = torch.stack(xs)[None]                                   # [1][m][d]
+    pos = torch.arange(L, L + mm)[None]
+    cos, sin = rot(x, pos)
+    fin = lambda t: F.rms_norm(t.reshape(-1, d), (d,), widen(w["g_final_norm"]), eps=s.rms_eps).numpy()
+    with torch.no_grad():
+        # (1) the block at once
+        cache = DynamicCache(config=cfg)
+        cache.update(widen(act["k_cache"])[0:1, :, :L], widen(act["v_cache"])[0:1, :, :L], 0)
+        mask = torch.zeros(1, 1, mm, L + mm, dtype=torch.float64)
+        for j in range(mm):
+            mask[0, 0, j, L + j + 1:] = -math.inf
+        out = layer(x, attention_mask=mask, position_ids=pos, past_key_values=cache, use_cache=True,
+                    position_embeddings=(cos, sin))
+        out = out[0] if isinstance(out, tuple) else out
+        hhat = fin(out)
+        scale = float(np.abs(hhat).max())
+        assert np.abs(ex["hidden"][:, 0] - hhat).max() < 2e-3 * scale
+        # (2) position by position on the stored cache
+        att = layer.self_attn
+        y = layer.input_layernorm(x)
+        shp = (1, mm, -1, s.head_dim)
+        q = att.q_proj(y).view(shp).transpose(1, 2)
+        k = att.k_proj(y).view(shp).transpose(1, 2)
+        q, k = m_lib.apply_rotary_pos_emb(q, k, cos, sin)
+        if orc.real == np.float32:   # the stored keys are the library's keys for positions L .. L+m-1, rounded
+            k_bits = k.float().to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)[0]   # [Hkv][m][hd]
+            assert (kc[0][:, L:L + mm] != k_bits).mean() < 0.01     # float32 rotary table: a rare last-bit flip
+        for j in range(mm):
+            for visible, close in ((L + j + 1, True), (L + j, False)):
+                Kall, Vall = widen(kc)[0:1, :, :visible], widen(vc)[0:1, :, :visible]
+                a, _ = m_lib.eager_attention_forward(att, q[:, :, j:j + 1], Kall, Vall, None,
+                                                     scaling=s.head_dim ** -0.5, dropout=0.0)
+                x1 = x[:, j:j + 1] + att.o_proj(a.reshape(1, 1, -1))
+                x2 = x1 + layer.mlp(layer.post_attention_layernorm(x1))
+                gap = float(np.abs(ex["hidden"][j, 0] - fin(x2)[0]).max())
+                assert (gap < 3e-5 * scale) if close else (gap > 3e-4 * scale), (j, visible, gap)
+
+
+def test_extend_is_causal_splittable_and_ragged(orc, tiny):
+    act = tiny["act"]
+    B = len(act["kv_len"])
+    mm = 5
+    hid, tok = _extend_inputs(tiny, B, mm, 12)
+    ext = np.array([(3 * b + 5) % (mm + 1) for b in range(B)], np.int32)   # 0 .. mm, ragged
+    ext[0] = mm
+    if B > 1:
+        ext[1] = 0
+    kc, vc = act["k_cache"].copy(), act["v_cache"].copy()
+    full = orc.extend(hid, tok, ext, kc, vc, act["kv_len"], tiny["ids"])
+    assert not full["overflow"]
+    np.testing.assert_array_equal(full["kv_len"], act["kv_len"] + ext)
+    for b in range(B):
+        assert (full["draft"][:ext[b], b] >= 0).all() and (full["draft"][ext[b]:, b] == -1).all()
+        # nothing outside the new slots was written
+        L = int(act["kv_len"][b])
+        np.testing.assert_array_equal(kc[b, :, :L], act["k_cache"][b, :, :L])
+        np.testing.assert_array_equal(kc[b, :, L + ext[b]:], act["k_cache"][b, :, L + ext[b]:])
+    # two calls (the first two positions, then the rest) leave the same bits behind
+    kc2, vc2 = act["k_cache"].copy(), act["v_cache"].copy()
+    first = np.minimum(ext, 2)
+    a = orc.extend(hid[:2], tok[:2], first, kc2, vc2, act["kv_len"], tiny["ids"])
+    b2 = orc.extend(hid[2:], tok[2:], ext - first, kc2, vc2, a["kv_len"], tiny["ids"])
+    np.testing.assert_array_equal(kc, kc2)
+    np.testing.assert_array_equal(vc, vc2)
+    for b in range(B):
+        np.testing.assert_array_equal(full["logits"][:first[b], b], a["logits"][:first[b], b])
+        np.testing.assert_array_equal(full["logits"][2:ext[b], b], b2["logits"][:ext[b] - first[b], b])
+    # later positions do not reach back: new inputs at positions >= 2 leave positions 0, 1 as they were
+    hid3, tok3 = hid.copy(), tok.copy()
+    hid3[2:], tok3[2:] = _extend_inputs(tiny, B, mm - 2, 13)
+    kc3, vc3 = act["k_cache"].copy(), act["v_cache"].copy()
+    c = orc.extend(hid3, tok3, ext, kc3, vc3, act["kv_len"], tiny["ids"])
+    np.testing.assert_array_equal(c["logits"][:2], full["logits"][:2])
+    assert np.abs(c["logits"][2:, 0] - full["logits"][2:, 0]).max() > 0
+
+
+def test_extend_overflow_leaves_the_sequence_alone(orc, tiny):
+    act = tiny["act"]
+    cap = act["kv_capacity"]
+    B = min(2, len(act["kv_len"]))
+    hid, tok = _extend_inputs(tiny, B, 3, 14)
+    kv = act["kv_len"][:B].copy()
+    kv[0] = cap - 2                                              # three new positions do not fit
+    kc, vc = act["k_cache"][:B].copy(), act["v_cache"][:B].copy()
+    res = orc.extend(hid, tok, np.full(B, 3, np.int32), kc, vc, kv, tiny["ids"])
+    assert res["overflow"] and (res["draft"][:, 0] == -1).all() and res["kv_len"][0] == cap - 2
+    np.testing.assert_array_equal(kc[0], act["k_cache"][0])
+    if B > 1:
+        assert (res["draft"][:, 1] >= 0).all() and res["kv_len"][1] == kv[1] + 3
+
+
 def test_f32_oracle_within_rounding_of_f64(tiny):
     act, ids = tiny["act"], tiny["ids"]
     outs = {}
