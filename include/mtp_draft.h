@@ -154,6 +154,32 @@ int32_t mtp_accept(mtp_handle *h, int32_t B, int32_t K, const int32_t *draft, co
                    int32_t rollback_mode, int32_t *kv_len, int32_t *accept_len, int32_t *out_tokens,
                    int32_t *pending, void *hip_stream);
 
+/*
+ * The first draft step over a block of new positions (Sec. 2.3 "Drafting phase": step 1 runs over the shifted
+ * prefix): the head is applied to every new position of every sequence with the TARGET model's hidden state of that
+ * position and the token that follows it.  Position j of sequence b is written to cache slot kv_len[b] + j and attends
+ * slots 0 .. kv_len[b] + j (causal inside the block).  The last position of a sequence yields its first draft token;
+ * the others fill the head's KV cache, e.g. with the a + 1 tokens a verification has just confirmed, or a prompt.
+ * Every weight is read once for all B * m_max (position, sequence) rows; the attention runs position by position.
+ *
+ *   B, m_max     sequences and positions per sequence; B * m_max <= max_batch of mtp_draft_init (else
+ *                MTP_ERR_BATCH)
+ *   hidden_in    device [m_max][B][d] bf16     target hidden states, position-major
+ *   tokens       device [m_max][B] int32       token paired with each hidden state
+ *   ext_len      device [B] int32              new positions of each sequence, 0 .. m_max
+ *   k_cache, v_cache  as for mtp_draft_steps; slots kv_len[b] .. kv_len[b] + ext_len[b] - 1 are written
+ *   kv_len       device [B] int32              read, then advanced by ext_len[b] (on the stream, after the block)
+ *   draft_out    device [m_max][B] int32       greedy token of every position; -1 at positions >= ext_len[b]
+ *   logits_out   device [m_max][B][n] float or NULL;  hidden_out device [m_max][B][d] float or NULL (rows of
+ *                positions >= ext_len[b] are unspecified)
+ * A sequence whose block does not fit its cache (kv_len[b] + ext_len[b] > kv_capacity), or with a negative kv_len
+ * or an ext_len outside 0 .. m_max, is left alone: drafts -1, cache and kv_len untouched, MTP_ERR_KV_OVERFLOW from
+ * mtp_poll_error.  Always one launch per phase, whatever the launch mode.
+ */
+int32_t mtp_draft_extend(mtp_handle *h, int32_t B, int32_t m_max, int32_t subset_index, const void *hidden_in,
+                         const int32_t *tokens, const int32_t *ext_len, void *k_cache, void *v_cache, int32_t *kv_len,
+                         int32_t *draft_out, float *logits_out, float *hidden_out, void *hip_stream);
+
 /* Waits for `hip_stream`, then returns and clears the sticky device error word:
  * MTP_OK, MTP_ERR_KV_OVERFLOW or MTP_ERR_TOKEN_RANGE (or MTP_ERR_HIP). */
 int32_t mtp_poll_error(mtp_handle *h, void *hip_stream);

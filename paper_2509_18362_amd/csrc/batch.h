@@ -763,7 +763,7 @@ __device__ __forceinline__ void phase_bprep(const DraftParams &p, int step, char
     float *red = reinterpret_cast<float *>(smem);
     uint16_t *hi = p.act[0] + (size_t)b * p.a_stride;
     uint16_t *lo = hi + p.a_lo;
-    if (step == 0 && threadIdx.x == 0 && seq_dead(p, b)) atomicOr(p.err, kErrKvOverflow);
+    if (step == 0 && threadIdx.x == 0 && seq_overflows(p, b)) atomicOr(p.err, kErrKvOverflow);
     int did = 0;
     if (step > 0) {
         did = key_token(p, winner_key(p, step - 1, b, reinterpret_cast<unsigned long long *>(red)));

@@ -92,6 +92,24 @@ __global__ void k_accept(int B, int K, const int *draft, const int *target, int 
     }
 }
 
+// Several new positions per sequence: the cache length each (position, sequence) row starts from.  A sequence whose
+// block does not fit (or whose length is invalid) gets -1 in every row, which the first phase reports; rows beyond
+// a sequence's new positions are marked inactive.
+__global__ void k_extend_prep(int B, int m_max, int cap, const int *kv_len, const int *ext_len, int *row_len) {
+    const int r = blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= B * m_max) return;
+    const int b = r % B, j = r / B;
+    const int L = kv_len[b], m = ext_len[b];
+    const bool bad = L < 0 || m < 0 || m > m_max || L + m > cap;
+    row_len[r] = bad ? -1 : (j < m ? L + j : kRowInactive);
+}
+__global__ void k_extend_finish(int B, int m_max, int cap, int *kv_len, const int *ext_len) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    const int L = kv_len[b], m = ext_len[b];
+    if (L >= 0 && m >= 0 && m <= m_max && L + m <= cap) kv_len[b] = L + m;
+}
+
 typedef void (*phase_kernel_t)(DraftParams, int);
 
 phase_kernel_t attn_kernel(int G, int HD) {
@@ -204,7 +222,7 @@ size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 struct WsLayout {
     size_t x, qkv, attn, o, gu, dn, hhat, err, bar, cand, rope_inv, attn_part, total;
     // batched path (max_batch above kBatchMinSeq - 1 only)
-    size_t act0, act1, ssq, part, ticket, a_lo, attn_ticket;
+    size_t act0, act1, ssq, part, ticket, a_lo, attn_ticket, row_len;
     int a_stride;
 };
 
@@ -243,6 +261,7 @@ WsLayout ws_layout(const mtp_config &c) {
     l.rope_inv = take((size_t)c.head_dim / 2 * 8);
     l.attn_part = take(attn_part_floats(c) * 4);
     l.attn_ticket = take(mb * (size_t)c.n_kv_heads * 4);
+    l.row_len = take(mb * 4);
     if (c.max_batch >= kBatchMinSeq) {
         size_t kmax = std::max({2 * d, qd, (size_t)c.d_ffn});
         l.a_stride = (int)((kmax + 31) / 32 * 32);
@@ -431,19 +450,23 @@ int32_t mtp_draft_init(mtp_handle **out, const mtp_config *cfg, const mtp_weight
     return MTP_OK;
 }
 
-int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, const void *hidden_in,
-                        const int32_t *token_in, void *k_cache, void *v_cache, const int32_t *kv_len,
-                        const int32_t *forced_tokens, int32_t *draft_out, float *logits_out, float *hidden_out,
-                        void *hip_stream) {
-    if (!h || !hidden_in || !token_in || !k_cache || !v_cache || !kv_len || !draft_out) return MTP_ERR_NULL;
-    const void *ptrs[] = {hidden_in, token_in, k_cache, v_cache, kv_len, forced_tokens, draft_out, logits_out,
-                          hidden_out};
-    for (const void *p : ptrs)
-        if (!aligned16(p)) return MTP_ERR_ALIGN;
+} // extern "C"
+
+namespace {
+// The first draft step over a block of new positions (mtp_draft_extend) reuses the one-step pipeline with one row per
+// (position, sequence); only the attention needs to know: it runs once per position over the real sequences.
+struct ExtendCall {
+    int B, m_max;           // real sequences, positions per sequence (rows = m_max * B)
+    const int32_t *ext_len; // device [B]
+    int32_t *kv_len;        // device [B], the real lengths (advanced at the end)
+};
+
+// B sequences (or rows), K steps; arguments checked by the callers
+int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, const void *hidden_in,
+                  const int32_t *token_in, void *k_cache, void *v_cache, const int32_t *kv_len,
+                  const int32_t *forced_tokens, int32_t *draft_out, float *logits_out, float *hidden_out,
+                  void *hip_stream, const ExtendCall *ext) {
     const mtp_config &c = h->cfg;
-    if (B < 1 || B > c.max_batch) return MTP_ERR_BATCH;
-    if (K < 1 || K > c.max_draft_steps) return MTP_ERR_STEPS;
-    if (subset_index < -1 || subset_index >= (int)h->subset_dev.size()) return MTP_ERR_SUBSET;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
 
     DraftParams p{};
@@ -511,8 +534,15 @@ int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_inde
     p.bar_timeout = 200000000ll; // 2 s of the 100 MHz wall clock
     p.trace = h->trace;
     p.max_batch = c.max_batch;
-    p.split_tokens = split_tokens_for(c, B);
-    p.max_splits = max_splits_for(c, B);
+    const int att_B = ext ? ext->B : B; // sequences an attention launch covers
+    p.split_tokens = split_tokens_for(c, att_B);
+    p.max_splits = max_splits_for(c, att_B);
+    if (ext) { // per-row cache lengths for the matrix phases
+        int *row_len = reinterpret_cast<int *>(ws + l.row_len);
+        hipLaunchKernelGGL(k_extend_prep, dim3((B + 255) / 256), dim3(256), 0, st, ext->B, ext->m_max, c.kv_capacity,
+                           ext->kv_len, ext->ext_len, row_len);
+        p.kv_len = row_len;
+    }
 
     // sequences per weight pass, bounded by LDS
     size_t budget = std::min(h->lds_limit, B <= 2 ? kLdsSmallBatch : kLdsLargeBatch);
@@ -537,13 +567,13 @@ int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_inde
     const int grid = std::min(h->num_cus, kMaxFusedGrid); // one 512-thread workgroup per CU: the register ring
                                                           // leaves no room for a second
     p.head_grid = grid;
-    const int attn_items = B * p.Hkv * p.max_splits;
+    const int attn_items = att_B * p.Hkv * p.max_splits;
     const int attn_grid = std::max(1, std::min(attn_items, h->num_cus * 2));
-    const int merge_grid = std::max(1, std::min((B * p.Hq + kWaves - 1) / kWaves, h->num_cus));
+    const int merge_grid = std::max(1, std::min((att_B * p.Hq + kWaves - 1) / kWaves, h->num_cus));
 
     const int tphase = h->timing >= 2 ? h->timing - 2 : -1;
     h->pev_used = 0;
-    if (h->mode == 1 && tphase < 0) {
+    if (h->mode == 1 && tphase < 0 && !ext) {
         // single launch: all B sequences are staged together and every workgroup must be resident at once (one
         // per CU; the cooperative launch checks it).  Falls back to one launch per phase when LDS cannot hold B.
         const int fgrid = std::min(h->num_cus, kMaxFusedGrid);
@@ -591,11 +621,29 @@ int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_inde
     // vector version
     const bool mfma_attn = p.split_tokens >= kMfmaAttnMinSplit;
     const bool merge_launch = mfma_attn && p.max_splits > 1; // the vector version merges its own splits
-    auto launch_attention = [&](int step) {
+    auto launch_attention_of = [&](const DraftParams &pa, int step) {
         if (mfma_attn)
-            launch_attn_mfma(p.Hq / p.Hkv, p.hd, p, step, attn_grid, lds_attn, st);
+            launch_attn_mfma(pa.Hq / pa.Hkv, pa.hd, pa, step, attn_grid, lds_attn, st);
         else
-            hipLaunchKernelGGL(h->attn_fn, dim3(attn_grid), dim3(kBlock), lds_attn, st, p, step);
+            hipLaunchKernelGGL(h->attn_fn, dim3(attn_grid), dim3(kBlock), lds_attn, st, pa, step);
+        if (merge_launch) hipLaunchKernelGGL(h->merge_fn, dim3(merge_grid), dim3(kBlock), lds_merge, st, pa, step);
+    };
+    // attention (and the merge of its splits, where that is a launch of its own)
+    auto launch_attention = [&](int step) {
+        if (!ext) {
+            launch_attention_of(p, step);
+            return;
+        }
+        // a block of new positions: position j of every sequence, in order, each launch finding the entries of the
+        // positions before it in the cache
+        DraftParams pa = p;
+        pa.B = ext->B;
+        pa.kv_len = ext->kv_len;
+        pa.ext_len = ext->ext_len;
+        for (int j = 0; j < ext->m_max; ++j) {
+            pa.row0 = j * ext->B;
+            launch_attention_of(pa, j);
+        }
     };
     auto launch = [&](int phase, phase_kernel_t fn, int g, size_t lds, int step) {
         mark_begin(phase, step);
@@ -674,8 +722,6 @@ int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_inde
             matrix_phase(PH_QKV, BG_QKV, step);
             mark_begin(PH_ATTN, step);
             launch_attention(step);
-            if (merge_launch)
-                hipLaunchKernelGGL(h->merge_fn, dim3(merge_grid), dim3(kBlock), lds_merge, st, p, step);
             mark_end(PH_ATTN, step);
             mark_begin(PH_OPROJ, step);
             matrix_phase(PH_OPROJ, BG_OPROJ, step);
@@ -687,6 +733,9 @@ int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_inde
             matrix_phase(PH_LMHEAD, BG_LMHEAD, step);
         }
         launch_bprep(p, K, st);
+        if (ext)
+            hipLaunchKernelGGL(k_extend_finish, dim3((ext->B + 63) / 64), dim3(64), 0, st, ext->B, ext->m_max,
+                               c.kv_capacity, ext->kv_len, ext->ext_len);
         if (h->timing == 1) {
             (void)hipEventRecord(h->ev[1], st);
             h->ev_recorded = true;
@@ -700,19 +749,57 @@ int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_inde
         mark_begin(PH_ATTN, step);
         launch_attention(step);
         mark_end(PH_ATTN, step);
-        if (merge_launch) launch(PH_MERGE, h->merge_fn, merge_grid, lds_merge, step);
         launch(PH_OPROJ, k_oproj, grid, lds_q, step);
         launch(PH_GATEUP, k_gateup, grid, lds_d2, step);
         launch(PH_DOWN, k_down, grid, lds_down, step);
         launch(PH_LMHEAD, k_lmhead, grid, lds_d1, step);
     }
     hipLaunchKernelGGL(k_finalize, dim3((B + kWaves - 1) / kWaves), dim3(kBlock), 0, st, p);
+    if (ext)
+        hipLaunchKernelGGL(k_extend_finish, dim3((ext->B + 63) / 64), dim3(64), 0, st, ext->B, ext->m_max,
+                           c.kv_capacity, ext->kv_len, ext->ext_len);
     if (h->timing == 1) {
         (void)hipEventRecord(h->ev[1], st);
         h->ev_recorded = true;
     }
     if (hipGetLastError() != hipSuccess) return MTP_ERR_HIP;
     return MTP_OK;
+}
+
+} // namespace
+
+extern "C" {
+
+int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, const void *hidden_in,
+                        const int32_t *token_in, void *k_cache, void *v_cache, const int32_t *kv_len,
+                        const int32_t *forced_tokens, int32_t *draft_out, float *logits_out, float *hidden_out,
+                        void *hip_stream) {
+    if (!h || !hidden_in || !token_in || !k_cache || !v_cache || !kv_len || !draft_out) return MTP_ERR_NULL;
+    const void *ptrs[] = {hidden_in, token_in, k_cache, v_cache, kv_len, forced_tokens, draft_out, logits_out,
+                          hidden_out};
+    for (const void *p : ptrs)
+        if (!aligned16(p)) return MTP_ERR_ALIGN;
+    const mtp_config &c = h->cfg;
+    if (B < 1 || B > c.max_batch) return MTP_ERR_BATCH;
+    if (K < 1 || K > c.max_draft_steps) return MTP_ERR_STEPS;
+    if (subset_index < -1 || subset_index >= (int)h->subset_dev.size()) return MTP_ERR_SUBSET;
+    return run_draft(h, B, K, subset_index, hidden_in, token_in, k_cache, v_cache, kv_len, forced_tokens, draft_out,
+                     logits_out, hidden_out, hip_stream, nullptr);
+}
+
+int32_t mtp_draft_extend(mtp_handle *h, int32_t B, int32_t m_max, int32_t subset_index, const void *hidden_in,
+                         const int32_t *tokens, const int32_t *ext_len, void *k_cache, void *v_cache, int32_t *kv_len,
+                         int32_t *draft_out, float *logits_out, float *hidden_out, void *hip_stream) {
+    if (!h || !hidden_in || !tokens || !ext_len || !k_cache || !v_cache || !kv_len || !draft_out) return MTP_ERR_NULL;
+    const void *ptrs[] = {hidden_in, tokens, ext_len, k_cache, v_cache, kv_len, draft_out, logits_out, hidden_out};
+    for (const void *p : ptrs)
+        if (!aligned16(p)) return MTP_ERR_ALIGN;
+    const mtp_config &c = h->cfg;
+    if (B < 1 || m_max < 1 || (long long)B * m_max > c.max_batch) return MTP_ERR_BATCH;
+    if (subset_index < -1 || subset_index >= (int)h->subset_dev.size()) return MTP_ERR_SUBSET;
+    const ExtendCall ext{B, m_max, ext_len, kv_len};
+    return run_draft(h, B * m_max, 1, subset_index, hidden_in, tokens, k_cache, v_cache, kv_len, nullptr, draft_out,
+                     logits_out, hidden_out, hip_stream, &ext);
 }
 
 int32_t mtp_accept(mtp_handle *h, int32_t B, int32_t K, const int32_t *draft, const int32_t *target,

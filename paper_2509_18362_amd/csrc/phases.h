@@ -42,6 +42,12 @@ struct DraftParams {
     // launch plan
     int split_tokens, max_splits; // attention: tokens per split, splits per (sequence, KV head)
     int mfma_attn;                // the splits are long enough for the matrix-core attention
+    // Several new positions per sequence (first draft step over a block): the matrix phases see one row per
+    // (position, sequence), row = position * sequences + sequence, with a cache length per ROW in kv_len; the
+    // attention runs once per position over the real sequences, with B = their number, kv_len = their real lengths
+    // and:
+    int row0;                     // activation row of sequence 0 in this attention launch (position * sequences)
+    const int *ext_len;           // [B] new positions per sequence, or null: the ordinary one-position step
     int nb_proj, nb_d, nb_q, nb_down; // sequences staged in LDS per pass, by reduction length (2d, d, Hq*hd, F)
     // batched path (five or more sequences): activations travel between the phases as bf16 hi + lo in global memory
     uint16_t *act[2];    // two [max_batch][a_stride] hi arrays, each followed (a_lo elements later) by its lo array
@@ -66,9 +72,25 @@ enum : int { SSQ_X = 0, SSQ_X1, SSQ_X2, SSQ_COUNT };
 // ---------------------------------------------------------------------------------------------------
 // per-sequence state helpers
 // ---------------------------------------------------------------------------------------------------
+constexpr int kRowInactive = -0x40000000; // kv_len of a (position, sequence) row beyond the sequence's new positions
 __device__ __forceinline__ bool seq_dead(const DraftParams &p, int b) {
     int L = p.kv_len[b];
     return L < 0 || L + p.K > p.cap;
+}
+// dead because its cache cannot take the new entries (or its length is invalid): reported; an inactive row is not
+__device__ __forceinline__ bool seq_overflows(const DraftParams &p, int b) {
+    return seq_dead(p, b) && p.kv_len[b] != kRowInactive;
+}
+// What an attention work item needs to know about its sequence: false = nothing to do (a position beyond the
+// sequence's new ones, or a block that does not fit the cache).  `dead` keeps its meaning for the one-position step.
+__device__ __forceinline__ bool attn_seq_state(const DraftParams &p, int b, int step, bool &dead) {
+    if (p.ext_len) {
+        const int L = p.kv_len[b], m = p.ext_len[b];
+        dead = false;
+        return step < m && L >= 0 && L + m <= p.cap;
+    }
+    dead = seq_dead(p, b);
+    return true;
 }
 
 // maximum of a 64-bit key over the workgroup; red64 holds kWaves words; contains two barriers
@@ -682,7 +704,7 @@ __device__ inline GemvLds gemv_lds(char *smem, int K, int nb, int nmat) {
 // ---------------------------------------------------------------------------------------------------
 __device__ __forceinline__ void phase_proj(const DraftParams &p, int step, int vb, int nvb, char *smem) {
     const int d = p.d;
-    if (step == 0 && vb == 0 && (int)threadIdx.x < p.B && seq_dead(p, threadIdx.x)) atomicOr(p.err, kErrKvOverflow);
+    if (step == 0 && vb == 0 && (int)threadIdx.x < p.B && seq_overflows(p, threadIdx.x)) atomicOr(p.err, kErrKvOverflow);
     const int nbmax = p.nb_proj;
     GemvLds l = gemv_lds(smem, 2 * d, nbmax, 1);
     for (int b0 = 0; b0 < p.B; b0 += nbmax) {
@@ -803,11 +825,11 @@ __device__ __forceinline__ void merge_head(const DraftParams &p, int b, int hq, 
     const int S = p.max_splits, PW = HD + 2;
     const float *src = p.attn_part + ((size_t)b * p.Hq + hq) * S * PW;
     auto store = [&](int dd, float r) {
-        st_f32<OCOH>(p.attn + (size_t)b * p.qd + (size_t)hq * HD + dd, r);
+        st_f32<OCOH>(p.attn + (size_t)(p.row0 + b) * p.qd + (size_t)hq * HD + dd, r);
         if (p.attn_split) {
             uint16_t h, l;
             split_bf16(r, h, l);
-            const size_t at = (size_t)b * p.a_stride + (size_t)hq * HD + dd;
+            const size_t at = (size_t)(p.row0 + b) * p.a_stride + (size_t)hq * HD + dd;
             p.attn_split[at] = h;
             p.attn_split[p.a_lo + at] = l;
         }
@@ -896,7 +918,8 @@ __device__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char
     bool first_item = true;
     for (int item = vb; item < n_items; item += nvb) {
         const int b = item / (p.Hkv * S), rem = item % (p.Hkv * S), kvh = rem / S, sp = rem % S;
-        const bool dead = seq_dead(p, b);
+        bool dead;
+        if (!attn_seq_state(p, b, step, dead)) continue; // uniform for the workgroup
         const int Lb = dead ? 0 : p.kv_len[b];
         const int len = Lb + step + 1, pnew = len - 1;
         const int nsplit = (len + T - 1) / T;
@@ -906,7 +929,7 @@ __device__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char
         const int ntok = last ? (t1 - 1 - t0) : (t1 - t0); // slots read from the cache; the new token comes from qkv
         const uint16_t *kc = p.k_cache + ((size_t)b * p.Hkv + kvh) * p.cap * HD;
         const uint16_t *vc = p.v_cache + ((size_t)b * p.Hkv + kvh) * p.cap * HD;
-        const float *qkv = p.qkv + (size_t)b * p.qkv_dim;
+        const float *qkv = p.qkv + (size_t)(p.row0 + b) * p.qkv_dim;
         const int nblk = (ntok + TPI - 1) / TPI;
 
         u32x4 kr[U], vr[U];
@@ -1110,11 +1133,11 @@ __device__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char
             int hq = kvh * G + g;
             if (nsplit == 1) {
                 const float r = A / Ls;
-                st_f32<COH>(p.attn + (size_t)b * p.qd + (size_t)hq * HD + dd, r);
+                st_f32<COH>(p.attn + (size_t)(p.row0 + b) * p.qd + (size_t)hq * HD + dd, r);
                 if (p.attn_split) {
                     uint16_t h, l;
                     split_bf16(r, h, l);
-                    const size_t at = (size_t)b * p.a_stride + (size_t)hq * HD + dd;
+                    const size_t at = (size_t)(p.row0 + b) * p.a_stride + (size_t)hq * HD + dd;
                     p.attn_split[at] = h;
                     p.attn_split[p.a_lo + at] = l;
                 }
@@ -1159,7 +1182,9 @@ __device__ void phase_attn_merge(const DraftParams &p, int step, int vb, int nvb
     const int n_items = p.B * p.Hq;
     for (int item = vb * kWaves + wave; item < n_items; item += nvb * kWaves) {
         const int b = item / p.Hq, hq = item % p.Hq;
-        const int Lb = seq_dead(p, b) ? 0 : p.kv_len[b];
+        bool dead;
+        if (!attn_seq_state(p, b, step, dead)) continue;
+        const int Lb = dead ? 0 : p.kv_len[b];
         const int nsplit = (Lb + step + 1 + T - 1) / T;
         if (nsplit <= 1) continue; // finished by phase_attn
         merge_head<HD, COH, COH>(p, b, hq, nsplit, w);

@@ -297,6 +297,122 @@ def test_single_launch_one_sequence_row_streaming(gpu, hq, hkv, hd):
         eng.close()
 
 
+# ------------------------------------------------------------------------------------------ block of new positions
+def extend_inputs(shape, act, m_max, seed):
+    """Position-major inputs of the multi-position first step: hidden states with the workload's spread, tokens."""
+    rng = np.random.default_rng(seed)
+    B = len(act["kv_len"])
+    std = float(synth.bf16_bits_to_f32(act["hidden_in"]).std())
+    hid = synth.f32_to_bf16_bits((rng.standard_normal((m_max, B, shape.d_model)) * std).astype(np.float32))
+    tok = rng.integers(0, shape.vocab_size, size=(m_max, B)).astype(np.int32)
+    return hid, tok
+
+
+def run_extend(gpu, shape, w_host, w_dev, act, subsets, subset_index, hid, tok, ext_len, engine=None, seqs=None):
+    """Oracle and library on the same block; returns (ref, res, (oracle caches), engine-side kv_len)."""
+    torch, Oracle, binding = gpu["torch"], gpu["Oracle"], gpu["binding"]
+    m_max, B = tok.shape
+    cap = act["kv_capacity"]
+    ids = None if subset_index < 0 else subsets[subset_index]
+    sel = list(range(B)) if seqs is None else list(seqs)
+    orc = Oracle(shape, w_host, cap, "f32")
+    okc, ovc = act["k_cache"][sel].copy(), act["v_cache"][sel].copy()
+    ref = orc.extend(np.ascontiguousarray(hid[:, sel]), np.ascontiguousarray(tok[:, sel]), ext_len[sel], okc, ovc,
+                     act["kv_len"][sel], ids)
+    own = engine is None
+    if own:
+        engine = binding.DraftEngine(shape, w_dev, subsets, B * m_max, cap, 1)
+    dkc, dvc = engine.to_device_bits(act["k_cache"]), engine.to_device_bits(act["v_cache"])
+    dkv = engine.to_device_i32(act["kv_len"])
+    out = engine.extend(subset_index, engine.to_device_bits(hid), engine.to_device_i32(tok),
+                        engine.to_device_i32(ext_len), dkc, dvc, dkv, want_logits=True, want_hidden=True)
+    torch.cuda.synchronize()
+    err = engine.poll_error()
+    res = {"draft": out["draft"].cpu().numpy()[:, sel], "logits": out["logits"].cpu().numpy()[:, sel],
+           "hidden": out["hidden"].cpu().numpy()[:, sel], "kv_len": dkv.cpu().numpy()[sel],
+           "k_cache": dkc.cpu().numpy().view(np.uint16)[sel], "v_cache": dvc.cpu().numpy().view(np.uint16)[sel],
+           "err": err}
+    if own:
+        engine.close()
+    return ref, res, (okc, ovc)
+
+
+def check_extend(ref, res, caches, act, ext_len, sel=None):
+    okc, ovc = caches
+    sel = list(range(len(ext_len))) if sel is None else list(sel)
+    np.testing.assert_array_equal(res["kv_len"], ref["kv_len"])
+    worst = 0.0
+    for i, b in enumerate(sel):
+        m, L = int(ext_len[b]), int(act["kv_len"][b])
+        fits = L + m <= act["kv_capacity"]
+        live = m if fits else 0
+        assert (res["draft"][live:, i] == -1).all() and (ref["draft"][live:, i] == -1).all()
+        if live:
+            gap = float(np.abs(ref["logits"][:live, i] - res["logits"][:live, i]).max())
+            worst = max(worst, gap)
+            assert gap <= LOGIT_TIGHT, (b, gap)
+            assert np.abs(ref["hidden"][:live, i] - res["hidden"][:live, i]).max() <= 2e-3
+            clear = ref["margin"][:live, i] > MARGIN
+            np.testing.assert_array_equal(ref["draft"][:live, i][clear], res["draft"][:live, i][clear])
+        # cache: only the new slots change, and they match the oracle's up to one bf16 step
+        assert np.array_equal(res["k_cache"][i][:, :L], okc[i][:, :L])
+        assert np.array_equal(res["v_cache"][i][:, :L], ovc[i][:, :L])
+        if live:
+            assert appended_entries_close(res["k_cache"][i][:, L:L + live], okc[i][:, L:L + live])
+            assert appended_entries_close(res["v_cache"][i][:, L:L + live], ovc[i][:, L:L + live])
+        assert np.array_equal(res["k_cache"][i][:, L + live:], okc[i][:, L + live:])
+        assert np.array_equal(res["v_cache"][i][:, L + live:], ovc[i][:, L + live:])
+    return worst
+
+
+@pytest.mark.parametrize("ctx,ext,m_max", [
+    ([100], [3], 3),                         # three rows: the row-streaming matrix phases
+    ([0, 60], [2, 1], 2),                    # four rows, one sequence starting from an empty cache
+    ([0, 130, 64], [4, 0, 2], 4),            # twelve rows (batched matrix phases), ragged, one sequence idle
+    ([5, 150, 64, 1, 99, 127], [5, 5, 1, 3, 0, 5], 5),   # thirty rows: two sequence tiles per weight tile
+])
+def test_tiny_extend_block_of_positions(gpu, tiny, ctx, ext, m_max):
+    """The first draft step over several new positions per sequence against the oracle's position-by-position
+    result: logits, hidden states and drafts of every live position, the appended cache slots, the new kv_len."""
+    act = synth.make_activations(tiny["wl"], ctx=np.array(ctx, dtype=np.int32), capacity=192)
+    ext_len = np.array(ext, dtype=np.int32)
+    hid, tok = extend_inputs(tiny["shape"], act, m_max, 200 + len(ctx))
+    ref, res, caches = run_extend(gpu, tiny["shape"], tiny["w"], tiny["w"], act, [tiny["ids"]], 0, hid, tok, ext_len)
+    assert res["err"] == 0
+    check_extend(ref, res, caches, act, ext_len)
+
+
+def test_tiny_extend_long_capacity_matrix_core_attention(gpu, tiny):
+    """A large capacity makes the splits long enough for the matrix-core attention and its separate merge launch."""
+    act = synth.make_activations(tiny["wl"], ctx=np.array([0, 31, 300, 1000], dtype=np.int32), capacity=32768)
+    ext_len = np.array([3, 2, 3, 1], dtype=np.int32)
+    hid, tok = extend_inputs(tiny["shape"], act, 3, 210)
+    ref, res, caches = run_extend(gpu, tiny["shape"], tiny["w"], tiny["w"], act, [tiny["ids"]], 0, hid, tok, ext_len)
+    assert res["err"] == 0
+    check_extend(ref, res, caches, act, ext_len)
+
+
+def test_tiny_extend_overflow_and_then_draft(gpu, tiny):
+    """A block that does not fit leaves its sequence alone and is reported; the other sequence is extended, and the
+    recursive draft steps that follow start from the extended cache on both sides."""
+    torch, binding = gpu["torch"], gpu["binding"]
+    cap = 192
+    act = synth.make_activations(tiny["wl"], ctx=np.array([cap - 2, 80], dtype=np.int32), capacity=cap)
+    ext_len = np.array([3, 3], dtype=np.int32)
+    hid, tok = extend_inputs(tiny["shape"], act, 3, 220)
+    eng = binding.DraftEngine(tiny["shape"], tiny["w"], [tiny["ids"]], 6, cap, 3)
+    ref, res, caches = run_extend(gpu, tiny["shape"], tiny["w"], tiny["w"], act, [tiny["ids"]], 0, hid, tok, ext_len,
+                                  engine=eng)
+    assert res["err"] == -9 and ref["overflow"]
+    check_extend(ref, res, caches, act, ext_len)
+    # K = 3 recursive steps of sequence 1 from the extended caches (the oracle's own on its side)
+    act2 = {"hidden_in": act["hidden_in"][1:], "token_in": act["token_in"][1:], "kv_len": ref["kv_len"][1:],
+            "k_cache": caches[0][1:].copy(), "v_cache": caches[1][1:].copy(), "kv_capacity": cap}
+    ref2, res2, caches2 = run_both(gpu, tiny["shape"], tiny["w"], tiny["w"], act2, [tiny["ids"]], 0, 3, engine=eng)
+    check_chain(ref2, res2, caches2, act2["kv_len"], 3, need_clear=False)
+    eng.close()
+
+
 # ------------------------------------------------------------------------------------------ accept / rollback
 @pytest.mark.parametrize("K", [1, 3, 5])
 @pytest.mark.parametrize("mode", [0, 1])
@@ -375,6 +491,24 @@ def test_7b_batch1_ctx2048(gpu, big):
     ref, res, caches = run_both(gpu, big["shape"], big["w"], big["dev"], act, subsets, 0, wl.draft_steps, engine=eng)
     check_chain(ref, res, caches, act["kv_len"], wl.draft_steps)
     eng.close()
+
+
+def test_7b_extend_four_positions(gpu, big):
+    """Config 2's head and context with a block of four new positions (an accepted run of three plus the bonus
+    token), one sequence, and config 3's ragged batch of sixteen with up to four positions each (64 rows)."""
+    for name, seed in (("c2_7b_b1", 230), ("c3_7b_b16", 231)):
+        wl = synth.WORKLOADS[name]
+        act = synth.make_activations(wl)
+        subsets = synth.make_subsets(wl)
+        B = wl.batch
+        ext_len = np.array([max(0, 4 - (b % 4 == 3) * 3 - (b % 5 == 2) * 2) for b in range(B)], dtype=np.int32)
+        hid, tok = extend_inputs(big["shape"], act, 4, seed)
+        seqs = None if B == 1 else [0, 3, 7]   # the oracle on three of the sixteen sequences
+        ref, res, caches = run_extend(gpu, big["shape"], big["w"], big["dev"], act, subsets, 0, hid, tok, ext_len,
+                                      seqs=seqs)
+        assert res["err"] == 0
+        gap = check_extend(ref, res, caches, act, ext_len, sel=seqs)
+        print(name, "extend max |dlogit| =", gap)
 
 
 def test_7b_vocab_sweep_ctx8192(gpu, big):
