@@ -60,6 +60,9 @@ def main() -> int:
     ap.add_argument("--launch-mode", default="auto", choices=("auto", "per-phase", "single"),
                     help="how the library enqueues a call: one launch per phase, or one cooperative launch for all "
                          "phases of all K steps; auto times both briefly for one sequence and keeps the faster")
+    ap.add_argument("--extend", type=int, default=0,
+                    help="also time the first draft step over a block of this many new positions per sequence "
+                         "(mtp_draft_extend); reported beside the main figures, never part of `value`")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full-vocab", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
@@ -188,6 +191,43 @@ def main() -> int:
     torch.cuda.synchronize()
     accept_us = e0.elapsed_time(e1) * 1e3 / n_acc
 
+    extend = None
+    if args.extend > 0:
+        m = args.extend
+        assert int(act["kv_len"].max()) + m <= cap, "the block does not fit the workload's cache capacity"
+        eng2 = binding.DraftEngine(shape, w, subsets, B * m, cap, 1, device="cuda:0")
+        rng = np.random.default_rng(7)
+        std = float(synth.bf16_bits_to_f32(act["hidden_in"]).std())
+        hid_m = eng2.to_device_bits(synth.f32_to_bf16_bits(
+            (rng.standard_normal((m, B, shape.d_model)) * std).astype(np.float32)))
+        tok_m = eng2.to_device_i32(rng.integers(0, shape.vocab_size, size=(m, B)).astype(np.int32))
+        ext_len = eng2.to_device_i32(np.full(B, m, dtype=np.int32))
+        draft_m = torch.empty((m, B), dtype=torch.int32, device="cuda:0")
+
+        def one_block():
+            st = binding.mtp_draft_extend(eng2.handle, B, m, args.subset, hid_m, tok_m, ext_len, kc, vc, kv, draft_m,
+                                          None, None, stream)
+            assert st == 0, binding.mtp_status_string(st)
+            kv.copy_(kv0)
+
+        n_blk = max(20, args.steps // 3)
+        for _ in range(max(3, args.warmup // 3)):
+            one_block()
+        torch.cuda.synchronize()
+        assert eng2.poll_error() == 0
+        t = time.perf_counter()
+        for _ in range(n_blk):
+            one_block()
+        torch.cuda.synchronize()
+        el_b = time.perf_counter() - t
+        # what one pass has to read: every weight once, the head's rows once, the caches once per position
+        blk_bytes = algorithmic_bytes_per_mtp_step(shape, n_rows, act["kv_len"], 1, args.subset >= 0)
+        extend = {"positions_per_sequence": m, "rows": B * m, "us_per_call": el_b / n_blk * 1e6,
+                  "positions_per_s": B * m * n_blk / el_b,
+                  "speedup_over_one_position_at_a_time": m * us_per_mtp_step / (el_b / n_blk * 1e6),
+                  "weight_pass_bytes": blk_bytes}
+        eng2.close()
+
     full = None
     if not args.no_full_vocab and args.subset >= 0:
         fs = max(10, args.steps // 4)
@@ -247,7 +287,8 @@ def main() -> int:
         "us_per_mtp_step": us_per_mtp_step, "mean_accept_len": mean_accept,
         "chain_us": {"p10": p10, "p50": p50, "p90": p90, "what": f"{K} draft steps, one library call"},
         "accept_us": accept_us,
-        "algorithmic_bytes_per_step": chain_bytes, "roofline": roofline, "full_vocab": full, "cpu_baseline": cpu,
+        "algorithmic_bytes_per_step": chain_bytes, "roofline": roofline, "full_vocab": full, "extend": extend,
+        "cpu_baseline": cpu,
         "input_generation_s": gen_s,
     }
     if args.k_sweep_target_ms > 0:
@@ -262,4 +303,6 @@ def main() -> int:
 
 
 if __name__ == "__main__":
-    sys.exit(main())
+    status = main()
+    if status:
+        sys.exit(status)
