@@ -204,7 +204,9 @@ float mtp_last_draft_ms(mtp_handle *h);
  *               reduction is split over workgroups.
  *   1           one cooperative launch runs all phases of all K steps (up to 16 sequences; otherwise as mode 0);
  *               phases are separated by grid-wide barriers inside the kernel.  A barrier that is not passed within
- *               ~2 s sets MTP_ERR_TIMEOUT.
+ *               ~2 s sets MTP_ERR_TIMEOUT.  For one sequence this is the faster mode (3-4 % at a 32768-row head,
+ *               more with larger heads); for 2-16 sequences it is slower than mode 0.  The launch needs every
+ *               compute unit of the device to itself.
  * Other values return MTP_ERR_MODE.  Results agree between the modes to rounding (bit for bit up to four
  * sequences).
  */

@@ -511,13 +511,16 @@ def test_7b_extend_four_positions(gpu, big):
         print(name, "extend max |dlogit| =", gap)
 
 
-def test_7b_vocab_sweep_ctx8192(gpu, big):
-    """Full 151680-row head against nested compressed heads; the compressed logits are rows of the full ones."""
+@pytest.mark.parametrize("launch_mode", [0, 1])
+def test_7b_vocab_sweep_ctx8192(gpu, big, launch_mode):
+    """Full 151680-row head against nested compressed heads; the compressed logits are rows of the full ones.
+    Once with a launch per phase and once through the single-launch kernel (the mode the bench times here)."""
     wl = synth.WORKLOADS["c4_7b_vocab"]
     act = synth.make_activations(wl)
     subsets = synth.make_subsets(wl)
     binding = gpu["binding"]
     eng = binding.DraftEngine(big["shape"], big["dev"], subsets, 1, act["kv_capacity"], wl.draft_steps)
+    assert binding.mtp_set_launch_mode(eng.handle, launch_mode) == 0
     K = 2
     ref_full, res_full, caches = run_both(gpu, big["shape"], big["w"], big["dev"], act, subsets, -1, K, engine=eng)
     check_chain(ref_full, res_full, caches, act["kv_len"], K)
