@@ -180,6 +180,21 @@ int32_t mtp_draft_extend(mtp_handle *h, int32_t B, int32_t m_max, int32_t subset
                          const int32_t *tokens, const int32_t *ext_len, void *k_cache, void *v_cache, int32_t *kv_len,
                          int32_t *draft_out, float *logits_out, float *hidden_out, void *hip_stream);
 
+/*
+ * Draft steps that start from the head's OWN output instead of the target model's hidden state (Sec. 2.3: from the
+ * second step on the head consumes its own output hidden state and the previously drafted token).  After
+ * mtp_draft_extend has produced the first draft token d_1 and the hidden state of a sequence's last new position,
+ * this call drafts d_2 .. d_{K+1}: identical to mtp_draft_steps except that the first step reads
+ *   own_hidden   device [B][d] float     the head's output (mtp_draft_extend's hidden_out row of the last live
+ *                                        position of each sequence; copied into the workspace on the stream)
+ * in place of hidden_in, and token_in [B] is the token drafted from it.  Everything else (cache slots kv_len[b] ..
+ * kv_len[b] + K - 1, outputs, errors, launch modes) as for mtp_draft_steps.
+ */
+int32_t mtp_draft_continue(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, const float *own_hidden,
+                           const int32_t *token_in, void *k_cache, void *v_cache, const int32_t *kv_len,
+                           const int32_t *forced_tokens, int32_t *draft_out, float *logits_out, float *hidden_out,
+                           void *hip_stream);
+
 /* Waits for `hip_stream`, then returns and clears the sticky device error word:
  * MTP_OK, MTP_ERR_KV_OVERFLOW or MTP_ERR_TOKEN_RANGE (or MTP_ERR_HIP). */
 int32_t mtp_poll_error(mtp_handle *h, void *hip_stream);

@@ -223,6 +223,20 @@ class Oracle:
         return {"draft": draft, "logits": logits, "hidden": hidden, "margin": margin}
 
 
+    def chain_from_own_hidden(self, K: int, hhat, token: int, kc_bits, vc_bits, pos: int, ids, forced=None):
+        """K recursive steps of ONE sequence that start from the head's own output hidden state (Sec. 2.3: from the
+        second step on): single steps fed back by hand.  forced [K-1]: tokens fed at the later steps instead of the
+        previous draft.  Returns dict(draft [K], logits [K][n], hidden [K][d], margin [K])."""
+        h, tok = self._r(hhat), int(token)
+        out = {"draft": [], "logits": [], "hidden": [], "margin": []}
+        for k in range(K):
+            r = self.step(h, tok, kc_bits, vc_bits, pos + k, ids)
+            for key, name in (("draft", "draft"), ("logits", "logits"), ("hidden", "hhat"), ("margin", "margin")):
+                out[key].append(r[name])
+            h = r["hhat"]
+            tok = int(forced[k]) if (forced is not None and k + 1 < K) else r["draft"]
+        return {k: np.array(v) for k, v in out.items()}
+
     def extend(self, hidden_in_bits, tokens, ext_len, k_cache_bits, v_cache_bits, kv_len, ids,
                want_logits: bool = True, want_hidden: bool = True):
         """First draft step over several new positions (Sec. 2.3, "Drafting phase").

@@ -28,6 +28,7 @@ STATUS = {0: "MTP_OK", -1: "MTP_ERR_NULL", -2: "MTP_ERR_ALIGN", -3: "MTP_ERR_CON
           -5: "MTP_ERR_STEPS", -6: "MTP_ERR_SUBSET", -7: "MTP_ERR_WORKSPACE", -8: "MTP_ERR_HIP",
           -9: "MTP_ERR_KV_OVERFLOW", -10: "MTP_ERR_TOKEN_RANGE", -11: "MTP_ERR_MODE", -12: "MTP_ERR_TIMEOUT"}
 EXPORTS = ["mtp_status_string", "mtp_workspace_bytes", "mtp_draft_init", "mtp_draft_steps", "mtp_draft_extend",
+           "mtp_draft_continue",
            "mtp_accept",
            "mtp_poll_error", "mtp_set_timing", "mtp_last_draft_ms", "mtp_set_launch_mode", "mtp_set_phase_trace",
            "mtp_draft_destroy"]
@@ -65,6 +66,8 @@ _lib.mtp_draft_init.argtypes = [C.POINTER(C.c_void_p), C.POINTER(mtp_config), C.
                                 C.POINTER(C.c_void_p), C.POINTER(C.c_int32), C.c_void_p, C.c_size_t]
 _lib.mtp_draft_steps.restype = C.c_int32
 _lib.mtp_draft_steps.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32] + [C.c_void_p] * 10
+_lib.mtp_draft_continue.restype = C.c_int32
+_lib.mtp_draft_continue.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32] + [C.c_void_p] * 10
 _lib.mtp_draft_extend.restype = C.c_int32
 _lib.mtp_draft_extend.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32] + [C.c_void_p] * 10
 _lib.mtp_accept.restype = C.c_int32
@@ -116,6 +119,13 @@ def mtp_draft_init(cfg: mtp_config, weights: Dict[str, object], subsets: Sequenc
     st = _lib.mtp_draft_init(C.byref(handle), C.byref(cfg), C.byref(w), ns, ids if ns else None,
                              sizes if ns else None, _addr(workspace), workspace_bytes)
     return int(st), (handle if st == MTP_OK else None)
+
+
+def mtp_draft_continue(handle, B: int, K: int, subset_index: int, own_hidden, token_in, k_cache, v_cache, kv_len,
+                       forced_tokens, draft_out, logits_out=None, hidden_out=None, stream=0) -> int:
+    return int(_lib.mtp_draft_continue(handle, B, K, subset_index, _addr(own_hidden), _addr(token_in), _addr(k_cache),
+                                       _addr(v_cache), _addr(kv_len), _addr(forced_tokens), _addr(draft_out),
+                                       _addr(logits_out), _addr(hidden_out), stream))
 
 
 def mtp_draft_extend(handle, B: int, m_max: int, subset_index: int, hidden_in, tokens, ext_len, k_cache, v_cache,
@@ -219,6 +229,22 @@ class DraftEngine:
             else None
         st = mtp_draft_steps(self.handle, B, K, subset_index, hidden_in, token_in, k_cache, v_cache, kv_len, forced,
                              draft, logits, hidden, stream)
+        if st != MTP_OK:
+            raise MTPError(st)
+        return {"draft": draft, "logits": logits, "hidden": hidden}
+
+    def draft_continue(self, K: int, subset_index: int, own_hidden, token_in, k_cache, v_cache, kv_len, forced=None,
+                       want_logits: bool = False, want_hidden: bool = False, stream: int = 0):
+        """Draft steps from the head's own fp32 hidden state [B][d] (see mtp_draft_continue)."""
+        torch = self.torch
+        B = token_in.numel()
+        n = self.subset_size(subset_index)
+        draft = torch.empty((B, K), dtype=torch.int32, device=self.device)
+        logits = torch.empty((B, K, n), dtype=torch.float32, device=self.device) if want_logits else None
+        hidden = torch.empty((B, K, self.shape.d_model), dtype=torch.float32, device=self.device) if want_hidden \
+            else None
+        st = mtp_draft_continue(self.handle, B, K, subset_index, own_hidden, token_in, k_cache, v_cache, kv_len,
+                                forced, draft, logits, hidden, stream)
         if st != MTP_OK:
             raise MTPError(st)
         return {"draft": draft, "logits": logits, "hidden": hidden}

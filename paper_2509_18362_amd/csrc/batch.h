@@ -779,7 +779,7 @@ __device__ __forceinline__ void phase_bprep(const DraftParams &p, int step, char
         if (threadIdx.x == 0) atomicOr(p.err, kErrTokenRange);
         tok = 0;
     }
-    if (step == 0)
+    if (step == 0 && !p.own_hidden)
         stage_rmsnorm<true>(p.hidden_in + (size_t)b * d, p.g_h, d, p.eps, hi, lo, red, nullptr);
     else
         stage_rmsnorm<false>(p.hhat + (size_t)b * d, p.g_h, d, p.eps, hi, lo, red, nullptr);

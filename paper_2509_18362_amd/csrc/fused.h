@@ -213,7 +213,7 @@ __device__ __forceinline__ void fused_steps2(const DraftParams &p, char *smem) {
                 }
                 if (step == 0 && vb == 0 && threadIdx.x == 0 && seq_dead(p, i)) atomicOr(p.err, kErrKvOverflow);
                 uint16_t *hi = l.hi + (size_t)i * l.kpad, *lo = l.lo + (size_t)i * l.kpad;
-                if (step == 0)
+                if (step == 0 && !p.own_hidden)
                     stage_rmsnorm<true>(p.hidden_in + (size_t)i * d, p.g_h, d, p.eps, hi, lo, l.red, nullptr);
                 else
                     stage_rmsnorm<false, true>(p.hhat + (size_t)i * d, p.g_h, d, p.eps, hi, lo, l.red, nullptr);
@@ -456,7 +456,7 @@ __device__ __forceinline__ void fused_steps_rows(const DraftParams &p, char *sme
                         if (threadIdx.x == 0) atomicOr(p.err, kErrTokenRange);
                         tok = 0;
                     }
-                    if (step == 0)
+                    if (step == 0 && !p.own_hidden)
                         stage_rmsnorm<true>(p.hidden_in, p.g_h, d, p.eps, l.hi, l.lo, l.red, nullptr);
                     else
                         stage_rmsnorm<false, true>(p.hhat, p.g_h, d, p.eps, l.hi, l.lo, l.red, nullptr);

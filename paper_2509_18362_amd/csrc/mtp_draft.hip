@@ -465,7 +465,7 @@ struct ExtendCall {
 int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, const void *hidden_in,
                   const int32_t *token_in, void *k_cache, void *v_cache, const int32_t *kv_len,
                   const int32_t *forced_tokens, int32_t *draft_out, float *logits_out, float *hidden_out,
-                  void *hip_stream, const ExtendCall *ext) {
+                  void *hip_stream, const ExtendCall *ext, const float *own_hidden = nullptr) {
     const mtp_config &c = h->cfg;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
 
@@ -534,6 +534,11 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
     p.bar_timeout = 200000000ll; // 2 s of the 100 MHz wall clock
     p.trace = h->trace;
     p.max_batch = c.max_batch;
+    if (own_hidden) { // the first step starts from the head's own output of an earlier call
+        if (hipMemcpyAsync(p.hhat, own_hidden, (size_t)B * p.d * sizeof(float), hipMemcpyDeviceToDevice, st) != hipSuccess)
+            return MTP_ERR_HIP;
+        p.own_hidden = 1;
+    }
     const int att_B = ext ? ext->B : B; // sequences an attention launch covers
     p.split_tokens = split_tokens_for(c, att_B);
     p.max_splits = max_splits_for(c, att_B);
@@ -785,6 +790,23 @@ int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_inde
     if (subset_index < -1 || subset_index >= (int)h->subset_dev.size()) return MTP_ERR_SUBSET;
     return run_draft(h, B, K, subset_index, hidden_in, token_in, k_cache, v_cache, kv_len, forced_tokens, draft_out,
                      logits_out, hidden_out, hip_stream, nullptr);
+}
+
+int32_t mtp_draft_continue(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, const float *own_hidden,
+                           const int32_t *token_in, void *k_cache, void *v_cache, const int32_t *kv_len,
+                           const int32_t *forced_tokens, int32_t *draft_out, float *logits_out, float *hidden_out,
+                           void *hip_stream) {
+    if (!h || !own_hidden || !token_in || !k_cache || !v_cache || !kv_len || !draft_out) return MTP_ERR_NULL;
+    const void *ptrs[] = {own_hidden, token_in, k_cache, v_cache, kv_len, forced_tokens, draft_out, logits_out,
+                          hidden_out};
+    for (const void *p : ptrs)
+        if (!aligned16(p)) return MTP_ERR_ALIGN;
+    const mtp_config &c = h->cfg;
+    if (B < 1 || B > c.max_batch) return MTP_ERR_BATCH;
+    if (K < 1 || K > c.max_draft_steps) return MTP_ERR_STEPS;
+    if (subset_index < -1 || subset_index >= (int)h->subset_dev.size()) return MTP_ERR_SUBSET;
+    return run_draft(h, B, K, subset_index, own_hidden, token_in, k_cache, v_cache, kv_len, forced_tokens, draft_out,
+                     logits_out, hidden_out, hip_stream, nullptr, own_hidden);
 }
 
 int32_t mtp_draft_extend(mtp_handle *h, int32_t B, int32_t m_max, int32_t subset_index, const void *hidden_in,

@@ -46,6 +46,8 @@ struct DraftParams {
     // (position, sequence), row = position * sequences + sequence, with a cache length per ROW in kv_len; the
     // attention runs once per position over the real sequences, with B = their number, kv_len = their real lengths
     // and:
+    int own_hidden;               // step 1 of this call starts from hhat (fp32, put there by the host: the head's own
+                                  // output of an earlier call) instead of hidden_in (bf16, the target model's)
     int row0;                     // activation row of sequence 0 in this attention launch (position * sequences)
     const int *ext_len;           // [B] new positions per sequence, or null: the ordinary one-position step
     int nb_proj, nb_d, nb_q, nb_down; // sequences staged in LDS per pass, by reduction length (2d, d, Hq*hd, F)
@@ -730,13 +732,13 @@ __device__ __forceinline__ void phase_proj(const DraftParams &p, int step, int v
                 }
                 uint16_t *hi = l.hi + (size_t)i * l.kpad, *lo = l.lo + (size_t)i * l.kpad;
                 if (whole) {
-                    if (step == 0)
+                    if (step == 0 && !p.own_hidden)
                         stage_rmsnorm<true>(p.hidden_in + (size_t)b * d, p.g_h, d, p.eps, hi, lo, l.red, nullptr);
                     else
                         stage_rmsnorm<false>(p.hhat + (size_t)b * d, p.g_h, d, p.eps, hi, lo, l.red, nullptr);
                     stage_rmsnorm<true>(p.embed + (size_t)tok * d, p.g_e, d, p.eps, hi + d, lo + d, l.red, nullptr);
                 } else {
-                    if (step == 0)
+                    if (step == 0 && !p.own_hidden)
                         stage_rmsnorm_wave<true>(p.hidden_in + (size_t)b * d, p.g_h, d, p.eps, hi, lo, nullptr);
                     else
                         stage_rmsnorm_wave<false>(p.hhat + (size_t)b * d, p.g_h, d, p.eps, hi, lo, nullptr);

@@ -413,6 +413,76 @@ def test_tiny_extend_overflow_and_then_draft(gpu, tiny):
     eng.close()
 
 
+def check_extend_then_continue(gpu, shape, w_host, w_dev, act, subsets, ext_len, m_max, K, seed, launch_mode=0,
+                               seqs=None):
+    """A block of new positions, then K recursive steps from the hidden state and draft of each sequence's last new
+    position: the oracle by single steps fed back by hand, the library by mtp_draft_extend + mtp_draft_continue
+    (fed its own hidden state, the oracle's tokens)."""
+    torch, Oracle, binding = gpu["torch"], gpu["Oracle"], gpu["binding"]
+    B = len(ext_len)
+    cap = act["kv_capacity"]
+    ids = subsets[0]
+    sel = list(range(B)) if seqs is None else list(seqs)
+    hid, tok = extend_inputs(shape, act, m_max, seed)
+    eng = binding.DraftEngine(shape, w_dev, subsets, B * m_max, cap, K)
+    ref, res, (okc, ovc) = run_extend(gpu, shape, w_host, w_dev, act, subsets, 0, hid, tok, ext_len, engine=eng,
+                                      seqs=seqs)
+    assert res["err"] == 0
+    check_extend(ref, res, (okc, ovc), act, ext_len, sel=seqs)
+    # the oracle's continuation, sequence by sequence, on its own extended caches
+    orc = Oracle(shape, w_host, cap, "f32")
+    cont = []
+    for i, b in enumerate(sel):
+        last = int(ext_len[b]) - 1
+        cont.append(orc.chain_from_own_hidden(K, ref["hidden"][last, i], int(ref["draft"][last, i]), okc[i], ovc[i],
+                                              int(ref["kv_len"][i]), ids))
+    # the library's: engine state after the same extend
+    dkc, dvc = eng.to_device_bits(act["k_cache"]), eng.to_device_bits(act["v_cache"])
+    dkv = eng.to_device_i32(act["kv_len"])
+    ex = eng.extend(0, eng.to_device_bits(hid), eng.to_device_i32(tok), eng.to_device_i32(ext_len), dkc, dvc, dkv,
+                    want_hidden=True)
+    rows = torch.tensor([int(ext_len[b]) - 1 for b in range(B)], device="cuda:0")
+    own = ex["hidden"][rows, torch.arange(B, device="cuda:0")].contiguous()          # [B][d], the library's own
+    tok1 = np.zeros(B, np.int32)
+    forced = np.zeros((B, max(K - 1, 1)), np.int32)
+    for i, b in enumerate(sel):
+        tok1[b] = ref["draft"][int(ext_len[b]) - 1, i]
+        forced[b, :K - 1] = cont[i]["draft"][:K - 1]
+    assert binding.mtp_set_launch_mode(eng.handle, launch_mode) == 0
+    out = eng.draft_continue(K, 0, own, eng.to_device_i32(tok1), dkc, dvc, dkv,
+                             forced=eng.to_device_i32(forced) if K > 1 else None, want_logits=True, want_hidden=True)
+    torch.cuda.synchronize()
+    assert eng.poll_error() == 0
+    lg, hd, dr = out["logits"].cpu().numpy(), out["hidden"].cpu().numpy(), out["draft"].cpu().numpy()
+    kc_after = dkc.cpu().numpy().view(np.uint16)
+    worst = 0.0
+    for i, b in enumerate(sel):
+        gap = float(np.abs(lg[b] - cont[i]["logits"]).max())
+        worst = max(worst, gap)
+        assert gap <= LOGIT_TIGHT, (b, gap)
+        assert np.abs(hd[b] - cont[i]["hidden"]).max() <= 2e-3
+        clear = cont[i]["margin"] > MARGIN
+        np.testing.assert_array_equal(dr[b][clear], cont[i]["draft"][clear])
+        L = int(ref["kv_len"][i])
+        assert appended_entries_close(kc_after[b][:, L:L + K], okc[i][:, L:L + K])
+        assert np.array_equal(kc_after[b][:, L + K:], okc[i][:, L + K:])
+    eng.close()
+    return worst
+
+
+def test_tiny_extend_then_continue(gpu, tiny):
+    act = synth.make_activations(tiny["wl"], ctx=np.array([40, 0, 120], dtype=np.int32), capacity=192)
+    check_extend_then_continue(gpu, tiny["shape"], tiny["w"], tiny["w"], act, [tiny["ids"]],
+                               np.array([3, 1, 2], dtype=np.int32), 3, 2, 240)
+    # the same through the single-launch kernel of the recursive steps (tile core, three sequences)
+    check_extend_then_continue(gpu, tiny["shape"], tiny["w"], tiny["w"], act, [tiny["ids"]],
+                               np.array([3, 1, 2], dtype=np.int32), 3, 2, 241, launch_mode=1)
+    # seven sequences: batched kernels on both calls
+    act = synth.make_activations(tiny["wl"], ctx=np.array([40, 0, 120, 7, 99, 64, 3], dtype=np.int32), capacity=192)
+    check_extend_then_continue(gpu, tiny["shape"], tiny["w"], tiny["w"], act, [tiny["ids"]],
+                               np.array([2, 1, 2, 2, 1, 2, 1], dtype=np.int32), 2, 3, 242)
+
+
 # ------------------------------------------------------------------------------------------ accept / rollback
 @pytest.mark.parametrize("K", [1, 3, 5])
 @pytest.mark.parametrize("mode", [0, 1])
@@ -509,6 +579,17 @@ def test_7b_extend_four_positions(gpu, big):
         assert res["err"] == 0
         gap = check_extend(ref, res, caches, act, ext_len, sel=seqs)
         print(name, "extend max |dlogit| =", gap)
+
+
+@pytest.mark.parametrize("launch_mode", [0, 1])
+def test_7b_extend_then_continue(gpu, big, launch_mode):
+    """Config 2: four new positions, then two recursive steps from the head's own hidden state, with a launch per
+    phase and through the single-launch kernel for one sequence."""
+    wl = synth.WORKLOADS["c2_7b_b1"]
+    act = synth.make_activations(wl)
+    gap = check_extend_then_continue(gpu, big["shape"], big["w"], big["dev"], act, synth.make_subsets(wl),
+                                     np.array([4], dtype=np.int32), 4, 2, 250 + launch_mode, launch_mode=launch_mode)
+    print("c2 extend + continue max |dlogit| =", gap)
 
 
 @pytest.mark.parametrize("launch_mode", [0, 1])
