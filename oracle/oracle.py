@@ -266,6 +266,20 @@ class Oracle:
                 "overflow": rc == 1}
 
 
+def build_subset(tokens, vocab_size: int, n: int):
+    """The high-frequency id list of Sec. 2.2 from a token stream ("identified through corpus-level statistics"):
+    occurrence counts per id, the n ids with the largest counts (equal counts: the lower id first), returned in
+    ascending id order - the format the output head of Eq. (3) is gathered with.  Ids outside [0, vocab_size) are
+    skipped and counted.  Returns dict(counts [V] int64, ids [n] int32, invalid int)."""
+    t = np.asarray(tokens, dtype=np.int64).ravel()
+    ok = (t >= 0) & (t < vocab_size)
+    counts = np.bincount(t[ok], minlength=vocab_size)
+    if not 0 <= n <= vocab_size:
+        raise ValueError("n outside 0 .. vocab_size")
+    order = np.lexsort((np.arange(vocab_size), -counts))      # by count descending, then id ascending
+    return {"counts": counts, "ids": np.sort(order[:n]).astype(np.int32), "invalid": int((~ok).sum())}
+
+
 def accept(draft, target, kv_len, mode: int = 0, precision: str = "f32"):
     """Returns dict(accept_len [B], out_tokens [B][K+1], kv_len [B] (new), pending [B])."""
     build()

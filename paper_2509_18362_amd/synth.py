@@ -222,6 +222,29 @@ def make_subsets(wl: Workload) -> List[np.ndarray]:
     return [np.sort(order[:n]).astype(np.int32) for n in wl.subset_sizes]
 
 
+def make_token_stream(vocab_size: int, n_tokens: int, seed: int, exponent: float = 1.1,
+                      invalid_every: int = 0) -> np.ndarray:
+    """Stand-in for a tokenised corpus (the frequency statistics behind the high-frequency lists of Sec. 2.2):
+    n_tokens ids drawn independently with P(rank r) ~ 1/(r+1)^exponent, ranks mapped to ids by a seeded
+    permutation, so frequent ids are scattered over the vocabulary.  invalid_every > 0 plants an out-of-range id
+    (-1 or vocab_size, alternating) at every invalid_every-th position."""
+    g = np.random.Generator(np.random.PCG64(BASE_SEED + 77000 + seed))
+    w = 1.0 / np.power(np.arange(vocab_size, dtype=np.float64) + 1.0, exponent)
+    cdf = np.cumsum(w)
+    cdf /= cdf[-1]
+    perm = g.permutation(vocab_size).astype(np.int32)
+    out = np.empty(n_tokens, dtype=np.int32)
+    step = 1 << 22
+    for lo in range(0, n_tokens, step):
+        hi = min(n_tokens, lo + step)
+        r = np.searchsorted(cdf, g.random(hi - lo), side="right")
+        out[lo:hi] = perm[np.minimum(r, vocab_size - 1)]
+    if invalid_every > 0:
+        idx = np.arange(invalid_every - 1, n_tokens, invalid_every)
+        out[idx] = np.where(np.arange(len(idx)) % 2 == 0, -1, vocab_size).astype(np.int32)
+    return out
+
+
 def make_targets(wl: Workload, drafts: np.ndarray, accept_prob: Optional[float] = None,
                  salt: int = 0) -> np.ndarray:
     """Stand-in for the target model's greedy tokens g_1..g_{K+1} (Sec. 2.3, verification):

@@ -561,6 +561,53 @@ def test_extend_overflow_leaves_the_sequence_alone(orc, tiny):
         assert (res["draft"][:, 1] >= 0).all() and res["kv_len"][1] == kv[1] + 3
 
 
+# ---------------------------------------------------------------- high-frequency list from a token stream
+def test_build_subset_brute_force_and_invariants():
+    """Counts and the top-n rule against plain Python on small streams (dict counting, sort with an explicit key),
+    including ties at the cut, ids that never occur, ids out of range, n = 0 and n = V."""
+    rng = np.random.default_rng(5)
+    for V, N, n in ((7, 40, 3), (16, 10, 12), (50, 2000, 50), (50, 2000, 0), (33, 500, 5)):
+        toks = rng.integers(-2, V + 2, size=N)
+        got = orc_mod.build_subset(toks, V, n)
+        cnt = {}
+        bad = 0
+        for t in toks.tolist():
+            if 0 <= t < V:
+                cnt[t] = cnt.get(t, 0) + 1
+            else:
+                bad += 1
+        ranked = sorted(range(V), key=lambda v: (-cnt.get(v, 0), v))
+        assert got["invalid"] == bad
+        assert got["counts"].tolist() == [cnt.get(v, 0) for v in range(V)]
+        assert got["ids"].tolist() == sorted(ranked[:n])
+        # what makes it a top-n list: nothing outside occurs more often than anything inside
+        inside = set(got["ids"].tolist())
+        if 0 < n < V:
+            assert min(cnt.get(v, 0) for v in inside) >= max(cnt.get(v, 0) for v in range(V) if v not in inside)
+    # a worked example: counts 3, 1, 3, 0, 2 -> top-3 = ids {0, 2, 4}; top-2 takes the tie 0, 2 (not 4)
+    ex = [0, 0, 0, 1, 2, 2, 2, 4, 4]
+    assert orc_mod.build_subset(ex, 5, 3)["ids"].tolist() == [0, 2, 4]
+    assert orc_mod.build_subset(ex, 5, 2)["ids"].tolist() == [0, 2]
+    assert orc_mod.build_subset(ex, 5, 4)["ids"].tolist() == [0, 1, 2, 4]
+    assert orc_mod.build_subset(ex, 5, 5)["ids"].tolist() == [0, 1, 2, 3, 4]
+
+
+def test_token_stream_is_long_tailed_and_list_covers_it():
+    """The synthetic corpus has the long tail Sec. 2.2 describes: a fifth of the vocabulary covers most occurrences,
+    and the list built from one half of a stream covers the other half almost as well."""
+    V, N = 4096, 1 << 18
+    s = synth.make_token_stream(V, N, seed=1)
+    a, b = s[: N // 2], s[N // 2:]
+    lst = orc_mod.build_subset(a, V, V // 5)
+    assert lst["invalid"] == 0 and len(set(lst["ids"].tolist())) == V // 5
+    assert (np.diff(lst["ids"]) > 0).all()
+    cover_a = np.isin(a, lst["ids"]).mean()
+    cover_b = np.isin(b, lst["ids"]).mean()
+    assert cover_a > 0.75 and cover_b > cover_a - 0.02
+    s2 = synth.make_token_stream(V, 1000, seed=2, invalid_every=10)
+    assert orc_mod.build_subset(s2, V, 10)["invalid"] == 100
+
+
 def test_f32_oracle_within_rounding_of_f64(tiny):
     act, ids = tiny["act"], tiny["ids"]
     outs = {}
