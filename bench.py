@@ -63,6 +63,9 @@ def main() -> int:
     ap.add_argument("--extend", type=int, default=0,
                     help="also time the first draft step over a block of this many new positions per sequence "
                          "(mtp_draft_extend); reported beside the main figures, never part of `value`")
+    ap.add_argument("--list-builder", type=int, default=0, metavar="LOG2_TOKENS",
+                    help="also time the high-frequency list builder (mtp_subset_build) on a synthetic long-tailed "
+                         "stream of 2^LOG2_TOKENS tokens over this workload's vocabulary")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full-vocab", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
@@ -228,6 +231,41 @@ def main() -> int:
                   "weight_pass_bytes": blk_bytes}
         eng2.close()
 
+    builder = None
+    if args.list_builder > 0:
+        n_tok = 1 << args.list_builder
+        stream_host = synth.make_token_stream(shape.vocab_size, n_tok, seed=9)
+        stream_dev = torch.from_numpy(stream_host).to("cuda:0")
+        n_list = min(32768, shape.vocab_size)
+        ws_bytes = binding.mtp_subset_workspace_bytes(shape.vocab_size)
+        ws_b = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda:0")
+        ids_b = torch.empty(n_list, dtype=torch.int32, device="cuda:0")
+
+        def build_once():
+            st = binding.mtp_subset_build(stream_dev, n_tok, shape.vocab_size, n_list, ws_b, ws_bytes, ids_b, None,
+                                          None, stream)
+            assert st == 0, binding.mtp_status_string(st)
+
+        for _ in range(3):
+            build_once()
+        torch.cuda.synchronize()
+        reps_b = 20
+        t = time.perf_counter()
+        for _ in range(reps_b):
+            build_once()
+        torch.cuda.synchronize()
+        el_l = (time.perf_counter() - t) / reps_b
+        t = time.perf_counter()
+        from oracle import oracle as orc_list
+        ref_l = orc_list.build_subset(stream_host, shape.vocab_size, n_list)
+        cpu_l = time.perf_counter() - t
+        assert np.array_equal(ids_b.cpu().numpy(), ref_l["ids"])
+        builder = {"tokens": n_tok, "vocab": shape.vocab_size, "list_size": n_list, "us_per_build": el_l * 1e6,
+                   "tokens_per_s": n_tok / el_l, "algorithmic_gbs": 4.0 * n_tok / el_l / 1e9,
+                   "frac_of_hbm_peak": 4.0 * n_tok / el_l / 1e9 / HBM_PEAK_GBS,
+                   "stream_passes": -(-shape.vocab_size // 40000), "oracle_seconds": cpu_l,
+                   "matches_oracle": True}
+
     full = None
     if not args.no_full_vocab and args.subset >= 0:
         fs = max(10, args.steps // 4)
@@ -287,7 +325,7 @@ def main() -> int:
         "us_per_mtp_step": us_per_mtp_step, "mean_accept_len": mean_accept,
         "chain_us": {"p10": p10, "p50": p50, "p90": p90, "what": f"{K} draft steps, one library call"},
         "accept_us": accept_us,
-        "algorithmic_bytes_per_step": chain_bytes, "roofline": roofline, "full_vocab": full, "extend": extend,
+        "algorithmic_bytes_per_step": chain_bytes, "roofline": roofline, "full_vocab": full, "extend": extend, "list_builder": builder,
         "cpu_baseline": cpu,
         "input_generation_s": gen_s,
     }

@@ -234,6 +234,24 @@ int32_t mtp_set_launch_mode(mtp_handle *h, int32_t mode);
  */
 int32_t mtp_set_phase_trace(mtp_handle *h, void *device_buffer);
 
+/*
+ * The high-frequency id list of one language from a token stream (Sec. 2.2: the subsets are "identified through
+ * corpus-level statistics"; Eq. (3) gathers the output head's rows with them): occurrence counts per id, the n ids
+ * with the largest counts (equal counts: the lower id first), written in ascending id order - the format
+ * mtp_draft_init takes.  Stateless: no handle; everything is enqueued on hip_stream and nothing waits.
+ *   tokens       device [n_tokens] int32     ids; values outside [0, vocab_size) are skipped and counted (may be
+ *                                            NULL when n_tokens is 0)
+ *   n_tokens     0 .. 2^31 - 1;  n: 0 .. vocab_size (else MTP_ERR_CONFIG)
+ *   workspace    device, mtp_subset_workspace_bytes(vocab_size) bytes, owned by the caller; holds the counts
+ *   ids_out      device [n] int32            the list, ascending
+ *   counts_out   device [vocab_size] int32 or NULL;  invalid_out device [1] int32 or NULL (skipped ids)
+ * All device pointers 16-byte aligned.
+ */
+size_t mtp_subset_workspace_bytes(int32_t vocab_size);
+int32_t mtp_subset_build(const int32_t *tokens, int64_t n_tokens, int32_t vocab_size, int32_t n, void *workspace,
+                         size_t workspace_bytes, int32_t *ids_out, int32_t *counts_out, int32_t *invalid_out,
+                         void *hip_stream);
+
 /* Frees the host object.  Device memory stays with the caller. */
 void mtp_draft_destroy(mtp_handle *h);
 

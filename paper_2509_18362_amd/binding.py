@@ -28,7 +28,7 @@ STATUS = {0: "MTP_OK", -1: "MTP_ERR_NULL", -2: "MTP_ERR_ALIGN", -3: "MTP_ERR_CON
           -5: "MTP_ERR_STEPS", -6: "MTP_ERR_SUBSET", -7: "MTP_ERR_WORKSPACE", -8: "MTP_ERR_HIP",
           -9: "MTP_ERR_KV_OVERFLOW", -10: "MTP_ERR_TOKEN_RANGE", -11: "MTP_ERR_MODE", -12: "MTP_ERR_TIMEOUT"}
 EXPORTS = ["mtp_status_string", "mtp_workspace_bytes", "mtp_draft_init", "mtp_draft_steps", "mtp_draft_extend",
-           "mtp_draft_continue",
+           "mtp_draft_continue", "mtp_subset_workspace_bytes", "mtp_subset_build",
            "mtp_accept",
            "mtp_poll_error", "mtp_set_timing", "mtp_last_draft_ms", "mtp_set_launch_mode", "mtp_set_phase_trace",
            "mtp_draft_destroy"]
@@ -66,6 +66,11 @@ _lib.mtp_draft_init.argtypes = [C.POINTER(C.c_void_p), C.POINTER(mtp_config), C.
                                 C.POINTER(C.c_void_p), C.POINTER(C.c_int32), C.c_void_p, C.c_size_t]
 _lib.mtp_draft_steps.restype = C.c_int32
 _lib.mtp_draft_steps.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32] + [C.c_void_p] * 10
+_lib.mtp_subset_workspace_bytes.restype = C.c_size_t
+_lib.mtp_subset_workspace_bytes.argtypes = [C.c_int32]
+_lib.mtp_subset_build.restype = C.c_int32
+_lib.mtp_subset_build.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p,
+                                  C.c_void_p, C.c_void_p, C.c_void_p]
 _lib.mtp_draft_continue.restype = C.c_int32
 _lib.mtp_draft_continue.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32] + [C.c_void_p] * 10
 _lib.mtp_draft_extend.restype = C.c_int32
@@ -119,6 +124,31 @@ def mtp_draft_init(cfg: mtp_config, weights: Dict[str, object], subsets: Sequenc
     st = _lib.mtp_draft_init(C.byref(handle), C.byref(cfg), C.byref(w), ns, ids if ns else None,
                              sizes if ns else None, _addr(workspace), workspace_bytes)
     return int(st), (handle if st == MTP_OK else None)
+
+
+def mtp_subset_workspace_bytes(vocab_size: int) -> int:
+    return int(_lib.mtp_subset_workspace_bytes(vocab_size))
+
+
+def mtp_subset_build(tokens, n_tokens: int, vocab_size: int, n: int, workspace, workspace_bytes: int, ids_out,
+                     counts_out=None, invalid_out=None, stream=0) -> int:
+    return int(_lib.mtp_subset_build(_addr(tokens), n_tokens, vocab_size, n, _addr(workspace), workspace_bytes,
+                                     _addr(ids_out), _addr(counts_out), _addr(invalid_out), stream))
+
+
+def build_subset(tokens, vocab_size: int, n: int, want_counts: bool = False, stream: int = 0):
+    """tokens: device int32 tensor.  Returns dict(ids [n], counts [V] or None, invalid [1]) of device tensors."""
+    import torch
+    dev = tokens.device
+    nbytes = mtp_subset_workspace_bytes(vocab_size)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    ids = torch.empty(max(n, 1), dtype=torch.int32, device=dev)
+    counts = torch.empty(vocab_size, dtype=torch.int32, device=dev) if want_counts else None
+    invalid = torch.empty(4, dtype=torch.int32, device=dev)
+    st = mtp_subset_build(tokens, tokens.numel(), vocab_size, n, ws, nbytes, ids, counts, invalid, stream)
+    if st != MTP_OK:
+        raise MTPError(st)
+    return {"ids": ids[:n], "counts": counts, "invalid": invalid[:1], "workspace": ws}
 
 
 def mtp_draft_continue(handle, B: int, K: int, subset_index: int, own_hidden, token_in, k_cache, v_cache, kv_len,

@@ -19,7 +19,7 @@ HIPCC_FLAGS = [
 ]
 
 
-SOURCES = ["mtp_draft.hip", "mtp_batch.hip"]
+SOURCES = ["mtp_draft.hip", "mtp_batch.hip", "subset_build.hip"]
 
 
 def _run(cmd, verbose):
