@@ -181,6 +181,22 @@ int32_t mtp_draft_extend(mtp_handle *h, int32_t B, int32_t m_max, int32_t subset
                          int32_t *draft_out, float *logits_out, float *hidden_out, void *hip_stream);
 
 /*
+ * mtp_draft_steps with one id list per sequence: several languages in one batch (Sec. 2.2: the list is chosen "based
+ * on the current context", per language).  Every phase but the output head runs once for the whole batch; the output
+ * head runs once per list, over the sequences that use it.
+ *   seq_subset   HOST [B] int32   index of each sequence's list (-1 = full vocabulary).  Sequences that share a list
+ *                                 must be adjacent (sort the batch by language); at most 16 different lists per call;
+ *                                 otherwise MTP_ERR_SUBSET.  Read before the call returns.
+ *   logits_out   device [B][K][n_max] float or NULL, n_max = the largest list of the call; a sequence with a shorter
+ *                list fills its first n entries of every row.
+ * Everything else as for mtp_draft_steps.  Always one launch per phase, whatever the launch mode.
+ */
+int32_t mtp_draft_steps_lists(mtp_handle *h, int32_t B, int32_t K, const int32_t *seq_subset, const void *hidden_in,
+                              const int32_t *token_in, void *k_cache, void *v_cache, const int32_t *kv_len,
+                              const int32_t *forced_tokens, int32_t *draft_out, float *logits_out, float *hidden_out,
+                              void *hip_stream);
+
+/*
  * Draft steps that start from the head's OWN output instead of the target model's hidden state (Sec. 2.3: from the
  * second step on the head consumes its own output hidden state and the previously drafted token).  After
  * mtp_draft_extend has produced the first draft token d_1 and the hidden state of a sequence's last new position,

@@ -28,7 +28,7 @@ STATUS = {0: "MTP_OK", -1: "MTP_ERR_NULL", -2: "MTP_ERR_ALIGN", -3: "MTP_ERR_CON
           -5: "MTP_ERR_STEPS", -6: "MTP_ERR_SUBSET", -7: "MTP_ERR_WORKSPACE", -8: "MTP_ERR_HIP",
           -9: "MTP_ERR_KV_OVERFLOW", -10: "MTP_ERR_TOKEN_RANGE", -11: "MTP_ERR_MODE", -12: "MTP_ERR_TIMEOUT"}
 EXPORTS = ["mtp_status_string", "mtp_workspace_bytes", "mtp_draft_init", "mtp_draft_steps", "mtp_draft_extend",
-           "mtp_draft_continue", "mtp_subset_workspace_bytes", "mtp_subset_build",
+           "mtp_draft_continue", "mtp_draft_steps_lists", "mtp_subset_workspace_bytes", "mtp_subset_build",
            "mtp_accept",
            "mtp_poll_error", "mtp_set_timing", "mtp_last_draft_ms", "mtp_set_launch_mode", "mtp_set_phase_trace",
            "mtp_draft_destroy"]
@@ -71,6 +71,8 @@ _lib.mtp_subset_workspace_bytes.argtypes = [C.c_int32]
 _lib.mtp_subset_build.restype = C.c_int32
 _lib.mtp_subset_build.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p,
                                   C.c_void_p, C.c_void_p, C.c_void_p]
+_lib.mtp_draft_steps_lists.restype = C.c_int32
+_lib.mtp_draft_steps_lists.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_int32)] + [C.c_void_p] * 10
 _lib.mtp_draft_continue.restype = C.c_int32
 _lib.mtp_draft_continue.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32] + [C.c_void_p] * 10
 _lib.mtp_draft_extend.restype = C.c_int32
@@ -124,6 +126,15 @@ def mtp_draft_init(cfg: mtp_config, weights: Dict[str, object], subsets: Sequenc
     st = _lib.mtp_draft_init(C.byref(handle), C.byref(cfg), C.byref(w), ns, ids if ns else None,
                              sizes if ns else None, _addr(workspace), workspace_bytes)
     return int(st), (handle if st == MTP_OK else None)
+
+
+def mtp_draft_steps_lists(handle, B: int, K: int, seq_subset, hidden_in, token_in, k_cache, v_cache, kv_len,
+                          forced_tokens, draft_out, logits_out=None, hidden_out=None, stream=0) -> int:
+    """seq_subset: a host sequence of B list indices."""
+    arr = (C.c_int32 * B)(*[int(x) for x in seq_subset])
+    return int(_lib.mtp_draft_steps_lists(handle, B, K, arr, _addr(hidden_in), _addr(token_in), _addr(k_cache),
+                                          _addr(v_cache), _addr(kv_len), _addr(forced_tokens), _addr(draft_out),
+                                          _addr(logits_out), _addr(hidden_out), stream))
 
 
 def mtp_subset_workspace_bytes(vocab_size: int) -> int:
@@ -259,6 +270,22 @@ class DraftEngine:
             else None
         st = mtp_draft_steps(self.handle, B, K, subset_index, hidden_in, token_in, k_cache, v_cache, kv_len, forced,
                              draft, logits, hidden, stream)
+        if st != MTP_OK:
+            raise MTPError(st)
+        return {"draft": draft, "logits": logits, "hidden": hidden}
+
+    def draft_lists(self, K: int, seq_subset, hidden_in, token_in, k_cache, v_cache, kv_len, forced=None,
+                    want_logits: bool = False, want_hidden: bool = False, stream: int = 0):
+        """Draft steps with one id list per sequence (host list seq_subset).  logits: [B][K][largest list]."""
+        torch = self.torch
+        B = token_in.numel()
+        n_max = max(self.subset_size(int(s)) for s in seq_subset)
+        draft = torch.empty((B, K), dtype=torch.int32, device=self.device)
+        logits = torch.zeros((B, K, n_max), dtype=torch.float32, device=self.device) if want_logits else None
+        hidden = torch.empty((B, K, self.shape.d_model), dtype=torch.float32, device=self.device) if want_hidden \
+            else None
+        st = mtp_draft_steps_lists(self.handle, B, K, seq_subset, hidden_in, token_in, k_cache, v_cache, kv_len,
+                                   forced, draft, logits, hidden, stream)
         if st != MTP_OK:
             raise MTPError(st)
         return {"draft": draft, "logits": logits, "hidden": hidden}

@@ -699,7 +699,7 @@ struct BgHead : BgBase {
             const int bl = bf + c;
             if (bl < p.nb && pos < p.n) {
                 const float logit = v[c] * scale[bl];
-                if (p.logits_out) p.logits_out[((size_t)(p.b0 + bl) * p.K + step) * p.n + pos] = logit;
+                if (p.logits_out) p.logits_out[((size_t)(p.b0 + bl) * p.K + step) * p.logit_stride + pos] = logit;
                 const unsigned long long key = argmax_key(logit, (uint32_t)pos);
 #pragma unroll
                 for (int a = 0; a < kBatchMaxSeq / 16; ++a) // static indices keep the array in registers
@@ -766,7 +766,7 @@ __device__ __forceinline__ void phase_bprep(const DraftParams &p, int step, char
     if (step == 0 && threadIdx.x == 0 && seq_overflows(p, b)) atomicOr(p.err, kErrKvOverflow);
     int did = 0;
     if (step > 0) {
-        did = key_token(p, winner_key(p, step - 1, b, reinterpret_cast<unsigned long long *>(red)));
+        did = key_token(p, b, winner_key(p, step - 1, b, reinterpret_cast<unsigned long long *>(red)));
         if (threadIdx.x == 0) p.draft_out[(size_t)b * p.K + step - 1] = seq_dead(p, b) ? -1 : did;
         float *ho = p.hidden_out ? p.hidden_out + ((size_t)b * p.K + step - 1) * d : nullptr;
         // the hi/lo halves written here are overwritten below or never read

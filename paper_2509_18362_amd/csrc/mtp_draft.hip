@@ -110,6 +110,25 @@ __global__ void k_extend_finish(int B, int m_max, int cap, int *kv_len, const in
     if (L >= 0 && m >= 0 && m <= m_max && L + m <= cap) kv_len[b] = L + m;
 }
 
+// One id list per group of adjacent sequences: the tables the kernels look a sequence's list up in.
+constexpr int kMaxListGroups = 16;
+struct ListGroups {
+    int count;
+    int lo[kMaxListGroups], hi[kMaxListGroups]; // sequences [lo, hi)
+    const int *ids[kMaxListGroups];             // null = the full vocabulary
+    int n[kMaxListGroups], cands[kMaxListGroups];
+};
+__global__ void k_set_lists(ListGroups g, int *seq_list, const int **list_ids, int *list_n, int *list_cands) {
+    for (int s = 0; s < g.count; ++s) {
+        for (int b = g.lo[s] + threadIdx.x; b < g.hi[s]; b += blockDim.x) seq_list[b] = s;
+        if (threadIdx.x == 0) {
+            list_ids[s] = g.ids[s];
+            list_n[s] = g.n[s];
+            list_cands[s] = g.cands[s];
+        }
+    }
+}
+
 typedef void (*phase_kernel_t)(DraftParams, int);
 
 phase_kernel_t attn_kernel(int G, int HD) {
@@ -222,7 +241,7 @@ size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 struct WsLayout {
     size_t x, qkv, attn, o, gu, dn, hhat, err, bar, cand, rope_inv, attn_part, total;
     // batched path (max_batch above kBatchMinSeq - 1 only)
-    size_t act0, act1, ssq, part, ticket, a_lo, attn_ticket, row_len;
+    size_t act0, act1, ssq, part, ticket, a_lo, attn_ticket, row_len, seq_list, list_ids, list_n, list_cands;
     int a_stride;
 };
 
@@ -262,6 +281,10 @@ WsLayout ws_layout(const mtp_config &c) {
     l.attn_part = take(attn_part_floats(c) * 4);
     l.attn_ticket = take(mb * (size_t)c.n_kv_heads * 4);
     l.row_len = take(mb * 4);
+    l.seq_list = take(mb * 4);
+    l.list_ids = take(kMaxListGroups * 8);
+    l.list_n = take(kMaxListGroups * 4);
+    l.list_cands = take(kMaxListGroups * 4);
     if (c.max_batch >= kBatchMinSeq) {
         size_t kmax = std::max({2 * d, qd, (size_t)c.d_ffn});
         l.a_stride = (int)((kmax + 31) / 32 * 32);
@@ -465,8 +488,32 @@ struct ExtendCall {
 int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, const void *hidden_in,
                   const int32_t *token_in, void *k_cache, void *v_cache, const int32_t *kv_len,
                   const int32_t *forced_tokens, int32_t *draft_out, float *logits_out, float *hidden_out,
-                  void *hip_stream, const ExtendCall *ext, const float *own_hidden = nullptr) {
+                  void *hip_stream, const ExtendCall *ext, const float *own_hidden = nullptr,
+                  const int32_t *seq_subset = nullptr) {
     const mtp_config &c = h->cfg;
+    // one id list per group of adjacent sequences (host array seq_subset [B]); subset_index is then ignored
+    ListGroups groups{};
+    int group_subset[kMaxListGroups];
+    if (seq_subset) {
+        for (int b = 0; b < B; ++b) {
+            const int s = seq_subset[b];
+            if (s < -1 || s >= (int)h->subset_dev.size()) return MTP_ERR_SUBSET;
+            if (b > 0 && s == seq_subset[b - 1]) {
+                groups.hi[groups.count - 1] = b + 1;
+                continue;
+            }
+            for (int g = 0; g < groups.count; ++g) // a list may head one run of adjacent sequences only
+                if (group_subset[g] == s) return MTP_ERR_SUBSET;
+            if (groups.count == kMaxListGroups) return MTP_ERR_SUBSET;
+            group_subset[groups.count] = s;
+            const int g = groups.count++;
+            groups.lo[g] = b;
+            groups.hi[g] = b + 1;
+            groups.ids[g] = s < 0 ? nullptr : h->subset_dev[s];
+            groups.n[g] = s < 0 ? c.vocab_size : h->subset_n[s];
+        }
+        subset_index = seq_subset[0];
+    }
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
 
     DraftParams p{};
@@ -534,6 +581,10 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
     p.bar_timeout = 200000000ll; // 2 s of the 100 MHz wall clock
     p.trace = h->trace;
     p.max_batch = c.max_batch;
+    p.seq_lo = 0;
+    p.seq_hi = B;
+    p.logit_stride = p.n;
+    for (int g = 0; g < groups.count; ++g) p.logit_stride = std::max(p.logit_stride, groups.n[g]);
     if (own_hidden) { // the first step starts from the head's own output of an earlier call
         if (hipMemcpyAsync(p.hhat, own_hidden, (size_t)B * p.d * sizeof(float), hipMemcpyDeviceToDevice, st) != hipSuccess)
             return MTP_ERR_HIP;
@@ -549,6 +600,17 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
         p.kv_len = row_len;
     }
 
+    auto publish_lists = [&]() { // the groups' tables, once their candidate counts are known
+        if (!groups.count) return;
+        int *seq_list = reinterpret_cast<int *>(ws + l.seq_list);
+        const int **list_ids = reinterpret_cast<const int **>(ws + l.list_ids);
+        int *list_n = reinterpret_cast<int *>(ws + l.list_n), *list_cands = reinterpret_cast<int *>(ws + l.list_cands);
+        hipLaunchKernelGGL(k_set_lists, dim3(1), dim3(256), 0, st, groups, seq_list, list_ids, list_n, list_cands);
+        p.seq_list = seq_list;
+        p.list_ids = list_ids;
+        p.list_n = list_n;
+        p.list_cands = list_cands;
+    };
     // sequences per weight pass, bounded by LDS
     size_t budget = std::min(h->lds_limit, B <= 2 ? kLdsSmallBatch : kLdsLargeBatch);
     auto fit = [&](int Kdim, int nmat) {
@@ -578,7 +640,7 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
 
     const int tphase = h->timing >= 2 ? h->timing - 2 : -1;
     h->pev_used = 0;
-    if (h->mode == 1 && tphase < 0 && !ext) {
+    if (h->mode == 1 && tphase < 0 && !ext && !seq_subset) {
         // single launch: all B sequences are staged together and every workgroup must be resident at once (one
         // per CU; the cooperative launch checks it).  Falls back to one launch per phase when LDS cannot hold B.
         const int fgrid = std::min(h->num_cus, kMaxFusedGrid);
@@ -705,17 +767,48 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
         plan(BG_OPROJ, p.d / 16, 1, p.qd);
         plan(BG_GATEUP, (p.F + 15) / 16, 2, p.d);
         plan(BG_DOWN, p.d / 16, 1, p.F);
-        plan(BG_LMHEAD, (p.n + 15) / 16, 1, p.d);
+        // the output head: one plan per id list (one list: one plan)
+        struct HeadPlan {
+            int rg, kp, sep;
+            size_t lds;
+        } head_plan[kMaxListGroups];
+        const int n_heads = std::max(1, groups.count);
+        int max_cands = 0;
+        for (int g = 0; g < n_heads; ++g) {
+            plan(BG_LMHEAD, ((groups.count ? groups.n[g] : p.n) + 15) / 16, 1, p.d);
+            head_plan[g] = HeadPlan{p.bg_rg[BG_LMHEAD], p.bg_kp[BG_LMHEAD], p.bg_sep[BG_LMHEAD], lds_bg[BG_LMHEAD]};
+            if (lds_bg[BG_LMHEAD] > h->lds_limit) return MTP_ERR_CONFIG;
+            const int cands = p.bg_sep[BG_LMHEAD] ? batch_epilogue_grid(BG_LMHEAD, p, na) : p.bg_rg[BG_LMHEAD];
+            if (groups.count) groups.cands[g] = cands;
+            max_cands = std::max(max_cands, cands);
+        }
         for (int ph = 0; ph < BG_COUNT; ++ph)
             if (lds_bg[ph] > h->lds_limit) return MTP_ERR_CONFIG;
         // candidates of the output head: one per row group, or one per workgroup of its separate epilogue, whose
         // grid is then this number for every pass of the call (workgroups without work leave "no candidate")
-        p.head_grid = p.bg_sep[BG_LMHEAD] ? batch_epilogue_grid(BG_LMHEAD, p, na) : p.bg_rg[BG_LMHEAD];
+        p.head_grid = max_cands;
+        publish_lists();
         auto matrix_phase = [&](int timed_as, int ph, int step) {
-            for (int b0 = 0; b0 < B; b0 += kBatchPassSeq) {
-                p.b0 = b0;
-                p.nb = std::min(kBatchPassSeq, B - b0);
-                launch_bgemv(ph, p, step, p.bg_rg[ph] * p.bg_kp[ph], lds_bg[ph], st);
+            const int runs = ph == BG_LMHEAD ? n_heads : 1; // the output head: once per id list
+            for (int g = 0; g < runs; ++g) {
+                int lo = 0, hi = B;
+                if (ph == BG_LMHEAD) {
+                    p.bg_rg[ph] = head_plan[g].rg;
+                    p.bg_kp[ph] = head_plan[g].kp;
+                    p.bg_sep[ph] = head_plan[g].sep;
+                    lds_bg[ph] = head_plan[g].lds;
+                    if (groups.count) {
+                        lo = groups.lo[g];
+                        hi = groups.hi[g];
+                        p.ids = groups.ids[g];
+                        p.n = groups.n[g];
+                    }
+                }
+                for (int b0 = lo; b0 < hi; b0 += kBatchPassSeq) {
+                    p.b0 = b0;
+                    p.nb = std::min(kBatchPassSeq, hi - b0);
+                    launch_bgemv(ph, p, step, p.bg_rg[ph] * p.bg_kp[ph], lds_bg[ph], st);
+                }
             }
             mark_end(timed_as, step);
         };
@@ -748,6 +841,8 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
         if (hipGetLastError() != hipSuccess) return MTP_ERR_HIP;
         return MTP_OK;
     }
+    for (int g = 0; g < groups.count; ++g) groups.cands[g] = grid; // every launch leaves one candidate per workgroup
+    publish_lists();
     for (int step = 0; step < K; ++step) {
         launch(PH_PROJ, k_proj, grid, lds_proj, step);
         launch(PH_QKV, k_qkv, grid, lds_d1, step);
@@ -757,7 +852,19 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
         launch(PH_OPROJ, k_oproj, grid, lds_q, step);
         launch(PH_GATEUP, k_gateup, grid, lds_d2, step);
         launch(PH_DOWN, k_down, grid, lds_down, step);
-        launch(PH_LMHEAD, k_lmhead, grid, lds_d1, step);
+        if (!groups.count) {
+            launch(PH_LMHEAD, k_lmhead, grid, lds_d1, step);
+        } else { // once per id list, over that list's sequences
+            mark_begin(PH_LMHEAD, step);
+            for (int g = 0; g < groups.count; ++g) {
+                p.seq_lo = groups.lo[g];
+                p.seq_hi = groups.hi[g];
+                p.ids = groups.ids[g];
+                p.n = groups.n[g];
+                hipLaunchKernelGGL(k_lmhead, dim3(grid), dim3(kBlock), lds_d1, st, p, step);
+            }
+            mark_end(PH_LMHEAD, step);
+        }
     }
     hipLaunchKernelGGL(k_finalize, dim3((B + kWaves - 1) / kWaves), dim3(kBlock), 0, st, p);
     if (ext)
@@ -790,6 +897,23 @@ int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_inde
     if (subset_index < -1 || subset_index >= (int)h->subset_dev.size()) return MTP_ERR_SUBSET;
     return run_draft(h, B, K, subset_index, hidden_in, token_in, k_cache, v_cache, kv_len, forced_tokens, draft_out,
                      logits_out, hidden_out, hip_stream, nullptr);
+}
+
+int32_t mtp_draft_steps_lists(mtp_handle *h, int32_t B, int32_t K, const int32_t *seq_subset, const void *hidden_in,
+                              const int32_t *token_in, void *k_cache, void *v_cache, const int32_t *kv_len,
+                              const int32_t *forced_tokens, int32_t *draft_out, float *logits_out, float *hidden_out,
+                              void *hip_stream) {
+    if (!h || !seq_subset || !hidden_in || !token_in || !k_cache || !v_cache || !kv_len || !draft_out)
+        return MTP_ERR_NULL;
+    const void *ptrs[] = {hidden_in, token_in, k_cache, v_cache, kv_len, forced_tokens, draft_out, logits_out,
+                          hidden_out};
+    for (const void *p : ptrs)
+        if (!aligned16(p)) return MTP_ERR_ALIGN;
+    const mtp_config &c = h->cfg;
+    if (B < 1 || B > c.max_batch) return MTP_ERR_BATCH;
+    if (K < 1 || K > c.max_draft_steps) return MTP_ERR_STEPS;
+    return run_draft(h, B, K, 0, hidden_in, token_in, k_cache, v_cache, kv_len, forced_tokens, draft_out, logits_out,
+                     hidden_out, hip_stream, nullptr, nullptr, seq_subset);
 }
 
 int32_t mtp_draft_continue(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, const float *own_hidden,

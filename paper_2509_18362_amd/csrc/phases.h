@@ -34,7 +34,15 @@ struct DraftParams {
     unsigned long long bar_base; // barriers completed by earlier launches
     unsigned long long *cand; // [max_draft_steps][max_batch][head_grid] packed (logit, index) maximum of every
                               // workgroup of the output-head phase; the consumer takes the maximum over them
-    int head_grid;            // workgroups of the output-head phase
+    int head_grid;            // workgroups of the output-head phase = candidates per sequence (their stride in cand)
+    // One id list per sequence (several languages in one batch, Sec. 2.2): the output head is launched once per group
+    // of adjacent sequences with ids/n of that group; whoever turns a winner into a token id looks the sequence up.
+    const int *seq_list;             // [B] slot of each sequence's list in the tables below, or null: one list, ids/n
+    const int *const *list_ids;      // per slot: the id list (null = the full vocabulary)
+    const int *list_n;               // per slot: rows of the head
+    const int *list_cands;           // per slot: candidates the head's launch leaves per sequence (<= head_grid)
+    int seq_lo, seq_hi;              // output head, launch per phase: sequences of this launch (0, B if one list)
+    int logit_stride;                // floats per (sequence, step) in logits_out: n, or the largest n of the lists
     int fused_gemv_bytes, fused_ids_bytes; // LDS carve-up of the single-launch kernel
     long long bar_timeout;    // wall-clock ticks a workgroup may wait at one barrier before giving up
     long long *trace;         // optional [K][16] wall-clock stamps (100 MHz) of workgroup 0 in the single-launch path
@@ -113,21 +121,36 @@ __device__ __forceinline__ unsigned long long block_max_u64(unsigned long long v
 
 // Winner of the output head of `step` for sequence b: maximum over the candidates the head's workgroups left behind
 // (larger logit first, then lower subset index).  Called by all threads of a workgroup; contains barriers.
+// the output head as sequence b sees it: its id list, its row count, the candidates its launch left behind
+struct SeqHead {
+    const int *ids;
+    int n, cands;
+};
+__device__ __forceinline__ SeqHead seq_head(const DraftParams &p, int b) {
+    if (p.seq_list) {
+        const int s = p.seq_list[b];
+        return SeqHead{p.list_ids[s], p.list_n[s], p.list_cands[s]};
+    }
+    return SeqHead{p.ids, p.n, p.head_grid};
+}
+
 template <bool COH = false>
 __device__ __forceinline__ unsigned long long winner_key(const DraftParams &p, int step, int b,
                                                          unsigned long long *red64) {
     const unsigned long long *cand = p.cand + ((size_t)step * p.max_batch + b) * p.head_grid;
     unsigned long long best = 0ull;
-    for (int w = threadIdx.x; w < p.head_grid; w += kBlock) {
+    const int ncand = seq_head(p, b).cands;
+    for (int w = threadIdx.x; w < ncand; w += kBlock) {
         const unsigned long long c = ld_u64<COH>(cand + w);
         best = c > best ? c : best;
     }
     return block_max_u64(best, red64);
 }
-__device__ __forceinline__ int key_token(const DraftParams &p, unsigned long long key) {
+__device__ __forceinline__ int key_token(const DraftParams &p, int b, unsigned long long key) {
+    const SeqHead h = seq_head(p, b);
     uint32_t i = key_index(key);
-    if (i >= (uint32_t)p.n) i = 0;
-    return p.ids ? p.ids[i] : (int)i;
+    if (i >= (uint32_t)h.n) i = 0;
+    return h.ids ? h.ids[i] : (int)i;
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -288,7 +311,8 @@ __device__ __forceinline__ void stage_sequences(int nb, F f) {
 __device__ __forceinline__ unsigned long long winner_key_wave(const DraftParams &p, int step, int b) {
     const unsigned long long *cand = p.cand + ((size_t)step * p.max_batch + b) * p.head_grid;
     unsigned long long best = 0ull;
-    for (int w = threadIdx.x & (kWave - 1); w < p.head_grid; w += kWave) best = cand[w] > best ? cand[w] : best;
+    const int ncand = seq_head(p, b).cands;
+    for (int w = threadIdx.x & (kWave - 1); w < ncand; w += kWave) best = cand[w] > best ? cand[w] : best;
 #pragma unroll
     for (int off = 1; off < kWave; off <<= 1) {
         unsigned long long o = __shfl_xor(best, off, kWave);
@@ -722,7 +746,7 @@ __device__ __forceinline__ void phase_proj(const DraftParams &p, int step, int v
                 } else {
                     unsigned long long key = whole ? winner_key(p, step - 1, b, reinterpret_cast<unsigned long long *>(l.red))
                                                    : winner_key_wave(p, step - 1, b);
-                    int did = key_token(p, key);
+                    int did = key_token(p, b, key);
                     if (vb == 0 && lead) p.draft_out[(size_t)b * p.K + step - 1] = seq_dead(p, b) ? -1 : did;
                     tok = p.forced ? p.forced[(size_t)b * (p.K - 1) + step - 1] : did;
                 }
@@ -1274,8 +1298,8 @@ __device__ __forceinline__ void phase_lmhead(const DraftParams &p, int step, int
     const int d = p.d, n = p.n;
     const int nbmax = p.nb_d;
     GemvLds l = gemv_lds(smem, d, nbmax, 1);
-    for (int b0 = 0; b0 < p.B; b0 += nbmax) {
-        int nb = min(nbmax, p.B - b0);
+    for (int b0 = p.seq_lo; b0 < p.seq_hi; b0 += nbmax) { // the sequences that share this launch's id list
+        int nb = min(nbmax, p.seq_hi - b0);
         auto stage = [&]() {
             stage_sequences(nb, [&](int i, bool whole) {
                 const int b = b0 + i;
@@ -1303,7 +1327,7 @@ __device__ __forceinline__ void phase_lmhead(const DraftParams &p, int step, int
             return p.lm_head + (size_t)r * d;
         };
         auto epi = [&](int i, int row, float(&s)[1]) {
-            if (p.logits_out) p.logits_out[((size_t)(b0 + i) * p.K + step) * n + row] = s[0];
+            if (p.logits_out) p.logits_out[((size_t)(b0 + i) * p.K + step) * p.logit_stride + row] = s[0];
             unsigned long long key = argmax_key(s[0], (uint32_t)row);
 #pragma unroll
             for (int q = 0; q < kRowModeMaxSeq; ++q)
@@ -1346,13 +1370,14 @@ __device__ void phase_finalize(const DraftParams &p, int vb, int nvb) {
     for (int b = vb * kWaves + threadIdx.x / kWave; b < p.B; b += nvb * kWaves) {
         const unsigned long long *cand = p.cand + ((size_t)(p.K - 1) * p.max_batch + b) * p.head_grid;
         unsigned long long best = 0ull;
-        for (int w = lane; w < p.head_grid; w += kWave) best = cand[w] > best ? cand[w] : best;
+        const int ncand = seq_head(p, b).cands;
+        for (int w = lane; w < ncand; w += kWave) best = cand[w] > best ? cand[w] : best;
 #pragma unroll
         for (int off = 1; off < kWave; off <<= 1) {
             unsigned long long o = __shfl_xor(best, off, kWave);
             best = o > best ? o : best;
         }
-        if (lane == 0) p.draft_out[(size_t)b * p.K + p.K - 1] = seq_dead(p, b) ? -1 : key_token(p, best);
+        if (lane == 0) p.draft_out[(size_t)b * p.K + p.K - 1] = seq_dead(p, b) ? -1 : key_token(p, b, best);
     }
 }
 

@@ -483,6 +483,72 @@ def test_tiny_extend_then_continue(gpu, tiny):
                                np.array([2, 1, 2, 2, 1, 2, 1], dtype=np.int32), 2, 3, 242)
 
 
+# ------------------------------------------------------------------------------------------ one id list per sequence
+@pytest.mark.parametrize("ctx,seq_subset", [
+    ([100, 0, 64], [0, 1, -1]),                                   # row-streaming phases, three lists
+    ([10, 20, 150, 64], [1, 1, 0, 0]),
+    ([0, 1, 63, 64, 150, 7, 99], [0, 0, 0, 1, 1, -1, -1]),        # batched phases
+    (list(range(3, 123, 6)), [2] * 9 + [0] * 6 + [1] * 5),        # twenty sequences, two sequence tiles
+])
+def test_tiny_one_list_per_sequence(gpu, tiny, ctx, seq_subset):
+    """Several id lists in one batch (several languages): every sequence against the oracle run with its own list
+    - logits over its own rows, drafts mapped through its own list, caches - K = 3 with the oracle's drafts forced."""
+    torch, Oracle, binding = gpu["torch"], gpu["Oracle"], gpu["binding"]
+    shape, K = tiny["shape"], 3
+    rng = np.random.default_rng(11)
+    lists = [tiny["ids"], np.sort(rng.choice(shape.vocab_size, 300, replace=False)).astype(np.int32),
+             np.sort(rng.choice(shape.vocab_size, 37, replace=False)).astype(np.int32)]
+    act = synth.make_activations(tiny["wl"], ctx=np.array(ctx, dtype=np.int32), capacity=192)
+    B = len(ctx)
+    orc = Oracle(shape, tiny["w"], 192, "f32")
+    refs, okc, ovc = [], act["k_cache"].copy(), act["v_cache"].copy()
+    forced = np.zeros((B, K - 1), np.int32)
+    for b in range(B):
+        ids = None if seq_subset[b] < 0 else lists[seq_subset[b]]
+        r = orc.chain(K, act["hidden_in"][b:b + 1], act["token_in"][b:b + 1], okc[b:b + 1], ovc[b:b + 1],
+                      act["kv_len"][b:b + 1], ids)
+        refs.append(r)
+        forced[b] = r["draft"][0, :K - 1]
+    eng = binding.DraftEngine(shape, tiny["w"], lists, B, 192, K)
+    dkc, dvc = eng.to_device_bits(act["k_cache"]), eng.to_device_bits(act["v_cache"])
+    out = eng.draft_lists(K, seq_subset, eng.to_device_bits(act["hidden_in"]), eng.to_device_i32(act["token_in"]),
+                          dkc, dvc, eng.to_device_i32(act["kv_len"]), forced=eng.to_device_i32(forced),
+                          want_logits=True, want_hidden=True)
+    torch.cuda.synchronize()
+    assert eng.poll_error() == 0
+    lg, hd, dr = out["logits"].cpu().numpy(), out["hidden"].cpu().numpy(), out["draft"].cpu().numpy()
+    kc = dkc.cpu().numpy().view(np.uint16)
+    some_clear = False
+    for b in range(B):
+        r = refs[b]
+        n = r["logits"].shape[-1]
+        assert np.abs(lg[b, :, :n] - r["logits"][0]).max() <= LOGIT_TIGHT
+        assert np.abs(hd[b] - r["hidden"][0]).max() <= 2e-3
+        clear = r["margin"][0] > MARGIN
+        some_clear |= bool(clear.any())
+        np.testing.assert_array_equal(dr[b][clear], r["draft"][0][clear])
+        L = int(act["kv_len"][b])
+        assert appended_entries_close(kc[b][:, L:L + K], okc[b][:, L:L + K])
+        assert np.array_equal(kc[b][:, :L], okc[b][:, :L])
+    assert some_clear
+    # one list for everybody through the same entry point equals the plain call bit for bit
+    same = eng.draft_lists(K, [0] * B, eng.to_device_bits(act["hidden_in"]), eng.to_device_i32(act["token_in"]),
+                           eng.to_device_bits(act["k_cache"]), eng.to_device_bits(act["v_cache"]),
+                           eng.to_device_i32(act["kv_len"]), want_logits=True)
+    plain = eng.draft(K, 0, eng.to_device_bits(act["hidden_in"]), eng.to_device_i32(act["token_in"]),
+                      eng.to_device_bits(act["k_cache"]), eng.to_device_bits(act["v_cache"]),
+                      eng.to_device_i32(act["kv_len"]), want_logits=True)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(same["draft"].cpu().numpy(), plain["draft"].cpu().numpy())
+    np.testing.assert_array_equal(same["logits"].cpu().numpy(), plain["logits"].cpu().numpy())
+    # lists that are not adjacent are refused before anything is enqueued
+    if B >= 3:
+        bad = [0, 1, 0] + [0] * (B - 3)
+        st = binding.mtp_draft_steps_lists(eng.handle, B, K, bad, dkc, dkc, dkc, dvc, dkc, None, dkc)
+        assert st == -6
+    eng.close()
+
+
 # ------------------------------------------------------------------------------------------ accept / rollback
 @pytest.mark.parametrize("K", [1, 3, 5])
 @pytest.mark.parametrize("mode", [0, 1])
@@ -579,6 +645,34 @@ def test_7b_extend_four_positions(gpu, big):
         assert res["err"] == 0
         gap = check_extend(ref, res, caches, act, ext_len, sel=seqs)
         print(name, "extend max |dlogit| =", gap)
+
+
+def test_7b_batch16_two_lists(gpu, big):
+    """Config 3's ragged batch of sixteen with two id lists (nine sequences on the 32768-id list, seven on a 16384-id
+    one built like config 4's): sampled sequences of both groups against the oracle."""
+    torch, Oracle, binding = gpu["torch"], gpu["Oracle"], gpu["binding"]
+    wl = synth.WORKLOADS["c3_7b_b16"]
+    act = synth.make_activations(wl)
+    lists = [synth.make_subsets(wl)[0], synth.make_subsets(synth.WORKLOADS["c4_7b_vocab"])[0]]
+    B, K = wl.batch, wl.draft_steps
+    seq_subset = [0] * 9 + [1] * 7
+    eng = binding.DraftEngine(big["shape"], big["dev"], lists, B, act["kv_capacity"], K)
+    dkc, dvc = eng.to_device_bits(act["k_cache"]), eng.to_device_bits(act["v_cache"])
+    out = eng.draft_lists(K, seq_subset, eng.to_device_bits(act["hidden_in"]), eng.to_device_i32(act["token_in"]),
+                          dkc, dvc, eng.to_device_i32(act["kv_len"]), want_logits=True)
+    torch.cuda.synchronize()
+    assert eng.poll_error() == 0
+    lg, dr = out["logits"].cpu().numpy(), out["draft"].cpu().numpy()
+    orc = Oracle(big["shape"], big["w"], act["kv_capacity"], "f32")
+    for b in (0, 8, 9, 15):
+        ids = lists[seq_subset[b]]
+        r = orc.chain(1, act["hidden_in"][b:b + 1], act["token_in"][b:b + 1], act["k_cache"][b:b + 1].copy(),
+                      act["v_cache"][b:b + 1].copy(), act["kv_len"][b:b + 1], ids)
+        gap = float(np.abs(lg[b, 0, :len(ids)] - r["logits"][0, 0]).max())
+        assert gap <= LOGIT_TIGHT, (b, gap)
+        if r["margin"][0, 0] > MARGIN:
+            assert dr[b, 0] == r["draft"][0, 0]
+    eng.close()
 
 
 @pytest.mark.parametrize("launch_mode", [0, 1])
