@@ -89,7 +89,18 @@ __device__ __forceinline__ void batch_scales(const DraftParams &p, int kind, flo
 
 // Adds the KP parts of one epilogue slot (virtual tile vt, or the pair starting there, and sequence tile at) in the
 // order of the parts and hands the sums to the phase's epilogue.  Called by whole waves.
-template <int NA, class Ph>
+// A workgroup's sums for the partial buffer: plain when a later kernel adds the parts, device-coherent when the last
+// workgroup of this kernel does (uniform choice).
+__device__ __forceinline__ void st_part(float *dst, f32x4 v, bool coherent) {
+    if (coherent)
+        st_f32x4<true>(dst, v);
+    else
+        *reinterpret_cast<f32x4 *>(dst) = v;
+}
+
+// COH: the parts are read past the caches (the caller is the last workgroup of a ticket, inside the kernel that
+// wrote them).
+template <int NA, bool COH = false, class Ph>
 __device__ __forceinline__ void bg_slot_epilogue(const DraftParams &p, Ph &ph, int KP, int ntv, int vt, int at,
                                                  const float *scale_lds) {
     constexpr int NMAT = Ph::NMAT;
@@ -104,7 +115,7 @@ __device__ __forceinline__ void bg_slot_epilogue(const DraftParams &p, Ph &ph, i
             f32x4 v[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u)
-                v[u] = *reinterpret_cast<const f32x4 *>(src + (size_t)min(k2 + u, KP - 1) * kstride);
+                v[u] = ld_f32x4<COH>(src + (size_t)min(k2 + u, KP - 1) * kstride);
 #pragma unroll
             for (int u = 0; u < 8; ++u)
                 if (k2 + u < KP) sacc += v[u];
@@ -120,22 +131,25 @@ __device__ __forceinline__ void bg_slot_epilogue(const DraftParams &p, Ph &ph, i
 template <int NA, class Ph, class Slots>
 __device__ __forceinline__ void bg_tail(const DraftParams &p, Ph &ph, int KP, int rg, int ntv, int vt0, char *smem,
                                         const float *scale_lds, Slots slots) {
-    __syncthreads(); // every store of this workgroup's sums has completed
+    __syncthreads(); // every store of this workgroup's sums has completed (each wave waits for its own first)
     if (KP > 1) {
+        // The sums were written through to memory (device-coherent stores) and acknowledged before the ticket is
+        // drawn, and the last workgroup reads them past its caches: relaxed atomics suffice, and no cache is written
+        // back or invalidated (a release/acquire pair here cost ~10 us per phase).
         int *flag = reinterpret_cast<int *>(smem); // the LDS of the main loop is dead now
         if (threadIdx.x == 0) {
-            // release: the sums above become visible to the other compute dies before the ticket does;
-            // acquire: the last to arrive drops stale lines of its L1 and L2 before it reads the others' sums
-            int old = __hip_atomic_fetch_add(p.ticket + rg, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+            int old = __hip_atomic_fetch_add(p.ticket + rg, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             *flag = (old == KP - 1);
-            if (old == KP - 1) p.ticket[rg] = 0; // ready for the next launch
+            if (old == KP - 1) __hip_atomic_store(p.ticket + rg, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         __syncthreads();
         const bool last = *flag != 0;
         __syncthreads();
         if (!last) return;
+        slots([&](int t, int at) { bg_slot_epilogue<NA, true>(p, ph, KP, ntv, vt0 + t, at, scale_lds); });
+    } else {
+        slots([&](int t, int at) { bg_slot_epilogue<NA>(p, ph, KP, ntv, vt0 + t, at, scale_lds); }); // uniform per wave
     }
-    slots([&](int t, int at) { bg_slot_epilogue<NA>(p, ph, KP, ntv, vt0 + t, at, scale_lds); }); // uniform per wave
     ph.finish(rg, smem);
 }
 
@@ -311,7 +325,8 @@ __device__ __forceinline__ void bgemv(const DraftParams &p, Ph &ph, int RG, int 
             for (int w = 1; w < kWaves; ++w) sum += pb[(w * kBatchAcc + a) * kWave + lane];
             const int ts = a / NA, at = a % NA, t = grp * TG + ts;
             if (t < nvt)
-                *reinterpret_cast<f32x4 *>(part + ((((size_t)kp * ntv + vt0 + t) * NA + at) * kWave + lane) * 4) = sum;
+                st_part(part + ((((size_t)kp * ntv + vt0 + t) * NA + at) * kWave + lane) * 4, sum,
+                        KP > 1 && !p.bg_sep[Ph::WHICH]);
         }
     }
 
@@ -486,8 +501,8 @@ __device__ __forceinline__ void bgemv_lds(const DraftParams &p, Ph &ph, int RG, 
 #pragma unroll
             for (int at = 0; at < NA; ++at) {
                 if (t < nvt)
-                    *reinterpret_cast<f32x4 *>(part + ((((size_t)kp * ntv + vt0 + t) * NA + at) * kWave + lane) * 4) =
-                        acc[tw * NA + at];
+                    st_part(part + ((((size_t)kp * ntv + vt0 + t) * NA + at) * kWave + lane) * 4, acc[tw * NA + at],
+                            KP > 1 && !p.bg_sep[Ph::WHICH]);
                 acc[tw * NA + at] = f32x4{0.f, 0.f, 0.f, 0.f};
             }
         }

@@ -754,12 +754,14 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
             }
             p.bg_rg[ph] = rg;
             p.bg_kp[ph] = kp;
-            // Split reductions: the parts are added by an epilogue kernel spread over the chip.  The alternative, the
-            // last workgroup of a row group to arrive (a ticket with a device-scope release/acquire pair, which
-            // writes back and invalidates L2), costs more than the extra launch - except for the output head, whose
-            // epilogue kernel would leave four times as many argmax candidates behind (measured: 122 vs 97 us at 64
-            // sequences).
-            p.bg_sep[ph] = (kp >= 2 && ph != BG_LMHEAD) ? 1 : 0;
+            // Split reductions: who adds the parts.  Up to 16 sequences the last workgroup of a row group to arrive
+            // does (a relaxed ticket; the parts are written and read with device-coherent accesses, no cache is written
+            // back or invalidated): config 3 runs 2.4 % faster than with a kernel of its own per phase.  Above 16
+            // sequences a row group holds 64/NA tiles x NA sequence tiles of sums and the last workgroup becomes the
+            // bottleneck (config 5: 8.6 % slower), so there a small epilogue kernel spread over the chip adds them -
+            // except for the output head, whose epilogue kernel would leave four times as many argmax candidates
+            // behind (measured: 122 vs 97 us at 64 sequences).
+            p.bg_sep[ph] = (kp >= 2 && ph != BG_LMHEAD && na > 1) ? 1 : 0;
             lds_bg[ph] = bgemv_lds_bytes(((units + rg - 1) / rg) * 16);
         };
         plan(BG_PROJ, p.d / 16, 1, 2 * p.d);
