@@ -37,7 +37,8 @@ struct AttnMfmaLds {
     alignas(16) unsigned char k[kWaves][16][VS]; // one K tile per wave on its way into the MFMA operand layout
 };
 
-template <int G, int HD, bool COH = false, class Hook = NoHook>
+// TICKET: as in phase_attn, the workgroup whose split of a (sequence, KV head) finishes last merges the splits.
+template <int G, int HD, bool COH = false, bool TICKET = false, class Hook = NoHook>
 __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb, char *smem, Hook before_q = Hook()) {
     using L = AttnMfmaLds<G, HD>;
     constexpr int NS = HD / 32;        // MFMA depth steps over the head dimension
@@ -307,12 +308,28 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
                 }
             } else {
                 float *dst = p.attn_part + (((size_t)b * p.Hq + hq) * S + sp) * PW;
-                st_f32<COH>(dst + dd, A);
+                st_f32<COH || TICKET>(dst + dd, A);
                 if (dd == 0) {
-                    st_f32<COH>(dst + HD, M);
-                    st_f32<COH>(dst + HD + 1, Ls);
+                    st_f32<COH || TICKET>(dst + HD, M);
+                    st_f32<COH || TICKET>(dst + HD + 1, Ls);
                 }
             }
+        }
+        if (TICKET && nsplit > 1) { // see phase_attn: relaxed ticket, partials written and read past the caches
+            int &last_to_arrive = *reinterpret_cast<int *>(smem + sizeof(L));
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            if (tid == 0) {
+                int *ticket = p.attn_ticket + (size_t)b * p.Hkv + kvh;
+                const int old = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (old == nsplit - 1) __hip_atomic_store(ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                last_to_arrive = (old == nsplit - 1) ? 1 : 0;
+            }
+            __syncthreads();
+            const bool merges = last_to_arrive != 0;
+            if (merges && wave < G)
+                merge_head<HD, true, COH>(p, b, kvh * G + wave, nsplit, reinterpret_cast<float *>(smem) + (size_t)wave * S);
+            __syncthreads(); // the strips and the flag are free again before the next item touches the LDS
         }
     }
     if (first_item) before_q();

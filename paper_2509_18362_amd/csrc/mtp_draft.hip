@@ -19,7 +19,7 @@ using namespace mtp;
 
 namespace {
 
-enum Phase : int { PH_PROJ = 0, PH_QKV, PH_ATTN, PH_OPROJ, PH_GATEUP, PH_DOWN, PH_LMHEAD, PH_COUNT, PH_MERGE };
+enum Phase : int { PH_PROJ = 0, PH_QKV, PH_ATTN, PH_OPROJ, PH_GATEUP, PH_DOWN, PH_LMHEAD, PH_COUNT };
 
 // ---- kernels: one launch per phase ------------------------------------------------------------------
 __global__ __launch_bounds__(kBlock) void k_proj(DraftParams p, int step) {
@@ -34,11 +34,6 @@ template <int G, int HD>
 __global__ __launch_bounds__(kBlock) void k_attn(DraftParams p, int step) {
     extern __shared__ __align__(16) char smem[];
     phase_attn<G, HD, false, true>(p, step, blockIdx.x, gridDim.x, smem); // merges its own splits (tickets)
-}
-template <int HD>
-__global__ __launch_bounds__(kBlock) void k_attn_merge(DraftParams p, int step) {
-    extern __shared__ __align__(16) char smem[];
-    phase_attn_merge<HD>(p, step, blockIdx.x, gridDim.x, smem);
 }
 __global__ __launch_bounds__(kBlock) void k_oproj(DraftParams p, int step) {
     extern __shared__ __align__(16) char smem[];
@@ -315,7 +310,7 @@ struct mtp_handle {
     WsLayout lay;
     int num_cus;
     size_t lds_limit;
-    phase_kernel_t attn_fn, merge_fn;
+    phase_kernel_t attn_fn;
     fused_kernel_t fused_fn;
     fused_kernel_t fused_rows_fn;  // one sequence, row-streaming core
     int mode;                    // 0: one launch per phase, 1: single cooperative launch for the whole call
@@ -429,7 +424,6 @@ int32_t mtp_draft_init(mtp_handle **out, const mtp_config *cfg, const mtp_weight
     h->num_cus = cus;
     h->lds_limit = (size_t)lds;
     h->attn_fn = attn_kernel(cfg->n_q_heads / cfg->n_kv_heads, cfg->head_dim);
-    h->merge_fn = cfg->head_dim == 128 ? k_attn_merge<128> : k_attn_merge<64>;
     h->fused_fn = fused_kernel(cfg->n_q_heads / cfg->n_kv_heads, cfg->head_dim);
     h->fused_rows_fn = fused_rows_kernel(cfg->n_q_heads / cfg->n_kv_heads, cfg->head_dim);
     h->mode = 0;
@@ -447,7 +441,7 @@ int32_t mtp_draft_init(mtp_handle **out, const mtp_config *cfg, const mtp_weight
     } fns[] = {{(const void *)k_proj, "k_proj"},         {(const void *)k_qkv, "k_qkv"},
                {(const void *)k_oproj, "k_oproj"},       {(const void *)k_gateup, "k_gateup"},
                {(const void *)k_down, "k_down"},         {(const void *)k_lmhead, "k_lmhead"},
-               {(const void *)h->attn_fn, "k_attn"},     {(const void *)h->merge_fn, "k_attn_merge"},
+               {(const void *)h->attn_fn, "k_attn"},
                {(const void *)h->fused_fn, "k_fused"},   {(const void *)h->fused_rows_fn, "k_fused_rows"}};
     for (const auto &f : fns)
         if (ok) run(hipFuncSetAttribute(f.fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)h->lds_limit), f.name);
@@ -636,7 +630,6 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
     p.head_grid = grid;
     const int attn_items = att_B * p.Hkv * p.max_splits;
     const int attn_grid = std::max(1, std::min(attn_items, h->num_cus * 2));
-    const int merge_grid = std::max(1, std::min((att_B * p.Hq + kWaves - 1) / kWaves, h->num_cus));
 
     const int tphase = h->timing >= 2 ? h->timing - 2 : -1;
     h->pev_used = 0;
@@ -687,15 +680,13 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
     // long splits go to the matrix-core attention; short ones (small batch, short context) to the latency-lean
     // vector version
     const bool mfma_attn = p.split_tokens >= kMfmaAttnMinSplit;
-    const bool merge_launch = mfma_attn && p.max_splits > 1; // the vector version merges its own splits
     auto launch_attention_of = [&](const DraftParams &pa, int step) {
         if (mfma_attn)
             launch_attn_mfma(pa.Hq / pa.Hkv, pa.hd, pa, step, attn_grid, lds_attn, st);
         else
             hipLaunchKernelGGL(h->attn_fn, dim3(attn_grid), dim3(kBlock), lds_attn, st, pa, step);
-        if (merge_launch) hipLaunchKernelGGL(h->merge_fn, dim3(merge_grid), dim3(kBlock), lds_merge, st, pa, step);
     };
-    // attention (and the merge of its splits, where that is a launch of its own)
+    // attention (both kernels merge their own splits)
     auto launch_attention = [&](int step) {
         if (!ext) {
             launch_attention_of(p, step);

@@ -67,8 +67,8 @@ struct DraftParams {
     float *ssq;          // [3][max_batch][d/16] sums of squares over 16-row tiles of x, x1, x2
     float *part;         // partial sums of the row groups, [KP][tiles][sequence tiles][64] x 4 floats
     int *ticket;         // arrival counters of the row groups (zero between launches)
-    int *attn_ticket;    // [max_batch][Hkv] arrival counters of the attention splits (zero between phases), or null:
-                         // then the splits are merged by phase_attn_merge
+    int *attn_ticket;    // [max_batch][Hkv] arrival counters of the attention splits (zero between phases): the
+                         // workgroup that finishes last merges the splits
     int b0, nb;          // sequences of this pass
     int bg_rg[6], bg_kp[6]; // row groups and reduction parts of the six matrix phases
     int bg_sep[6];          // 1: the phase's epilogue runs as a kernel of its own
@@ -814,7 +814,8 @@ __device__ __forceinline__ void phase_qkv(const DraftParams &p, int step, int vb
 // every key/value they read.  A token's head vector is spread over HD/8 lanes (16 bytes each), so a wave-wide
 // load covers 64/(HD/8) consecutive tokens = 1 KiB of contiguous cache.  Each lane group keeps its own online
 // softmax state; the groups of all 8 waves are merged through LDS.  A sequence that fits one split is finished
-// here; otherwise the item leaves (sum of p*V, max, sum of p) per head in the workspace for phase_attn_merge.
+// here; otherwise the item leaves (sum of p*V, max, sum of p) per head in the workspace and the item of the same
+// (sequence, KV head) that finishes last merges them (merge_head).
 // At batch 1 the phase moves little data and is bound by its chain of dependent memory round trips, so the first
 // cache loads are issued before anything else and the rotary table costs no double-precision transcendental.
 template <int G, int HD>
@@ -1197,24 +1198,6 @@ __device__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char
         }
     }
     if (first_item) before_q();
-}
-
-// phase 3b: merge of the split partials, one wave per (sequence, query head) whose context spans several splits.
-template <int HD, bool COH = false>
-__device__ void phase_attn_merge(const DraftParams &p, int step, int vb, int nvb, char *smem) {
-    const int wave = threadIdx.x / kWave;
-    const int T = p.split_tokens, S = p.max_splits;
-    float *w = reinterpret_cast<float *>(smem) + (size_t)wave * S;
-    const int n_items = p.B * p.Hq;
-    for (int item = vb * kWaves + wave; item < n_items; item += nvb * kWaves) {
-        const int b = item / p.Hq, hq = item % p.Hq;
-        bool dead;
-        if (!attn_seq_state(p, b, step, dead)) continue;
-        const int Lb = dead ? 0 : p.kv_len[b];
-        const int nsplit = (Lb + step + 1 + T - 1) / T;
-        if (nsplit <= 1) continue; // finished by phase_attn
-        merge_head<HD, COH, COH>(p, b, hq, nsplit, w);
-    }
 }
 
 // ---------------------------------------------------------------------------------------------------
