@@ -229,7 +229,10 @@ float mtp_last_draft_ms(mtp_handle *h);
 
 /*
  * How mtp_draft_steps enqueues its work.
- *   0 (default) one launch per phase.  Up to four sequences: 7 or 8 launches per step plus one to publish the
+ *   2 (default) automatic: mode 1 for one sequence whose reduction lengths are all at least 512 (where it is the
+ *               faster one), mode 0 otherwise; if the device cannot take the cooperative launch at that moment
+ *               (it needs every compute unit), mode 0 for that call.
+ *   0           one launch per phase.  Up to four sequences: 7 or 8 launches per step plus one to publish the
  *               last draft id.  Five or more: the batched kernels (every weight read once per pass of up to 64
  *               sequences), one preparation launch per step, and one epilogue launch after each matrix phase whose
  *               reduction is split over workgroups.

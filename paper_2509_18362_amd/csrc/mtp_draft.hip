@@ -426,7 +426,7 @@ int32_t mtp_draft_init(mtp_handle **out, const mtp_config *cfg, const mtp_weight
     h->attn_fn = attn_kernel(cfg->n_q_heads / cfg->n_kv_heads, cfg->head_dim);
     h->fused_fn = fused_kernel(cfg->n_q_heads / cfg->n_kv_heads, cfg->head_dim);
     h->fused_rows_fn = fused_rows_kernel(cfg->n_q_heads / cfg->n_kv_heads, cfg->head_dim);
-    h->mode = 0;
+    h->mode = 2;
     h->bar_epochs = 0;
     h->fused_grid = 0;
     h->trace = nullptr;
@@ -620,8 +620,7 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
                  lds_d2 = gemv_lds_bytes(p.d, p.nb_d, 2), lds_q = gemv_lds_bytes(p.qd, p.nb_q, 1),
                  lds_down = gemv_lds_bytes(p.F, p.nb_down, 1),
                  lds_attn = std::max({attn_lds_bytes(p.Hq / p.Hkv, p.hd), attn_mfma_lds_bytes(p.Hq / p.Hkv, p.hd) + 64,
-                                      (size_t)kWaves * p.max_splits * 4 + 64}),
-                 lds_merge = (size_t)kWaves * p.max_splits * 4 + 64;
+                                      (size_t)kWaves * p.max_splits * 4 + 64}); // incl. the merge's strips
     const size_t lds_max = std::max({lds_proj, lds_d2, lds_q, lds_down, lds_attn});
     if (lds_max > h->lds_limit) return MTP_ERR_CONFIG;
 
@@ -633,14 +632,15 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
 
     const int tphase = h->timing >= 2 ? h->timing - 2 : -1;
     h->pev_used = 0;
-    if (h->mode == 1 && tphase < 0 && !ext && !seq_subset) {
+    // one sequence and every reduction at least 512 long: the single launch has the row-streaming core (which keeps no id
+    // strip in LDS) and is the faster way; mode 2 picks it there and nowhere else
+    const bool rows = B == 1 && p.d >= 512 && p.qd >= 512 && p.F >= 512;
+    if ((h->mode == 1 || (h->mode == 2 && rows)) && tphase < 0 && !ext && !seq_subset) {
         // single launch: all B sequences are staged together and every workgroup must be resident at once (one
         // per CU; the cooperative launch checks it).  Falls back to one launch per phase when LDS cannot hold B.
         const int fgrid = std::min(h->num_cus, kMaxFusedGrid);
-        size_t region = std::max({fused_gemv_region(p.d, p.qd, p.F, B), lds_attn, lds_merge});
+        size_t region = std::max(fused_gemv_region(p.d, p.qd, p.F, B), lds_attn);
         region = (region + 255) / 256 * 256;
-        // one sequence and every reduction at least 512 long: the row-streaming core, which keeps no id strip in LDS
-        const bool rows = B == 1 && p.d >= 512 && p.qd >= 512 && p.F >= 512;
         const size_t ids_bytes = rows ? 0 : ((size_t)(p.n + fgrid - 1) / fgrid * 4 + 255) / 256 * 256;
         const size_t lds_fused = region + ids_bytes + 256;
         if (B <= 16 && lds_fused <= h->lds_limit) {
@@ -655,17 +655,20 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
             }
             void *args[] = {(void *)&p};
             if (h->timing == 1) (void)hipEventRecord(h->ev[0], st);
-            if (hipLaunchCooperativeKernel((const void *)(rows ? h->fused_rows_fn : h->fused_fn), dim3(fgrid), dim3(kBlock), args,
-                                           (unsigned)lds_fused, st) != hipSuccess) {
-                (void)hipGetLastError();
-                return MTP_ERR_HIP;
+            const bool launched =
+                hipLaunchCooperativeKernel((const void *)(rows ? h->fused_rows_fn : h->fused_fn), dim3(fgrid),
+                                           dim3(kBlock), args, (unsigned)lds_fused, st) == hipSuccess;
+            if (launched) {
+                h->bar_epochs += (unsigned long long)K * kBarriersPerStep;
+                if (h->timing == 1) {
+                    (void)hipEventRecord(h->ev[1], st);
+                    h->ev_recorded = true;
+                }
+                return MTP_OK;
             }
-            h->bar_epochs += (unsigned long long)K * kBarriersPerStep;
-            if (h->timing == 1) {
-                (void)hipEventRecord(h->ev[1], st);
-                h->ev_recorded = true;
-            }
-            return MTP_OK;
+            (void)hipGetLastError();
+            if (h->mode == 1) return MTP_ERR_HIP; // asked for explicitly
+            // mode 2: the device could not take a cooperative launch right now (it needs every CU): one launch per phase
         }
     }
     auto mark_begin = [&](int phase, int step) {
@@ -713,7 +716,7 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
     // Five or more sequences: the batched kernels, every weight read once per pass of up to 64 sequences.  Their
     // buffer loads address a matrix with 32-bit offsets and mark missing rows with an offset of 2 GiB.
     const size_t widest = std::max({(size_t)p.V * p.d, (size_t)p.d * 2 * p.d, (size_t)p.F * p.d, (size_t)p.qd * p.d}) * 2;
-    if (B >= kBatchMinSeq && h->mode != 1 && widest < ((size_t)1 << 31)) {
+    if (B >= kBatchMinSeq && h->mode != 1 && widest < ((size_t)1 << 31)) { // (mode 1 beyond 16 sequences: see above)
         p.act[0] = reinterpret_cast<uint16_t *>(ws + l.act0);
         p.act[1] = reinterpret_cast<uint16_t *>(ws + l.act1);
         p.a_lo = l.a_lo;
@@ -991,7 +994,7 @@ int32_t mtp_set_timing(mtp_handle *h, int32_t mode) {
 
 int32_t mtp_set_launch_mode(mtp_handle *h, int32_t mode) {
     if (!h) return MTP_ERR_NULL;
-    if (mode != 0 && mode != 1) return MTP_ERR_MODE;
+    if (mode < 0 || mode > 2) return MTP_ERR_MODE;
     h->mode = mode;
     return MTP_OK;
 }

@@ -615,14 +615,21 @@ def test_7b_batch1_ctx2048(gpu, big):
     wl = synth.WORKLOADS["c2_7b_b1"]
     act = synth.make_activations(wl)
     subsets = synth.make_subsets(wl)
-    ref, res, caches = run_both(gpu, big["shape"], big["w"], big["dev"], act, subsets, 0, wl.draft_steps)
-    gap = check_chain(ref, res, caches, act["kv_len"], wl.draft_steps)
-    print("c2 max |dlogit| =", gap)
-    ref, res, caches = run_both(gpu, big["shape"], big["w"], big["dev"], act, subsets, 0, wl.draft_steps, forced=None)
-    check_chain(ref, res, caches, act["kv_len"], wl.draft_steps, aligned=False)
-    # the same through the single-launch path
     binding = gpu["binding"]
     eng = binding.DraftEngine(big["shape"], big["dev"], subsets, 1, act["kv_capacity"], wl.draft_steps)
+    assert binding.mtp_set_launch_mode(eng.handle, binding.LAUNCH_PER_PHASE) == 0   # one launch per phase
+    ref, res, caches = run_both(gpu, big["shape"], big["w"], big["dev"], act, subsets, 0, wl.draft_steps, engine=eng)
+    gap = check_chain(ref, res, caches, act["kv_len"], wl.draft_steps)
+    print("c2 max |dlogit| =", gap)
+    ref, res, caches = run_both(gpu, big["shape"], big["w"], big["dev"], act, subsets, 0, wl.draft_steps, forced=None,
+                                engine=eng)
+    check_chain(ref, res, caches, act["kv_len"], wl.draft_steps, aligned=False)
+    # the library's default (automatic: the single launch for this shape), free-running
+    assert binding.mtp_set_launch_mode(eng.handle, binding.LAUNCH_AUTO) == 0
+    ref, res, caches = run_both(gpu, big["shape"], big["w"], big["dev"], act, subsets, 0, wl.draft_steps, forced=None,
+                                engine=eng)
+    check_chain(ref, res, caches, act["kv_len"], wl.draft_steps, aligned=False)
+    # the same through the single-launch path, asked for explicitly
     assert binding.mtp_set_launch_mode(eng.handle, binding.LAUNCH_SINGLE) == 0
     ref, res, caches = run_both(gpu, big["shape"], big["w"], big["dev"], act, subsets, 0, wl.draft_steps, engine=eng)
     check_chain(ref, res, caches, act["kv_len"], wl.draft_steps)
