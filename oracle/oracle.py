@@ -266,6 +266,56 @@ class Oracle:
                 "overflow": rc == 1}
 
 
+def loss_weights(K: int, beta: float) -> np.ndarray:
+    """Eq. (2): alpha_k = beta^(k-1) / sum_j beta^(j-1), k = 1..K."""
+    w = np.power(float(beta), np.arange(K, dtype=np.float64))
+    return w / w.sum()
+
+
+def train_loss(orc: "Oracle", hidden_in_bits, tokens, K: int, beta: float):
+    """Teacher-forced K-step forward of the shared head over all positions of one sequence and the weighted
+    cross-entropy of Eq. (1) (Sec. 2.1 "Training Mechanism" / "Training Objective"), forward only.
+      hidden_in_bits [n_pos][d] bf16: the main model's hidden states h_1 .. h_n (positions i = 1 .. n = T - K)
+      tokens [n_pos + K + 1]: t_1 .. t_{n+K+1}
+    Step k at position i consumes (h^{k-1}_i, embedding of t_{i+k}) and is scored against t_{i+k+1}; h^0 is the main
+    model's state, h^k the head's own output; inside a step a position attends the step's own keys of positions <= i
+    (a fresh cache per step, slot = position index; rotary attention only sees position differences).  CE_k is the
+    mean over the n positions of logsumexp(z) - z[label] over the FULL vocabulary, in float64 from the step's logits.
+    Returns dict(ce [K], loss, alpha [K], logits [K][n][V], hidden [K][n][d])."""
+    s = orc.shape
+    hid = _u16(hidden_in_bits)
+    n = hid.shape[0]
+    tok = _i32(tokens)
+    assert tok.shape == (n + K + 1,)
+    cap = orc.cfg.kv_capacity
+    assert n <= cap
+    h = bf16_to_real(hid, orc.real)
+    ce = np.zeros(K)
+    all_logits, all_hidden = [], []
+    for k in range(1, K + 1):
+        kc = np.zeros((s.n_kv_heads, cap, s.head_dim), dtype=np.uint16)
+        vc = np.zeros_like(kc)
+        logits = np.empty((n, s.vocab_size), dtype=orc.real)
+        nxt = np.empty((n, s.d_model), dtype=orc.real)
+        for i in range(n):                       # position i + 1 of the text
+            r = orc.step(h[i], int(tok[i + k]), kc, vc, i, None)
+            logits[i], nxt[i] = r["logits"], r["hhat"]
+        z = logits.astype(np.float64)
+        m = z.max(axis=1)
+        lse = m + np.log(np.exp(z - m[:, None]).sum(axis=1))
+        ce[k - 1] = float((lse - z[np.arange(n), tok[k + 1:k + 1 + n]]).mean())
+        all_logits.append(logits)
+        all_hidden.append(nxt)
+        h = nxt
+    alpha = loss_weights(K, beta)
+    return {"ce": ce, "loss": float((alpha * ce).sum()), "alpha": alpha, "logits": np.array(all_logits),
+            "hidden": np.array(all_hidden)}
+
+
+def bf16_to_real(bits: np.ndarray, real) -> np.ndarray:
+    return (np.ascontiguousarray(bits, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32).astype(real)
+
+
 def build_subset(tokens, vocab_size: int, n: int):
     """The high-frequency id list of Sec. 2.2 from a token stream ("identified through corpus-level statistics"):
     occurrence counts per id, the n ids with the largest counts (equal counts: the lower id first), returned in

@@ -124,6 +124,12 @@ __global__ void k_set_lists(ListGroups g, int *seq_list, const int **list_ids, i
     }
 }
 
+// a fill kernel instead of a memset node: calls that a caller may capture into a HIP graph record no hipMemsetAsync
+__global__ void k_zero_words(unsigned long long *dst, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = 0ull;
+}
+
 typedef void (*phase_kernel_t)(DraftParams, int);
 
 phase_kernel_t attn_kernel(int G, int HD) {
@@ -648,7 +654,8 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
             p.fused_gemv_bytes = (int)region;
             p.fused_ids_bytes = (int)ids_bytes;
             if (h->fused_grid != fgrid) { // first use, or the grid changed: restart the barrier counters
-                if (hipMemsetAsync(ws + l.bar, 0, kBarWords * 8, st) != hipSuccess) return MTP_ERR_HIP;
+                hipLaunchKernelGGL(k_zero_words, dim3(((int)kBarWords + 255) / 256), dim3(256), 0, st,
+                                   reinterpret_cast<unsigned long long *>(ws + l.bar), (int)kBarWords);
                 h->bar_epochs = 0;
                 h->fused_grid = fgrid;
                 p.bar_base = 0;
@@ -972,6 +979,10 @@ int32_t mtp_poll_error(mtp_handle *h, void *hip_stream) {
         if (hipMemsetAsync(dev, 0, 4, st) != hipSuccess) return MTP_ERR_HIP;
         if (word & kErrBarrierTimeout) { // the barrier counter is out of step with the host's mirror: restart both
             if (hipMemsetAsync(h->ws + h->lay.bar, 0, 8, st) != hipSuccess) return MTP_ERR_HIP;
+            // a kernel that gave up may have left arrival counters of the attention splits behind
+            if (hipMemsetAsync(h->ws + h->lay.attn_ticket, 0, (size_t)h->cfg.max_batch * h->cfg.n_kv_heads * 4, st) !=
+                hipSuccess)
+                return MTP_ERR_HIP;
             h->bar_epochs = 0;
     h->fused_grid = 0;
         }

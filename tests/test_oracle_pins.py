@@ -608,6 +608,66 @@ def test_token_stream_is_long_tailed_and_list_covers_it():
     assert orc_mod.build_subset(s2, V, 10)["invalid"] == 100
 
 
+# ---------------------------------------------------------------- teacher-forced K-step forward and its loss
+def test_loss_weights_eq2():
+    """Eq. (2) with the paper's decay 0.6 and depth 3 (Sec. 3.1): 1 : 0.6 : 0.36 normalised."""
+    a = orc_mod.loss_weights(3, 0.6)
+    np.testing.assert_allclose(a, np.array([1.0, 0.6, 0.36]) / 1.96, rtol=1e-15)
+    assert abs(a.sum() - 1.0) < 1e-15 and abs(a[1] / a[0] - 0.6) < 1e-15
+    np.testing.assert_allclose(orc_mod.loss_weights(1, 0.3), [1.0])
+    np.testing.assert_allclose(orc_mod.loss_weights(4, 1.0), [0.25] * 4)
+
+
+def test_train_loss_against_library_cross_entropy_and_hand_fed_steps(orc, tiny):
+    """The K-step teacher-forced forward: (1) step 1 is the block-of-positions routine from an empty cache, and its
+    loss is torch's cross_entropy of those logits against t_{i+2}; (2) step 2 at every position is a single step
+    fed by hand with the step-1 output of the SAME position and t_{i+2}, attending only step-2 keys, scored
+    against t_{i+3}; (3) the total is the Eq. (2) mix.  Shifting any label or input token by one breaks (1) or (2)."""
+    s, act = tiny["shape"], tiny["act"]
+    n, K, beta = 6, 3, 0.6
+    rng = np.random.default_rng(21)
+    hid = rand_bits(rng, (n, s.d_model), std=float(synth.bf16_bits_to_f32(act["hidden_in"]).std()))
+    tok = rng.integers(0, s.vocab_size, size=n + K + 1).astype(np.int32)
+    res = orc_mod.train_loss(orc, hid, tok, K, beta)
+    cap = act["kv_capacity"]
+    zero = lambda: (np.zeros((1, s.n_kv_heads, cap, s.head_dim), np.uint16), np.zeros((1, s.n_kv_heads, cap, s.head_dim), np.uint16))
+    # (1)
+    kc, vc = zero()
+    ex = orc.extend(hid[:, None], tok[1:1 + n, None], np.array([n], np.int32), kc, vc, np.zeros(1, np.int32), None)
+    np.testing.assert_array_equal(res["logits"][0], ex["logits"][:, 0])
+    ce1 = F.cross_entropy(torch.from_numpy(ex["logits"][:, 0].astype(np.float64)), torch.from_numpy(tok[2:2 + n]).long())
+    assert abs(res["ce"][0] - float(ce1)) < 1e-12
+    # (2)
+    kc2, vc2 = zero()
+    for i in range(n):
+        r = orc.step(ex["hidden"][i, 0], int(tok[i + 2]), kc2[0], vc2[0], i, None)
+        np.testing.assert_array_equal(res["logits"][1][i], r["logits"])
+    ce2 = F.cross_entropy(torch.from_numpy(res["logits"][1].astype(np.float64)), torch.from_numpy(tok[3:3 + n]).long())
+    assert abs(res["ce"][1] - float(ce2)) < 1e-12
+    ce3 = F.cross_entropy(torch.from_numpy(res["logits"][2].astype(np.float64)), torch.from_numpy(tok[4:4 + n]).long())
+    # (3)
+    want = (1.0 * float(ce1) + 0.6 * float(ce2) + 0.36 * float(ce3)) / 1.96
+    assert abs(res["loss"] - want) < 1e-12
+    # a label off by one is a different number altogether
+    wrong = F.cross_entropy(torch.from_numpy(ex["logits"][:, 0].astype(np.float64)), torch.from_numpy(tok[1:1 + n]).long())
+    assert abs(float(wrong) - res["ce"][0]) > 1e-3
+
+
+def test_train_loss_uniform_head_is_log_vocab(tiny):
+    """With every row of the output head equal, all logits of a position are equal and each CE_k is ln |V| exactly,
+    whatever the rest of the head computes: the loss is ln |V| for any beta."""
+    s = tiny["shape"]
+    w = dict(tiny["w"])
+    w["lm_head"] = np.tile(tiny["w"]["lm_head"][:1], (s.vocab_size, 1))
+    o = Oracle(s, w, tiny["act"]["kv_capacity"], "f64")
+    rng = np.random.default_rng(22)
+    hid = rand_bits(rng, (4, s.d_model))
+    tok = rng.integers(0, s.vocab_size, size=4 + 2 + 1).astype(np.int32)
+    res = orc_mod.train_loss(o, hid, tok, 2, 0.6)
+    np.testing.assert_allclose(res["ce"], math.log(s.vocab_size), rtol=1e-12)
+    assert abs(res["loss"] - math.log(s.vocab_size)) < 1e-10
+
+
 def test_f32_oracle_within_rounding_of_f64(tiny):
     act, ids = tiny["act"], tiny["ids"]
     outs = {}
