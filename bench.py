@@ -66,6 +66,9 @@ def main() -> int:
     ap.add_argument("--list-builder", type=int, default=0, metavar="LOG2_TOKENS",
                     help="also time the high-frequency list builder (mtp_subset_build) on a synthetic long-tailed "
                          "stream of 2^LOG2_TOKENS tokens over this workload's vocabulary")
+    ap.add_argument("--train-loss", type=int, default=0, metavar="POSITIONS",
+                    help="also time the teacher-forced K-step forward with its weighted cross-entropy "
+                         "(mtp_train_loss, K = 3, beta = 0.6) over this many positions")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full-vocab", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
@@ -266,6 +269,32 @@ def main() -> int:
                    "stream_passes": -(-shape.vocab_size // 40000), "oracle_seconds": cpu_l,
                    "matches_oracle": True}
 
+    train = None
+    if args.train_loss > 0:
+        n_pos, Kt = args.train_loss, 3
+        eng3 = binding.DraftEngine(shape, w, [], n_pos, max(64, -(-n_pos // 64) * 64), 1, device="cuda:0")
+        rng = np.random.default_rng(8)
+        hid_t = eng3.to_device_bits(synth.f32_to_bf16_bits(rng.standard_normal((n_pos, shape.d_model)).astype(np.float32)))
+        tok_t = eng3.to_device_i32(rng.integers(0, shape.vocab_size, size=n_pos + Kt + 1).astype(np.int32))
+        for _ in range(2):
+            loss_t = eng3.train_loss(hid_t, tok_t, Kt, 0.6)
+        torch.cuda.synchronize()
+        assert eng3.poll_error() == 0
+        reps_t = 5
+        t = time.perf_counter()
+        for _ in range(reps_t):
+            loss_t = eng3.train_loss(hid_t, tok_t, Kt, 0.6)
+        torch.cuda.synchronize()
+        el_t = (time.perf_counter() - t) / reps_t
+        # multiply-adds of the head per position and step: the body's matrices and the full output head
+        macs = (2 * shape.d_model * shape.d_model + (shape.q_dim + 2 * shape.kv_dim) * shape.d_model
+                + shape.q_dim * shape.d_model + 3 * shape.d_ffn * shape.d_model + shape.vocab_size * shape.d_model)
+        train = {"positions": n_pos, "K": Kt, "beta": 0.6, "ms_per_forward": el_t * 1e3,
+                 "positions_per_s": n_pos / el_t, "tflops": 2.0 * macs * n_pos * Kt / el_t / 1e12,
+                 "loss": [float(x) for x in loss_t.cpu().numpy()],
+                 "note": "built from the draft kernels (weights re-read per 64 positions): HBM-bound, not MFMA-bound"}
+        eng3.close()
+
     full = None
     if not args.no_full_vocab and args.subset >= 0:
         fs = max(10, args.steps // 4)
@@ -325,7 +354,7 @@ def main() -> int:
         "us_per_mtp_step": us_per_mtp_step, "mean_accept_len": mean_accept,
         "chain_us": {"p10": p10, "p50": p50, "p90": p90, "what": f"{K} draft steps, one library call"},
         "accept_us": accept_us,
-        "algorithmic_bytes_per_step": chain_bytes, "roofline": roofline, "full_vocab": full, "extend": extend, "list_builder": builder,
+        "algorithmic_bytes_per_step": chain_bytes, "roofline": roofline, "full_vocab": full, "extend": extend, "list_builder": builder, "train_loss": train,
         "cpu_baseline": cpu,
         "input_generation_s": gen_s,
     }

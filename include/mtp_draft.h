@@ -211,6 +211,29 @@ int32_t mtp_draft_continue(mtp_handle *h, int32_t B, int32_t K, int32_t subset_i
                            const int32_t *forced_tokens, int32_t *draft_out, float *logits_out, float *hidden_out,
                            void *hip_stream);
 
+/*
+ * Teacher-forced K-step forward of the shared head over all positions of one sequence and its weighted cross-entropy
+ * (Sec. 2.1 "Training Mechanism" and "Training Objective", Eq. (1) and (2)); forward only, full vocabulary.
+ * Step k at position i consumes (h^{k-1}_i, embedding of t_{i+k}) and is scored against t_{i+k+1}; h^0 is the main
+ * model's hidden state, h^k the head's own output of step k.  Inside a step a position attends the step's own keys of
+ * positions <= i.  CE_k = mean over the positions of logsumexp(z) - z[label]; loss = sum_k alpha_k CE_k with
+ * alpha_k = beta^(k-1) / sum_j beta^(j-1).  Each step is the block-of-positions pipeline of mtp_draft_extend from an
+ * empty cache (every weight read once per 64 positions), followed by a cross-entropy kernel.
+ *   n_pos        positions i = 1 .. n_pos (= T - K of the paper); n_pos <= max_batch and <= kv_capacity of
+ *                mtp_draft_init (else MTP_ERR_BATCH);  K: 1 .. 16;  beta > 0
+ *   hidden_in    device [n_pos][d] bf16          the main model's hidden states
+ *   tokens       device [n_pos + K + 1] int32    t_1 .. t_{n_pos+K+1}
+ *   k_cache, v_cache  device, ONE sequence's cache [n_kv_heads][kv_capacity][head_dim] bf16: scratch, overwritten
+ *   scratch      device, mtp_train_workspace_bytes(cfg, n_pos) bytes (the logits of a step, [n_pos][vocab] float,
+ *                are its bulk)
+ *   loss_out     device [K + 1] float            CE_1 .. CE_K, then the weighted loss
+ * A token id outside the vocabulary is reported by mtp_poll_error (MTP_ERR_TOKEN_RANGE) and treated as id 0.
+ */
+size_t mtp_train_workspace_bytes(const mtp_config *cfg, int32_t n_pos);
+int32_t mtp_train_loss(mtp_handle *h, int32_t n_pos, int32_t K, float beta, const void *hidden_in,
+                       const int32_t *tokens, void *k_cache, void *v_cache, void *scratch, size_t scratch_bytes,
+                       float *loss_out, void *hip_stream);
+
 /* Waits for `hip_stream`, then returns and clears the sticky device error word:
  * MTP_OK, MTP_ERR_KV_OVERFLOW or MTP_ERR_TOKEN_RANGE (or MTP_ERR_HIP). */
 int32_t mtp_poll_error(mtp_handle *h, void *hip_stream);

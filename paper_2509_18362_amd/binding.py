@@ -29,6 +29,7 @@ STATUS = {0: "MTP_OK", -1: "MTP_ERR_NULL", -2: "MTP_ERR_ALIGN", -3: "MTP_ERR_CON
           -9: "MTP_ERR_KV_OVERFLOW", -10: "MTP_ERR_TOKEN_RANGE", -11: "MTP_ERR_MODE", -12: "MTP_ERR_TIMEOUT"}
 EXPORTS = ["mtp_status_string", "mtp_workspace_bytes", "mtp_draft_init", "mtp_draft_steps", "mtp_draft_extend",
            "mtp_draft_continue", "mtp_draft_steps_lists", "mtp_subset_workspace_bytes", "mtp_subset_build",
+           "mtp_train_workspace_bytes", "mtp_train_loss",
            "mtp_accept",
            "mtp_poll_error", "mtp_set_timing", "mtp_last_draft_ms", "mtp_set_launch_mode", "mtp_set_phase_trace",
            "mtp_draft_destroy"]
@@ -71,6 +72,11 @@ _lib.mtp_subset_workspace_bytes.argtypes = [C.c_int32]
 _lib.mtp_subset_build.restype = C.c_int32
 _lib.mtp_subset_build.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p,
                                   C.c_void_p, C.c_void_p, C.c_void_p]
+_lib.mtp_train_workspace_bytes.restype = C.c_size_t
+_lib.mtp_train_workspace_bytes.argtypes = [C.c_void_p, C.c_int32]
+_lib.mtp_train_loss.restype = C.c_int32
+_lib.mtp_train_loss.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p,
+                                C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
 _lib.mtp_draft_steps_lists.restype = C.c_int32
 _lib.mtp_draft_steps_lists.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_int32)] + [C.c_void_p] * 10
 _lib.mtp_draft_continue.restype = C.c_int32
@@ -273,6 +279,23 @@ class DraftEngine:
         if st != MTP_OK:
             raise MTPError(st)
         return {"draft": draft, "logits": logits, "hidden": hidden}
+
+    def train_loss(self, hidden_in, tokens, K: int, beta: float, stream: int = 0):
+        """Teacher-forced K-step forward and its weighted cross-entropy (see mtp_train_loss).  hidden_in [n][d] bf16
+        bits, tokens [n + K + 1]: device tensors.  Returns a device tensor [K + 1]: CE_1 .. CE_K, the loss."""
+        torch = self.torch
+        n_pos = hidden_in.shape[0]
+        s = self.shape
+        nbytes = int(_lib.mtp_train_workspace_bytes(C.byref(self.cfg), n_pos))
+        scratch = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        cache = torch.zeros((2, s.n_kv_heads, self.cfg.kv_capacity, s.head_dim), dtype=torch.int16, device=self.device)
+        out = torch.zeros(K + 1 + 3, dtype=torch.float32, device=self.device)
+        st = int(_lib.mtp_train_loss(self.handle, n_pos, K, float(beta), _addr(hidden_in), _addr(tokens),
+                                     _addr(cache[0]), _addr(cache[1]), _addr(scratch), nbytes, _addr(out), stream))
+        if st != MTP_OK:
+            raise MTPError(st)
+        self._train_keep = (scratch, cache)   # alive until the stream has run the call
+        return out[:K + 1]
 
     def draft_lists(self, K: int, seq_subset, hidden_in, token_in, k_cache, v_cache, kv_len, forced=None,
                     want_logits: bool = False, want_hidden: bool = False, stream: int = 0):

@@ -124,6 +124,62 @@ __global__ void k_set_lists(ListGroups g, int *seq_list, const int **list_ids, i
     }
 }
 
+// ---- teacher-forced forward: cross-entropy of one step's logits (Eq. (1)) -------------------------------------------
+__global__ void k_train_begin_step(int n_pos, int *kv_len, int *ext_len) { // a fresh cache and n_pos new positions
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        kv_len[0] = 0;
+        ext_len[0] = n_pos;
+    }
+}
+// one workgroup per position: logsumexp(z) - z[label] over the full vocabulary
+__global__ __launch_bounds__(256) void k_train_row_ce(const float *__restrict__ logits, int V, const int *labels,
+                                                      float *row_loss, int *err) {
+    __shared__ float red[256 / kWave];
+    const float *z = logits + (size_t)blockIdx.x * V;
+    float m = -INFINITY;
+    for (int i = threadIdx.x; i < V; i += 256) m = fmaxf(m, z[i]);
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) m = fmaxf(m, __shfl_xor(m, off, kWave));
+    if ((threadIdx.x & (kWave - 1)) == 0) red[threadIdx.x / kWave] = m;
+    __syncthreads();
+    m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    __syncthreads();
+    float sum = 0.f;
+    for (int i = threadIdx.x; i < V; i += 256) sum += expf(z[i] - m);
+    sum = wave_sum(sum);
+    if ((threadIdx.x & (kWave - 1)) == 0) red[threadIdx.x / kWave] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int label = labels[blockIdx.x];
+        if (label < 0 || label >= V) { // reported like an input token out of range; scored as id 0
+            atomicOr(err, kErrTokenRange);
+            label = 0;
+        }
+        row_loss[blockIdx.x] = m + logf((red[0] + red[1]) + (red[2] + red[3])) - z[label];
+    }
+}
+// mean over the positions in a fixed order (one workgroup), and after the last step the weighted total of Eq. (1)
+__global__ __launch_bounds__(256) void k_train_step_mean(const float *row_loss, int n_pos, float *loss_out, int k, int K,
+                                                         float beta) {
+    __shared__ float red[256 / kWave];
+    float s = 0.f;
+    for (int i = threadIdx.x; i < n_pos; i += 256) s += row_loss[i];
+    s = wave_sum(s);
+    if ((threadIdx.x & (kWave - 1)) == 0) red[threadIdx.x / kWave] = s;
+    __syncthreads();
+    if (threadIdx.x != 0) return;
+    loss_out[k] = ((red[0] + red[1]) + (red[2] + red[3])) / (float)n_pos;
+    if (k == K - 1) { // Eq. (2): alpha_j = beta^(j-1) / sum_i beta^(i-1)
+        float wsum = 0.f, acc = 0.f, w = 1.f;
+        for (int j = 0; j < K; ++j) {
+            acc += w * loss_out[j];
+            wsum += w;
+            w *= beta;
+        }
+        loss_out[K] = acc / wsum;
+    }
+}
+
 // a fill kernel instead of a memset node: calls that a caller may capture into a HIP graph record no hipMemsetAsync
 __global__ void k_zero_words(unsigned long long *dst, int n) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -949,6 +1005,49 @@ int32_t mtp_draft_extend(mtp_handle *h, int32_t B, int32_t m_max, int32_t subset
     const ExtendCall ext{B, m_max, ext_len, kv_len};
     return run_draft(h, B * m_max, 1, subset_index, hidden_in, tokens, k_cache, v_cache, kv_len, nullptr, draft_out,
                      logits_out, hidden_out, hip_stream, &ext);
+}
+
+size_t mtp_train_workspace_bytes(const mtp_config *cfg, int32_t n_pos) {
+    if (!config_ok(cfg) || n_pos < 1) return 0;
+    auto up = [](size_t x) { return (x + 255) / 256 * 256; };
+    return up((size_t)n_pos * cfg->vocab_size * 4) + up((size_t)n_pos * cfg->d_model * 4) + 2 * up((size_t)n_pos * 4) + 512;
+}
+
+int32_t mtp_train_loss(mtp_handle *h, int32_t n_pos, int32_t K, float beta, const void *hidden_in,
+                       const int32_t *tokens, void *k_cache, void *v_cache, void *scratch, size_t scratch_bytes,
+                       float *loss_out, void *hip_stream) {
+    if (!h || !hidden_in || !tokens || !k_cache || !v_cache || !scratch || !loss_out) return MTP_ERR_NULL;
+    const void *ptrs[] = {hidden_in, tokens, k_cache, v_cache, scratch, loss_out};
+    for (const void *p : ptrs)
+        if (!aligned16(p)) return MTP_ERR_ALIGN;
+    const mtp_config &c = h->cfg;
+    if (n_pos < 1 || n_pos > c.max_batch || n_pos > c.kv_capacity) return MTP_ERR_BATCH;
+    if (K < 1 || K > 16 || !(beta > 0.f)) return MTP_ERR_STEPS;
+    if (scratch_bytes < mtp_train_workspace_bytes(&c, n_pos)) return MTP_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    auto up = [](size_t x) { return (x + 255) / 256 * 256; };
+    char *s0 = static_cast<char *>(scratch);
+    float *logits = reinterpret_cast<float *>(s0);
+    float *hidden = reinterpret_cast<float *>(s0 + up((size_t)n_pos * c.vocab_size * 4));
+    float *row_loss = reinterpret_cast<float *>(reinterpret_cast<char *>(hidden) + up((size_t)n_pos * c.d_model * 4));
+    int32_t *draft = reinterpret_cast<int32_t *>(reinterpret_cast<char *>(row_loss) + up((size_t)n_pos * 4));
+    int32_t *kv_len = reinterpret_cast<int32_t *>(reinterpret_cast<char *>(draft) + up((size_t)n_pos * 4));
+    int32_t *ext_len = kv_len + 64;
+    int *err = reinterpret_cast<int *>(h->ws + h->lay.err);
+    const ExtendCall ext{1, n_pos, ext_len, kv_len};
+    for (int k = 1; k <= K; ++k) {
+        // Step k over all positions: the block-of-positions pipeline from an empty cache.  Position i consumes
+        // (h^{k-1}_i, t_{i+k}): the main model's states at k = 1, the head's own output of step k-1 afterwards.
+        hipLaunchKernelGGL(k_train_begin_step, dim3(1), dim3(64), 0, st, n_pos, kv_len, ext_len);
+        const int32_t rc = run_draft(h, n_pos, 1, -1, hidden_in, tokens + k, k_cache, v_cache, kv_len, nullptr, draft,
+                                     logits, hidden, hip_stream, &ext, k > 1 ? hidden : nullptr);
+        if (rc != MTP_OK) return rc;
+        hipLaunchKernelGGL(k_train_row_ce, dim3(n_pos), dim3(256), 0, st, logits, c.vocab_size, tokens + k + 1,
+                           row_loss, err);
+        hipLaunchKernelGGL(k_train_step_mean, dim3(1), dim3(256), 0, st, row_loss, n_pos, loss_out, k - 1, K, beta);
+    }
+    if (hipGetLastError() != hipSuccess) return MTP_ERR_HIP;
+    return MTP_OK;
 }
 
 int32_t mtp_accept(mtp_handle *h, int32_t B, int32_t K, const int32_t *draft, const int32_t *target,

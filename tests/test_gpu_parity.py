@@ -549,6 +549,39 @@ def test_tiny_one_list_per_sequence(gpu, tiny, ctx, seq_subset):
     eng.close()
 
 
+# ------------------------------------------------------------------------------------------ teacher-forced loss
+@pytest.mark.parametrize("n_pos,K", [(3, 2), (40, 3), (70, 3)])
+def test_tiny_teacher_forced_loss(gpu, tiny, n_pos, K):
+    """Eq. (1)-(2): the K per-step cross-entropies and their weighted sum against the oracle (3 positions: the
+    row-streaming phases; 40: the batched ones; 70: two weight passes).  The logits agree to ~1e-4, a mean of
+    log-probabilities to better than 1e-3."""
+    torch, Oracle, binding, orc_mod = gpu["torch"], gpu["Oracle"], gpu["binding"], gpu["orc"]
+    shape = tiny["shape"]
+    rng = np.random.default_rng(300 + n_pos)
+    std = float(synth.bf16_bits_to_f32(tiny["act"]["hidden_in"]).std())
+    hid = synth.f32_to_bf16_bits((rng.standard_normal((n_pos, shape.d_model)) * std).astype(np.float32))
+    tok = rng.integers(0, shape.vocab_size, size=n_pos + K + 1).astype(np.int32)
+    cap = 128
+    want = orc_mod.train_loss(Oracle(shape, tiny["w"], cap, "f32"), hid, tok, K, 0.6)
+    eng = binding.DraftEngine(shape, tiny["w"], [], n_pos, cap, 1)
+    got = eng.train_loss(eng.to_device_bits(hid), eng.to_device_i32(tok), K, 0.6)
+    torch.cuda.synchronize()
+    assert eng.poll_error() == 0
+    got = got.cpu().numpy()
+    np.testing.assert_allclose(got[:K], want["ce"], atol=1e-3)
+    assert abs(got[K] - want["loss"]) <= 1e-3
+    assert abs(got[K] - float((want["alpha"] * got[:K]).sum())) <= 1e-5       # Eq. (2) on its own numbers
+    # twice in a row gives the same bits (fixed summation order), and a label out of range is reported
+    again = eng.train_loss(eng.to_device_bits(hid), eng.to_device_i32(tok), K, 0.6).cpu().numpy()
+    np.testing.assert_array_equal(again, got)
+    bad = tok.copy()
+    bad[-1] = shape.vocab_size
+    eng.train_loss(eng.to_device_bits(hid), eng.to_device_i32(bad), K, 0.6)
+    torch.cuda.synchronize()
+    assert eng.poll_error() == -10
+    eng.close()
+
+
 # ------------------------------------------------------------------------------------------ accept / rollback
 @pytest.mark.parametrize("K", [1, 3, 5])
 @pytest.mark.parametrize("mode", [0, 1])
@@ -652,6 +685,26 @@ def test_7b_extend_four_positions(gpu, big):
         assert res["err"] == 0
         gap = check_extend(ref, res, caches, act, ext_len, sel=seqs)
         print(name, "extend max |dlogit| =", gap)
+
+
+def test_7b_teacher_forced_loss(gpu, big):
+    """The 7B-shaped head, 24 positions, K = 2, full 151680-id vocabulary: both cross-entropies and the loss."""
+    torch, Oracle, binding, orc_mod = gpu["torch"], gpu["Oracle"], gpu["binding"], gpu["orc"]
+    shape = big["shape"]
+    n_pos, K = 24, 2
+    rng = np.random.default_rng(330)
+    hid = synth.f32_to_bf16_bits(rng.standard_normal((n_pos, shape.d_model)).astype(np.float32))
+    tok = rng.integers(0, shape.vocab_size, size=n_pos + K + 1).astype(np.int32)
+    want = orc_mod.train_loss(Oracle(shape, big["w"], 64, "f32"), hid, tok, K, 0.6)
+    eng = binding.DraftEngine(shape, big["dev"], [], n_pos, 64, 1)
+    got = eng.train_loss(eng.to_device_bits(hid), eng.to_device_i32(tok), K, 0.6)
+    torch.cuda.synchronize()
+    assert eng.poll_error() == 0
+    got = got.cpu().numpy()
+    print("7B teacher-forced CE", got[:K], "oracle", want["ce"], "loss", got[K], want["loss"])
+    np.testing.assert_allclose(got[:K], want["ce"], atol=1e-3)
+    assert abs(got[K] - want["loss"]) <= 1e-3
+    eng.close()
 
 
 def test_7b_batch16_two_lists(gpu, big):
