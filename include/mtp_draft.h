@@ -160,7 +160,7 @@ int32_t mtp_accept(mtp_handle *h, int32_t B, int32_t K, const int32_t *draft, co
  * position and the token that follows it.  Position j of sequence b is written to cache slot kv_len[b] + j and attends
  * slots 0 .. kv_len[b] + j (causal inside the block).  The last position of a sequence yields its first draft token;
  * the others fill the head's KV cache, e.g. with the a + 1 tokens a verification has just confirmed, or a prompt.
- * Every weight is read once for all B * m_max (position, sequence) rows; the attention runs position by position.
+ * Every weight is read once for all B * m_max (position, sequence) rows, and one attention launch serves all rows.
  *
  *   B, m_max     sequences and positions per sequence; B * m_max <= max_batch of mtp_draft_init (else
  *                MTP_ERR_BATCH)

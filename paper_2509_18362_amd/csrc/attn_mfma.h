@@ -59,18 +59,19 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
     bool first_item = true;
     for (int item = vb; item < n_items; item += nvb) {
         const int b = item / (p.Hkv * S), rem = item % (p.Hkv * S), kvh = rem / S, sp = rem % S;
-        bool dead;
-        if (!attn_seq_state(p, b, step, dead)) continue; // uniform for the workgroup
+        const bool dead = seq_dead(p, b);
+        if (p.kv_appended && dead) continue; // a row that is not part of the block (uniform for the workgroup)
         const int Lb = dead ? 0 : p.kv_len[b];
         const int len = Lb + step + 1, pnew = len - 1;
         const int nsplit = (len + T - 1) / T;
         if (sp >= nsplit) continue; // uniform for the workgroup
         const int t0 = sp * T, t1 = min(t0 + T, len);
-        const bool last = (sp == nsplit - 1);
-        const int ntok = last ? (t1 - 1 - t0) : (t1 - t0); // slots read from the cache; the new token comes from qkv
-        const uint16_t *kc = p.k_cache + (((size_t)b * p.Hkv + kvh) * p.cap + t0) * HD;
-        const uint16_t *vc = p.v_cache + (((size_t)b * p.Hkv + kvh) * p.cap + t0) * HD;
-        const float *qkv = p.qkv + (size_t)(p.row0 + b) * p.qkv_dim;
+        const bool last = (sp == nsplit - 1) && !p.kv_appended; // as in phase_attn
+        const int ntok = last ? (t1 - 1 - t0) : (t1 - t0);      // slots read from the cache
+        const int cb = p.kv_appended ? b % p.ext_B : b;          // whose cache
+        const uint16_t *kc = p.k_cache + (((size_t)cb * p.Hkv + kvh) * p.cap + t0) * HD;
+        const uint16_t *vc = p.v_cache + (((size_t)cb * p.Hkv + kvh) * p.cap + t0) * HD;
+        const float *qkv = p.qkv + (size_t)b * p.qkv_dim;
         const int niter = (ntok + 31) / 32;
 
         u32x4 kn[2][NS], vr[NV];
@@ -298,11 +299,11 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
             int hq = kvh * G + g;
             if (nsplit == 1) {
                 const float r = A / Ls;
-                st_f32<COH>(p.attn + (size_t)(p.row0 + b) * p.qd + (size_t)hq * HD + dd, r);
+                st_f32<COH>(p.attn + (size_t)b * p.qd + (size_t)hq * HD + dd, r);
                 if (p.attn_split) {
                     uint16_t h, l;
                     split_bf16(r, h, l);
-                    const size_t at = (size_t)(p.row0 + b) * p.a_stride + (size_t)hq * HD + dd;
+                    const size_t at = (size_t)b * p.a_stride + (size_t)hq * HD + dd;
                     p.attn_split[at] = h;
                     p.attn_split[p.a_lo + at] = l;
                 }

@@ -98,6 +98,36 @@ __global__ void k_extend_prep(int B, int m_max, int cap, const int *kv_len, cons
     const bool bad = L < 0 || m < 0 || m > m_max || L + m > cap;
     row_len[r] = bad ? -1 : (j < m ? L + j : kRowInactive);
 }
+// A block of new positions: bias, rotary embedding and the bf16 cache append of EVERY row's key and value (the work the
+// attention's last split does for the one new position of an ordinary step), so that one attention launch can serve
+// all positions.  grid (rows, KV heads), HD/2 + HD threads: pairs of the key, then the elements of the value.
+template <int HD>
+__global__ void k_extend_append(DraftParams p) {
+    const int r = blockIdx.x, kvh = blockIdx.y, tid = threadIdx.x;
+    const int pos = p.kv_len[r]; // the row's own slot; negative: the row is not part of the block
+    if (pos < 0 || pos >= p.cap) return;
+    const int seq = r % p.ext_B;
+    const float *qkv = p.qkv + (size_t)r * p.qkv_dim;
+    const size_t slot = (((size_t)seq * p.Hkv + kvh) * p.cap + pos) * HD;
+    if (tid < HD / 2) {
+        const int e = tid;
+        const float *src = qkv + p.qd + (size_t)kvh * HD;
+        float a = src[e], bb = src[e + HD / 2], cs, sn;
+        if (p.b_k) {
+            a += bf16_to_f32(p.b_k[kvh * HD + e]);
+            bb += bf16_to_f32(p.b_k[kvh * HD + e + HD / 2]);
+        }
+        rope_cos_sin(pos, p.rope_inv[e], cs, sn);
+        p.k_cache[slot + e] = f32_to_bf16(a * cs - bb * sn);
+        p.k_cache[slot + e + HD / 2] = f32_to_bf16(bb * cs + a * sn);
+    } else if (tid < HD / 2 + HD) {
+        const int e = tid - HD / 2;
+        float v = qkv[p.qd + p.kvd + (size_t)kvh * HD + e];
+        if (p.b_v) v += bf16_to_f32(p.b_v[kvh * HD + e]);
+        p.v_cache[slot + e] = f32_to_bf16(v);
+    }
+}
+
 __global__ void k_extend_finish(int B, int m_max, int cap, int *kv_len, const int *ext_len) {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= B) return;
@@ -646,7 +676,7 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
             return MTP_ERR_HIP;
         p.own_hidden = 1;
     }
-    const int att_B = ext ? ext->B : B; // sequences an attention launch covers
+    const int att_B = B; // sequences (or rows of a block of positions) an attention launch covers
     p.split_tokens = split_tokens_for(c, att_B);
     p.max_splits = max_splits_for(c, att_B);
     if (ext) { // per-row cache lengths for the matrix phases
@@ -758,16 +788,16 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
             launch_attention_of(p, step);
             return;
         }
-        // a block of new positions: position j of every sequence, in order, each launch finding the entries of the
-        // positions before it in the cache
+        // a block of new positions: every row's key and value go into the cache first, then one launch serves all
+        // rows, each reading its sequence's cache up to and including its own slot (kv_len = the rows' lengths)
         DraftParams pa = p;
-        pa.B = ext->B;
-        pa.kv_len = ext->kv_len;
-        pa.ext_len = ext->ext_len;
-        for (int j = 0; j < ext->m_max; ++j) {
-            pa.row0 = j * ext->B;
-            launch_attention_of(pa, j);
-        }
+        pa.kv_appended = 1;
+        pa.ext_B = ext->B;
+        if (p.hd == 128)
+            hipLaunchKernelGGL(k_extend_append<128>, dim3(B, p.Hkv), dim3(192), 0, st, pa);
+        else
+            hipLaunchKernelGGL(k_extend_append<64>, dim3(B, p.Hkv), dim3(96), 0, st, pa);
+        launch_attention_of(pa, 0);
     };
     auto launch = [&](int phase, phase_kernel_t fn, int g, size_t lds, int step) {
         mark_begin(phase, step);

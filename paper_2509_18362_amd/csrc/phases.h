@@ -50,14 +50,13 @@ struct DraftParams {
     // launch plan
     int split_tokens, max_splits; // attention: tokens per split, splits per (sequence, KV head)
     int mfma_attn;                // the splits are long enough for the matrix-core attention
-    // Several new positions per sequence (first draft step over a block): the matrix phases see one row per
-    // (position, sequence), row = position * sequences + sequence, with a cache length per ROW in kv_len; the
-    // attention runs once per position over the real sequences, with B = their number, kv_len = their real lengths
-    // and:
     int own_hidden;               // step 1 of this call starts from hhat (fp32, put there by the host: the head's own
                                   // output of an earlier call) instead of hidden_in (bf16, the target model's)
-    int row0;                     // activation row of sequence 0 in this attention launch (position * sequences)
-    const int *ext_len;           // [B] new positions per sequence, or null: the ordinary one-position step
+    // Several new positions per sequence (first draft step over a block): every phase sees one row per (position,
+    // sequence), row = position * sequences + sequence, B = rows, with a cache length per ROW in kv_len.  A small
+    // kernel appends every row's key and value before the attention, which then runs once over all rows: a row's
+    // cache is that of sequence row % ext_B, and its own position is read from the cache like the others.
+    int kv_appended, ext_B;
     int nb_proj, nb_d, nb_q, nb_down; // sequences staged in LDS per pass, by reduction length (2d, d, Hq*hd, F)
     // batched path (five or more sequences): activations travel between the phases as bf16 hi + lo in global memory
     uint16_t *act[2];    // two [max_batch][a_stride] hi arrays, each followed (a_lo elements later) by its lo array
@@ -90,17 +89,6 @@ __device__ __forceinline__ bool seq_dead(const DraftParams &p, int b) {
 // dead because its cache cannot take the new entries (or its length is invalid): reported; an inactive row is not
 __device__ __forceinline__ bool seq_overflows(const DraftParams &p, int b) {
     return seq_dead(p, b) && p.kv_len[b] != kRowInactive;
-}
-// What an attention work item needs to know about its sequence: false = nothing to do (a position beyond the
-// sequence's new ones, or a block that does not fit the cache).  `dead` keeps its meaning for the one-position step.
-__device__ __forceinline__ bool attn_seq_state(const DraftParams &p, int b, int step, bool &dead) {
-    if (p.ext_len) {
-        const int L = p.kv_len[b], m = p.ext_len[b];
-        dead = false;
-        return step < m && L >= 0 && L + m <= p.cap;
-    }
-    dead = seq_dead(p, b);
-    return true;
 }
 
 // maximum of a 64-bit key over the workgroup; red64 holds kWaves words; contains two barriers
@@ -852,11 +840,11 @@ __device__ __forceinline__ void merge_head(const DraftParams &p, int b, int hq, 
     const int S = p.max_splits, PW = HD + 2;
     const float *src = p.attn_part + ((size_t)b * p.Hq + hq) * S * PW;
     auto store = [&](int dd, float r) {
-        st_f32<OCOH>(p.attn + (size_t)(p.row0 + b) * p.qd + (size_t)hq * HD + dd, r);
+        st_f32<OCOH>(p.attn + (size_t)b * p.qd + (size_t)hq * HD + dd, r);
         if (p.attn_split) {
             uint16_t h, l;
             split_bf16(r, h, l);
-            const size_t at = (size_t)(p.row0 + b) * p.a_stride + (size_t)hq * HD + dd;
+            const size_t at = (size_t)b * p.a_stride + (size_t)hq * HD + dd;
             p.attn_split[at] = h;
             p.attn_split[p.a_lo + at] = l;
         }
@@ -945,18 +933,21 @@ __device__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char
     bool first_item = true;
     for (int item = vb; item < n_items; item += nvb) {
         const int b = item / (p.Hkv * S), rem = item % (p.Hkv * S), kvh = rem / S, sp = rem % S;
-        bool dead;
-        if (!attn_seq_state(p, b, step, dead)) continue; // uniform for the workgroup
+        const bool dead = seq_dead(p, b);
+        if (p.kv_appended && dead) continue; // a row that is not part of the block (uniform for the workgroup)
         const int Lb = dead ? 0 : p.kv_len[b];
         const int len = Lb + step + 1, pnew = len - 1;
         const int nsplit = (len + T - 1) / T;
         if (sp >= nsplit) continue; // uniform for the workgroup
         const int t0 = sp * T, t1 = min(t0 + T, len);
-        const bool last = (sp == nsplit - 1);
-        const int ntok = last ? (t1 - 1 - t0) : (t1 - t0); // slots read from the cache; the new token comes from qkv
-        const uint16_t *kc = p.k_cache + ((size_t)b * p.Hkv + kvh) * p.cap * HD;
-        const uint16_t *vc = p.v_cache + ((size_t)b * p.Hkv + kvh) * p.cap * HD;
-        const float *qkv = p.qkv + (size_t)(p.row0 + b) * p.qkv_dim;
+        // `last`: this split appends the new position and scores it from the projection output; when every row's
+        // entry is in the cache already (kv_appended) no split does, and the new position is one more cached token
+        const bool last = (sp == nsplit - 1) && !p.kv_appended;
+        const int ntok = last ? (t1 - 1 - t0) : (t1 - t0); // slots read from the cache
+        const int cb = p.kv_appended ? b % p.ext_B : b;     // whose cache
+        const uint16_t *kc = p.k_cache + ((size_t)cb * p.Hkv + kvh) * p.cap * HD;
+        const uint16_t *vc = p.v_cache + ((size_t)cb * p.Hkv + kvh) * p.cap * HD;
+        const float *qkv = p.qkv + (size_t)b * p.qkv_dim;
         const int nblk = (ntok + TPI - 1) / TPI;
 
         u32x4 kr[U], vr[U];
@@ -1160,11 +1151,11 @@ __device__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char
             int hq = kvh * G + g;
             if (nsplit == 1) {
                 const float r = A / Ls;
-                st_f32<COH>(p.attn + (size_t)(p.row0 + b) * p.qd + (size_t)hq * HD + dd, r);
+                st_f32<COH>(p.attn + (size_t)b * p.qd + (size_t)hq * HD + dd, r);
                 if (p.attn_split) {
                     uint16_t h, l;
                     split_bf16(r, h, l);
-                    const size_t at = (size_t)(p.row0 + b) * p.a_stride + (size_t)hq * HD + dd;
+                    const size_t at = (size_t)b * p.a_stride + (size_t)hq * HD + dd;
                     p.attn_split[at] = h;
                     p.attn_split[p.a_lo + at] = l;
                 }
