@@ -48,6 +48,27 @@ def algorithmic_bytes_per_mtp_step(shape, n_rows: int, ctx, k_index: int, with_i
     return body + head + kv
 
 
+def device_state():
+    """Name, unit count and clocks of the GPU the figures were taken on (the clocks in force are read
+    from rocm-smi in a child process when that tool is present; the maxima come from the device properties)."""
+    import subprocess
+    import torch
+    prop = torch.cuda.get_device_properties(0)
+    dev = {"name": prop.name, "arch": getattr(prop, "gcnArchName", None), "compute_units": prop.multi_processor_count,
+           "hbm_gib": round(prop.total_memory / 2**30, 1),
+           "max_engine_mhz": getattr(prop, "clock_rate", 0) / 1e3 or None,
+           "max_memory_mhz": getattr(prop, "memory_clock_rate", 0) / 1e3 or None}
+    try:
+        out = subprocess.run(["rocm-smi", "-d", "0", "--showclocks", "--showperflevel", "--showpower", "--json"],
+                             capture_output=True, text=True, timeout=20).stdout
+        card = next(iter(json.loads(out).values()))
+        dev["rocm_smi"] = {k: v for k, v in card.items()
+                           if any(t in k.lower() for t in ("sclk", "mclk", "fclk", "performance", "power"))}
+    except Exception as e:   # the tool is optional: the bench line does not depend on it
+        dev["rocm_smi"] = f"unavailable ({type(e).__name__})"
+    return dev
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -357,6 +378,7 @@ def main() -> int:
         "algorithmic_bytes_per_step": chain_bytes, "roofline": roofline, "full_vocab": full, "extend": extend, "list_builder": builder, "train_loss": train,
         "cpu_baseline": cpu,
         "input_generation_s": gen_s,
+        "device": device_state(),
     }
     if args.k_sweep_target_ms > 0:
         from paper_2509_18362_amd import ksweep
