@@ -49,23 +49,26 @@ def algorithmic_bytes_per_mtp_step(shape, n_rows: int, ctx, k_index: int, with_i
 
 
 def device_state():
-    """Name, unit count and clocks of the GPU the figures were taken on (the clocks in force are read
-    from rocm-smi in a child process when that tool is present; the maxima come from the device properties)."""
-    import subprocess
+    """Name, unit count and, where the driver's sysfs files are readable, the engine and memory clock levels in force
+    after the timed region (files are read, no other program is started: the GPU is initialised by now)."""
+    import glob
     import torch
     prop = torch.cuda.get_device_properties(0)
     dev = {"name": prop.name, "arch": getattr(prop, "gcnArchName", None), "compute_units": prop.multi_processor_count,
-           "hbm_gib": round(prop.total_memory / 2**30, 1),
-           "max_engine_mhz": getattr(prop, "clock_rate", 0) / 1e3 or None,
-           "max_memory_mhz": getattr(prop, "memory_clock_rate", 0) / 1e3 or None}
-    try:
-        out = subprocess.run(["rocm-smi", "-d", "0", "--showclocks", "--showperflevel", "--showpower", "--json"],
-                             capture_output=True, text=True, timeout=20).stdout
-        card = next(iter(json.loads(out).values()))
-        dev["rocm_smi"] = {k: v for k, v in card.items()
-                           if any(t in k.lower() for t in ("sclk", "mclk", "fclk", "performance", "power"))}
-    except Exception as e:   # the tool is optional: the bench line does not depend on it
-        dev["rocm_smi"] = f"unavailable ({type(e).__name__})"
+           "hbm_gib": round(prop.total_memory / 2**30, 1)}
+    cards = []
+    for path in sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"))[:8]:
+        card = {"card": path.split("/")[4]}
+        for key, name in (("sclk", "pp_dpm_sclk"), ("mclk", "pp_dpm_mclk"), ("level", "power_dpm_force_performance_level")):
+            try:
+                with open(os.path.join(os.path.dirname(path), name)) as f:
+                    lines = [l.strip() for l in f if l.strip()]
+                starred = [l for l in lines if l.endswith("*")]
+                card[key] = (starred or lines)[0] if lines else None
+            except OSError:
+                card[key] = None
+        cards.append(card)
+    dev["clock_levels"] = cards or "not readable"
     return dev
 
 

@@ -27,18 +27,24 @@ namespace mtp {
 template <int G, int HD>
 struct AttnMfmaLds {
     static constexpr int VS = HD * 2 + 16;  // bytes per parked V row
+    static constexpr bool VREG = HD == 128;  // V goes from the load registers straight into the MFMA operand
     static constexpr int NSTREAM = kWaves + 1; // one softmax stream per wave, one for the token being appended
     float q[G][HD];
     float cs[HD / 2], sn[HD / 2];
     float knew[HD], vnew[HD];
     float acc[NSTREAM][G][HD];
     float ml[NSTREAM][G][2];
-    alignas(16) unsigned char v[kWaves][32][VS];
+    alignas(16) unsigned char v[VREG ? 1 : kWaves][VREG ? 1 : 32][VS];
     alignas(16) unsigned char k[kWaves][16][VS]; // one K tile per wave on its way into the MFMA operand layout
 };
 
 // TICKET: as in phase_attn, the workgroup whose split of a (sequence, KV head) finishes last merges the splits.
-template <int G, int HD, bool COH = false, bool TICKET = false, class Hook = NoHook>
+// QUEUE (and p.attn_queue set): the workgroups draw their items from one counter (p.attn_queue[0]) instead of taking
+// every nvb-th: contexts of a batch differ in length, the host does not know them, and a fixed assignment leaves the
+// launch waiting for the workgroup that happened to get the long ones.  The counter only grows, so every workgroup
+// draws a number past the end and leaves; the last one to leave (p.attn_queue[1] counts them) puts both words back
+// to zero for the next launch.
+template <int G, int HD, bool COH = false, bool TICKET = false, class Hook = NoHook, bool QUEUE = false>
 __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb, char *smem, Hook before_q = Hook()) {
     using L = AttnMfmaLds<G, HD>;
     constexpr int NS = HD / 32;        // MFMA depth steps over the head dimension
@@ -56,15 +62,39 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
     const float scale = 1.0f / sqrtf((float)HD);
     const int PW = HD + 2; // floats per (head, split) partial: acc[HD], max, sum
 
+    int &drawn = *reinterpret_cast<int *>(smem + sizeof(L) + 4); // the number thread 0 drew, for the workgroup
+    // items 0 .. nvb-1 are the workgroups' first ones, the counter hands out those from nvb on
+    auto draw = [&]() { return nvb + __hip_atomic_fetch_add(p.attn_queue, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
+    int item = vb, next_item = 0, pending = 0; // pending: thread 0's next number, asked for at the start of an item
+    auto hand_out = [&]() {                     // and handed to the workgroup at its end
+        if (tid == 0) drawn = pending;
+        __syncthreads();
+        const int v = drawn;
+        __syncthreads(); // read by all before thread 0 writes the next one
+        return v;
+    };
+    const bool queue = QUEUE && p.attn_queue != nullptr; // uniform
     bool first_item = true;
-    for (int item = vb; item < n_items; item += nvb) {
-        const int b = item / (p.Hkv * S), rem = item % (p.Hkv * S), kvh = rem / S, sp = rem % S;
+    for (;; item = next_item) {
+        if (queue) {
+            if (item >= n_items) break;
+            if (tid == 0) pending = draw(); // on its way while this item is worked on
+        } else {
+            if (item >= n_items) break;
+            next_item = item + nvb;
+        }
+        // split-major numbering: the splits of one (sequence, KV head) land on workgroups of different XCDs, and with
+        // the counter the short final splits are drawn last
+        const int sp = item / (p.B * p.Hkv), b = item % (p.B * p.Hkv) / p.Hkv, kvh = item % p.Hkv;
         const bool dead = seq_dead(p, b);
-        if (p.kv_appended && dead) continue; // a row that is not part of the block (uniform for the workgroup)
         const int Lb = dead ? 0 : p.kv_len[b];
         const int len = Lb + step + 1, pnew = len - 1;
         const int nsplit = (len + T - 1) / T;
-        if (sp >= nsplit) continue; // uniform for the workgroup
+        // a row that is not part of the block, or a split past the end of this context (uniform for the workgroup)
+        if ((p.kv_appended && dead) || sp >= nsplit) {
+            if (queue) next_item = hand_out();
+            continue;
+        }
         const int t0 = sp * T, t1 = min(t0 + T, len);
         const bool last = (sp == nsplit - 1) && !p.kv_appended; // as in phase_attn
         const int ntok = last ? (t1 - 1 - t0) : (t1 - t0);      // slots read from the cache
@@ -75,21 +105,27 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
         const int niter = (ntok + 31) / 32;
 
         u32x4 kn[2][NS], vr[NV];
-        auto load_iter = [&](int it) {
+        // K like V: a lane group of HD/8 lanes covers one row, so a load instruction reads whole rows (loaded
+        // straight into the operand layout every lane would touch another row, four times the address-unit work)
+        auto load_k = [&](int it) {
 #pragma unroll
-            // K like V: a lane group of HD/8 lanes covers one row, so a load instruction reads whole rows (loaded
-            // straight into the operand layout every lane would touch another row, four times the address-unit work)
             for (int tl = 0; tl < 2; ++tl)
 #pragma unroll
                 for (int u = 0; u < NS; ++u) {
                     const int tok = min(it * 32 + tl * 16 + u * TPI + lane / LPT, ntok - 1); // past the end: the last row again
                     kn[tl][u] = ldg16(kc + (size_t)tok * HD + (lane % LPT) * 8);
                 }
+        };
+        auto load_v = [&](int it) {
 #pragma unroll
             for (int u = 0; u < NV; ++u) {
                 const int tok = min(it * 32 + u * TPI + lane / LPT, ntok - 1);
                 vr[u] = ldg16(vc + (size_t)tok * HD + (lane % LPT) * 8);
             }
+        };
+        auto load_iter = [&](int it) {
+            load_k(it);
+            load_v(it);
         };
         if (wave < niter) load_iter(wave); // in flight while q, the rotary table and the new key/value are prepared
         if (first_item) {
@@ -163,13 +199,18 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
         f32x4 oacc[NDB];
 #pragma unroll
         for (int db = 0; db < NDB; ++db) oacc[db] = f32x4{0.f, 0.f, 0.f, 0.f};
-        unsigned char *vrow = &s.v[wave][0][0], *krow = &s.k[wave][0][0];
+        unsigned char *vrow = &s.v[L::VREG ? 0 : wave][0][0], *krow = &s.k[wave][0][0];
+        // which parked K row becomes row i16 of a score tile: with V in registers, row 4 g + e is token 4 e + g of the
+        // tile, so that a lane's eight scores belong to the eight tokens whose V rows it loaded
+        const int krd = L::VREG ? (i16 & 3) * 4 + (i16 >> 2) : i16;
 
         for (int it = wave; it < niter; it += kWaves) {
             // park the V rows, then request the next iteration's rows into the same registers
+            if constexpr (!L::VREG) {
 #pragma unroll
-            for (int u = 0; u < NV; ++u)
-                *reinterpret_cast<u32x4 *>(vrow + (size_t)(u * TPI + lane / LPT) * L::VS + (lane % LPT) * 16) = vr[u];
+                for (int u = 0; u < NV; ++u)
+                    *reinterpret_cast<u32x4 *>(vrow + (size_t)(u * TPI + lane / LPT) * L::VS + (lane % LPT) * 16) = vr[u];
+            }
             // K through the wave's strip into the operand layout: row i16, elements g4*HD/4 + 8u .. +8 for step u
             u32x4 kcur[2][NS];
 #pragma unroll
@@ -182,11 +223,14 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
                 for (int u = 0; u < NS; ++u)
-                    kcur[tl][u] = *reinterpret_cast<const u32x4 *>(krow + (size_t)i16 * L::VS + g4 * (HD / 2) + u * 16);
+                    kcur[tl][u] = *reinterpret_cast<const u32x4 *>(krow + (size_t)krd * L::VS + g4 * (HD / 2) + u * 16);
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                 __builtin_amdgcn_wave_barrier();
             }
-            if (it + kWaves < niter) load_iter(it + kWaves);
+            if (it + kWaves < niter) {
+                load_k(it + kWaves);
+                if constexpr (!L::VREG) load_v(it + kWaves);
+            }
 
             // scores of 2 x 16 tokens against the G heads
             f32x4 sc[2];
@@ -204,7 +248,7 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
             float tmax = -INFINITY;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const int tok = it * 32 + (e >> 2) * 16 + g4 * 4 + (e & 3);
+                const int tok = it * 32 + (L::VREG ? e * 4 + g4 : (e >> 2) * 16 + g4 * 4 + (e & 3));
                 sv[e] = tok < ntok ? sv[e] : -INFINITY;
                 tmax = fmaxf(tmax, sv[e]);
             }
@@ -231,6 +275,27 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
             }
             const u32x4 pH = {ph[0], ph[1], ph[2], ph[3]}, pL = {pl[0], pl[1], pl[2], pl[3]};
 
+            if constexpr (L::VREG) {
+                // the lane's load u holds dimensions 8 i16 .. +8 of token 4 u + g4, the token whose probability sits in
+                // pv[u]: output block db takes dimension 8 i16 + db as its row i16, its eight depth elements are
+                // element db of the eight loads (a byte permute per pair), no LDS in between
+#pragma unroll
+                for (int db = 0; db < NDB; ++db) {
+                    const uint32_t sel = (db & 1) ? 0x07060302u : 0x05040100u;
+                    uint32_t w[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const uint32_t a = vr[2 * e][db >> 1], c = vr[2 * e + 1][db >> 1];
+                        w[e] = __builtin_amdgcn_perm(c, a, sel);
+                    }
+                    const u32x4 va = {w[0], w[1], w[2], w[3]};
+                    f32x4 o = oacc[db] * alpha;
+                    o = mfma16(va, pH, o);
+                    o = mfma16(va, pL, o);
+                    oacc[db] = o;
+                }
+                if (it + kWaves < niter) load_v(it + kWaves); // the registers are free again
+            } else {
             // the parked rows were written by this wave's own lanes; LDS operations of a wave complete in order
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
@@ -255,6 +320,7 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
+            }
         }
 
         // ---- merge the waves (and the token being appended) through LDS ----
@@ -265,7 +331,8 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
             for (int db = 0; db < NDB; ++db) {
                 const float o[4] = {oacc[db].x, oacc[db].y, oacc[db].z, oacc[db].w};
 #pragma unroll
-                for (int v = 0; v < 4; ++v) s.acc[wave][i16][db * 16 + g4 * 4 + v] = o[v];
+                for (int v = 0; v < 4; ++v)
+                    s.acc[wave][i16][L::VREG ? 8 * (4 * g4 + v) + db : db * 16 + g4 * 4 + v] = o[v];
             }
             if (g4 == 0) {
                 s.ml[wave][i16][0] = mx * kLn2;
@@ -331,6 +398,14 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
             if (merges && wave < G)
                 merge_head<HD, true, COH>(p, b, kvh * G + wave, nsplit, reinterpret_cast<float *>(smem) + (size_t)wave * S);
             __syncthreads(); // the strips and the flag are free again before the next item touches the LDS
+        }
+        if (queue) next_item = hand_out();
+    }
+    if (queue && tid == 0) {
+        const int left = __hip_atomic_fetch_add(p.attn_queue + 1, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (left == nvb - 1) { // every workgroup has drawn its last number
+            __hip_atomic_store(p.attn_queue, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(p.attn_queue + 1, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
     if (first_item) before_q();

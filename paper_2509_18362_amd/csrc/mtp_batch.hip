@@ -75,7 +75,8 @@ __global__ __launch_bounds__(kBlock) void k_bprep(DraftParams p, int step) {
 template <int G, int HD>
 __global__ __launch_bounds__(kBlock) void k_attn_mfma(DraftParams p, int step) {
     extern __shared__ __align__(16) char smem[];
-    phase_attn_mfma<G, HD, false, true>(p, step, blockIdx.x, gridDim.x, smem); // merges its own splits (tickets)
+    // merges its own splits (tickets), hands its items out one by one
+    phase_attn_mfma<G, HD, false, true, NoHook, true>(p, step, blockIdx.x, gridDim.x, smem);
 }
 
 typedef void (*bg_kernel_t)(DraftParams, int);

@@ -282,6 +282,7 @@ size_t attn_lds_bytes(int G, int HD) {
 // ---- plan: how a call of B sequences is cut up ----------------------------------------------------------
 constexpr int kTargetAttnItems = 256; // (sequence, KV head, split) items aimed for
 constexpr int kMinSplitTokens = 128;
+constexpr int kMaxSplitTokens = 4096;
 constexpr int kMfmaAttnMinSplit = 256; // splits of at least this many tokens use the matrix-core attention
 constexpr size_t kLdsSmallBatch = 72 * 1024;  // two workgroups per CU
 constexpr size_t kLdsLargeBatch = 150 * 1024; // one workgroup per CU, more sequences per weight pass
@@ -290,6 +291,9 @@ int split_tokens_for(const mtp_config &c, int B) {
     long long t = ((long long)c.kv_capacity * B * c.n_kv_heads + kTargetAttnItems - 1) / kTargetAttnItems;
     t = std::max<long long>(t, kMinSplitTokens);
     t = (t + 63) / 64 * 64;
+    // past this length a split costs more in waiting for the longest context than another item costs in set-up; the
+    // launch then has more items than workgroups and hands them out one by one
+    t = std::min<long long>(t, kMaxSplitTokens);
     return (int)t;
 }
 int max_splits_for(const mtp_config &c, int B) {
@@ -366,7 +370,7 @@ WsLayout ws_layout(const mtp_config &c) {
     l.cand = take((size_t)c.max_draft_steps * mb * kMaxFusedGrid * 8);
     l.rope_inv = take((size_t)c.head_dim / 2 * 8);
     l.attn_part = take(attn_part_floats(c) * 4);
-    l.attn_ticket = take(mb * (size_t)c.n_kv_heads * 4);
+    l.attn_ticket = take(mb * (size_t)c.n_kv_heads * 4 + 64); // + the attention launch's item counter
     l.row_len = take(mb * 4);
     l.seq_list = take(mb * 4);
     l.list_ids = take(kMaxListGroups * 8);
@@ -661,6 +665,7 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
     p.rope_inv = reinterpret_cast<const double *>(ws + l.rope_inv);
     p.attn_part = reinterpret_cast<float *>(ws + l.attn_part);
     p.attn_ticket = reinterpret_cast<int *>(ws + l.attn_ticket); // the vector attention merges its own splits
+    p.attn_queue = p.attn_ticket + (size_t)c.max_batch * c.n_kv_heads;
     p.bar = reinterpret_cast<unsigned long long *>(ws + l.bar);
     p.bar_base = h->bar_epochs;
     p.cand = reinterpret_cast<unsigned long long *>(ws + l.cand);
@@ -721,6 +726,8 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
     p.head_grid = grid;
     const int attn_items = att_B * p.Hkv * p.max_splits;
     const int attn_grid = std::max(1, std::min(attn_items, h->num_cus * 2));
+    // more items than workgroups: the matrix-core attention hands them out one by one (contexts differ in length)
+    if (attn_items <= attn_grid) p.attn_queue = nullptr;
 
     const int tphase = h->timing >= 2 ? h->timing - 2 : -1;
     h->pev_used = 0;
@@ -1109,7 +1116,7 @@ int32_t mtp_poll_error(mtp_handle *h, void *hip_stream) {
         if (word & kErrBarrierTimeout) { // the barrier counter is out of step with the host's mirror: restart both
             if (hipMemsetAsync(h->ws + h->lay.bar, 0, 8, st) != hipSuccess) return MTP_ERR_HIP;
             // a kernel that gave up may have left arrival counters of the attention splits behind
-            if (hipMemsetAsync(h->ws + h->lay.attn_ticket, 0, (size_t)h->cfg.max_batch * h->cfg.n_kv_heads * 4, st) !=
+            if (hipMemsetAsync(h->ws + h->lay.attn_ticket, 0, (size_t)h->cfg.max_batch * h->cfg.n_kv_heads * 4 + 64, st) !=
                 hipSuccess)
                 return MTP_ERR_HIP;
             h->bar_epochs = 0;

@@ -68,6 +68,8 @@ struct DraftParams {
     int *ticket;         // arrival counters of the row groups (zero between launches)
     int *attn_ticket;    // [max_batch][Hkv] arrival counters of the attention splits (zero between phases): the
                          // workgroup that finishes last merges the splits
+    int *attn_queue;     // two words (zero between launches): next item of the attention launch that hands its items
+                         // out one by one, and the workgroups that have left it
     int b0, nb;          // sequences of this pass
     int bg_rg[6], bg_kp[6]; // row groups and reduction parts of the six matrix phases
     int bg_sep[6];          // 1: the phase's epilogue runs as a kernel of its own
