@@ -124,12 +124,30 @@ def test_tiny_long_capacity_matrix_core_attention(gpu, tiny):
     """A large cache capacity makes the split plan long enough for the matrix-core attention kernel (448 tokens per
     split here) and, with seven sequences, for the batched matrix phases.  Contexts cover: nothing cached, fewer
     tokens than one 16-row tile, exactly one 32-token iteration, one more, several iterations per wave, and several
-    splits (merged by the second kernel)."""
+    splits (merged by the workgroup that finishes last)."""
     wl = tiny["wl"]
     ctx = np.array([0, 1, 31, 32, 33, 300, 1000], dtype=np.int32)
     act = synth.make_activations(wl, ctx=ctx, capacity=32768)
     ref, res, caches = run_both(gpu, tiny["shape"], tiny["w"], tiny["w"], act, [tiny["ids"]], 0, 3)
     check_chain(ref, res, caches, act["kv_len"], 3)
+
+
+def test_tiny_many_long_contexts_items_handed_out(gpu, tiny):
+    """Forty sequences with a capacity of 32768: splits are capped at 4096 tokens, which leaves 640 attention items
+    for 512 workgroups, so the matrix-core attention hands its items out through the counter.  Contexts sit on
+    and around the split boundaries, at zero, and at the last slot that still fits K drafts; the call is made twice
+    on one engine (the counter must be back at zero after the first)."""
+    wl = tiny["wl"]
+    K, cap = 3, 32768
+    edge = [0, 1, 4092, 4093, 4094, 4095, 4096, 4097, 8191, 8192, 12000, 20000, 28671, 28672, 30000, cap - K]
+    rng = np.random.default_rng(77)
+    ctx = np.array(edge + list(rng.integers(0, cap - K, size=40 - len(edge))), dtype=np.int32)
+    act = synth.make_activations(wl, ctx=ctx, capacity=cap)
+    engine = gpu["binding"].DraftEngine(tiny["shape"], tiny["w"], [tiny["ids"]], len(ctx), cap, K)
+    for _ in range(2):
+        ref, res, caches = run_both(gpu, tiny["shape"], tiny["w"], tiny["w"], act, [tiny["ids"]], 0, K, engine=engine)
+        check_chain(ref, res, caches, act["kv_len"], K)
+    engine.close()
 
 
 @pytest.mark.parametrize("B", [17, 20, 40, 70, 130])
