@@ -317,7 +317,7 @@ def bf16_to_real(bits: np.ndarray, real) -> np.ndarray:
 
 
 def build_subset(tokens, vocab_size: int, n: int):
-    """The high-frequency id list of Sec. 2.2 from a token stream ("identified through corpus-level statistics"):
+    """The high-frequency id list of Sec. 2.2 (which takes it from statistics over a corpus) from a token stream:
     occurrence counts per id, the n ids with the largest counts (equal counts: the lower id first), returned in
     ascending id order - the format the output head of Eq. (3) is gathered with.  Ids outside [0, vocab_size) are
     skipped and counted.  Returns dict(counts [V] int64, ids [n] int32, invalid int)."""

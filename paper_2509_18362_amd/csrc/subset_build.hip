@@ -1,6 +1,6 @@
 // High-frequency vocabulary list from a token stream (gfx950): occurrence counts per id, the n most frequent ids
 // (equal counts: lower id first), written in ascending id order - the list the compressed output head is gathered
-// with (Sec. 2.2: "high-frequency tokens ... identified through corpus-level statistics", Eq. (3)).
+// with (Sec. 2.2, which takes the frequent tokens of a language from statistics over a corpus; Eq. (3)).
 //
 // Counting is the only part that touches much memory.  Global atomics on a long-tailed stream would pile up on the
 // few hottest ids (same-address device atomics serialize at ~40 ns each), so every workgroup counts in LDS: the
