@@ -774,31 +774,185 @@ __device__ __forceinline__ void phase_bepilogue(const DraftParams &p, Ph &ph, in
 //   s < K: the input of step s, [RMSNorm(h; g_h); RMSNorm(E[token]; g_e)], split into bf16 hi + lo
 // ---------------------------------------------------------------------------------------------------
 __device__ __forceinline__ void phase_bprep(const DraftParams &p, int step, char *smem) {
-    const int b = blockIdx.x, d = p.d;
-    float *red = reinterpret_cast<float *>(smem);
+    const int b = blockIdx.x, d = p.d, tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    float *ra = reinterpret_cast<float *>(smem), *rb = ra + kWaves, *rc = rb + kWaves; // [kWaves] each
+    unsigned long long *rk = reinterpret_cast<unsigned long long *>(smem + 128);       // [kWaves]
     uint16_t *hi = p.act[0] + (size_t)b * p.a_stride;
     uint16_t *lo = hi + p.a_lo;
-    if (step == 0 && threadIdx.x == 0 && seq_overflows(p, b)) atomicOr(p.err, kErrKvOverflow);
-    int did = 0;
+    if (step == 0 && tid == 0 && seq_overflows(p, b)) atomicOr(p.err, kErrKvOverflow);
+
+    // Everything that can be asked for before the previous step's winner is known is asked for first, and the sums
+    // of squares travel through ONE reduction together with the winner: the kernel is a chain of memory round trips
+    // and barriers on sixteen to sixty-four CUs, not a bandwidth problem.
+    auto split_store = [&](uint16_t *dh, uint16_t *dl, int e, const float (&o)[4]) {
+        uint16_t h[4], l[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) split_bf16(o[q], h[q], l[q]);
+        *reinterpret_cast<u32x2 *>(dh + e) = u32x2{(uint32_t)h[0] | ((uint32_t)h[1] << 16), (uint32_t)h[2] | ((uint32_t)h[3] << 16)};
+        *reinterpret_cast<u32x2 *>(dl + e) = u32x2{(uint32_t)l[0] | ((uint32_t)l[1] << 16), (uint32_t)l[2] | ((uint32_t)l[3] << 16)};
+    };
+    auto load_bf16x4 = [&](const uint16_t *src, int e, float (&v)[4]) {
+        const u32x2 raw = *reinterpret_cast<const u32x2 *>(src + e);
+        v[0] = lo_half(raw.x);
+        v[1] = hi_half(raw.x);
+        v[2] = lo_half(raw.y);
+        v[3] = hi_half(raw.y);
+    };
+    auto checked = [&](int t) { // reported, and replaced by id 0 so that every access stays in bounds
+        if (t < 0 || t >= p.V) {
+            if (tid == 0) atomicOr(p.err, kErrTokenRange);
+            t = 0;
+        }
+        return t;
+    };
+
+    // the previous step's candidates
+    unsigned long long best = 0ull;
     if (step > 0) {
-        did = key_token(p, b, winner_key(p, step - 1, b, reinterpret_cast<unsigned long long *>(red)));
-        if (threadIdx.x == 0) p.draft_out[(size_t)b * p.K + step - 1] = seq_dead(p, b) ? -1 : did;
-        float *ho = p.hidden_out ? p.hidden_out + ((size_t)b * p.K + step - 1) * d : nullptr;
-        // the hi/lo halves written here are overwritten below or never read
-        stage_rmsnorm<false>(p.dn + (size_t)b * d, p.g_final, d, p.eps, hi, lo, red, p.hhat + (size_t)b * d, ho);
-        __syncthreads();
+        const unsigned long long *cand = p.cand + ((size_t)(step - 1) * p.max_batch + b) * p.head_grid;
+        const int ncand = seq_head(p, b).cands;
+        for (int w = tid; w < ncand; w += kBlock) {
+            const unsigned long long c = cand[w];
+            best = c > best ? c : best;
+        }
+    }
+    // the vector the hidden half is made of: step 0, the caller's hidden state (bf16) or the head's own output of an
+    // earlier call (float); later, x2 of the previous step, which first becomes h_hat = RMSNorm(x2; g_final)
+    const bool from_x2 = step > 0, src_float = from_x2 || p.own_hidden;
+    const float *xf = from_x2 ? p.dn + (size_t)b * d : p.hhat + (size_t)b * d;
+    float x[kMaxNormIter][4], ev[kMaxNormIter][4];
+    float sx = 0.f, sg = 0.f, se = 0.f;
+#pragma unroll
+    for (int it = 0; it < kMaxNormIter; ++it) {
+        const int e = (it * kBlock + tid) * 4;
+        if (e < d) {
+            if (src_float) {
+                const f32x4 raw = *reinterpret_cast<const f32x4 *>(xf + e);
+                x[it][0] = raw.x;
+                x[it][1] = raw.y;
+                x[it][2] = raw.z;
+                x[it][3] = raw.w;
+            } else {
+                load_bf16x4(p.hidden_in + (size_t)b * d, e, x[it]);
+            }
+        }
+    }
+    // the token whose embedding forms the other half, where it does not depend on the winner
+    const bool early_tok = step < p.K && (step == 0 || p.forced != nullptr);
+    int tok = 0;
+    if (early_tok) tok = checked(step == 0 ? p.token_in[b] : p.forced[(size_t)b * (p.K - 1) + step - 1]);
+    auto load_embed = [&]() {
+        float s = 0.f;
+#pragma unroll
+        for (int it = 0; it < kMaxNormIter; ++it) {
+            const int e = (it * kBlock + tid) * 4;
+            if (e < d) {
+                load_bf16x4(p.embed + (size_t)tok * d, e, ev[it]);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) s += ev[it][q] * ev[it][q];
+            }
+        }
+        return s;
+    };
+    if (early_tok) se = load_embed();
+#pragma unroll
+    for (int it = 0; it < kMaxNormIter; ++it) {
+        const int e = (it * kBlock + tid) * 4;
+        if (e < d) {
+            float gf[4] = {1.f, 1.f, 1.f, 1.f};
+            if (from_x2) load_bf16x4(p.g_final, e, gf);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                sx += x[it][q] * x[it][q];
+                sg += (gf[q] * x[it][q]) * (gf[q] * x[it][q]);
+            }
+        }
+    }
+    // one reduction: three sums and the winner
+    sx = wave_sum(sx);
+    sg = wave_sum(sg);
+    se = wave_sum(se);
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        const unsigned long long o = __shfl_xor(best, off, kWave);
+        best = o > best ? o : best;
+    }
+    if (lane == 0) {
+        ra[wave] = sx;
+        rb[wave] = sg;
+        rc[wave] = se;
+        rk[wave] = best;
+    }
+    __syncthreads();
+    sx = sg = se = 0.f;
+    best = 0ull;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        sx += ra[w];
+        sg += rb[w];
+        se += rc[w];
+        best = rk[w] > best ? rk[w] : best;
+    }
+    int did = 0;
+    if (from_x2) {
+        did = key_token(p, b, best);
+        if (tid == 0) p.draft_out[(size_t)b * p.K + step - 1] = seq_dead(p, b) ? -1 : did;
+    }
+    // h_hat = g_final * (x2 * inv1); its own mean square is inv1^2 * mean((g_final x2)^2) up to rounding, which saves a
+    // second reduction
+    const float inv1 = 1.0f / sqrtf(sx / (float)d + p.eps);
+    const float inv2 = from_x2 ? 1.0f / sqrtf(inv1 * inv1 * sg / (float)d + p.eps) : inv1;
+    float *ho = (from_x2 && p.hidden_out) ? p.hidden_out + ((size_t)b * p.K + step - 1) * d : nullptr;
+#pragma unroll
+    for (int it = 0; it < kMaxNormIter; ++it) {
+        const int e = (it * kBlock + tid) * 4;
+        if (e < d) {
+            float h[4];
+            if (from_x2) {
+                float gf[4];
+                load_bf16x4(p.g_final, e, gf);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) h[q] = gf[q] * (x[it][q] * inv1);
+                const f32x4 w = {h[0], h[1], h[2], h[3]};
+                *reinterpret_cast<f32x4 *>(p.hhat + (size_t)b * d + e) = w;
+                if (ho) *reinterpret_cast<f32x4 *>(ho + e) = w;
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) h[q] = x[it][q];
+            }
+            if (step < p.K) {
+                float gh[4], o[4];
+                load_bf16x4(p.g_h, e, gh);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) o[q] = gh[q] * (h[q] * inv2);
+                split_store(hi, lo, e, o);
+            }
+        }
     }
     if (step >= p.K) return;
-    int tok = step == 0 ? p.token_in[b] : (p.forced ? p.forced[(size_t)b * (p.K - 1) + step - 1] : did);
-    if (tok < 0 || tok >= p.V) { // reported, and replaced by id 0 so that every access stays in bounds
-        if (threadIdx.x == 0) atomicOr(p.err, kErrTokenRange);
-        tok = 0;
+    if (!early_tok) { // the winner is the next input token
+        tok = checked(did);
+        se = load_embed();
+        se = wave_sum(se);
+        __syncthreads(); // rc has been read by everyone
+        if (lane == 0) rc[wave] = se;
+        __syncthreads();
+        se = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) se += rc[w];
     }
-    if (step == 0 && !p.own_hidden)
-        stage_rmsnorm<true>(p.hidden_in + (size_t)b * d, p.g_h, d, p.eps, hi, lo, red, nullptr);
-    else
-        stage_rmsnorm<false>(p.hhat + (size_t)b * d, p.g_h, d, p.eps, hi, lo, red, nullptr);
-    stage_rmsnorm<true>(p.embed + (size_t)tok * d, p.g_e, d, p.eps, hi + d, lo + d, red, nullptr);
+    const float inve = 1.0f / sqrtf(se / (float)d + p.eps);
+#pragma unroll
+    for (int it = 0; it < kMaxNormIter; ++it) {
+        const int e = (it * kBlock + tid) * 4;
+        if (e < d) {
+            float ge[4], o[4];
+            load_bf16x4(p.g_e, e, ge);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) o[q] = ge[q] * (ev[it][q] * inve);
+            split_store(hi + d, lo + d, e, o);
+        }
+    }
 }
 
 } // namespace mtp
