@@ -224,8 +224,8 @@ int32_t mtp_draft_continue(mtp_handle *h, int32_t B, int32_t K, int32_t subset_i
  *   hidden_in    device [n_pos][d] bf16          the main model's hidden states
  *   tokens       device [n_pos + K + 1] int32    t_1 .. t_{n_pos+K+1}
  *   k_cache, v_cache  device, ONE sequence's cache [n_kv_heads][kv_capacity][head_dim] bf16: scratch, overwritten
- *   scratch      device, mtp_train_workspace_bytes(cfg, n_pos) bytes (the logits of a step, [n_pos][vocab] float,
- *                are its bulk)
+ *   scratch      device, mtp_train_workspace_bytes(cfg, n_pos) bytes.  Its first n_pos * vocab_size floats hold the
+ *                logits of a step, [n_pos][vocab_size]: after the call, those of step K
  *   loss_out     device [K + 1] float            CE_1 .. CE_K, then the weighted loss
  * A token id outside the vocabulary is reported by mtp_poll_error (MTP_ERR_TOKEN_RANGE) and treated as id 0.
  */

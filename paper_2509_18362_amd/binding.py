@@ -280,9 +280,10 @@ class DraftEngine:
             raise MTPError(st)
         return {"draft": draft, "logits": logits, "hidden": hidden}
 
-    def train_loss(self, hidden_in, tokens, K: int, beta: float, stream: int = 0):
+    def train_loss(self, hidden_in, tokens, K: int, beta: float, stream: int = 0, want_logits: bool = False):
         """Teacher-forced K-step forward and its weighted cross-entropy (see mtp_train_loss).  hidden_in [n][d] bf16
-        bits, tokens [n + K + 1]: device tensors.  Returns a device tensor [K + 1]: CE_1 .. CE_K, the loss."""
+        bits, tokens [n + K + 1]: device tensors.  Returns a device tensor [K + 1]: CE_1 .. CE_K, the loss; with
+        want_logits also the last step's logits [n][V] (a view of the call's scratch buffer)."""
         torch = self.torch
         n_pos = hidden_in.shape[0]
         s = self.shape
@@ -295,6 +296,8 @@ class DraftEngine:
         if st != MTP_OK:
             raise MTPError(st)
         self._train_keep = (scratch, cache)   # alive until the stream has run the call
+        if want_logits:
+            return out[:K + 1], scratch[:n_pos * s.vocab_size * 4].view(torch.float32).view(n_pos, s.vocab_size)
         return out[:K + 1]
 
     def draft_lists(self, K: int, seq_subset, hidden_in, token_in, k_cache, v_cache, kv_len, forced=None,

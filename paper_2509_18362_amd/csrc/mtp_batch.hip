@@ -6,6 +6,7 @@
 #include "attn_mfma.h"
 #include "batch.h"
 #include "batch_launch.h"
+#include "head_gemm.h"
 
 namespace mtp {
 namespace {
@@ -70,6 +71,11 @@ __global__ __launch_bounds__(kBlock) void k_bepilogue(DraftParams p, int step) {
 __global__ __launch_bounds__(kBlock) void k_bprep(DraftParams p, int step) {
     __shared__ __align__(16) char smem[256];
     phase_bprep(p, step, smem);
+}
+
+__global__ __launch_bounds__(kBlock, 4) void k_head_gemm(DraftParams p, int step) {
+    extern __shared__ __align__(16) char smem[];
+    phase_head_gemm(p, step, smem);
 }
 
 template <int G, int HD>
@@ -157,7 +163,8 @@ void launch_attn_mfma(int G, int HD, const DraftParams &p, int step, int grid, s
 }
 
 bool batch_allow_lds(size_t lds_limit) {
-    bool ok = true;
+    bool ok = hipFuncSetAttribute((const void *)k_head_gemm, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)lds_limit) == hipSuccess;
     for (int hd = 64; hd <= 128; hd *= 2)
         for (int g = 1; g <= 8; g *= 2)
             ok = ok && hipFuncSetAttribute((const void *)attn_mfma_kernel(g, hd),
@@ -176,6 +183,10 @@ void launch_bgemv(int phase, const DraftParams &p, int step, int grid, size_t ld
         hipLaunchKernelGGL(pick_epilogue(phase, na),
                            dim3(phase == BG_LMHEAD ? p.head_grid : batch_epilogue_grid(phase, p, na)), dim3(kBlock), 0, st,
                            p, step);
+}
+
+void launch_head_gemm(const DraftParams &p, int step, hipStream_t st) {
+    hipLaunchKernelGGL(k_head_gemm, dim3(head_gemm_grid(p.B, p.n)), dim3(kBlock), sizeof(HeadGemmLds), st, p, step);
 }
 
 void launch_bprep(const DraftParams &p, int step, hipStream_t st) {

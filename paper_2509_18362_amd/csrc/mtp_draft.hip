@@ -164,20 +164,36 @@ __global__ void k_train_begin_step(int n_pos, int *kv_len, int *ext_len) { // a 
 // one workgroup per position: logsumexp(z) - z[label] over the full vocabulary
 __global__ __launch_bounds__(256) void k_train_row_ce(const float *__restrict__ logits, int V, const int *labels,
                                                       float *row_loss, int *err) {
-    __shared__ float red[256 / kWave];
+    __shared__ float red_m[256 / kWave], red_s[256 / kWave];
     const float *z = logits + (size_t)blockIdx.x * V;
-    float m = -INFINITY;
-    for (int i = threadIdx.x; i < V; i += 256) m = fmaxf(m, z[i]);
+    // one pass: every thread keeps a running maximum and the sum of exp(z - maximum) of its elements (16-byte loads
+    // where the row allows them), the pairs are combined at the end
+    float m = -INFINITY, sum = 0.f;
+    auto take = [&](float a, float b, float c, float d) {
+        const float mm = fmaxf(fmaxf(a, b), fmaxf(c, d));
+        if (mm > m) {
+            sum *= expf(m - mm); // exp(-inf) = 0 the first time
+            m = mm;
+        }
+        sum += (expf(a - m) + expf(b - m)) + (expf(c - m) + expf(d - m));
+    };
+    const int head = (int)((4 - (((size_t)blockIdx.x * V) & 3)) & 3); // elements before the first aligned one
+    const int nvec = V > head ? (V - head) / 4 : 0;
+    const f32x4 *z4 = reinterpret_cast<const f32x4 *>(z + head);
+    for (int i = threadIdx.x; i < nvec; i += 256) {
+        const f32x4 v = z4[i];
+        take(v.x, v.y, v.z, v.w);
+    }
+    for (int i = threadIdx.x; i < V; i += 256) // the few elements outside the aligned middle
+        if (i < head || i >= head + nvec * 4) take(z[i], -INFINITY, -INFINITY, -INFINITY);
+    float wm = m;
 #pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) m = fmaxf(m, __shfl_xor(m, off, kWave));
-    if ((threadIdx.x & (kWave - 1)) == 0) red[threadIdx.x / kWave] = m;
-    __syncthreads();
-    m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-    __syncthreads();
-    float sum = 0.f;
-    for (int i = threadIdx.x; i < V; i += 256) sum += expf(z[i] - m);
-    sum = wave_sum(sum);
-    if ((threadIdx.x & (kWave - 1)) == 0) red[threadIdx.x / kWave] = sum;
+    for (int off = 1; off < kWave; off <<= 1) wm = fmaxf(wm, __shfl_xor(wm, off, kWave));
+    sum = wave_sum(wm == -INFINITY ? 0.f : sum * expf(m - wm));
+    if ((threadIdx.x & (kWave - 1)) == 0) {
+        red_m[threadIdx.x / kWave] = wm;
+        red_s[threadIdx.x / kWave] = sum;
+    }
     __syncthreads();
     if (threadIdx.x == 0) {
         int label = labels[blockIdx.x];
@@ -185,7 +201,11 @@ __global__ __launch_bounds__(256) void k_train_row_ce(const float *__restrict__ 
             atomicOr(err, kErrTokenRange);
             label = 0;
         }
-        row_loss[blockIdx.x] = m + logf((red[0] + red[1]) + (red[2] + red[3])) - z[label];
+        const float M = fmaxf(fmaxf(red_m[0], red_m[1]), fmaxf(red_m[2], red_m[3]));
+        float tot = 0.f;
+#pragma unroll
+        for (int w = 0; w < 256 / kWave; ++w) tot += red_m[w] == -INFINITY ? 0.f : red_s[w] * expf(red_m[w] - M);
+        row_loss[blockIdx.x] = M + logf(tot) - z[label];
     }
 }
 // mean over the positions in a fixed order (one workgroup), and after the last step the weighted total of Eq. (1)
@@ -572,6 +592,8 @@ struct ExtendCall {
     int B, m_max;           // real sequences, positions per sequence (rows = m_max * B)
     const int32_t *ext_len; // device [B]
     int32_t *kv_len;        // device [B], the real lengths (advanced at the end)
+    bool logits_only = false; // the caller wants logits and no drafts (the training loss): many rows take the
+                              // tiled matrix product for the output head
 };
 
 // B sequences (or rows), K steps; arguments checked by the callers
@@ -884,7 +906,14 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
         // grid is then this number for every pass of the call (workgroups without work leave "no candidate")
         p.head_grid = max_cands;
         publish_lists();
+        // more rows than one pass of the batched core serves, and only logits wanted: one tiled matrix product
+        const bool head_gemm = ext && ext->logits_only && B > kBatchPassSeq && !groups.count && logits_out;
         auto matrix_phase = [&](int timed_as, int ph, int step) {
+            if (ph == BG_LMHEAD && head_gemm) {
+                launch_head_gemm(p, step, st);
+                mark_end(timed_as, step);
+                return;
+            }
             const int runs = ph == BG_LMHEAD ? n_heads : 1; // the output head: once per id list
             for (int g = 0; g < runs; ++g) {
                 int lo = 0, hi = B;
@@ -1071,7 +1100,7 @@ int32_t mtp_train_loss(mtp_handle *h, int32_t n_pos, int32_t K, float beta, cons
     int32_t *kv_len = reinterpret_cast<int32_t *>(reinterpret_cast<char *>(draft) + up((size_t)n_pos * 4));
     int32_t *ext_len = kv_len + 64;
     int *err = reinterpret_cast<int *>(h->ws + h->lay.err);
-    const ExtendCall ext{1, n_pos, ext_len, kv_len};
+    const ExtendCall ext{1, n_pos, ext_len, kv_len, true};
     for (int k = 1; k <= K; ++k) {
         // Step k over all positions: the block-of-positions pipeline from an empty cache.  Position i consumes
         // (h^{k-1}_i, t_{i+k}): the main model's states at k = 1, the head's own output of step k-1 afterwards.
