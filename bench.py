@@ -316,8 +316,8 @@ def main() -> int:
         train = {"positions": n_pos, "K": Kt, "beta": 0.6, "ms_per_forward": el_t * 1e3,
                  "positions_per_s": n_pos / el_t, "tflops": 2.0 * macs * n_pos * Kt / el_t / 1e12,
                  "loss": [float(x) for x in loss_t.cpu().numpy()],
-                 "note": "output head: one tiled MFMA matrix product over all positions; the body's matrices: the draft "
-                         "kernels, weights re-read per 64 positions"}
+                 "note": "every matrix phase is one LDS-tiled MFMA matrix product over all positions (activations as "
+                         "bf16 hi + lo: two MFMAs per product)"}
         eng3.close()
 
     full = None

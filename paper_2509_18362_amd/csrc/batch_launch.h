@@ -17,8 +17,10 @@ int batch_epilogue_grid(int phase, const DraftParams &p, int na);
 // the preparation kernel before step `step` (step == K: after the last step), all sequences
 void launch_bprep(const DraftParams &p, int step, hipStream_t st);
 
-// the output head of all p.B rows as one tiled matrix product, logits only (head_gemm.h)
-void launch_head_gemm(const DraftParams &p, int step, hipStream_t st);
+// a matrix phase (BG_* index) over all p.B rows as one tiled matrix product (rows_gemm.h); the output head leaves
+// logits only, no candidates.  rows_gemm_serves: the phase's reduction length is a multiple of the tiling's step
+bool rows_gemm_serves(int phase, const DraftParams &p);
+void launch_rows_gemm(int phase, const DraftParams &p, int step, hipStream_t st);
 
 // matrix-core attention (attn_mfma.h): dynamic LDS, and the launch for query-group size G and head dimension HD
 size_t attn_mfma_lds_bytes(int G, int HD);

@@ -6,7 +6,7 @@
 #include "attn_mfma.h"
 #include "batch.h"
 #include "batch_launch.h"
-#include "head_gemm.h"
+#include "rows_gemm.h"
 
 namespace mtp {
 namespace {
@@ -73,9 +73,23 @@ __global__ __launch_bounds__(kBlock) void k_bprep(DraftParams p, int step) {
     phase_bprep(p, step, smem);
 }
 
-__global__ __launch_bounds__(kBlock, 4) void k_head_gemm(DraftParams p, int step) {
+// a matrix phase over all p.B rows as one tiled matrix product (rows_gemm.h); at most 128 registers, so that two
+// workgroups of the 80 KB tiling (four of the 40 KB one) share a CU
+template <int PH>
+__global__ __launch_bounds__(kBlock, 4) void k_rows_gemm(DraftParams p, int step) {
     extern __shared__ __align__(16) char smem[];
-    phase_head_gemm(p, step, smem);
+    if constexpr (PH == BG_PROJ)
+        rows_gemm<64, 128, BgProj>(p, [](const DraftParams &q) { return BgProj(q); }, smem);
+    else if constexpr (PH == BG_QKV)
+        rows_gemm<64, 128, BgQkv>(p, [](const DraftParams &q) { return BgQkv(q); }, smem);
+    else if constexpr (PH == BG_OPROJ)
+        rows_gemm<64, 128, BgOproj>(p, [](const DraftParams &q) { return BgOproj(q); }, smem);
+    else if constexpr (PH == BG_GATEUP)
+        rows_gemm<64, 128, BgGateUp>(p, [](const DraftParams &q) { return BgGateUp(q); }, smem);
+    else if constexpr (PH == BG_DOWN)
+        rows_gemm<64, 128, BgDown>(p, [](const DraftParams &q) { return BgDown(q); }, smem);
+    else
+        rows_gemm<128, 256, BgHeadLogits>(p, [step](const DraftParams &q) { return BgHeadLogits(q, step); }, smem);
 }
 
 template <int G, int HD>
@@ -163,8 +177,10 @@ void launch_attn_mfma(int G, int HD, const DraftParams &p, int step, int grid, s
 }
 
 bool batch_allow_lds(size_t lds_limit) {
-    bool ok = hipFuncSetAttribute((const void *)k_head_gemm, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  (int)lds_limit) == hipSuccess;
+    bool ok = true;
+    for (bg_kernel_t k : {k_rows_gemm<BG_GATEUP>, k_rows_gemm<BG_LMHEAD>})
+        ok = ok && hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_limit) ==
+                       hipSuccess;
     for (int hd = 64; hd <= 128; hd *= 2)
         for (int g = 1; g <= 8; g *= 2)
             ok = ok && hipFuncSetAttribute((const void *)attn_mfma_kernel(g, hd),
@@ -185,8 +201,26 @@ void launch_bgemv(int phase, const DraftParams &p, int step, int grid, size_t ld
                            p, step);
 }
 
-void launch_head_gemm(const DraftParams &p, int step, hipStream_t st) {
-    hipLaunchKernelGGL(k_head_gemm, dim3(head_gemm_grid(p.B, p.n)), dim3(kBlock), sizeof(HeadGemmLds), st, p, step);
+bool rows_gemm_serves(int phase, const DraftParams &p) {
+    const int K = phase == BG_PROJ ? 2 * p.d : phase == BG_OPROJ ? p.qd : phase == BG_DOWN ? p.F : p.d;
+    return K % kRgBK == 0;
+}
+void launch_rows_gemm(int phase, const DraftParams &p, int step, hipStream_t st) {
+    auto rows16 = [](int rows) { return (rows + 15) / 16 * 16; };
+    auto small = [&](bg_kernel_t k, int n) {
+        hipLaunchKernelGGL(k, dim3(rows_gemm_grid<64, 128>(p.B, n)), dim3(kBlock), sizeof(RowsGemmLds<64, 128>), st, p, step);
+    };
+    auto large = [&](bg_kernel_t k, int n) {
+        hipLaunchKernelGGL(k, dim3(rows_gemm_grid<128, 256>(p.B, n)), dim3(kBlock), sizeof(RowsGemmLds<128, 256>), st, p, step);
+    };
+    switch (phase) {
+    case BG_PROJ: small(k_rows_gemm<BG_PROJ>, p.d); break;
+    case BG_QKV: small(k_rows_gemm<BG_QKV>, rows16(p.qkv_dim)); break;
+    case BG_OPROJ: small(k_rows_gemm<BG_OPROJ>, p.d); break;
+    case BG_GATEUP: small(k_rows_gemm<BG_GATEUP>, 2 * rows16(p.F)); break;
+    case BG_DOWN: small(k_rows_gemm<BG_DOWN>, p.d); break;
+    default: large(k_rows_gemm<BG_LMHEAD>, rows16(p.n)); break;
+    }
 }
 
 void launch_bprep(const DraftParams &p, int step, hipStream_t st) {

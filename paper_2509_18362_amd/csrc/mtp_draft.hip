@@ -906,11 +906,12 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
         // grid is then this number for every pass of the call (workgroups without work leave "no candidate")
         p.head_grid = max_cands;
         publish_lists();
-        // more rows than one pass of the batched core serves, and only logits wanted: one tiled matrix product
-        const bool head_gemm = ext && ext->logits_only && B > kBatchPassSeq && !groups.count && logits_out;
+        // more rows than one pass of the batched core serves, and only logits wanted: every matrix phase is one tiled
+        // matrix product over all rows
+        const bool tiled = ext && ext->logits_only && B > kBatchPassSeq && !groups.count && logits_out;
         auto matrix_phase = [&](int timed_as, int ph, int step) {
-            if (ph == BG_LMHEAD && head_gemm) {
-                launch_head_gemm(p, step, st);
+            if (tiled && rows_gemm_serves(ph, p)) {
+                launch_rows_gemm(ph, p, step, st);
                 mark_end(timed_as, step);
                 return;
             }
