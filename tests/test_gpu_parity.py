@@ -571,8 +571,9 @@ def test_tiny_one_list_per_sequence(gpu, tiny, ctx, seq_subset):
 @pytest.mark.parametrize("n_pos,K", [(3, 2), (40, 3), (70, 3), (300, 2)])
 def test_tiny_teacher_forced_loss(gpu, tiny, n_pos, K):
     """Eq. (1)-(2): the K per-step cross-entropies and their weighted sum against the oracle (3 positions: the
-    row-streaming phases; 40: the batched ones; 70: two weight passes).  The logits agree to ~1e-4, a mean of
-    log-probabilities to better than 1e-3."""
+    row-streaming phases; 40: the batched ones; 70: two weight passes and the output head as a tiled matrix product;
+    300: every matrix phase tiled except the down projection, whose reduction length 688 is not a multiple of the
+    tiling's step).  The logits agree to ~1e-4, a mean of log-probabilities to better than 1e-3."""
     torch, Oracle, binding, orc_mod = gpu["torch"], gpu["Oracle"], gpu["binding"], gpu["orc"]
     shape = tiny["shape"]
     rng = np.random.default_rng(300 + n_pos)
@@ -707,14 +708,14 @@ def test_7b_extend_four_positions(gpu, big):
         print(name, "extend max |dlogit| =", gap)
 
 
-@pytest.mark.parametrize("n_pos", [24, 80])
-def test_7b_teacher_forced_loss(gpu, big, n_pos):
-    """The 7B-shaped head, K = 2, full 151680-id vocabulary: both cross-entropies and the loss.  24 positions run the
+@pytest.mark.parametrize("n_pos,K", [(24, 2), (80, 2), (260, 1)])
+def test_7b_teacher_forced_loss(gpu, big, n_pos, K):
+    """The 7B-shaped head, full 151680-id vocabulary: the cross-entropies and the loss.  24 positions run the
     output head on the batched core, 80 (more than one pass of it) as the tiled matrix product, with a ragged block
-    of positions and a ragged last block of vocabulary rows."""
+    of positions and a ragged last block of vocabulary rows; from 256 positions on the body's matrix phases are tiled
+    matrix products too."""
     torch, Oracle, binding, orc_mod = gpu["torch"], gpu["Oracle"], gpu["binding"], gpu["orc"]
     shape = big["shape"]
-    K = 2
     rng = np.random.default_rng(330)
     hid = synth.f32_to_bf16_bits(rng.standard_normal((n_pos, shape.d_model)).astype(np.float32))
     tok = rng.integers(0, shape.vocab_size, size=n_pos + K + 1).astype(np.int32)
