@@ -906,13 +906,13 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
         // grid is then this number for every pass of the call (workgroups without work leave "no candidate")
         p.head_grid = max_cands;
         publish_lists();
-        // more rows than one pass of the batched core serves, and only logits wanted: every matrix phase is one tiled
-        // matrix product over all rows
+        // Many rows: matrix phases as tiled matrix products over all rows instead of one pass of the batched core per
+        // 64.  The output head has hundreds of weight-row blocks at any row count, but its tiled form leaves no
+        // candidates: for callers that want logits only (the training loss), from 65 rows on.  The body's phases have
+        // as few as 32 blocks of weight rows and fill the chip only from four passes' worth of rows on (measured at
+        // 128 rows: 1034 us per step against 757 with two passes, at 256 rows 1350 against 1458).
         const bool tiled = ext && ext->logits_only && B > kBatchPassSeq && !groups.count && logits_out;
-        // the output head has hundreds of weight-row blocks at any row count; the body's phases have as few as 32 and
-        // fill the chip only from four passes' worth of rows on (measured at 128 rows: 1034 us per step against 757
-        // with two passes of the batched core, at 256 rows 1350 against 1458)
-        const bool tiled_body = tiled && B >= 4 * kBatchPassSeq;
+        const bool tiled_body = B >= 4 * kBatchPassSeq;
         auto matrix_phase = [&](int timed_as, int ph, int step) {
             if ((ph == BG_LMHEAD ? tiled : tiled_body) && rows_gemm_serves(ph, p)) {
                 launch_rows_gemm(ph, p, step, st);

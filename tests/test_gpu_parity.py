@@ -150,10 +150,11 @@ def test_tiny_many_long_contexts_items_handed_out(gpu, tiny):
     engine.close()
 
 
-@pytest.mark.parametrize("B", [17, 20, 40, 70, 130])
+@pytest.mark.parametrize("B", [17, 20, 40, 70, 130, 300])
 def test_tiny_wide_batches(gpu, tiny, B):
     """Batches above 16 take the core whose waves split the tiles (two or four sequence tiles, the last one ragged);
-    70 sequences are two weight passes (64 + 6), 130 are three (64 + 64 + 2).  The tiny head has a reduction length (d_ffn = 688) that is not a
+    70 sequences are two weight passes (64 + 6), 130 are three (64 + 64 + 2); from 256 on the body's matrix phases are
+    tiled matrix products over all sequences (300: a ragged last block of 64).  The tiny head has a reduction length (d_ffn = 688) that is not a
     multiple of the 64-element double step, and row counts that leave most tile slots of a block empty."""
     wl = tiny["wl"]
     rng = np.random.default_rng(100 + B)
@@ -388,6 +389,7 @@ def check_extend(ref, res, caches, act, ext_len, sel=None):
     ([0, 60], [2, 1], 2),                    # four rows, one sequence starting from an empty cache
     ([0, 130, 64], [4, 0, 2], 4),            # twelve rows (batched matrix phases), ragged, one sequence idle
     ([5, 150, 64, 1, 99, 127], [5, 5, 1, 3, 0, 5], 5),   # thirty rows: two sequence tiles per weight tile
+    ([0, 40, 7, 90], [70, 65, 0, 33], 70),   # 280 rows (a prompt's worth): the body's phases as tiled matrix products
 ])
 def test_tiny_extend_block_of_positions(gpu, tiny, ctx, ext, m_max):
     """The first draft step over several new positions per sequence against the oracle's position-by-position
@@ -401,7 +403,7 @@ def test_tiny_extend_block_of_positions(gpu, tiny, ctx, ext, m_max):
 
 
 def test_tiny_extend_long_capacity_matrix_core_attention(gpu, tiny):
-    """A large capacity makes the splits long enough for the matrix-core attention and its separate merge launch."""
+    """A large capacity makes the splits long enough for the matrix-core attention (which merges its own splits)."""
     act = synth.make_activations(tiny["wl"], ctx=np.array([0, 31, 300, 1000], dtype=np.int32), capacity=32768)
     ext_len = np.array([3, 2, 3, 1], dtype=np.int32)
     hid, tok = extend_inputs(tiny["shape"], act, 3, 210)
