@@ -203,7 +203,7 @@ void launch_bgemv(int phase, const DraftParams &p, int step, int grid, size_t ld
 
 bool rows_gemm_serves(int phase, const DraftParams &p) {
     const int K = phase == BG_PROJ ? 2 * p.d : phase == BG_OPROJ ? p.qd : phase == BG_DOWN ? p.F : p.d;
-    return K % kRgBK == 0;
+    return K % (2 * kRgBK) == 0;
 }
 void launch_rows_gemm(int phase, const DraftParams &p, int step, hipStream_t st) {
     auto rows16 = [](int rows) { return (rows + 15) / 16 * 16; };

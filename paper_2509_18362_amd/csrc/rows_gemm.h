@@ -16,7 +16,7 @@
 
 namespace mtp {
 
-constexpr int kRgBK = 32;
+constexpr int kRgBK = 32; // elements per reduction step; the loop takes two steps per round
 constexpr int kRgRow = kRgBK * 2 + 16; // bytes per LDS row
 
 // 128 x 256 (the output head, gate/up at many rows): 80 KB, two workgroups per CU.  64 x 128: 40 KB; phases with
@@ -111,18 +111,27 @@ __device__ __forceinline__ void rows_gemm(const DraftParams &pin, Make make_phas
     }
     const int w_dst = (int)offsetof(L, w) + (tid >> 2) * kRgRow + lchunk * 16;
     constexpr int kStageA = BM * kRgRow, kStageW = BN * kRgRow; // a stage of each array
-    u32x4 pa[NAP], pw[NWP];
-    auto fetch = [&](int ks) {
-        pa[0] = ldg16(a_src + ks * kRgBK);
-        if (NAP == 2) pa[NAP - 1] = ldg16(a_src + p.a_lo + ks * kRgBK);
-#pragma unroll
-        for (int h = 0; h < NWP; ++h) pw[h] = ldg16(w_src[h] + ks * kRgBK);
+    // Two sets of registers: the pieces of step k + 2 are requested while step k is multiplied and those of step k + 1
+    // wait to be parked, so a request has two steps' time to arrive (one step is shorter than a trip to L2).  Requests
+    // past the last step repeat it (in bounds, parked into the buffer nobody reads any more): no branch around a load,
+    // which would make the compiler wait for all loads in flight.  The host admits reduction lengths of whole pairs of
+    // steps only.
+    struct Pieces {
+        u32x4 a[NAP], w[NWP];
     };
-    auto park = [&](int st) {
-        *reinterpret_cast<u32x4 *>(smem + a_dst + st * kStageA) = pa[0];
-        if (NAP == 2) *reinterpret_cast<u32x4 *>(smem + a_dst + (int)(offsetof(L, a_lo) - offsetof(L, a_hi)) + st * kStageA) = pa[NAP - 1];
+    auto fetch = [&](Pieces &q, int ks) {
+        ks = min(ks, nk - 1);
+        q.a[0] = ldg16(a_src + ks * kRgBK);
+        if (NAP == 2) q.a[NAP - 1] = ldg16(a_src + p.a_lo + ks * kRgBK);
 #pragma unroll
-        for (int h = 0; h < NWP; ++h) *reinterpret_cast<u32x4 *>(smem + w_dst + h * 128 * kRgRow + st * kStageW) = pw[h];
+        for (int h = 0; h < NWP; ++h) q.w[h] = ldg16(w_src[h] + ks * kRgBK);
+    };
+    auto park = [&](const Pieces &q, int st) {
+        *reinterpret_cast<u32x4 *>(smem + a_dst + st * kStageA) = q.a[0];
+        if (NAP == 2)
+            *reinterpret_cast<u32x4 *>(smem + a_dst + (int)(offsetof(L, a_lo) - offsetof(L, a_hi)) + st * kStageA) = q.a[NAP - 1];
+#pragma unroll
+        for (int h = 0; h < NWP; ++h) *reinterpret_cast<u32x4 *>(smem + w_dst + h * 128 * kRgRow + st * kStageW) = q.w[h];
     };
 
     const int wm = wave >> 2, wn = wave & 3; // the wave's piece: rows (BM/2) wm .., weight rows (BN/4) wn ..
@@ -131,13 +140,7 @@ __device__ __forceinline__ void rows_gemm(const DraftParams &pin, Make make_phas
     for (int ti = 0; ti < TI; ++ti)
 #pragma unroll
         for (int tj = 0; tj < TJ; ++tj) acc[ti][tj] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    fetch(0);
-    park(0);
-    __syncthreads();
-    for (int ks = 0; ks < nk; ++ks) {
-        const int st = ks & 1;
-        if (ks + 1 < nk) fetch(ks + 1);
+    auto multiply = [&](int st) {
         u32x4 ah[TI], al[TI];
 #pragma unroll
         for (int ti = 0; ti < TI; ++ti) {
@@ -155,7 +158,21 @@ __device__ __forceinline__ void rows_gemm(const DraftParams &pin, Make make_phas
                 acc[ti][tj] = a;
             }
         }
-        if (ks + 1 < nk) park(st ^ 1); // everyone left that buffer at the barrier of the step before
+    };
+
+    Pieces q0, q1;
+    fetch(q0, 0);
+    park(q0, 0);
+    fetch(q1, 1);
+    __syncthreads();
+    for (int ks = 0; ks < nk; ks += 2) { // nk is even
+        fetch(q0, ks + 2);
+        multiply(0);
+        park(q1, 1); // step ks + 1; everyone left that buffer at the barrier of the step before
+        __syncthreads();
+        fetch(q1, ks + 3);
+        multiply(1);
+        park(q0, 0); // step ks + 2
         __syncthreads();
     }
 
