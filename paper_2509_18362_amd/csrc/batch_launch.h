@@ -18,7 +18,7 @@ int batch_epilogue_grid(int phase, const DraftParams &p, int na);
 void launch_bprep(const DraftParams &p, int step, hipStream_t st);
 
 // a matrix phase (BG_* index) over all p.B rows as one tiled matrix product (rows_gemm.h); the output head leaves
-// logits only, no candidates.  rows_gemm_serves: the phase's reduction length is a whole number of the tiling's pairs of steps
+// logits only, no candidates.  rows_gemm_serves: the phase's reduction length is a whole number of the tilings' rounds of steps
 bool rows_gemm_serves(int phase, const DraftParams &p);
 void launch_rows_gemm(int phase, const DraftParams &p, int step, hipStream_t st);
 

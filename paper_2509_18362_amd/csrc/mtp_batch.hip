@@ -79,17 +79,17 @@ template <int PH>
 __global__ __launch_bounds__(kBlock, 4) void k_rows_gemm(DraftParams p, int step) {
     extern __shared__ __align__(16) char smem[];
     if constexpr (PH == BG_PROJ)
-        rows_gemm<64, 128, BgProj>(p, [](const DraftParams &q) { return BgProj(q); }, smem);
+        rows_gemm<64, 128, 4, BgProj>(p, [](const DraftParams &q) { return BgProj(q); }, smem);
     else if constexpr (PH == BG_QKV)
-        rows_gemm<64, 128, BgQkv>(p, [](const DraftParams &q) { return BgQkv(q); }, smem);
+        rows_gemm<64, 128, 4, BgQkv>(p, [](const DraftParams &q) { return BgQkv(q); }, smem);
     else if constexpr (PH == BG_OPROJ)
-        rows_gemm<64, 128, BgOproj>(p, [](const DraftParams &q) { return BgOproj(q); }, smem);
+        rows_gemm<64, 128, 4, BgOproj>(p, [](const DraftParams &q) { return BgOproj(q); }, smem);
     else if constexpr (PH == BG_GATEUP)
-        rows_gemm<64, 128, BgGateUp>(p, [](const DraftParams &q) { return BgGateUp(q); }, smem);
+        rows_gemm<64, 128, 4, BgGateUp>(p, [](const DraftParams &q) { return BgGateUp(q); }, smem);
     else if constexpr (PH == BG_DOWN)
-        rows_gemm<64, 128, BgDown>(p, [](const DraftParams &q) { return BgDown(q); }, smem);
+        rows_gemm<64, 128, 4, BgDown>(p, [](const DraftParams &q) { return BgDown(q); }, smem);
     else
-        rows_gemm<128, 256, BgHeadLogits>(p, [step](const DraftParams &q) { return BgHeadLogits(q, step); }, smem);
+        rows_gemm<128, 256, 2, BgHeadLogits>(p, [step](const DraftParams &q) { return BgHeadLogits(q, step); }, smem);
 }
 
 template <int G, int HD>
@@ -203,7 +203,7 @@ void launch_bgemv(int phase, const DraftParams &p, int step, int grid, size_t ld
 
 bool rows_gemm_serves(int phase, const DraftParams &p) {
     const int K = phase == BG_PROJ ? 2 * p.d : phase == BG_OPROJ ? p.qd : phase == BG_DOWN ? p.F : p.d;
-    return K % (2 * kRgBK) == 0;
+    return K % (kRgRound * kRgBK) == 0;
 }
 void launch_rows_gemm(int phase, const DraftParams &p, int step, hipStream_t st) {
     auto rows16 = [](int rows) { return (rows + 15) / 16 * 16; };

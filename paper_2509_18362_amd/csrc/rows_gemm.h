@@ -16,7 +16,8 @@
 
 namespace mtp {
 
-constexpr int kRgBK = 32; // elements per reduction step; the loop takes two steps per round
+constexpr int kRgBK = 32; // elements per reduction step
+constexpr int kRgRound = 4; // the longest round of steps of any tiling (the host checks reduction lengths against it)
 constexpr int kRgRow = kRgBK * 2 + 16; // bytes per LDS row
 
 // 128 x 256 (the output head, gate/up at many rows): 80 KB, two workgroups per CU.  64 x 128: 40 KB; phases with
@@ -64,7 +65,7 @@ struct BgHeadLogits : BgBase {
 
 // pin: the DraftParams of the launch (all rows); the phase object is built on a copy whose (b0, nb) name the
 // workgroup's rows, which is what the epilogues index with.
-template <int BM, int BN, class Ph, class Make>
+template <int BM, int BN, int PF, class Ph, class Make>
 __device__ __forceinline__ void rows_gemm(const DraftParams &pin, Make make_phase, char *smem) {
     using L = RowsGemmLds<BM, BN>;
     constexpr int NMAT = Ph::NMAT;
@@ -111,11 +112,12 @@ __device__ __forceinline__ void rows_gemm(const DraftParams &pin, Make make_phas
     }
     const int w_dst = (int)offsetof(L, w) + (tid >> 2) * kRgRow + lchunk * 16;
     constexpr int kStageA = BM * kRgRow, kStageW = BN * kRgRow; // a stage of each array
-    // Two sets of registers: the pieces of step k + 2 are requested while step k is multiplied and those of step k + 1
-    // wait to be parked, so a request has two steps' time to arrive (one step is shorter than a trip to L2).  Requests
-    // past the last step repeat it (in bounds, parked into the buffer nobody reads any more): no branch around a load,
-    // which would make the compiler wait for all loads in flight.  The host admits reduction lengths of whole pairs of
-    // steps only.
+    // PF sets of registers: the pieces of step k + PF are requested while step k is multiplied and those of steps
+    // k + 1 .. k + PF - 1 wait to be parked, so a request has PF steps' time to arrive (one step is shorter than a trip
+    // to L2).  Requests past the last step repeat it (in bounds, parked into the buffer nobody reads any more): no
+    // branch around a load, which would make the compiler wait for all loads in flight.  The host admits reduction
+    // lengths of whole rounds of PF steps only.
+    static_assert(PF % 2 == 0, "a round starts on LDS buffer 0");
     struct Pieces {
         u32x4 a[NAP], w[NWP];
     };
@@ -160,20 +162,20 @@ __device__ __forceinline__ void rows_gemm(const DraftParams &pin, Make make_phas
         }
     };
 
-    Pieces q0, q1;
-    fetch(q0, 0);
-    park(q0, 0);
-    fetch(q1, 1);
+    Pieces q[PF];
+    fetch(q[0], 0);
+    park(q[0], 0);
+#pragma unroll
+    for (int u = 1; u < PF; ++u) fetch(q[u], u);
     __syncthreads();
-    for (int ks = 0; ks < nk; ks += 2) { // nk is even
-        fetch(q0, ks + 2);
-        multiply(0);
-        park(q1, 1); // step ks + 1; everyone left that buffer at the barrier of the step before
-        __syncthreads();
-        fetch(q1, ks + 3);
-        multiply(1);
-        park(q0, 0); // step ks + 2
-        __syncthreads();
+    for (int ks = 0; ks < nk; ks += PF) { // nk is a multiple of PF
+#pragma unroll
+        for (int u = 0; u < PF; ++u) {
+            fetch(q[u], ks + u + PF);             // q[u] held step ks + u, parked a step ago
+            multiply(u & 1);
+            park(q[(u + 1) % PF], (u + 1) & 1);   // step ks + u + 1; everyone left that buffer at the last barrier
+            __syncthreads();
+        }
     }
 
     // the tiles are dead: the rows' norm scales take their place (the barrier above ended the last reads)
