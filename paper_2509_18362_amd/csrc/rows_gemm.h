@@ -90,14 +90,19 @@ __device__ __forceinline__ void rows_gemm(const DraftParams &pin, Make make_phas
     p.nb = min(BM, pin.B - p.b0);
 
     // global -> LDS: a thread moves 16-byte pieces of the 64-byte row slices, always chunk tid % 4 of its rows.
-    // BM = 128: row tid / 4 of the activations, hi and lo; BM = 64: the lower half of the threads the hi rows, the
-    // upper half the lo rows.  Weights: rows tid / 4 (+ 128).
-    constexpr int NAP = BM * 8 / kBlock, NWP = BN * 4 / kBlock;
-    static_assert(NAP == 1 || NAP == 2, "activation pieces per thread");
+    // Activations, BM >= 128: rows tid / 4 (+ 128, ...), hi and lo of each; BM = 64: the lower half of the threads the
+    // hi rows, the upper half the lo rows.  Weights: rows tid / 4 (+ 128, ...).
+    constexpr int NAR = BM >= 128 ? BM / 128 : 1;  // activation rows per thread
+    constexpr int NAP = BM >= 128 ? 2 * NAR : 1;   // activation pieces per thread (hi, lo of each row)
+    constexpr int NWP = BN * 4 / kBlock;
+    static_assert(BM == 64 || BM % 128 == 0, "activation rows per thread");
     const int lchunk = tid & 3;
-    const bool upper = NAP == 1 && tid >= kBlock / 2;
-    const int arow = NAP == 2 ? tid >> 2 : (tid & (kBlock / 2 - 1)) >> 2;
-    const uint16_t *a_src = ph.in + (size_t)min(p.b0 + arow, pin.B - 1) * p.a_stride + (upper ? p.a_lo : 0) + lchunk * 8;
+    const bool upper = BM == 64 && tid >= kBlock / 2;
+    const int arow = BM == 64 ? (tid & (kBlock / 2 - 1)) >> 2 : tid >> 2;
+    const uint16_t *a_src[NAR];
+#pragma unroll
+    for (int i = 0; i < NAR; ++i)
+        a_src[i] = ph.in + (size_t)min(p.b0 + arow + 128 * i, pin.B - 1) * p.a_stride + (upper ? p.a_lo : 0) + lchunk * 8;
     const int a_dst = (int)(upper ? offsetof(L, a_lo) : offsetof(L, a_hi)) + arow * kRgRow + lchunk * 16;
     const uint16_t *w_src[NWP];
 #pragma unroll
@@ -123,15 +128,21 @@ __device__ __forceinline__ void rows_gemm(const DraftParams &pin, Make make_phas
     };
     auto fetch = [&](Pieces &q, int ks) {
         ks = min(ks, nk - 1);
-        q.a[0] = ldg16(a_src + ks * kRgBK);
-        if (NAP == 2) q.a[NAP - 1] = ldg16(a_src + p.a_lo + ks * kRgBK);
+#pragma unroll
+        for (int i = 0; i < NAR; ++i) {
+            q.a[i] = ldg16(a_src[i] + ks * kRgBK);
+            if (NAP > 1) q.a[NAP - 1 - i] = ldg16(a_src[i] + p.a_lo + ks * kRgBK); // lo of row i in slot NAP-1-i
+        }
 #pragma unroll
         for (int h = 0; h < NWP; ++h) q.w[h] = ldg16(w_src[h] + ks * kRgBK);
     };
     auto park = [&](const Pieces &q, int st) {
-        *reinterpret_cast<u32x4 *>(smem + a_dst + st * kStageA) = q.a[0];
-        if (NAP == 2)
-            *reinterpret_cast<u32x4 *>(smem + a_dst + (int)(offsetof(L, a_lo) - offsetof(L, a_hi)) + st * kStageA) = q.a[NAP - 1];
+        constexpr int kLo = (int)(offsetof(L, a_lo) - offsetof(L, a_hi));
+#pragma unroll
+        for (int i = 0; i < NAR; ++i) {
+            *reinterpret_cast<u32x4 *>(smem + a_dst + i * 128 * kRgRow + st * kStageA) = q.a[i];
+            if (NAP > 1) *reinterpret_cast<u32x4 *>(smem + a_dst + kLo + i * 128 * kRgRow + st * kStageA) = q.a[NAP - 1 - i];
+        }
 #pragma unroll
         for (int h = 0; h < NWP; ++h) *reinterpret_cast<u32x4 *>(smem + w_dst + h * 128 * kRgRow + st * kStageW) = q.w[h];
     };
@@ -143,20 +154,19 @@ __device__ __forceinline__ void rows_gemm(const DraftParams &pin, Make make_phas
 #pragma unroll
         for (int tj = 0; tj < TJ; ++tj) acc[ti][tj] = f32x4{0.f, 0.f, 0.f, 0.f};
     auto multiply = [&](int st) {
-        u32x4 ah[TI], al[TI];
+        u32x4 wf[TJ];
+#pragma unroll
+        for (int tj = 0; tj < TJ; ++tj)
+            wf[tj] = *reinterpret_cast<const u32x4 *>(&s.w[st][(BN / 4) * wn + 16 * tj + i16][g * 16]);
 #pragma unroll
         for (int ti = 0; ti < TI; ++ti) {
-            ah[ti] = *reinterpret_cast<const u32x4 *>(&s.a_hi[st][(BM / 2) * wm + 16 * ti + i16][g * 16]);
-            al[ti] = *reinterpret_cast<const u32x4 *>(&s.a_lo[st][(BM / 2) * wm + 16 * ti + i16][g * 16]);
-        }
+            const u32x4 ah = *reinterpret_cast<const u32x4 *>(&s.a_hi[st][(BM / 2) * wm + 16 * ti + i16][g * 16]);
+            const u32x4 al = *reinterpret_cast<const u32x4 *>(&s.a_lo[st][(BM / 2) * wm + 16 * ti + i16][g * 16]);
 #pragma unroll
-        for (int tj = 0; tj < TJ; ++tj) {
-            const u32x4 wf = *reinterpret_cast<const u32x4 *>(&s.w[st][(BN / 4) * wn + 16 * tj + i16][g * 16]);
-#pragma unroll
-            for (int ti = 0; ti < TI; ++ti) {
+            for (int tj = 0; tj < TJ; ++tj) {
                 f32x4 a = acc[ti][tj];
-                a = mfma16(ah[ti], wf, a);
-                a = mfma16(al[ti], wf, a);
+                a = mfma16(ah, wf[tj], a);
+                a = mfma16(al, wf[tj], a);
                 acc[ti][tj] = a;
             }
         }
