@@ -180,12 +180,20 @@ __global__ __launch_bounds__(256) void k_train_row_ce(const float *__restrict__ 
     const int head = (int)((4 - (((size_t)blockIdx.x * V) & 3)) & 3); // elements before the first aligned one
     const int nvec = V > head ? (V - head) / 4 : 0;
     const f32x4 *z4 = reinterpret_cast<const f32x4 *>(z + head);
-    for (int i = threadIdx.x; i < nvec; i += 256) {
+    int i = threadIdx.x;
+    for (; i + 3 * 256 < nvec; i += 4 * 256) { // four loads in flight per thread
+        const f32x4 v0 = z4[i], v1 = z4[i + 256], v2 = z4[i + 512], v3 = z4[i + 768];
+        take(v0.x, v0.y, v0.z, v0.w);
+        take(v1.x, v1.y, v1.z, v1.w);
+        take(v2.x, v2.y, v2.z, v2.w);
+        take(v3.x, v3.y, v3.z, v3.w);
+    }
+    for (; i < nvec; i += 256) {
         const f32x4 v = z4[i];
         take(v.x, v.y, v.z, v.w);
     }
-    for (int i = threadIdx.x; i < V; i += 256) // the few elements outside the aligned middle
-        if (i < head || i >= head + nvec * 4) take(z[i], -INFINITY, -INFINITY, -INFINITY);
+    for (int e = threadIdx.x; e < V; e += 256) // the few elements outside the aligned middle
+        if (e < head || e >= head + nvec * 4) take(z[e], -INFINITY, -INFINITY, -INFINITY);
     float wm = m;
 #pragma unroll
     for (int off = 1; off < kWave; off <<= 1) wm = fmaxf(wm, __shfl_xor(wm, off, kWave));
