@@ -85,7 +85,7 @@ __global__ __launch_bounds__(kBlock, 4) void k_rows_gemm(DraftParams p, int step
     else if constexpr (PH == BG_OPROJ)
         rows_gemm<64, 128, 4, BgOproj>(p, [](const DraftParams &q) { return BgOproj(q); }, smem);
     else if constexpr (PH == BG_GATEUP)
-        rows_gemm<64, 128, 4, BgGateUp>(p, [](const DraftParams &q) { return BgGateUp(q); }, smem);
+        rows_gemm<128, 128, 4, BgGateUp>(p, [](const DraftParams &q) { return BgGateUp(q); }, smem);
     else if constexpr (PH == BG_DOWN)
         rows_gemm<64, 128, 4, BgDown>(p, [](const DraftParams &q) { return BgDown(q); }, smem);
     else
@@ -210,6 +210,9 @@ void launch_rows_gemm(int phase, const DraftParams &p, int step, hipStream_t st)
     auto small = [&](bg_kernel_t k, int n) {
         hipLaunchKernelGGL(k, dim3(rows_gemm_grid<64, 128>(p.B, n)), dim3(kBlock), sizeof(RowsGemmLds<64, 128>), st, p, step);
     };
+    auto mid = [&](bg_kernel_t k, int n) {
+        hipLaunchKernelGGL(k, dim3(rows_gemm_grid<128, 128>(p.B, n)), dim3(kBlock), sizeof(RowsGemmLds<128, 128>), st, p, step);
+    };
     auto large = [&](bg_kernel_t k, int n) {
         hipLaunchKernelGGL(k, dim3(rows_gemm_grid<128, 256>(p.B, n)), dim3(kBlock), sizeof(RowsGemmLds<128, 256>), st, p, step);
     };
@@ -217,7 +220,7 @@ void launch_rows_gemm(int phase, const DraftParams &p, int step, hipStream_t st)
     case BG_PROJ: small(k_rows_gemm<BG_PROJ>, p.d); break;
     case BG_QKV: small(k_rows_gemm<BG_QKV>, rows16(p.qkv_dim)); break;
     case BG_OPROJ: small(k_rows_gemm<BG_OPROJ>, p.d); break;
-    case BG_GATEUP: small(k_rows_gemm<BG_GATEUP>, 2 * rows16(p.F)); break;
+    case BG_GATEUP: mid(k_rows_gemm<BG_GATEUP>, 2 * rows16(p.F)); break;
     case BG_DOWN: small(k_rows_gemm<BG_DOWN>, p.d); break;
     default: large(k_rows_gemm<BG_LMHEAD>, rows16(p.n)); break;
     }
