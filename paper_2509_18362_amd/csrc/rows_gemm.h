@@ -172,6 +172,26 @@ __device__ __forceinline__ void rows_gemm(const DraftParams &pin, Make make_phas
         }
     };
 
+    // s_b = 1/sqrt(mean(u_b^2) + eps) of the workgroup's rows from the producer's per-tile sums of squares: kBlock / BM
+    // threads per row, asked for here (eight loads at a time) so that the epilogue finds it in a register
+    constexpr int TPR = kBlock / BM;
+    float my_scale = 0.f;
+    if (Ph::SCALE >= 0) {
+        const int npart = p.d / 16, sub = tid & (TPR - 1);
+        const float *part = p.ssq + ((size_t)Ph::SCALE * p.max_batch + min(p.b0 + tid / TPR, pin.B - 1)) * npart;
+        float sum = 0.f;
+        for (int i0 = sub; i0 < npart; i0 += TPR * 8) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = i0 + u * TPR < npart ? part[i0 + u * TPR] : 0.f;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) sum += v[u];
+        }
+#pragma unroll
+        for (int off = 1; off < TPR; off <<= 1) sum += __shfl_xor(sum, off, kWave);
+        my_scale = 1.0f / sqrtf(sum / (float)p.d + p.eps);
+    }
+
     Pieces q[PF];
     fetch(q[0], 0);
     park(q[0], 0);
@@ -191,17 +211,7 @@ __device__ __forceinline__ void rows_gemm(const DraftParams &pin, Make make_phas
     // the tiles are dead: the rows' norm scales take their place (the barrier above ended the last reads)
     float *scale = reinterpret_cast<float *>(smem);
     if (Ph::SCALE >= 0) {
-        // s_b = 1/sqrt(mean(u_b^2) + eps) from the producer's per-tile sums of squares, four threads per row
-        const int npart = p.d / 16;
-        for (int row = tid >> 2; row < BM; row += kBlock / 4) {
-            const int sub = tid & 3, b = min(p.b0 + row, pin.B - 1);
-            const float *part = p.ssq + ((size_t)Ph::SCALE * p.max_batch + b) * npart;
-            float sum = 0.f;
-            for (int i = sub; i < npart; i += 4) sum += part[i];
-            sum += __shfl_xor(sum, 1, kWave);
-            sum += __shfl_xor(sum, 2, kWave);
-            if (sub == 0) scale[row] = 1.0f / sqrtf(sum / (float)p.d + p.eps);
-        }
+        if ((tid & (TPR - 1)) == 0) scale[tid / TPR] = my_scale;
         __syncthreads();
     }
     // D[i][j] of a 16 x 16 tile: lane (i16, g) holds rows 4 g + v (v = 0..3), weight row i16 - the batched core's layout
