@@ -509,6 +509,7 @@ def test_tiny_extend_then_continue(gpu, tiny):
     ([10, 20, 150, 64], [1, 1, 0, 0]),
     ([0, 1, 63, 64, 150, 7, 99], [0, 0, 0, 1, 1, -1, -1]),        # batched phases
     (list(range(3, 123, 6)), [2] * 9 + [0] * 6 + [1] * 5),        # twenty sequences, two sequence tiles
+    ([(7 * i) % 150 for i in range(270)], [1] * 100 + [-1] * 90 + [0] * 80),  # 270: tiled body phases, passes per list
 ])
 def test_tiny_one_list_per_sequence(gpu, tiny, ctx, seq_subset):
     """Several id lists in one batch (several languages): every sequence against the oracle run with its own list
