@@ -84,15 +84,17 @@ def main() -> int:
     ap.add_argument("--launch-mode", default="auto", choices=("auto", "per-phase", "single"),
                     help="how the library enqueues a call: one launch per phase, or one cooperative launch for all "
                          "phases of all K steps; auto times both briefly for one sequence and keeps the faster")
-    ap.add_argument("--extend", type=int, default=0,
+    ap.add_argument("--extend", type=int, default=4,
                     help="also time the first draft step over a block of this many new positions per sequence "
-                         "(mtp_draft_extend); reported beside the main figures, never part of `value`")
-    ap.add_argument("--list-builder", type=int, default=0, metavar="LOG2_TOKENS",
+                         "(mtp_draft_extend); reported beside the main figures, never part of `value`; 0: skip")
+    ap.add_argument("--list-builder", type=int, default=26, metavar="LOG2_TOKENS",
                     help="also time the high-frequency list builder (mtp_subset_build) on a synthetic long-tailed "
                          "stream of 2^LOG2_TOKENS tokens over this workload's vocabulary")
-    ap.add_argument("--train-loss", type=int, default=0, metavar="POSITIONS",
+    ap.add_argument("--train-loss", type=int, default=512, metavar="POSITIONS",
                     help="also time the teacher-forced K-step forward with its weighted cross-entropy "
                          "(mtp_train_loss, K = 3, beta = 0.6) over this many positions")
+    ap.add_argument("--no-next-rows", action="store_true",
+                    help="skip the three side measurements above (block of positions, list builder, training forward)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full-vocab", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
@@ -105,6 +107,8 @@ def main() -> int:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding are part of it); "
               "run with --gpus 1", file=sys.stderr)
         return 2
+    if args.no_next_rows:
+        args.extend = args.list_builder = args.train_loss = 0
 
     import numpy as np
     import torch
