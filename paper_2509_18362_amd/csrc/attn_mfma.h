@@ -24,18 +24,23 @@
 
 namespace mtp {
 
-template <int G, int HD>
+// JP: positions of one sequence served together (a block of new positions whose keys and values are in the cache
+// already): their query heads sit side by side in the MFMA columns, NC = G * JP of 16, and share every key/value read.
+template <int G, int HD, int JP = 1>
 struct AttnMfmaLds {
     static constexpr int VS = HD * 2 + 16;  // bytes per parked V row
     static constexpr bool VREG = HD == 128;  // V goes from the load registers straight into the MFMA operand
     static constexpr int NSTREAM = kWaves + 1; // one softmax stream per wave, one for the token being appended
-    float q[G][HD];
-    float cs[HD / 2], sn[HD / 2];
+    static constexpr int NC = G * JP;          // query columns: (position, head of the group)
+    static_assert(NC <= 16, "the columns of one MFMA tile");
+    float q[NC][HD];
+    float cs[JP][HD / 2], sn[JP][HD / 2];
     float knew[HD], vnew[HD];
-    float acc[NSTREAM][G][HD];
-    float ml[NSTREAM][G][2];
+    float acc[NSTREAM][NC][HD];
+    float ml[NSTREAM][NC][2];
     alignas(16) unsigned char v[VREG ? 1 : kWaves][VREG ? 1 : 32][VS];
     alignas(16) unsigned char k[kWaves][16][VS]; // one K tile per wave on its way into the MFMA operand layout
+    int len[JP], last[JP];                       // JP > 1: the positions' lengths, and whose splits this item completed
 };
 
 // TICKET: as in phase_attn, the workgroup whose split of a (sequence, KV head) finishes last merges the splits.
@@ -44,9 +49,14 @@ struct AttnMfmaLds {
 // launch waiting for the workgroup that happened to get the long ones.  The counter only grows, so every workgroup
 // draws a number past the end and leaves; the last one to leave (p.attn_queue[1] counts them) puts both words back
 // to zero for the next launch.
-template <int G, int HD, bool COH = false, bool TICKET = false, class Hook = NoHook, bool QUEUE = false>
+// JP > 1 (needs p.kv_appended and TICKET): an item is (sequence, KV head, split, group of JP positions); position j of
+// sequence b is row j * p.ext_B + b of the call and sees the cache up to its own slot, so the columns of an item differ
+// only in where their tokens end.
+template <int G, int HD, bool COH = false, bool TICKET = false, class Hook = NoHook, bool QUEUE = false, int JP = 1>
 __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb, char *smem, Hook before_q = Hook()) {
-    using L = AttnMfmaLds<G, HD>;
+    using L = AttnMfmaLds<G, HD, JP>;
+    constexpr int NC = L::NC;
+    static_assert(JP == 1 || TICKET, "blocks of positions merge their splits by ticket");
     constexpr int NS = HD / 32;        // MFMA depth steps over the head dimension
     constexpr int NDB = HD / 16;       // 16-dimension blocks of the output
     constexpr int LPT = HD / 8;        // lanes per V row in a wave-wide load
@@ -58,7 +68,10 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int i16 = lane & 15, g4 = lane >> 4;
     const int T = p.split_tokens, S = p.max_splits;
-    const int n_items = p.B * p.Hkv * S;
+    const int nseq = JP > 1 ? p.ext_B : p.B;             // sequences whose caches are read
+    const int mpos = JP > 1 ? p.B / p.ext_B : 1;         // positions per sequence
+    const int JG = (mpos + JP - 1) / JP;                 // groups of positions
+    const int n_items = nseq * p.Hkv * S * JG;
     const float scale = 1.0f / sqrtf((float)HD);
     const int PW = HD + 2; // floats per (head, split) partial: acc[HD], max, sum
 
@@ -85,10 +98,24 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
         }
         // split-major numbering: the splits of one (sequence, KV head) land on workgroups of different XCDs, and with
         // the counter the short final splits are drawn last
-        const int sp = item / (p.B * p.Hkv), b = item % (p.B * p.Hkv) / p.Hkv, kvh = item % p.Hkv;
-        const bool dead = seq_dead(p, b);
-        const int Lb = dead ? 0 : p.kv_len[b];
-        const int len = Lb + step + 1, pnew = len - 1;
+        const int kvh = item % p.Hkv, b = item / p.Hkv % nseq, jg = item / (p.Hkv * nseq) % JG,
+                  sp = item / (p.Hkv * nseq * JG);
+        bool dead;
+        int len = 0;      // tokens the longest position of the item sees
+        int lenj[JP];     // per position (0: not part of the block)
+        if constexpr (JP == 1) {
+            dead = seq_dead(p, b);
+            len = lenj[0] = (dead ? 0 : p.kv_len[b]) + step + 1;
+        } else {
+#pragma unroll
+            for (int jp = 0; jp < JP; ++jp) {
+                const int j = jg * JP + jp, r = min(j, mpos - 1) * nseq + b;
+                lenj[jp] = (j < mpos && !seq_dead(p, r)) ? p.kv_len[r] + step + 1 : 0;
+                len = max(len, lenj[jp]);
+            }
+            dead = len == 0;
+        }
+        const int pnew = len - 1;
         const int nsplit = (len + T - 1) / T;
         // a row that is not part of the block, or a split past the end of this context (uniform for the workgroup)
         if ((p.kv_appended && dead) || sp >= nsplit) {
@@ -134,18 +161,34 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
         }
 
         __syncthreads(); // LDS of the previous item is free
-        if (tid < HD / 2) rope_cos_sin(pnew, p.rope_inv[tid], s.cs[tid], s.sn[tid]);
+        for (int idx = tid; idx < JP * (HD / 2); idx += kBlock) {
+            const int jp = idx / (HD / 2), e = idx % (HD / 2);
+            int pos = pnew; // JP == 1
+            if constexpr (JP > 1) {
+                pos = 0;
+#pragma unroll
+                for (int u = 0; u < JP; ++u) pos = u == jp ? max(lenj[u] - 1, 0) : pos;
+            }
+            rope_cos_sin(pos, p.rope_inv[e], s.cs[jp][e], s.sn[jp][e]);
+        }
+        if constexpr (JP > 1) {
+#pragma unroll
+            for (int u = 0; u < JP; ++u)
+                if (tid == u) s.len[u] = lenj[u];
+        }
         __syncthreads();
-        for (int idx = tid; idx < G * HD / 2; idx += kBlock) {
-            int gq = idx / (HD / 2), jj = idx % (HD / 2);
-            const float *src = qkv + (size_t)(kvh * G + gq) * HD;
-            float a = ld_f32<COH>(src + jj), bb = ld_f32<COH>(src + jj + HD / 2), cs = s.cs[jj], sn = s.sn[jj];
+        for (int idx = tid; idx < NC * HD / 2; idx += kBlock) {
+            const int c = idx / (HD / 2), jj = idx % (HD / 2), jp = c / G, gq = c % G;
+            // the row the column's query comes from (a position past the block: any row, the column is not used)
+            const int row = JP > 1 ? min(jg * JP + jp, mpos - 1) * nseq + b : b;
+            const float *src = p.qkv + (size_t)row * p.qkv_dim + (size_t)(kvh * G + gq) * HD;
+            float a = ld_f32<COH>(src + jj), bb = ld_f32<COH>(src + jj + HD / 2), cs = s.cs[jp][jj], sn = s.sn[jp][jj];
             if (p.b_q) {
                 a += bf16_to_f32(p.b_q[(kvh * G + gq) * HD + jj]);
                 bb += bf16_to_f32(p.b_q[(kvh * G + gq) * HD + jj + HD / 2]);
             }
-            s.q[gq][jj] = (a * cs - bb * sn) * scale;
-            s.q[gq][jj + HD / 2] = (bb * cs + a * sn) * scale;
+            s.q[c][jj] = (a * cs - bb * sn) * scale;
+            s.q[c][jj + HD / 2] = (bb * cs + a * sn) * scale;
         }
         if (last) {
             uint16_t *kdst = p.k_cache + (((size_t)b * p.Hkv + kvh) * p.cap + pnew) * HD;
@@ -153,7 +196,7 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
             if (tid >= kWave * 4 && tid < kWave * 4 + HD / 2) {
                 int e = tid - kWave * 4;
                 const float *src = qkv + p.qd + (size_t)kvh * HD;
-                float a = ld_f32<COH>(src + e), bb = ld_f32<COH>(src + e + HD / 2), cs = s.cs[e], sn = s.sn[e];
+                float a = ld_f32<COH>(src + e), bb = ld_f32<COH>(src + e + HD / 2), cs = s.cs[0][e], sn = s.sn[0][e];
                 if (p.b_k) {
                     a += bf16_to_f32(p.b_k[kvh * HD + e]);
                     bb += bf16_to_f32(p.b_k[kvh * HD + e + HD / 2]);
@@ -176,13 +219,13 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
         }
         __syncthreads();
 
-        // the query operand: column i16 = query head, depth slot g4 holds elements g4*HD/4 + 8u .. +8 for step u
+        // the query operand: column i16 = (position, query head), depth slot g4 holds elements g4*HD/4 + 8u .. +8 for step u
         u32x4 qh[NS], ql[NS];
 #pragma unroll
         for (int u = 0; u < NS; ++u) {
             uint32_t h[4] = {0u, 0u, 0u, 0u}, l[4] = {0u, 0u, 0u, 0u};
-            if (i16 < G) {
-                const float *src = &s.q[i16 < G ? i16 : 0][g4 * (HD / 4) + u * 8];
+            if (i16 < NC) {
+                const float *src = &s.q[i16 < NC ? i16 : 0][g4 * (HD / 4) + u * 8];
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     uint16_t hh, ll;
@@ -195,6 +238,9 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
             ql[u] = u32x4{l[0], l[1], l[2], l[3]};
         }
 
+        // tokens of the split this lane's column sees: all of them, or up to its own position's end
+        int lim = ntok;
+        if constexpr (JP > 1) lim = min(max(s.len[min(i16 / G, JP - 1)] - t0, 0), ntok);
         float mx = -INFINITY, lsum = 0.f; // of head column i16, in units of log2
         f32x4 oacc[NDB];
 #pragma unroll
@@ -249,12 +295,12 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const int tok = it * 32 + (L::VREG ? e * 4 + g4 : (e >> 2) * 16 + g4 * 4 + (e & 3));
-                sv[e] = tok < ntok ? sv[e] : -INFINITY;
+                sv[e] = tok < lim ? sv[e] : -INFINITY;
                 tmax = fmaxf(tmax, sv[e]);
             }
             tmax = fmaxf(tmax, __shfl_xor(tmax, 16, kWave));
             tmax = fmaxf(tmax, __shfl_xor(tmax, 32, kWave));
-            const float mnew = fmaxf(mx, tmax); // finite: an iteration holds at least one token
+            const float mnew = fmaxf(mx, tmax); // finite for a column that has seen a token (others: -inf, weights 0)
             const float alpha = (mx == mnew) ? 1.0f : __builtin_amdgcn_exp2f(mx - mnew);
             mx = mnew;
             float pv[8], psum = 0.f;
@@ -326,7 +372,7 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
         // ---- merge the waves (and the token being appended) through LDS ----
         lsum += __shfl_xor(lsum, 16, kWave);
         lsum += __shfl_xor(lsum, 32, kWave);
-        if (i16 < G) {
+        if (i16 < NC) {
 #pragma unroll
             for (int db = 0; db < NDB; ++db) {
                 const float o[4] = {oacc[db].x, oacc[db].y, oacc[db].z, oacc[db].w};
@@ -339,43 +385,56 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
                 s.ml[wave][i16][1] = lsum;
             }
         }
-        if (wave < G) { // stream kWaves: the new token, score q . k_new from LDS
-            float a = 0.f;
-            for (int e = lane; e < HD; e += kWave) a += s.q[wave][e] * s.knew[e];
-            a = wave_sum(a);
-            if (lane == 0) {
-                s.ml[kWaves][wave][0] = last ? a : -INFINITY;
-                s.ml[kWaves][wave][1] = 1.0f;
+        if constexpr (JP == 1) {
+            if (wave < G) { // stream kWaves: the new token, score q . k_new from LDS
+                float a = 0.f;
+                for (int e = lane; e < HD; e += kWave) a += s.q[wave][e] * s.knew[e];
+                a = wave_sum(a);
+                if (lane == 0) {
+                    s.ml[kWaves][wave][0] = last ? a : -INFINITY;
+                    s.ml[kWaves][wave][1] = 1.0f;
+                }
+                for (int e = lane; e < HD; e += kWave) s.acc[kWaves][wave][e] = last ? s.vnew[e] : 0.f;
             }
-            for (int e = lane; e < HD; e += kWave) s.acc[kWaves][wave][e] = last ? s.vnew[e] : 0.f;
+        } else if (tid < NC) { // every key and value is in the cache: no stream of its own for a new token
+            s.ml[kWaves][tid][0] = -INFINITY;
+            s.ml[kWaves][tid][1] = 1.0f;
         }
         __syncthreads();
-        for (int o = tid; o < G * HD; o += kBlock) {
-            int g = o / HD, dd = o % HD;
+        for (int o = tid; o < NC * HD; o += kBlock) {
+            const int c = o / HD, dd = o % HD, jp = c / G, g = c % G;
+            // the column's row of the call, and its own number of splits
+            int row = b, nsplit_c = nsplit;
+            if constexpr (JP > 1) {
+                const int len_c = s.len[jp];
+                nsplit_c = (len_c + T - 1) / T;
+                if (len_c == 0 || sp >= nsplit_c) continue; // not part of the block, or this split is past its end
+                row = (jg * JP + jp) * nseq + b;
+            }
             float M = -INFINITY;
-            for (int st = 0; st < NSTREAM; ++st) M = fmaxf(M, s.ml[st][g][0]);
+            for (int st = 0; st < NSTREAM; ++st) M = fmaxf(M, s.ml[st][c][0]);
             float Ls = 0.f, A = 0.f;
             for (int st = 0; st < NSTREAM; ++st) {
-                float mm = s.ml[st][g][0];
+                float mm = s.ml[st][c][0];
                 if (mm != -INFINITY) {
                     float w = expf(mm - M);
-                    Ls += s.ml[st][g][1] * w;
-                    A += s.acc[st][g][dd] * w;
+                    Ls += s.ml[st][c][1] * w;
+                    A += s.acc[st][c][dd] * w;
                 }
             }
             int hq = kvh * G + g;
-            if (nsplit == 1) {
+            if (nsplit_c == 1) {
                 const float r = A / Ls;
-                st_f32<COH>(p.attn + (size_t)b * p.qd + (size_t)hq * HD + dd, r);
+                st_f32<COH>(p.attn + (size_t)row * p.qd + (size_t)hq * HD + dd, r);
                 if (p.attn_split) {
                     uint16_t h, l;
                     split_bf16(r, h, l);
-                    const size_t at = (size_t)b * p.a_stride + (size_t)hq * HD + dd;
+                    const size_t at = (size_t)row * p.a_stride + (size_t)hq * HD + dd;
                     p.attn_split[at] = h;
                     p.attn_split[p.a_lo + at] = l;
                 }
             } else {
-                float *dst = p.attn_part + (((size_t)b * p.Hq + hq) * S + sp) * PW;
+                float *dst = p.attn_part + (((size_t)row * p.Hq + hq) * S + sp) * PW;
                 st_f32<COH || TICKET>(dst + dd, A);
                 if (dd == 0) {
                     st_f32<COH || TICKET>(dst + HD, M);
@@ -387,16 +446,39 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
             int &last_to_arrive = *reinterpret_cast<int *>(smem + sizeof(L));
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
-            if (tid == 0) {
-                int *ticket = p.attn_ticket + (size_t)b * p.Hkv + kvh;
-                const int old = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if (old == nsplit - 1) __hip_atomic_store(ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                last_to_arrive = (old == nsplit - 1) ? 1 : 0;
+            if constexpr (JP == 1) {
+                if (tid == 0) {
+                    int *ticket = p.attn_ticket + (size_t)b * p.Hkv + kvh;
+                    const int old = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if (old == nsplit - 1) __hip_atomic_store(ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    last_to_arrive = (old == nsplit - 1) ? 1 : 0;
+                }
+                __syncthreads();
+                const bool merges = last_to_arrive != 0;
+                if (merges && wave < G)
+                    merge_head<HD, true, COH>(p, b, kvh * G + wave, nsplit, reinterpret_cast<float *>(smem) + (size_t)wave * S);
+            } else {
+                // one ticket per (row, KV head): a position counts the splits up to its own end
+                if (tid < JP) {
+                    const int len_c = s.len[tid], ns = (len_c + T - 1) / T;
+                    int done = 0;
+                    if (len_c > 0 && sp < ns && ns > 1) {
+                        int *ticket = p.attn_ticket + (size_t)((jg * JP + tid) * nseq + b) * p.Hkv + kvh;
+                        const int old = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        if (old == ns - 1) {
+                            __hip_atomic_store(ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            done = 1;
+                        }
+                    }
+                    s.last[tid] = done;
+                }
+                __syncthreads();
+                // s.len and s.last sit behind the tiles, the strips of the merge at the front of the LDS
+                for (int jp = 0; jp < JP; ++jp)
+                    if (s.last[jp] && wave < G)
+                        merge_head<HD, true, COH>(p, (jg * JP + jp) * nseq + b, kvh * G + wave, (s.len[jp] + T - 1) / T,
+                                                  reinterpret_cast<float *>(smem) + (size_t)wave * S);
             }
-            __syncthreads();
-            const bool merges = last_to_arrive != 0;
-            if (merges && wave < G)
-                merge_head<HD, true, COH>(p, b, kvh * G + wave, nsplit, reinterpret_cast<float *>(smem) + (size_t)wave * S);
             __syncthreads(); // the strips and the flag are free again before the next item touches the LDS
         }
         if (queue) next_item = hand_out();

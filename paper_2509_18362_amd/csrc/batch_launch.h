@@ -25,5 +25,9 @@ void launch_rows_gemm(int phase, const DraftParams &p, int step, hipStream_t st)
 // matrix-core attention (attn_mfma.h): dynamic LDS, and the launch for query-group size G and head dimension HD
 size_t attn_mfma_lds_bytes(int G, int HD);
 void launch_attn_mfma(int G, int HD, const DraftParams &p, int step, int grid, size_t lds, hipStream_t st);
+// the same for a block of new positions per sequence whose keys and values are in the cache (p.kv_appended, p.ext_B):
+// positions_per_item = 16 / G positions of a sequence share its key/value reads
+size_t attn_mfma_block_lds_bytes(int G, int HD);
+void launch_attn_mfma_block(int G, int HD, const DraftParams &p, int step, int grid, size_t lds, hipStream_t st);
 
 } // namespace mtp

@@ -99,7 +99,33 @@ __global__ __launch_bounds__(kBlock) void k_attn_mfma(DraftParams p, int step) {
     phase_attn_mfma<G, HD, false, true, NoHook, true>(p, step, blockIdx.x, gridDim.x, smem);
 }
 
+// a block of new positions per sequence (keys and values already in the cache): the positions of a sequence share its
+// key/value reads, 16 / G of them beside the G query heads in the MFMA columns
+template <int G, int HD>
+__global__ __launch_bounds__(kBlock) void k_attn_mfma_block(DraftParams p, int step) {
+    extern __shared__ __align__(16) char smem[];
+    phase_attn_mfma<G, HD, false, true, NoHook, true, 16 / G>(p, step, blockIdx.x, gridDim.x, smem);
+}
+
 typedef void (*bg_kernel_t)(DraftParams, int);
+bg_kernel_t attn_mfma_block_kernel(int G, int HD) {
+    if (HD == 128) {
+        switch (G) {
+        case 1: return k_attn_mfma_block<1, 128>;
+        case 2: return k_attn_mfma_block<2, 128>;
+        case 4: return k_attn_mfma_block<4, 128>;
+        case 8: return k_attn_mfma_block<8, 128>;
+        }
+    } else if (HD == 64) {
+        switch (G) {
+        case 1: return k_attn_mfma_block<1, 64>;
+        case 2: return k_attn_mfma_block<2, 64>;
+        case 4: return k_attn_mfma_block<4, 64>;
+        case 8: return k_attn_mfma_block<8, 64>;
+        }
+    }
+    return nullptr;
+}
 bg_kernel_t attn_mfma_kernel(int G, int HD) {
     if (HD == 128) {
         switch (G) {
@@ -172,8 +198,25 @@ size_t attn_mfma_lds_bytes(int G, int HD) {
     return 0;
 }
 
+size_t attn_mfma_block_lds_bytes(int G, int HD) {
+    switch (HD * 16 + G) {
+    case 128 * 16 + 1: return sizeof(AttnMfmaLds<1, 128, 16>);
+    case 128 * 16 + 2: return sizeof(AttnMfmaLds<2, 128, 8>);
+    case 128 * 16 + 4: return sizeof(AttnMfmaLds<4, 128, 4>);
+    case 128 * 16 + 8: return sizeof(AttnMfmaLds<8, 128, 2>);
+    case 64 * 16 + 1: return sizeof(AttnMfmaLds<1, 64, 16>);
+    case 64 * 16 + 2: return sizeof(AttnMfmaLds<2, 64, 8>);
+    case 64 * 16 + 4: return sizeof(AttnMfmaLds<4, 64, 4>);
+    case 64 * 16 + 8: return sizeof(AttnMfmaLds<8, 64, 2>);
+    }
+    return 0;
+}
+
 void launch_attn_mfma(int G, int HD, const DraftParams &p, int step, int grid, size_t lds, hipStream_t st) {
     hipLaunchKernelGGL(attn_mfma_kernel(G, HD), dim3(grid), dim3(kBlock), lds, st, p, step);
+}
+void launch_attn_mfma_block(int G, int HD, const DraftParams &p, int step, int grid, size_t lds, hipStream_t st) {
+    hipLaunchKernelGGL(attn_mfma_block_kernel(G, HD), dim3(grid), dim3(kBlock), lds, st, p, step);
 }
 
 bool batch_allow_lds(size_t lds_limit) {
@@ -184,7 +227,9 @@ bool batch_allow_lds(size_t lds_limit) {
     for (int hd = 64; hd <= 128; hd *= 2)
         for (int g = 1; g <= 8; g *= 2)
             ok = ok && hipFuncSetAttribute((const void *)attn_mfma_kernel(g, hd),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_limit) == hipSuccess;
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_limit) == hipSuccess &&
+                 hipFuncSetAttribute((const void *)attn_mfma_block_kernel(g, hd),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_limit) == hipSuccess;
     for (int ph = 0; ph < BG_COUNT; ++ph)
         for (int na = 1; na <= 4; na *= 2)
             ok = ok && hipFuncSetAttribute((const void *)pick(ph, na), hipFuncAttributeMaxDynamicSharedMemorySize,

@@ -748,7 +748,10 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
                  lds_down = gemv_lds_bytes(p.F, p.nb_down, 1),
                  lds_attn = std::max({attn_lds_bytes(p.Hq / p.Hkv, p.hd), attn_mfma_lds_bytes(p.Hq / p.Hkv, p.hd) + 64,
                                       (size_t)kWaves * p.max_splits * 4 + 64}); // incl. the merge's strips
-    const size_t lds_max = std::max({lds_proj, lds_d2, lds_q, lds_down, lds_attn});
+    // the matrix-core attention over a block of positions (sixteen query columns)
+    const size_t lds_attn_block = std::max(attn_mfma_block_lds_bytes(p.Hq / p.Hkv, p.hd) + 64,
+                                           (size_t)kWaves * p.max_splits * 4 + 64);
+    const size_t lds_max = std::max({lds_proj, lds_d2, lds_q, lds_down, lds_attn, ext ? lds_attn_block : 0});
     if (lds_max > h->lds_limit) return MTP_ERR_CONFIG;
 
     const int grid = std::min(h->num_cus, kMaxFusedGrid); // one 512-thread workgroup per CU: the register ring
@@ -834,7 +837,16 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
             hipLaunchKernelGGL(k_extend_append<128>, dim3(B, p.Hkv), dim3(192), 0, st, pa);
         else
             hipLaunchKernelGGL(k_extend_append<64>, dim3(B, p.Hkv), dim3(96), 0, st, pa);
-        launch_attention_of(pa, 0);
+        if (mfma_attn && ext->m_max > 1) {
+            // long splits: the positions of a sequence share its key/value reads (16 / G of them per item)
+            const int G = pa.Hq / pa.Hkv, jp = 16 / G, jg = (ext->m_max + jp - 1) / jp;
+            const int items = ext->B * pa.Hkv * pa.max_splits * jg;
+            const int grid_b = std::max(1, std::min(items, h->num_cus * 2));
+            pa.attn_queue = items > grid_b ? pa.attn_ticket + (size_t)c.max_batch * c.n_kv_heads : nullptr;
+            launch_attn_mfma_block(G, pa.hd, pa, 0, grid_b, lds_attn_block, st);
+        } else {
+            launch_attention_of(pa, 0);
+        }
     };
     auto launch = [&](int phase, phase_kernel_t fn, int g, size_t lds, int step) {
         mark_begin(phase, step);

@@ -412,6 +412,19 @@ def test_tiny_extend_long_capacity_matrix_core_attention(gpu, tiny):
     check_extend(ref, res, caches, act, ext_len)
 
 
+def test_tiny_extend_long_block_positions_share_the_cache_reads(gpu, tiny):
+    """Twenty positions per sequence with splits of 4096 tokens: the matrix-core attention serves eight positions of
+    a sequence per item (three groups, the last ragged), each position seeing the cache up to its own slot.  One block
+    crosses a split boundary (positions 4090 .. 4109: the later ones have a second split, the earlier ones not), one
+    sequence starts empty, one sits deep in its cache, one is idle, one has a block shorter than a group."""
+    act = synth.make_activations(tiny["wl"], ctx=np.array([4090, 0, 12000, 77, 8191], dtype=np.int32), capacity=32768)
+    ext_len = np.array([20, 20, 13, 0, 3], dtype=np.int32)
+    hid, tok = extend_inputs(tiny["shape"], act, 20, 212)
+    ref, res, caches = run_extend(gpu, tiny["shape"], tiny["w"], tiny["w"], act, [tiny["ids"]], 0, hid, tok, ext_len)
+    assert res["err"] == 0
+    check_extend(ref, res, caches, act, ext_len)
+
+
 def test_tiny_extend_overflow_and_then_draft(gpu, tiny):
     """A block that does not fit leaves its sequence alone and is reported; the other sequence is extended, and the
     recursive draft steps that follow start from the extended cache on both sides."""
