@@ -15,10 +15,17 @@
 //   O^T += V^T P  with the 16 dimensions of a block as rows and the heads as columns, contraction over the 32 tokens.
 //                 The eight probabilities a lane just computed are exactly the eight contraction elements the P
 //                 operand wants from it (tokens 4g..4g+3 of both tiles: the assignment of tokens to MFMA depth slots
-//                 is free as long as both operands agree), split into bf16 hi + lo.  V has to be transposed: the
-//                 wave parks its 32 V rows in a private LDS strip (row stride HD*2 + 16 bytes, which spreads the
-//                 four lane groups over different banks) and gathers eight 16-bit values per lane and block.
+//                 is free as long as both operands agree), split into bf16 hi + lo.  V has to be transposed.  At
+//                 head dimension 128 a lane's eight 16-byte loads hold eight dimensions of eight tokens: the score
+//                 tiles' rows are permuted (K passes through LDS anyway) so that these are the tokens of the lane's
+//                 eight probabilities, and the operand of output block j is element j of the eight loads (a byte
+//                 permute per pair), no LDS.  At head dimension 64 the wave parks its 32 V rows in a private LDS
+//                 strip (row stride HD*2 + 16 bytes, which spreads the four lane groups over different banks) and
+//                 gathers eight 16-bit values per lane and block.
 // Loads of the next iteration (16 KiB per wave) are in flight while the current one is computed.
+// Items (sequence, KV head, split) are numbered split-major and, when there are more of them than workgroups, handed
+// out through a counter.  For a block of new positions whose keys and values are already in the cache, 16 / G
+// positions of a sequence sit beside the G query heads in the columns and share every key/value read.
 #pragma once
 #include "phases.h"
 
