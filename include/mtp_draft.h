@@ -255,17 +255,20 @@ float mtp_last_draft_ms(mtp_handle *h);
  *   2 (default) automatic: mode 1 for one sequence whose reduction lengths are all at least 512 (where it is the
  *               faster one), mode 0 otherwise; if the device cannot take the cooperative launch at that moment
  *               (it needs every compute unit), mode 0 for that call.
- *   0           one launch per phase.  Up to four sequences: 7 or 8 launches per step plus one to publish the
- *               last draft id.  Five or more: the batched kernels (every weight read once per pass of up to 64
- *               sequences), one preparation launch per step, and one epilogue launch after each matrix phase whose
- *               reduction is split over workgroups.
+ *   0           one launch per phase.  One sequence: the row-streaming kernels, 7 or 8 launches per step plus one
+ *               to publish the last draft id.  Two or more (also the rows of a block of positions): the batched
+ *               kernels (every weight read once per pass of up to 64 sequences), one preparation launch per step,
+ *               and one epilogue launch after each matrix phase whose reduction is split over workgroups (above 16
+ *               sequences).  Matrices of 2 GiB or more: as mode 3.
  *   1           one cooperative launch runs all phases of all K steps (up to 16 sequences; otherwise as mode 0);
  *               phases are separated by grid-wide barriers inside the kernel.  A barrier that is not passed within
  *               ~2 s sets MTP_ERR_TIMEOUT.  For one sequence this is the faster mode (3-4 % at a 32768-row head,
  *               more with larger heads); for 2-16 sequences it is slower than mode 0.  The launch needs every
  *               compute unit of the device to itself.
- * Other values return MTP_ERR_MODE.  Results agree between the modes to rounding (bit for bit up to four
- * sequences).
+ *   3           as mode 0, with the row-streaming kernels for up to four sequences (slower from the second
+ *               sequence on; the form the library itself falls back to for matrices of 2 GiB or more).
+ * Other values return MTP_ERR_MODE.  Results agree between the modes to rounding (bit for bit for one
+ * sequence between modes 0, 1 and 2).
  */
 int32_t mtp_set_launch_mode(mtp_handle *h, int32_t mode);
 

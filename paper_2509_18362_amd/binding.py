@@ -33,7 +33,7 @@ EXPORTS = ["mtp_status_string", "mtp_workspace_bytes", "mtp_draft_init", "mtp_dr
            "mtp_accept",
            "mtp_poll_error", "mtp_set_timing", "mtp_last_draft_ms", "mtp_set_launch_mode", "mtp_set_phase_trace",
            "mtp_draft_destroy"]
-LAUNCH_PER_PHASE, LAUNCH_SINGLE, LAUNCH_AUTO = 0, 1, 2
+LAUNCH_PER_PHASE, LAUNCH_SINGLE, LAUNCH_AUTO, LAUNCH_ROWS = 0, 1, 2, 3
 # mtp_set_timing modes
 TIMING_OFF, TIMING_CALL = 0, 1
 PHASES = ["proj", "qkv", "attn", "oproj", "gateup", "down", "lmhead"]

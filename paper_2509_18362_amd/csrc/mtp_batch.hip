@@ -1,4 +1,4 @@
-// Kernels of the batched draft path (five or more sequences per call) for gfx950.
+// Kernels of the batched draft path (two or more sequences per call) for gfx950.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>

@@ -365,7 +365,8 @@ struct WsLayout {
 };
 
 // the batched path serves calls with this many sequences or more; fewer take the row-streaming kernels
-constexpr int kBatchMinSeq = 5;
+constexpr int kBatchMinSeq = 2;
+constexpr int kMaxRowSeq = 4;          // sequences the row-streaming kernels serve at once
 constexpr int kBatchPassSeq = 64;     // sequences per weight pass of the batched path
 constexpr int kBatchGroupTiles = 8;   // weight tiles per wave and group
 constexpr size_t kBatchTileBytes = 1024; // one 16 x 16 float tile of partial sums
@@ -855,10 +856,14 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
     };
     if (h->timing == 1) (void)hipEventRecord(h->ev[0], st);
 
-    // Five or more sequences: the batched kernels, every weight read once per pass of up to 64 sequences.  Their
-    // buffer loads address a matrix with 32-bit offsets and mark missing rows with an offset of 2 GiB.
+    // Two or more sequences (or rows of a block of positions): the batched kernels, every weight read once per pass of
+    // up to 64 sequences.  The row-streaming kernels serve up to four at once but at half their one-sequence rate from
+    // the second on (a block of four positions at a 32768-row head: 404 us against 234 here); they remain for one
+    // sequence, on request (mode 3), and for matrices of 2 GiB or more: the batched kernels' buffer loads address a
+    // matrix with 32-bit offsets and mark missing rows with an offset of 2 GiB.
     const size_t widest = std::max({(size_t)p.V * p.d, (size_t)p.d * 2 * p.d, (size_t)p.F * p.d, (size_t)p.qd * p.d}) * 2;
-    if (B >= kBatchMinSeq && h->mode != 1 && widest < ((size_t)1 << 31)) { // (mode 1 beyond 16 sequences: see above)
+    const bool rows_wanted = h->mode == 3 && B <= kMaxRowSeq; // the row-streaming kernels on request
+    if (B >= kBatchMinSeq && h->mode != 1 && !rows_wanted && widest < ((size_t)1 << 31)) { // (mode 1 beyond 16 sequences: see above)
         p.act[0] = reinterpret_cast<uint16_t *>(ws + l.act0);
         p.act[1] = reinterpret_cast<uint16_t *>(ws + l.act1);
         p.a_lo = l.a_lo;
@@ -1195,7 +1200,7 @@ int32_t mtp_set_timing(mtp_handle *h, int32_t mode) {
 
 int32_t mtp_set_launch_mode(mtp_handle *h, int32_t mode) {
     if (!h) return MTP_ERR_NULL;
-    if (mode < 0 || mode > 2) return MTP_ERR_MODE;
+    if (mode < 0 || mode > 3) return MTP_ERR_MODE;
     h->mode = mode;
     return MTP_OK;
 }

@@ -58,7 +58,7 @@ struct DraftParams {
     // cache is that of sequence row % ext_B, and its own position is read from the cache like the others.
     int kv_appended, ext_B;
     int nb_proj, nb_d, nb_q, nb_down; // sequences staged in LDS per pass, by reduction length (2d, d, Hq*hd, F)
-    // batched path (five or more sequences): activations travel between the phases as bf16 hi + lo in global memory
+    // batched path (two or more sequences): activations travel between the phases as bf16 hi + lo in global memory
     uint16_t *act[2];    // two [max_batch][a_stride] hi arrays, each followed (a_lo elements later) by its lo array
     size_t a_lo;
     int a_stride;

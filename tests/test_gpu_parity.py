@@ -164,6 +164,32 @@ def test_tiny_wide_batches(gpu, tiny, B):
     check_chain(ref, res, caches, act["kv_len"], 3)
 
 
+@pytest.mark.parametrize("B", [2, 3, 4])
+def test_tiny_row_kernels_on_request(gpu, tiny, B):
+    """Two to four sequences take the batched kernels by default; launch mode 3 keeps them on the row-streaming
+    kernels (the form the library falls back to for matrices of 2 GiB or more): a K = 3 chain with ragged contexts,
+    and a block of new positions whose rows (two per sequence where they fit) are row-streamed."""
+    binding = gpu["binding"]
+    wl = tiny["wl"]
+    ctx = np.array([0, 63, 150, 7][:B], dtype=np.int32)
+    act = synth.make_activations(wl, ctx=ctx, capacity=192)
+    engine = binding.DraftEngine(tiny["shape"], tiny["w"], [tiny["ids"]], B, 192, 3)
+    assert binding.mtp_set_launch_mode(engine.handle, binding.LAUNCH_ROWS) == 0
+    ref, res, caches = run_both(gpu, tiny["shape"], tiny["w"], tiny["w"], act, [tiny["ids"]], 0, 3, engine=engine)
+    check_chain(ref, res, caches, act["kv_len"], 3)
+    engine.close()
+    if B == 2:
+        engine = binding.DraftEngine(tiny["shape"], tiny["w"], [tiny["ids"]], 4, 192, 1)
+        assert binding.mtp_set_launch_mode(engine.handle, binding.LAUNCH_ROWS) == 0
+        ext_len = np.array([2, 1], dtype=np.int32)
+        hid, tok = extend_inputs(tiny["shape"], act, 2, 215)
+        ref, res, caches = run_extend(gpu, tiny["shape"], tiny["w"], tiny["w"], act, [tiny["ids"]], 0, hid, tok, ext_len,
+                                      engine=engine)
+        assert res["err"] == 0
+        check_extend(ref, res, caches, act, ext_len)
+        engine.close()
+
+
 # head geometries that together instantiate every (query-group size, head dimension) variant of the attention kernels
 GEOMETRIES = [(4, 4, 64), (8, 2, 64), (8, 1, 64), (2, 2, 128), (2, 1, 128), (4, 1, 128), (8, 1, 128)]
 
@@ -287,6 +313,7 @@ def test_single_launch_mode_matches_oracle(gpu, tiny):
         ref, res, caches = run_both(gpu, tiny["shape"], tiny["w"], tiny["w"], act, [tiny["ids"]], 0, 3, engine=eng)
         check_chain(ref, res, caches, act["kv_len"], 3)
     assert binding.mtp_set_launch_mode(eng.handle, 7) == -11
+    assert binding.mtp_set_launch_mode(eng.handle, -1) == -11
     eng.close()
 
 
@@ -385,7 +412,7 @@ def check_extend(ref, res, caches, act, ext_len, sel=None):
 
 
 @pytest.mark.parametrize("ctx,ext,m_max", [
-    ([100], [3], 3),                         # three rows: the row-streaming matrix phases
+    ([100], [3], 3),                         # three rows
     ([0, 60], [2, 1], 2),                    # four rows, one sequence starting from an empty cache
     ([0, 130, 64], [4, 0, 2], 4),            # twelve rows (batched matrix phases), ragged, one sequence idle
     ([5, 150, 64, 1, 99, 127], [5, 5, 1, 3, 0, 5], 5),   # thirty rows: two sequence tiles per weight tile
@@ -586,9 +613,9 @@ def test_tiny_one_list_per_sequence(gpu, tiny, ctx, seq_subset):
 # ------------------------------------------------------------------------------------------ teacher-forced loss
 @pytest.mark.parametrize("n_pos,K", [(3, 2), (40, 3), (70, 3), (300, 2)])
 def test_tiny_teacher_forced_loss(gpu, tiny, n_pos, K):
-    """Eq. (1)-(2): the K per-step cross-entropies and their weighted sum against the oracle (3 positions: the
-    row-streaming phases; 40: the batched ones; 70: two weight passes and the output head as a tiled matrix product;
-    300: every matrix phase tiled except the down projection, whose reduction length 688 is not a multiple of the
+    """Eq. (1)-(2): the K per-step cross-entropies and their weighted sum against the oracle (3 positions: one
+    sequence tile; 40: three; 70: two weight passes, and the output head as a tiled matrix product; 300: every
+    matrix phase tiled except the down projection, whose reduction length 688 is not a multiple of the
     tiling's step).  The logits agree to ~1e-4, a mean of log-probabilities to better than 1e-3."""
     torch, Oracle, binding, orc_mod = gpu["torch"], gpu["Oracle"], gpu["binding"], gpu["orc"]
     shape = tiny["shape"]
