@@ -260,6 +260,40 @@ def main() -> int:
                   "positions_per_s": B * m * n_blk / el_b,
                   "speedup_over_one_position_at_a_time": m * us_per_mtp_step / (el_b / n_blk * 1e6),
                   "weight_pass_bytes": blk_bytes}
+        # One cycle of the drafting loop as Sec. 2.3 runs it after a verification that accepted m - 1 drafts: step 1
+        # over the m new positions (target hidden states), K - 1 recursive steps from the last position's own output,
+        # acceptance (against a dummy target chain: what is timed is the work, not the acceptance rate).
+        if K >= 2 and int(act["kv_len"].max()) + m + K - 1 <= cap:
+            hid_out = torch.empty((m, B, shape.d_model), dtype=torch.float32, device="cuda:0")
+            draft_c = torch.empty((B, K - 1), dtype=torch.int32, device="cuda:0")
+            draft_k = torch.empty((B, K), dtype=torch.int32, device="cuda:0")
+            tok_c = torch.empty(B, dtype=torch.int32, device="cuda:0")  # the last position's draft, 16-byte aligned
+
+            def one_cycle():
+                st = binding.mtp_draft_extend(eng2.handle, B, m, args.subset, hid_m, tok_m, ext_len, kc, vc, kv,
+                                              draft_m, None, hid_out, stream)
+                assert st == 0, binding.mtp_status_string(st)
+                tok_c.copy_(draft_m[m - 1])
+                st = binding.mtp_draft_continue(eng.handle, B, K - 1, args.subset, hid_out[m - 1], tok_c, kc, vc,
+                                                kv, None, draft_c, None, None, stream)
+                assert st == 0, binding.mtp_status_string(st)
+                draft_k[:, 0] = tok_c
+                draft_k[:, 1:] = draft_c
+                st = binding.mtp_accept(eng.handle, B, K, draft_k, dummy, 0, kv, acc, out_tok, pend, stream)
+                assert st == 0, binding.mtp_status_string(st)
+                kv.copy_(kv0)
+
+            for _ in range(max(3, args.warmup // 3)):
+                one_cycle()
+            torch.cuda.synchronize()
+            assert eng.poll_error() == 0 and eng2.poll_error() == 0
+            t = time.perf_counter()
+            for _ in range(n_blk):
+                one_cycle()
+            torch.cuda.synchronize()
+            el_c = (time.perf_counter() - t) / n_blk
+            extend["cycle"] = {"what": f"block of {m} positions, {K - 1} recursive steps, acceptance", "us": el_c * 1e6,
+                               "draft_tokens_per_s": B * K / el_c}
         eng2.close()
 
     builder = None
