@@ -30,14 +30,21 @@ def gpu():
     return {"torch": torch, "Oracle": Oracle, "orc": orc_mod, "binding": binding}
 
 
-def appended_entries_close(got_bits, ref_bits):
-    """Appended cache entries: both sides round a float32 value to bf16, but they sum in different orders, so the
-    float32 values differ by ~1e-6 of the vector's scale and the rounded ones by at most one bf16 step (2^-7
-    relative) plus that absolute slack (which matters only for entries that cancel to almost zero)."""
+def appended_entries_close(got_bits, ref_bits, recursive_from=None):
+    """Appended cache entries [Hkv][slots][hd]: both sides round a float32 value to bf16, but they sum in different
+    orders, so the float32 values differ by ~1e-6 of the vector's scale and the rounded ones by at most one bf16 step
+    (2^-7 relative) plus that absolute slack (which matters only for entries that cancel to almost zero).
+    Slots from `recursive_from` on were produced by recursive steps (Sec. 2.3: step k > 1 consumes the head's own
+    output hidden state), where the two sides' INPUTS already differ by the hidden-state gap the same test bounds by
+    2e-3: their keys and values may differ by a matrix row's worth of that (measured up to 6e-5 of the scale at the
+    third step of a one-token context), so the absolute slack there is 2e-4 of the scale."""
     g = synth.bf16_bits_to_f32(got_bits).astype(np.float64)
     r = synth.bf16_bits_to_f32(ref_bits).astype(np.float64)
     scale = max(float(np.abs(r).max()), 1e-30)
-    return bool((np.abs(g - r) <= 2.0 ** -7 * np.abs(r) + 1e-5 * scale).all())
+    slack = np.full(r.shape[1], 1e-5)
+    if recursive_from is not None:
+        slack[recursive_from:] = 2e-4
+    return bool((np.abs(g - r) <= 2.0 ** -7 * np.abs(r) + slack[None, :, None] * scale).all())
 
 
 def run_both(gpu, shape, w_host, w_dev, act, subsets, subset_index, K, engine=None, forced="oracle", seqs=None,
@@ -98,8 +105,8 @@ def check_chain(ref, res, caches, kv_len, K, aligned=True, need_clear=True):
         assert np.array_equal(res["k_cache"][i][:, :L], okc[i][:, :L])
         assert np.array_equal(res["v_cache"][i][:, :L], ovc[i][:, :L])
         if aligned:
-            assert appended_entries_close(res["k_cache"][i][:, L:L + K], okc[i][:, L:L + K])
-            assert appended_entries_close(res["v_cache"][i][:, L:L + K], ovc[i][:, L:L + K])
+            assert appended_entries_close(res["k_cache"][i][:, L:L + K], okc[i][:, L:L + K], recursive_from=1)
+            assert appended_entries_close(res["v_cache"][i][:, L:L + K], ovc[i][:, L:L + K], recursive_from=1)
         assert np.array_equal(res["k_cache"][i][:, L + K:], okc[i][:, L + K:])
     return gap
 
@@ -524,7 +531,7 @@ def check_extend_then_continue(gpu, shape, w_host, w_dev, act, subsets, ext_len,
         clear = cont[i]["margin"] > MARGIN
         np.testing.assert_array_equal(dr[b][clear], cont[i]["draft"][clear])
         L = int(ref["kv_len"][i])
-        assert appended_entries_close(kc_after[b][:, L:L + K], okc[i][:, L:L + K])
+        assert appended_entries_close(kc_after[b][:, L:L + K], okc[i][:, L:L + K], recursive_from=0)
         assert np.array_equal(kc_after[b][:, L + K:], okc[i][:, L + K:])
     eng.close()
     return worst
@@ -589,7 +596,7 @@ def test_tiny_one_list_per_sequence(gpu, tiny, ctx, seq_subset):
         some_clear |= bool(clear.any())
         np.testing.assert_array_equal(dr[b][clear], r["draft"][0][clear])
         L = int(act["kv_len"][b])
-        assert appended_entries_close(kc[b][:, L:L + K], okc[b][:, L:L + K])
+        assert appended_entries_close(kc[b][:, L:L + K], okc[b][:, L:L + K], recursive_from=1)
         assert np.array_equal(kc[b][:, :L], okc[b][:, :L])
     assert some_clear
     # one list for everybody through the same entry point equals the plain call bit for bit
