@@ -654,6 +654,66 @@ def test_tiny_teacher_forced_loss(gpu, tiny, n_pos, K):
 
 
 # ------------------------------------------------------------------------------------------ accept / rollback
+# ------------------------------------------------------------------------------------------ randomized cases
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_tiny_randomized_cases(gpu, tiny, seed):
+    """Fifty seeded random cases per seed on the tiny head, each against the oracle: draft chains (1 to 257 sequences,
+    K = 1..5, capacities from 192 to 32768, random contexts including empty ones), blocks of new positions (up to 40
+    positions per sequence, ragged counts) and the teacher-forced loss (1 to 300 positions, K = 1..3).  The draws
+    walk through every dispatch boundary of the host side: row-streaming / batched / tiled phases, one to four
+    sequence tiles, one to five weight passes, vector / matrix-core / shared-read attention, static and handed-out
+    attention items."""
+    torch, Oracle, binding, orc_mod = gpu["torch"], gpu["Oracle"], gpu["binding"], gpu["orc"]
+    wl, shape = tiny["wl"], tiny["shape"]
+    rng = np.random.default_rng(seed)
+    for case in range(50):
+        kind = int(rng.integers(0, 3))
+        cap = int(rng.choice([192, 512, 4096, 32768]))
+        K = int(rng.integers(1, 6))
+        if kind == 0:
+            B = int(rng.choice([1, 2, 3, 4, 5, 9, 16, 17, 33, 64, 65, 100, 257]))
+            if cap >= 4096:
+                B = min(B, 40)
+            ctx = rng.integers(0, cap - K, size=B).astype(np.int32)
+            if rng.random() < 0.3:
+                ctx[rng.integers(0, B)] = 0
+            print(f"seed {seed} case {case}: chain B={B} capacity={cap} K={K}", flush=True)
+            act = synth.make_activations(wl, ctx=ctx, capacity=cap)
+            ref, res, caches = run_both(gpu, shape, tiny["w"], tiny["w"], act, [tiny["ids"]], 0, K)
+            check_chain(ref, res, caches, act["kv_len"], K, need_clear=False)
+        elif kind == 1:
+            B = int(rng.choice([1, 2, 3, 5, 8, 16, 30]))
+            m = int(rng.choice([1, 2, 3, 4, 5, 9, 17, 40]))
+            if cap >= 4096:
+                B = min(B, 8)
+            while B * m > 320:
+                m = max(1, m // 2)
+            ctx = rng.integers(0, max(1, cap - m), size=B).astype(np.int32)
+            ext = rng.integers(0, m + 1, size=B).astype(np.int32)
+            ext[rng.integers(0, B)] = m
+            print(f"seed {seed} case {case}: block B={B} positions={m} capacity={cap}", flush=True)
+            act = synth.make_activations(wl, ctx=ctx, capacity=cap)
+            hid, tok = extend_inputs(shape, act, m, 1000 * seed + case)
+            ref, res, caches = run_extend(gpu, shape, tiny["w"], tiny["w"], act, [tiny["ids"]], 0, hid, tok, ext)
+            assert res["err"] == 0
+            check_extend(ref, res, caches, act, ext)
+        else:
+            n_pos = int(rng.choice([1, 2, 5, 33, 64, 65, 129, 256, 300]))
+            Kt = int(rng.integers(1, 4))
+            print(f"seed {seed} case {case}: loss positions={n_pos} K={Kt}", flush=True)
+            hid = synth.f32_to_bf16_bits(rng.standard_normal((n_pos, shape.d_model)).astype(np.float32))
+            tok = rng.integers(0, shape.vocab_size, size=n_pos + Kt + 1).astype(np.int32)
+            capt = max(128, (n_pos + 63) // 64 * 64)
+            want = orc_mod.train_loss(Oracle(shape, tiny["w"], capt, "f32"), hid, tok, Kt, 0.6)
+            eng = binding.DraftEngine(shape, tiny["w"], [], n_pos, capt, 1)
+            got, logits = eng.train_loss(eng.to_device_bits(hid), eng.to_device_i32(tok), Kt, 0.6, want_logits=True)
+            torch.cuda.synchronize()
+            assert eng.poll_error() == 0
+            np.testing.assert_allclose(got.cpu().numpy()[:Kt], want["ce"], atol=1e-3)
+            assert np.abs(logits.cpu().numpy() - want["logits"][Kt - 1]).max() <= LOGIT_TIGHT
+            eng.close()
+
+
 @pytest.mark.parametrize("K", [1, 3, 5])
 @pytest.mark.parametrize("mode", [0, 1])
 def test_accept_bit_exact(gpu, tiny, K, mode):
