@@ -220,6 +220,27 @@ def test_small_heads_every_attention_variant(gpu, hq, hkv, hd, long_splits):
     check_chain(ref, res, caches, act["kv_len"], 2)
 
 
+@pytest.mark.parametrize("hq,hkv,hd", GEOMETRIES)
+def test_small_heads_block_of_positions_shared_reads(gpu, hq, hkv, hd):
+    """Blocks of new positions on every (group size, head dimension) variant of the matrix-core attention that serves
+    16 / G positions of a sequence per item (sixteen, eight, four or two): 19 positions per sequence (a ragged last
+    group everywhere), ragged counts including zero, a block that crosses a split boundary, an empty cache."""
+    shape = synth.HeadShape(256, hq, hkv, hd, 512, 2048)
+    wl = synth.Workload(f"block_{hq}_{hkv}_{hd}", 60 + hq + 3 * hkv + hd, shape, 4, 0, 0, (512,), 1, 0.5,
+                        zipf_subset=False)
+    w = synth.make_weights(wl)
+    ids = synth.make_subsets(wl)[0]
+    cap, m = 16384, 19
+    # 4 x 19 rows and hkv KV heads: splits of capacity * 76 * hkv / 256 tokens, capped at 4096
+    ctx = np.array([4090, 0, 9000, 300], dtype=np.int32)
+    ext_len = np.array([19, 19, 7, 0], dtype=np.int32)
+    act = synth.make_activations(wl, ctx=ctx, capacity=cap)
+    hid, tok = extend_inputs(shape, act, m, 77 + hq + hkv + hd)
+    ref, res, caches = run_extend(gpu, shape, w, w, act, [ids], 0, hid, tok, ext_len)
+    assert res["err"] == 0
+    check_extend(ref, res, caches, act, ext_len)
+
+
 def test_tiny_full_vocab_equals_identity_subset(gpu, tiny):
     """Eq. (3) with the identity list is the full head: same logits bit for bit on the device as well."""
     act = tiny["act"]
