@@ -81,7 +81,7 @@ __global__ __launch_bounds__(kBlock, 4) void k_rows_gemm(DraftParams p, int step
     if constexpr (PH == BG_PROJ)
         rows_gemm<64, 128, 4, BgProj>(p, [](const DraftParams &q) { return BgProj(q); }, smem);
     else if constexpr (PH == BG_QKV)
-        rows_gemm<64, 128, 4, BgQkv>(p, [](const DraftParams &q) { return BgQkv(q); }, smem);
+        rows_gemm<128, 128, 4, BgQkv>(p, [](const DraftParams &q) { return BgQkv(q); }, smem);
     else if constexpr (PH == BG_OPROJ)
         rows_gemm<64, 128, 4, BgOproj>(p, [](const DraftParams &q) { return BgOproj(q); }, smem);
     else if constexpr (PH == BG_GATEUP)
@@ -263,7 +263,7 @@ void launch_rows_gemm(int phase, const DraftParams &p, int step, hipStream_t st)
     };
     switch (phase) {
     case BG_PROJ: small(k_rows_gemm<BG_PROJ>, p.d); break;
-    case BG_QKV: small(k_rows_gemm<BG_QKV>, rows16(p.qkv_dim)); break;
+    case BG_QKV: mid(k_rows_gemm<BG_QKV>, rows16(p.qkv_dim)); break;
     case BG_OPROJ: small(k_rows_gemm<BG_OPROJ>, p.d); break;
     case BG_GATEUP: mid(k_rows_gemm<BG_GATEUP>, 2 * rows16(p.F)); break;
     case BG_DOWN: small(k_rows_gemm<BG_DOWN>, p.d); break;
