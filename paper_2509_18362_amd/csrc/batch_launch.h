@@ -20,7 +20,7 @@ void launch_bprep(const DraftParams &p, int step, hipStream_t st);
 // a matrix phase (BG_* index) over all p.B rows as one tiled matrix product (rows_gemm.h); the output head leaves
 // logits only, no candidates.  rows_gemm_serves: the phase's reduction length is a whole number of the tilings' rounds of steps
 bool rows_gemm_serves(int phase, const DraftParams &p);
-void launch_rows_gemm(int phase, const DraftParams &p, int step, hipStream_t st);
+void launch_rows_gemm(int phase, const DraftParams &p, int step, int cus, hipStream_t st);
 
 // matrix-core attention (attn_mfma.h): dynamic LDS, and the launch for query-group size G and head dimension HD
 size_t attn_mfma_lds_bytes(int G, int HD);

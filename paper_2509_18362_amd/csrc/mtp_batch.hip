@@ -92,6 +92,12 @@ __global__ __launch_bounds__(kBlock, 4) void k_rows_gemm(DraftParams p, int step
         rows_gemm<128, 256, 2, BgHeadLogits>(p, [step](const DraftParams &q) { return BgHeadLogits(q, step); }, smem);
 }
 
+// q/k/v with the small tiles: for row counts whose small tiles still fit the chip one per CU
+__global__ __launch_bounds__(kBlock, 4) void k_rows_gemm_qkv_small(DraftParams p, int step) {
+    extern __shared__ __align__(16) char smem[];
+    rows_gemm<64, 128, 4, BgQkv>(p, [](const DraftParams &q) { return BgQkv(q); }, smem);
+}
+
 template <int G, int HD>
 __global__ __launch_bounds__(kBlock) void k_attn_mfma(DraftParams p, int step) {
     extern __shared__ __align__(16) char smem[];
@@ -250,7 +256,7 @@ bool rows_gemm_serves(int phase, const DraftParams &p) {
     const int K = phase == BG_PROJ ? 2 * p.d : phase == BG_OPROJ ? p.qd : phase == BG_DOWN ? p.F : p.d;
     return K % (kRgRound * kRgBK) == 0;
 }
-void launch_rows_gemm(int phase, const DraftParams &p, int step, hipStream_t st) {
+void launch_rows_gemm(int phase, const DraftParams &p, int step, int cus, hipStream_t st) {
     auto rows16 = [](int rows) { return (rows + 15) / 16 * 16; };
     auto small = [&](bg_kernel_t k, int n) {
         hipLaunchKernelGGL(k, dim3(rows_gemm_grid<64, 128>(p.B, n)), dim3(kBlock), sizeof(RowsGemmLds<64, 128>), st, p, step);
@@ -263,7 +269,13 @@ void launch_rows_gemm(int phase, const DraftParams &p, int step, hipStream_t st)
     };
     switch (phase) {
     case BG_PROJ: small(k_rows_gemm<BG_PROJ>, p.d); break;
-    case BG_QKV: mid(k_rows_gemm<BG_QKV>, rows16(p.qkv_dim)); break;
+    case BG_QKV:
+        // a tile count between one and two per CU costs two rounds: small tiles only while they fit one per CU
+        if (rows_gemm_grid<64, 128>(p.B, rows16(p.qkv_dim)) <= cus)
+            small(k_rows_gemm_qkv_small, rows16(p.qkv_dim));
+        else
+            mid(k_rows_gemm<BG_QKV>, rows16(p.qkv_dim));
+        break;
     case BG_OPROJ: small(k_rows_gemm<BG_OPROJ>, p.d); break;
     case BG_GATEUP: mid(k_rows_gemm<BG_GATEUP>, 2 * rows16(p.F)); break;
     case BG_DOWN: small(k_rows_gemm<BG_DOWN>, p.d); break;

@@ -940,7 +940,7 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
         const bool tiled_body = B >= 4 * kBatchPassSeq;
         auto matrix_phase = [&](int timed_as, int ph, int step) {
             if ((ph == BG_LMHEAD ? tiled : tiled_body) && rows_gemm_serves(ph, p)) {
-                launch_rows_gemm(ph, p, step, st);
+                launch_rows_gemm(ph, p, step, h->num_cus, st);
                 mark_end(timed_as, step);
                 return;
             }
