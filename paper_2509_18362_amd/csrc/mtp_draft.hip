@@ -816,7 +816,9 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
     };
     // long splits go to the matrix-core attention; short ones (small batch, short context) to the latency-lean
     // vector version
-    const bool mfma_attn = p.split_tokens >= kMfmaAttnMinSplit;
+    // (a block of positions pays more set-up per item on the matrix cores, sixteen query columns: 320-token splits of a
+    // four-position block take 40 us there and 26 us on the vector units)
+    const bool mfma_attn = p.split_tokens >= (ext && ext->m_max > 1 ? 2 * kMfmaAttnMinSplit : kMfmaAttnMinSplit);
     auto launch_attention_of = [&](const DraftParams &pa, int step) {
         if (mfma_attn)
             launch_attn_mfma(pa.Hq / pa.Hkv, pa.hd, pa, step, attn_grid, lds_attn, st);
