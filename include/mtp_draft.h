@@ -127,9 +127,10 @@ int32_t mtp_draft_init(mtp_handle **out, const mtp_config *cfg, const mtp_weight
  *   draft_out     device [B][K] int32: drafted full-vocabulary ids
  *   logits_out    device [B][K][n] float32 or NULL
  *   hidden_out    device [B][K][d] float32 or NULL: hh of every step
- * Host-detected errors: NULL/misaligned pointers, B, K, subset_index.  Device-detected conditions
- * (kv_len[b] + K > kv_capacity, token id out of range) make the affected sequence write draft id -1 from the
- * failing step on, leave its cache untouched, and set a sticky error word read by mtp_poll_error.
+ * Host-detected errors: NULL/misaligned pointers, B, K, subset_index.  Device-detected conditions set a sticky
+ * error word read by mtp_poll_error: a sequence with kv_len[b] < 0 or kv_len[b] + K > kv_capacity writes draft id -1
+ * at every step and its cache is left untouched; an input or forced token id outside [0, vocab_size) is replaced by
+ * id 0 (so that every access stays in bounds) and the sequence goes on drafting and appending from that embedding.
  */
 int32_t mtp_draft_steps(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, const void *hidden_in,
                         const int32_t *token_in, void *k_cache, void *v_cache, const int32_t *kv_len,
@@ -181,8 +182,8 @@ int32_t mtp_draft_extend(mtp_handle *h, int32_t B, int32_t m_max, int32_t subset
                          int32_t *draft_out, float *logits_out, float *hidden_out, void *hip_stream);
 
 /*
- * mtp_draft_steps with one id list per sequence: several languages in one batch (Sec. 2.2: the list is chosen "based
- * on the current context", per language).  Every phase but the output head runs once for the whole batch; the output
+ * mtp_draft_steps with one id list per sequence: several languages in one batch (Sec. 2.2: which language's list a
+ * sequence uses follows from its context).  Every phase but the output head runs once for the whole batch; the output
  * head runs once per list, over the sequences that use it.
  *   seq_subset   HOST [B] int32   index of each sequence's list (-1 = full vocabulary).  Sequences that share a list
  *                                 must be adjacent (sort the batch by language); at most 16 different lists per call;
@@ -260,7 +261,8 @@ float mtp_last_draft_ms(mtp_handle *h);
  *               kernels (every weight read once per pass of up to 64 sequences), one preparation launch per step,
  *               and one epilogue launch after each matrix phase whose reduction is split over workgroups (above 16
  *               sequences).  Matrices of 2 GiB or more: as mode 3.
- *   1           one cooperative launch runs all phases of all K steps (up to 16 sequences; otherwise as mode 0);
+ *   1           one cooperative launch runs all phases of all K steps (up to 16 sequences; more sequences take the
+ *               batched kernels of mode 0);
  *               phases are separated by grid-wide barriers inside the kernel.  A barrier that is not passed within
  *               ~2 s sets MTP_ERR_TIMEOUT.  For one sequence this is the faster mode (3-4 % at a 32768-row head,
  *               more with larger heads); for 2-16 sequences it is slower than mode 0.  The launch needs every
@@ -280,8 +282,8 @@ int32_t mtp_set_launch_mode(mtp_handle *h, int32_t mode);
 int32_t mtp_set_phase_trace(mtp_handle *h, void *device_buffer);
 
 /*
- * The high-frequency id list of one language from a token stream (Sec. 2.2: the subsets are "identified through
- * corpus-level statistics"; Eq. (3) gathers the output head's rows with them): occurrence counts per id, the n ids
+ * The high-frequency id list of one language from a token stream (Sec. 2.2: the subsets come from token statistics
+ * over a corpus of that language; Eq. (3) gathers the output head's rows with them): occurrence counts per id, the n ids
  * with the largest counts (equal counts: the lower id first), written in ascending id order - the format
  * mtp_draft_init takes.  Stateless: no handle; everything is enqueued on hip_stream and nothing waits.
  *   tokens       device [n_tokens] int32     ids; values outside [0, vocab_size) are skipped and counted (may be

@@ -131,7 +131,10 @@ __device__ __forceinline__ void bg_slot_epilogue(const DraftParams &p, Ph &ph, i
 template <int NA, class Ph, class Slots>
 __device__ __forceinline__ void bg_tail(const DraftParams &p, Ph &ph, int KP, int rg, int ntv, int vt0, char *smem,
                                         const float *scale_lds, Slots slots) {
-    __syncthreads(); // every store of this workgroup's sums has completed (each wave waits for its own first)
+    // Every wave waits for the acknowledgement of its own stores before the workgroup barrier: a workgroup-scope
+    // barrier alone orders accesses inside the CU and need not wait for stores still on their way to memory.
+    if (KP > 1) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
     if (KP > 1) {
         // The sums were written through to memory (device-coherent stores) and acknowledged before the ticket is
         // drawn, and the last workgroup reads them past its caches: relaxed atomics suffice, and no cache is written

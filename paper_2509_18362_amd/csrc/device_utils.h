@@ -72,8 +72,10 @@ __device__ __forceinline__ float block_sum(float x, float *red) {
 }
 
 // ---- argmax key: larger logit wins, then smaller index ------------------------------------------------
+// (-0.0 and +0.0 compare equal as logits, so both map to the key of +0.0 and the index decides)
 __device__ __forceinline__ uint32_t orderable(float f) {
     uint32_t u = __float_as_uint(f);
+    u = (u == 0x80000000u) ? 0u : u;
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 __device__ __forceinline__ unsigned long long argmax_key(float logit, uint32_t index) {

@@ -38,7 +38,10 @@ constexpr int kBarStride = 32; // 64-bit words between counters: one 256-byte li
 constexpr size_t kBarWords = (size_t)kBarStride * (1 + 2 * kBarGroups);
 
 __device__ __forceinline__ void bar_arrive(const DraftParams &p, unsigned epoch) {
-    __syncthreads(); // every store of the phase has completed (each wave waits for its own before the barrier)
+    // Each wave waits until its own device-coherent stores have been acknowledged, then the workgroup meets: the
+    // workgroup barrier by itself orders accesses inside the CU only and need not wait for stores still in flight.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
     if (threadIdx.x == 0) {
         const int g = blockIdx.x % kBarGroups;
         const int gsize = ((int)gridDim.x - g + kBarGroups - 1) / kBarGroups;

@@ -865,7 +865,7 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
     // matrix with 32-bit offsets and mark missing rows with an offset of 2 GiB.
     const size_t widest = std::max({(size_t)p.V * p.d, (size_t)p.d * 2 * p.d, (size_t)p.F * p.d, (size_t)p.qd * p.d}) * 2;
     const bool rows_wanted = h->mode == 3 && B <= kMaxRowSeq; // the row-streaming kernels on request
-    if (B >= kBatchMinSeq && h->mode != 1 && !rows_wanted && widest < ((size_t)1 << 31)) { // (mode 1 beyond 16 sequences: see above)
+    if (B >= kBatchMinSeq && (h->mode != 1 || B > 16) && !rows_wanted && widest < ((size_t)1 << 31)) {
         p.act[0] = reinterpret_cast<uint16_t *>(ws + l.act0);
         p.act[1] = reinterpret_cast<uint16_t *>(ws + l.act1);
         p.a_lo = l.a_lo;

@@ -1268,8 +1268,9 @@ __device__ __forceinline__ void phase_down(const DraftParams &p, int, int vb, in
 // phase 7: final RMSNorm + compressed output head + argmax                       (steps 9-10; Eq. (3))
 // ---------------------------------------------------------------------------------------------------
 // Row i of the compressed head is lm_head[ids[i]]; rows are dealt out in subset order, so every workgroup scans a
-// contiguous, ascending range of subset indices.  Each reducing thread keeps the best (logit, index) it has seen;
-// the workgroup's winner per sequence goes into a 64-bit atomic max whose key orders by logit, then by lower index.
+// contiguous, ascending range of subset indices (row mode: rows interleaved over the waves).  Each reporting thread
+// keeps the best (logit, index) it has seen as a 64-bit key that orders by logit, then by lower index; the workgroup's
+// best per sequence is stored as one candidate, and whoever needs the winner takes the maximum over the candidates.
 __device__ __forceinline__ void phase_lmhead(const DraftParams &p, int step, int vb, int nvb, char *smem) {
     const int d = p.d, n = p.n;
     const int nbmax = p.nb_d;

@@ -312,10 +312,19 @@ def test_device_detected_errors(gpu, tiny):
     np.testing.assert_array_equal(kc.cpu().numpy().view(np.uint16)[1], act["k_cache"][1])  # cache untouched
     tok = act["token_in"].copy()
     tok[0] = tiny["shape"].vocab_size
-    eng.draft(1, 0, eng.to_device_bits(act["hidden_in"]), eng.to_device_i32(tok), kc, vc,
-              eng.to_device_i32(np.array([100, 100])))
+    bad_tok = eng.draft(1, 0, eng.to_device_bits(act["hidden_in"]), eng.to_device_i32(tok), kc, vc,
+                        eng.to_device_i32(np.array([100, 100])), want_logits=True)
     torch.cuda.synchronize()
     assert eng.poll_error() == -10
+    # the id outside the vocabulary is reported and replaced by id 0: the call equals one that was given id 0
+    bad_draft, bad_logits = bad_tok["draft"].cpu().numpy().copy(), bad_tok["logits"].cpu().numpy().copy()
+    tok[0] = 0
+    zero_tok = eng.draft(1, 0, eng.to_device_bits(act["hidden_in"]), eng.to_device_i32(tok), kc, vc,
+                         eng.to_device_i32(np.array([100, 100])), want_logits=True)
+    torch.cuda.synchronize()
+    assert eng.poll_error() == 0
+    np.testing.assert_array_equal(bad_draft, zero_tok["draft"].cpu().numpy())
+    np.testing.assert_array_equal(bad_logits, zero_tok["logits"].cpu().numpy())
     # host-detected
     assert binding.mtp_draft_steps(eng.handle, 3, 1, 0, kc, kc, kc, vc, kc, None, kc, None, None) == -4
     assert binding.mtp_draft_steps(eng.handle, 1, 4, 0, kc, kc, kc, vc, kc, None, kc, None, None) == -5
