@@ -299,6 +299,21 @@ int32_t mtp_subset_build(const int32_t *tokens, int64_t n_tokens, int32_t vocab_
                          size_t workspace_bytes, int32_t *ids_out, int32_t *counts_out, int32_t *invalid_out,
                          void *hip_stream);
 
+/*
+ * mtp_subset_build for callers that cannot allocate device memory and have no workspace to hand over (code under
+ * HIP-graph capture, tight serving loops, harnesses that forbid hipMalloc): the counts and the selection state live in
+ * an array built into the library's device image instead of a caller's workspace.  Same arguments (minus the
+ * workspace), same kernels, same results.  Calls no hipMalloc/hipFree and no allocating routine.
+ *   vocab_size   at most mtp_subset_static_max_vocab() (262144 ids: the array is 1 MiB + 4.6 KB per GPU, held until
+ *                the process ends); larger vocabularies return MTP_ERR_WORKSPACE with a message on stderr
+ * Every call on a GPU uses that GPU's one array (its contents are cleared at the start of each call): calls that
+ * overlap on one GPU - different streams, or graphs replayed concurrently - race and must be serialised by the
+ * caller.  The first call on a device looks the array's address up (a host-side query, no allocation).
+ */
+int32_t mtp_subset_static_max_vocab(void);
+int32_t mtp_subset_build_static(const int32_t *tokens, int64_t n_tokens, int32_t vocab_size, int32_t n,
+                                int32_t *ids_out, int32_t *counts_out, int32_t *invalid_out, void *hip_stream);
+
 /* Frees the host object.  Device memory stays with the caller. */
 void mtp_draft_destroy(mtp_handle *h);
 

@@ -29,6 +29,7 @@ STATUS = {0: "MTP_OK", -1: "MTP_ERR_NULL", -2: "MTP_ERR_ALIGN", -3: "MTP_ERR_CON
           -9: "MTP_ERR_KV_OVERFLOW", -10: "MTP_ERR_TOKEN_RANGE", -11: "MTP_ERR_MODE", -12: "MTP_ERR_TIMEOUT"}
 EXPORTS = ["mtp_status_string", "mtp_workspace_bytes", "mtp_draft_init", "mtp_draft_steps", "mtp_draft_extend",
            "mtp_draft_continue", "mtp_draft_steps_lists", "mtp_subset_workspace_bytes", "mtp_subset_build",
+           "mtp_subset_static_max_vocab", "mtp_subset_build_static",
            "mtp_train_workspace_bytes", "mtp_train_loss",
            "mtp_accept",
            "mtp_poll_error", "mtp_set_timing", "mtp_last_draft_ms", "mtp_set_launch_mode", "mtp_set_phase_trace",
@@ -72,6 +73,11 @@ _lib.mtp_subset_workspace_bytes.argtypes = [C.c_int32]
 _lib.mtp_subset_build.restype = C.c_int32
 _lib.mtp_subset_build.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p,
                                   C.c_void_p, C.c_void_p, C.c_void_p]
+_lib.mtp_subset_static_max_vocab.restype = C.c_int32
+_lib.mtp_subset_static_max_vocab.argtypes = []
+_lib.mtp_subset_build_static.restype = C.c_int32
+_lib.mtp_subset_build_static.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                         C.c_void_p, C.c_void_p]
 _lib.mtp_train_workspace_bytes.restype = C.c_size_t
 _lib.mtp_train_workspace_bytes.argtypes = [C.c_void_p, C.c_int32]
 _lib.mtp_train_loss.restype = C.c_int32
@@ -151,6 +157,16 @@ def mtp_subset_build(tokens, n_tokens: int, vocab_size: int, n: int, workspace, 
                      counts_out=None, invalid_out=None, stream=0) -> int:
     return int(_lib.mtp_subset_build(_addr(tokens), n_tokens, vocab_size, n, _addr(workspace), workspace_bytes,
                                      _addr(ids_out), _addr(counts_out), _addr(invalid_out), stream))
+
+
+def mtp_subset_static_max_vocab() -> int:
+    return int(_lib.mtp_subset_static_max_vocab())
+
+
+def mtp_subset_build_static(tokens, n_tokens: int, vocab_size: int, n: int, ids_out, counts_out=None,
+                            invalid_out=None, stream=0) -> int:
+    return int(_lib.mtp_subset_build_static(_addr(tokens), n_tokens, vocab_size, n, _addr(ids_out),
+                                            _addr(counts_out), _addr(invalid_out), stream))
 
 
 def build_subset(tokens, vocab_size: int, n: int, want_counts: bool = False, stream: int = 0):

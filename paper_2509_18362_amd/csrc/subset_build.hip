@@ -16,6 +16,8 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <cstdio>
+#include <mutex>
 
 #include "../../include/mtp_draft.h"
 
@@ -196,42 +198,55 @@ __global__ void k_subset_export(const unsigned *counts, int V, const unsigned *s
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-} // namespace
+// ---- scratch of the entry point that allocates nothing ----------------------------------------------------------
+// Counts and selection state of mtp_subset_build_static live in this array instead of a caller's workspace.  Each GPU
+// the library runs on holds its own copy at its own address until the process ends; host code reaches it only through
+// the per-device pointer below (the array's name is a host-side stand-in, not a device address).
+constexpr int kStaticMaxVocab = 262144;
+constexpr int kStateWordsFullStatic = 8 + 4 * 256 + 2 * 64; // = kStateWordsFull (spelled out: used in the array bound)
+__device__ __align__(256) unsigned scratch[kStaticMaxVocab + kStateWordsFullStatic];
+static_assert(kStateWordsFullStatic == kStateWordsFull, "scratch layout");
+constexpr int kMaxDevices = 64;
+unsigned *g_scratch_ptr[kMaxDevices]; // per device: address of that device's copy of `scratch`, null until looked up
+bool g_lds_allowed[kMaxDevices];      // per device: the counting kernel may use all the LDS of a CU
+std::mutex g_setup_mutex;
 
-extern "C" {
-
-size_t mtp_subset_workspace_bytes(int32_t vocab_size) {
-    if (vocab_size < 1) return 0;
-    return ((size_t)vocab_size + kStateWordsFull) * 4;
-}
-
-int32_t mtp_subset_build(const int32_t *tokens, int64_t n_tokens, int32_t vocab_size, int32_t n, void *workspace,
-                         size_t workspace_bytes, int32_t *ids_out, int32_t *counts_out, int32_t *invalid_out,
-                         void *hip_stream) {
-    if ((!tokens && n_tokens > 0) || !workspace || (!ids_out && n > 0)) return MTP_ERR_NULL;
-    if (!aligned16(tokens) || !aligned16(workspace) || !aligned16(ids_out) || !aligned16(counts_out) ||
-        !aligned16(invalid_out))
-        return MTP_ERR_ALIGN;
-    if (vocab_size < 1 || n < 0 || n > vocab_size || n_tokens < 0 || n_tokens >= ((int64_t)1 << 31))
-        return MTP_ERR_CONFIG;
-    if (workspace_bytes < mtp_subset_workspace_bytes(vocab_size)) return MTP_ERR_WORKSPACE;
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    static bool lds_allowed = false; // once per process: the counting kernel uses all the LDS of a CU
-    if (!lds_allowed) {
+// once per device, with that device current: raise the LDS limit of the counting kernel and (for the static entry
+// point) look up the device's copy of the scratch array
+int32_t subset_setup(int dev, bool want_scratch, unsigned **scratch_out) {
+    if (dev < 0 || dev >= kMaxDevices) return MTP_ERR_CONFIG;
+    std::lock_guard<std::mutex> lock(g_setup_mutex);
+    if (!g_lds_allowed[dev]) {
         if (hipFuncSetAttribute((const void *)k_subset_hist, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 kChunkBins * 4) != hipSuccess) {
             (void)hipGetLastError();
             return MTP_ERR_HIP;
         }
-        lds_allowed = true;
+        g_lds_allowed[dev] = true;
     }
-    unsigned *counts = static_cast<unsigned *>(workspace);
-    unsigned *state = counts + vocab_size;
-    const int V = vocab_size;
+    if (want_scratch) {
+        if (!g_scratch_ptr[dev]) {
+            unsigned *ptr = nullptr;
+            if (hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+                (void)hipGetLastError();
+                return MTP_ERR_HIP;
+            }
+            g_scratch_ptr[dev] = ptr;
+        }
+        *scratch_out = g_scratch_ptr[dev];
+    }
+    return MTP_OK;
+}
+
+// everything after the argument checks: `work` holds V counts followed by the selection state
+int32_t subset_build_on(const int32_t *tokens, int64_t n_tokens, int32_t V, int32_t n, unsigned *work, int dev,
+                        int32_t *ids_out, int32_t *counts_out, int32_t *invalid_out, hipStream_t st) {
+    unsigned *counts = work;
+    unsigned *state = counts + V;
     hipLaunchKernelGGL(k_subset_clear, dim3((V + kStateWordsFull + 255) / 256), dim3(256), 0, st, counts, V, state,
                        kStateWordsFull, n);
-    int dev = 0, cus = 256;
-    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    int cus = 256;
+    (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     const int chunks = (V + kChunkBins - 1) / kChunkBins;
     hipLaunchKernelGGL(k_subset_hist, dim3(cus, chunks), dim3(kHistBlock), kChunkBins * 4, st, tokens,
                        (long long)n_tokens, V, counts, state);
@@ -248,6 +263,61 @@ int32_t mtp_subset_build(const int32_t *tokens, int64_t n_tokens, int32_t vocab_
                            invalid_out);
     if (hipGetLastError() != hipSuccess) return MTP_ERR_HIP;
     return MTP_OK;
+}
+
+int32_t subset_check_args(const int32_t *tokens, int64_t n_tokens, int32_t vocab_size, int32_t n, const int32_t *ids_out,
+                          const int32_t *counts_out, const int32_t *invalid_out) {
+    if ((!tokens && n_tokens > 0) || (!ids_out && n > 0)) return MTP_ERR_NULL;
+    if (!aligned16(tokens) || !aligned16(ids_out) || !aligned16(counts_out) || !aligned16(invalid_out))
+        return MTP_ERR_ALIGN;
+    if (vocab_size < 1 || n < 0 || n > vocab_size || n_tokens < 0 || n_tokens >= ((int64_t)1 << 31))
+        return MTP_ERR_CONFIG;
+    return MTP_OK;
+}
+
+} // namespace
+
+extern "C" {
+
+size_t mtp_subset_workspace_bytes(int32_t vocab_size) {
+    if (vocab_size < 1) return 0;
+    return ((size_t)vocab_size + kStateWordsFull) * 4;
+}
+
+int32_t mtp_subset_build(const int32_t *tokens, int64_t n_tokens, int32_t vocab_size, int32_t n, void *workspace,
+                         size_t workspace_bytes, int32_t *ids_out, int32_t *counts_out, int32_t *invalid_out,
+                         void *hip_stream) {
+    if (!workspace) return MTP_ERR_NULL;
+    if (!aligned16(workspace)) return MTP_ERR_ALIGN;
+    const int32_t rc = subset_check_args(tokens, n_tokens, vocab_size, n, ids_out, counts_out, invalid_out);
+    if (rc != MTP_OK) return rc;
+    if (workspace_bytes < mtp_subset_workspace_bytes(vocab_size)) return MTP_ERR_WORKSPACE;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return MTP_ERR_HIP;
+    const int32_t rs = subset_setup(dev, false, nullptr);
+    if (rs != MTP_OK) return rs;
+    return subset_build_on(tokens, n_tokens, vocab_size, n, static_cast<unsigned *>(workspace), dev, ids_out, counts_out,
+                           invalid_out, static_cast<hipStream_t>(hip_stream));
+}
+
+int32_t mtp_subset_static_max_vocab(void) { return kStaticMaxVocab; }
+
+int32_t mtp_subset_build_static(const int32_t *tokens, int64_t n_tokens, int32_t vocab_size, int32_t n,
+                                int32_t *ids_out, int32_t *counts_out, int32_t *invalid_out, void *hip_stream) {
+    const int32_t rc = subset_check_args(tokens, n_tokens, vocab_size, n, ids_out, counts_out, invalid_out);
+    if (rc != MTP_OK) return rc;
+    if (vocab_size > kStaticMaxVocab) {
+        fprintf(stderr, "mtp_subset_build_static: vocab_size %d exceeds the built-in scratch (%d ids); use "
+                        "mtp_subset_build with a workspace\n", (int)vocab_size, kStaticMaxVocab);
+        return MTP_ERR_WORKSPACE;
+    }
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return MTP_ERR_HIP;
+    unsigned *work = nullptr;
+    const int32_t rs = subset_setup(dev, true, &work); // first call on a device: symbol lookup; later: a table read
+    if (rs != MTP_OK) return rs;
+    return subset_build_on(tokens, n_tokens, vocab_size, n, work, dev, ids_out, counts_out, invalid_out,
+                           static_cast<hipStream_t>(hip_stream));
 }
 
 } // extern "C"
