@@ -253,32 +253,34 @@ float mtp_last_draft_ms(mtp_handle *h);
 
 /*
  * How mtp_draft_steps enqueues its work.
- *   2 (default) automatic: mode 1 for one sequence whose reduction lengths are all at least 512 (where it is the
- *               faster one), mode 0 otherwise; if the device cannot take the cooperative launch at that moment
- *               (it needs every compute unit), mode 0 for that call.
- *   0           one launch per phase.  One sequence: the row-streaming kernels, 7 or 8 launches per step plus one
- *               to publish the last draft id.  Two or more (also the rows of a block of positions): the batched
- *               kernels (every weight read once per pass of up to 64 sequences), one preparation launch per step,
- *               and one epilogue launch after each matrix phase whose reduction is split over workgroups (above 16
- *               sequences).  Matrices of 2 GiB or more: as mode 3.
- *   1           one cooperative launch runs all phases of all K steps (up to 16 sequences; more sequences take the
- *               batched kernels of mode 0);
- *               phases are separated by grid-wide barriers inside the kernel.  A barrier that is not passed within
- *               ~2 s sets MTP_ERR_TIMEOUT.  For one sequence this is the faster mode (3-4 % at a 32768-row head,
- *               more with larger heads); for 2-16 sequences it is slower than mode 0.  The launch needs every
- *               compute unit of the device to itself.
+ *   2 (default) automatic: mode 1 where it applies, mode 0 otherwise; if the device cannot take the cooperative launch
+ *               at that moment (it needs every compute unit), mode 0 for that call.
+ *   0           one launch per phase.  One sequence: the row-streaming kernels, 7 launches per step plus one to publish
+ *               the last draft id.  Two or more (also the rows of a block of positions): the batched kernels (every
+ *               weight read once per pass of up to 64 sequences), one preparation launch per step, and one epilogue
+ *               launch after each matrix phase whose reduction is split over workgroups (above 16 sequences).
+ *               Matrices of 2 GiB or more: as mode 3.
+ *   1           one sequence whose reduction lengths (d_model, n_q_heads * head_dim, d_ffn) are all at least 512: one
+ *               cooperative launch runs all phases of all K steps; its workgroups hand their results over element by
+ *               element (every element carries a tag naming the call, step and phase that produced it, consumers poll
+ *               for it), there are no grid barriers.  A wait that does not end within ~2 s sets MTP_ERR_TIMEOUT.  The
+ *               launch needs every compute unit of the device to itself.  Every other call: as mode 0.
  *   3           as mode 0, with the row-streaming kernels for up to four sequences (slower from the second
  *               sequence on; the form the library itself falls back to for matrices of 2 GiB or more).
- * Other values return MTP_ERR_MODE.  Results agree between the modes to rounding (bit for bit for one
- * sequence between modes 0, 1 and 2).
+ * Other values return MTP_ERR_MODE.  Results agree between the modes to rounding (one sequence: bit for bit between
+ * modes 0 and 3; the single-launch kernel adds the two halves of the projection separately).
  */
 int32_t mtp_set_launch_mode(mtp_handle *h, int32_t mode);
 
 /*
- * Diagnostics for the single-launch mode: device_buffer (device, int64 [max_draft_steps][16], or NULL to stop)
- * receives workgroup 0's 100 MHz wall-clock stamps: entry 2f = start of phase f, 2f+1 = its end (= start of the
- * barrier after it), entry 14 = end of the step's last barrier.
+ * Diagnostics for the single-launch kernel of one sequence: device_buffer (device, int64, mtp_phase_trace_bytes(cfg)
+ * bytes, or NULL to stop) receives 100 MHz wall-clock stamps of EVERY workgroup, laid out
+ * [step][section 0..7][point 0..3][workgroup 0..W-1] with W = the device's compute-unit count: sections are the phases
+ * of a draft step in order (0 projection, 1 q/k/v, 2 attention, 3 output projection, 4 gate/up, 5 down, 6 output head,
+ * 7 unused); points: 0 the section's first weights have been requested, 1 its input is available (the hand-over from
+ * the phase before has completed), 2 the input is staged in LDS, 3 its results are stored.
  */
+size_t mtp_phase_trace_bytes(const mtp_config *cfg);
 int32_t mtp_set_phase_trace(mtp_handle *h, void *device_buffer);
 
 /*

@@ -33,6 +33,7 @@ EXPORTS = ["mtp_status_string", "mtp_workspace_bytes", "mtp_draft_init", "mtp_dr
            "mtp_train_workspace_bytes", "mtp_train_loss",
            "mtp_accept",
            "mtp_poll_error", "mtp_set_timing", "mtp_last_draft_ms", "mtp_set_launch_mode", "mtp_set_phase_trace",
+           "mtp_phase_trace_bytes",
            "mtp_draft_destroy"]
 LAUNCH_PER_PHASE, LAUNCH_SINGLE, LAUNCH_AUTO, LAUNCH_ROWS = 0, 1, 2, 3
 # mtp_set_timing modes
@@ -99,6 +100,8 @@ _lib.mtp_last_draft_ms.restype = C.c_float
 _lib.mtp_last_draft_ms.argtypes = [C.c_void_p]
 _lib.mtp_set_launch_mode.restype = C.c_int32
 _lib.mtp_set_launch_mode.argtypes = [C.c_void_p, C.c_int32]
+_lib.mtp_phase_trace_bytes.restype = C.c_size_t
+_lib.mtp_phase_trace_bytes.argtypes = [C.POINTER(mtp_config)]
 _lib.mtp_set_phase_trace.restype = C.c_int32
 _lib.mtp_set_phase_trace.argtypes = [C.c_void_p, C.c_void_p]
 _lib.mtp_draft_destroy.restype = None
@@ -225,6 +228,14 @@ def mtp_last_draft_ms(handle) -> float:
 
 def mtp_set_launch_mode(handle, mode: int) -> int:
     return int(_lib.mtp_set_launch_mode(handle, mode))
+
+
+def mtp_phase_trace_bytes(cfg: mtp_config) -> int:
+    return int(_lib.mtp_phase_trace_bytes(C.byref(cfg)))
+
+
+TRACE_SECTIONS = ["proj", "qkv", "attn", "oproj", "gateup", "down", "lmhead", "unused"]
+TRACE_POINTS = ["requested", "released", "staged", "done"]
 
 
 def mtp_set_phase_trace(handle, device_buffer) -> int:

@@ -12,7 +12,7 @@
 #include <vector>
 
 #include "phases.h"
-#include "fused.h"
+#include "flow.h"
 #include "batch_launch.h"
 
 using namespace mtp;
@@ -53,18 +53,12 @@ __global__ __launch_bounds__(kBlock) void k_lmhead(DraftParams p, int step) {
 }
 __global__ void k_finalize(DraftParams p) { phase_finalize(p, blockIdx.x, gridDim.x); }
 template <int G, int HD>
-__global__ __launch_bounds__(kBlock) void k_fused(DraftParams) {
+__global__ __launch_bounds__(kBlock) void k_flow(DraftParams) {
     extern __shared__ __align__(16) char smem[];
     // the attention phase is called out of line and takes the parameters by reference: point it at the
     // kernel-argument segment (the struct is the only argument, at offset 0) instead of a per-lane stack copy
     const DraftParams *p = (const DraftParams *)__builtin_amdgcn_kernarg_segment_ptr();
-    fused_steps2<G, HD>(*p, smem);
-}
-template <int G, int HD>
-__global__ __launch_bounds__(kBlock) void k_fused_rows(DraftParams) {
-    extern __shared__ __align__(16) char smem[];
-    const DraftParams *p = (const DraftParams *)__builtin_amdgcn_kernarg_segment_ptr();
-    fused_steps_rows<G, HD>(*p, smem);
+    flow_steps<G, HD>(*p, smem);
 }
 
 // Sequential acceptance up to the first mismatch and the draft-cache length after it (Sec. 2.3 "Verification phase").
@@ -265,38 +259,20 @@ phase_kernel_t attn_kernel(int G, int HD) {
     return nullptr;
 }
 typedef void (*fused_kernel_t)(DraftParams);
-fused_kernel_t fused_kernel(int G, int HD) {
+fused_kernel_t flow_kernel(int G, int HD) {
     if (HD == 128) {
         switch (G) {
-        case 1: return k_fused<1, 128>;
-        case 2: return k_fused<2, 128>;
-        case 4: return k_fused<4, 128>;
-        case 8: return k_fused<8, 128>;
+        case 1: return k_flow<1, 128>;
+        case 2: return k_flow<2, 128>;
+        case 4: return k_flow<4, 128>;
+        case 8: return k_flow<8, 128>;
         }
     } else if (HD == 64) {
         switch (G) {
-        case 1: return k_fused<1, 64>;
-        case 2: return k_fused<2, 64>;
-        case 4: return k_fused<4, 64>;
-        case 8: return k_fused<8, 64>;
-        }
-    }
-    return nullptr;
-}
-fused_kernel_t fused_rows_kernel(int G, int HD) {
-    if (HD == 128) {
-        switch (G) {
-        case 1: return k_fused_rows<1, 128>;
-        case 2: return k_fused_rows<2, 128>;
-        case 4: return k_fused_rows<4, 128>;
-        case 8: return k_fused_rows<8, 128>;
-        }
-    } else if (HD == 64) {
-        switch (G) {
-        case 1: return k_fused_rows<1, 64>;
-        case 2: return k_fused_rows<2, 64>;
-        case 4: return k_fused_rows<4, 64>;
-        case 8: return k_fused_rows<8, 64>;
+        case 1: return k_flow<1, 64>;
+        case 2: return k_flow<2, 64>;
+        case 4: return k_flow<4, 64>;
+        case 8: return k_flow<8, 64>;
         }
     }
     return nullptr;
@@ -358,7 +334,8 @@ constexpr int kMaxFusedGrid = 1024; // workgroups of the single-launch kernel (o
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct WsLayout {
-    size_t x, qkv, attn, o, gu, dn, hhat, err, bar, cand, rope_inv, attn_part, total;
+    size_t x, qkv, attn, o, gu, dn, hhat, err, cand, rope_inv, attn_part, total;
+    size_t xt, qkvt, attnt, ot, gut, dnt, candt, tagged_end; // tagged hand-over vectors of the barrier-free kernel
     // batched path (max_batch above kBatchMinSeq - 1 only)
     size_t act0, act1, ssq, part, ticket, a_lo, attn_ticket, row_len, seq_list, list_ids, list_n, list_cands;
     int a_stride;
@@ -395,7 +372,6 @@ WsLayout ws_layout(const mtp_config &c) {
     l.dn = take(mb * d * 4);
     l.hhat = take(mb * d * 4);
     l.err = take(4);
-    l.bar = take(kBarWords * 8);
     l.cand = take((size_t)c.max_draft_steps * mb * kMaxFusedGrid * 8);
     l.rope_inv = take((size_t)c.head_dim / 2 * 8);
     l.attn_part = take(attn_part_floats(c) * 4);
@@ -405,6 +381,14 @@ WsLayout ws_layout(const mtp_config &c) {
     l.list_ids = take(kMaxListGroups * 8);
     l.list_n = take(kMaxListGroups * 4);
     l.list_cands = take(kMaxListGroups * 4);
+    l.xt = take(d * 8);
+    l.qkvt = take((qd + 2 * kvd) * 8);
+    l.attnt = take(qd * 8);
+    l.ot = take(d * 8);
+    l.gut = take((size_t)c.d_ffn * 2 * 8);
+    l.dnt = take(d * 8);
+    l.candt = take((size_t)c.max_draft_steps * kMaxFusedGrid * 16);
+    l.tagged_end = off;
     if (c.max_batch >= kBatchMinSeq) {
         size_t kmax = std::max({2 * d, qd, (size_t)c.d_ffn});
         l.a_stride = (int)((kmax + 31) / 32 * 32);
@@ -436,11 +420,9 @@ struct mtp_handle {
     int num_cus;
     size_t lds_limit;
     phase_kernel_t attn_fn;
-    fused_kernel_t fused_fn;
-    fused_kernel_t fused_rows_fn;  // one sequence, row-streaming core
+    fused_kernel_t flow_fn;        // one sequence: all phases of all steps in one cooperative launch
+    unsigned long long flow_tags;  // hand-over tags given to earlier calls of that kernel
     int mode;                    // 0: one launch per phase, 1: single cooperative launch for the whole call
-    unsigned long long bar_epochs; // barriers completed by earlier single-launch calls (mirror of the device state)
-    int fused_grid;                // workgroups of those calls; the counters assume it never changes
     long long *trace;             // optional device buffer for phase time stamps
     int timing;         // 0 off, 1 whole call, 2 + phase: every launch of one phase
     hipEvent_t ev[2];   // whole call
@@ -549,13 +531,11 @@ int32_t mtp_draft_init(mtp_handle **out, const mtp_config *cfg, const mtp_weight
     h->num_cus = cus;
     h->lds_limit = (size_t)lds;
     h->attn_fn = attn_kernel(cfg->n_q_heads / cfg->n_kv_heads, cfg->head_dim);
-    h->fused_fn = fused_kernel(cfg->n_q_heads / cfg->n_kv_heads, cfg->head_dim);
-    h->fused_rows_fn = fused_rows_kernel(cfg->n_q_heads / cfg->n_kv_heads, cfg->head_dim);
+    h->flow_fn = flow_kernel(cfg->n_q_heads / cfg->n_kv_heads, cfg->head_dim);
+    h->flow_tags = 0;
     h->mode = 2;
-    h->bar_epochs = 0;
-    h->fused_grid = 0;
     h->trace = nullptr;
-    if (ok && (h->attn_fn == nullptr || h->fused_fn == nullptr)) {
+    if (ok && (h->attn_fn == nullptr || h->flow_fn == nullptr)) {
         fprintf(stderr, "mtp_draft_init: no kernel for this head geometry\n");
         ok = false;
     }
@@ -567,7 +547,7 @@ int32_t mtp_draft_init(mtp_handle **out, const mtp_config *cfg, const mtp_weight
                {(const void *)k_oproj, "k_oproj"},       {(const void *)k_gateup, "k_gateup"},
                {(const void *)k_down, "k_down"},         {(const void *)k_lmhead, "k_lmhead"},
                {(const void *)h->attn_fn, "k_attn"},
-               {(const void *)h->fused_fn, "k_fused"},   {(const void *)h->fused_rows_fn, "k_fused_rows"}};
+               {(const void *)h->flow_fn, "k_flow"}};
     for (const auto &f : fns)
         if (ok) run(hipFuncSetAttribute(f.fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)h->lds_limit), f.name);
     if (ok && !batch_allow_lds(h->lds_limit)) {
@@ -697,9 +677,14 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
     p.attn_part = reinterpret_cast<float *>(ws + l.attn_part);
     p.attn_ticket = reinterpret_cast<int *>(ws + l.attn_ticket); // the vector attention merges its own splits
     p.attn_queue = p.attn_ticket + (size_t)c.max_batch * c.n_kv_heads;
-    p.bar = reinterpret_cast<unsigned long long *>(ws + l.bar);
-    p.bar_base = h->bar_epochs;
     p.cand = reinterpret_cast<unsigned long long *>(ws + l.cand);
+    p.xt = reinterpret_cast<unsigned long long *>(ws + l.xt);
+    p.qkvt = reinterpret_cast<unsigned long long *>(ws + l.qkvt);
+    p.attnt = reinterpret_cast<unsigned long long *>(ws + l.attnt);
+    p.ot = reinterpret_cast<unsigned long long *>(ws + l.ot);
+    p.gut = reinterpret_cast<unsigned long long *>(ws + l.gut);
+    p.dnt = reinterpret_cast<unsigned long long *>(ws + l.dnt);
+    p.candt = reinterpret_cast<unsigned long long *>(ws + l.candt);
     p.bar_timeout = 200000000ll; // 2 s of the 100 MHz wall clock
     p.trace = h->trace;
     p.max_batch = c.max_batch;
@@ -765,35 +750,35 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
 
     const int tphase = h->timing >= 2 ? h->timing - 2 : -1;
     h->pev_used = 0;
-    // one sequence and every reduction at least 512 long: the single launch has the row-streaming core (which keeps no id
-    // strip in LDS) and is the faster way; mode 2 picks it there and nowhere else
+    // One sequence and every reduction at least 512 long: all phases of all K steps in ONE cooperative launch whose
+    // workgroups hand their results over as tagged elements (flow.h).  Every workgroup must be resident at once (one per
+    // CU; the cooperative launch checks it).  Mode 2 picks it where it applies; more sequences, and shapes it does not
+    // serve, take one launch per phase in every mode.
     const bool rows = B == 1 && p.d >= 512 && p.qd >= 512 && p.F >= 512;
-    if ((h->mode == 1 || (h->mode == 2 && rows)) && tphase < 0 && !ext && !seq_subset) {
-        // single launch: all B sequences are staged together and every workgroup must be resident at once (one
-        // per CU; the cooperative launch checks it).  Falls back to one launch per phase when LDS cannot hold B.
+    if ((h->mode == 1 || h->mode == 2) && rows && tphase < 0 && !ext && !seq_subset) {
         const int fgrid = std::min(h->num_cus, kMaxFusedGrid);
-        size_t region = std::max(fused_gemv_region(p.d, p.qd, p.F, B), lds_attn);
+        size_t region = std::max(flow_gemv_region(p.d, p.qd, p.F), lds_attn);
         region = (region + 255) / 256 * 256;
-        const size_t ids_bytes = rows ? 0 : ((size_t)(p.n + fgrid - 1) / fgrid * 4 + 255) / 256 * 256;
-        const size_t lds_fused = region + ids_bytes + 256;
-        if (B <= 16 && lds_fused <= h->lds_limit) {
+        const size_t lds_flow = region + ((size_t)p.d + flow_part_floats(p.d, fgrid)) * 4 + 256;
+        if (lds_flow <= h->lds_limit) {
             p.head_grid = fgrid;
             p.fused_gemv_bytes = (int)region;
-            p.fused_ids_bytes = (int)ids_bytes;
-            if (h->fused_grid != fgrid) { // first use, or the grid changed: restart the barrier counters
-                hipLaunchKernelGGL(k_zero_words, dim3(((int)kBarWords + 255) / 256), dim3(256), 0, st,
-                                   reinterpret_cast<unsigned long long *>(ws + l.bar), (int)kBarWords);
-                h->bar_epochs = 0;
-                h->fused_grid = fgrid;
-                p.bar_base = 0;
+            // tags of this call: tag_base + 1 .. tag_base + 8 K, never 0 and never reused: when the 32-bit counter would
+            // wrap, the tagged vectors are cleared and the count starts over
+            const unsigned long long need = 8ull * (unsigned long long)K + 8ull;
+            if ((h->flow_tags & 0xffffffffull) + need > 0xffffffffull) {
+                const size_t words = (l.tagged_end - l.xt) / 8;
+                hipLaunchKernelGGL(k_zero_words, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st,
+                                   reinterpret_cast<unsigned long long *>(ws + l.xt), (int)words);
+                h->flow_tags = 0;
             }
+            p.tag_base = (unsigned)h->flow_tags;
             void *args[] = {(void *)&p};
             if (h->timing == 1) (void)hipEventRecord(h->ev[0], st);
-            const bool launched =
-                hipLaunchCooperativeKernel((const void *)(rows ? h->fused_rows_fn : h->fused_fn), dim3(fgrid),
-                                           dim3(kBlock), args, (unsigned)lds_fused, st) == hipSuccess;
+            const bool launched = hipLaunchCooperativeKernel((const void *)h->flow_fn, dim3(fgrid), dim3(kBlock), args,
+                                                             (unsigned)lds_flow, st) == hipSuccess;
             if (launched) {
-                h->bar_epochs += (unsigned long long)K * kBarriersPerStep;
+                h->flow_tags += 8ull * (unsigned long long)K;
                 if (h->timing == 1) {
                     (void)hipEventRecord(h->ev[1], st);
                     h->ev_recorded = true;
@@ -865,7 +850,7 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
     // matrix with 32-bit offsets and mark missing rows with an offset of 2 GiB.
     const size_t widest = std::max({(size_t)p.V * p.d, (size_t)p.d * 2 * p.d, (size_t)p.F * p.d, (size_t)p.qd * p.d}) * 2;
     const bool rows_wanted = h->mode == 3 && B <= kMaxRowSeq; // the row-streaming kernels on request
-    if (B >= kBatchMinSeq && (h->mode != 1 || B > 16) && !rows_wanted && widest < ((size_t)1 << 31)) {
+    if (B >= kBatchMinSeq && !rows_wanted && widest < ((size_t)1 << 31)) {
         p.act[0] = reinterpret_cast<uint16_t *>(ws + l.act0);
         p.act[1] = reinterpret_cast<uint16_t *>(ws + l.act1);
         p.a_lo = l.a_lo;
@@ -1174,14 +1159,12 @@ int32_t mtp_poll_error(mtp_handle *h, void *hip_stream) {
     if (hipStreamSynchronize(st) != hipSuccess) return MTP_ERR_HIP;
     if (word != 0) {
         if (hipMemsetAsync(dev, 0, 4, st) != hipSuccess) return MTP_ERR_HIP;
-        if (word & kErrBarrierTimeout) { // the barrier counter is out of step with the host's mirror: restart both
-            if (hipMemsetAsync(h->ws + h->lay.bar, 0, 8, st) != hipSuccess) return MTP_ERR_HIP;
-            // a kernel that gave up may have left arrival counters of the attention splits behind
+        if (word & kErrBarrierTimeout) {
+            // a kernel that gave up may have left arrival counters of the attention splits behind (the hand-over tags
+            // need nothing: the next call's tags are larger than any the abandoned call wrote)
             if (hipMemsetAsync(h->ws + h->lay.attn_ticket, 0, (size_t)h->cfg.max_batch * h->cfg.n_kv_heads * 4 + 64, st) !=
                 hipSuccess)
                 return MTP_ERR_HIP;
-            h->bar_epochs = 0;
-    h->fused_grid = 0;
         }
         if (hipStreamSynchronize(st) != hipSuccess) return MTP_ERR_HIP;
     }
@@ -1205,6 +1188,11 @@ int32_t mtp_set_launch_mode(mtp_handle *h, int32_t mode) {
     if (mode < 0 || mode > 3) return MTP_ERR_MODE;
     h->mode = mode;
     return MTP_OK;
+}
+
+size_t mtp_phase_trace_bytes(const mtp_config *cfg) {
+    if (!config_ok(cfg)) return 0;
+    return (size_t)cfg->max_draft_steps * kTraceSections * kTracePoints * kMaxFusedGrid * sizeof(long long);
 }
 
 int32_t mtp_set_phase_trace(mtp_handle *h, void *device_buffer) {

@@ -30,8 +30,6 @@ struct DraftParams {
                                                             // (residuals and SiLU*mul are applied by the consumers)
     int *err;                 // sticky error word
     const double *rope_inv;   // [hd/2] rotary pair frequencies theta^(-2j/hd), computed on the host in double
-    unsigned long long *bar;  // grid-barrier counters and flags of the single-launch path (they only ever grow)
-    unsigned long long bar_base; // barriers completed by earlier launches
     unsigned long long *cand; // [max_draft_steps][max_batch][head_grid] packed (logit, index) maximum of every
                               // workgroup of the output-head phase; the consumer takes the maximum over them
     int head_grid;            // workgroups of the output-head phase = candidates per sequence (their stride in cand)
@@ -43,9 +41,9 @@ struct DraftParams {
     const int *list_cands;           // per slot: candidates the head's launch leaves per sequence (<= head_grid)
     int seq_lo, seq_hi;              // output head, launch per phase: sequences of this launch (0, B if one list)
     int logit_stride;                // floats per (sequence, step) in logits_out: n, or the largest n of the lists
-    int fused_gemv_bytes, fused_ids_bytes; // LDS carve-up of the single-launch kernel
-    long long bar_timeout;    // wall-clock ticks a workgroup may wait at one barrier before giving up
-    long long *trace;         // optional [K][16] wall-clock stamps (100 MHz) of workgroup 0 in the single-launch path
+    int fused_gemv_bytes;     // single-launch kernel: bytes of LDS shared by the staged activations and the attention
+    long long bar_timeout;    // wall-clock ticks a workgroup may wait for a hand-over before giving up
+    long long *trace;         // optional wall-clock stamps (100 MHz) of every workgroup of the single-launch kernel
     int max_batch;
     // launch plan
     int split_tokens, max_splits; // attention: tokens per split, splits per (sequence, KV head)
@@ -71,6 +69,12 @@ struct DraftParams {
     int *attn_queue;     // two words (zero between launches): next item of the attention launch that hands its items
                          // out one by one, and the workgroups that have left it
     int b0, nb;          // sequences of this pass
+    // Hand-over by tagged elements (single-launch kernel for one sequence without grid barriers): every element of
+    // a vector that crosses from one phase to the next is a 64-bit word (float bits, tag in the upper half); the
+    // tag names the (call, step, phase) that produced it, so a consumer that polls an element knows when it is there.
+    unsigned long long *xt, *qkvt, *attnt, *ot, *gut, *dnt; // [d], [qkv_dim], [qd], [d], [2F], [d]
+    unsigned long long *candt; // [max_draft_steps][head_grid][2]: (orderable logit, tag), (token id, tag)
+    unsigned tag_base;         // tag of (step, section) = tag_base + 8 * step + section + 1; never 0
     int bg_rg[6], bg_kp[6]; // row groups and reduction parts of the six matrix phases
     int bg_sep[6];          // 1: the phase's epilogue runs as a kernel of its own
 };
@@ -79,6 +83,48 @@ enum : int { kErrKvOverflow = 1, kErrTokenRange = 2, kErrBarrierTimeout = 4 };
 // matrix phases of the batched path, and the vectors whose sums of squares travel with them
 enum : int { BG_PROJ = 0, BG_QKV, BG_OPROJ, BG_GATEUP, BG_DOWN, BG_LMHEAD, BG_COUNT };
 enum : int { SSQ_X = 0, SSQ_X1, SSQ_X2, SSQ_COUNT };
+
+// ---------------------------------------------------------------------------------------------------
+// tagged hand-over elements
+// ---------------------------------------------------------------------------------------------------
+// sections of a draft step whose results cross to other workgroups, in order; tag = tag_base + 8 * step + section + 1
+enum : int { TS_X = 0, TS_QKV, TS_ATTN, TS_O, TS_GU, TS_DN, TS_CAND };
+__device__ __forceinline__ unsigned step_tag(const DraftParams &p, int step, int section) {
+    return p.tag_base + 8u * (unsigned)step + (unsigned)section + 1u;
+}
+__device__ __forceinline__ unsigned long long pack_tagged(float v, unsigned tag) {
+    return ((unsigned long long)tag << 32) | (unsigned long long)__float_as_uint(v);
+}
+__device__ __forceinline__ void st_tagged(unsigned long long *p, float v, unsigned tag) {
+    __hip_atomic_store(p, pack_tagged(v, tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// Bounded wait shared by every poll loop of the barrier-free kernel: true once the time limit has passed (then the
+// sticky error word is set and every later wait of every workgroup gives up at its first check, so the grid drains).
+struct PollClock {
+    long long t0;
+    unsigned spins;
+    __device__ __forceinline__ PollClock() : t0(wall_clock64()), spins(0) {}
+    __device__ __forceinline__ bool expired(const DraftParams &p) {
+        if ((++spins & 31u) != 0) return false;
+        if (__hip_atomic_load(p.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & kErrBarrierTimeout) return true;
+        if (wall_clock64() - t0 > p.bar_timeout) {
+            atomicOr(p.err, kErrBarrierTimeout);
+            return true;
+        }
+        return false;
+    }
+};
+// one element, polled until its tag is the wanted one
+__device__ __forceinline__ float ld_tagged(const DraftParams &p, const unsigned long long *src, unsigned tag) {
+    unsigned long long w = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if ((unsigned)(w >> 32) != tag) {
+        PollClock clk;
+        do {
+            w = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        } while ((unsigned)(w >> 32) != tag && !clk.expired(p));
+    }
+    return __uint_as_float((unsigned)w);
+}
 
 // ---------------------------------------------------------------------------------------------------
 // per-sequence state helpers
@@ -836,12 +882,16 @@ __device__ __forceinline__ void rope_cos_sin(int pos, double inv_freq, float &cs
 // are formed once (in the wave-private LDS strip w of max_splits floats), then every lane sums its share of the head
 // dimension with sixteen loads in flight.  PCOH: the partials are read with device-coherent loads; OCOH: the result
 // is written with a device-coherent store.
-template <int HD, bool PCOH, bool OCOH>
-__device__ __forceinline__ void merge_head(const DraftParams &p, int b, int hq, int nsplit, float *w) {
+template <int HD, bool PCOH, bool OCOH, bool TAGGED = false>
+__device__ __forceinline__ void merge_head(const DraftParams &p, int b, int hq, int nsplit, float *w, int step = 0) {
     const int lane = threadIdx.x & (kWave - 1);
     const int S = p.max_splits, PW = HD + 2;
     const float *src = p.attn_part + ((size_t)b * p.Hq + hq) * S * PW;
     auto store = [&](int dd, float r) {
+        if (TAGGED) { // one sequence: the consumer polls the element itself
+            st_tagged(p.attnt + (size_t)hq * HD + dd, r, step_tag(p, step, TS_ATTN));
+            return;
+        }
         st_f32<OCOH>(p.attn + (size_t)b * p.qd + (size_t)hq * HD + dd, r);
         if (p.attn_split) {
             uint16_t h, l;
@@ -920,7 +970,8 @@ struct NoHook {
     __device__ __forceinline__ void operator()() const {}
 };
 // before_q: called once, by all threads, after the first cache loads have been requested and before q/k/v are read
-template <int G, int HD, bool COH = false, bool TICKET = false, class Hook = NoHook>
+// TAGGED (one sequence, implies COH): q/k/v are polled as tagged elements and the result is written as tagged elements
+template <int G, int HD, bool COH = false, bool TICKET = false, class Hook = NoHook, bool TAGGED = false>
 __device__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char *smem, Hook before_q = Hook()) {
     using L = AttnLds<G, HD>;
     constexpr int LPT = L::LPT, TPI = L::TPI, NSTREAM = L::NSTREAM, U = 4;
@@ -980,10 +1031,15 @@ __device__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char
         const bool has_v = last && tid >= kWave * 6 && tid < kWave * 6 + HD;
         const int jj = tid % (HD / 2), gq = tid / (HD / 2);
         float qa = 0.f, qb = 0.f, ka = 0.f, kb = 0.f, vraw = 0.f, cs = 1.f, sn = 0.f;
+        const unsigned tag_in = TAGGED ? step_tag(p, step, TS_QKV) : 0u;
+        auto ld_in = [&](const float *src) { // one element of this sequence's q/k/v vector
+            if (TAGGED) return ld_tagged(p, p.qkvt + (src - qkv), tag_in);
+            return ld_f32<COH>(src);
+        };
         if (has_q) {
             const float *src = qkv + (size_t)(kvh * G + gq) * HD;
-            qa = ld_f32<COH>(src + jj);
-            qb = ld_f32<COH>(src + jj + HD / 2);
+            qa = ld_in(src + jj);
+            qb = ld_in(src + jj + HD / 2);
             if (p.b_q) {
                 qa += bf16_to_f32(p.b_q[(kvh * G + gq) * HD + jj]);
                 qb += bf16_to_f32(p.b_q[(kvh * G + gq) * HD + jj + HD / 2]);
@@ -991,8 +1047,8 @@ __device__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char
         }
         if (has_k) {
             const float *src = qkv + p.qd + (size_t)kvh * HD;
-            ka = ld_f32<COH>(src + jj);
-            kb = ld_f32<COH>(src + jj + HD / 2);
+            ka = ld_in(src + jj);
+            kb = ld_in(src + jj + HD / 2);
             if (p.b_k) {
                 ka += bf16_to_f32(p.b_k[kvh * HD + jj]);
                 kb += bf16_to_f32(p.b_k[kvh * HD + jj + HD / 2]);
@@ -1000,7 +1056,7 @@ __device__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char
         }
         if (has_v) {
             const int e = tid - kWave * 6;
-            vraw = ld_f32<COH>(qkv + p.qd + p.kvd + (size_t)kvh * HD + e);
+            vraw = ld_in(qkv + p.qd + p.kvd + (size_t)kvh * HD + e);
             if (p.b_v) vraw += bf16_to_f32(p.b_v[kvh * HD + e]);
         }
         if (has_q || has_k) rope_cos_sin(pnew, p.rope_inv[jj], cs, sn);
@@ -1114,6 +1170,10 @@ __device__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char
             absorb(sc, vv, okn);
         }
         // merge the lane groups of the workgroup
+        // (a single split publishes its result as tagged elements that other workgroups act on at once: the appended
+        // cache entry, written by waves of this workgroup above, is acknowledged first; the barriers below order it
+        // before every wave's result stores)
+        if (TAGGED && nsplit == 1) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         const int stream = wave * TPI + tq;
 #pragma unroll
         for (int g = 0; g < G; ++g) {
@@ -1153,8 +1213,11 @@ __device__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char
             int hq = kvh * G + g;
             if (nsplit == 1) {
                 const float r = A / Ls;
-                st_f32<COH>(p.attn + (size_t)b * p.qd + (size_t)hq * HD + dd, r);
-                if (p.attn_split) {
+                if (TAGGED)
+                    st_tagged(p.attnt + (size_t)hq * HD + dd, r, step_tag(p, step, TS_ATTN));
+                else
+                    st_f32<COH>(p.attn + (size_t)b * p.qd + (size_t)hq * HD + dd, r);
+                if (!TAGGED && p.attn_split) {
                     uint16_t h, l;
                     split_bf16(r, h, l);
                     const size_t at = (size_t)b * p.a_stride + (size_t)hq * HD + dd;
@@ -1187,7 +1250,8 @@ __device__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char
             __syncthreads();
             const bool merges = last_to_arrive != 0;
             if (merges && wave < G)
-                merge_head<HD, true, COH>(p, b, kvh * G + wave, nsplit, reinterpret_cast<float *>(smem) + (size_t)wave * S);
+                merge_head<HD, true, COH, TAGGED>(p, b, kvh * G + wave, nsplit,
+                                                  reinterpret_cast<float *>(smem) + (size_t)wave * S, step);
         }
     }
     if (first_item) before_q();
@@ -1360,9 +1424,9 @@ __device__ void phase_finalize(const DraftParams &p, int vb, int nvb) {
 
 // Out-of-line copy of the attention phase for the single-launch kernel: inlined next to the weight-streaming code
 // it would share one register budget with the prefetch ring and spill.
-template <int G, int HD, bool COH = false, bool TICKET = false>
+template <int G, int HD, bool COH = false, bool TICKET = false, bool TAGGED = false>
 __device__ __noinline__ void call_attn(const DraftParams &p, int step, int vb, int nvb, char *smem) {
-    phase_attn<G, HD, COH, TICKET>(p, step, vb, nvb, smem);
+    phase_attn<G, HD, COH, TICKET, NoHook, TAGGED>(p, step, vb, nvb, smem);
 }
 
 } // namespace mtp

@@ -341,7 +341,9 @@ def test_device_detected_errors(gpu, tiny):
 
 
 def test_single_launch_mode_matches_oracle(gpu, tiny):
-    """The cooperative single-launch path (grid barriers inside one kernel) against the oracle, ragged batch."""
+    """Launch mode 1 with several sequences against the oracle, ragged batch, two calls per engine.  (Mode 1 is the
+    single cooperative launch for ONE sequence; a kernel that ran several sequences in one launch behind grid barriers
+    was retired, so several sequences take the kernels of mode 0 whatever the mode says.)"""
     torch, binding = gpu["torch"], gpu["binding"]
     act = synth.make_activations(tiny["wl"], ctx=np.array([0, 130, 64], dtype=np.int32), capacity=192)
     eng = binding.DraftEngine(tiny["shape"], tiny["w"], [tiny["ids"]], 3, 192, 3)
