@@ -242,9 +242,9 @@ __device__ __forceinline__ unsigned long long block_max_u64_lds(unsigned long lo
     return r;
 }
 
-// RMSNorm(u; gain) of the values this thread holds (v[it][q] = element (it * kBlock + tid) * 4 + q of a d-vector) into
-// hi/lo.  keep_raw (LDS, optional) receives u itself, keep_norm (LDS, optional) and out_global (optional) the result.
-__device__ __forceinline__ void flow_norm(float (&v)[kMaxNormIter][4], const uint16_t *gain, int d, float eps,
+// RMSNorm(u; gain) of the values this thread holds (v[it][q] = element (it * kBlock + tid) * 4 + q of a d-vector, gq[it]
+// the four bf16 gains of the same elements) into hi/lo.  keep_raw (LDS, optional) receives u itself, keep_norm (LDS, optional) and out_global (optional) the result.
+__device__ __forceinline__ void flow_norm(float (&v)[kMaxNormIter][4], const u32x2 (&gq)[kMaxNormIter], int d, float eps,
                                           uint16_t *hi, uint16_t *lo, float *red, float *keep_raw, float *keep_norm,
                                           float *out_global) {
     float ss = 0.f;
@@ -263,7 +263,7 @@ __device__ __forceinline__ void flow_norm(float (&v)[kMaxNormIter][4], const uin
     for (int it = 0; it < kMaxNormIter; ++it) {
         const int e = (it * kBlock + (int)threadIdx.x) * 4;
         if (e < d) {
-            const u32x2 g = *reinterpret_cast<const u32x2 *>(gain + e);
+            const u32x2 g = gq[it];
             float o[4];
             o[0] = lo_half(g.x) * (v[it][0] * inv);
             o[1] = hi_half(g.x) * (v[it][1] * inv);
@@ -362,6 +362,16 @@ __device__ __forceinline__ void flow_steps(const DraftParams &p, char *smem) {
             // ---- stage this phase's input vector into LDS as bf16 hi + lo ------------------------------------------
             {
                 float v[kMaxNormIter][4];
+                // The gains of this phase's norm are requested before anything is polled: they do not depend on it, and a
+                // load issued after the poll would add its own trip through the (busy) memory system to the hand-over.
+                const uint16_t *gain = ph == FL_PROJH ? p.g_h : ph == FL_PROJE ? p.g_e : ph == FL_QKV ? p.g_attn
+                                       : ph == FL_GATEUP ? p.g_mlp : p.g_final;
+                u32x2 gq[kMaxNormIter];
+#pragma unroll
+                for (int it = 0; it < kMaxNormIter; ++it) {
+                    const int e = (it * kBlock + (int)threadIdx.x) * 4;
+                    gq[it] = (e < d && ph != FL_O && ph != FL_DOWN) ? *reinterpret_cast<const u32x2 *>(gain + e) : u32x2{0u, 0u};
+                }
                 switch (ph) {
                 case FL_PROJH: {
                     if (step == 0) {
@@ -398,7 +408,7 @@ __device__ __forceinline__ void flow_steps(const DraftParams &p, char *smem) {
                         }
                     }
                     stamp(step, sec, kTraceReleased);
-                    flow_norm(v, p.g_h, d, p.eps, l.hi, l.lo, red, nullptr, nullptr, nullptr);
+                    flow_norm(v, gq, d, p.eps, l.hi, l.lo, red, nullptr, nullptr, nullptr);
                     break;
                 }
                 case FL_PROJE: {
@@ -427,13 +437,13 @@ __device__ __forceinline__ void flow_steps(const DraftParams &p, char *smem) {
                             v[it][3] = hi_half(raw.y);
                         }
                     }
-                    flow_norm(v, p.g_e, d, p.eps, l.hi, l.lo, red, nullptr, nullptr, nullptr);
+                    flow_norm(v, gq, d, p.eps, l.hi, l.lo, red, nullptr, nullptr, nullptr);
                     break;
                 }
                 case FL_QKV:
                     poll_vec<kMaxNormIter>(p, p.xt, d, step_tag(p, step, TS_X), v);
                     stamp(step, sec, kTraceReleased);
-                    flow_norm(v, p.g_attn, d, p.eps, l.hi, l.lo, red, resid, nullptr, nullptr);
+                    flow_norm(v, gq, d, p.eps, l.hi, l.lo, red, resid, nullptr, nullptr);
                     break;
                 case FL_GATEUP: { // x1 = x + w_o a
                     poll_vec<kMaxNormIter>(p, p.ot, d, step_tag(p, step, TS_O), v);
@@ -449,7 +459,7 @@ __device__ __forceinline__ void flow_steps(const DraftParams &p, char *smem) {
                             v[it][3] = r.w + v[it][3];
                         }
                     }
-                    flow_norm(v, p.g_mlp, d, p.eps, l.hi, l.lo, red, resid, nullptr, nullptr);
+                    flow_norm(v, gq, d, p.eps, l.hi, l.lo, red, resid, nullptr, nullptr);
                     break;
                 }
                 case FL_HEAD: { // x2 = x1 + w_down m; the step's output hidden state
@@ -467,7 +477,7 @@ __device__ __forceinline__ void flow_steps(const DraftParams &p, char *smem) {
                         }
                     }
                     float *ho = (vb == 0 && p.hidden_out) ? p.hidden_out + (size_t)step * d : nullptr;
-                    flow_norm(v, p.g_final, d, p.eps, l.hi, l.lo, red, nullptr, resid, ho);
+                    flow_norm(v, gq, d, p.eps, l.hi, l.lo, red, nullptr, resid, ho);
                     break;
                 }
                 case FL_O: { // the attention's result, as it is

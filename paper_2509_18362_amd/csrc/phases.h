@@ -126,6 +126,22 @@ __device__ __forceinline__ float ld_tagged(const DraftParams &p, const unsigned 
     return __uint_as_float((unsigned)w);
 }
 
+// two elements, polled together
+__device__ __forceinline__ void ld_tagged2(const DraftParams &p, const unsigned long long *a, const unsigned long long *b,
+                                           unsigned tag, float &va, float &vb) {
+    unsigned long long wa = __hip_atomic_load(a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    unsigned long long wb = __hip_atomic_load(b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if ((unsigned)(wa >> 32) != tag || (unsigned)(wb >> 32) != tag) {
+        PollClock clk;
+        do {
+            wa = __hip_atomic_load(a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            wb = __hip_atomic_load(b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        } while (((unsigned)(wa >> 32) != tag || (unsigned)(wb >> 32) != tag) && !clk.expired(p));
+    }
+    va = __uint_as_float((unsigned)wa);
+    vb = __uint_as_float((unsigned)wb);
+}
+
 // ---------------------------------------------------------------------------------------------------
 // per-sequence state helpers
 // ---------------------------------------------------------------------------------------------------
@@ -972,7 +988,7 @@ struct NoHook {
 // before_q: called once, by all threads, after the first cache loads have been requested and before q/k/v are read
 // TAGGED (one sequence, implies COH): q/k/v are polled as tagged elements and the result is written as tagged elements
 template <int G, int HD, bool COH = false, bool TICKET = false, class Hook = NoHook, bool TAGGED = false>
-__device__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char *smem, Hook before_q = Hook()) {
+__device__ __forceinline__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char *smem, Hook before_q = Hook()) {
     using L = AttnLds<G, HD>;
     constexpr int LPT = L::LPT, TPI = L::TPI, NSTREAM = L::NSTREAM, U = 4;
     L &s = *reinterpret_cast<L *>(smem);
@@ -1032,34 +1048,46 @@ __device__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char
         const int jj = tid % (HD / 2), gq = tid / (HD / 2);
         float qa = 0.f, qb = 0.f, ka = 0.f, kb = 0.f, vraw = 0.f, cs = 1.f, sn = 0.f;
         const unsigned tag_in = TAGGED ? step_tag(p, step, TS_QKV) : 0u;
-        auto ld_in = [&](const float *src) { // one element of this sequence's q/k/v vector
-            if (TAGGED) return ld_tagged(p, p.qkvt + (src - qkv), tag_in);
-            return ld_f32<COH>(src);
+        // two elements of this sequence's q/k/v vector (tagged: polled together until both are there)
+        auto ld_in2 = [&](const float *sa, const float *sb, float &va, float &vb) {
+            if (TAGGED) {
+                ld_tagged2(p, p.qkvt + (sa - qkv), p.qkvt + (sb - qkv), tag_in, va, vb);
+            } else {
+                va = ld_f32<COH>(sa);
+                vb = ld_f32<COH>(sb);
+            }
         };
+        // what does not depend on the projection's output comes first (biases, the rotary factors): when q/k/v arrive,
+        // nothing else is waited for
+        float bqa = 0.f, bqb = 0.f, bka = 0.f, bkb = 0.f, bv = 0.f;
+        if (has_q && p.b_q) {
+            bqa = bf16_to_f32(p.b_q[(kvh * G + gq) * HD + jj]);
+            bqb = bf16_to_f32(p.b_q[(kvh * G + gq) * HD + jj + HD / 2]);
+        }
+        if (has_k && p.b_k) {
+            bka = bf16_to_f32(p.b_k[kvh * HD + jj]);
+            bkb = bf16_to_f32(p.b_k[kvh * HD + jj + HD / 2]);
+        }
+        if (has_v && p.b_v) bv = bf16_to_f32(p.b_v[kvh * HD + (tid - kWave * 6)]);
+        if (has_q || has_k) rope_cos_sin(pnew, p.rope_inv[jj], cs, sn);
         if (has_q) {
             const float *src = qkv + (size_t)(kvh * G + gq) * HD;
-            qa = ld_in(src + jj);
-            qb = ld_in(src + jj + HD / 2);
-            if (p.b_q) {
-                qa += bf16_to_f32(p.b_q[(kvh * G + gq) * HD + jj]);
-                qb += bf16_to_f32(p.b_q[(kvh * G + gq) * HD + jj + HD / 2]);
-            }
+            ld_in2(src + jj, src + jj + HD / 2, qa, qb);
+            qa += bqa;
+            qb += bqb;
         }
         if (has_k) {
             const float *src = qkv + p.qd + (size_t)kvh * HD;
-            ka = ld_in(src + jj);
-            kb = ld_in(src + jj + HD / 2);
-            if (p.b_k) {
-                ka += bf16_to_f32(p.b_k[kvh * HD + jj]);
-                kb += bf16_to_f32(p.b_k[kvh * HD + jj + HD / 2]);
-            }
+            ld_in2(src + jj, src + jj + HD / 2, ka, kb);
+            ka += bka;
+            kb += bkb;
         }
         if (has_v) {
-            const int e = tid - kWave * 6;
-            vraw = ld_in(qkv + p.qd + p.kvd + (size_t)kvh * HD + e);
-            if (p.b_v) vraw += bf16_to_f32(p.b_v[kvh * HD + e]);
+            const float *src = qkv + p.qd + p.kvd + (size_t)kvh * HD + (tid - kWave * 6);
+            float dummy;
+            ld_in2(src, src, vraw, dummy);
+            vraw += bv;
         }
-        if (has_q || has_k) rope_cos_sin(pnew, p.rope_inv[jj], cs, sn);
         lds_barrier(); // LDS of the previous item is free
         if (has_q) {
             s.q[gq][jj] = (qa * cs - qb * sn) * scale;
@@ -1422,10 +1450,11 @@ __device__ void phase_finalize(const DraftParams &p, int vb, int nvb) {
     }
 }
 
-// Out-of-line copy of the attention phase for the single-launch kernel: inlined next to the weight-streaming code
-// it would share one register budget with the prefetch ring and spill.
+// The attention phase as the single-launch kernel runs it.  Inlined: as a function of its own it saved and restored
+// about a hundred registers per lane through scratch memory at every call (47 MB written and read back per draft step
+// over the chip, for workgroups without an attention item too), which was most of the phase's 15 us.
 template <int G, int HD, bool COH = false, bool TICKET = false, bool TAGGED = false>
-__device__ __noinline__ void call_attn(const DraftParams &p, int step, int vb, int nvb, char *smem) {
+__device__ __forceinline__ void call_attn(const DraftParams &p, int step, int vb, int nvb, char *smem) {
     phase_attn<G, HD, COH, TICKET, NoHook, TAGGED>(p, step, vb, nvb, smem);
 }
 
