@@ -253,18 +253,19 @@ float mtp_last_draft_ms(mtp_handle *h);
 
 /*
  * How mtp_draft_steps enqueues its work.
- *   2 (default) automatic: mode 1 where it applies, mode 0 otherwise; if the device cannot take the cooperative launch
- *               at that moment (it needs every compute unit), mode 0 for that call.
+ *   2 (default) automatic: mode 1 where it applies, mode 0 otherwise (also when the single launch is refused).
  *   0           one launch per phase.  One sequence: the row-streaming kernels, 7 launches per step plus one to publish
  *               the last draft id.  Two or more (also the rows of a block of positions): the batched kernels (every
  *               weight read once per pass of up to 64 sequences), one preparation launch per step, and one epilogue
  *               launch after each matrix phase whose reduction is split over workgroups (above 16 sequences).
  *               Matrices of 2 GiB or more: as mode 3.
  *   1           one sequence whose reduction lengths (d_model, n_q_heads * head_dim, d_ffn) are all at least 512: one
- *               cooperative launch runs all phases of all K steps; its workgroups hand their results over element by
- *               element (every element carries a tag naming the call, step and phase that produced it, consumers poll
- *               for it), there are no grid barriers.  A wait that does not end within ~2 s sets MTP_ERR_TIMEOUT.  The
- *               launch needs every compute unit of the device to itself.  Every other call: as mode 0.
+ *               launch of one workgroup per compute unit runs all phases of all K steps; its workgroups hand their
+ *               results over element by element (every element carries a tag naming the call, step and phase that
+ *               produced it, consumers poll for it), there are no grid barriers.  The workgroups wait for one another,
+ *               so the launch needs every compute unit of the device to itself: do not overlap it with other kernels
+ *               (other streams, other processes); a wait that does not end within ~2 s gives up and sets
+ *               MTP_ERR_TIMEOUT.  Every other call: as mode 0.
  *   3           as mode 0, with the row-streaming kernels for up to four sequences (slower from the second
  *               sequence on; the form the library itself falls back to for matrices of 2 GiB or more).
  * Other values return MTP_ERR_MODE.  Results agree between the modes to rounding (one sequence: bit for bit between

@@ -1,5 +1,5 @@
 // Single-launch path for ONE sequence without grid barriers (gfx950): all phases of all K draft steps in one
-// cooperative kernel whose workgroups hand their results over element by element.
+// kernel (one workgroup per compute unit, all resident) whose workgroups hand their results over element by element.
 //
 // A draft step at batch 1 is a chain of dependent matrix-vector products (Sec. 2.1) of 30-270 MB each; between two of
 // them every workgroup needs the whole result vector of the phase before.  With a grid barrier that hand-over is a
@@ -52,7 +52,14 @@ struct FlowJob {
     int K, rows;
     const int *ids; // optional row indirection (the compressed output head)
     int paired, pair_rounds, rem, nw;
-    __device__ __forceinline__ const uint16_t *rowptr(int v, int j) const {
+    // The id list is read-only during the call and row indices are wave-uniform: a scalar load (a vector load would make
+    // the wave wait for every weight chunk in flight before it can form the row's address).
+    __device__ __forceinline__ int row_id(int v) const {
+        typedef const int __attribute__((address_space(4))) *const_int_ptr;
+        return ids ? *((const_int_ptr)(ids + min(v, rows - 1))) : 0;
+    }
+    // rid: the row's entry of the id list (ids jobs), fetched by the caller one chunk ahead
+    __device__ __forceinline__ const uint16_t *rowptr(int v, int j, int rid) const {
         if (paired) {
             const int w = v - j * nw;
             int mat, r;
@@ -65,10 +72,7 @@ struct FlowJob {
             }
             return (mat ? base[1] : base[0]) + (size_t)r * pitch; // (no run-time index: the struct stays in registers)
         }
-        // the id list is read-only during the call and v is wave-uniform: a scalar load (a vector load here would
-        // make the wave wait for every weight chunk in flight before it can form the row's address)
-        typedef const int __attribute__((address_space(4))) *const_int_ptr;
-        const int r = ids ? *((const_int_ptr)(ids + v)) : v;
+        const int r = ids ? rid : v;
         const uint16_t *b = r < seg1 ? base[0] : r < seg2 ? base[1] : base[2];
         const int o = r < seg1 ? r : r < seg2 ? r - seg1 : r - seg2;
         return b + (size_t)o * pitch;
@@ -126,6 +130,7 @@ struct FlowLoad {
     FlowGeom g;
     int id;           // FlowPhase the cursor is in
     int row, jr, c, n; // next chunk: virtual row, its round, chunk within the row, chunks requested so far
+    int rid;           // id-list entry of `row` (requested when the cursor moved there, used at the next request)
 };
 __device__ __forceinline__ void flow_load_begin(FlowLoad &L, const FlowJob &j, const FlowGeom &g, int id, int wr0) {
     L.j = j;
@@ -135,6 +140,7 @@ __device__ __forceinline__ void flow_load_begin(FlowLoad &L, const FlowJob &j, c
     L.jr = 0;
     L.c = 0;
     L.n = 0;
+    L.rid = j.row_id(wr0);
 }
 // Request the cursor's next chunk into a ring slot.  Past the wave's last chunk (padding, or no next phase) the
 // request goes to a zero-length buffer: it returns zeros and moves no data, so the ring is refilled without a branch
@@ -143,7 +149,7 @@ __device__ __forceinline__ void flow_issue(FlowLoad &L, u32x4 (&buf)[kChunkLoads
     const bool live = L.n < L.g.nreal;
     const int v = live ? min(L.row, L.g.wr_last) : 0;
     const int jr = live ? L.jr : 0;
-    const row_rsrc rs = make_row_rsrc(L.j.rowptr(v, jr), live ? L.j.K * 2 : 0); // wave-uniform
+    const row_rsrc rs = make_row_rsrc(L.j.rowptr(v, jr, L.rid), live ? L.j.K * 2 : 0); // wave-uniform
 #pragma unroll
     for (int u = 0; u < kChunkLoads; ++u) {
         const int blk = min(L.c * kChunkLoads + u, L.g.nblk - 1); // empty slots of a row's last chunk re-read its last block
@@ -154,6 +160,7 @@ __device__ __forceinline__ void flow_issue(FlowLoad &L, u32x4 (&buf)[kChunkLoads
         L.c = 0;
         L.row += L.j.nw;
         ++L.jr;
+        L.rid = L.j.row_id(L.row);
     }
 }
 
@@ -539,6 +546,7 @@ __device__ __forceinline__ void flow_steps(const DraftParams &p, char *smem) {
             unsigned long long best = 0ull; // output head: best (logit, row) this wave has seen (lane 0)
             float gate_saved = 0.f;
             const int pair_rows = 2 * job.pair_rounds;
+            const bool throttle = g.nchunks >= 8;
 
             f32x4 acc_h = {0.f, 0.f, 0.f, 0.f}, acc_l = {0.f, 0.f, 0.f, 0.f};
             const int dv = (lane & 15) - 4 * (lane >> 4); // which of this lane's four results lies on the diagonal
@@ -566,6 +574,12 @@ __device__ __forceinline__ void flow_steps(const DraftParams &p, char *smem) {
                         const FlowJob nj = flow_job(p, next, nw);
                         flow_load_begin(L, nj, flow_geom(nj, wr0, nw), next, wr0);
                     }
+                    // Long phases keep ONE chunk in flight per wave while they stream (the other slot's loads are waited
+                    // for before the next request goes out): 16 MiB over the chip already covers the memory latency, more
+                    // only deepens the queues, and the compute dies then share the bandwidth unevenly (output head: the
+                    // odd-numbered dies finished 6 us after the even ones with two chunks in flight).  The second slot
+                    // earns its keep at the ends of a phase, where the requests run ahead into the next one.
+                    if (throttle && L.id == ph) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
                     flow_issue(L, ring[s], lane);
                     if (n0 + s < g.nreal && ++c_c == g.cpr) { // end of a row: sum the diagonal
                         c_c = 0;

@@ -420,9 +420,10 @@ struct mtp_handle {
     int num_cus;
     size_t lds_limit;
     phase_kernel_t attn_fn;
-    fused_kernel_t flow_fn;        // one sequence: all phases of all steps in one cooperative launch
+    fused_kernel_t flow_fn;        // one sequence: all phases of all steps in one launch
     unsigned long long flow_tags;  // hand-over tags given to earlier calls of that kernel
-    int mode;                    // 0: one launch per phase, 1: single cooperative launch for the whole call
+    size_t flow_lds_ok;            // largest LDS size for which a workgroup of that kernel was seen to fit a CU
+    int mode;                    // 0: one launch per phase, 1: single launch for the whole call
     long long *trace;             // optional device buffer for phase time stamps
     int timing;         // 0 off, 1 whole call, 2 + phase: every launch of one phase
     hipEvent_t ev[2];   // whole call
@@ -533,6 +534,7 @@ int32_t mtp_draft_init(mtp_handle **out, const mtp_config *cfg, const mtp_weight
     h->attn_fn = attn_kernel(cfg->n_q_heads / cfg->n_kv_heads, cfg->head_dim);
     h->flow_fn = flow_kernel(cfg->n_q_heads / cfg->n_kv_heads, cfg->head_dim);
     h->flow_tags = 0;
+    h->flow_lds_ok = 0;
     h->mode = 2;
     h->trace = nullptr;
     if (ok && (h->attn_fn == nullptr || h->flow_fn == nullptr)) {
@@ -750,17 +752,31 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
 
     const int tphase = h->timing >= 2 ? h->timing - 2 : -1;
     h->pev_used = 0;
-    // One sequence and every reduction at least 512 long: all phases of all K steps in ONE cooperative launch whose
-    // workgroups hand their results over as tagged elements (flow.h).  Every workgroup must be resident at once (one per
-    // CU; the cooperative launch checks it).  Mode 2 picks it where it applies; more sequences, and shapes it does not
-    // serve, take one launch per phase in every mode.
+    // One sequence and every reduction at least 512 long: all phases of all K steps in ONE launch whose workgroups hand
+    // their results over as tagged elements (flow.h).  Its workgroups wait for one another, so all of them must be
+    // resident at once: one per CU (the launch's LDS and registers leave no room for a second, and init has checked
+    // that one fits).  A cooperative launch would have the runtime verify that, but it leaves a 20 us gap between
+    // consecutive launches (measured: 464 us kernels every 485 us) where an ordinary launch leaves 5; on a device that
+    // another kernel occupies at that moment the waits are bounded (MTP_ERR_TIMEOUT).  Mode 2 picks it where it
+    // applies; more sequences, and shapes it does not serve, take one launch per phase in every mode.
     const bool rows = B == 1 && p.d >= 512 && p.qd >= 512 && p.F >= 512;
     if ((h->mode == 1 || h->mode == 2) && rows && tphase < 0 && !ext && !seq_subset) {
         const int fgrid = std::min(h->num_cus, kMaxFusedGrid);
         size_t region = std::max(flow_gemv_region(p.d, p.qd, p.F), lds_attn);
         region = (region + 255) / 256 * 256;
         const size_t lds_flow = region + ((size_t)p.d + flow_part_floats(p.d, fgrid)) * 4 + 256;
-        if (lds_flow <= h->lds_limit) {
+        bool fits = lds_flow <= h->lds_limit;
+        if (fits && lds_flow > h->flow_lds_ok) { // once per LDS size: a workgroup of this kernel fits a compute unit
+            int per_cu = 0;
+            fits = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)h->flow_fn, kBlock, lds_flow) ==
+                       hipSuccess &&
+                   per_cu >= 1;
+            if (fits)
+                h->flow_lds_ok = lds_flow;
+            else
+                (void)hipGetLastError();
+        }
+        if (fits) {
             p.head_grid = fgrid;
             p.fused_gemv_bytes = (int)region;
             // tags of this call: tag_base + 1 .. tag_base + 8 K, never 0 and never reused: when the 32-bit counter would
@@ -771,12 +787,13 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
                 hipLaunchKernelGGL(k_zero_words, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st,
                                    reinterpret_cast<unsigned long long *>(ws + l.xt), (int)words);
                 h->flow_tags = 0;
+    h->flow_lds_ok = 0;
             }
             p.tag_base = (unsigned)h->flow_tags;
             void *args[] = {(void *)&p};
             if (h->timing == 1) (void)hipEventRecord(h->ev[0], st);
-            const bool launched = hipLaunchCooperativeKernel((const void *)h->flow_fn, dim3(fgrid), dim3(kBlock), args,
-                                                             (unsigned)lds_flow, st) == hipSuccess;
+            const bool launched = hipLaunchKernel((const void *)h->flow_fn, dim3(fgrid), dim3(kBlock), args,
+                                                  (unsigned)lds_flow, st) == hipSuccess;
             if (launched) {
                 h->flow_tags += 8ull * (unsigned long long)K;
                 if (h->timing == 1) {
@@ -787,7 +804,7 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
             }
             (void)hipGetLastError();
             if (h->mode == 1) return MTP_ERR_HIP; // asked for explicitly
-            // mode 2: the device could not take a cooperative launch right now (it needs every CU): one launch per phase
+            // mode 2: the launch was refused: one launch per phase
         }
     }
     auto mark_begin = [&](int phase, int step) {
