@@ -5,9 +5,19 @@ One "step" = one pass of the whole hot path over one batch: K recursive draft st
 compressed output head (mtp_draft_steps), then acceptance + rollback against a synthetic target chain (mtp_accept).
 Inputs are seeded and synthetic (7B-shaped head, bf16 ~N(0,0.02) weights), resident in HBM before timing starts.
 
-Prints ONE JSON line: draft tokens/s (value), ms per step, and the objects `roofline` (dominant kernel against the
-8 TB/s HBM peak), `full_vocab` (same path with the uncompressed head) and `cpu_baseline` (the CPU oracle, timed on
-this machine's host cores on the same workload).
+Prints ONE JSON line.  `value` = draft tokens/s of the headline workload (config 2: one sequence, context 2048,
+32768-row head, K = 3).  Beside it:
+  roofline       the kernel the timed path launches (the single-launch kernel: all phases of all K steps), its average
+                 launch duration from HIP events on the launch stream, algorithmic bytes per launch, the 8 TB/s HBM
+                 peak, HBM bytes from the committed counter runs; `phases`: every phase of a draft step from the
+                 kernel's own time stamps; `k_lmhead`: the output-head kernel of the one-launch-per-phase mode
+  stream_ceiling a plain streaming read and a device copy, timed here: what this machine sustains
+  full_vocab     the same path with the uncompressed head
+  configs        the other configurations (batch 16; the vocabulary sweep at context 8192 incl. the full head through
+                 the identity list; batch 64), each timed the same way
+  k_sweep        the K-step chain measured for K = 1..7 and the draft-length model of Sec. 3.5 fed with those times
+  cpu_baseline   the CPU oracle timed on this machine's host cores on the headline workload
+and, unless --no-next-rows, the block of new positions, the list builder and the teacher-forced forward.
 """
 from __future__ import annotations
 
@@ -23,6 +33,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 PMC_SUMMARY = os.path.join(ROOT, "profiles", "pmc_hbm_traffic_c2_7b_b1.md")
+EXPECTED_ACCEPT = {0.8: (3, 1.952), 0.7: (5, 1.94117)}  # sum_j p^j for (p, K) of configs 3 and 5
 
 
 def measured_traffic(kernel: str):
@@ -33,19 +44,24 @@ def measured_traffic(kernel: str):
             cells = [c.strip() for c in line.split("|")]
             if len(cells) > 5 and cells[1] == kernel:
                 return float(cells[-2])
-    except OSError:
+    except (OSError, ValueError):
         pass
     return None
 
 
-def algorithmic_bytes_per_mtp_step(shape, n_rows: int, ctx, k_index: int, with_ids: bool) -> float:
-    """HBM bytes one draft step must move: every weight of the head once, n_rows rows of the output head (+ the id
-    list), and the K/V entries of every sequence up to and including the new one (k_index = 1-based step)."""
+def step_bytes(shape, n_rows: int, ctx, k_index: int, with_ids: bool):
+    """HBM bytes one draft step must move, by phase: every weight of the head once, n_rows rows of the output head (+
+    the id list), and the K/V entries of every sequence up to and including the new one (k_index = 1-based step)."""
     d, F = shape.d_model, shape.d_ffn
-    body = 2.0 * (2 * d * d + (shape.q_dim + 2 * shape.kv_dim) * d + d * shape.q_dim + 3 * F * d)
-    head = 2.0 * n_rows * d + (4.0 * n_rows if with_ids else 0.0)
-    kv = sum((int(L) + k_index) * 2 * shape.kv_dim * 2.0 for L in ctx)
-    return body + head + kv
+    ph = {"proj": 2.0 * 2 * d * d, "qkv": 2.0 * (shape.q_dim + 2 * shape.kv_dim) * d,
+          "attn": sum((int(L) + k_index) * 2 * shape.kv_dim * 2.0 for L in ctx), "oproj": 2.0 * d * shape.q_dim,
+          "gateup": 2.0 * 2 * F * d, "down": 2.0 * F * d,
+          "lmhead": 2.0 * n_rows * d + (4.0 * n_rows if with_ids else 0.0)}
+    return ph
+
+
+def chain_bytes(shape, n_rows, ctx, K, with_ids) -> float:
+    return sum(sum(step_bytes(shape, n_rows, ctx, k, with_ids).values()) for k in range(1, K + 1))
 
 
 def device_state():
@@ -72,6 +88,80 @@ def device_state():
     return dev
 
 
+class Chain:
+    """One workload on one engine: the K-step chain + acceptance, replayed on the same inputs."""
+
+    def __init__(self, binding, synth, torch, wl, w, subsets, max_steps=None, act=None):
+        self.binding, self.synth, self.torch, self.wl = binding, synth, torch, wl
+        self.shape, self.B = wl.shape, wl.batch
+        self.act = act if act is not None else synth.make_activations(wl, threads=16)
+        self.cap = self.act["kv_capacity"]
+        self.kmax = max_steps or wl.draft_steps
+        self.eng = binding.DraftEngine(self.shape, w, subsets, self.B, self.cap, self.kmax, device="cuda:0")
+        e = self.eng
+        self.hidden, self.token = e.to_device_bits(self.act["hidden_in"]), e.to_device_i32(self.act["token_in"])
+        self.kc, self.vc = e.to_device_bits(self.act["k_cache"]), e.to_device_bits(self.act["v_cache"])
+        self.kv0 = e.to_device_i32(self.act["kv_len"])
+        self.kv = self.kv0.clone()
+        B, K = self.B, self.kmax
+        self.draft_buf = {k: torch.empty((B, k), dtype=torch.int32, device="cuda:0") for k in range(1, K + 1)}
+        self.acc = torch.empty(B, dtype=torch.int32, device="cuda:0")
+        self.out_tok = torch.empty((B, K + 1), dtype=torch.int32, device="cuda:0")
+        self.pend = torch.empty(B, dtype=torch.int32, device="cuda:0")
+
+    def one(self, subset_index, K, target):
+        b, e = self.binding, self.eng
+        draft = self.draft_buf[K]
+        st = b.mtp_draft_steps(e.handle, self.B, K, subset_index, self.hidden, self.token, self.kc, self.vc, self.kv,
+                               None, draft, None, None, 0)
+        assert st == 0, b.mtp_status_string(st)
+        st = b.mtp_accept(e.handle, self.B, K, draft, target, 0, self.kv, self.acc, self.out_tok, self.pend, 0)
+        assert st == 0, b.mtp_status_string(st)
+        self.kv.copy_(self.kv0)  # replay the same cycle next time (4*B bytes, device to device)
+
+    def target_for(self, subset_index, K):
+        """Target chain built from this configuration's own drafts (stand-in for the target model's verification)."""
+        torch = self.torch
+        dummy = torch.zeros((self.B, K + 1), dtype=torch.int32, device="cuda:0")
+        self.one(subset_index, K, dummy)
+        torch.cuda.synchronize()
+        assert self.eng.poll_error() == 0
+        tg = self.synth.make_targets(self.wl, self.draft_buf[K].cpu().numpy())
+        return self.eng.to_device_i32(tg)
+
+    def timed(self, subset_index, steps, warmup, K=None):
+        torch = self.torch
+        K = K or self.wl.draft_steps
+        target = self.target_for(subset_index, K)
+        for _ in range(warmup):
+            self.one(subset_index, K, target)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(steps):
+            self.one(subset_index, K, target)
+        torch.cuda.synchronize()
+        el = time.perf_counter() - t
+        return el, float(self.acc.float().mean().item())
+
+    def row(self, name, subset_index, steps, warmup, with_ids=None, K=None):
+        """One line of the `configs` table."""
+        K = K or self.wl.draft_steps
+        el, mean_acc = self.timed(subset_index, steps, warmup, K)
+        n_rows = self.eng.subset_size(subset_index)
+        ids = (subset_index >= 0) if with_ids is None else with_ids
+        cb = chain_bytes(self.shape, n_rows, self.act["kv_len"], K, ids)
+        gbs = cb * steps / el / 1e9
+        r = {"name": name, "batch": self.B, "draft_steps": K,
+             "context": [int(self.act["kv_len"].min()), int(self.act["kv_len"].max())], "head_rows": n_rows,
+             "us_per_mtp_step": el / (steps * K) * 1e6, "draft_tokens_per_s": self.B * K * steps / el,
+             "algorithmic_bytes_per_step": cb / K, "achieved_gbs": gbs, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS,
+             "mean_accept_len": mean_acc}
+        exp = EXPECTED_ACCEPT.get(self.wl.accept_prob)
+        if exp and exp[0] == K:
+            r["expected_accept_len"] = exp[1]
+        return r
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -79,11 +169,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--workload", default="c2_7b_b1")
     ap.add_argument("--subset", type=int, default=0, help="index into the workload's subset list; -1 = full vocabulary")
-    ap.add_argument("--identity-list", action="store_true",
-                    help="time the indirect head with the identity id list (all V rows through the gather path)")
     ap.add_argument("--launch-mode", default="auto", choices=("auto", "per-phase", "single"),
-                    help="how the library enqueues a call: one launch per phase, or one cooperative launch for all "
-                         "phases of all K steps; auto times both briefly for one sequence and keeps the faster")
+                    help="how the library enqueues a call; auto = the library's own choice (single launch for one "
+                         "sequence); both are timed briefly for one sequence and reported")
     ap.add_argument("--extend", type=int, default=4,
                     help="also time the first draft step over a block of this many new positions per sequence "
                          "(mtp_draft_extend); reported beside the main figures, never part of `value`; 0: skip")
@@ -95,11 +183,15 @@ def main() -> int:
                          "(mtp_train_loss, K = 3, beta = 0.6) over this many positions")
     ap.add_argument("--no-next-rows", action="store_true",
                     help="skip the three side measurements above (block of positions, list builder, training forward)")
+    ap.add_argument("--no-configs", action="store_true", help="skip the other configurations (3, 4, 5)")
+    ap.add_argument("--no-k-sweep", action="store_true", help="skip the measured K = 1..7 chains")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full-vocab", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
-    ap.add_argument("--k-sweep-target-ms", type=float, default=0.0,
-                    help="if > 0: add a MODEL of the draft-length sweep (Sec. 3.5) for this assumed target-forward time")
+    ap.add_argument("--k-sweep-target-ms", type=float, default=2.6,
+                    help="ASSUMED time of one target-model forward for the draft-length model of Sec. 3.5")
+    ap.add_argument("--phase-table", default="",
+                    help="also write the per-phase time stamps of the single-launch kernel as a markdown table here")
     ap.add_argument("--copy-calib", action="store_true",
                     help="also run one plain 256 MiB device copy (a known-size reference for HBM byte counters)")
     args = ap.parse_args()
@@ -112,138 +204,251 @@ def main() -> int:
 
     import numpy as np
     import torch
-    from paper_2509_18362_amd import binding, synth
+    from paper_2509_18362_amd import binding, ksweep, synth
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     wl = synth.WORKLOADS[args.workload]
     shape, K, B = wl.shape, wl.draft_steps, wl.batch
     t0 = time.time()
     w = synth.make_weights(wl if wl.shape is synth.TINY else synth.WORKLOADS["c2_7b_b1"], threads=16)
-    act = synth.make_activations(wl, threads=16)
     subsets = synth.make_subsets(wl)
-    if args.identity_list:
-        subsets = list(subsets) + [np.arange(shape.vocab_size, dtype=np.int32)]
-        args.subset = len(subsets) - 1
+    kmax = 7 if (B == 1 and not args.no_k_sweep) else K
+    main_chain = Chain(binding, synth, torch, wl, w, subsets, max_steps=kmax)
     gen_s = time.time() - t0
-    cap = act["kv_capacity"]
-    eng = binding.DraftEngine(shape, w, subsets, B, cap, K, device="cuda:0")
-    hidden = eng.to_device_bits(act["hidden_in"])
-    token = eng.to_device_i32(act["token_in"])
-    kc, vc = eng.to_device_bits(act["k_cache"]), eng.to_device_bits(act["v_cache"])
-    kv0 = eng.to_device_i32(act["kv_len"])
-    kv = kv0.clone()
-    draft = torch.empty((B, K), dtype=torch.int32, device="cuda:0")
-    acc = torch.empty(B, dtype=torch.int32, device="cuda:0")
-    out_tok = torch.empty((B, K + 1), dtype=torch.int32, device="cuda:0")
-    pend = torch.empty(B, dtype=torch.int32, device="cuda:0")
-    stream = 0  # the null stream, which is also torch's current stream here
-
-    def one_step(subset_index, target):
-        st = binding.mtp_draft_steps(eng.handle, B, K, subset_index, hidden, token, kc, vc, kv, None, draft, None,
-                                     None, stream)
-        assert st == 0, binding.mtp_status_string(st)
-        st = binding.mtp_accept(eng.handle, B, K, draft, target, 0, kv, acc, out_tok, pend, stream)
-        assert st == 0, binding.mtp_status_string(st)
-        kv.copy_(kv0)  # replay the same cycle next time (4*B bytes, device to device)
-
-    def timed(subset_index, steps, warmup):
-        # target chain built from this configuration's own drafts (stand-in for the target model's verification)
-        dummy = torch.zeros((B, K + 1), dtype=torch.int32, device="cuda:0")
-        one_step(subset_index, dummy)
-        torch.cuda.synchronize()
-        assert eng.poll_error() == 0
-        target = eng.to_device_i32(synth.make_targets(wl, draft.cpu().numpy()))
-        for _ in range(warmup):
-            one_step(subset_index, target)
-        torch.cuda.synchronize()
-        t = time.perf_counter()
-        for _ in range(steps):
-            one_step(subset_index, target)
-        torch.cuda.synchronize()
-        el = time.perf_counter() - t
-        return el, float(acc.float().mean().item())
+    eng, act, cap = main_chain.eng, main_chain.act, main_chain.cap
+    w_dev = eng.w  # device tensors: later engines share them
+    stream = 0     # the null stream, which is also torch's current stream here
 
     if args.copy_calib:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0")
         dst = torch.empty_like(src)
         dst.copy_(src)
         torch.cuda.synchronize()
-    mode_ids = {"per-phase": binding.LAUNCH_PER_PHASE, "single": binding.LAUNCH_SINGLE}
+
+    # ---- headline: K draft steps + acceptance, launch mode as the library chooses (or as asked) -------------------
+    mode_ids = {"per-phase": binding.LAUNCH_PER_PHASE, "single": binding.LAUNCH_SINGLE, "auto": binding.LAUNCH_AUTO}
     mode_us = {}
-    launch_mode = args.launch_mode
-    if launch_mode == "auto":
-        launch_mode = "per-phase"
-        if B == 1:  # the single launch pays off where a phase is short against a kernel boundary
-            for name, mid in mode_ids.items():
-                assert binding.mtp_set_launch_mode(eng.handle, mid) == 0
-                el, _ = timed(args.subset, max(20, args.steps // 5), max(5, args.warmup // 3))
-                mode_us[name] = el / (max(20, args.steps // 5) * K) * 1e6
-            launch_mode = min(mode_us, key=mode_us.get)
-    assert binding.mtp_set_launch_mode(eng.handle, mode_ids[launch_mode]) == 0
-    elapsed, mean_accept = timed(args.subset, args.steps, args.warmup)
+    if B == 1:
+        for name in ("per-phase", "single"):
+            assert binding.mtp_set_launch_mode(eng.handle, mode_ids[name]) == 0
+            n_t = max(20, args.steps // 5)
+            el, _ = main_chain.timed(args.subset, n_t, max(5, args.warmup // 3))
+            mode_us[name] = el / (n_t * K) * 1e6
+    assert binding.mtp_set_launch_mode(eng.handle, mode_ids[args.launch_mode]) == 0
+    elapsed, mean_accept = main_chain.timed(args.subset, args.steps, args.warmup)
     n_rows = eng.subset_size(args.subset)
-    chain_bytes = sum(algorithmic_bytes_per_mtp_step(shape, n_rows, act["kv_len"], k, args.subset >= 0)
-                      for k in range(1, K + 1))
+    cbytes = chain_bytes(shape, n_rows, act["kv_len"], K, args.subset >= 0)
     tok_s = B * K * args.steps / elapsed
     us_per_mtp_step = elapsed / (args.steps * K) * 1e6
-    path_gbs = chain_bytes * args.steps / elapsed / 1e9
+    path_gbs = cbytes * args.steps / elapsed / 1e9
+    single = B == 1 and args.launch_mode != "per-phase"  # the path that was timed is the single-launch kernel
+    target = main_chain.target_for(args.subset, K)
+    draft, kv, acc, out_tok, pend = main_chain.draft_buf[K], main_chain.kv, main_chain.acc, main_chain.out_tok, main_chain.pend
 
-    # dominant kernel: the compressed-head launch (final norm + gathered rows + argmax), timed with HIP events on the
-    # launch stream over a region of the same length
-    binding.mtp_set_timing(eng.handle, binding.timing_phase("lmhead"))
-    dummy = eng.to_device_i32(synth.make_targets(wl, draft.cpu().numpy()))
-    durs = []
-    for i in range(args.steps):
-        one_step(args.subset, dummy)
-        if i % 10 == 9 or i == args.steps - 1:  # reading the events waits for the stream: do it sparsely
-            durs.append(binding.mtp_last_draft_ms(eng.handle))
-    torch.cuda.synchronize()
-    binding.mtp_set_timing(eng.handle, binding.TIMING_OFF)
-    k_ms = float(np.median(durs))
-    head_bytes = 2.0 * n_rows * shape.d_model + (4.0 * n_rows if args.subset >= 0 else 0.0)
+    # ---- the dominant kernel of the timed path, timed with HIP events on the launch stream -------------------------
     # What an event pair around ONE launch adds to the kernel's own duration (the dispatch of a dependent launch):
-    # the same bracket around single launches of the acceptance kernel, whose own duration the back-to-back run above
-    # cannot exceed.  Reported so that the event-based figure can be set beside the profiler's begin/end stamps.
+    # the same bracket around single launches of the acceptance kernel against back-to-back launches of it.
     brackets = []
     for _ in range(50):
         b0, b1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         b0.record()
-        binding.mtp_accept(eng.handle, B, K, draft, dummy, 1, kv, acc, out_tok, pend, stream)
+        binding.mtp_accept(eng.handle, B, K, draft, target, 1, kv, acc, out_tok, pend, stream)
         b1.record()
         b1.synchronize()
         brackets.append(b0.elapsed_time(b1) * 1e3)
     bracket_us = float(np.median(brackets))
-    roofline = {"bound": "hbm", "kernel": "k_lmhead", "achieved": head_bytes / (k_ms * 1e-3) / 1e9,
-                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": head_bytes / (k_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                "traffic": measured_traffic("k_lmhead") if (args.workload == "c2_7b_b1" and args.subset == 0) else None,
-                "bytes_per_launch": head_bytes, "avg_launch_us": k_ms * 1e3,
-                "whole_path_achieved": path_gbs, "whole_path_frac": path_gbs / HBM_PEAK_GBS}
-
-    # spread of the K-step chain alone (HIP events inside the library around one mtp_draft_steps call), and the
-    # acceptance kernel alone (back-to-back launches between two events on the same stream)
-    binding.mtp_set_timing(eng.handle, binding.TIMING_CALL)
-    chain_us = []
-    for _ in range(min(args.steps, 100)):
-        one_step(args.subset, dummy)
-        chain_us.append(binding.mtp_last_draft_ms(eng.handle) * 1e3)
-    binding.mtp_set_timing(eng.handle, binding.TIMING_OFF)
-    p10, p50, p90 = (float(np.percentile(chain_us, q)) for q in (10, 50, 90))
     n_acc = 200
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(n_acc):
-        binding.mtp_accept(eng.handle, B, K, draft, dummy, 1, kv, acc, out_tok, pend, stream)  # mode 1: kv_len unchanged
+        binding.mtp_accept(eng.handle, B, K, draft, target, 1, kv, acc, out_tok, pend, stream)  # mode 1: kv_len unchanged
     e1.record()
     torch.cuda.synchronize()
     accept_us = e0.elapsed_time(e1) * 1e3 / n_acc
-    roofline["event_pair_around_one_accept_launch_us"] = bracket_us
-    roofline["event_pair_overhead_us"] = bracket_us - accept_us  # at least this much of avg_launch_us is not the kernel
+
+    # the whole call (one kernel in single-launch mode): events inside the library around mtp_draft_steps' launches
+    binding.mtp_set_timing(eng.handle, binding.TIMING_CALL)
+    chain_us = []
+    for _ in range(min(args.steps, 100)):
+        main_chain.one(args.subset, K, target)
+        chain_us.append(binding.mtp_last_draft_ms(eng.handle) * 1e3)
+    binding.mtp_set_timing(eng.handle, binding.TIMING_OFF)
+    p10, p50, p90 = (float(np.percentile(chain_us, q)) for q in (10, 50, 90))
+
+    # the output-head kernel of the one-launch-per-phase mode (the largest single phase)
+    assert binding.mtp_set_launch_mode(eng.handle, binding.LAUNCH_PER_PHASE) == 0
+    binding.mtp_set_timing(eng.handle, binding.timing_phase("lmhead"))
+    durs = []
+    for i in range(max(30, args.steps // 3)):
+        main_chain.one(args.subset, K, target)
+        if i % 10 == 9:  # reading the events waits for the stream: do it sparsely
+            durs.append(binding.mtp_last_draft_ms(eng.handle))
+    torch.cuda.synchronize()
+    binding.mtp_set_timing(eng.handle, binding.TIMING_OFF)
+    assert binding.mtp_set_launch_mode(eng.handle, mode_ids[args.launch_mode]) == 0
+    head_ms = float(np.median(durs))
+    head_bytes = step_bytes(shape, n_rows, act["kv_len"], 1, args.subset >= 0)["lmhead"]
+    k_lmhead = {"what": "output-head kernel of the one-launch-per-phase mode, event pair around each launch",
+                "bytes_per_launch": head_bytes, "avg_launch_us": head_ms * 1e3,
+                "achieved": head_bytes / (head_ms * 1e-3) / 1e9, "frac": head_bytes / (head_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                "traffic": measured_traffic("k_lmhead") if (args.workload == "c2_7b_b1" and args.subset == 0) else None}
+
+    # per-phase breakdown of the single-launch kernel from its own time stamps
+    phases = None
+    if single:
+        W = torch.cuda.get_device_properties(0).multi_processor_count
+        tbuf = torch.zeros(binding.mtp_phase_trace_bytes(eng.cfg) // 8, dtype=torch.int64, device="cuda:0")
+        assert binding.mtp_set_phase_trace(eng.handle, tbuf) == 0
+        acc_t, reps_t = None, 20
+        for _ in range(reps_t):
+            tbuf.zero_()
+            main_chain.one(args.subset, K, target)
+            torch.cuda.synchronize()
+            t = tbuf.cpu().numpy()[:K * 8 * 4 * W].reshape(K, 8, 4, W).astype(np.float64) * 0.01  # us
+            t = t - t[0, 7, 0].min()
+            acc_t = t if acc_t is None else acc_t + t
+        assert binding.mtp_set_phase_trace(eng.handle, None) == 0
+        t = acc_t / reps_t
+        order = [(7, "proj_hidden_half"), (0, "proj_embedding_half"), (1, "qkv"), (2, "attn"), (3, "oproj"),
+                 (4, "gateup"), (5, "down"), (6, "lmhead")]
+        phases, prev_end = [], None
+        for s in range(K):
+            sb = step_bytes(shape, n_rows, act["kv_len"], s + 1, args.subset >= 0)
+            for sec, name in order:
+                nbytes = sb["proj"] / 2 if name.startswith("proj") else sb[name]
+                end = float(t[s, sec, 3].max())
+                start = prev_end if prev_end is not None else float(t[s, sec, 0].min())
+                rel = t[s, sec, 1]
+                phases.append({"step": s + 1, "phase": name, "bytes": nbytes, "span_us": end - start,
+                               "gbs": nbytes / max(end - start, 1e-9) / 1e3,
+                               "input_ready_after_previous_phase_us": [float(rel.min() - start), float(rel.max() - start)],
+                               "staging_us": float(np.median(t[s, sec, 2] - rel)),
+                               "compute_us_min_median_max": [float(np.min(t[s, sec, 3] - t[s, sec, 2])),
+                                                             float(np.median(t[s, sec, 3] - t[s, sec, 2])),
+                                                             float(np.max(t[s, sec, 3] - t[s, sec, 2]))]})
+                prev_end = end
+        interior_us = float(t[K - 1, 6, 3].max() - t[0, 7, 0].min())
+        if args.phase_table:
+            with open(args.phase_table, "w") as f:
+                f.write(f"| step | phase | MB | span us | GB/s | input ready after previous phase ended, us (first..last "
+                        f"workgroup) | staging us | compute us (min / median / max over workgroups) |\n|---|---|---|---|---|---|---|---|\n")
+                for r in phases:
+                    a, b2 = r["input_ready_after_previous_phase_us"]
+                    c = r["compute_us_min_median_max"]
+                    f.write(f"| {r['step']} | {r['phase']} | {r['bytes'] / 1e6:.1f} | {r['span_us']:.1f} | {r['gbs']:.0f} | "
+                            f"{a:.1f}..{b2:.1f} | {r['staging_us']:.1f} | {c[0]:.1f} / {c[1]:.1f} / {c[2]:.1f} |\n")
+                f.write(f"\nkernel interior (first request to last result): {interior_us:.1f} us for {K} steps\n")
+
+    kname = "k_flow" if single else "k_lmhead"
+    if single:
+        k_us, k_bytes = p50, cbytes
+    else:
+        k_us, k_bytes = head_ms * 1e3, head_bytes
+    roofline = {"bound": "hbm", "kernel": kname, "achieved": k_bytes / (k_us * 1e-6) / 1e9, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": k_bytes / (k_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                "traffic": measured_traffic(kname) if (args.workload == "c2_7b_b1" and args.subset == 0) else None,
+                "bytes_per_launch": k_bytes, "avg_launch_us": k_us,
+                "what": (f"one launch = all phases of {K} draft steps" if single else "one launch = one output-head phase"),
+                "whole_path_achieved": path_gbs, "whole_path_frac": path_gbs / HBM_PEAK_GBS,
+                "event_pair_around_one_accept_launch_us": bracket_us,
+                "event_pair_overhead_us": bracket_us - accept_us,  # at least this much of avg_launch_us is not the kernel
+                "phases": phases, "k_lmhead": k_lmhead}
+
+    # ---- what this machine sustains: a plain streaming read (the weight stream's own access pattern) and a device copy ---
+    probe_bytes = (eng.w["lm_head"].numel() * 2) // 16384 * 16384
+    out8 = torch.zeros(2, dtype=torch.int64, device="cuda:0")
+    for _ in range(3):
+        assert binding.mtp_stream_probe(eng.w["lm_head"], probe_bytes, out8, stream) == 0
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        binding.mtp_stream_probe(eng.w["lm_head"], probe_bytes, out8, stream)
+    e1.record()
+    torch.cuda.synchronize()
+    read_gbs = probe_bytes * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0")
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 2.0 * (1 << 30) * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del src, dst
+    stream_ceiling = {"read_gbs": read_gbs, "read_frac_of_peak": read_gbs / HBM_PEAK_GBS,
+                      "read_what": f"mtp_stream_probe over the {probe_bytes / 1e6:.0f} MB output head, 10 passes",
+                      "copy_gbs_read_plus_write": copy_gbs, "copy_what": "torch copy of 1 GiB, bytes read + written"}
+
+    # ---- the uncompressed head on the same workload ----------------------------------------------------------------
+    full = None
+    if not args.no_full_vocab and args.subset >= 0:
+        fs = max(10, args.steps // 4)
+        el_f, _ = main_chain.timed(-1, fs, max(3, args.warmup // 4))
+        full = {"value": B * K * fs / el_f, "unit": "draft tokens/s", "us_per_mtp_step": el_f / (fs * K) * 1e6,
+                "rows": shape.vocab_size, "compressed_speedup": (el_f / fs) / (elapsed / args.steps),
+                "roofline_speedup": chain_bytes(shape, shape.vocab_size, act["kv_len"], K, False) / cbytes}
+
+    # ---- the K-step chain for K = 1..7 (Sec. 3.5) and the draft-length model fed with the measured times -----------
+    k_sweep = None
+    if kmax >= 7:
+        chains = []
+        for k in range(1, 8):
+            n_k = max(20, args.steps // 6)
+            tg = main_chain.target_for(args.subset, k)
+            for _ in range(5):
+                main_chain.one(args.subset, k, tg)
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            for _ in range(n_k):
+                main_chain.one(args.subset, k, tg)
+            torch.cuda.synchronize()
+            chains.append((time.perf_counter() - t) / n_k)  # chain + acceptance, seconds
+        rows = ksweep.sweep(chains, 0.0, args.k_sweep_target_ms * 1e-3)
+        k_sweep = {"measured_chain_plus_accept_us": [c * 1e6 for c in chains],
+                   "us_per_mtp_step_by_K": [c * 1e6 / (k + 1) for k, c in enumerate(chains)],
+                   "model": {"assumed_target_forward_ms": args.k_sweep_target_ms,
+                             "acceptance": "the paper's 0.81/0.56/0.36 cumulative (Sec. 3.4), later positions extrapolated",
+                             "rows": rows, "best_K": max(rows, key=lambda r: r["speedup_vs_plain_decoding"])["K"]}}
+
+    # ---- the other configurations ------------------------------------------------------------------------------------
+    configs = None
+    if not args.no_configs and args.workload == "c2_7b_b1":
+        configs = []
+        # config 3: batch 16, ragged contexts, acceptance probability 0.8
+        c3 = Chain(binding, synth, torch, synth.WORKLOADS["c3_7b_b16"], w_dev, synth.make_subsets(synth.WORKLOADS["c3_7b_b16"]))
+        configs.append(c3.row("c3_7b_b16", 0, 100, 10))
+        c3.eng.close()
+        del c3
+        # config 4: the vocabulary sweep at context 8192 (Table 2's sizes), incl. the full head through the identity list
+        wl4 = synth.WORKLOADS["c4_7b_vocab"]
+        subs4 = list(synth.make_subsets(wl4)) + [np.arange(shape.vocab_size, dtype=np.int32)]
+        c4 = Chain(binding, synth, torch, wl4, w_dev, subs4)
+        rows4 = [c4.row("c4_full_dense", -1, 60, 6)]
+        rows4.append(c4.row("c4_full_identity_list", len(subs4) - 1, 60, 6))
+        for i in range(len(subs4) - 2, -1, -1):
+            rows4.append(c4.row(f"c4_subset_{len(subs4[i])}", i, 100, 10))
+        full_us, full_b = rows4[0]["us_per_mtp_step"], rows4[0]["algorithmic_bytes_per_step"]
+        for r in rows4:
+            r["speedup_over_full_dense"] = full_us / r["us_per_mtp_step"]
+            r["bytes_ratio_to_full_dense"] = full_b / r["algorithmic_bytes_per_step"]
+        configs.extend(rows4)
+        c4.eng.close()
+        del c4
+        # config 5: batch 64, long ragged contexts, K = 5, acceptance probability 0.7
+        wl5 = synth.WORKLOADS["c5_7b_b64"]
+        c5 = Chain(binding, synth, torch, wl5, w_dev, synth.make_subsets(wl5))
+        configs.append(c5.row("c5_7b_b64", 0, 20, 3))
+        c5.eng.close()
+        del c5
+        torch.cuda.empty_cache()
 
     extend = None
     if args.extend > 0:
         m = args.extend
         assert int(act["kv_len"].max()) + m <= cap, "the block does not fit the workload's cache capacity"
-        eng2 = binding.DraftEngine(shape, w, subsets, B * m, cap, 1, device="cuda:0")
+        eng2 = binding.DraftEngine(shape, w_dev, subsets, B * m, cap, 1, device="cuda:0")
         rng = np.random.default_rng(7)
         std = float(synth.bf16_bits_to_f32(act["hidden_in"]).std())
         hid_m = eng2.to_device_bits(synth.f32_to_bf16_bits(
@@ -251,6 +456,7 @@ def main() -> int:
         tok_m = eng2.to_device_i32(rng.integers(0, shape.vocab_size, size=(m, B)).astype(np.int32))
         ext_len = eng2.to_device_i32(np.full(B, m, dtype=np.int32))
         draft_m = torch.empty((m, B), dtype=torch.int32, device="cuda:0")
+        kc, vc, kv0 = main_chain.kc, main_chain.vc, main_chain.kv0
 
         def one_block():
             st = binding.mtp_draft_extend(eng2.handle, B, m, args.subset, hid_m, tok_m, ext_len, kc, vc, kv, draft_m,
@@ -269,7 +475,7 @@ def main() -> int:
         torch.cuda.synchronize()
         el_b = time.perf_counter() - t
         # what one pass has to read: every weight once, the head's rows once, the caches once per position
-        blk_bytes = algorithmic_bytes_per_mtp_step(shape, n_rows, act["kv_len"], 1, args.subset >= 0)
+        blk_bytes = sum(step_bytes(shape, n_rows, act["kv_len"], 1, args.subset >= 0).values())
         extend = {"positions_per_sequence": m, "rows": B * m, "us_per_call": el_b / n_blk * 1e6,
                   "positions_per_s": B * m * n_blk / el_b,
                   "speedup_over_one_position_at_a_time": m * us_per_mtp_step / (el_b / n_blk * 1e6),
@@ -293,7 +499,7 @@ def main() -> int:
                 assert st == 0, binding.mtp_status_string(st)
                 draft_k[:, 0] = tok_c
                 draft_k[:, 1:] = draft_c
-                st = binding.mtp_accept(eng.handle, B, K, draft_k, dummy, 0, kv, acc, out_tok, pend, stream)
+                st = binding.mtp_accept(eng.handle, B, K, draft_k, target, 0, kv, acc, out_tok, pend, stream)
                 assert st == 0, binding.mtp_status_string(st)
                 kv.copy_(kv0)
 
@@ -342,13 +548,13 @@ def main() -> int:
         builder = {"tokens": n_tok, "vocab": shape.vocab_size, "list_size": n_list, "us_per_build": el_l * 1e6,
                    "tokens_per_s": n_tok / el_l, "algorithmic_gbs": 4.0 * n_tok / el_l / 1e9,
                    "frac_of_hbm_peak": 4.0 * n_tok / el_l / 1e9 / HBM_PEAK_GBS,
-                   "stream_passes": -(-shape.vocab_size // 40000), "oracle_seconds": cpu_l,
-                   "matches_oracle": True}
+                   "oracle_seconds": cpu_l, "matches_oracle": True}
+        del stream_dev
 
     train = None
     if args.train_loss > 0:
         n_pos, Kt = args.train_loss, 3
-        eng3 = binding.DraftEngine(shape, w, [], n_pos, max(64, -(-n_pos // 64) * 64), 1, device="cuda:0")
+        eng3 = binding.DraftEngine(shape, w_dev, [], n_pos, max(64, -(-n_pos // 64) * 64), 1, device="cuda:0")
         rng = np.random.default_rng(8)
         hid_t = eng3.to_device_bits(synth.f32_to_bf16_bits(rng.standard_normal((n_pos, shape.d_model)).astype(np.float32)))
         tok_t = eng3.to_device_i32(rng.integers(0, shape.vocab_size, size=n_pos + Kt + 1).astype(np.int32))
@@ -371,15 +577,6 @@ def main() -> int:
                  "note": "every matrix phase is one LDS-tiled MFMA matrix product over all positions (activations as "
                          "bf16 hi + lo: two MFMAs per product)"}
         eng3.close()
-
-    full = None
-    if not args.no_full_vocab and args.subset >= 0:
-        fs = max(10, args.steps // 4)
-        el_f, acc_f = timed(-1, fs, max(3, args.warmup // 4))
-        full = {"value": B * K * fs / el_f, "unit": "draft tokens/s", "us_per_mtp_step": el_f / (fs * K) * 1e6,
-                "rows": shape.vocab_size, "compressed_speedup": (el_f / fs) / (elapsed / args.steps),
-                "roofline_speedup": sum(algorithmic_bytes_per_mtp_step(shape, shape.vocab_size, act["kv_len"], k, False)
-                                        for k in range(1, K + 1)) / chain_bytes}
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -426,22 +623,20 @@ def main() -> int:
         "config": {"workload": wl.name, "batch": B, "draft_steps": K, "context": [int(act["kv_len"].min()),
                                                                                    int(act["kv_len"].max())],
                    "head_rows": n_rows, "vocab": shape.vocab_size, "d_model": shape.d_model,
-                   "launch_mode": launch_mode},
+                   "launch_mode": ("single" if single else "per-phase")},
         "launch_mode_trial_us_per_mtp_step": mode_us or None,
         "us_per_mtp_step": us_per_mtp_step, "mean_accept_len": mean_accept,
+        "mean_accept_len_note": "one sequence, one fixed target chain: a single sample, not a rate (configs 3 and 5 "
+                                "report rates over their batches)" if B == 1 else None,
         "chain_us": {"p10": p10, "p50": p50, "p90": p90, "what": f"{K} draft steps, one library call"},
         "accept_us": accept_us,
-        "algorithmic_bytes_per_step": chain_bytes, "roofline": roofline, "full_vocab": full, "extend": extend, "list_builder": builder, "train_loss": train,
+        "algorithmic_bytes_per_step": cbytes / K, "roofline": roofline, "stream_ceiling": stream_ceiling,
+        "full_vocab": full, "configs": configs, "k_sweep": k_sweep,
+        "extend": extend, "list_builder": builder, "train_loss": train,
         "cpu_baseline": cpu,
         "input_generation_s": gen_s,
         "device": device_state(),
     }
-    if args.k_sweep_target_ms > 0:
-        from paper_2509_18362_amd import ksweep
-        line["k_sweep_model"] = {
-            "assumed_target_forward_ms": args.k_sweep_target_ms,
-            "acceptance": "paper's 0.81/0.56/0.36 cumulative (Sec. 3.4), later positions extrapolated",
-            "rows": ksweep.sweep(us_per_mtp_step * 1e-6, accept_us * 1e-6, args.k_sweep_target_ms * 1e-3)}
     eng.close()
     print(json.dumps(line))
     return 0

@@ -274,6 +274,15 @@ float mtp_last_draft_ms(mtp_handle *h);
 int32_t mtp_set_launch_mode(mtp_handle *h, int32_t mode);
 
 /*
+ * Measurement aid: reads the first bytes / 16384 * 16384 bytes of buffer (device, 16-byte aligned, at least 16 KiB) once,
+ * with the access pattern of the draft kernels' weight stream (one workgroup per compute unit, 1 KiB per wave and load,
+ * sixteen loads in flight, non-temporal) and nothing else; out8 (device, 8 bytes) may receive a checksum.  Timed by the
+ * caller (events on hip_stream), bytes / time is the streaming-read rate this device sustains: the ceiling the
+ * kernels' own rates are to be read against.  Stateless; nothing waits.
+ */
+int32_t mtp_stream_probe(const void *buffer, size_t bytes, void *out8, void *hip_stream);
+
+/*
  * Diagnostics for the single-launch kernel of one sequence: device_buffer (device, int64, mtp_phase_trace_bytes(cfg)
  * bytes, or NULL to stop) receives 100 MHz wall-clock stamps of EVERY workgroup, laid out
  * [step][section 0..7][point 0..3][workgroup 0..W-1] with W = the device's compute-unit count: sections are the phases

@@ -33,7 +33,7 @@ EXPORTS = ["mtp_status_string", "mtp_workspace_bytes", "mtp_draft_init", "mtp_dr
            "mtp_train_workspace_bytes", "mtp_train_loss",
            "mtp_accept",
            "mtp_poll_error", "mtp_set_timing", "mtp_last_draft_ms", "mtp_set_launch_mode", "mtp_set_phase_trace",
-           "mtp_phase_trace_bytes",
+           "mtp_phase_trace_bytes", "mtp_stream_probe",
            "mtp_draft_destroy"]
 LAUNCH_PER_PHASE, LAUNCH_SINGLE, LAUNCH_AUTO, LAUNCH_ROWS = 0, 1, 2, 3
 # mtp_set_timing modes
@@ -100,6 +100,8 @@ _lib.mtp_last_draft_ms.restype = C.c_float
 _lib.mtp_last_draft_ms.argtypes = [C.c_void_p]
 _lib.mtp_set_launch_mode.restype = C.c_int32
 _lib.mtp_set_launch_mode.argtypes = [C.c_void_p, C.c_int32]
+_lib.mtp_stream_probe.restype = C.c_int32
+_lib.mtp_stream_probe.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
 _lib.mtp_phase_trace_bytes.restype = C.c_size_t
 _lib.mtp_phase_trace_bytes.argtypes = [C.POINTER(mtp_config)]
 _lib.mtp_set_phase_trace.restype = C.c_int32
@@ -228,6 +230,10 @@ def mtp_last_draft_ms(handle) -> float:
 
 def mtp_set_launch_mode(handle, mode: int) -> int:
     return int(_lib.mtp_set_launch_mode(handle, mode))
+
+
+def mtp_stream_probe(buffer, nbytes: int, out8, stream=0) -> int:
+    return int(_lib.mtp_stream_probe(_addr(buffer), nbytes, _addr(out8), stream))
 
 
 def mtp_phase_trace_bytes(cfg: mtp_config) -> int:
