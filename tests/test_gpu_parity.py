@@ -928,10 +928,10 @@ def test_7b_vocab_sweep_ctx8192(gpu, big, launch_mode):
     binding = gpu["binding"]
     eng = binding.DraftEngine(big["shape"], big["dev"], subsets, 1, act["kv_capacity"], wl.draft_steps)
     assert binding.mtp_set_launch_mode(eng.handle, launch_mode) == 0
-    K = 2
+    K = wl.draft_steps
     ref_full, res_full, caches = run_both(gpu, big["shape"], big["w"], big["dev"], act, subsets, -1, K, engine=eng)
     check_chain(ref_full, res_full, caches, act["kv_len"], K)
-    for si in (0, 2):
+    for si in range(len(subsets)):
         ref, res, caches = run_both(gpu, big["shape"], big["w"], big["dev"], act, subsets, si, K, engine=eng)
         check_chain(ref, res, caches, act["kv_len"], K)
         # step 1 sees the same inputs whatever the head: compressed logits are a row gather of the full logits
@@ -946,10 +946,9 @@ def test_7b_batch16_ragged_with_accept(gpu, big):
     act = synth.make_activations(wl, threads=16)
     subsets = synth.make_subsets(wl)
     K = wl.draft_steps
-    seqs = [0, 3, 8, 9, 15]  # shortest (719), longest (3958) and three others
     eng = binding.DraftEngine(big["shape"], big["dev"], subsets, wl.batch, act["kv_capacity"], K)
-    ref, res, caches = run_both(gpu, big["shape"], big["w"], big["dev"], act, subsets, 0, K, engine=eng, seqs=seqs)
-    check_chain(ref, res, caches, act["kv_len"][seqs], K)
+    ref, res, caches = run_both(gpu, big["shape"], big["w"], big["dev"], act, subsets, 0, K, engine=eng)  # all 16
+    check_chain(ref, res, caches, act["kv_len"], K)
     # accept + rollback on the whole batch, per-position acceptance 0.8
     kv = eng.to_device_i32(act["kv_len"])
     o = eng.draft(K, 0, eng.to_device_bits(act["hidden_in"]), eng.to_device_i32(act["token_in"]),
@@ -967,13 +966,170 @@ def test_7b_batch16_ragged_with_accept(gpu, big):
 
 def test_7b_batch64_long_context_sampled(gpu, big):
     """Throughput regime (B = 64, contexts in [8192, 32768], K = 5): the library runs the whole batch, the oracle
-    the shortest, the longest and one more sequence."""
+    sixteen of its sequences: the shortest, the longest, the four whose contexts end closest below and the four closest
+    above a multiple of the 4096-token attention split, and six more spread over the lengths."""
     wl = synth.WORKLOADS["c5_7b_b64"]
     act = synth.make_activations(wl, threads=16)
     subsets = synth.make_subsets(wl)
     K = wl.draft_steps
     L = act["kv_len"]
-    seqs = sorted({int(np.argmin(L)), int(np.argmax(L)), 7})
+    by_len = np.argsort(L)
+    edge = np.argsort(L % 4096)
+    pick = {int(by_len[0]), int(by_len[-1])} | {int(b) for b in edge[:4]} | {int(b) for b in edge[-4:]}
+    for b in by_len[3::9]:
+        if len(pick) < 16:
+            pick.add(int(b))
+    for b in by_len:
+        if len(pick) < 16:
+            pick.add(int(b))
+    seqs = sorted(pick)
+    assert len(seqs) == 16
     ref, res, caches = run_both(gpu, big["shape"], big["w"], big["dev"], act, subsets, 0, K, seqs=seqs,
                                 max_batch=wl.batch)
     check_chain(ref, res, caches, L[seqs], K)
+
+
+def test_7b_seven_draft_steps(gpu, big):
+    """Config 2 with K = 7, the longest chain of the draft-length sweep (Sec. 3.5), through the single-launch kernel and
+    with a launch per phase; the oracle's drafts forced, so that every step sees the same inputs on both sides."""
+    wl = synth.WORKLOADS["c2_7b_b1"]
+    act = synth.make_activations(wl, capacity=2112)
+    subsets = synth.make_subsets(wl)
+    binding = gpu["binding"]
+    eng = binding.DraftEngine(big["shape"], big["dev"], subsets, 1, act["kv_capacity"], 7)
+    for mode in (binding.LAUNCH_AUTO, binding.LAUNCH_PER_PHASE):
+        assert binding.mtp_set_launch_mode(eng.handle, mode) == 0
+        ref, res, caches = run_both(gpu, big["shape"], big["w"], big["dev"], act, subsets, 0, 7, engine=eng)
+        gap = check_chain(ref, res, caches, act["kv_len"], 7)
+        print("c2 K=7 mode", mode, "max |dlogit| =", gap)
+    eng.close()
+
+
+@pytest.mark.parametrize("B", [1, 3])
+def test_tiny_seven_draft_steps(gpu, tiny, B):
+    act = synth.make_activations(tiny["wl"], ctx=np.array([100, 0, 150][:B], dtype=np.int32), capacity=192)
+    ref, res, caches = run_both(gpu, tiny["shape"], tiny["w"], tiny["w"], act, [tiny["ids"]], 0, 7)
+    check_chain(ref, res, caches, act["kv_len"], 7)
+
+
+NAN_BITS = np.uint16(0x7FC0)
+
+
+def drafting_loop(gpu, wl, w_host, w_dev, act, subsets, K, cycles, seed, accept_prob=0.6):
+    """The loop of Sec. 2.3 over several cycles, library against oracle.  One cycle: the first draft step over the new
+    confirmed positions with the target model's hidden states (mtp_draft_extend: one position, or two where the cycle
+    before accepted all K drafts and the entry of the last one is still missing), K - 1 recursive steps from the head's
+    own output (mtp_draft_continue), acceptance with rollback mode 0 (mtp_accept).  Every cache slot at or beyond the
+    live length holds NaN on both sides, at the start and again after every rollback: a read past the live length
+    would poison the logits.  The library is fed the oracle's tokens, so both sides see the same inputs in every cycle;
+    integer results (accept lengths, emitted tokens, pending flags, lengths) must agree bit for bit."""
+    torch, Oracle, binding, orc_mod = gpu["torch"], gpu["Oracle"], gpu["binding"], gpu["orc"]
+    shape = wl.shape
+    B, cap, ids = len(act["kv_len"]), act["kv_capacity"], subsets[0]
+    rng = np.random.default_rng(seed)
+    std = float(synth.bf16_bits_to_f32(act["hidden_in"]).std())
+    okc, ovc = act["k_cache"].copy(), act["v_cache"].copy()
+    kv = act["kv_len"].astype(np.int32).copy()
+    for b in range(B):
+        okc[b][:, kv[b]:] = NAN_BITS
+        ovc[b][:, kv[b]:] = NAN_BITS
+    eng = binding.DraftEngine(shape, w_dev, subsets, 2 * B, cap, K)
+    dkc, dvc = eng.to_device_bits(okc), eng.to_device_bits(ovc)
+    dkv = eng.to_device_i32(kv)
+    orc = Oracle(shape, w_host, cap, "f32")
+    pending = np.zeros(B, dtype=np.int32)
+    tok_next = act["token_in"].astype(np.int32).copy()   # the token the next cycle starts from
+    tok_pending = np.zeros(B, dtype=np.int32)            # the accepted draft whose cache entry is missing
+    worst = 0.0
+    for c in range(cycles):
+        ext_len = (1 + pending).astype(np.int32)
+        hid = synth.f32_to_bf16_bits((rng.standard_normal((2, B, shape.d_model)) * std).astype(np.float32))
+        tok = np.zeros((2, B), dtype=np.int32)
+        for b in range(B):
+            if pending[b]:
+                tok[0, b], tok[1, b] = tok_pending[b], tok_next[b]
+            else:
+                tok[0, b] = tok_next[b]
+        # ---- first step over the new positions -------------------------------------------------------------------
+        ref = orc.extend(hid, tok, ext_len, okc, ovc, kv, ids)
+        ex = eng.extend(0, eng.to_device_bits(hid), eng.to_device_i32(tok), eng.to_device_i32(ext_len), dkc, dvc, dkv,
+                        want_logits=True, want_hidden=True)
+        torch.cuda.synchronize()
+        assert eng.poll_error() == 0
+        np.testing.assert_array_equal(dkv.cpu().numpy(), ref["kv_len"])
+        lg, hd = ex["logits"].cpu().numpy(), ex["hidden"].cpu().numpy()
+        assert np.isfinite(lg[0]).all()
+        drafts = np.zeros((B, K), dtype=np.int32)
+        own = torch.empty((B, shape.d_model), dtype=torch.float32, device="cuda:0")
+        cont = []
+        for b in range(B):
+            last = int(ext_len[b]) - 1
+            gap = float(np.abs(lg[:last + 1, b] - ref["logits"][:last + 1, b]).max())
+            worst = max(worst, gap)
+            assert gap <= LOGIT_TIGHT, (c, b, gap)
+            drafts[b, 0] = ref["draft"][last, b]
+            own[b] = ex["hidden"][last, b]
+            # ---- K - 1 recursive steps, the oracle's by single steps fed back by hand ------------------------------
+            cont.append(orc.chain_from_own_hidden(K - 1, ref["hidden"][last, b], int(drafts[b, 0]), okc[b], ovc[b],
+                                                  int(ref["kv_len"][b]), ids))
+            drafts[b, 1:] = cont[b]["draft"]
+        kv = ref["kv_len"].astype(np.int32).copy()
+        forced = np.ascontiguousarray(drafts[:, 1:K - 1]) if K > 2 else None
+        out = eng.draft_continue(K - 1, 0, own, eng.to_device_i32(drafts[:, 0].copy()), dkc, dvc, dkv,
+                                 forced=eng.to_device_i32(forced) if forced is not None else None, want_logits=True)
+        torch.cuda.synchronize()
+        assert eng.poll_error() == 0
+        lgc, drc = out["logits"].cpu().numpy(), out["draft"].cpu().numpy()
+        for b in range(B):
+            gap = float(np.abs(lgc[b] - cont[b]["logits"]).max())
+            worst = max(worst, gap)
+            assert gap <= LOGIT_TIGHT, (c, b, gap)
+            clear = cont[b]["margin"] > MARGIN
+            np.testing.assert_array_equal(drc[b][clear], cont[b]["draft"][clear])
+        # ---- acceptance + rollback: the first of the K drafts came from the block's last position, whose slot the block
+        # already counted, so the draft started one slot below the present length -----------------------------------
+        tgt = synth.make_targets(wl, drafts, accept_prob=accept_prob, salt=c)
+        want = orc_mod.accept(drafts, tgt, kv - 1, 0)
+        dkv -= 1
+        got = eng.accept(eng.to_device_i32(drafts), eng.to_device_i32(tgt), dkv, 0)
+        torch.cuda.synchronize()
+        for key in ("accept_len", "out_tokens", "pending", "kv_len"):
+            np.testing.assert_array_equal(got[key].cpu().numpy(), want[key])
+        np.testing.assert_array_equal(dkv.cpu().numpy(), want["kv_len"])
+        kv, pending = want["kv_len"].astype(np.int32).copy(), want["pending"].astype(np.int32).copy()
+        a = want["accept_len"]
+        for b in range(B):
+            tok_next[b] = tgt[b, a[b]]          # the target's own token after the accepted run
+            tok_pending[b] = drafts[b, K - 1]
+            # live entries agree (up to a bf16 step where the recursive steps wrote them), dead ones become NaN again
+            hk, hv = dkc[b].cpu().numpy().view(np.uint16), dvc[b].cpu().numpy().view(np.uint16)
+            assert appended_entries_close(hk[:, :kv[b]], okc[b][:, :kv[b]], recursive_from=0)
+            assert appended_entries_close(hv[:, :kv[b]], ovc[b][:, :kv[b]], recursive_from=0)
+            okc[b][:, kv[b]:] = NAN_BITS
+            ovc[b][:, kv[b]:] = NAN_BITS
+            # the library's own live entries stay as they are; only the dead slots are overwritten
+            dkc[b][:, kv[b]:] = int(NAN_BITS.view(np.int16))
+            dvc[b][:, kv[b]:] = int(NAN_BITS.view(np.int16))
+            okc[b][:, :kv[b]] = hk[:, :kv[b]]   # both sides continue from the same live entries
+            ovc[b][:, :kv[b]] = hv[:, :kv[b]]
+    eng.close()
+    return worst, pending
+
+
+def test_tiny_drafting_loop_with_poisoned_dead_slots(gpu, tiny):
+    act = synth.make_activations(tiny["wl"], ctx=np.array([40, 0, 120], dtype=np.int32), capacity=192)
+    worst, _ = drafting_loop(gpu, tiny["wl"], tiny["w"], tiny["w"], act, [tiny["ids"]], 3, 5, 901)
+    print("tiny loop: largest logit gap", worst)
+    # acceptance probability 1: every cycle accepts all K drafts and leaves a pending entry for the next block to close
+    worst, pending = drafting_loop(gpu, tiny["wl"], tiny["w"], tiny["w"], act, [tiny["ids"]], 3, 4, 902,
+                                   accept_prob=1.0)
+    assert pending.all()
+
+
+def test_7b_drafting_loop_with_poisoned_dead_slots(gpu, big):
+    """Config 2, four cycles: the recursive steps run through the single-launch kernel."""
+    wl = synth.WORKLOADS["c2_7b_b1"]
+    act = synth.make_activations(wl, capacity=2112)
+    worst, _ = drafting_loop(gpu, wl, big["w"], big["dev"], act, synth.make_subsets(wl), 3, 4, 903,
+                             accept_prob=0.8)
+    print("c2 loop: largest logit gap", worst)
