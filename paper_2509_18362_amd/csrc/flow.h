@@ -109,7 +109,8 @@ __device__ __forceinline__ FlowJob flow_job(const DraftParams &p, int ph, int nw
 }
 
 // a wave's share of a job: rows wr0, wr0 + nw, ...; chunks of eight 1 KiB loads, a chunk never straddles rows; the
-// chunk count is padded to even (the ring has two slots and a phase always starts in slot 0)
+// chunk count is padded to an odd number of at least three (a phase's first three chunks sit in register slot 0,
+// register slot 1 and the LDS slot, the rest alternate between the register slots)
 struct FlowGeom {
     int nblk, cpr, nrows, nreal, nchunks, wr_last;
 };
@@ -119,7 +120,7 @@ __device__ __forceinline__ FlowGeom flow_geom(const FlowJob &j, int wr0, int nw)
     g.cpr = (g.nblk + kChunkLoads - 1) / kChunkLoads;
     g.nrows = wr0 < j.rows ? (j.rows - wr0 + nw - 1) / nw : 0;
     g.nreal = g.nrows * g.cpr;
-    g.nchunks = (g.nreal + 1) & ~1;
+    g.nchunks = max(3, g.nreal | 1);
     g.wr_last = wr0 + max(g.nrows - 1, 0) * nw;
     return g;
 }
@@ -163,6 +164,33 @@ __device__ __forceinline__ void flow_issue(FlowLoad &L, u32x4 (&buf)[kChunkLoads
         L.rid = L.j.row_id(L.row);
     }
 }
+
+// The same request into the wave's LDS slot (8 KiB: eight loads of 1 KiB, each lane's 16 bytes where a register load
+// would have put them).  The compiler counts these loads like the others but does not wait for them before LDS reads:
+// the reader does (flow_wait_lds_slot).
+constexpr int kLdsSlotBytes = kChunkLoads * 1024;
+__device__ __forceinline__ void flow_issue_lds(FlowLoad &L, char *slot, int lane) {
+    const bool live = L.n < L.g.nreal;
+    const int v = live ? min(L.row, L.g.wr_last) : 0;
+    const int jr = live ? L.jr : 0;
+    const row_rsrc rs = make_row_rsrc(L.j.rowptr(v, jr, L.rid), live ? L.j.K * 2 : 0); // wave-uniform
+#pragma unroll
+    for (int u = 0; u < kChunkLoads; ++u) {
+        const int blk = min(L.c * kChunkLoads + u, L.g.nblk - 1);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (__attribute__((address_space(3))) void *)(slot + u * 1024), 16,
+                                                 lane * 16, min(blk * 512, L.j.K - 512) * 2, 0, 2);
+    }
+    ++L.n;
+    if (++L.c == L.g.cpr) {
+        L.c = 0;
+        L.row += L.j.nw;
+        ++L.jr;
+        L.rid = L.j.row_id(L.row);
+    }
+}
+// The LDS slot's chunk was requested before the two register chunks that follow it in the stream (sixteen loads) and
+// loads complete in order: once at most sixteen requests are outstanding it has landed.
+__device__ __forceinline__ void flow_wait_lds_slot() { asm volatile("s_waitcnt vmcnt(16)" ::: "memory"); }
 
 // ---- polling -----------------------------------------------------------------------------------------------
 __device__ __forceinline__ row_rsrc make_vec_rsrc(const void *base, size_t bytes) {
@@ -223,12 +251,20 @@ __device__ __forceinline__ void poll4x2(const DraftParams &p, row_rsrc rs, int a
     }
 }
 
+// Workgroup barrier of this kernel: the wave's own LDS reads and writes have completed, nothing else is waited for.
+// (A fence on LDS would also wait for the chunk that is on its way INTO the LDS slot, i.e. for every load in flight.)
+__device__ __forceinline__ void flow_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
 // workgroup sum whose barriers order LDS traffic only (weight chunks stay in flight); red holds kWaves floats
 __device__ __forceinline__ float block_sum_lds(float x, float *red) {
     x = wave_sum(x);
-    lds_barrier();
+    flow_barrier();
     if ((threadIdx.x & (kWave - 1)) == 0) red[threadIdx.x / kWave] = x;
-    lds_barrier();
+    flow_barrier();
     float t = 0.f;
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) t += red[w];
@@ -240,9 +276,9 @@ __device__ __forceinline__ unsigned long long block_max_u64_lds(unsigned long lo
         unsigned long long o = __shfl_xor(v, off, kWave);
         v = o > v ? o : v;
     }
-    lds_barrier();
+    flow_barrier();
     if ((threadIdx.x & (kWave - 1)) == 0) red64[threadIdx.x / kWave] = v;
-    lds_barrier();
+    flow_barrier();
     unsigned long long r = 0ull;
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) r = red64[w] > r ? red64[w] : r;
@@ -304,6 +340,10 @@ __device__ __forceinline__ float silu_mul(float g, float u) { return (g / (1.0f 
 // LDS of the kernel: [activations hi/lo of the widest phase | attention scratch] then the residual stream (d floats),
 // the wave-private strips of the projection's first half, and reduction scratch
 __host__ __device__ inline size_t flow_part_floats(int d, int nvb) { return (size_t)kWaves * ((d + nvb * kWaves - 1) / (nvb * kWaves)) + 8; }
+// bytes behind the shared region: the waves' LDS chunk slots, the residual stream, the projection's strips, scratch
+__host__ __device__ inline size_t flow_tail_bytes(int d, int nvb) {
+    return (size_t)kWaves * kLdsSlotBytes + ((size_t)d + flow_part_floats(d, nvb)) * 4 + 256;
+}
 
 // ---------------------------------------------------------------------------------------------------
 // the kernel body
@@ -314,7 +354,9 @@ __device__ __forceinline__ void flow_steps(const DraftParams &p, char *smem) {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
     const int nw = nvb * kWaves, wr0 = vb * kWaves + wave;
-    float *resid = reinterpret_cast<float *>(smem + p.fused_gemv_bytes); // x, x1 = x + o, then the step's output state
+    char *slot = smem + p.fused_gemv_bytes + (size_t)wave * kLdsSlotBytes; // this wave's third chunk slot
+    float *resid = reinterpret_cast<float *>(smem + p.fused_gemv_bytes + (size_t)kWaves * kLdsSlotBytes); // x, x1 = x + o,
+                                                                           // then the step's output state
     const int part_rows = (d + nw - 1) / nw;                             // rows of the projection per wave
     float *ppart = resid + d + (size_t)wave * part_rows;                 // this wave's first-half sums
     unsigned long long *red64 = reinterpret_cast<unsigned long long *>(resid + d + flow_part_floats(d, nvb));
@@ -362,9 +404,10 @@ __device__ __forceinline__ void flow_steps(const DraftParams &p, char *smem) {
                 flow_load_begin(L, job, g, ph, wr0);
                 flow_issue(L, ring[0], lane);
                 flow_issue(L, ring[1], lane);
+                flow_issue_lds(L, slot, lane);
             }
             stamp(step, sec, kTraceRequested);
-            lds_barrier(); // every wave has finished with the activations of the phase before
+            flow_barrier(); // every wave has finished with the activations of the phase before
 
             // ---- stage this phase's input vector into LDS as bf16 hi + lo ------------------------------------------
             {
@@ -533,7 +576,7 @@ __device__ __forceinline__ void flow_steps(const DraftParams &p, char *smem) {
                 }
                 }
             }
-            lds_barrier();
+            flow_barrier();
             stamp(step, sec, kTraceStaged);
 
             // ---- stream this wave's rows --------------------------------------------------------------------------
@@ -551,73 +594,95 @@ __device__ __forceinline__ void flow_steps(const DraftParams &p, char *smem) {
             f32x4 acc_h = {0.f, 0.f, 0.f, 0.f}, acc_l = {0.f, 0.f, 0.f, 0.f};
             const int dv = (lane & 15) - 4 * (lane >> 4); // which of this lane's four results lies on the diagonal
             int c_row = wr0, c_j = 0, c_c = 0;
-            for (int n0 = 0; n0 < g.nchunks; n0 += 2) {
+            // one chunk: eight blocks of the row against the staged activations; w(u) = the chunk's u-th 1 KiB
+            auto consume = [&](auto w) {
+#pragma unroll
+                for (int u = 0; u < kChunkLoads; ++u) {
+                    const int blk = c_c * kChunkLoads + u;
+                    const int e0 = min(min(blk, g.nblk - 1) * 512, job.K - 512) + lane * 8;
+                    // slots past the row's last block contribute nothing; a last block that was shifted left to
+                    // stay inside the row only contributes the elements the block before it did not cover
+                    const bool own = blk < g.nblk && e0 >= blk * 512;
+                    u32x4 ah = *reinterpret_cast<const u32x4 *>(l.hi + e0);
+                    u32x4 al = *reinterpret_cast<const u32x4 *>(l.lo + e0);
+                    ah = own ? ah : zero4;
+                    al = own ? al : zero4;
+                    const u32x4 wv = w(u);
+                    acc_h = mfma16(ah, wv, acc_h);
+                    acc_l = mfma16(al, wv, acc_l);
+                }
+            };
+            // the cursor moves on to the phase that follows once this phase's share is exhausted
+            auto advance_cursor = [&]() {
+                if (L.n >= L.g.nchunks && L.id == ph && next != FL_NONE) {
+                    const FlowJob nj = flow_job(p, next, nw);
+                    flow_load_begin(L, nj, flow_geom(nj, wr0, nw), next, wr0);
+                }
+            };
+            auto row_end = [&](int n) {
+                if (n < g.nreal && ++c_c == g.cpr) { // end of a row: sum the diagonal
+                    c_c = 0;
+                    const f32x4 t = acc_h + acc_l;
+                    float val = dv == 0 ? t.x : dv == 1 ? t.y : dv == 2 ? t.z : dv == 3 ? t.w : 0.f;
+                    val = wave_sum(val);
+                    acc_h = f32x4{0.f, 0.f, 0.f, 0.f};
+                    acc_l = f32x4{0.f, 0.f, 0.f, 0.f};
+                    if (lane == 0) {
+                        const int li = c_j; // this wave's c_j-th row
+                        switch (ph) {
+                        case FL_PROJH: ppart[li] = val; break;
+                        case FL_PROJE: st_tagged(out_t + c_row, ppart[li] + val, out_tag); break;
+                        case FL_GATEUP: {
+                            const int w = c_row - c_j * nw;
+                            if (c_j < pair_rows) {
+                                if ((c_j & 1) == 0)
+                                    gate_saved = val;
+                                else
+                                    st_tagged(out_t + (c_j >> 1) * nw + w, silu_mul(gate_saved, val), out_tag);
+                            } else { // dealt singly: gate values, then up values, behind the pairs
+                                st_tagged(out_t + job.pair_rounds * nw + w, val, out_tag);
+                            }
+                            break;
+                        }
+                        case FL_HEAD: {
+                            if (logits) logits[c_row] = val;
+                            const unsigned long long key = argmax_key(val, (uint32_t)c_row);
+                            best = key > best ? key : best;
+                            break;
+                        }
+                        default: st_tagged(out_t + c_row, val, out_tag); break;
+                        }
+                    }
+                    c_row += nw;
+                    ++c_j;
+                }
+            };
+            // Chunks n0 and n0 + 1 sit in the register slots; the phase's third chunk sits in the LDS slot and is taken
+            // after the first two.  Every register slot is refilled as soon as it is free; the LDS slot is refilled once,
+            // at the end of the phase, with the third chunk of the phase that follows.
+            for (int n0 = 0; n0 < g.nchunks; n0 += (n0 == 0 ? 3 : 2)) {
 #pragma unroll
                 for (int s = 0; s < 2; ++s) {
-#pragma unroll
-                    for (int u = 0; u < kChunkLoads; ++u) {
-                        const int blk = c_c * kChunkLoads + u;
-                        const int e0 = min(min(blk, g.nblk - 1) * 512, job.K - 512) + lane * 8;
-                        // slots past the row's last block contribute nothing; a last block that was shifted left to
-                        // stay inside the row only contributes the elements the block before it did not cover
-                        const bool own = blk < g.nblk && e0 >= blk * 512;
-                        u32x4 ah = *reinterpret_cast<const u32x4 *>(l.hi + e0);
-                        u32x4 al = *reinterpret_cast<const u32x4 *>(l.lo + e0);
-                        ah = own ? ah : zero4;
-                        al = own ? al : zero4;
-                        acc_h = mfma16(ah, ring[s][u], acc_h);
-                        acc_l = mfma16(al, ring[s][u], acc_l);
-                    }
-                    // the slot is free again: this phase's next chunk, or (its share exhausted) the first chunks of the
-                    // phase that follows
-                    if (L.n >= L.g.nchunks && L.id == ph && next != FL_NONE) {
-                        const FlowJob nj = flow_job(p, next, nw);
-                        flow_load_begin(L, nj, flow_geom(nj, wr0, nw), next, wr0);
-                    }
+                    consume([&](int u) { return ring[s][u]; });
+                    advance_cursor();
                     // Long phases keep ONE chunk in flight per wave while they stream (the other slot's loads are waited
                     // for before the next request goes out): 16 MiB over the chip already covers the memory latency, more
                     // only deepens the queues, and the compute dies then share the bandwidth unevenly (output head: the
-                    // odd-numbered dies finished 6 us after the even ones with two chunks in flight).  The second slot
-                    // earns its keep at the ends of a phase, where the requests run ahead into the next one.
+                    // odd-numbered dies finished 6 us after the even ones with two chunks in flight).  The other slots
+                    // earn their keep at the ends of a phase, where the requests run ahead into the next one.
                     if (throttle && L.id == ph) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
                     flow_issue(L, ring[s], lane);
-                    if (n0 + s < g.nreal && ++c_c == g.cpr) { // end of a row: sum the diagonal
-                        c_c = 0;
-                        const f32x4 t = acc_h + acc_l;
-                        float val = dv == 0 ? t.x : dv == 1 ? t.y : dv == 2 ? t.z : dv == 3 ? t.w : 0.f;
-                        val = wave_sum(val);
-                        acc_h = f32x4{0.f, 0.f, 0.f, 0.f};
-                        acc_l = f32x4{0.f, 0.f, 0.f, 0.f};
-                        if (lane == 0) {
-                            const int li = c_j; // this wave's c_j-th row
-                            switch (ph) {
-                            case FL_PROJH: ppart[li] = val; break;
-                            case FL_PROJE: st_tagged(out_t + c_row, ppart[li] + val, out_tag); break;
-                            case FL_GATEUP: {
-                                const int w = c_row - c_j * nw;
-                                if (c_j < pair_rows) {
-                                    if ((c_j & 1) == 0)
-                                        gate_saved = val;
-                                    else
-                                        st_tagged(out_t + (c_j >> 1) * nw + w, silu_mul(gate_saved, val), out_tag);
-                                } else { // dealt singly: gate values, then up values, behind the pairs
-                                    st_tagged(out_t + job.pair_rounds * nw + w, val, out_tag);
-                                }
-                                break;
-                            }
-                            case FL_HEAD: {
-                                if (logits) logits[c_row] = val;
-                                const unsigned long long key = argmax_key(val, (uint32_t)c_row);
-                                best = key > best ? key : best;
-                                break;
-                            }
-                            default: st_tagged(out_t + c_row, val, out_tag); break;
-                            }
-                        }
-                        c_row += nw;
-                        ++c_j;
-                    }
+                    row_end(n0 + s);
                 }
+                if (n0 == 0) {
+                    flow_wait_lds_slot();
+                    consume([&](int u) { return *reinterpret_cast<const u32x4 *>(slot + u * 1024 + lane * 16); });
+                    row_end(2);
+                }
+            }
+            if (next != FL_NONE) { // (no next phase: nothing is written into LDS that the attention may be using)
+                advance_cursor();
+                flow_issue_lds(L, slot, lane);
             }
             if (ph == FL_HEAD) {
                 // the workgroup's candidate: (logit, token id), each with the tag in its upper half
@@ -639,7 +704,7 @@ __device__ __forceinline__ void flow_steps(const DraftParams &p, char *smem) {
             stamp(step, sec, kTraceDone);
             if (ph == FL_QKV) { // attention: polls q, k, v itself and publishes its result as tagged elements
                 stamp(step, 2, kTraceRequested);
-                lds_barrier(); // the activations' LDS becomes the attention's
+                flow_barrier(); // the activations' LDS becomes the attention's
                 stamp(step, 2, kTraceReleased);
                 stamp(step, 2, kTraceStaged);
                 call_attn<G, HD, true, true, true>(p, step, vb, nvb, smem);
@@ -649,7 +714,7 @@ __device__ __forceinline__ void flow_steps(const DraftParams &p, char *smem) {
     }
     // publish the last draft id
     if (vb == 0) {
-        lds_barrier();
+        flow_barrier();
         const int did = winner(p.K - 1);
         if (threadIdx.x == 0) p.draft_out[p.K - 1] = seq_dead(p, 0) ? -1 : did;
     }

@@ -785,7 +785,7 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
         const int fgrid = std::min(h->num_cus, kMaxFusedGrid);
         size_t region = std::max(flow_gemv_region(p.d, p.qd, p.F), lds_attn);
         region = (region + 255) / 256 * 256;
-        const size_t lds_flow = region + ((size_t)p.d + flow_part_floats(p.d, fgrid)) * 4 + 256;
+        const size_t lds_flow = region + flow_tail_bytes(p.d, fgrid);
         bool fits = lds_flow <= h->lds_limit;
         if (fits && lds_flow > h->flow_lds_ok) { // once per LDS size: a workgroup of this kernel fits a compute unit
             int per_cu = 0;
