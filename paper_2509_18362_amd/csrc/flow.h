@@ -22,6 +22,9 @@
 #pragma once
 #include "phases.h"
 
+#ifndef MTP_THR
+#define MTP_THR "0"
+#endif
 namespace mtp {
 
 // time stamps of every workgroup (mtp_set_phase_trace): [step][section][point][workgroup]
@@ -30,13 +33,15 @@ constexpr int kTraceSections = 8; // projection (embedding half), q/k/v, attenti
 constexpr int kTracePoints = 4;
 enum : int { kTraceRequested = 0, kTraceReleased, kTraceStaged, kTraceDone };
 
-// LDS region shared by the staged activations of every matrix phase (one sequence)
+// LDS region shared by the staged activations of every matrix phase (one sequence): bf16 hi then lo halves, each padded
+// with zeros to whole 512-element blocks (a row's last block is multiplied in full: the weights beyond the row read as
+// zeros, so what stands beside them only has to be finite)
+__host__ __device__ inline int flow_kpad(int K) { return (K + 511) / 512 * 512; }
 __host__ __device__ inline size_t flow_gemv_region(int d, int qd, int F) {
-    size_t m = gemv_lds_bytes(d, 1, 1);
-    const size_t b = gemv_lds_bytes(qd, 1, 1), c = gemv_lds_bytes(F, 1, 1);
-    m = b > m ? b : m;
-    m = c > m ? c : m;
-    return (m + 255) / 256 * 256;
+    int m = flow_kpad(d);
+    m = flow_kpad(qd) > m ? flow_kpad(qd) : m;
+    m = flow_kpad(F) > m ? flow_kpad(F) : m;
+    return ((size_t)m * 4 + 255) / 256 * 256;
 }
 
 enum FlowPhase : int { FL_PROJH = 0, FL_PROJE, FL_QKV, FL_O, FL_GATEUP, FL_DOWN, FL_HEAD, FL_NONE };
@@ -151,11 +156,11 @@ __device__ __forceinline__ void flow_issue(FlowLoad &L, u32x4 (&buf)[kChunkLoads
     const int v = live ? min(L.row, L.g.wr_last) : 0;
     const int jr = live ? L.jr : 0;
     const row_rsrc rs = make_row_rsrc(L.j.rowptr(v, jr, L.rid), live ? L.j.K * 2 : 0); // wave-uniform
+    // The block's offset travels in the per-lane offset, which the buffer's range check covers: whatever lies beyond the
+    // row (the tail of its last block, the empty slots of its last chunk) reads as zeros and moves no data.
+    const int voff = lane * 16 + L.c * (kChunkLoads * 1024);
 #pragma unroll
-    for (int u = 0; u < kChunkLoads; ++u) {
-        const int blk = min(L.c * kChunkLoads + u, L.g.nblk - 1); // empty slots of a row's last chunk re-read its last block
-        buf[u] = row_load16<true>(rs, lane * 16, min(blk * 512, L.j.K - 512) * 2);
-    }
+    for (int u = 0; u < kChunkLoads; ++u) buf[u] = row_load16<true>(rs, voff + u * 1024, 0);
     ++L.n;
     if (++L.c == L.g.cpr) {
         L.c = 0;
@@ -174,12 +179,11 @@ __device__ __forceinline__ void flow_issue_lds(FlowLoad &L, char *slot, int lane
     const int v = live ? min(L.row, L.g.wr_last) : 0;
     const int jr = live ? L.jr : 0;
     const row_rsrc rs = make_row_rsrc(L.j.rowptr(v, jr, L.rid), live ? L.j.K * 2 : 0); // wave-uniform
+    const int voff = lane * 16 + L.c * (kChunkLoads * 1024);
 #pragma unroll
-    for (int u = 0; u < kChunkLoads; ++u) {
-        const int blk = min(L.c * kChunkLoads + u, L.g.nblk - 1);
+    for (int u = 0; u < kChunkLoads; ++u)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (__attribute__((address_space(3))) void *)(slot + u * 1024), 16,
-                                                 lane * 16, min(blk * 512, L.j.K - 512) * 2, 0, 2);
-    }
+                                                 voff + u * 1024, 0, 0, 2);
     ++L.n;
     if (++L.c == L.g.cpr) {
         L.c = 0;
@@ -287,7 +291,7 @@ __device__ __forceinline__ unsigned long long block_max_u64_lds(unsigned long lo
 
 // RMSNorm(u; gain) of the values this thread holds (v[it][q] = element (it * kBlock + tid) * 4 + q of a d-vector, gq[it]
 // the four bf16 gains of the same elements) into hi/lo.  keep_raw (LDS, optional) receives u itself, keep_norm (LDS, optional) and out_global (optional) the result.
-__device__ __forceinline__ void flow_norm(float (&v)[kMaxNormIter][4], const u32x2 (&gq)[kMaxNormIter], int d, float eps,
+__device__ __forceinline__ void flow_norm(float (&v)[kMaxNormIter][4], const u32x2 (&gq)[kMaxNormIter], int d, int kpad, float eps,
                                           uint16_t *hi, uint16_t *lo, float *red, float *keep_raw, float *keep_norm,
                                           float *out_global) {
     float ss = 0.f;
@@ -322,6 +326,9 @@ __device__ __forceinline__ void flow_norm(float (&v)[kMaxNormIter][4], const u32
             const f32x4 w = {o[0], o[1], o[2], o[3]};
             if (keep_norm) *reinterpret_cast<f32x4 *>(keep_norm + e) = w;
             if (out_global) *reinterpret_cast<f32x4 *>(out_global + e) = w;
+        } else if (e < kpad) { // the tail of the last 512-element block
+            *reinterpret_cast<u32x2 *>(hi + e) = u32x2{0u, 0u};
+            *reinterpret_cast<u32x2 *>(lo + e) = u32x2{0u, 0u};
         }
     }
 }
@@ -361,7 +368,6 @@ __device__ __forceinline__ void flow_steps(const DraftParams &p, char *smem) {
     float *ppart = resid + d + (size_t)wave * part_rows;                 // this wave's first-half sums
     unsigned long long *red64 = reinterpret_cast<unsigned long long *>(resid + d + flow_part_floats(d, nvb));
     float *red = reinterpret_cast<float *>(red64 + kWaves);
-    const u32x4 zero4 = {0u, 0u, 0u, 0u};
 
     auto stamp = [&](int step, int sec, int pt) {
         if (p.trace && threadIdx.x == 0)
@@ -398,7 +404,8 @@ __device__ __forceinline__ void flow_steps(const DraftParams &p, char *smem) {
         for (int ph = FL_PROJH; ph <= FL_HEAD; ++ph) {
             const FlowJob job = flow_job(p, ph, nw);
             const FlowGeom g = flow_geom(job, wr0, nw);
-            const GemvLds l = gemv_lds(smem, job.K, 1, 1);
+            const int kpad = flow_kpad(job.K);
+            uint16_t *act_hi = reinterpret_cast<uint16_t *>(smem), *act_lo = act_hi + kpad;
             const int sec = ph == FL_PROJH ? 7 : ph == FL_PROJE ? 0 : ph == FL_QKV ? 1 : ph + 0; // O..HEAD are 3..6
             if (L.id != ph) { // first phase of the call, or the phase after the attention: nothing was requested ahead
                 flow_load_begin(L, job, g, ph, wr0);
@@ -458,7 +465,7 @@ __device__ __forceinline__ void flow_steps(const DraftParams &p, char *smem) {
                         }
                     }
                     stamp(step, sec, kTraceReleased);
-                    flow_norm(v, gq, d, p.eps, l.hi, l.lo, red, nullptr, nullptr, nullptr);
+                    flow_norm(v, gq, d, kpad, p.eps, act_hi, act_lo, red, nullptr, nullptr, nullptr);
                     break;
                 }
                 case FL_PROJE: {
@@ -487,13 +494,13 @@ __device__ __forceinline__ void flow_steps(const DraftParams &p, char *smem) {
                             v[it][3] = hi_half(raw.y);
                         }
                     }
-                    flow_norm(v, gq, d, p.eps, l.hi, l.lo, red, nullptr, nullptr, nullptr);
+                    flow_norm(v, gq, d, kpad, p.eps, act_hi, act_lo, red, nullptr, nullptr, nullptr);
                     break;
                 }
                 case FL_QKV:
                     poll_vec<kMaxNormIter>(p, p.xt, d, step_tag(p, step, TS_X), v);
                     stamp(step, sec, kTraceReleased);
-                    flow_norm(v, gq, d, p.eps, l.hi, l.lo, red, resid, nullptr, nullptr);
+                    flow_norm(v, gq, d, kpad, p.eps, act_hi, act_lo, red, resid, nullptr, nullptr);
                     break;
                 case FL_GATEUP: { // x1 = x + w_o a
                     poll_vec<kMaxNormIter>(p, p.ot, d, step_tag(p, step, TS_O), v);
@@ -509,7 +516,7 @@ __device__ __forceinline__ void flow_steps(const DraftParams &p, char *smem) {
                             v[it][3] = r.w + v[it][3];
                         }
                     }
-                    flow_norm(v, gq, d, p.eps, l.hi, l.lo, red, resid, nullptr, nullptr);
+                    flow_norm(v, gq, d, kpad, p.eps, act_hi, act_lo, red, resid, nullptr, nullptr);
                     break;
                 }
                 case FL_HEAD: { // x2 = x1 + w_down m; the step's output hidden state
@@ -527,20 +534,20 @@ __device__ __forceinline__ void flow_steps(const DraftParams &p, char *smem) {
                         }
                     }
                     float *ho = (vb == 0 && p.hidden_out) ? p.hidden_out + (size_t)step * d : nullptr;
-                    flow_norm(v, gq, d, p.eps, l.hi, l.lo, red, nullptr, resid, ho);
+                    flow_norm(v, gq, d, kpad, p.eps, act_hi, act_lo, red, nullptr, resid, ho);
                     break;
                 }
                 case FL_O: { // the attention's result, as it is
                     const int n = p.qd;
                     const unsigned tag = step_tag(p, step, TS_ATTN);
-                    for (int e0 = 0; e0 < l.kpad; e0 += kMaxNormIter * kBlock * 4) {
+                    for (int e0 = 0; e0 < kpad; e0 += kMaxNormIter * kBlock * 4) {
                         poll_vec<kMaxNormIter>(p, p.attnt + e0, max(min(n - e0, kMaxNormIter * kBlock * 4), 0), tag, v);
 #pragma unroll
                         for (int it = 0; it < kMaxNormIter; ++it) {
                             const int e = e0 + (it * kBlock + (int)threadIdx.x) * 4;
-                            if (e < l.kpad) {
+                            if (e < kpad) {
                                 const float z[4] = {0.f, 0.f, 0.f, 0.f};
-                                flow_split4(e < n ? v[it] : z, l.hi, l.lo, e);
+                                flow_split4(e < n ? v[it] : z, act_hi, act_lo, e);
                             }
                         }
                     }
@@ -551,12 +558,12 @@ __device__ __forceinline__ void flow_steps(const DraftParams &p, char *smem) {
                     const int pn = (F / nw) * nw, rem = F - pn; // pairs, then rem gate values, then rem up values
                     const unsigned tag = step_tag(p, step, TS_GU);
                     const row_rsrc gu_rs = make_vec_rsrc(p.gut, (size_t)(F + rem) * 8);
-                    for (int e0 = 0; e0 < l.kpad; e0 += kMaxNormIter * kBlock * 4) {
+                    for (int e0 = 0; e0 < kpad; e0 += kMaxNormIter * kBlock * 4) {
                         poll_vec<kMaxNormIter>(p, p.gut + e0, max(min(pn - e0, kMaxNormIter * kBlock * 4), 0), tag, v);
 #pragma unroll
                         for (int it = 0; it < kMaxNormIter; ++it) {
                             const int e = e0 + (it * kBlock + (int)threadIdx.x) * 4;
-                            if (e < l.kpad) {
+                            if (e < kpad) {
                                 float m[4] = {0.f, 0.f, 0.f, 0.f};
                                 if (e < pn) {
 #pragma unroll
@@ -567,7 +574,7 @@ __device__ __forceinline__ void flow_steps(const DraftParams &p, char *smem) {
 #pragma unroll
                                     for (int q = 0; q < 4; ++q) m[q] = silu_mul(gt[q], up[q]);
                                 }
-                                flow_split4(m, l.hi, l.lo, e);
+                                flow_split4(m, act_hi, act_lo, e);
                             }
                         }
                     }
@@ -598,15 +605,10 @@ __device__ __forceinline__ void flow_steps(const DraftParams &p, char *smem) {
             auto consume = [&](auto w) {
 #pragma unroll
                 for (int u = 0; u < kChunkLoads; ++u) {
-                    const int blk = c_c * kChunkLoads + u;
-                    const int e0 = min(min(blk, g.nblk - 1) * 512, job.K - 512) + lane * 8;
-                    // slots past the row's last block contribute nothing; a last block that was shifted left to
-                    // stay inside the row only contributes the elements the block before it did not cover
-                    const bool own = blk < g.nblk && e0 >= blk * 512;
-                    u32x4 ah = *reinterpret_cast<const u32x4 *>(l.hi + e0);
-                    u32x4 al = *reinterpret_cast<const u32x4 *>(l.lo + e0);
-                    ah = own ? ah : zero4;
-                    al = own ? al : zero4;
+                    // slots past the row's last block hold zero weights: they re-read the last block's activations
+                    const int e0 = min(c_c * kChunkLoads + u, g.nblk - 1) * 512 + lane * 8;
+                    const u32x4 ah = *reinterpret_cast<const u32x4 *>(act_hi + e0);
+                    const u32x4 al = *reinterpret_cast<const u32x4 *>(act_lo + e0);
                     const u32x4 wv = w(u);
                     acc_h = mfma16(ah, wv, acc_h);
                     acc_l = mfma16(al, wv, acc_l);
@@ -670,7 +672,7 @@ __device__ __forceinline__ void flow_steps(const DraftParams &p, char *smem) {
                     // only deepens the queues, and the compute dies then share the bandwidth unevenly (output head: the
                     // odd-numbered dies finished 6 us after the even ones with two chunks in flight).  The other slots
                     // earn their keep at the ends of a phase, where the requests run ahead into the next one.
-                    if (throttle && L.id == ph) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                    if (throttle && L.id == ph) asm volatile("s_waitcnt vmcnt(" MTP_THR ")" ::: "memory");
                     flow_issue(L, ring[s], lane);
                     row_end(n0 + s);
                 }
