@@ -22,9 +22,6 @@
 #pragma once
 #include "phases.h"
 
-#ifndef MTP_THR
-#define MTP_THR "0"
-#endif
 namespace mtp {
 
 // time stamps of every workgroup (mtp_set_phase_trace): [step][section][point][workgroup]
@@ -672,7 +669,7 @@ __device__ __forceinline__ void flow_steps(const DraftParams &p, char *smem) {
                     // only deepens the queues, and the compute dies then share the bandwidth unevenly (output head: the
                     // odd-numbered dies finished 6 us after the even ones with two chunks in flight).  The other slots
                     // earn their keep at the ends of a phase, where the requests run ahead into the next one.
-                    if (throttle && L.id == ph) asm volatile("s_waitcnt vmcnt(" MTP_THR ")" ::: "memory");
+                    if (throttle && L.id == ph) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
                     flow_issue(L, ring[s], lane);
                     row_end(n0 + s);
                 }
