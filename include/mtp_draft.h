@@ -268,7 +268,11 @@ float mtp_last_draft_ms(mtp_handle *h);
  *               MTP_ERR_TIMEOUT.  Every other call: as mode 0.
  *   3           as mode 0, with the row-streaming kernels for up to four sequences (slower from the second
  *               sequence on; the form the library itself falls back to for matrices of 2 GiB or more).
- * Other values return MTP_ERR_MODE.  Results agree between the modes to rounding (one sequence: bit for bit between
+ * Other values return MTP_ERR_MODE.  HIP-graph capture: mtp_draft_steps, mtp_draft_steps_lists, mtp_draft_extend,
+ * mtp_draft_continue and mtp_accept only enqueue kernels (no memset or copy nodes except mtp_draft_continue's one
+ * device-to-device copy, no synchronisation, no allocation) and may be captured on a non-default stream with timing
+ * off; a captured call always takes one launch per phase (the single-launch kernel's tags count calls on the host,
+ * which replays do not).  Results agree between the modes to rounding (one sequence: bit for bit between
  * modes 0 and 3; the single-launch kernel adds the two halves of the projection separately).
  */
 int32_t mtp_set_launch_mode(mtp_handle *h, int32_t mode);

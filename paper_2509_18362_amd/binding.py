@@ -265,7 +265,7 @@ class DraftEngine:
     """
 
     def __init__(self, shape, weights_bits: Dict[str, object], subsets: Sequence[object], max_batch: int,
-                 kv_capacity: int, max_draft_steps: int, device: str = "cuda:0"):
+                 kv_capacity: int, max_draft_steps: int, device: str = "cuda:0", guard_bytes: int = 0):
         import numpy as np
         import torch
         self.torch = torch
@@ -280,11 +280,19 @@ class DraftEngine:
         nbytes = mtp_workspace_bytes(self.cfg)
         if nbytes == 0:
             raise MTPError(-3)
-        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        # guard_bytes (a multiple of 256): that many bytes of a fixed pattern in front of and behind the workspace, for
+        # tests that check that nothing is written outside it (guards_intact)
+        self.guard_bytes = guard_bytes
+        self._arena = torch.full((nbytes + 2 * guard_bytes,), 0xA5, dtype=torch.uint8, device=self.device)
+        self.workspace = self._arena[guard_bytes:guard_bytes + nbytes]
         st, self.handle = mtp_draft_init(self.cfg, self.w, self.subsets, [s.numel() for s in self.subsets],
                                          self.workspace, nbytes)
         if st != MTP_OK:
             raise MTPError(st)
+
+    def guards_intact(self) -> bool:
+        g = self.guard_bytes
+        return g == 0 or bool((self._arena[:g] == 0xA5).all().item() and (self._arena[-g:] == 0xA5).all().item())
 
     def subset_size(self, subset_index: int) -> int:
         return self.shape.vocab_size if subset_index < 0 else self.subsets[subset_index].numel()

@@ -780,8 +780,20 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
     // consecutive launches (measured: 464 us kernels every 485 us) where an ordinary launch leaves 5; on a device that
     // another kernel occupies at that moment the waits are bounded (MTP_ERR_TIMEOUT).  Mode 2 picks it where it
     // applies; more sequences, and shapes it does not serve, take one launch per phase in every mode.
+    // Its tags count calls on the host, so a call that is being captured into a HIP graph - whose replays would all
+    // carry the tags of the captured call - takes one launch per phase instead (those kernels keep no state across
+    // calls on the host).
     const bool rows = B == 1 && p.d >= 512 && p.qd >= 512 && p.F >= 512;
-    if ((h->mode == 1 || h->mode == 2) && rows && tphase < 0 && !ext && !seq_subset) {
+    bool capturing = false;
+    if (st != nullptr) { // (the legacy default stream cannot be captured, and asking about it disturbs other captures)
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(st, &cap) != hipSuccess) {
+            (void)hipGetLastError();
+            return MTP_ERR_HIP;
+        }
+        capturing = cap != hipStreamCaptureStatusNone;
+    }
+    if ((h->mode == 1 || h->mode == 2) && rows && tphase < 0 && !ext && !seq_subset && !capturing) {
         const int fgrid = std::min(h->num_cus, kMaxFusedGrid);
         size_t region = std::max(flow_gemv_region(p.d, p.qd, p.F), lds_attn);
         region = (region + 255) / 256 * 256;
@@ -808,7 +820,6 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
                 hipLaunchKernelGGL(k_zero_words, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st,
                                    reinterpret_cast<unsigned long long *>(ws + l.xt), (int)words);
                 h->flow_tags = 0;
-    h->flow_lds_ok = 0;
             }
             p.tag_base = (unsigned)h->flow_tags;
             void *args[] = {(void *)&p};

@@ -1133,3 +1133,140 @@ def test_7b_drafting_loop_with_poisoned_dead_slots(gpu, big):
     worst, _ = drafting_loop(gpu, wl, big["w"], big["dev"], act, synth.make_subsets(wl), 3, 4, 903,
                              accept_prob=0.8)
     print("c2 loop: largest logit gap", worst)
+
+
+# ------------------------------------------------------------------------------ workspace guards, HIP-graph capture
+def exercise_every_entry_point(gpu, eng, wl, act, K, tiny_ids=None):
+    """One call of every draft entry point on `eng` (results are checked elsewhere)."""
+    torch, binding = gpu["torch"], gpu["binding"]
+    B = len(act["kv_len"])
+    hid, tok = eng.to_device_bits(act["hidden_in"]), eng.to_device_i32(act["token_in"])
+    kc, vc = eng.to_device_bits(act["k_cache"]), eng.to_device_bits(act["v_cache"])
+    for mode in (0, 1, 2, 3):
+        if mode == 3 and B > 4:
+            continue
+        assert binding.mtp_set_launch_mode(eng.handle, mode) == 0
+        kv = eng.to_device_i32(act["kv_len"])
+        o = eng.draft(K, 0, hid, tok, kc, vc, kv, want_logits=True, want_hidden=True)
+        tgt = synth.make_targets(wl, o["draft"].cpu().numpy(), accept_prob=0.7)
+        eng.accept(o["draft"], eng.to_device_i32(tgt), kv, 0)
+    assert binding.mtp_set_launch_mode(eng.handle, 2) == 0
+    kv = eng.to_device_i32(act["kv_len"])
+    eng.draft_lists(K, [0] * B, hid, tok, kc, vc, kv)
+    hid2, tok2 = extend_inputs(wl.shape, act, 2, seed=5)
+    kv = eng.to_device_i32(act["kv_len"])
+    ex = eng.extend(0, eng.to_device_bits(hid2), eng.to_device_i32(tok2), eng.to_device_i32(np.full(B, 2, np.int32)),
+                    kc, vc, kv, want_hidden=True)
+    own = ex["hidden"][1].contiguous()
+    eng.draft_continue(K - 1, 0, own.clone(), ex["draft"][1].clone(), kc, vc, kv)
+    torch.cuda.synchronize()
+    assert eng.poll_error() == 0
+
+
+@pytest.mark.parametrize("B", [1, 3, 20])
+def test_tiny_nothing_is_written_outside_the_workspace(gpu, tiny, B):
+    """The workspace sits between two guard areas of a fixed byte pattern; after every entry point has run in every
+    launch mode both are unchanged."""
+    binding = gpu["binding"]
+    wl, K = tiny["wl"], 3
+    ctx = (np.arange(B, dtype=np.int32) * 37) % 150 + 1
+    act = synth.make_activations(wl, ctx=ctx, capacity=192)
+    eng = binding.DraftEngine(tiny["shape"], tiny["w"], [tiny["ids"]], 2 * B, 192, K, guard_bytes=1 << 16)
+    assert eng.guards_intact()
+    exercise_every_entry_point(gpu, eng, wl, act, K)
+    assert eng.guards_intact()
+    eng.close()
+
+
+def test_7b_nothing_is_written_outside_the_workspace(gpu, big):
+    binding = gpu["binding"]
+    wl = synth.WORKLOADS["c2_7b_b1"]
+    act = synth.make_activations(wl)
+    eng = binding.DraftEngine(big["shape"], big["dev"], synth.make_subsets(wl), 2, act["kv_capacity"], wl.draft_steps,
+                              guard_bytes=1 << 20)
+    exercise_every_entry_point(gpu, eng, wl, act, wl.draft_steps)
+    assert eng.guards_intact()
+    eng.close()
+
+
+def graph_replays_match_eager(gpu, wl, eng, act, K):
+    """mtp_draft_steps + mtp_accept captured into a HIP graph on a stream of default priority and replayed four times,
+    with eager work of the same engine and synchronisations between the replays: every replay must give what the eager
+    calls (one launch per phase, the form a captured call takes) give on the same inputs: drafts, logits, the appended
+    cache entries, accept results, bit for bit."""
+    torch, binding = gpu["torch"], gpu["binding"]
+    B = len(act["kv_len"])
+    hid, tok = eng.to_device_bits(act["hidden_in"]), eng.to_device_i32(act["token_in"])
+    kc0, vc0 = eng.to_device_bits(act["k_cache"]), eng.to_device_bits(act["v_cache"])
+    kv0 = eng.to_device_i32(act["kv_len"])
+
+    def fresh():
+        return kc0.clone(), vc0.clone(), kv0.clone()
+
+    # eager reference
+    assert binding.mtp_set_launch_mode(eng.handle, binding.LAUNCH_PER_PHASE) == 0
+    kc, vc, kv = fresh()
+    o = eng.draft(K, 0, hid, tok, kc, vc, kv, want_logits=True)
+    torch.cuda.synchronize()
+    tgt = eng.to_device_i32(synth.make_targets(wl, o["draft"].cpu().numpy(), accept_prob=0.7))
+    a = eng.accept(o["draft"], tgt, kv, 0)
+    torch.cuda.synchronize()
+    want = [o["draft"].cpu().numpy(), o["logits"].cpu().numpy(), kc.cpu().numpy(), vc.cpu().numpy(),
+            kv.cpu().numpy()] + [a[k].cpu().numpy() for k in ("accept_len", "out_tokens", "pending")]
+    assert binding.mtp_set_launch_mode(eng.handle, binding.LAUNCH_AUTO) == 0  # the default, as a caller would capture it
+
+    # static buffers of the graph
+    gkc, gvc, gkv = fresh()
+    n = eng.subset_size(0)
+    draft = torch.empty((B, K), dtype=torch.int32, device="cuda:0")
+    logits = torch.empty((B, K, n), dtype=torch.float32, device="cuda:0")
+    acc = torch.empty(B, dtype=torch.int32, device="cuda:0")
+    out = torch.empty((B, K + 1), dtype=torch.int32, device="cuda:0")
+    pend = torch.empty(B, dtype=torch.int32, device="cuda:0")
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()  # default priority
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        st = torch.cuda.current_stream().cuda_stream
+        assert binding.mtp_draft_steps(eng.handle, B, K, 0, hid, tok, gkc, gvc, gkv, None, draft, logits, None, st) == 0
+        assert binding.mtp_accept(eng.handle, B, K, draft, tgt, 0, gkv, acc, out, pend, st) == 0
+    for replay in range(4):
+        k2, v2, l2 = fresh()
+        gkc.copy_(k2)
+        gvc.copy_(v2)
+        gkv.copy_(l2)
+        draft.fill_(-7)
+        logits.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [draft.cpu().numpy(), logits.cpu().numpy(), gkc.cpu().numpy(), gvc.cpu().numpy(), gkv.cpu().numpy(),
+               acc.cpu().numpy(), out.cpu().numpy(), pend.cpu().numpy()]
+        for g, w_ in zip(got, want):
+            np.testing.assert_array_equal(g, w_, err_msg=f"replay {replay}")
+        # eager work of the same engine between the replays (other inputs, the engine's default launch mode)
+        kc, vc, kv = fresh()
+        eng.draft(K, 0, hid, torch.roll(tok, 1), kc, vc, kv)
+        torch.cuda.synchronize()
+    assert eng.poll_error() == 0
+
+
+@pytest.mark.parametrize("B", [1, 5])
+def test_tiny_calls_captured_into_a_hip_graph(gpu, tiny, B):
+    binding = gpu["binding"]
+    wl, K = tiny["wl"], 3
+    ctx = (np.arange(B, dtype=np.int32) * 41) % 120 + 3
+    act = synth.make_activations(wl, ctx=ctx, capacity=192)
+    eng = binding.DraftEngine(tiny["shape"], tiny["w"], [tiny["ids"]], B, 192, K)
+    graph_replays_match_eager(gpu, wl, eng, act, K)
+    eng.close()
+
+
+def test_7b_call_captured_into_a_hip_graph(gpu, big):
+    """One sequence at the 7B shape: eager calls take the single-launch kernel, whose tags count calls on the host; a
+    captured call must not (its replays would all carry the captured call's tags)."""
+    binding = gpu["binding"]
+    wl = synth.WORKLOADS["c2_7b_b1"]
+    act = synth.make_activations(wl)
+    eng = binding.DraftEngine(big["shape"], big["dev"], synth.make_subsets(wl), 1, act["kv_capacity"], wl.draft_steps)
+    graph_replays_match_eager(gpu, wl, eng, act, wl.draft_steps)
+    eng.close()
