@@ -305,7 +305,8 @@ int32_t mtp_set_phase_trace(mtp_handle *h, void *device_buffer);
  *   tokens       device [n_tokens] int32     ids; values outside [0, vocab_size) are skipped and counted (may be
  *                                            NULL when n_tokens is 0)
  *   n_tokens     0 .. 2^31 - 1;  n: 0 .. vocab_size (else MTP_ERR_CONFIG)
- *   workspace    device, mtp_subset_workspace_bytes(vocab_size) bytes, owned by the caller; holds the counts
+ *   workspace    device, mtp_subset_workspace_bytes(vocab_size) bytes, owned by the caller; holds the counts, the
+ *                selection state and one 160 KB copy of the counting kernel's bins per workgroup (41 MB in all)
  *   ids_out      device [n] int32            the list, ascending
  *   counts_out   device [vocab_size] int32 or NULL;  invalid_out device [1] int32 or NULL (skipped ids)
  * All device pointers 16-byte aligned.
@@ -319,9 +320,11 @@ int32_t mtp_subset_build(const int32_t *tokens, int64_t n_tokens, int32_t vocab_
  * mtp_subset_build for callers that cannot allocate device memory and have no workspace to hand over (code under
  * HIP-graph capture, tight serving loops, harnesses that forbid hipMalloc): the counts and the selection state live in
  * an array built into the library's device image instead of a caller's workspace.  Same arguments (minus the
- * workspace), same kernels, same results.  Calls no hipMalloc/hipFree and no allocating routine.
- *   vocab_size   at most mtp_subset_static_max_vocab() (262144 ids: the array is 1 MiB + 4.6 KB per GPU, held until
+ * workspace), same results.  Calls no hipMalloc/hipFree and no allocating routine.
+ *   vocab_size   at most mtp_subset_static_max_vocab() (262144 ids: the array is 1 MiB + 26 KB per GPU, held until
  *                the process ends); larger vocabularies return MTP_ERR_WORKSPACE with a message on stderr
+ * The array has no room for the per-workgroup copies of the bins, so the counting kernel adds its bins to the counts
+ * with atomics instead: about twice the time of mtp_subset_build on a stream of 2^26 tokens.
  * Every call on a GPU uses that GPU's one array (its contents are cleared at the start of each call): calls that
  * overlap on one GPU - different streams, or graphs replayed concurrently - race and must be serialised by the
  * caller.  The first call on a device looks the array's address up (a host-side query, no allocation).
