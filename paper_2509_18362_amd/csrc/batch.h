@@ -81,7 +81,15 @@ __device__ __forceinline__ void batch_scales(const DraftParams &p, int kind, flo
     float s = 0.f;
     if (bl < p.nb) {
         const float *src = p.ssq + ((size_t)kind * p.max_batch + p.b0 + bl) * npart;
-        for (int i = sub; i < npart; i += 8) s += src[i];
+        // sixteen loads in flight at a time (one at a time, each behind the weight requests of its wave, this sum was
+        // the longest chain of the kernel: 20 us in the two waves that hold sixteen sequences)
+        for (int i0 = sub; i0 < npart; i0 += 8 * 16) {
+            float t[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) t[u] = i0 + 8 * u < npart ? src[i0 + 8 * u] : 0.f;
+#pragma unroll
+            for (int u = 0; u < 16; ++u) s += t[u];
+        }
     }
     s = oct_sum(s);
     if (sub == 0 && bl < kBatchMaxSeq) scale_lds[bl] = bl < p.nb ? 1.0f / sqrtf(s / (float)p.d + p.eps) : 0.f;
@@ -261,12 +269,14 @@ __device__ __forceinline__ void bgemv(const DraftParams &p, Ph &ph, int RG, int 
     for (int a = 0; a < kBatchAcc; ++a) acc[a] = f32x4{0.f, 0.f, 0.f, 0.f};
     char *strip0 = strips + (size_t)wave * 2 * kStripBytes, *strip1 = strip0 + kStripBytes;
     float *part = p.part;
+    // The norm scales for the epilogue (visible after the first group's barrier): BEFORE the weight requests.  Loads of a
+    // wave return in order, so behind forty weight loads per wave these few values arrived a trip through the busy
+    // memory system later each.
+    if (Ph::SCALE >= 0 && !p.bg_sep[Ph::WHICH]) batch_scales(p, Ph::SCALE, scale_lds);
     for (int grp = 0; grp < ngroups; ++grp) {
         setup_group(grp);
 #pragma unroll
         for (int s = 0; s < D; ++s) issue(ring[s], s);
-        // with the first loads under way: the norm scales for the epilogue (visible after the group's barrier)
-        if (Ph::SCALE >= 0 && grp == 0 && !p.bg_sep[Ph::WHICH]) batch_scales(p, Ph::SCALE, scale_lds);
         for (int n0 = 0; n0 < per; n0 += D) {
 #pragma unroll
             for (int s = 0; s < D; ++s) {
@@ -444,12 +454,12 @@ __device__ __forceinline__ void bgemv_lds(const DraftParams &p, Ph &ph, int RG, 
     for (int a = 0; a < kBatchAcc; ++a) acc[a] = f32x4{0.f, 0.f, 0.f, 0.f};
     char *strip0 = strips + (size_t)wave * 2 * kStripBytes, *strip1 = strip0 + kStripBytes;
     float *part = p.part;
+    // (before the weight requests, see bgemv; visible after the first step's barrier)
+    if (Ph::SCALE >= 0 && !p.bg_sep[Ph::WHICH]) batch_scales(p, Ph::SCALE, scale_lds);
     for (int blk = 0; blk < nblocks; ++blk) {
         setup_block(blk);
 #pragma unroll
         for (int s = 0; s < D; ++s) issue(ring[s], s);
-        if (Ph::SCALE >= 0 && blk == 0 && !p.bg_sep[Ph::WHICH])
-            batch_scales(p, Ph::SCALE, scale_lds); // visible after the first step's barrier
         for (int n0 = 0; n0 < steps; n0 += D) {
 #pragma unroll
             for (int s = 0; s < D; ++s) {
