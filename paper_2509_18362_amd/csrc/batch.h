@@ -275,12 +275,16 @@ __device__ __forceinline__ void bgemv(const DraftParams &p, Ph &ph, int RG, int 
     if (Ph::SCALE >= 0 && !p.bg_sep[Ph::WHICH]) batch_scales(p, Ph::SCALE, scale_lds);
     for (int grp = 0; grp < ngroups; ++grp) {
         setup_group(grp);
-#pragma unroll
-        for (int s = 0; s < D; ++s) issue(ring[s], s);
+        // One item ahead: the request for item i + 1 goes out when item i is about to be multiplied.  (Two items ahead -
+        // both slots requested at the start, each refilled as it is used up - put 80 MiB of requests into the memory
+        // system at once over the chip; the waves that came last then got their first data 20 us into the kernel and
+        // every workgroup waited for them at its barrier.)
+        issue(ring[0], 0);
         for (int n0 = 0; n0 < per; n0 += D) {
 #pragma unroll
             for (int s = 0; s < D; ++s) {
                 const int idx = n0 + s;
+                issue(ring[(s + 1) % D], idx + 1);
                 const int ksn = ksA + idx * kWaves + wave;
                 const int ks = min(ksn, nks - 1);
                 const int koff = min(ks * 64, K - 64);
@@ -319,7 +323,6 @@ __device__ __forceinline__ void bgemv(const DraftParams &p, Ph &ph, int RG, int 
                         acc[ts * NA + at] = a;
                     }
                 }
-                issue(ring[s], idx + D);
             }
         }
         // group complete: meet the other waves in LDS, hand the sums to the partial buffer
@@ -458,12 +461,12 @@ __device__ __forceinline__ void bgemv_lds(const DraftParams &p, Ph &ph, int RG, 
     if (Ph::SCALE >= 0 && !p.bg_sep[Ph::WHICH]) batch_scales(p, Ph::SCALE, scale_lds);
     for (int blk = 0; blk < nblocks; ++blk) {
         setup_block(blk);
-#pragma unroll
-        for (int s = 0; s < D; ++s) issue(ring[s], s);
+        issue(ring[0], 0); // one step ahead, as in bgemv
         for (int n0 = 0; n0 < steps; n0 += D) {
 #pragma unroll
             for (int s = 0; s < D; ++s) {
                 const int idx = n0 + s;
+                issue(ring[(s + 1) % D], idx + 1);
                 const int ksn = ksA + idx;
                 const int ks = min(ksn, nks - 1);
                 const int koff = min(ks * 64, K - 64);
@@ -504,7 +507,6 @@ __device__ __forceinline__ void bgemv_lds(const DraftParams &p, Ph &ph, int RG, 
                         for (int at = 0; at < NA; ++at) acc[tw * NA + at] = mfma16(al[at][hf], w[hf], acc[tw * NA + at]);
                     }
                 }
-                issue(ring[s], idx + D);
             }
         }
         // block complete: this wave's sums go to the partial buffer
