@@ -146,14 +146,15 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
             for (int tl = 0; tl < 2; ++tl)
 #pragma unroll
                 for (int u = 0; u < NS; ++u) {
-                    const int tok = min(it * 32 + tl * 16 + u * TPI + lane / LPT, ntok - 1); // past the end: the last row again
+                    // past the end: the last row again (an empty range: the first slot, which is inside the cache)
+                    const int tok = max(min(it * 32 + tl * 16 + u * TPI + lane / LPT, ntok - 1), 0);
                     kn[tl][u] = ldg16(kc + (size_t)tok * HD + (lane % LPT) * 8);
                 }
         };
         auto load_v = [&](int it) {
 #pragma unroll
             for (int u = 0; u < NV; ++u) {
-                const int tok = min(it * 32 + u * TPI + lane / LPT, ntok - 1);
+                const int tok = max(min(it * 32 + u * TPI + lane / LPT, ntok - 1), 0);
                 vr[u] = ldg16(vc + (size_t)tok * HD + (lane % LPT) * 8);
             }
         };
@@ -161,7 +162,12 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
             load_k(it);
             load_v(it);
         };
-        if (wave < niter) load_iter(wave); // in flight while q, the rotary table and the new key/value are prepared
+        // in flight while q, the rotary table and the new key/value are prepared.  None of the requests of this kernel
+        // sits behind a branch: a request past the wave's last iteration reads the range's last row again (every lane
+        // the same row: next to no traffic).  Behind a branch the compiler cannot count the loads in flight and waits
+        // for ALL of them wherever it waits for any: the wait for V then also waited for the keys of the next
+        // iteration, requested a moment before, and an iteration lasted a whole trip to memory.
+        load_iter(wave);
         if (first_item) {
             before_q();
             first_item = false;
@@ -280,10 +286,8 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                 __builtin_amdgcn_wave_barrier();
             }
-            if (it + kWaves < niter) {
-                load_k(it + kWaves);
-                if constexpr (!L::VREG) load_v(it + kWaves);
-            }
+            load_k(it + kWaves);
+            if constexpr (!L::VREG) load_v(it + kWaves);
 
             // scores of 2 x 16 tokens against the G heads
             f32x4 sc[2];
@@ -347,7 +351,7 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
                     o = mfma16(va, pL, o);
                     oacc[db] = o;
                 }
-                if (it + kWaves < niter) load_v(it + kWaves); // the registers are free again
+                load_v(it + kWaves); // the registers are free again
             } else {
             // the parked rows were written by this wave's own lanes; LDS operations of a wave complete in order
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
