@@ -659,6 +659,7 @@ __device__ __forceinline__ void flow_steps(const DraftParams &p, char *smem) {
             // Chunks n0 and n0 + 1 sit in the register slots; the phase's third chunk sits in the LDS slot and is taken
             // after the first two.  Every register slot is refilled as soon as it is free; the LDS slot is refilled once,
             // at the end of the phase, with the third chunk of the phase that follows.
+            int pend = 0; // register slots whose refill waits for the end of the phase
             for (int n0 = 0; n0 < g.nchunks; n0 += (n0 == 0 ? 3 : 2)) {
 #pragma unroll
                 for (int s = 0; s < 2; ++s) {
@@ -669,9 +670,18 @@ __device__ __forceinline__ void flow_steps(const DraftParams &p, char *smem) {
                     // only deepens the queues, and the compute dies then share the bandwidth unevenly (output head: the
                     // odd-numbered dies finished 6 us after the even ones with two chunks in flight).  The other slots
                     // earn their keep at the ends of a phase, where the requests run ahead into the next one.
-                    if (throttle && L.id == ph) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                    flow_issue(L, ring[s], lane);
-                    row_end(n0 + s);
+                    // The phase's last chunks (the cursor has moved on to the phase that follows): the row's result goes
+                    // out first, and the slot's next request waits until the wave has published all its results.  A
+                    // request can wait a microsecond for room in the memory queues, and other workgroups poll for
+                    // these results.
+                    if (L.id != ph) {
+                        row_end(n0 + s);
+                        pend |= 1 << s;
+                    } else {
+                        if (throttle) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                        flow_issue(L, ring[s], lane);
+                        row_end(n0 + s);
+                    }
                 }
                 if (n0 == 0) {
                     flow_wait_lds_slot();
@@ -679,6 +689,8 @@ __device__ __forceinline__ void flow_steps(const DraftParams &p, char *smem) {
                     row_end(2);
                 }
             }
+            if (pend & 1) flow_issue(L, ring[0], lane);
+            if (pend & 2) flow_issue(L, ring[1], lane);
             if (next != FL_NONE) { // (no next phase: nothing is written into LDS that the attention may be using)
                 advance_cursor();
                 flow_issue_lds(L, slot, lane);
