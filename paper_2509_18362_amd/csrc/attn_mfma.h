@@ -23,8 +23,8 @@
 //                 strip (row stride HD*2 + 16 bytes, which spreads the four lane groups over different banks) and
 //                 gathers eight 16-bit values per lane and block.
 // Loads of the next iteration (16 KiB per wave) are in flight while the current one is computed.
-// Items (sequence, KV head, split) are numbered split-major and, when there are more of them than workgroups, handed
-// out through a counter.  For a block of new positions whose keys and values are already in the cache, 16 / G
+// Items (sequence, KV head, split) are numbered split-major; when there are more of them than workgroups they are
+// handed out through a counter and (one position per sequence) numbered longest first.  For a block of new positions whose keys and values are already in the cache, 16 / G
 // positions of a sequence sit beside the G query heads in the columns and share every key/value read.
 #pragma once
 #include "phases.h"
@@ -59,7 +59,9 @@ struct AttnMfmaLds {
 // JP > 1 (needs p.kv_appended and TICKET): an item is (sequence, KV head, split, group of JP positions); position j of
 // sequence b is row j * p.ext_B + b of the call and sees the cache up to its own slot, so the columns of an item differ
 // only in where their tokens end.
-template <int G, int HD, bool COH = false, bool TICKET = false, class Hook = NoHook, bool QUEUE = false, int JP = 1>
+// MAP (needs QUEUE with a counter, JP == 1): the items are numbered longest first (below).
+template <int G, int HD, bool COH = false, bool TICKET = false, class Hook = NoHook, bool QUEUE = false, int JP = 1,
+          bool MAP = false>
 __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb, char *smem, Hook before_q = Hook()) {
     using L = AttnMfmaLds<G, HD, JP>;
     constexpr int NC = L::NC;
@@ -78,11 +80,52 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
     const int nseq = JP > 1 ? p.ext_B : p.B;             // sequences whose caches are read
     const int mpos = JP > 1 ? p.B / p.ext_B : 1;         // positions per sequence
     const int JG = (mpos + JP - 1) / JP;                 // groups of positions
-    const int n_items = nseq * p.Hkv * S * JG;
+    int n_items = nseq * p.Hkv * S * JG;
     const float scale = 1.0f / sqrtf((float)HD);
     const int PW = HD + 2; // floats per (head, split) partial: acc[HD], max, sum
 
     int &drawn = *reinterpret_cast<int *>(smem + sizeof(L) + 4); // the number thread 0 drew, for the workgroup
+    const bool queue = QUEUE && p.attn_queue != nullptr; // uniform
+    // One position per sequence, more items than workgroups: the items are numbered longest first - every full split (T tokens) of every sequence,
+    // split by split, then the sequences' ragged final splits by decreasing length - and only splits that exist get a
+    // number.  Handed out in that order the workgroups end within a short item of one another; numbered (sequence, KV
+    // head, split) over the longest possible context, a long context's last full splits were drawn last and the
+    // launch waited 100 us for them (and every number without a split cost a trip to the counter).
+    // The map (behind the flags, attn_map_bytes): every workgroup derives it from the lengths, identically.  (With an
+    // item per workgroup at most the launch takes the kernel without the map: nothing to balance, and the map would
+    // delay the first loads.)
+    int *len_l = reinterpret_cast<int *>(smem + sizeof(L) + 64); // [nseq] tokens seen
+    int *ord = len_l + nseq;                                     // [nseq] sequences by decreasing length
+    int *ord_r = ord + nseq;                                     // [nseq] sequences by decreasing ragged length
+    int *pre = ord_r + nseq;                                     // [S + 1] full splits with index < sp, all sequences
+    int n_full = 0;                                              // full splits of all sequences
+    static_assert(!MAP || (JP == 1 && QUEUE), "the item map serves one position per sequence, handed out by the counter");
+    constexpr bool mapped = MAP;
+    if constexpr (mapped) {
+        for (int t = tid; t < nseq; t += kBlock) len_l[t] = (seq_dead(p, t) ? 0 : p.kv_len[t]) + step + 1;
+        __syncthreads();
+        for (int t = tid; t < nseq; t += kBlock) {
+            const int lt = len_l[t], rt = lt % T;
+            int rank = 0, rank_r = 0;
+            for (int u = 0; u < nseq; ++u) {
+                const int lu = len_l[u], ru = lu % T;
+                rank += (lu > lt || (lu == lt && u < t)) ? 1 : 0;
+                rank_r += (ru > rt || (ru == rt && u < t)) ? 1 : 0;
+            }
+            ord[rank] = t;
+            ord_r[rank_r] = t;
+        }
+        for (int sp = tid; sp <= S; sp += kBlock) {
+            int n = 0;
+            for (int u = 0; u < nseq; ++u) n += min(len_l[u] / T, sp);
+            pre[sp] = n;
+        }
+        __syncthreads();
+        n_full = pre[S];
+        int n_ragged = 0;
+        for (int u = 0; u < nseq; ++u) n_ragged += (len_l[u] % T) != 0 ? 1 : 0;
+        n_items = (n_full + n_ragged) * p.Hkv;
+    }
     // items 0 .. nvb-1 are the workgroups' first ones, the counter hands out those from nvb on
     auto draw = [&]() { return nvb + __hip_atomic_fetch_add(p.attn_queue, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
     int item = vb, next_item = 0, pending = 0; // pending: thread 0's next number, asked for at the start of an item
@@ -93,7 +136,6 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
         __syncthreads(); // read by all before thread 0 writes the next one
         return v;
     };
-    const bool queue = QUEUE && p.attn_queue != nullptr; // uniform
     bool first_item = true;
     for (;; item = next_item) {
         if (queue) {
@@ -105,8 +147,22 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
         }
         // split-major numbering: the splits of one (sequence, KV head) land on workgroups of different XCDs, and with
         // the counter the short final splits are drawn last
-        const int kvh = item % p.Hkv, b = item / p.Hkv % nseq, jg = item / (p.Hkv * nseq) % JG,
-                  sp = item / (p.Hkv * nseq * JG);
+        int kvh = item % p.Hkv, b = item / p.Hkv % nseq, jg = item / (p.Hkv * nseq) % JG, sp = item / (p.Hkv * nseq * JG);
+        if constexpr (mapped) {
+            const int m = item / p.Hkv;
+            if (m < n_full) { // the m-th full split: the sequences that have split sp lead the order by length
+                sp = 0;
+                while (pre[sp + 1] <= m) ++sp;
+                b = ord[m - pre[sp]];
+            } else {
+                b = ord_r[m - n_full];
+                sp = len_l[b] / T;
+            }
+            // (read from LDS: said explicitly to be the same in every lane, so that what is derived from them - the
+            // cache pointers, the loop bounds - stays in scalar registers)
+            b = __builtin_amdgcn_readfirstlane(b);
+            sp = __builtin_amdgcn_readfirstlane(sp);
+        }
         bool dead;
         int len = 0;      // tokens the longest position of the item sees
         int lenj[JP];     // per position (0: not part of the block)

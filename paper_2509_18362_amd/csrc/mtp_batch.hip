@@ -105,6 +105,13 @@ __global__ __launch_bounds__(kBlock) void k_attn_mfma(DraftParams p, int step) {
     phase_attn_mfma<G, HD, false, true, NoHook, true>(p, step, blockIdx.x, gridDim.x, smem);
 }
 
+// the same with the items numbered longest first, for launches with more items than workgroups
+template <int G, int HD>
+__global__ __launch_bounds__(kBlock) void k_attn_mfma_lpt(DraftParams p, int step) {
+    extern __shared__ __align__(16) char smem[];
+    phase_attn_mfma<G, HD, false, true, NoHook, true, 1, true>(p, step, blockIdx.x, gridDim.x, smem);
+}
+
 // a block of new positions per sequence (keys and values already in the cache): the positions of a sequence share its
 // key/value reads, 16 / G of them beside the G query heads in the MFMA columns
 template <int G, int HD>
@@ -132,20 +139,21 @@ bg_kernel_t attn_mfma_block_kernel(int G, int HD) {
     }
     return nullptr;
 }
-bg_kernel_t attn_mfma_kernel(int G, int HD) {
+// lpt: the launch hands its items out through the counter (more items than workgroups)
+bg_kernel_t attn_mfma_kernel(int G, int HD, bool lpt) {
     if (HD == 128) {
         switch (G) {
-        case 1: return k_attn_mfma<1, 128>;
-        case 2: return k_attn_mfma<2, 128>;
-        case 4: return k_attn_mfma<4, 128>;
-        case 8: return k_attn_mfma<8, 128>;
+        case 1: return lpt ? k_attn_mfma_lpt<1, 128> : k_attn_mfma<1, 128>;
+        case 2: return lpt ? k_attn_mfma_lpt<2, 128> : k_attn_mfma<2, 128>;
+        case 4: return lpt ? k_attn_mfma_lpt<4, 128> : k_attn_mfma<4, 128>;
+        case 8: return lpt ? k_attn_mfma_lpt<8, 128> : k_attn_mfma<8, 128>;
         }
     } else if (HD == 64) {
         switch (G) {
-        case 1: return k_attn_mfma<1, 64>;
-        case 2: return k_attn_mfma<2, 64>;
-        case 4: return k_attn_mfma<4, 64>;
-        case 8: return k_attn_mfma<8, 64>;
+        case 1: return lpt ? k_attn_mfma_lpt<1, 64> : k_attn_mfma<1, 64>;
+        case 2: return lpt ? k_attn_mfma_lpt<2, 64> : k_attn_mfma<2, 64>;
+        case 4: return lpt ? k_attn_mfma_lpt<4, 64> : k_attn_mfma<4, 64>;
+        case 8: return lpt ? k_attn_mfma_lpt<8, 64> : k_attn_mfma<8, 64>;
         }
     }
     return nullptr;
@@ -219,7 +227,7 @@ size_t attn_mfma_block_lds_bytes(int G, int HD) {
 }
 
 void launch_attn_mfma(int G, int HD, const DraftParams &p, int step, int grid, size_t lds, hipStream_t st) {
-    hipLaunchKernelGGL(attn_mfma_kernel(G, HD), dim3(grid), dim3(kBlock), lds, st, p, step);
+    hipLaunchKernelGGL(attn_mfma_kernel(G, HD, p.attn_queue != nullptr), dim3(grid), dim3(kBlock), lds, st, p, step);
 }
 void launch_attn_mfma_block(int G, int HD, const DraftParams &p, int step, int grid, size_t lds, hipStream_t st) {
     hipLaunchKernelGGL(attn_mfma_block_kernel(G, HD), dim3(grid), dim3(kBlock), lds, st, p, step);
@@ -232,8 +240,10 @@ bool batch_allow_lds(size_t lds_limit) {
                        hipSuccess;
     for (int hd = 64; hd <= 128; hd *= 2)
         for (int g = 1; g <= 8; g *= 2)
-            ok = ok && hipFuncSetAttribute((const void *)attn_mfma_kernel(g, hd),
+            ok = ok && hipFuncSetAttribute((const void *)attn_mfma_kernel(g, hd, false),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_limit) == hipSuccess &&
+                 hipFuncSetAttribute((const void *)attn_mfma_kernel(g, hd, true),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_limit) == hipSuccess &&
                  hipFuncSetAttribute((const void *)attn_mfma_block_kernel(g, hd),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_limit) == hipSuccess;
     for (int ph = 0; ph < BG_COUNT; ++ph)

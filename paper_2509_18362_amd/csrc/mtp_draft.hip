@@ -298,6 +298,8 @@ fused_kernel_t flow_kernel(int G, int HD) {
     }
     return nullptr;
 }
+// the matrix-core attention's item map: lengths and two orders of the sequences, full splits below each split index
+size_t attn_map_bytes(int B, int max_splits) { return ((size_t)3 * B + max_splits + 2) * 4; }
 size_t attn_lds_bytes(int G, int HD) {
     int tpi = kWave / (HD / 8), ns = kWaves * tpi;
     size_t fl = (size_t)G * HD + HD + 2 * HD + (size_t)ns * G * HD + (size_t)ns * G * 2;
@@ -755,7 +757,8 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
     const size_t lds_proj = gemv_lds_bytes(2 * p.d, p.nb_proj, 1), lds_d1 = gemv_lds_bytes(p.d, p.nb_d, 1),
                  lds_d2 = gemv_lds_bytes(p.d, p.nb_d, 2), lds_q = gemv_lds_bytes(p.qd, p.nb_q, 1),
                  lds_down = gemv_lds_bytes(p.F, p.nb_down, 1),
-                 lds_attn = std::max({attn_lds_bytes(p.Hq / p.Hkv, p.hd), attn_mfma_lds_bytes(p.Hq / p.Hkv, p.hd) + 64,
+                 lds_attn = std::max({attn_lds_bytes(p.Hq / p.Hkv, p.hd),
+                                      attn_mfma_lds_bytes(p.Hq / p.Hkv, p.hd) + 64 + attn_map_bytes(att_B, p.max_splits),
                                       (size_t)kWaves * p.max_splits * 4 + 64}); // incl. the merge's strips
     // the matrix-core attention over a block of positions (sixteen query columns)
     const size_t lds_attn_block = std::max(attn_mfma_block_lds_bytes(p.Hq / p.Hkv, p.hd) + 64,
@@ -767,7 +770,11 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
                                                           // leaves no room for a second
     p.head_grid = grid;
     const int attn_items = att_B * p.Hkv * p.max_splits;
-    const int attn_grid = std::max(1, std::min(attn_items, h->num_cus * 2));
+    // splits of at least kMfmaAttnMinSplit tokens: the matrix-core attention (below); one of its workgroups fills a
+    // compute unit, and a workgroup that starts only when another has left would take its first item, a whole split
+    // of the first sequences, at the very end
+    const bool mfma_attn = p.split_tokens >= (ext && ext->m_max > 1 ? 2 * kMfmaAttnMinSplit : kMfmaAttnMinSplit);
+    const int attn_grid = std::max(1, std::min(attn_items, h->num_cus * (mfma_attn ? 1 : 2)));
     // more items than workgroups: the matrix-core attention hands them out one by one (contexts differ in length)
     if (attn_items <= attn_grid) p.attn_queue = nullptr;
 
@@ -852,7 +859,6 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
     // vector version
     // (a block of positions pays more set-up per item on the matrix cores, sixteen query columns: 320-token splits of a
     // four-position block take 40 us there and 26 us on the vector units)
-    const bool mfma_attn = p.split_tokens >= (ext && ext->m_max > 1 ? 2 * kMfmaAttnMinSplit : kMfmaAttnMinSplit);
     auto launch_attention_of = [&](const DraftParams &pa, int step) {
         if (mfma_attn)
             launch_attn_mfma(pa.Hq / pa.Hkv, pa.hd, pa, step, attn_grid, lds_attn, st);

@@ -140,10 +140,12 @@ def test_tiny_long_capacity_matrix_core_attention(gpu, tiny):
 
 
 def test_tiny_many_long_contexts_items_handed_out(gpu, tiny):
-    """Forty sequences with a capacity of 32768: splits are capped at 4096 tokens, which leaves 640 attention items
-    for 512 workgroups, so the matrix-core attention hands its items out through the counter.  Contexts sit on
-    and around the split boundaries, at zero, and at the last slot that still fits K drafts; the call is made twice
-    on one engine (the counter must be back at zero after the first)."""
+    """Forty sequences with a capacity of 32768: splits are capped at 4096 tokens, which leaves up to 640 attention
+    items for one workgroup per compute unit, so the matrix-core attention numbers the splits that exist longest
+    first and hands them out through the counter.  Contexts sit on and around the split boundaries (a length that is
+    a whole number of splits has no ragged final split, at each of the three steps once), at zero, and at the last
+    slot that still fits K drafts; the call is made twice on one engine (the counter must be back at zero after the
+    first)."""
     wl = tiny["wl"]
     K, cap = 3, 32768
     edge = [0, 1, 4092, 4093, 4094, 4095, 4096, 4097, 8191, 8192, 12000, 20000, 28671, 28672, 30000, cap - K]
