@@ -94,7 +94,9 @@ __device__ void phase_attn_mfma(const DraftParams &p, int step, int vb, int nvb,
     // The map (behind the flags, attn_map_bytes): every workgroup derives it from the lengths, identically.  (With an
     // item per workgroup at most the launch takes the kernel without the map: nothing to balance, and the map would
     // delay the first loads.)
-    int *len_l = reinterpret_cast<int *>(smem + sizeof(L) + 64); // [nseq] tokens seen
+    // (behind the tiles and flags and behind the strips of the merge, which start at the front of the LDS)
+    const size_t map_at = (max(sizeof(L), (size_t)kWaves * S * sizeof(float)) + 64 + 15) / 16 * 16;
+    int *len_l = reinterpret_cast<int *>(smem + map_at); // [nseq] tokens seen
     int *ord = len_l + nseq;                                     // [nseq] sequences by decreasing length
     int *ord_r = ord + nseq;                                     // [nseq] sequences by decreasing ragged length
     int *pre = ord_r + nseq;                                     // [S + 1] full splits with index < sp, all sequences

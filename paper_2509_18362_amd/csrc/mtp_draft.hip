@@ -757,9 +757,10 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
     const size_t lds_proj = gemv_lds_bytes(2 * p.d, p.nb_proj, 1), lds_d1 = gemv_lds_bytes(p.d, p.nb_d, 1),
                  lds_d2 = gemv_lds_bytes(p.d, p.nb_d, 2), lds_q = gemv_lds_bytes(p.qd, p.nb_q, 1),
                  lds_down = gemv_lds_bytes(p.F, p.nb_down, 1),
-                 lds_attn = std::max({attn_lds_bytes(p.Hq / p.Hkv, p.hd),
-                                      attn_mfma_lds_bytes(p.Hq / p.Hkv, p.hd) + 64 + attn_map_bytes(att_B, p.max_splits),
-                                      (size_t)kWaves * p.max_splits * 4 + 64}); // incl. the merge's strips
+                 lds_attn = std::max(attn_lds_bytes(p.Hq / p.Hkv, p.hd),
+                                     // the matrix-core kernel's tiles or the merge's strips, flags, then the item map
+                                     std::max(attn_mfma_lds_bytes(p.Hq / p.Hkv, p.hd), (size_t)kWaves * p.max_splits * 4) +
+                                         64 + 16 + attn_map_bytes(att_B, p.max_splits));
     // the matrix-core attention over a block of positions (sixteen query columns)
     const size_t lds_attn_block = std::max(attn_mfma_block_lds_bytes(p.Hq / p.Hkv, p.hd) + 64,
                                            (size_t)kWaves * p.max_splits * 4 + 64);
