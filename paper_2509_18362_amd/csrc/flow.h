@@ -24,6 +24,10 @@
 
 namespace mtp {
 
+// parts the query heads of a KV head are dealt to in the attention of the single-launch kernel (phase_attn, GS)
+template <int G>
+constexpr int kFlowAttnParts = G >= 2 ? 2 : 1;
+
 // time stamps of every workgroup (mtp_set_phase_trace): [step][section][point][workgroup]
 constexpr int kTraceSections = 8; // projection (embedding half), q/k/v, attention, output projection, gate/up, down,
                                   // output head, projection (hidden-state half)
@@ -718,7 +722,7 @@ __device__ __forceinline__ void flow_steps(const DraftParams &p, char *smem) {
                 flow_barrier(); // the activations' LDS becomes the attention's
                 stamp(step, 2, kTraceReleased);
                 stamp(step, 2, kTraceStaged);
-                call_attn<G, HD, true, true, true>(p, step, vb, nvb, smem);
+                call_attn<G, HD, true, true, true, kFlowAttnParts<G>>(p, step, vb, nvb, smem);
                 stamp(step, 2, kTraceDone);
             }
         }

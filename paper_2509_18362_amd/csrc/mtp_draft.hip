@@ -398,7 +398,8 @@ WsLayout ws_layout(const mtp_config &c) {
     l.cand = take((size_t)c.max_draft_steps * mb * kMaxFusedGrid * 8);
     l.rope_inv = take((size_t)c.head_dim / 2 * 8);
     l.attn_part = take(attn_part_floats(c) * 4);
-    l.attn_ticket = take(mb * (size_t)c.n_kv_heads * 4 + 64); // + the attention launch's item counter
+    // two per (sequence, KV head): the single-launch kernel deals a KV head's query heads to two items
+    l.attn_ticket = take(mb * (size_t)c.n_kv_heads * 4 * 2 + 64); // + the attention launch's item counter
     l.row_len = take(mb * 4);
     l.seq_list = take(mb * 4);
     l.list_ids = take(kMaxListGroups * 8);
@@ -701,7 +702,7 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
     p.rope_inv = reinterpret_cast<const double *>(ws + l.rope_inv);
     p.attn_part = reinterpret_cast<float *>(ws + l.attn_part);
     p.attn_ticket = reinterpret_cast<int *>(ws + l.attn_ticket); // the vector attention merges its own splits
-    p.attn_queue = p.attn_ticket + (size_t)c.max_batch * c.n_kv_heads;
+    p.attn_queue = p.attn_ticket + (size_t)2 * c.max_batch * c.n_kv_heads;
     p.cand = reinterpret_cast<unsigned long long *>(ws + l.cand);
     p.xt = reinterpret_cast<unsigned long long *>(ws + l.xt);
     p.qkvt = reinterpret_cast<unsigned long long *>(ws + l.qkvt);
@@ -820,6 +821,16 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
         if (fits) {
             p.head_grid = fgrid;
             p.fused_gemv_bytes = (int)region;
+            // The attention inside this kernel: its items are (KV head, split, half of the KV head's query heads), as
+            // many as there are workgroups; never shorter splits than the plan the workspace was sized for.
+            const int plan_tokens = p.split_tokens, plan_splits = p.max_splits;
+            {
+                const int parts = p.Hq / p.Hkv >= 2 ? 2 : 1; // kFlowAttnParts
+                const long long want = ((long long)c.kv_capacity * p.Hkv * parts + fgrid - 1) / fgrid;
+                const long long t = std::min<long long>(std::max<long long>(plan_tokens, (want + 7) / 8 * 8), kMaxSplitTokens);
+                p.split_tokens = (int)t;
+                p.max_splits = (int)((c.kv_capacity + t - 1) / t);
+            }
             // tags of this call: tag_base + 1 .. tag_base + 8 K, never 0 and never reused: when the 32-bit counter would
             // wrap, the tagged vectors are cleared and the count starts over
             const unsigned long long need = 8ull * (unsigned long long)K + 8ull;
@@ -845,6 +856,8 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
             (void)hipGetLastError();
             if (h->mode == 1) return MTP_ERR_HIP; // asked for explicitly
             // mode 2: the launch was refused: one launch per phase
+            p.split_tokens = plan_tokens;
+            p.max_splits = plan_splits;
         }
     }
     auto mark_begin = [&](int phase, int step) {
@@ -886,7 +899,7 @@ int32_t run_draft(mtp_handle *h, int32_t B, int32_t K, int32_t subset_index, con
             const int G = pa.Hq / pa.Hkv, jp = 16 / G, jg = (ext->m_max + jp - 1) / jp;
             const int items = ext->B * pa.Hkv * pa.max_splits * jg;
             const int grid_b = std::max(1, std::min(items, h->num_cus * 2));
-            pa.attn_queue = items > grid_b ? pa.attn_ticket + (size_t)c.max_batch * c.n_kv_heads : nullptr;
+            pa.attn_queue = items > grid_b ? pa.attn_ticket + (size_t)2 * c.max_batch * c.n_kv_heads : nullptr;
             launch_attn_mfma_block(G, pa.hd, pa, 0, grid_b, lds_attn_block, st);
         } else {
             launch_attention_of(pa, 0);
@@ -1218,7 +1231,7 @@ int32_t mtp_poll_error(mtp_handle *h, void *hip_stream) {
         if (word & kErrBarrierTimeout) {
             // a kernel that gave up may have left arrival counters of the attention splits behind (the hand-over tags
             // need nothing: the next call's tags are larger than any the abandoned call wrote)
-            if (hipMemsetAsync(h->ws + h->lay.attn_ticket, 0, (size_t)h->cfg.max_batch * h->cfg.n_kv_heads * 4 + 64, st) !=
+            if (hipMemsetAsync(h->ws + h->lay.attn_ticket, 0, (size_t)h->cfg.max_batch * h->cfg.n_kv_heads * 4 * 2 + 64, st) !=
                 hipSuccess)
                 return MTP_ERR_HIP;
         }

@@ -987,21 +987,32 @@ struct NoHook {
 };
 // before_q: called once, by all threads, after the first cache loads have been requested and before q/k/v are read
 // TAGGED (one sequence, implies COH): q/k/v are polled as tagged elements and the result is written as tagged elements
-template <int G, int HD, bool COH = false, bool TICKET = false, class Hook = NoHook, bool TAGGED = false>
+// GS: an item serves GT / GS of the GT query heads of a KV head (items: sequence, KV head, split, part of the heads);
+// the parts read the same keys and values.  The phase's stages are bound by vector instructions per workgroup, which
+// go with tokens x heads: halving the heads per item halves them where halving the tokens would double the partials.
+template <int GT, int HD, bool COH = false, bool TICKET = false, class Hook = NoHook, bool TAGGED = false, int GS = 1>
 __device__ __forceinline__ void phase_attn(const DraftParams &p, int step, int vb, int nvb, char *smem, Hook before_q = Hook()) {
+    static_assert(GT % GS == 0, "whole heads per part");
+    constexpr int G = GT / GS; // query heads per item
     using L = AttnLds<G, HD>;
-    constexpr int LPT = L::LPT, TPI = L::TPI, NSTREAM = L::NSTREAM, U = 4;
+    // U blocks of TPI tokens per wave and round: one round covers kWaves * U * TPI tokens (with half the heads per
+    // item the registers allow a fifth block, and the single-launch kernel's splits of up to 160 tokens need one round)
+    constexpr int LPT = L::LPT, TPI = L::TPI, NSTREAM = L::NSTREAM, U = GS > 1 ? 5 : 4;
     L &s = *reinterpret_cast<L *>(smem);
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int c = lane % LPT, tq = lane / LPT;
     const int T = p.split_tokens, S = p.max_splits;
-    const int n_items = p.B * p.Hkv * S;
+    const int n_seq_items = p.B * p.Hkv * S, n_items = n_seq_items * GS;
     const float scale = 1.0f / sqrtf((float)HD);
     const int PW = HD + 2; // floats per (head, split) partial: acc[HD], max, sum
 
     bool first_item = true;
     for (int item = vb; item < n_items; item += nvb) {
-        const int b = item / (p.Hkv * S), rem = item % (p.Hkv * S), kvh = rem / S, sp = rem % S;
+        // the parts of one (KV head, split) are n_seq_items apart: workgroups of the same compute die when that is a
+        // multiple of eight, so the second reads the keys and values from its L2
+        const int part = item / n_seq_items, it1 = item % n_seq_items;
+        const int b = it1 / (p.Hkv * S), rem = it1 % (p.Hkv * S), kvh = rem / S, sp = rem % S;
+        const int h0 = kvh * GT + part * G; // the item's first query head
         const bool dead = seq_dead(p, b);
         if (p.kv_appended && dead) continue; // a row that is not part of the block (uniform for the workgroup)
         const int Lb = dead ? 0 : p.kv_len[b];
@@ -1061,8 +1072,8 @@ __device__ __forceinline__ void phase_attn(const DraftParams &p, int step, int v
         // nothing else is waited for
         float bqa = 0.f, bqb = 0.f, bka = 0.f, bkb = 0.f, bv = 0.f;
         if (has_q && p.b_q) {
-            bqa = bf16_to_f32(p.b_q[(kvh * G + gq) * HD + jj]);
-            bqb = bf16_to_f32(p.b_q[(kvh * G + gq) * HD + jj + HD / 2]);
+            bqa = bf16_to_f32(p.b_q[(h0 + gq) * HD + jj]);
+            bqb = bf16_to_f32(p.b_q[(h0 + gq) * HD + jj + HD / 2]);
         }
         if (has_k && p.b_k) {
             bka = bf16_to_f32(p.b_k[kvh * HD + jj]);
@@ -1071,7 +1082,7 @@ __device__ __forceinline__ void phase_attn(const DraftParams &p, int step, int v
         if (has_v && p.b_v) bv = bf16_to_f32(p.b_v[kvh * HD + (tid - kWave * 6)]);
         if (has_q || has_k) rope_cos_sin(pnew, p.rope_inv[jj], cs, sn);
         if (has_q) {
-            const float *src = qkv + (size_t)(kvh * G + gq) * HD;
+            const float *src = qkv + (size_t)(h0 + gq) * HD;
             ld_in2(src + jj, src + jj + HD / 2, qa, qb);
             qa += bqa;
             qb += bqb;
@@ -1097,7 +1108,7 @@ __device__ __forceinline__ void phase_attn(const DraftParams &p, int step, int v
             const uint16_t r0 = f32_to_bf16(ka * cs - kb * sn), r1 = f32_to_bf16(kb * cs + ka * sn);
             s.knew[jj] = bf16_to_f32(r0);
             s.knew[jj + HD / 2] = bf16_to_f32(r1);
-            if (!dead) {
+            if (!dead && part == 0) { // every part needs the new key and value, one of them appends
                 uint16_t *kdst = p.k_cache + (((size_t)b * p.Hkv + kvh) * p.cap + pnew) * HD;
                 st_u16<COH>(kdst + jj, r0);
                 st_u16<COH>(kdst + jj + HD / 2, r1);
@@ -1107,7 +1118,7 @@ __device__ __forceinline__ void phase_attn(const DraftParams &p, int step, int v
             const int e = tid - kWave * 6;
             const uint16_t r = f32_to_bf16(vraw);
             s.vnew[e] = bf16_to_f32(r);
-            if (!dead) st_u16<COH>(p.v_cache + (((size_t)b * p.Hkv + kvh) * p.cap + pnew) * HD + e, r);
+            if (!dead && part == 0) st_u16<COH>(p.v_cache + (((size_t)b * p.Hkv + kvh) * p.cap + pnew) * HD + e, r);
         }
         lds_barrier();
 
@@ -1125,13 +1136,14 @@ __device__ __forceinline__ void phase_attn(const DraftParams &p, int step, int v
             for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
         }
 
-        auto absorb = [&](const float(&sc)[U][G], const float(&vv)[U][8], const bool(&okk)[U]) {
+        // nl: blocks of this round that exist for the wave (uniform): the others are skipped, not masked
+        auto absorb = [&](const float(&sc)[U][G], const float(&vv)[U][8], const bool(&okk)[U], int nl) {
 #pragma unroll
             for (int g = 0; g < G; ++g) {
                 float mb = mx[g];
 #pragma unroll
                 for (int u = 0; u < U; ++u)
-                    if (okk[u]) mb = fmaxf(mb, sc[u][g]);
+                    if (u < nl && okk[u]) mb = fmaxf(mb, sc[u][g]);
                 if (mb == -INFINITY) continue;
                 float alpha = expf(mx[g] - mb); // 0 when nothing was absorbed before
                 float sm = sum[g] * alpha;
@@ -1139,7 +1151,7 @@ __device__ __forceinline__ void phase_attn(const DraftParams &p, int step, int v
                 for (int e = 0; e < 8; ++e) acc[g][e] *= alpha;
 #pragma unroll
                 for (int u = 0; u < U; ++u)
-                    if (okk[u]) {
+                    if (u < nl && okk[u]) {
                         float pr = expf(sc[u][g] - mb);
                         sm += pr;
 #pragma unroll
@@ -1152,9 +1164,17 @@ __device__ __forceinline__ void phase_attn(const DraftParams &p, int step, int v
 
         for (int base = wave; base < nblk; base += kWaves * U) {
             if (base != wave) load_blocks(base);
+            const int nl = __builtin_amdgcn_readfirstlane(min(U, (nblk - base + kWaves - 1) / kWaves));
             float sc[U][G], vv[U][8];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
+                if (u >= nl) { // no such block: nothing of it is used
+#pragma unroll
+                    for (int g = 0; g < G; ++g) sc[u][g] = 0.f;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) vv[u][e] = 0.f;
+                    continue;
+                }
                 float kf[8] = {lo_half(kr[u].x), hi_half(kr[u].x), lo_half(kr[u].y), hi_half(kr[u].y),
                                lo_half(kr[u].z), hi_half(kr[u].z), lo_half(kr[u].w), hi_half(kr[u].w)};
                 vv[u][0] = lo_half(vr[u].x);
@@ -1173,7 +1193,7 @@ __device__ __forceinline__ void phase_attn(const DraftParams &p, int step, int v
                     sc[u][g] = (LPT == 16) ? row16_sum(a) : oct_sum(a);
                 }
             }
-            absorb(sc, vv, ok);
+            absorb(sc, vv, ok, nl);
         }
         if (last && wave == 0) { // the token being appended, from LDS; every lane group computes it, group 0 keeps it
             float sc[U][G], vv[U][8];
@@ -1195,7 +1215,7 @@ __device__ __forceinline__ void phase_attn(const DraftParams &p, int step, int v
                 for (int e = 0; e < 8; ++e) a += q[g][e] * s.knew[c * 8 + e];
                 sc[0][g] = (LPT == 16) ? row16_sum(a) : oct_sum(a);
             }
-            absorb(sc, vv, okn);
+            absorb(sc, vv, okn, 1);
         }
         // merge the lane groups of the workgroup
         // (a single split publishes its result as tagged elements that other workgroups act on at once: the appended
@@ -1238,7 +1258,7 @@ __device__ __forceinline__ void phase_attn(const DraftParams &p, int step, int v
             float A = 0.f;
 #pragma unroll 8
             for (int st = 0; st < NSTREAM; ++st) A += s.acc[st][g][dd] * s.ml[st][g][0];
-            int hq = kvh * G + g;
+            int hq = h0 + g;
             if (nsplit == 1) {
                 const float r = A / Ls;
                 if (TAGGED)
@@ -1270,7 +1290,7 @@ __device__ __forceinline__ void phase_attn(const DraftParams &p, int step, int v
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
             if (tid == 0) {
-                int *ticket = p.attn_ticket + (size_t)b * p.Hkv + kvh;
+                int *ticket = p.attn_ticket + ((size_t)b * p.Hkv + kvh) * GS + part; // (GS > 1: one sequence)
                 const int old = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 if (old == nsplit - 1) __hip_atomic_store(ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 last_to_arrive = (old == nsplit - 1) ? 1 : 0;
@@ -1278,7 +1298,7 @@ __device__ __forceinline__ void phase_attn(const DraftParams &p, int step, int v
             __syncthreads();
             const bool merges = last_to_arrive != 0;
             if (merges && wave < G)
-                merge_head<HD, true, COH, TAGGED>(p, b, kvh * G + wave, nsplit,
+                merge_head<HD, true, COH, TAGGED>(p, b, h0 + wave, nsplit,
                                                   reinterpret_cast<float *>(smem) + (size_t)wave * S, step);
         }
     }
@@ -1453,9 +1473,9 @@ __device__ void phase_finalize(const DraftParams &p, int vb, int nvb) {
 // The attention phase as the single-launch kernel runs it.  Inlined: as a function of its own it saved and restored
 // about a hundred registers per lane through scratch memory at every call (47 MB written and read back per draft step
 // over the chip, for workgroups without an attention item too), which was most of the phase's 15 us.
-template <int G, int HD, bool COH = false, bool TICKET = false, bool TAGGED = false>
+template <int G, int HD, bool COH = false, bool TICKET = false, bool TAGGED = false, int GS = 1>
 __device__ __forceinline__ void call_attn(const DraftParams &p, int step, int vb, int nvb, char *smem) {
-    phase_attn<G, HD, COH, TICKET, NoHook, TAGGED>(p, step, vb, nvb, smem);
+    phase_attn<G, HD, COH, TICKET, NoHook, TAGGED, GS>(p, step, vb, nvb, smem);
 }
 
 } // namespace mtp
