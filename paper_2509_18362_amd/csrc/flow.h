@@ -399,6 +399,7 @@ __device__ __forceinline__ void flow_steps(const DraftParams &p, char *smem) {
     u32x4 ring[2][kChunkLoads];
     FlowLoad L;
     L.id = FL_NONE;
+    bool slot_late = false; // the LDS slot's chunk of the phase that begins has not been requested yet
 
     for (int step = 0; step < p.K; ++step) {
 #pragma unroll 1
@@ -584,6 +585,10 @@ __device__ __forceinline__ void flow_steps(const DraftParams &p, char *smem) {
                 }
                 }
             }
+            if (slot_late) { // the third chunk requested ahead for this phase (see the end of a phase)
+                flow_issue_lds(L, slot, lane);
+                slot_late = false;
+            }
             flow_barrier();
             stamp(step, sec, kTraceStaged);
 
@@ -695,9 +700,13 @@ __device__ __forceinline__ void flow_steps(const DraftParams &p, char *smem) {
             }
             if (pend & 1) flow_issue(L, ring[0], lane);
             if (pend & 2) flow_issue(L, ring[1], lane);
+            // The LDS slot's chunk of the next phase is requested by that phase, behind its polls (a wave's loads
+            // complete in order, and a poll behind three chunks per wave returns 2 us later than behind two; with one
+            // chunk or none in front of them the polls gain less than the memory system loses: 141.7 and 149.5 us per
+            // step against 137.4).
             if (next != FL_NONE) { // (no next phase: nothing is written into LDS that the attention may be using)
                 advance_cursor();
-                flow_issue_lds(L, slot, lane);
+                slot_late = true;
             }
             if (ph == FL_HEAD) {
                 // the workgroup's candidate: (logit, token id), each with the tag in its upper half
